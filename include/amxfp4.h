@@ -1,0 +1,136 @@
+/*
+ * amxfp4.h — C ABI of libamxfp4: direct-cast BF16 -> AMXFP4 / MXFP4 group quantization and the fully
+ * quantized matrix multiplication that consumes the quantized operands, for AMD MI355X (gfx950).
+ *
+ * Formats (paper Sec. 2.1, Sec. 4.2 Eq. 1, Sec. 4.3, Appendix B Algorithm 1 and the table of MX-compliant formats):
+ *   element   FP4 E2M1: 1 sign, 2 exponent (bias 1), 1 mantissa bit; magnitudes {0, .5, 1, 1.5, 2, 3, 4, 6}.
+ *   group     `group_size` consecutive elements along the contraction axis K share the scale(s) (32 in MX).
+ *   MXFP4     one scale S per group;            x_hat = (-1)^s * elem * S
+ *   AMXFP4    two scales (S_p, S_n) per group;  x_hat = (-1)^s * elem * (s == 0 ? S_p : S_n)         (Eq. 1)
+ *   scale     8 bits: E8M0 power of two (Algorithm 1, exponent floored), or FP8 E5M2 (Sec. 4.2 "FP8";
+ *             this is the format the paper calls AMXFP4 when asymmetric and "MXFP4" in its result tables when
+ *             symmetric).
+ *   product   every elementwise product in a dot product carries the scale pair picked by the signs of its
+ *             two factors (Sec. 4.3); accumulation is FP32 on the GPU.
+ *
+ * Quantization rule (Algorithm 1; Sec. 4.2; Appendix B worked example), per group and per sign class c in {p, n}:
+ *   amax_p = largest positive element (0 if none), amax_n = largest |negative element| (0 if none);
+ *   symmetric formats use amax = max(amax_p, amax_n) for both classes.
+ *   E5M2      S_c = round-to-nearest-even onto the non-negative E5M2 values of the real quotient amax_c / 6,
+ *             saturating at 57344, subnormals kept;
+ *   E8M0      S_c = 2^(floor(log2 amax_c) - 2)  (S_c byte 0 when amax_c == 0);
+ *   element   magnitude = round-to-nearest (ties to the even code) of min(|x| / S_c, 6) onto the E2M1 grid,
+ *             0 when S_c == 0; sign bit copied from the input's IEEE sign bit.
+ *
+ * Storage (the paper gives none; this layout is this library's):
+ *   codes     row-major [rows][K/2] bytes; byte b holds element 2b in bits 3:0 and element 2b+1 in bits 7:4;
+ *             nibble = s e1 e0 m.
+ *   scales    asymmetric: row-major [rows][K/group_size][2] bytes = (S_p, S_n); symmetric: [rows][K/group_size].
+ *             E5M2 byte = 0eeeeemm, bias 15, subnormals m * 2^-16.  E8M0 byte = exponent + 127.
+ *
+ * Conventions for every entry point below:
+ *   - all data pointers are DEVICE pointers owned by the caller unless stated otherwise; the library never
+ *     frees or retains them; `fmt` is a HOST pointer read during the call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Work is enqueued on it and the
+ *     call returns without synchronising.
+ *   - arguments are validated on the host before anything is launched; on a non-zero return no output byte has
+ *     been written. Inputs must be finite BF16 (NaN/Inf give unspecified codes but never an out-of-bounds access).
+ *   - returns AMX_OK or a negative amx_status_t; amxfp4_last_error() gives a thread-local message.
+ */
+#ifndef AMXFP4_H
+#define AMXFP4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AMX_OK = 0,
+  AMX_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, K not a multiple of the group, bad enum, misalignment */
+  AMX_ERR_UNSUPPORTED = -2, /* a legal format this GPU library does not implement (group_size != 32, E4M3 scale, ...) */
+  AMX_ERR_WORKSPACE = -3,   /* workspace missing or smaller than amxfp4_gemm_workspace_bytes() */
+  AMX_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed */
+} amx_status_t;
+
+typedef enum {
+  AMX_ELEM_FP4_E2M1 = 0 /* Sec. 2.1; table of MX-compliant formats */
+} amx_elem_t;
+
+typedef enum {
+  AMX_SCALE_E8M0_FLOOR = 0, /* OCP MX power-of-two scale, exponent floored (Appendix B, Algorithm 1) */
+  AMX_SCALE_E8M0_ROUND = 1, /* power-of-two scale with the exponent rounded instead of floored (Appendix B, "Floor vs. Round") */
+  AMX_SCALE_FP8_E5M2 = 2,   /* FP8 scale with a 5-bit exponent, the paper's choice (Sec. 4.2 "FP8") */
+  AMX_SCALE_FP8_E4M3 = 3    /* FP8 scale with a 4-bit exponent (Sec. 4.2 ablation); not implemented on the GPU */
+} amx_scale_t;
+
+typedef struct {
+  int32_t group_size; /* elements per group along K (Sec. 2.1: 32). The GPU library implements 32 only. */
+  int32_t elem;       /* amx_elem_t */
+  int32_t scale;      /* amx_scale_t */
+  int32_t asymmetric; /* 1 = AMXFP4: sign-dependent scale pair (Eq. 1); 0 = MXFP4: one scale per group */
+} amx_format_t;
+
+/* Human-readable description of the last non-zero status returned on this thread (never NULL). */
+const char* amxfp4_last_error(void);
+
+/* Size in bytes of the packed code array for a [rows][K] operand: rows*K/2. 0 on invalid arguments. */
+size_t amxfp4_codes_bytes(const amx_format_t* fmt, int64_t rows, int64_t K);
+/* Size in bytes of the scale array: rows*(K/group_size)*(asymmetric ? 2 : 1). 0 on invalid arguments. */
+size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K);
+/* Device scratch amxfp4_gemm needs for `batch` problems of shape M x N x K in this format (may be 0). */
+size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch);
+
+/*
+ * Direct-cast quantization (Algorithm 1 generalised by Sec. 4.2 / Eq. 1; rule restated at the top of this file).
+ *   x_bf16      device, BF16 bit patterns; element (r, k) is x_bf16[r*row_stride + k*k_stride] (strides in elements).
+ *               k_stride == 1 is the contiguous case (16-byte aligned base, row_stride % 8 == 0);
+ *               row_stride == 1 with k_stride >= rows quantizes along a strided axis (groups run down a column,
+ *               e.g. V in softmax(P).V, grouped along the key sequence).
+ *   rows, K     operand shape; K % group_size == 0.
+ *   codes       device out, amxfp4_codes_bytes() bytes, 16-byte aligned.
+ *   scales      device out, amxfp4_scales_bytes() bytes, 4-byte aligned.
+ */
+int amxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
+                    int64_t k_stride, uint8_t* codes, uint8_t* scales, void* stream);
+
+/*
+ * Dequantization x_hat = (-1)^s * elem * S_class (Eq. 1), exact in both output types.
+ *   out         device out, row-major [rows][K]; out_dtype 0 = float32, 1 = BF16 bit patterns.
+ */
+int amxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
+                      void* out, int32_t out_dtype, void* stream);
+
+/*
+ * Fully quantized GEMM (Sec. 4.3): C[b][i][j] = sum_k A_hat[b][i][k] * B_hat[b][j][k], with A_hat, B_hat the
+ * dequantized operands of Eq. 1, so that each product is scaled by the pair of scales its two signs select.
+ * FP32 accumulation, FP32 output.
+ *   A_codes/A_scales   [batch][M][K] operand, K contiguous, layouts as above (both operands use `fmt`).
+ *   B_codes/B_scales   [batch][N][K] operand, K contiguous (C = A . B^T).
+ *   C                  device out, [batch][M][ldc] floats, ldc >= N; columns >= N are not touched.
+ *   batch              number of independent back-to-back problems (attention heads), >= 1.
+ *   workspace          device scratch of at least amxfp4_gemm_workspace_bytes() bytes, 256-byte aligned;
+ *                      contents are undefined afterwards. May be NULL when the required size is 0.
+ */
+int amxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
+                int64_t batch, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * MXFP4 symmetric baseline: the same three calls with `asymmetric` forced to 0 (one scale per group, Sec. 2.1 /
+ * Algorithm 1 with the scale format taken from fmt->scale). All other arguments as above.
+ */
+int mxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
+                   int64_t k_stride, uint8_t* codes, uint8_t* scales, void* stream);
+int mxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
+                     void* out, int32_t out_dtype, void* stream);
+int mxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+               const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
+               int64_t batch, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMXFP4_H */
