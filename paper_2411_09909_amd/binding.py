@@ -1,0 +1,139 @@
+"""Thin ctypes binding of libamxfp4.so: the same entry points as include/amxfp4.h, taking torch CUDA tensors.
+
+Only argument marshalling happens here (pointers, sizes, the current HIP stream); every step of the path runs in
+the library's kernels. There is no fallback: if the library has not been built, or no GPU is present, calls raise.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libamxfp4.so")
+
+E8M0_FLOOR, E8M0_ROUND, FP8_E5M2, FP8_E4M3 = 0, 1, 2, 3
+
+
+class AmxFormat(ctypes.Structure):
+    _fields_ = [("group_size", ctypes.c_int32), ("elem", ctypes.c_int32), ("scale", ctypes.c_int32),
+                ("asymmetric", ctypes.c_int32)]
+
+
+class AmxError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load():
+    """Loads the built library (does not compile it) and declares the signatures of include/amxfp4.h."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise AmxError("libamxfp4.so is not built: run `python -m paper_2411_09909_amd.build` (needs hipcc)")
+    L = ctypes.CDLL(LIB_PATH)
+    i64, vp, fp = ctypes.c_int64, ctypes.c_void_p, ctypes.POINTER(AmxFormat)
+    L.amxfp4_last_error.restype = ctypes.c_char_p
+    for name in ("amxfp4_codes_bytes", "amxfp4_scales_bytes"):
+        getattr(L, name).argtypes = [fp, i64, i64]
+        getattr(L, name).restype = ctypes.c_size_t
+    L.amxfp4_gemm_workspace_bytes.argtypes = [fp, i64, i64, i64, i64]
+    L.amxfp4_gemm_workspace_bytes.restype = ctypes.c_size_t
+    for p in ("amxfp4", "mxfp4"):
+        q, d, g = getattr(L, p + "_quantize"), getattr(L, p + "_dequantize"), getattr(L, p + "_gemm")
+        q.argtypes = [fp, vp, i64, i64, i64, i64, vp, vp, vp]
+        d.argtypes = [fp, vp, vp, i64, i64, vp, ctypes.c_int32, vp]
+        g.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, i64, i64, vp, ctypes.c_size_t, vp]
+        q.restype = d.restype = g.restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != 0:
+        raise AmxError("libamxfp4 error %d: %s" % (rc, load().amxfp4_last_error().decode()))
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _need_cuda(*ts):
+    for t in ts:
+        if not t.is_cuda:
+            raise AmxError("libamxfp4 works on device memory only")
+
+
+def make_format(scale=FP8_E5M2, asymmetric=True, group_size=32):
+    return AmxFormat(int(group_size), 0, int(scale), int(bool(asymmetric)))
+
+
+def codes_bytes(fmt, rows, K):
+    return load().amxfp4_codes_bytes(ctypes.byref(fmt), rows, K)
+
+
+def scales_bytes(fmt, rows, K):
+    return load().amxfp4_scales_bytes(ctypes.byref(fmt), rows, K)
+
+
+def gemm_workspace_bytes(fmt, M, N, K, batch=1):
+    return load().amxfp4_gemm_workspace_bytes(ctypes.byref(fmt), M, N, K, batch)
+
+
+def _fn(fmt, name, baseline):
+    return getattr(load(), ("mxfp4_" if baseline else "amxfp4_") + name)
+
+
+def quantize(fmt, x, k_axis=-1, codes=None, scales=None, baseline=False):
+    """x: 2-D BF16 (or uint16 bit pattern) CUDA tensor. k_axis=-1: groups along each row (rows contiguous in K);
+    k_axis=0: groups run down the columns (operand = x.T, strided cast). Returns (codes u8 [rows, K/2], scales u8)."""
+    _need_cuda(x)
+    assert x.dim() == 2 and x.element_size() == 2
+    if k_axis in (-1, 1):
+        rows, K = x.shape
+        row_stride, k_stride = x.stride(0), x.stride(1)
+    else:
+        K, rows = x.shape
+        k_stride, row_stride = x.stride(0), x.stride(1)
+    asym = bool(fmt.asymmetric) and not baseline
+    if codes is None:
+        codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        shape = (rows, K // fmt.group_size, 2) if asym else (rows, K // fmt.group_size)
+        scales = torch.empty(shape, dtype=torch.uint8, device=x.device)
+    _check(_fn(fmt, "quantize", baseline)(ctypes.byref(fmt), x.data_ptr(), rows, K, row_stride, k_stride,
+                                          codes.data_ptr(), scales.data_ptr(), _stream()))
+    return codes, scales
+
+
+def dequantize(fmt, codes, scales, out_dtype=torch.float32, baseline=False):
+    _need_cuda(codes, scales)
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    out = torch.empty((rows, K), dtype=out_dtype, device=codes.device)
+    _check(_fn(fmt, "dequantize", baseline)(ctypes.byref(fmt), codes.data_ptr(), scales.data_ptr(), rows, K,
+                                            out.data_ptr(), 1 if out_dtype == torch.bfloat16 else 0, _stream()))
+    return out
+
+
+def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, baseline=False):
+    """a_codes [M, K/2] or [batch, M, K/2]; b_codes [N, K/2] or [batch, N, K/2] (contiguous). Returns FP32 C."""
+    _need_cuda(a_codes, a_scales, b_codes, b_scales)
+    batched = a_codes.dim() == 3
+    batch = a_codes.shape[0] if batched else 1
+    M, K = a_codes.shape[-2], a_codes.shape[-1] * 2
+    N = b_codes.shape[-2]
+    for t in (a_codes, a_scales, b_codes, b_scales):
+        assert t.is_contiguous()
+    if out is None:
+        out = torch.empty((batch, M, N) if batched else (M, N), dtype=torch.float32, device=a_codes.device)
+    need = gemm_workspace_bytes(fmt, M, N, K, batch)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_fn(fmt, "gemm", baseline)(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
+                                      b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(), out.stride(-2), batch,
+                                      ws_ptr, ws_len, _stream()))
+    return out

@@ -1,0 +1,171 @@
+// C ABI of libamxfp4 (declared in include/amxfp4.h): host-side validation and dispatch. No arithmetic of the
+// method happens here; every step runs in the kernels of cast.hip / gemm_*.hip.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "../../include/amxfp4.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local char g_err[256] = "no error";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+// Validates a format for the GPU library. Returns AMX_OK or a negative status (message set).
+int check_format(const amx_format_t* f) {
+  if (!f) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  if (f->elem != AMX_ELEM_FP4_E2M1) return fail(AMX_ERR_INVALID_ARG, "unknown element format %d", f->elem);
+  if (f->scale < AMX_SCALE_E8M0_FLOOR || f->scale > AMX_SCALE_FP8_E4M3)
+    return fail(AMX_ERR_INVALID_ARG, "unknown scale format %d", f->scale);
+  if (f->asymmetric != 0 && f->asymmetric != 1) return fail(AMX_ERR_INVALID_ARG, "asymmetric must be 0 or 1");
+  if (f->group_size == 0 || f->group_size < -1) return fail(AMX_ERR_INVALID_ARG, "bad group_size %d", f->group_size);
+  if (f->group_size != 32) return fail(AMX_ERR_UNSUPPORTED, "the GPU library implements group_size 32 only");
+  if (f->scale == AMX_SCALE_FP8_E4M3) return fail(AMX_ERR_UNSUPPORTED, "E4M3 scales are not implemented on the GPU");
+  return AMX_OK;
+}
+
+int check_shape(int64_t rows, int64_t K) {
+  if (rows <= 0 || K <= 0) return fail(AMX_ERR_INVALID_ARG, "rows and K must be positive (got %lld, %lld)",
+                                       (long long)rows, (long long)K);
+  if (K % 32 != 0) return fail(AMX_ERR_INVALID_ARG, "K = %lld is not a multiple of the group size 32", (long long)K);
+  return AMX_OK;
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int hip_fail(hipError_t e, const char* what) {
+  return fail(AMX_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int quantize_impl(amx_format_t f, const void* x, int64_t rows, int64_t K, int64_t row_stride, int64_t k_stride,
+                  uint8_t* codes, uint8_t* scales, void* stream) {
+  if (int rc = check_format(&f)) return rc;
+  if (int rc = check_shape(rows, K)) return rc;
+  if (!x || !codes || !scales) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
+  if (!aligned(codes, 16) || !aligned(scales, 4)) return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales 4-byte alignment");
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const uint16_t* xb = reinterpret_cast<const uint16_t*>(x);
+  if (k_stride == 1) {
+    if (row_stride < K || row_stride % 8 != 0 || !aligned(x, 16))
+      return fail(AMX_ERR_INVALID_ARG, "contiguous cast needs row_stride >= K, row_stride %% 8 == 0 and a 16-byte aligned base");
+    hipError_t e = amx::launch_quantize_contig(f.scale, f.asymmetric != 0, xb, rows, K, row_stride, codes, scales, s);
+    return e == hipSuccess ? AMX_OK : hip_fail(e, "quantize launch");
+  }
+  if (row_stride == 1 && k_stride >= rows) {
+    if (!aligned(x, 2)) return fail(AMX_ERR_INVALID_ARG, "x must be 2-byte aligned");
+    hipError_t e = amx::launch_quantize_strided(f.scale, f.asymmetric != 0, xb, rows, K, k_stride, codes, scales, s);
+    return e == hipSuccess ? AMX_OK : hip_fail(e, "strided quantize launch");
+  }
+  return fail(AMX_ERR_INVALID_ARG, "unsupported strides: need k_stride == 1, or row_stride == 1 with k_stride >= rows");
+}
+
+int dequantize_impl(amx_format_t f, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K, void* out,
+                    int32_t out_dtype, void* stream) {
+  if (int rc = check_format(&f)) return rc;
+  if (int rc = check_shape(rows, K)) return rc;
+  if (!codes || !scales || !out) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
+  if (out_dtype != 0 && out_dtype != 1) return fail(AMX_ERR_INVALID_ARG, "out_dtype must be 0 (f32) or 1 (bf16)");
+  if (!aligned(codes, 4) || !aligned(scales, 2) || !aligned(out, 16))
+    return fail(AMX_ERR_INVALID_ARG, "misaligned pointer");
+  hipError_t e = amx::launch_dequantize(f.scale, f.asymmetric != 0, codes, scales, rows, K, out, out_dtype,
+                                        reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AMX_OK : hip_fail(e, "dequantize launch");
+}
+
+int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
+              const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch, void* workspace,
+              size_t workspace_bytes, void* stream) {
+  if (int rc = check_format(&f)) return rc;
+  if (int rc = check_shape(M, K)) return rc;
+  if (N <= 0 || batch <= 0) return fail(AMX_ERR_INVALID_ARG, "N and batch must be positive");
+  if (ldc < N) return fail(AMX_ERR_INVALID_ARG, "ldc < N");
+  if (!A_codes || !A_scales || !B_codes || !B_scales || !C) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
+  if (!aligned(A_codes, 16) || !aligned(B_codes, 16) || !aligned(A_scales, 4) || !aligned(B_scales, 4) ||
+      !aligned(C, 4))
+    return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales and C 4-byte alignment");
+  const size_t need = amxfp4_gemm_workspace_bytes(&f, M, N, K, batch);
+  if (need > 0) {
+    if (!workspace || workspace_bytes < need)
+      return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
+    if (!aligned(workspace, 256)) return fail(AMX_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  }
+  hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales,
+                                            C, ldc, batch, workspace, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
+}
+
+amx_format_t symmetric(const amx_format_t* f) {
+  amx_format_t g = *f;
+  g.asymmetric = 0;
+  return g;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* amxfp4_last_error(void) { return g_err; }
+
+size_t amxfp4_codes_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
+  if (!fmt || rows <= 0 || K <= 0 || K % 2) return 0;
+  return (size_t)(rows * K / 2);
+}
+
+size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
+  if (!fmt || rows <= 0 || K <= 0 || fmt->group_size <= 0 || K % fmt->group_size) return 0;
+  return (size_t)(rows * (K / fmt->group_size) * (fmt->asymmetric ? 2 : 1));
+}
+
+size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch) {
+  if (!fmt || M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
+  return amx::bf16_path_workspace_bytes(M, N, K, batch);
+}
+
+int amxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
+                    int64_t k_stride, uint8_t* codes, uint8_t* scales, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  return quantize_impl(*fmt, x_bf16, rows, K, row_stride, k_stride, codes, scales, stream);
+}
+
+int amxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
+                      void* out, int32_t out_dtype, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  return dequantize_impl(*fmt, codes, scales, rows, K, out, out_dtype, stream);
+}
+
+int amxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
+                int64_t batch, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  return gemm_impl(*fmt, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, workspace_bytes,
+                   stream);
+}
+
+int mxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
+                   int64_t k_stride, uint8_t* codes, uint8_t* scales, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  return quantize_impl(symmetric(fmt), x_bf16, rows, K, row_stride, k_stride, codes, scales, stream);
+}
+
+int mxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
+                     void* out, int32_t out_dtype, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  return dequantize_impl(symmetric(fmt), codes, scales, rows, K, out, out_dtype, stream);
+}
+
+int mxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+               const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
+               int64_t batch, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  return gemm_impl(symmetric(fmt), M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace,
+                   workspace_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,301 @@
+// Fully quantized GEMM for scale formats whose values are not powers of two (FP8 E5M2, Sec. 4.2) and for the
+// sign-asymmetric formats (Eq. 1, Sec. 4.3).
+//
+// A dequantized element is elem * S_class with elem in {0,.5,1,1.5,2,3,4,6} and S = (1 + m/4) * 2^e: up to 5
+// significant bits (3 * 7 = 21), which FP8/FP6/FP4 MFMA operands cannot hold but BF16 holds exactly. The GEMM is
+// therefore run on the BF16 MFMA (v_mfma_f32_32x32x16_bf16) with exact operands and FP32 accumulation:
+//
+//   1. expand kernel: codes + scale pair -> BF16, written into "fragment-major" panels in the workspace:
+//        panel[row_block of 32][k_block of 16][lane 0..63][8 BF16],  lane = 32 * (k / 8 % 2) + row % 32,
+//      which is exactly the register image of one MFMA operand (lane l holds row l%32, k = 8*(l/32) .. +7).
+//      Rows are padded to a multiple of 256 and K to a multiple of 128 with zeros.
+//   2. GEMM kernel: every operand fragment is one contiguous KiB in the workspace, so staging global -> LDS is a
+//      linear copy and LDS -> register reads are conflict-free 128-bit reads at lane * 16.
+#include "device_formats.h"
+
+namespace amx {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kFragBytes = 1024;  // 32 rows x 16 k x 2 bytes
+
+size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch) {
+  const int64_t Kp = round_up(K, kPanelK);
+  return (size_t)(batch * (round_up(M, kPanelRows) + round_up(N, kPanelRows)) * Kp * 2);
+}
+
+// ------------------------------------------------------------------------------------------------ expand ----------
+// grid: (Kp / 64, Rp / 128, batch); block 256 = 4 waves; wave w expands row block rb = blockIdx.y * 4 + w for the two
+// groups of a 64-wide K slice: lane = 32 * group_in_slice + row_in_block.
+template <int SCALE_KIND, bool ASYM>
+__global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__ codes,
+                                                     const uint8_t* __restrict__ scales, int64_t R, int64_t K,
+                                                     int64_t Rp, int64_t Kp, uint16_t* __restrict__ panel) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t rb = (int64_t)blockIdx.y * 4 + wave;
+  const int64_t r = rb * 32 + (lane & 31);
+  const int64_t g = (int64_t)blockIdx.x * 2 + (lane >> 5);
+  const int64_t G = K >> 5;
+  const int64_t b = blockIdx.z;
+  uint32_t w[4] = {0, 0, 0, 0};
+  float s_pos = 0.f, s_neg = 0.f;
+  if (r < R && g < G) {
+    const uint4 c = *reinterpret_cast<const uint4*>(codes + (b * R + r) * (K >> 1) + g * 16);
+    w[0] = c.x, w[1] = c.y, w[2] = c.z, w[3] = c.w;
+    if constexpr (ASYM) {
+      const uint32_t sb = *reinterpret_cast<const uint16_t*>(scales + ((b * R + r) * G + g) * 2);
+      s_pos = scale_value<SCALE_KIND>(sb & 255u);
+      s_neg = scale_value<SCALE_KIND>(sb >> 8);
+    } else {
+      s_pos = s_neg = scale_value<SCALE_KIND>(scales[(b * R + r) * G + g]);
+    }
+  }
+  s_pos *= 0.5f;
+  s_neg *= -0.5f;
+  uint16_t* dst = panel + ((b * (Rp >> 5) + rb) * (Kp >> 4) + (int64_t)blockIdx.x * 4 + (lane >> 5) * 2) * 512;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {  // t-th run of 8 elements of the group: k block (t / 2), half (t % 2)
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t n0 = (w[t] >> (8 * j)) & 15u, n1 = (w[t] >> (8 * j + 4)) & 15u;
+      const float v0 = (float)e2m1_twice(n0 & 7u) * ((n0 & 8u) ? s_neg : s_pos);
+      const float v1 = (float)e2m1_twice(n1 & 7u) * ((n1 & 8u) ? s_neg : s_pos);
+      o[j] = (f2u(v0) >> 16) | (f2u(v1) & 0xFFFF0000u);  // truncation is exact: <= 5 significant bits
+    }
+    *reinterpret_cast<uint4*>(dst + (t >> 1) * 512 + ((t & 1) * 32 + (lane & 31)) * 8) =
+        make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ GEMM ------------
+// Workgroup tile (32*FM*WM) x (32*FN*WN), WM x WN waves, each wave FM x FN MFMA tiles of 32x32.
+// LDS holds a ring of 4 stages (four arrays); one stage is a K slice of 32 (2 MFMA k-steps): per 32-row block 2 fragments.
+constexpr int kStageK = 32;
+
+template <int WM, int WN, int FM, int FN>
+struct TileCfg {
+  static constexpr int kWaves = WM * WN;
+  static constexpr int kThreads = 64 * kWaves;
+  static constexpr int kTileM = 32 * FM * WM;
+  static constexpr int kTileN = 32 * FN * WN;
+  static constexpr int kFragsA = (kTileM / 32) * 2;  // fragments per stage
+  static constexpr int kFragsB = (kTileN / 32) * 2;
+  static constexpr int kLoads = (kFragsA + kFragsB) / kWaves;  // direct-to-LDS loads per wave per stage
+  static constexpr int kStageBytes = (kFragsA + kFragsB) * kFragBytes;
+  static_assert(kFragsA % kWaves == 0 && kFragsB % kWaves == 0, "fragments must divide evenly over the waves");
+  static_assert(FM % 2 == 0, "the A register ring of 4 needs an even number of steps per k-step");
+  static_assert(kLoads <= 15, "s_waitcnt immediates below assume at most 15 loads per stage");
+};
+
+// Supertile: the tiles that run at the same time on one XCD (32 CUs, one L2): 8 along M x 4 along N, so that every
+// staged A panel is shared by 4 and every B panel by 8 workgroups through that L2. Workgroups are dealt to the 8 XCDs
+// round-robin by their linear id, hence id % 8 picks the XCD and id / 8 the slot on it.
+constexpr int kSuperM = 8, kSuperN = 4;
+
+// s_waitcnt immediate that waits until at most n (< 16) vector-memory operations are outstanding and nothing else
+#define AMX_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
+// workgroup barrier without the memory fence __syncthreads() implies: the data movement around it is ordered by the
+// explicit vmcnt waits (direct-to-LDS loads) and by the MFMA operand dependencies (LDS reads)
+#define AMX_BARRIER() asm volatile("s_barrier" ::: "memory")
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+template <int WM, int WN, int FM, int FN>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t* __restrict__ Ap,
+                                                                 const uint16_t* __restrict__ Bp, float* __restrict__ C,
+                                                                 int64_t M, int64_t N, int64_t Mp, int64_t Np,
+                                                                 int64_t Kp, int64_t ldc, int tiles_m, int tiles_n,
+                                                                 int super_m) {
+  using Cfg = TileCfg<WM, WN, FM, FN>;
+  // Four separate arrays rather than one ring buffer: the compiler then knows that a direct-to-LDS load into one
+  // stage cannot alias the fragment reads of another and does not serialise them.
+  __shared__ __attribute__((aligned(1024))) uint8_t lds0[Cfg::kStageBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t lds1[Cfg::kStageBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t lds2[Cfg::kStageBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t lds3[Cfg::kStageBytes];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int64_t b = blockIdx.z;
+
+  int tm, tn;
+  {
+    const int p = blockIdx.x, xcd = p & 7, q = p >> 3;
+    const int st = (q / (kSuperM * kSuperN)) * 8 + xcd, slot = q % (kSuperM * kSuperN);
+    tm = (st % super_m) * kSuperM + slot % kSuperM;
+    tn = (st / super_m) * kSuperN + slot / kSuperM;
+    if (tm >= tiles_m || tn >= tiles_n) return;  // uniform over the workgroup, before any barrier
+  }
+
+  // Buffer descriptors over this tile's slice of each panel: (tile rows / 32) row blocks x kblocks fragments of 1 KiB.
+  // Raw buffer (stride 0), so reads past num_records return zero instead of faulting.
+  const int kblocks = (int)(Kp >> 4);
+  const uint8_t* Abase = reinterpret_cast<const uint8_t*>(Ap) +
+                         ((b * (Mp >> 5) + (int64_t)tm * (Cfg::kTileM / 32)) * kblocks) * kFragBytes;
+  const uint8_t* Bbase = reinterpret_cast<const uint8_t*>(Bp) +
+                         ((b * (Np >> 5) + (int64_t)tn * (Cfg::kTileN / 32)) * kblocks) * kFragBytes;
+  const __amdgpu_buffer_rsrc_t Ar = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(Abase), 0, (Cfg::kTileM / 32) * kblocks * kFragBytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t Br = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(Bbase), 0, (Cfg::kTileN / 32) * kblocks * kFragBytes, 0x00020000);
+  const int lane_off = lane * 16;
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // Load number L (0 .. kLoads-1) of this wave for K stage ST into ring slot array DST: fragment f = wave + kWaves * L
+  // of the stage; f < kFragsA: A row block f / 2, k block f % 2; otherwise the same for B. One contiguous KiB of the
+  // panel goes to DST + f KiB (the hardware adds lane * 16 on the LDS side).
+  // (local copies of the tile constants: naming Cfg:: members directly inside the builtin's arguments trips the host
+  // pass of the compiler, which then drops the kernel's launch stub)
+  constexpr int kWaves = Cfg::kWaves, kFragsA = Cfg::kFragsA, kLoads = Cfg::kLoads;
+#define AMX_ISSUE_LOAD(L, ST, DST)                                                                         \
+  {                                                                                                        \
+    const int f_ = wave + kWaves * (L);                                                                    \
+    if ((L) < kFragsA / kWaves) /* decided at compile time once the loops are unrolled */                  \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(Ar, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, lane_off,     \
+                                               ((f_ >> 1) * kblocks + (ST) * 2 + (f_ & 1)) * kFragBytes,   \
+                                               0, 0);                                                      \
+    else                                                                                                   \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                            \
+          Br, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, lane_off,                                          \
+          (((f_ - kFragsA) >> 1) * kblocks + (ST) * 2 + (f_ & 1)) * kFragBytes, 0, 0);                     \
+  }
+
+  const int nstages = (int)(Kp / kStageK);  // multiple of 4
+  // prologue: 3 stages in flight; stages 0 and 1 must have landed before the first fragment reads
+#pragma unroll
+  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 0, lds0);
+#pragma unroll
+  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 1, lds1);
+#pragma unroll
+  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 2, lds2);
+  AMX_WAIT_VMCNT(kLoads);
+  AMX_BARRIER();
+
+  // register rings: the A fragment for step t lives in aR[t & 3] (read two steps ahead), the B fragments of k-step ks
+  // in bR[ks & 1] (read during the previous k-step)
+  bf16x8 aR[4], bR[2][FN];
+  const int offA = lane_off + (wm * FM) * 2 * kFragBytes;
+  const int offB = lane_off + (Cfg::kFragsA + (wn * FN) * 2) * kFragBytes;
+  aR[0] = *reinterpret_cast<const bf16x8*>(lds0 + offA);
+  aR[1] = *reinterpret_cast<const bf16x8*>(lds0 + offA + 2 * kFragBytes);
+#pragma unroll
+  for (int j = 0; j < FN; ++j) bR[0][j] = *reinterpret_cast<const bf16x8*>(lds0 + offB + j * 2 * kFragBytes);
+
+  // One stage: 2 k-steps x FM steps; a step issues the fragment reads needed two steps (A) or one k-step (B) later,
+  // its share of the direct-to-LDS loads for stage S + 3, then FN MFMAs. CUR / NXT are the ring arrays of stage S and
+  // S + 1, FETCH the one stage S + 3 lands in (last read during stage S - 1). Past the end of K the fetch is pointed
+  // at the last real stage instead of being skipped: it lands in a slot nobody reads any more and the body stays free
+  // of branches.
+#define AMX_STAGE(S, CUR, NXT, FETCH)                                                                                \
+  {                                                                                                                  \
+    const int fetch_ = (S) + 3 < nstages ? (S) + 3 : nstages - 1;                                                    \
+    _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                               \
+      _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                                               \
+        const int t = ks * FM + i;                                                                                   \
+        {                                                                                                            \
+          const int t2 = t + 2, ks2 = t2 / FM, i2 = t2 % FM;                                                         \
+          const uint8_t* src_ = ks2 < 2 ? (CUR) : (NXT);                                                             \
+          aR[t2 & 3] = *reinterpret_cast<const bf16x8*>(src_ + offA + (i2 * 2 + (ks2 & 1)) * kFragBytes);           \
+        }                                                                                                            \
+        _Pragma("unroll") for (int jj = 2 * i; jj < 2 * i + 2; ++jj) {                                               \
+          if (jj < FN) {                                                                                             \
+            const uint8_t* src_ = ks == 0 ? (CUR) : (NXT);                                                           \
+            bR[(ks + 1) & 1][jj] =                                                                                   \
+                *reinterpret_cast<const bf16x8*>(src_ + offB + (jj * 2 + ((ks + 1) & 1)) * kFragBytes);             \
+          }                                                                                                          \
+        }                                                                                                            \
+        _Pragma("unroll") for (int l = t; l < kLoads; l += 2 * FM) AMX_ISSUE_LOAD(l, fetch_, FETCH);            \
+        _Pragma("unroll") for (int j = 0; j < FN; ++j) acc[i][j] =                                                   \
+            __builtin_amdgcn_mfma_f32_32x32x16_bf16(aR[t & 3], bR[ks & 1][j], acc[i][j], 0, 0, 0);                   \
+        __builtin_amdgcn_sched_barrier(0);                                                                           \
+      }                                                                                                              \
+    }                                                                                                                \
+    /* stage S + 2 must be complete in LDS for every wave before stage S + 1 starts reading ahead into it; the same  \
+       barrier tells every wave that stage S is no longer read, so its slot may be refilled during stage S + 1 */    \
+    AMX_WAIT_VMCNT(kLoads);                                                                                     \
+    AMX_BARRIER();                                                                                                   \
+  }
+
+  for (int s = 0; s < nstages; s += 4) {
+    AMX_STAGE(s, lds0, lds1, lds3);
+    AMX_STAGE(s + 1, lds1, lds2, lds0);
+    AMX_STAGE(s + 2, lds2, lds3, lds1);
+    AMX_STAGE(s + 3, lds3, lds0, lds2);
+  }
+  AMX_WAIT_VMCNT(0);  // nothing may still be writing this workgroup's LDS when it retires
+#undef AMX_STAGE
+#undef AMX_ISSUE_LOAD
+
+  // C tile: accumulator register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 block
+  float* Cb = C + b * M * ldc;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int64_t col = (int64_t)tn * Cfg::kTileN + (wn * FN + j) * 32 + (lane & 31);
+      const int64_t row0 = (int64_t)tm * Cfg::kTileM + (wm * FM + i) * 32 + 4 * (lane >> 5);
+      if (col < N) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int64_t row = row0 + 8 * (v >> 2) + (v & 3);
+          if (row < M) __builtin_nontemporal_store(acc[i][j][v], Cb + row * ldc + col);
+        }
+      }
+    }
+  }
+}
+
+template <int SK, bool ASYM>
+static hipError_t launch_expand(const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K, int64_t Rp,
+                                int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s) {
+  hipLaunchKernelGGL((expand_kernel<SK, ASYM>), dim3((unsigned)(Kp / 64), (unsigned)(Rp / 128), (unsigned)batch),
+                     dim3(256), 0, s, codes, scales, R, K, Rp, Kp, panel);
+  return hipGetLastError();
+}
+
+static hipError_t expand_dispatch(int scale_kind, bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R,
+                                  int64_t K, int64_t Rp, int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s) {
+  if (scale_kind == kScaleE5M2)
+    return asym ? launch_expand<kScaleE5M2, true>(codes, scales, R, K, Rp, Kp, batch, panel, s)
+                : launch_expand<kScaleE5M2, false>(codes, scales, R, K, Rp, Kp, batch, panel, s);
+  return asym ? launch_expand<kScaleE8M0Floor, true>(codes, scales, R, K, Rp, Kp, batch, panel, s)
+              : launch_expand<kScaleE8M0Floor, false>(codes, scales, R, K, Rp, Kp, batch, panel, s);
+}
+
+template <int WM, int WN, int FM, int FN>
+static hipError_t launch_tiles(const uint16_t* Ap, const uint16_t* Bp, float* C, int64_t M, int64_t N, int64_t Mp,
+                               int64_t Np, int64_t Kp, int64_t ldc, int64_t batch, hipStream_t s) {
+  using Cfg = TileCfg<WM, WN, FM, FN>;
+  const int tiles_m = (int)((M + Cfg::kTileM - 1) / Cfg::kTileM), tiles_n = (int)((N + Cfg::kTileN - 1) / Cfg::kTileN);
+  const int super_m = (tiles_m + kSuperM - 1) / kSuperM, super_n = (tiles_n + kSuperN - 1) / kSuperN;
+  const int rounds = (super_m * super_n + 7) / 8;  // supertiles are dealt 8 at a time, one per XCD
+  hipLaunchKernelGGL((gemm_bf16_kernel<WM, WN, FM, FN>), dim3((unsigned)(rounds * 8 * kSuperM * kSuperN), 1,
+                                                              (unsigned)batch),
+                     dim3(Cfg::kThreads), 0, s, Ap, Bp, C, M, N, Mp, Np, Kp, ldc, tiles_m, tiles_n, super_m);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
+                                 int64_t ldc, int64_t batch, void* workspace, hipStream_t s) {
+  const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows), Kp = round_up(K, kPanelK);
+  uint16_t* Ap = reinterpret_cast<uint16_t*>(workspace);
+  uint16_t* Bp = Ap + batch * Mp * Kp;
+  hipError_t e = expand_dispatch(scale_kind, asym, A_codes, A_scales, M, K, Mp, Kp, batch, Ap, s);
+  if (e != hipSuccess) return e;
+  e = expand_dispatch(scale_kind, asym, B_codes, B_scales, N, K, Np, Kp, batch, Bp, s);
+  if (e != hipSuccess) return e;
+  return launch_tiles<2, 2, 4, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);
+}
+
+}  // namespace amx

@@ -1,0 +1,33 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the kernel files. Not installed.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace amx {
+
+// Scale formats (values of amx_scale_t in include/amxfp4.h).
+enum : int { kScaleE8M0Floor = 0, kScaleE8M0Round = 1, kScaleE5M2 = 2, kScaleE4M3 = 3 };
+
+// GEMM tiling of the BF16-expanded path: operands are expanded into MFMA-fragment-major BF16 panels whose row count
+// is padded to kPanelRows and whose K is padded to kPanelK, so that the GEMM main loop needs no bounds checks.
+constexpr int kPanelRows = 256;
+constexpr int kPanelK = 128;
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+// cast.hip
+hipError_t launch_quantize_contig(int scale_kind, bool asym, const uint16_t* x, int64_t rows, int64_t K,
+                                  int64_t row_stride, uint8_t* codes, uint8_t* scales, hipStream_t s);
+hipError_t launch_quantize_strided(int scale_kind, bool asym, const uint16_t* x, int64_t rows, int64_t K,
+                                   int64_t k_stride, uint8_t* codes, uint8_t* scales, hipStream_t s);
+hipError_t launch_dequantize(int scale_kind, bool asym, const uint8_t* codes, const uint8_t* scales, int64_t rows,
+                             int64_t K, void* out, int out_dtype, hipStream_t s);
+
+// gemm_bf16.hip
+size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
+hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
+                                 int64_t ldc, int64_t batch, void* workspace, hipStream_t s);
+
+}  // namespace amx

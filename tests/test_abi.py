@@ -1,0 +1,83 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the header declares, and
+rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2411_09909_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "amxfp4.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2411_09909_amd import build
+        build.build(verbose=False)
+    return binding.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:amxfp4|mxfp4)_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"amxfp4_quantize", "amxfp4_dequantize", "amxfp4_gemm", "mxfp4_quantize", "mxfp4_dequantize",
+            "mxfp4_gemm", "amxfp4_last_error", "amxfp4_codes_bytes", "amxfp4_scales_bytes",
+            "amxfp4_gemm_workspace_bytes"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_size_queries(lib):
+    f = binding.make_format(binding.FP8_E5M2, True)
+    assert binding.codes_bytes(f, 64, 1024) == 64 * 512
+    assert binding.scales_bytes(f, 64, 1024) == 64 * 32 * 2
+    g = binding.make_format(binding.E8M0_FLOOR, False)
+    assert binding.scales_bytes(g, 64, 1024) == 64 * 32
+    assert binding.codes_bytes(f, 0, 1024) == 0
+    # workspace: BF16 panels padded to 256 rows / 128 columns of K
+    assert binding.gemm_workspace_bytes(f, 64, 1024, 1024) == (256 + 1024) * 1024 * 2
+    assert binding.gemm_workspace_bytes(f, 300, 10, 96, 2) == 2 * (512 + 256) * 128 * 2
+
+
+def _q(lib, fmt, x, rows, K, rs, ks, codes, scales):
+    return lib.amxfp4_quantize(ctypes.byref(fmt), x, rows, K, rs, ks, codes, scales, None)
+
+
+def test_invalid_arguments_are_rejected_on_the_host(lib):
+    ok = binding.make_format(binding.FP8_E5M2, True)
+    p = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
+    assert _q(lib, ok, None, 4, 64, 64, 1, p, p) == -1
+    assert _q(lib, ok, p, 0, 64, 64, 1, p, p) == -1
+    assert _q(lib, ok, p, 4, 48, 48, 1, p, p) == -1          # K not a multiple of the group size
+    assert _q(lib, ok, p, 4, 64, 32, 1, p, p) == -1          # row stride shorter than a row
+    assert _q(lib, ok, p, 4, 64, 64, 1, ctypes.c_void_p(0x1001), p) == -1   # misaligned codes
+    assert _q(lib, ok, p, 4, 64, 3, 2, p, p) == -1           # unsupported stride combination
+    assert b"stride" in lib.amxfp4_last_error()
+    for bad, code in [(binding.AmxFormat(16, 0, 2, 1), -2), (binding.AmxFormat(32, 0, 3, 1), -2),
+                      (binding.AmxFormat(32, 1, 2, 1), -1), (binding.AmxFormat(32, 0, 7, 1), -1),
+                      (binding.AmxFormat(0, 0, 2, 1), -1), (binding.AmxFormat(32, 0, 2, 5), -1)]:
+        assert _q(lib, bad, p, 4, 64, 64, 1, p, p) == code
+    assert lib.amxfp4_quantize(None, p, 4, 64, 64, 1, p, p, None) == -1
+    assert lib.amxfp4_dequantize(ctypes.byref(ok), p, p, 4, 64, p, 2, None) == -1      # bad out_dtype
+    # GEMM: workspace too small / missing, ldc < N
+    g = lib.amxfp4_gemm
+    assert g(ctypes.byref(ok), 64, 64, 64, p, p, p, p, p, 64, 1, None, 0, None) == -3
+    assert g(ctypes.byref(ok), 64, 64, 64, p, p, p, p, p, 64, 1, p, 16, None) == -3
+    assert g(ctypes.byref(ok), 64, 64, 64, p, p, p, p, p, 32, 1, p, 1 << 30, None) == -1
+    assert g(ctypes.byref(ok), 64, 64, 64, p, p, p, p, p, 64, 0, p, 1 << 30, None) == -1
+    assert lib.mxfp4_gemm(ctypes.byref(ok), 64, 64, 40, p, p, p, p, p, 64, 1, p, 1 << 30, None) == -1
+
+
+def test_binding_refuses_host_tensors(lib):
+    import torch
+    f = binding.make_format()
+    with pytest.raises(binding.AmxError):
+        binding.quantize(f, torch.zeros(4, 64, dtype=torch.bfloat16))
