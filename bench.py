@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the AMXFP4 hot path on one MI355X: direct-cast quantization of the activations + fully quantized
+GEMM against pre-cast weights, on the 70B-shaped up-projection X[4096 x 8192] . W[28672 x 8192]^T (group 32,
+FP8-E5M2 asymmetric scales). One "step" = amxfp4_quantize(X) + amxfp4_gemm(Xq, Wq). Weights are static in inference,
+so their cast is done once outside the timed region and reported separately.
+
+Prints ONE JSON line: the whole-job throughput 2*M*N*K / t_step in TFLOP/s, a roofline object for the dominant
+kernel (the BF16 MFMA GEMM main loop, timed with HIP events recorded by the library around that kernel) and the CPU
+oracle timed on a bounded sample of the same workload on this machine's host cores.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+WORKLOAD = "c3_70b_up_4096x8192x28672"
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense BF16 MFMA
+PEAK_FP4_TFLOPS = 10100.0   # MI355X dense block-scaled FP4 MFMA (the metric's reference peak)
+# HBM bytes per GEMM-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see
+# profiles/gemm_bf16_c3_up_counters.md; None until that profile has been taken.
+MEASURED_TRAFFIC_BYTES = None
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs (the library records them around its GEMM kernel on the launch stream)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so.7" if sys.platform.startswith("linux") else "amdhip64")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0 and self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self, i):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.pairs[i][0], self.pairs[i][1])
+        assert rc == 0, "hipEventElapsedTime failed: %d" % rc
+        return ms.value
+
+    def destroy(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def cpu_baseline(x_bits, w_bits, K, sample_m=2048, sample_n=14336):
+    """The oracle as it stands (oracle/amxfp4_ref.c: scalar C, FP64 accumulate, OpenMP over rows), timed on a slab of
+    the same operands: quantize sample_m rows of X and sample_n rows of W, then the sample_m x sample_n x K GEMM."""
+    from oracle import ref
+    xs, ws = x_bits[:sample_m], w_bits[:sample_n]
+    ref.lib()  # compile / load outside the timed region
+    t0 = time.perf_counter()
+    xc, xsc = ref.quantize(xs)
+    wc, wsc = ref.quantize(ws)
+    ref.gemm(xc, xsc, wc, wsc)
+    dt = time.perf_counter() - t0
+    flops = 2.0 * sample_m * sample_n * K
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": ref.num_threads(), "kind": "oracle",
+            "sample": "cast of X[:%d] and W[:%d] + their %dx%dx%d GEMM, %.1f s" % (sample_m, sample_n, sample_m,
+                                                                                   sample_n, K, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default=WORKLOAD)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2411_09909_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs an MI355X", file=sys.stderr)
+        sys.exit(1)
+    binding.load()
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.workload]
+    M, N, K = cfg["M"], cfg["N"], cfg["K"]
+    x_bits, w_bits = synth.linear_operands(args.workload, seed=0)
+    xd = torch.from_numpy(x_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    wd = torch.from_numpy(w_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    fmt = binding.make_format(binding.FP8_E5M2, True)
+    xc = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+    xs = torch.empty((M, K // 32, 2), dtype=torch.uint8, device=dev)
+    C = torch.empty((M, N), dtype=torch.float32, device=dev)
+    ws = torch.empty(binding.gemm_workspace_bytes(fmt, M, N, K), dtype=torch.uint8, device=dev)
+
+    # weights: cast once (timed on its own)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    wc, wsc = binding.quantize(fmt, wd)
+    torch.cuda.synchronize()
+    t_cast_w = time.perf_counter() - t0
+    del wd
+
+    def step(pair=None):
+        binding.quantize(fmt, xd, codes=xc, scales=xs)
+        if pair is not None:
+            binding.profile_next_gemm(pair[0], pair[1])
+        binding.gemm(fmt, xc, xs, wc, wsc, out=C, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    ev = HipEvents(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(ev.pairs[i])
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t0
+    kern_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
+    ev.destroy()
+
+    # cast alone, for the breakdown
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        binding.quantize(fmt, xd, codes=xc, scales=xs)
+    torch.cuda.synchronize()
+    t_cast_x = (time.perf_counter() - t0) / args.steps
+
+    flops = 2.0 * M * N * K
+    ms_per_step = t_total / args.steps * 1e3
+    value = flops / (t_total / args.steps) / 1e12
+    kern_avg_ms = sum(kern_ms) / len(kern_ms)
+    achieved = flops / (kern_avg_ms * 1e-3) / 1e12
+    cast_bytes = M * K * 2 + M * K // 2 + M * (K // 32) * 2
+    out = {
+        "metric": "AMXFP4 cast+GEMM TFLOPS at 4096x8192x28672", "value": round(value, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "M": M, "N": N, "K": K, "format": "AMXFP4 (E2M1 elements, FP8-E5M2 "
+                   "asymmetric scales, group 32)", "step": "amxfp4_quantize(X) + amxfp4_gemm(Xq, Wq), W pre-cast"},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES, "kernel_ms": round(kern_avg_ms, 4)},
+        "frac_of_fp4_mfma_peak": round(value / PEAK_FP4_TFLOPS, 4),
+        "breakdown_ms": {"cast_x": round(t_cast_x * 1e3, 4), "gemm_call": round(ms_per_step - t_cast_x * 1e3, 4),
+                         "gemm_mfma_kernel": round(kern_avg_ms, 4), "cast_w_once": round(t_cast_w * 1e3, 3)},
+        "cast_x_gbps": round(cast_bytes / t_cast_x / 1e9, 1),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(x_bits, w_bits, K)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

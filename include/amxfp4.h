@@ -130,6 +130,14 @@ int mxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const u
                const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
                int64_t batch, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid (not part of the method): arms a pair of caller-owned hipEvent_t (passed as void*) for the NEXT
+ * amxfp4_gemm / mxfp4_gemm call made on this host thread. That call records `start` on its stream immediately before
+ * and `stop` immediately after the launch of its matrix-multiply kernel (the MFMA main loop, excluding the operand
+ * re-layout kernels that precede it), then disarms itself. Pass NULL, NULL to disarm. Returns AMX_OK.
+ */
+int amxfp4_profile_next_gemm(void* start_event, void* stop_event);
+
 #ifdef __cplusplus
 }
 #endif

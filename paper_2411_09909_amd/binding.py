@@ -47,6 +47,8 @@ def load():
         d.argtypes = [fp, vp, vp, i64, i64, vp, ctypes.c_int32, vp]
         g.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, i64, i64, vp, ctypes.c_size_t, vp]
         q.restype = d.restype = g.restype = ctypes.c_int
+    L.amxfp4_profile_next_gemm.argtypes = [vp, vp]
+    L.amxfp4_profile_next_gemm.restype = ctypes.c_int
     _lib = L
     return L
 
@@ -80,6 +82,11 @@ def scales_bytes(fmt, rows, K):
 
 def gemm_workspace_bytes(fmt, M, N, K, batch=1):
     return load().amxfp4_gemm_workspace_bytes(ctypes.byref(fmt), M, N, K, batch)
+
+
+def profile_next_gemm(start_event, stop_event):
+    """Arms raw hipEvent_t handles (ints) around the matrix-multiply kernel of the next gemm() call."""
+    _check(load().amxfp4_profile_next_gemm(start_event, stop_event))
 
 
 def _fn(fmt, name, baseline):

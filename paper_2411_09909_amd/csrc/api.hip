@@ -9,6 +9,7 @@
 namespace {
 
 thread_local char g_err[256] = "no error";
+thread_local amx::KernelTimer g_timer;  // armed by amxfp4_profile_next_gemm, consumed by the next GEMM call
 
 int fail(int code, const char* fmt, ...) {
   va_list ap;
@@ -96,8 +97,10 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
       return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
     if (!aligned(workspace, 256)) return fail(AMX_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
   }
+  const amx::KernelTimer timer = g_timer;
+  g_timer = amx::KernelTimer();
   hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales,
-                                            C, ldc, batch, workspace, reinterpret_cast<hipStream_t>(stream));
+                                            C, ldc, batch, workspace, reinterpret_cast<hipStream_t>(stream), timer);
   return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
 }
 
@@ -112,6 +115,12 @@ amx_format_t symmetric(const amx_format_t* f) {
 extern "C" {
 
 const char* amxfp4_last_error(void) { return g_err; }
+
+int amxfp4_profile_next_gemm(void* start_event, void* stop_event) {
+  g_timer.start = reinterpret_cast<hipEvent_t>(start_event);
+  g_timer.stop = reinterpret_cast<hipEvent_t>(stop_event);
+  return AMX_OK;
+}
 
 size_t amxfp4_codes_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
   if (!fmt || rows <= 0 || K <= 0 || K % 2) return 0;

@@ -287,7 +287,8 @@ static hipError_t launch_tiles(const uint16_t* Ap, const uint16_t* Bp, float* C,
 
 hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                                  const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
-                                 int64_t ldc, int64_t batch, void* workspace, hipStream_t s) {
+                                 int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
+                                 const KernelTimer& timer) {
   const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows), Kp = round_up(K, kPanelK);
   uint16_t* Ap = reinterpret_cast<uint16_t*>(workspace);
   uint16_t* Bp = Ap + batch * Mp * Kp;
@@ -295,7 +296,11 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t M, int64_t N
   if (e != hipSuccess) return e;
   e = expand_dispatch(scale_kind, asym, B_codes, B_scales, N, K, Np, Kp, batch, Bp, s);
   if (e != hipSuccess) return e;
-  return launch_tiles<2, 2, 4, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);
+  if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
+  e = launch_tiles<2, 2, 4, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);
+  if (e != hipSuccess) return e;
+  if (timer.stop) e = hipEventRecord(timer.stop, s);
+  return e;
 }
 
 }  // namespace amx

@@ -24,10 +24,15 @@ hipError_t launch_quantize_strided(int scale_kind, bool asym, const uint16_t* x,
 hipError_t launch_dequantize(int scale_kind, bool asym, const uint8_t* codes, const uint8_t* scales, int64_t rows,
                              int64_t K, void* out, int out_dtype, hipStream_t s);
 
+// Optional event pair recorded around the matrix-multiply kernel of one GEMM call (measurement aid).
+struct KernelTimer {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+
 // gemm_bf16.hip
 size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
 hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                                  const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
-                                 int64_t ldc, int64_t batch, void* workspace, hipStream_t s);
+                                 int64_t ldc, int64_t batch, void* workspace, hipStream_t s, const KernelTimer& timer);
 
 }  // namespace amx
