@@ -11,6 +11,8 @@
 //      Rows are padded to a multiple of 256 and K to a multiple of 128 with zeros.
 //   2. GEMM kernel: every operand fragment is one contiguous KiB in the workspace, so staging global -> LDS is a
 //      linear copy and LDS -> register reads are conflict-free 128-bit reads at lane * 16.
+#include <stdlib.h>
+
 #include "device_formats.h"
 
 namespace amx {
@@ -297,7 +299,13 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t M, int64_t N
   e = expand_dispatch(scale_kind, asym, B_codes, B_scales, N, K, Np, Kp, batch, Bp, s);
   if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
-  e = launch_tiles<2, 2, 4, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);
+  static const int tile_cfg = getenv("AMXFP4_TILE") ? atoi(getenv("AMXFP4_TILE")) : 0;  // tuning experiments only
+  if (tile_cfg == 1)
+    e = launch_tiles<2, 4, 4, 2>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);
+  else if (tile_cfg == 2)
+    e = launch_tiles<4, 2, 2, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);
+  else
+    e = launch_tiles<2, 2, 4, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);
   if (e != hipSuccess) return e;
   if (timer.stop) e = hipEventRecord(timer.stop, s);
   return e;
