@@ -80,6 +80,12 @@ int dequantize_impl(amx_format_t f, const uint8_t* codes, const uint8_t* scales,
   return e == hipSuccess ? AMX_OK : hip_fail(e, "dequantize launch");
 }
 
+// Power-of-two scales go to the block-scaled FP4 matrix instruction (codes and scales consumed as they are); FP8
+// scales, and shapes that path does not take, go through exact BF16 expansion.
+bool uses_fp4_mfma(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
+  return (f.scale == AMX_SCALE_E8M0_FLOOR || f.scale == AMX_SCALE_E8M0_ROUND) && amx::fp4_path_supported(M, N, K);
+}
+
 int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
               const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch, void* workspace,
               size_t workspace_bytes, void* stream) {
@@ -99,6 +105,11 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
   }
   const amx::KernelTimer timer = g_timer;
   g_timer = amx::KernelTimer();
+  if (uses_fp4_mfma(f, M, N, K)) {
+    hipError_t e = amx::launch_gemm_fp4_path(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc,
+                                             batch, reinterpret_cast<hipStream_t>(stream), timer);
+    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
+  }
   hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales,
                                             C, ldc, batch, workspace, reinterpret_cast<hipStream_t>(stream), timer);
   return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
@@ -134,6 +145,7 @@ size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
 
 size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch) {
   if (!fmt || M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
+  if (uses_fp4_mfma(*fmt, M, N, K)) return 0;
   return amx::bf16_path_workspace_bytes(M, N, K, batch);
 }
 

@@ -14,13 +14,12 @@
 #include <stdlib.h>
 
 #include "device_formats.h"
+#include "gemm_common.h"
 
 namespace amx {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-constexpr int kFragBytes = 1024;  // 32 rows x 16 k x 2 bytes
 
 size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch) {
   const int64_t Kp = round_up(K, kPanelK);
@@ -72,37 +71,7 @@ __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------ GEMM ------------
-// Workgroup tile (32*FM*WM) x (32*FN*WN), WM x WN waves, each wave FM x FN MFMA tiles of 32x32.
-// LDS holds a ring of 4 stages (four arrays); one stage is a K slice of 32 (2 MFMA k-steps): per 32-row block 2 fragments.
-constexpr int kStageK = 32;
-
-template <int WM, int WN, int FM, int FN>
-struct TileCfg {
-  static constexpr int kWaves = WM * WN;
-  static constexpr int kThreads = 64 * kWaves;
-  static constexpr int kTileM = 32 * FM * WM;
-  static constexpr int kTileN = 32 * FN * WN;
-  static constexpr int kFragsA = (kTileM / 32) * 2;  // fragments per stage
-  static constexpr int kFragsB = (kTileN / 32) * 2;
-  static constexpr int kLoads = (kFragsA + kFragsB) / kWaves;  // direct-to-LDS loads per wave per stage
-  static constexpr int kStageBytes = (kFragsA + kFragsB) * kFragBytes;
-  static_assert(kFragsA % kWaves == 0 && kFragsB % kWaves == 0, "fragments must divide evenly over the waves");
-  static_assert(FM % 2 == 0, "the A register ring of 4 needs an even number of steps per k-step");
-  static_assert(kLoads <= 15, "s_waitcnt immediates below assume at most 15 loads per stage");
-};
-
-// Supertile: the tiles that run at the same time on one XCD (32 CUs, one L2): 8 along M x 4 along N, so that every
-// staged A panel is shared by 4 and every B panel by 8 workgroups through that L2. Workgroups are dealt to the 8 XCDs
-// round-robin by their linear id, hence id % 8 picks the XCD and id / 8 the slot on it.
-constexpr int kSuperM = 8, kSuperN = 4;
-
-// s_waitcnt immediate that waits until at most n (< 16) vector-memory operations are outstanding and nothing else
-#define AMX_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
-// workgroup barrier without the memory fence __syncthreads() implies: the data movement around it is ordered by the
-// explicit vmcnt waits (direct-to-LDS loads) and by the MFMA operand dependencies (LDS reads)
-#define AMX_BARRIER() asm volatile("s_barrier" ::: "memory")
-
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
+// Tile configuration, stage ring and supertile order: gemm_common.h. Here one stage is a K slice of 32.
 
 template <int WM, int WN, int FM, int FN>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t* __restrict__ Ap,
@@ -124,13 +93,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t*
   const int64_t b = blockIdx.z;
 
   int tm, tn;
-  {
-    const int p = blockIdx.x, xcd = p & 7, q = p >> 3;
-    const int st = (q / (kSuperM * kSuperN)) * 8 + xcd, slot = q % (kSuperM * kSuperN);
-    tm = (st % super_m) * kSuperM + slot % kSuperM;
-    tn = (st / super_m) * kSuperN + slot / kSuperM;
-    if (tm >= tiles_m || tn >= tiles_n) return;  // uniform over the workgroup, before any barrier
-  }
+  if (!tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, super_m, tm, tn)) return;  // uniform, before any barrier
 
   // Buffer descriptors over this tile's slice of each panel: (tile rows / 32) row blocks x kblocks fragments of 1 KiB.
   // Raw buffer (stride 0), so reads past num_records return zero instead of faulting.
@@ -172,7 +135,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t*
           (((f_ - kFragsA) >> 1) * kblocks + (ST) * 2 + (f_ & 1)) * kFragBytes, 0, 0);                     \
   }
 
-  const int nstages = (int)(Kp / kStageK);  // multiple of 4
+  const int nstages = (int)(Kp / 32);  // one stage = a K slice of 32 BF16 (2 MFMA k-steps); multiple of 4
   // prologue: 3 stages in flight; stages 0 and 1 must have landed before the first fragment reads
 #pragma unroll
   for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 0, lds0);
@@ -279,10 +242,9 @@ static hipError_t launch_tiles(const uint16_t* Ap, const uint16_t* Bp, float* C,
                                int64_t Np, int64_t Kp, int64_t ldc, int64_t batch, hipStream_t s) {
   using Cfg = TileCfg<WM, WN, FM, FN>;
   const int tiles_m = (int)((M + Cfg::kTileM - 1) / Cfg::kTileM), tiles_n = (int)((N + Cfg::kTileN - 1) / Cfg::kTileN);
-  const int super_m = (tiles_m + kSuperM - 1) / kSuperM, super_n = (tiles_n + kSuperN - 1) / kSuperN;
-  const int rounds = (super_m * super_n + 7) / 8;  // supertiles are dealt 8 at a time, one per XCD
-  hipLaunchKernelGGL((gemm_bf16_kernel<WM, WN, FM, FN>), dim3((unsigned)(rounds * 8 * kSuperM * kSuperN), 1,
-                                                              (unsigned)batch),
+  int super_m;
+  const unsigned grid = supertile_grid(tiles_m, tiles_n, super_m);
+  hipLaunchKernelGGL((gemm_bf16_kernel<WM, WN, FM, FN>), dim3(grid, 1, (unsigned)batch),
                      dim3(Cfg::kThreads), 0, s, Ap, Bp, C, M, N, Mp, Np, Kp, ldc, tiles_m, tiles_n, super_m);
   return hipGetLastError();
 }

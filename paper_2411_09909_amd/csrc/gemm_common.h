@@ -1,0 +1,62 @@
+// Pieces shared by the GEMM kernels: tile configuration, the 4-stage LDS ring bookkeeping, the XCD-aware tile order and
+// the wait / barrier primitives of the software pipeline.
+//
+// Pipeline (both kernels): a workgroup tile of (32*FM*WM) x (32*FN*WN) outputs is computed by WM x WN waves, each
+// owning FM x FN MFMA tiles of 32x32. K is consumed in stages; one stage holds, per 32-row block of either operand,
+// 2 fragments of 1 KiB (64 lanes x 16 bytes = the register image of one MFMA operand). Four stage buffers form a
+// ring: while stage S is multiplied, stage S+1 is already complete in LDS (fragment reads run ahead into it), and
+// stages S+2 and S+3 are in flight as direct-to-LDS buffer loads.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace amx {
+
+constexpr int kFragBytes = 1024;  // one MFMA operand fragment: 64 lanes x 16 bytes
+
+template <int WM, int WN, int FM, int FN>
+struct TileCfg {
+  static constexpr int kWaves = WM * WN;
+  static constexpr int kThreads = 64 * kWaves;
+  static constexpr int kTileM = 32 * FM * WM;
+  static constexpr int kTileN = 32 * FN * WN;
+  static constexpr int kFragsA = (kTileM / 32) * 2;  // fragments per stage
+  static constexpr int kFragsB = (kTileN / 32) * 2;
+  static constexpr int kLoads = (kFragsA + kFragsB) / kWaves;  // direct-to-LDS loads per wave per stage
+  static constexpr int kStageBytes = (kFragsA + kFragsB) * kFragBytes;
+  static_assert(kFragsA % kWaves == 0 && kFragsB % kWaves == 0, "fragments must divide evenly over the waves");
+  static_assert(FM % 2 == 0, "the A register ring of 4 needs an even number of steps per k-step");
+};
+
+// Supertile: the tiles that run at the same time on one XCD (32 CUs, one L2): 8 along M x 4 along N, so that every
+// staged A panel is shared by 4 and every B panel by 8 workgroups through that L2. Workgroups are dealt to the 8 XCDs
+// round-robin by their linear id, hence id % 8 picks the XCD and id / 8 the slot on it.
+constexpr int kSuperM = 8, kSuperN = 4;
+
+// Tile coordinates of workgroup `p`; false if it has no tile (grid padding).
+__device__ __forceinline__ bool tile_of_workgroup(int p, int tiles_m, int tiles_n, int super_m, int& tm, int& tn) {
+  const int xcd = p & 7, q = p >> 3;
+  const int st = (q / (kSuperM * kSuperN)) * 8 + xcd, slot = q % (kSuperM * kSuperN);
+  tm = (st % super_m) * kSuperM + slot % kSuperM;
+  tn = (st / super_m) * kSuperN + slot / kSuperM;
+  return tm < tiles_m && tn < tiles_n;
+}
+
+// Grid size (x) for a tiles_m x tiles_n problem: supertiles are dealt 8 at a time, one per XCD.
+inline unsigned supertile_grid(int tiles_m, int tiles_n, int& super_m) {
+  super_m = (tiles_m + kSuperM - 1) / kSuperM;
+  const int super_n = (tiles_n + kSuperN - 1) / kSuperN;
+  const int rounds = (super_m * super_n + 7) / 8;
+  return (unsigned)(rounds * 8 * kSuperM * kSuperN);
+}
+
+// s_waitcnt immediate that waits until at most n (< 64) vector-memory operations are outstanding and nothing else
+// (gfx9 encoding: vmcnt = bits 3:0 and 15:14, expcnt = bits 6:4, lgkmcnt = bits 11:8)
+#define AMX_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+// workgroup barrier without the memory fence __syncthreads() implies: the data movement around it is ordered by the
+// explicit vmcnt waits (direct-to-LDS loads) and by the MFMA operand dependencies (LDS reads)
+#define AMX_BARRIER() asm volatile("s_barrier" ::: "memory")
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+}  // namespace amx

@@ -35,4 +35,10 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t M, int64_t N
                                  const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
                                  int64_t ldc, int64_t batch, void* workspace, hipStream_t s, const KernelTimer& timer);
 
+// gemm_fp4.hip: power-of-two scales on the block-scaled FP4 MFMA (no workspace)
+bool fp4_path_supported(int64_t M, int64_t N, int64_t K);
+hipError_t launch_gemm_fp4_path(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                                const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
+                                int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer);
+
 }  // namespace amx

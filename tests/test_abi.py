@@ -45,6 +45,9 @@ def test_size_queries(lib):
     # workspace: BF16 panels padded to 256 rows / 128 columns of K
     assert binding.gemm_workspace_bytes(f, 64, 1024, 1024) == (256 + 1024) * 1024 * 2
     assert binding.gemm_workspace_bytes(f, 300, 10, 96, 2) == 2 * (512 + 256) * 128 * 2
+    # power-of-two scales with K % 128 == 0 run on the FP4 MFMA straight from the caller's arrays: no workspace
+    assert binding.gemm_workspace_bytes(g, 64, 1024, 1024) == 0
+    assert binding.gemm_workspace_bytes(g, 64, 1024, 96) == (256 + 1024) * 128 * 2
 
 
 def _q(lib, fmt, x, rows, K, rs, ks, codes, scales):

@@ -28,20 +28,25 @@ def test_config1_full(scale, asym):
     assert np.allclose(C, Cr, rtol=1e-4, atol=1e-4 * np.abs(Cr).max())
 
 
-@pytest.mark.parametrize("M,N,K", [(1, 1, 32), (33, 65, 96), (100, 200, 160), (257, 255, 544), (300, 520, 1024)])
-def test_ragged_shapes(M, N, K):
-    """Shapes that are not multiples of the 256 x 256 x 128 tiling: partial tiles, K tail, single group."""
+@pytest.mark.parametrize("scale,asym", FORMATS)
+@pytest.mark.parametrize("M,N,K", [(1, 1, 32), (33, 65, 96), (100, 200, 160), (257, 255, 544), (300, 520, 1024),
+                                   (1, 1, 128), (31, 257, 384), (260, 300, 640)])
+def test_ragged_shapes(M, N, K, scale, asym):
+    """Shapes that are not multiples of the 256 x 256 tiling: partial tiles, K tails, a single group. For the
+    power-of-two scale formats, K % 128 == 0 runs on the block-scaled FP4 MFMA (with K / 128 not a multiple of the
+    4-stage ring), the other K values on the BF16 expansion path."""
     a = synth.activations(M, K, seed=M + K, n_outlier=1, outlier_gain=60.0)
     b = synth.weights(N, K, seed=N)
-    ac, as_ = ref.quantize(a)
-    bc, bs = ref.quantize(b)
-    C = G.gpu_gemm(ac, as_, bc, bs, ref.FP8_E5M2, 1)
-    Cr = ref.gemm(ac, as_, bc, bs)
+    ac, as_ = ref.quantize(a, 32, scale, asym)
+    bc, bs = ref.quantize(b, 32, scale, asym)
+    C = G.gpu_gemm(ac, as_, bc, bs, scale, asym)
+    Cr = ref.gemm(ac, as_, bc, bs, 32, scale, asym)
     assert C.shape == (M, N)
     assert G.rel_fro(C, Cr) <= TOL
 
 
-def test_integer_exact_bit_for_bit_and_batched():
+@pytest.mark.parametrize("asym", [1, 0])
+def test_integer_exact_bit_for_bit_and_batched(asym):
     """Scales 1 and integer codes: every partial sum is an integer below 2^24, so FP32 accumulation in any order is
     exact and the GPU result must equal the oracle bit for bit. Also covers batch > 1 and several tiles."""
     rng = np.random.default_rng(3)
@@ -52,12 +57,13 @@ def test_integer_exact_bit_for_bit_and_batched():
         mag = rng.choice(mags, size=(batch, rows, K))
         sgn = rng.integers(0, 2, size=(batch, rows, K))
         nib = (mag | (sgn << 3)).astype(np.uint8)
-        return nib[..., 0::2] | (nib[..., 1::2] << 4), np.full((batch, rows, K // 32, 2), 127, np.uint8)
+        shape = (batch, rows, K // 32, 2) if asym else (batch, rows, K // 32)
+        return nib[..., 0::2] | (nib[..., 1::2] << 4), np.full(shape, 127, np.uint8)
 
     ac, as_ = operand(M)
     bc, bs = operand(N)
-    C = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1)
-    Cr = ref.gemm(ac, as_, bc, bs, 32, ref.E8M0_FLOOR, 1)
+    C = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, asym)
+    Cr = ref.gemm(ac, as_, bc, bs, 32, ref.E8M0_FLOOR, asym)
     assert C.shape == (batch, M, N)
     assert np.array_equal(C, Cr)
 
@@ -72,16 +78,23 @@ def test_sign_pair_scale_selection_on_gpu():
     assert G.rel_fro(C1, Cr) <= TOL
     C0 = ref.gemm(ac, as_, bc, bs)
     assert G.rel_fro(C1, C0) > 0.05  # the swap really matters on this data
+    # the same on the sign-split FP4 path (power-of-two scales)
+    ac, as_, bc, bs = quantized("c1_linear_64x1024x1024", ref.E8M0_FLOOR, 1, M=32, N=64)
+    swapped = np.ascontiguousarray(bs[..., ::-1])
+    C1 = G.gpu_gemm(ac, as_, bc, swapped, ref.E8M0_FLOOR, 1)
+    assert G.rel_fro(C1, ref.gemm(ac, as_, bc, swapped, 32, ref.E8M0_FLOOR, 1)) <= TOL
+    assert G.rel_fro(C1, ref.gemm(ac, as_, bc, bs, 32, ref.E8M0_FLOOR, 1)) > 0.05
 
 
+@pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.E8M0_FLOOR, 0), (ref.E8M0_FLOOR, 1)])
 @pytest.mark.parametrize("name,M,N", [("c2_llama7b_qkvo_2048x4096x4096", 512, 768),
                                       ("c3_70b_up_4096x8192x28672", 256, 512),
                                       ("c3_70b_down_4096x28672x8192", 256, 256)])
-def test_llm_shapes_cut_down(name, M, N):
+def test_llm_shapes_cut_down(name, M, N, scale, asym):
     """Full K of the LLaMA-7B / 70B shaped linears, M and N cut so the oracle finishes in seconds."""
-    ac, as_, bc, bs = quantized(name, ref.FP8_E5M2, 1, M=M, N=N)
-    C = G.gpu_gemm(ac, as_, bc, bs, ref.FP8_E5M2, 1)
-    Cr = ref.gemm(ac, as_, bc, bs)
+    ac, as_, bc, bs = quantized(name, scale, asym, M=M, N=N)
+    C = G.gpu_gemm(ac, as_, bc, bs, scale, asym)
+    Cr = ref.gemm(ac, as_, bc, bs, 32, scale, asym)
     assert G.rel_fro(C, Cr) <= TOL
 
 
