@@ -22,8 +22,17 @@ WORKLOAD = "c3_70b_up_4096x8192x28672"
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense BF16 MFMA
 PEAK_FP4_TFLOPS = 10100.0   # MI355X dense block-scaled FP4 MFMA (the metric's reference peak)
 # HBM bytes per GEMM-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see
-# profiles/gemm_bf16_c3_up_counters.md; None until that profile has been taken.
-MEASURED_TRAFFIC_BYTES = None
+# profiles/gemm_bf16_c3_up_counters.md.
+MEASURED_TRAFFIC_BYTES = 3.29e9  # 2.82 GB fetched + 0.47 GB written
+
+
+# format name -> (scale kind, asymmetric, MFMA type issued by the GEMM, its dense peak in TFLOP/s)
+FORMATS = {
+    "amxfp4_e5m2": (2, True, "bf16", PEAK_BF16_TFLOPS),    # the paper's AMXFP4: FP8-E5M2 asymmetric scales
+    "mxfp4_e5m2": (2, False, "bf16", PEAK_BF16_TFLOPS),    # the paper's "MXFP4" rows: FP8-E5M2 symmetric scale
+    "mxfp4_e8m0": (0, False, "fp4", PEAK_FP4_TFLOPS),      # OCP MXFP4 (power-of-two scale, exponent floored)
+    "amxfp4_e8m0": (0, True, "fp4", PEAK_FP4_TFLOPS),      # asymmetric power-of-two scales: sign-split, 4 MFMAs/block
+}
 
 
 class HipEvents:
@@ -76,6 +85,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", default=WORKLOAD)
+    ap.add_argument("--format", default="amxfp4_e5m2", choices=sorted(FORMATS),
+                    help="operand format of the timed step (default: the paper's AMXFP4)")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time the other formats (MXFP4 baselines, power-of-two scales) and list them")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (the known-size reference that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -100,66 +113,83 @@ def main():
     xd = torch.from_numpy(x_bits.view(np.int16)).to(dev).view(torch.bfloat16)
     wd = torch.from_numpy(w_bits.view(np.int16)).to(dev).view(torch.bfloat16)
 
-    fmt = binding.make_format(binding.FP8_E5M2, True)
-    xc = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
-    xs = torch.empty((M, K // 32, 2), dtype=torch.uint8, device=dev)
     C = torch.empty((M, N), dtype=torch.float32, device=dev)
-    ws = torch.empty(binding.gemm_workspace_bytes(fmt, M, N, K), dtype=torch.uint8, device=dev)
-
-    # weights: cast once (timed on its own)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    wc, wsc = binding.quantize(fmt, wd)
-    torch.cuda.synchronize()
-    t_cast_w = time.perf_counter() - t0
-    del wd
-
-    def step(pair=None):
-        binding.quantize(fmt, xd, codes=xc, scales=xs)
-        if pair is not None:
-            binding.profile_next_gemm(pair[0], pair[1])
-        binding.gemm(fmt, xc, xs, wc, wsc, out=C, workspace=ws)
-
-    for _ in range(args.warmup):
-        step()
-    ev = HipEvents(args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(ev.pairs[i])
-    torch.cuda.synchronize()
-    t_total = time.perf_counter() - t0
-    kern_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
-    ev.destroy()
-
-    # cast alone, for the breakdown
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        binding.quantize(fmt, xd, codes=xc, scales=xs)
-    torch.cuda.synchronize()
-    t_cast_x = (time.perf_counter() - t0) / args.steps
-
     flops = 2.0 * M * N * K
-    ms_per_step = t_total / args.steps * 1e3
-    value = flops / (t_total / args.steps) / 1e12
-    kern_avg_ms = sum(kern_ms) / len(kern_ms)
-    achieved = flops / (kern_avg_ms * 1e-3) / 1e12
-    cast_bytes = M * K * 2 + M * K // 2 + M * (K // 32) * 2
+
+    def run_format(name, steps, warmup):
+        """Times `steps` steps (cast X + GEMM against pre-cast W) in the given format; returns a dict of timings."""
+        kind, asym, mfma, peak = FORMATS[name]
+        fmt = binding.make_format(kind, asym)
+        nsc = (M, K // 32, 2) if asym else (M, K // 32)
+        xc = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+        xs = torch.empty(nsc, dtype=torch.uint8, device=dev)
+        need = binding.gemm_workspace_bytes(fmt, M, N, K)
+        ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else None
+        binding.quantize(fmt, xd, codes=xc, scales=xs)  # first launch of this kernel: module load, not timed
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        wc, wsc = binding.quantize(fmt, wd)  # weights: cast once, outside the timed step
+        torch.cuda.synchronize()
+        t_cast_w = time.perf_counter() - t0
+
+        def step(pair=None):
+            binding.quantize(fmt, xd, codes=xc, scales=xs)
+            if pair is not None:
+                binding.profile_next_gemm(pair[0], pair[1])
+            binding.gemm(fmt, xc, xs, wc, wsc, out=C, workspace=ws)
+
+        for _ in range(warmup):
+            step()
+        ev = HipEvents(steps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(ev.pairs[i])
+        torch.cuda.synchronize()
+        t_total = time.perf_counter() - t0
+        kern_ms = sum(ev.elapsed_ms(i) for i in range(steps)) / steps
+        ev.destroy()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            binding.quantize(fmt, xd, codes=xc, scales=xs)
+        torch.cuda.synchronize()
+        t_cast_x = (time.perf_counter() - t0) / steps
+        return {"t_step": t_total / steps, "kern_ms": kern_ms, "t_cast_x": t_cast_x, "t_cast_w": t_cast_w,
+                "mfma": mfma, "peak": peak, "asym": asym}
+
+    r = run_format(args.format, args.steps, args.warmup)
+    ms_per_step = r["t_step"] * 1e3
+    value = flops / r["t_step"] / 1e12
+    achieved = flops / (r["kern_ms"] * 1e-3) / 1e12
+    cast_bytes = M * K * 2 + M * K // 2 + M * (K // 32) * (2 if r["asym"] else 1)
     out = {
         "metric": "AMXFP4 cast+GEMM TFLOPS at 4096x8192x28672", "value": round(value, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "M": M, "N": N, "K": K, "format": "AMXFP4 (E2M1 elements, FP8-E5M2 "
-                   "asymmetric scales, group 32)", "step": "amxfp4_quantize(X) + amxfp4_gemm(Xq, Wq), W pre-cast"},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": round(achieved, 2),
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES, "kernel_ms": round(kern_avg_ms, 4)},
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": r["mfma"], "data": "synthetic",
+        "config": {"workload": args.workload, "M": M, "N": N, "K": K, "format": args.format, "group_size": 32,
+                   "step": "amxfp4_quantize(X) + amxfp4_gemm(Xq, Wq), W pre-cast"},
+        "roofline": {"bound": "mfma", "kernel": "gemm_%s_kernel" % r["mfma"], "achieved": round(achieved, 2),
+                     "peak": r["peak"], "unit": "TFLOP/s", "frac": round(achieved / r["peak"], 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES if args.format == "amxfp4_e5m2" and args.workload == WORKLOAD
+                     else None, "kernel_ms": round(r["kern_ms"], 4)},
         "frac_of_fp4_mfma_peak": round(value / PEAK_FP4_TFLOPS, 4),
-        "breakdown_ms": {"cast_x": round(t_cast_x * 1e3, 4), "gemm_call": round(ms_per_step - t_cast_x * 1e3, 4),
-                         "gemm_mfma_kernel": round(kern_avg_ms, 4), "cast_w_once": round(t_cast_w * 1e3, 3)},
-        "cast_x_gbps": round(cast_bytes / t_cast_x / 1e9, 1),
+        "breakdown_ms": {"cast_x": round(r["t_cast_x"] * 1e3, 4),
+                         "gemm_call": round(ms_per_step - r["t_cast_x"] * 1e3, 4),
+                         "gemm_mfma_kernel": round(r["kern_ms"], 4), "cast_w_once": round(r["t_cast_w"] * 1e3, 3)},
+        "cast_x_gbps": round(cast_bytes / r["t_cast_x"] / 1e9, 1),
     }
+    if args.variants:
+        out["variants"] = {}
+        for name in sorted(FORMATS):
+            if name == args.format:
+                continue
+            v = run_format(name, max(3, args.steps // 2), 2)
+            out["variants"][name] = {"value": round(flops / v["t_step"] / 1e12, 2), "unit": "TFLOP/s",
+                                     "ms_per_step": round(v["t_step"] * 1e3, 4), "mfma": v["mfma"],
+                                     "gemm_kernel_ms": round(v["kern_ms"], 4),
+                                     "kernel_frac_of_mfma_peak": round(flops / (v["kern_ms"] * 1e-3) / 1e12 /
+                                                                       v["peak"], 4)}
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)

@@ -10,9 +10,9 @@
 //
 // Operand fragment of the instruction for FP4: lane l holds row l%32, K block l/32 (32 codes = 16 bytes, element k in
 // bits 4k+3:4k), and supplies the scale byte of that (row, K block) in a VGPR byte picked by the instruction's opsel.
-// The canonical code layout already has those 16 bytes contiguous, so fragments are gathered straight from the
-// caller's arrays by direct-to-LDS buffer loads with a per-lane offset (no re-layout pass, no workspace).
-// One stage = K slice of 128 (2 MFMA k-steps of 64): same fragment count and LDS ring as the BF16 kernel.
+// The canonical code layout already has those 16 bytes contiguous, so tiles are staged straight from the caller's
+// arrays by direct-to-LDS buffer loads with per-lane offsets (no re-layout pass, no workspace).
+// One stage = K slice of 128 (2 MFMA k-steps of 64): same byte count and LDS ring as the BF16 kernel.
 #include "device_formats.h"
 #include "gemm_common.h"
 
@@ -60,7 +60,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   constexpr int kWaves = Cfg::kWaves, kFragsA = Cfg::kFragsA, kLoads = Cfg::kLoads, kTileM = Cfg::kTileM,
                 kTileN = Cfg::kTileN;
   constexpr int kScaleBytes = ASYM ? 2 : 1;                    // per group
-  constexpr int kScaleLoads = (FM + FN) * (ASYM ? 2 : 1);      // dword loads per wave per stage
   const int row_bytes = (int)(K >> 1);                         // codes per row
   const int srow_bytes = (int)(K >> 5) * kScaleBytes;          // scale bytes per row
   const int rows_a = (int)(M - (int64_t)tm * kTileM < kTileM ? M - (int64_t)tm * kTileM : kTileM);
@@ -77,10 +76,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   const __amdgpu_buffer_rsrc_t Bsr = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t*>(Bs + (b * N + (int64_t)tn * kTileN) * srow_bytes), 0, rows_b * srow_bytes, 0x00020000);
 
-  const int lane_off = lane * 16;
-  const int kb = lane >> 5;                                   // K block of this lane inside a 64-wide k-step
-  const int gather_off = (lane & 31) * row_bytes + kb * 16;   // this lane's 16 bytes inside a 32-row x 64-k fragment
+  // Staging geometry. One direct-to-LDS load moves 16 rows x 64 bytes (4 lanes per row: the stage's 128 codes of that
+  // row), so every lane quad reads one aligned 64-byte segment of its row. Its LDS image is [16 rows][4 chunks of
+  // 16 bytes]; two loads make a row block of 32 rows x 64 bytes = 2 KiB. The chunk a lane fetches is permuted by the
+  // row (chunk = slot ^ ((row >> 2) & 3)) so that the fragment reads below (32 consecutive rows, one chunk each) fall
+  // on 16 distinct 16-byte bank groups per 16 lanes.
+  const int kb = lane >> 5;  // K block (of 32 codes) of this lane inside a 64-wide k-step
+  const int gather_off = (lane >> 2) * row_bytes + (((lane & 3) ^ ((lane >> 4) & 3)) << 4);
   const int sgather_off = (lane & 31) * srow_bytes;
+  // fragment read offsets inside a row block for k-step 0 and 1: row r = lane % 32 holds chunk c at slot c ^ ((r>>2)&3)
+  const int rr = lane & 31;
+  const int offk0 = rr * 64 + (((0 + kb) ^ ((rr >> 2) & 3)) << 4);
+  const int offk1 = rr * 64 + (((2 + kb) ^ ((rr >> 2) & 3)) << 4);
 
   f32x16 acc[FM][FN];
 #pragma unroll
@@ -90,33 +97,44 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // Load L of this wave for stage ST: fragment f = wave + kWaves * L; f < kFragsA: A row block f/2, k-step f%2.
-#define AMX_ISSUE_LOAD(L, ST, DST)                                                                           \
-  {                                                                                                          \
-    const int f_ = wave + kWaves * (L);                                                                      \
-    if ((L) < kFragsA / kWaves)                                                                              \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(Ar, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, gather_off,     \
-                                               (f_ >> 1) * 32 * row_bytes + (ST) * 64 + (f_ & 1) * 32, 0, 0); \
-    else                                                                                                     \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                              \
-          Br, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, gather_off,                                          \
-          ((f_ - kFragsA) >> 1) * 32 * row_bytes + (ST) * 64 + (f_ & 1) * 32, 0, 0);                         \
+  // Load L of this wave for stage ST: half row block f = wave + kWaves * L (row block f / 2, rows 16 * (f % 2) ..);
+  // f < kFragsA: operand A, otherwise B. Lands at DST + f KiB.
+#define AMX_ISSUE_LOAD(L, ST, DST)                                                                              \
+  {                                                                                                             \
+    const int f_ = wave + kWaves * (L);                                                                         \
+    if ((L) < kFragsA / kWaves)                                                                                 \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(Ar, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, gather_off,        \
+                                               f_ * 16 * row_bytes + (ST) * 64, 0, 0);                          \
+    else                                                                                                        \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(Br, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, gather_off,        \
+                                               (f_ - kFragsA) * 16 * row_bytes + (ST) * 64, 0, 0);              \
   }
 
-  // Scale words of one stage, per lane: for row block r of A (or B) the 4 (symmetric) or 2 x 4 (asymmetric: pos, neg
-  // interleaved) scale bytes of this lane's row for the stage's 4 groups, shifted so that the bytes of this lane's
-  // K block come first. sa[r][h]: h = k-step for the asymmetric layout (one dword = 2 groups x (pos, neg)).
-  constexpr int kSW = ASYM ? 2 : 1;
-  uint32_t sa[2][FM][kSW], sb[2][FN][kSW];
-#define AMX_LOAD_SCALES(BUF, ST)                                                                                   \
-  {                                                                                                                \
-    _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int h = 0; h < kSW; ++h) sa[BUF][i][h] = \
-        __builtin_amdgcn_raw_buffer_load_b32(Asr, sgather_off + (ST) * 4 * kScaleBytes + h * 4,                \
-                                                 (wm * FM + i) * 32 * srow_bytes, 0);                              \
-    _Pragma("unroll") for (int j = 0; j < FN; ++j) _Pragma("unroll") for (int h = 0; h < kSW; ++h) sb[BUF][j][h] = \
-        __builtin_amdgcn_raw_buffer_load_b32(Bsr, sgather_off + (ST) * 4 * kScaleBytes + h * 4,                \
-                                                 (wn * FN + j) * 32 * srow_bytes, 0);                              \
+  // Scale words, per lane and row block, for a PAIR of stages (8 groups of this lane's row): symmetric = 8 bytes
+  // (one per group), asymmetric = 16 bytes ((pos, neg) per group). Two register sets alternate: pair P of stages
+  // (2P, 2P+1) lives in set P & 1 and is requested two stages ahead.
+  typedef uint32_t sword_t __attribute__((ext_vector_type(ASYM ? 4 : 2)));
+  sword_t sa[2][FM], sb[2][FN];
+#define AMX_LOAD_SCALES(SET, PAIR)                                                                                  \
+  {                                                                                                                 \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                                                \
+      if constexpr (ASYM)                                                                                           \
+        sa[SET][i] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b128(                             \
+                                                     Asr, sgather_off + (PAIR) * 16, (wm * FM + i) * 32 * srow_bytes, 0)); \
+      else                                                                                                          \
+        sa[SET][i] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b64(                              \
+                                                     Asr, sgather_off + (PAIR) * 8, (wm * FM + i) * 32 * srow_bytes, 0));  \
+    }                                                                                                               \
+    _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                                                \
+      if constexpr (ASYM)                                                                                           \
+        sb[SET][j] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b128(                             \
+                                                     Bsr, sgather_off + (PAIR) * 16, (wn * FN + j) * 32 * srow_bytes, 0)); \
+      else                                                                                                          \
+        sb[SET][j] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b64(                              \
+                                                     Bsr, sgather_off + (PAIR) * 8, (wn * FN + j) * 32 * srow_bytes, 0));  \
+    }                                                                                                               \
   }
+  constexpr int kScaleLoads = FM + FN;  // per pair of stages
 
   const int nstages = (int)(K >> 7);  // K is a multiple of 128 on this path
 #pragma unroll
@@ -130,32 +148,32 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   AMX_BARRIER();
 
   uint4 aR[4], bR[2][FN];
-  const int offA = lane_off + (wm * FM) * 2 * kFragBytes;
-  const int offB = lane_off + (kFragsA + (wn * FN) * 2) * kFragBytes;
-  aR[0] = *reinterpret_cast<const uint4*>(lds0 + offA);
-  aR[1] = *reinterpret_cast<const uint4*>(lds0 + offA + 2 * kFragBytes);
+  const int baseA = (wm * FM) * 2 * kFragBytes;
+  const int baseB = (kFragsA + (wn * FN) * 2) * kFragBytes;
+  aR[0] = *reinterpret_cast<const uint4*>(lds0 + baseA + offk0);
+  aR[1] = *reinterpret_cast<const uint4*>(lds0 + baseA + 2 * kFragBytes + offk0);
 #pragma unroll
-  for (int j = 0; j < FN; ++j) bR[0][j] = *reinterpret_cast<const uint4*>(lds0 + offB + j * 2 * kFragBytes);
+  for (int j = 0; j < FN; ++j) bR[0][j] = *reinterpret_cast<const uint4*>(lds0 + baseB + j * 2 * kFragBytes + offk0);
 
-  // One MFMA group of step (ks, i): symmetric = FN instructions, asymmetric = 4 FN (the four sign pairs).
-  // Scale byte selection: symmetric word = bytes (g0 g1 g2 g3) >> 8*kb, k-step ks uses byte 2*ks; asymmetric word h=ks
-  // = bytes (p0 n0 p1 n1) >> 16*kb, pos = byte 0, neg = byte 1.
-#define AMX_MMA(BUF, KS, I)                                                                                          \
+  // The MFMAs of step (KS, I) of stage Q (0 or 1) of a scale pair held in set SET. Scale byte selection:
+  // symmetric: word Q = bytes (g0 g1 g2 g3) of the stage, shifted by 8*kb; k-step KS uses byte 2*KS (opsel);
+  // asymmetric: word 2*Q + KS = bytes (p0 n0 p1 n1) of the k-step, shifted by 16*kb; pos = byte 0, neg = byte 1.
+#define AMX_MMA(SET, Q, KS, I)                                                                                       \
   {                                                                                                                  \
     if constexpr (!ASYM) {                                                                                           \
-      const int sav = (int)(sa[BUF][I][0] >> (8 * kb));                                                              \
+      const int sav = (int)(sa[SET][I][Q] >> (8 * kb));                                                              \
       const i32x8 av = as_operand(aR[((KS) * FM + (I)) & 3]);                                                        \
       _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                                               \
-        const int sbv = (int)(sb[BUF][j][0] >> (8 * kb));                                                            \
+        const int sbv = (int)(sb[SET][j][Q] >> (8 * kb));                                                            \
         acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, as_operand(bR[(KS) & 1][j]), acc[I][j], 4,   \
                                                                     4, 2 * (KS), sav, 2 * (KS), sbv);                \
       }                                                                                                              \
     } else {                                                                                                         \
-      const int sav = (int)(sa[BUF][I][KS] >> (16 * kb));                                                            \
+      const int sav = (int)(sa[SET][I][2 * (Q) + (KS)] >> (16 * kb));                                                \
       const uint4 araw = aR[((KS) * FM + (I)) & 3];                                                                  \
       const i32x8 ap = as_operand(sign_class4<false>(araw)), an = as_operand(sign_class4<true>(araw));              \
       _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                                               \
-        const int sbv = (int)(sb[BUF][j][KS] >> (16 * kb));                                                          \
+        const int sbv = (int)(sb[SET][j][2 * (Q) + (KS)] >> (16 * kb));                                              \
         const i32x8 bp = as_operand(sign_class4<false>(bR[(KS) & 1][j])),                                            \
                     bn = as_operand(sign_class4<true>(bR[(KS) & 1][j]));                                             \
         acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ap, bp, acc[I][j], 4, 4, 0, sav, 0, sbv);        \
@@ -166,48 +184,51 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
     }                                                                                                                \
   }
 
-  // Stage S with scale buffer BUF (= S & 1): see gemm_bf16.hip for the ring discipline. The scale words of stage S + 1
-  // are requested first, then each step reads fragments ahead, issues its share of the stage S + 3 loads and multiplies.
-#define AMX_STAGE(S, BUF, CUR, NXT, FETCH)                                                                        \
+  // Stage S = stage Q (0 / 1) of the scale pair in set SET; ring discipline as in gemm_bf16.hip. An even stage first
+  // requests the scale words of the next pair (stages S + 2, S + 3) into the other set, whose previous contents
+  // (stages S - 2, S - 1) are dead. Then each step reads fragments ahead, issues its share of the stage S + 3 loads and
+  // multiplies.
+#define AMX_STAGE(S, SET, Q, CUR, NXT, FETCH)                                                                     \
   {                                                                                                               \
     const int fetch_ = (S) + 3 < nstages ? (S) + 3 : nstages - 1;                                                 \
-    AMX_LOAD_SCALES((BUF) ^ 1, (S) + 1);                                                                          \
+    if constexpr ((Q) == 0) AMX_LOAD_SCALES((SET) ^ 1, ((S) >> 1) + 1);                                           \
     _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                            \
       _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                                            \
         const int t = ks * FM + i;                                                                                \
         {                                                                                                         \
           const int t2 = t + 2, ks2 = t2 / FM, i2 = t2 % FM;                                                      \
           const uint8_t* src_ = ks2 < 2 ? (CUR) : (NXT);                                                          \
-          aR[t2 & 3] = *reinterpret_cast<const uint4*>(src_ + offA + (i2 * 2 + (ks2 & 1)) * kFragBytes);         \
+          aR[t2 & 3] = *reinterpret_cast<const uint4*>(src_ + baseA + i2 * 2 * kFragBytes +                       \
+                                                       ((ks2 & 1) ? offk1 : offk0));                              \
         }                                                                                                         \
         _Pragma("unroll") for (int jj = 2 * i; jj < 2 * i + 2; ++jj) {                                            \
           if (jj < FN) {                                                                                          \
             const uint8_t* src_ = ks == 0 ? (CUR) : (NXT);                                                        \
-            bR[(ks + 1) & 1][jj] =                                                                                \
-                *reinterpret_cast<const uint4*>(src_ + offB + (jj * 2 + ((ks + 1) & 1)) * kFragBytes);           \
+            bR[(ks + 1) & 1][jj] = *reinterpret_cast<const uint4*>(src_ + baseB + jj * 2 * kFragBytes +           \
+                                                                   (((ks + 1) & 1) ? offk1 : offk0));             \
           }                                                                                                       \
         }                                                                                                         \
         _Pragma("unroll") for (int l = t; l < kLoads; l += 2 * FM) AMX_ISSUE_LOAD(l, fetch_, FETCH);              \
-        if (ks == 0) AMX_MMA(BUF, 0, i) else AMX_MMA(BUF, 1, i);                                                  \
+        if (ks == 0) AMX_MMA(SET, Q, 0, i) else AMX_MMA(SET, Q, 1, i);                                            \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
       }                                                                                                           \
     }                                                                                                             \
-    /* younger than the stage S + 2 loads: this stage's scale loads and its stage S + 3 loads */                 \
-    AMX_WAIT_VMCNT(kLoads + kScaleLoads);                                                                         \
+    /* younger than the stage S + 2 loads: this stage's scale loads (even stages) and its stage S + 3 loads */   \
+    AMX_WAIT_VMCNT(kLoads + ((Q) == 0 ? kScaleLoads : 0));                                                        \
     AMX_BARRIER();                                                                                                \
   }
 
   int s = 0;
   for (; s + 4 <= nstages; s += 4) {
-    AMX_STAGE(s, 0, lds0, lds1, lds3);
-    AMX_STAGE(s + 1, 1, lds1, lds2, lds0);
-    AMX_STAGE(s + 2, 0, lds2, lds3, lds1);
-    AMX_STAGE(s + 3, 1, lds3, lds0, lds2);
+    AMX_STAGE(s, 0, 0, lds0, lds1, lds3);
+    AMX_STAGE(s + 1, 0, 1, lds1, lds2, lds0);
+    AMX_STAGE(s + 2, 1, 0, lds2, lds3, lds1);
+    AMX_STAGE(s + 3, 1, 1, lds3, lds0, lds2);
   }
   // up to 3 remaining stages (K / 128 need not be a multiple of 4)
-  if (s < nstages) AMX_STAGE(s, 0, lds0, lds1, lds3);
-  if (s + 1 < nstages) AMX_STAGE(s + 1, 1, lds1, lds2, lds0);
-  if (s + 2 < nstages) AMX_STAGE(s + 2, 0, lds2, lds3, lds1);
+  if (s < nstages) AMX_STAGE(s, 0, 0, lds0, lds1, lds3);
+  if (s + 1 < nstages) AMX_STAGE(s + 1, 0, 1, lds1, lds2, lds0);
+  if (s + 2 < nstages) AMX_STAGE(s + 2, 1, 0, lds2, lds3, lds1);
   AMX_WAIT_VMCNT(0);  // nothing may still be writing this workgroup's LDS when it retires
 #undef AMX_STAGE
 #undef AMX_MMA
