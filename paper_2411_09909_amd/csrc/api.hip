@@ -2,6 +2,8 @@
 // method happens here; every step runs in the kernels of cast.hip / gemm_*.hip.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include "../../include/amxfp4.h"
 #include "kernels.h"
@@ -86,6 +88,18 @@ bool uses_fp4_mfma(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
   return (f.scale == AMX_SCALE_E8M0_FLOOR || f.scale == AMX_SCALE_E8M0_ROUND) && amx::fp4_path_supported(M, N, K);
 }
 
+// FP8-E5M2 scales have two kernels. The default expands both operands to BF16 panels in the workspace and runs the
+// BF16 MFMA kernel over them. AMXFP4_GEMM_PATH=fused (environment, read once) selects the kernel that dequantizes
+// inside the main loop into FP16 MFMA operands instead (no workspace; K must be a whole number of its 128-wide
+// stages). The fused kernel is bound by LDS bandwidth and measures slower on the large linears, so it is opt-in.
+bool uses_fused_e5m2(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
+  static const bool want_fused = [] {
+    const char* v = getenv("AMXFP4_GEMM_PATH");
+    return v && strcmp(v, "fused") == 0;
+  }();
+  return f.scale == AMX_SCALE_FP8_E5M2 && want_fused && amx::e5m2_fused_supported(M, N, K);
+}
+
 int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
               const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch, void* workspace,
               size_t workspace_bytes, void* stream) {
@@ -108,6 +122,11 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
   if (uses_fp4_mfma(f, M, N, K)) {
     hipError_t e = amx::launch_gemm_fp4_path(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc,
                                              batch, reinterpret_cast<hipStream_t>(stream), timer);
+    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
+  }
+  if (uses_fused_e5m2(f, M, N, K)) {
+    hipError_t e = amx::launch_gemm_e5m2_fused(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc,
+                                               batch, reinterpret_cast<hipStream_t>(stream), timer);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
   }
   hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales,
@@ -145,7 +164,7 @@ size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
 
 size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch) {
   if (!fmt || M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
-  if (uses_fp4_mfma(*fmt, M, N, K)) return 0;
+  if (uses_fp4_mfma(*fmt, M, N, K) || uses_fused_e5m2(*fmt, M, N, K)) return 0;
   return amx::bf16_path_workspace_bytes(M, N, K, batch);
 }
 

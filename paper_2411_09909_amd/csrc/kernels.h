@@ -41,4 +41,10 @@ hipError_t launch_gemm_fp4_path(bool asym, int64_t M, int64_t N, int64_t K, cons
                                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
                                 int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer);
 
+// gemm_e5m2.hip: FP8-E5M2 scales, dequantization fused into the FP16-MFMA kernel (no workspace)
+bool e5m2_fused_supported(int64_t M, int64_t N, int64_t K);
+hipError_t launch_gemm_e5m2_fused(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                                  const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
+                                  int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer);
+
 }  // namespace amx
