@@ -27,16 +27,20 @@ size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch)
 }
 
 // ------------------------------------------------------------------------------------------------ expand ----------
-// grid: (Kp / 64, Rp / 128, batch); block 256 = 4 waves; wave w expands row block rb = blockIdx.y * 4 + w for the two
-// groups of a 64-wide K slice: lane = 32 * group_in_slice + row_in_block.
+// grid: (ceil(Kp / 256), Rp / 32, batch); block 256 = 4 waves. A workgroup expands one 32-row block over a K span of
+// 256, i.e. whole 128-byte lines of every code row (neighbouring workgroups run on different XCDs with separate L2s,
+// so a line split between two of them would be fetched from HBM twice); wave w takes the 64-wide slice w of the span:
+// lane = 32 * group_in_slice + row_in_block. The 16 fragments a workgroup writes are contiguous in the panel.
 template <int SCALE_KIND, bool ASYM>
 __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__ codes,
                                                      const uint8_t* __restrict__ scales, int64_t R, int64_t K,
                                                      int64_t Rp, int64_t Kp, uint16_t* __restrict__ panel) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t rb = (int64_t)blockIdx.y * 4 + wave;
+  const int64_t rb = blockIdx.y;
+  const int64_t slice = (int64_t)blockIdx.x * 4 + wave;  // 64-wide K slice
+  if (slice * 64 >= Kp) return;
   const int64_t r = rb * 32 + (lane & 31);
-  const int64_t g = (int64_t)blockIdx.x * 2 + (lane >> 5);
+  const int64_t g = slice * 2 + (lane >> 5);
   const int64_t G = K >> 5;
   const int64_t b = blockIdx.z;
   uint32_t w[4] = {0, 0, 0, 0};
@@ -54,7 +58,7 @@ __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__
   }
   s_pos *= 0.5f;
   s_neg *= -0.5f;
-  uint16_t* dst = panel + ((b * (Rp >> 5) + rb) * (Kp >> 4) + (int64_t)blockIdx.x * 4 + (lane >> 5) * 2) * 512;
+  uint16_t* dst = panel + ((b * (Rp >> 5) + rb) * (Kp >> 4) + slice * 4 + (lane >> 5) * 2) * 512;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {  // t-th run of 8 elements of the group: k block (t / 2), half (t % 2)
     uint32_t o[4];
@@ -223,7 +227,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t*
 template <int SK, bool ASYM>
 static hipError_t launch_expand(const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K, int64_t Rp,
                                 int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s) {
-  hipLaunchKernelGGL((expand_kernel<SK, ASYM>), dim3((unsigned)(Kp / 64), (unsigned)(Rp / 128), (unsigned)batch),
+  hipLaunchKernelGGL((expand_kernel<SK, ASYM>), dim3((unsigned)((Kp + 255) / 256), (unsigned)(Rp / 32), (unsigned)batch),
                      dim3(256), 0, s, codes, scales, R, K, Rp, Kp, panel);
   return hipGetLastError();
 }
