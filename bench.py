@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--workload", default=WORKLOAD)
     ap.add_argument("--format", default="amxfp4_e5m2", choices=sorted(FORMATS),
                     help="operand format of the timed step (default: the paper's AMXFP4)")
+    ap.add_argument("--e5m2-kernel", default="panel", choices=["panel", "hybrid", "fused"],
+                    help="which of the library's kernels for FP8-E5M2 scales runs the timed GEMM (default: panel)")
     ap.add_argument("--variants", action="store_true",
                     help="also time the other formats (MXFP4 baselines, power-of-two scales) and list them")
     ap.add_argument("--calib-copy", action="store_true",
@@ -116,9 +118,13 @@ def main():
     C = torch.empty((M, N), dtype=torch.float32, device=dev)
     flops = 2.0 * M * N * K
 
-    def run_format(name, steps, warmup):
-        """Times `steps` steps (cast X + GEMM against pre-cast W) in the given format; returns a dict of timings."""
+    def run_format(name, steps, warmup, e5m2_kernel="panel"):
+        """Times `steps` steps (cast X + GEMM against pre-cast W) in the given format; returns a dict of timings.
+        e5m2_kernel: which of the library's three kernels for FP8-E5M2 scales multiplies (ignored by other formats)."""
         kind, asym, mfma, peak = FORMATS[name]
+        if kind == 2 and e5m2_kernel != "panel":
+            mfma = "f16"
+        binding.select_e5m2_kernel(e5m2_kernel)
         fmt = binding.make_format(kind, asym)
         nsc = (M, K // 32, 2) if asym else (M, K // 32)
         xc = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
@@ -155,24 +161,28 @@ def main():
             binding.quantize(fmt, xd, codes=xc, scales=xs)
         torch.cuda.synchronize()
         t_cast_x = (time.perf_counter() - t0) / steps
+        binding.select_e5m2_kernel("panel")
         return {"t_step": t_total / steps, "kern_ms": kern_ms, "t_cast_x": t_cast_x, "t_cast_w": t_cast_w,
-                "mfma": mfma, "peak": peak, "asym": asym}
+                "mfma": mfma, "peak": peak, "asym": asym, "workspace_bytes": need}
 
-    r = run_format(args.format, args.steps, args.warmup)
+    r = run_format(args.format, args.steps, args.warmup, args.e5m2_kernel)
     ms_per_step = r["t_step"] * 1e3
     value = flops / r["t_step"] / 1e12
     achieved = flops / (r["kern_ms"] * 1e-3) / 1e12
     cast_bytes = M * K * 2 + M * K // 2 + M * (K // 32) * (2 if r["asym"] else 1)
+    kernel_name = "gemm_fp4_kernel" if r["mfma"] == "fp4" else {"panel": "gemm_bf16_kernel", "hybrid":
+                  "gemm_e5m2_hybrid_kernel", "fused": "gemm_e5m2_kernel"}[args.e5m2_kernel]
     out = {
         "metric": "AMXFP4 cast+GEMM TFLOPS at 4096x8192x28672", "value": round(value, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": r["mfma"], "data": "synthetic",
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "format": args.format, "group_size": 32,
+                   "e5m2_kernel": args.e5m2_kernel if FORMATS[args.format][0] == 2 else None,
                    "step": "amxfp4_quantize(X) + amxfp4_gemm(Xq, Wq), W pre-cast"},
-        "roofline": {"bound": "mfma", "kernel": "gemm_%s_kernel" % r["mfma"], "achieved": round(achieved, 2),
+        "roofline": {"bound": "mfma", "kernel": kernel_name, "achieved": round(achieved, 2),
                      "peak": r["peak"], "unit": "TFLOP/s", "frac": round(achieved / r["peak"], 4),
                      "traffic": MEASURED_TRAFFIC_BYTES if args.format == "amxfp4_e5m2" and args.workload == WORKLOAD
-                     else None, "kernel_ms": round(r["kern_ms"], 4)},
+                     and args.e5m2_kernel == "panel" else None, "kernel_ms": round(r["kern_ms"], 4)},
         "frac_of_fp4_mfma_peak": round(value / PEAK_FP4_TFLOPS, 4),
         "breakdown_ms": {"cast_x": round(r["t_cast_x"] * 1e3, 4),
                          "gemm_call": round(ms_per_step - r["t_cast_x"] * 1e3, 4),
@@ -181,12 +191,15 @@ def main():
     }
     if args.variants:
         out["variants"] = {}
-        for name in sorted(FORMATS):
-            if name == args.format:
+        cases = [(name, "panel") for name in sorted(FORMATS)]
+        cases += [(name, k) for name in ("amxfp4_e5m2", "mxfp4_e5m2") for k in ("hybrid", "fused")]
+        for name, kern in cases:
+            if name == args.format and kern == args.e5m2_kernel:
                 continue
-            v = run_format(name, max(3, args.steps // 2), 2)
-            out["variants"][name] = {"value": round(flops / v["t_step"] / 1e12, 2), "unit": "TFLOP/s",
+            v = run_format(name, max(3, args.steps // 2), 2, kern)
+            out["variants"][name if kern == "panel" else "%s[%s]" % (name, kern)] = {"value": round(flops / v["t_step"] / 1e12, 2), "unit": "TFLOP/s",
                                      "ms_per_step": round(v["t_step"] * 1e3, 4), "mfma": v["mfma"],
+                                     "workspace_MB": round(v["workspace_bytes"] / 1e6, 1),
                                      "gemm_kernel_ms": round(v["kern_ms"], 4),
                                      "kernel_frac_of_mfma_peak": round(flops / (v["kern_ms"] * 1e-3) / 1e12 /
                                                                        v["peak"], 4)}

@@ -138,6 +138,18 @@ int mxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const u
  */
 int amxfp4_profile_next_gemm(void* start_event, void* stop_event);
 
+/*
+ * Tuning aid (not part of the method): the GEMM for FP8-E5M2 scales (Sec. 4.2) exists in three kernels that compute
+ * the same product and differ only in where the operands are dequantized:
+ *   0  both operands expanded to BF16 panels in the workspace, BF16 MFMA over them (default; any K);
+ *   1  A expanded to an FP16 panel, B dequantized inside the FP16 MFMA kernel (K a multiple of 128);
+ *   2  both operands dequantized inside the kernel, no workspace (K a multiple of 128).
+ * A shape a kernel does not take falls back to 0. The choice is process-wide, affects amxfp4_gemm_workspace_bytes
+ * as well (query after selecting) and starts from the environment variable AMXFP4_GEMM_PATH = panel | hybrid | fused.
+ * Returns AMX_OK, or AMX_ERR_INVALID_ARG for another value.
+ */
+int amxfp4_select_e5m2_kernel(int32_t which);
+
 #ifdef __cplusplus
 }
 #endif

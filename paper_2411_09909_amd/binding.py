@@ -49,6 +49,8 @@ def load():
         q.restype = d.restype = g.restype = ctypes.c_int
     L.amxfp4_profile_next_gemm.argtypes = [vp, vp]
     L.amxfp4_profile_next_gemm.restype = ctypes.c_int
+    L.amxfp4_select_e5m2_kernel.argtypes = [ctypes.c_int32]
+    L.amxfp4_select_e5m2_kernel.restype = ctypes.c_int
     _lib = L
     return L
 
@@ -87,6 +89,15 @@ def gemm_workspace_bytes(fmt, M, N, K, batch=1):
 def profile_next_gemm(start_event, stop_event):
     """Arms raw hipEvent_t handles (ints) around the matrix-multiply kernel of the next gemm() call."""
     _check(load().amxfp4_profile_next_gemm(start_event, stop_event))
+
+
+E5M2_KERNELS = {"panel": 0, "hybrid": 1, "fused": 2}
+
+
+def select_e5m2_kernel(which):
+    """Chooses among the three GEMM kernels for FP8-E5M2 scales ("panel" | "hybrid" | "fused", or 0 | 1 | 2);
+    process-wide, also changes gemm_workspace_bytes."""
+    _check(load().amxfp4_select_e5m2_kernel(E5M2_KERNELS.get(which, which)))
 
 
 def _fn(fmt, name, baseline):

@@ -5,6 +5,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "../../include/amxfp4.h"
 #include "kernels.h"
 
@@ -88,16 +90,24 @@ bool uses_fp4_mfma(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
   return (f.scale == AMX_SCALE_E8M0_FLOOR || f.scale == AMX_SCALE_E8M0_ROUND) && amx::fp4_path_supported(M, N, K);
 }
 
-// FP8-E5M2 scales have two kernels. The default expands both operands to BF16 panels in the workspace and runs the
-// BF16 MFMA kernel over them. AMXFP4_GEMM_PATH=fused (environment, read once) selects the kernel that dequantizes
-// inside the main loop into FP16 MFMA operands instead (no workspace; K must be a whole number of its 128-wide
-// stages). The fused kernel is bound by LDS bandwidth and measures slower on the large linears, so it is opt-in.
-bool uses_fused_e5m2(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  static const bool want_fused = [] {
+// FP8-E5M2 scales have three kernels (amxfp4_select_e5m2_kernel in the header); shapes one does not take use the
+// panel kernel.
+enum E5m2Path : int { kPathPanel = 0, kPathHybrid = 1, kPathFused = 2 };
+std::atomic<int>& e5m2_choice() {
+  static std::atomic<int> choice([] {
     const char* v = getenv("AMXFP4_GEMM_PATH");
-    return v && strcmp(v, "fused") == 0;
-  }();
-  return f.scale == AMX_SCALE_FP8_E5M2 && want_fused && amx::e5m2_fused_supported(M, N, K);
+    if (v && strcmp(v, "fused") == 0) return (int)kPathFused;
+    if (v && strcmp(v, "hybrid") == 0) return (int)kPathHybrid;
+    return (int)kPathPanel;
+  }());
+  return choice;
+}
+E5m2Path e5m2_path(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
+  if (f.scale != AMX_SCALE_FP8_E5M2) return kPathPanel;
+  const int want = e5m2_choice().load(std::memory_order_relaxed);
+  if (want == kPathFused && amx::e5m2_fused_supported(M, N, K)) return kPathFused;
+  if (want == kPathHybrid && amx::e5m2_hybrid_supported(M, N, K)) return kPathHybrid;
+  return kPathPanel;
 }
 
 int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
@@ -124,9 +134,15 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
                                              batch, reinterpret_cast<hipStream_t>(stream), timer);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
   }
-  if (uses_fused_e5m2(f, M, N, K)) {
+  const E5m2Path path = e5m2_path(f, M, N, K);
+  if (path == kPathFused) {
     hipError_t e = amx::launch_gemm_e5m2_fused(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc,
                                                batch, reinterpret_cast<hipStream_t>(stream), timer);
+    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
+  }
+  if (path == kPathHybrid) {
+    hipError_t e = amx::launch_gemm_e5m2_hybrid(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C,
+                                                ldc, batch, workspace, reinterpret_cast<hipStream_t>(stream), timer);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
   }
   hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales,
@@ -146,6 +162,12 @@ extern "C" {
 
 const char* amxfp4_last_error(void) { return g_err; }
 
+int amxfp4_select_e5m2_kernel(int32_t which) {
+  if (which < kPathPanel || which > kPathFused) return fail(AMX_ERR_INVALID_ARG, "no such kernel: %d", (int)which);
+  e5m2_choice().store(which, std::memory_order_relaxed);
+  return AMX_OK;
+}
+
 int amxfp4_profile_next_gemm(void* start_event, void* stop_event) {
   g_timer.start = reinterpret_cast<hipEvent_t>(start_event);
   g_timer.stop = reinterpret_cast<hipEvent_t>(stop_event);
@@ -164,7 +186,10 @@ size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
 
 size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch) {
   if (!fmt || M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
-  if (uses_fp4_mfma(*fmt, M, N, K) || uses_fused_e5m2(*fmt, M, N, K)) return 0;
+  if (uses_fp4_mfma(*fmt, M, N, K)) return 0;
+  const E5m2Path path = e5m2_path(*fmt, M, N, K);
+  if (path == kPathFused) return 0;
+  if (path == kPathHybrid) return amx::e5m2_hybrid_workspace_bytes(M, K, batch);
   return amx::bf16_path_workspace_bytes(M, N, K, batch);
 }
 

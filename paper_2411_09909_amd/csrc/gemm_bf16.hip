@@ -31,7 +31,9 @@ size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch)
 // 256, i.e. whole 128-byte lines of every code row (neighbouring workgroups run on different XCDs with separate L2s,
 // so a line split between two of them would be fetched from HBM twice); wave w takes the 64-wide slice w of the span:
 // lane = 32 * group_in_slice + row_in_block. The 16 fragments a workgroup writes are contiguous in the panel.
-template <int SCALE_KIND, bool ASYM>
+// F16: the panel holds FP16 values biased by 2^-3 instead of BF16 (FP8-E5M2 scales only: every such value lies in
+// [2^-20, 43008] and has at most 5 significant bits, so it is an FP16 number, subnormals included).
+template <int SCALE_KIND, bool ASYM, bool F16>
 __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__ codes,
                                                      const uint8_t* __restrict__ scales, int64_t R, int64_t K,
                                                      int64_t Rp, int64_t Kp, uint16_t* __restrict__ panel) {
@@ -56,8 +58,8 @@ __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__
       s_pos = s_neg = scale_value<SCALE_KIND>(scales[(b * R + r) * G + g]);
     }
   }
-  s_pos *= 0.5f;
-  s_neg *= -0.5f;
+  s_pos *= F16 ? 0.0625f : 0.5f;
+  s_neg *= F16 ? -0.0625f : -0.5f;
   uint16_t* dst = panel + ((b * (Rp >> 5) + rb) * (Kp >> 4) + slice * 4 + (lane >> 5) * 2) * 512;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {  // t-th run of 8 elements of the group: k block (t / 2), half (t % 2)
@@ -67,7 +69,10 @@ __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__
       const uint32_t n0 = (w[t] >> (8 * j)) & 15u, n1 = (w[t] >> (8 * j + 4)) & 15u;
       const float v0 = (float)e2m1_twice(n0 & 7u) * ((n0 & 8u) ? s_neg : s_pos);
       const float v1 = (float)e2m1_twice(n1 & 7u) * ((n1 & 8u) ? s_neg : s_pos);
-      o[j] = (f2u(v0) >> 16) | (f2u(v1) & 0xFFFF0000u);  // truncation is exact: <= 5 significant bits
+      if constexpr (F16)
+        o[j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(v0, v1));  // exact, see above
+      else
+        o[j] = (f2u(v0) >> 16) | (f2u(v1) & 0xFFFF0000u);  // truncation is exact: <= 5 significant bits
     }
     *reinterpret_cast<uint4*>(dst + (t >> 1) * 512 + ((t & 1) * 32 + (lane & 31)) * 8) =
         make_uint4(o[0], o[1], o[2], o[3]);
@@ -224,10 +229,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t*
   }
 }
 
-template <int SK, bool ASYM>
+template <int SK, bool ASYM, bool F16 = false>
 static hipError_t launch_expand(const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K, int64_t Rp,
                                 int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s) {
-  hipLaunchKernelGGL((expand_kernel<SK, ASYM>), dim3((unsigned)((Kp + 255) / 256), (unsigned)(Rp / 32), (unsigned)batch),
+  hipLaunchKernelGGL((expand_kernel<SK, ASYM, F16>), dim3((unsigned)((Kp + 255) / 256), (unsigned)(Rp / 32), (unsigned)batch),
                      dim3(256), 0, s, codes, scales, R, K, Rp, Kp, panel);
   return hipGetLastError();
 }
@@ -239,6 +244,12 @@ static hipError_t expand_dispatch(int scale_kind, bool asym, const uint8_t* code
                 : launch_expand<kScaleE5M2, false>(codes, scales, R, K, Rp, Kp, batch, panel, s);
   return asym ? launch_expand<kScaleE8M0Floor, true>(codes, scales, R, K, Rp, Kp, batch, panel, s)
               : launch_expand<kScaleE8M0Floor, false>(codes, scales, R, K, Rp, Kp, batch, panel, s);
+}
+
+hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K,
+                                  int64_t Rp, int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s) {
+  return asym ? launch_expand<kScaleE5M2, true, true>(codes, scales, R, K, Rp, Kp, batch, panel, s)
+              : launch_expand<kScaleE5M2, false, true>(codes, scales, R, K, Rp, Kp, batch, panel, s);
 }
 
 template <int WM, int WN, int FM, int FN>

@@ -35,6 +35,10 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t M, int64_t N
                                  const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
                                  int64_t ldc, int64_t batch, void* workspace, hipStream_t s, const KernelTimer& timer);
 
+// FP16 fragment-major panel (values biased by 2^-3) of an operand with FP8-E5M2 scales; layout as the BF16 panels
+hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K,
+                                  int64_t Rp, int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s);
+
 // gemm_fp4.hip: power-of-two scales on the block-scaled FP4 MFMA (no workspace)
 bool fp4_path_supported(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm_fp4_path(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
@@ -46,5 +50,13 @@ bool e5m2_fused_supported(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm_e5m2_fused(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                                   const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
                                   int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer);
+
+// FP8-E5M2 scales, A from an FP16 panel in the workspace, B dequantized inside the kernel (workspace: the A panel only)
+bool e5m2_hybrid_supported(int64_t M, int64_t N, int64_t K);
+size_t e5m2_hybrid_workspace_bytes(int64_t M, int64_t K, int64_t batch);
+hipError_t launch_gemm_e5m2_hybrid(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                                   const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
+                                   int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
+                                   const KernelTimer& timer);
 
 }  // namespace amx

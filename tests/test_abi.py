@@ -50,6 +50,21 @@ def test_size_queries(lib):
     assert binding.gemm_workspace_bytes(g, 64, 1024, 96) == (256 + 1024) * 128 * 2
 
 
+def test_e5m2_kernel_selection_changes_the_workspace(lib):
+    f = binding.make_format(binding.FP8_E5M2, True)
+    try:
+        binding.select_e5m2_kernel("hybrid")   # only the A panel (FP16) lives in the workspace
+        assert binding.gemm_workspace_bytes(f, 64, 1024, 1024) == 256 * 1024 * 2
+        assert binding.gemm_workspace_bytes(f, 64, 1024, 96) == (256 + 1024) * 128 * 2  # K % 128 != 0: panel kernel
+        binding.select_e5m2_kernel("fused")
+        assert binding.gemm_workspace_bytes(f, 64, 1024, 1024) == 0
+        with pytest.raises(binding.AmxError):
+            binding.select_e5m2_kernel(7)
+    finally:
+        binding.select_e5m2_kernel("panel")
+    assert binding.gemm_workspace_bytes(f, 64, 1024, 1024) == (256 + 1024) * 1024 * 2
+
+
 def _q(lib, fmt, x, rows, K, rs, ks, codes, scales):
     return lib.amxfp4_quantize(ctypes.byref(fmt), x, rows, K, rs, ks, codes, scales, None)
 

@@ -102,3 +102,41 @@ def test_mxfp4_baseline_gemm():
     ac, as_, bc, bs = quantized("c1_linear_64x1024x1024", ref.FP8_E5M2, 0)
     C = G.gpu_gemm(ac, as_, bc, bs, ref.FP8_E5M2, 1, baseline=True)  # flag ignored by mxfp4_gemm
     assert G.rel_fro(C, ref.gemm(ac, as_, bc, bs, 32, ref.FP8_E5M2, 0)) <= TOL
+
+
+@pytest.fixture(params=["hybrid", "fused"])
+def alternative_e5m2_kernel(request):
+    """The two other kernels for FP8-E5M2 scales (dequantization inside the GEMM kernel); the default one is what
+    every other test in this file runs."""
+    from paper_2411_09909_amd import binding
+    binding.select_e5m2_kernel(request.param)
+    yield request.param
+    binding.select_e5m2_kernel("panel")
+
+
+@pytest.mark.parametrize("asym", [1, 0])
+@pytest.mark.parametrize("M,N,K", [(1, 1, 128), (64, 1024, 1024), (257, 255, 384), (300, 520, 1280), (31, 700, 640)])
+def test_alternative_e5m2_kernels(alternative_e5m2_kernel, M, N, K, asym):
+    """Ragged M and N, K of 1, 3, 5, 8 and 10 raw stages of 128 (odd and even counts, shorter than the pipeline)."""
+    a = synth.activations(M, K, seed=M + K, n_outlier=1, outlier_gain=60.0)
+    b = synth.weights(N, K, seed=N)
+    ac, as_ = ref.quantize(a, 32, ref.FP8_E5M2, asym)
+    bc, bs = ref.quantize(b, 32, ref.FP8_E5M2, asym)
+    C = G.gpu_gemm(ac, as_, bc, bs, ref.FP8_E5M2, asym)
+    assert G.rel_fro(C, ref.gemm(ac, as_, bc, bs, 32, ref.FP8_E5M2, asym)) <= TOL
+
+
+def test_alternative_e5m2_kernels_batched_and_llm_shape(alternative_e5m2_kernel):
+    ac, as_, bc, bs = quantized("c3_70b_up_4096x8192x28672", ref.FP8_E5M2, 1, M=300, N=520)
+    C = G.gpu_gemm(ac, as_, bc, bs, ref.FP8_E5M2, 1)
+    assert G.rel_fro(C, ref.gemm(ac, as_, bc, bs, 32, ref.FP8_E5M2, 1)) <= TOL
+    # batch of 3 independent problems (heads)
+    a = synth.activations(3 * 130, 256, seed=5, n_outlier=1, outlier_gain=20.0)
+    b = synth.weights(3 * 200, 256, seed=6)
+    ac, as_ = ref.quantize(a, 32, ref.FP8_E5M2, 1)
+    bc, bs = ref.quantize(b, 32, ref.FP8_E5M2, 1)
+    shp = lambda t, r: t.reshape((3, r) + t.shape[1:])
+    C = G.gpu_gemm(shp(ac, 130), shp(as_, 130), shp(bc, 200), shp(bs, 200), ref.FP8_E5M2, 1)
+    Cr = ref.gemm(shp(ac, 130), shp(as_, 130), shp(bc, 200), shp(bs, 200), 32, ref.FP8_E5M2, 1)
+    assert C.shape == (3, 130, 200)
+    assert G.rel_fro(C, Cr) <= TOL
