@@ -19,9 +19,13 @@
 namespace amx {
 
 typedef int i32x8 __attribute__((ext_vector_type(8)));
+// 16 bytes of codes as one native vector: a fragment read is then a single load in the compiler's eyes and keeps the
+// information which LDS array it reads (a struct of four words is read as four loads, three of which lose it, and the
+// compiler then waits for every direct-to-LDS load in flight before each read)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-__device__ __forceinline__ i32x8 as_operand(uint4 v) {
+__device__ __forceinline__ i32x8 as_operand(u32x4 v) {
   i32x8 r = {(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};  // FP4 uses the first 4 of the 8 operand registers
   return r;
 }
@@ -33,10 +37,18 @@ __device__ __forceinline__ uint32_t sign_class(uint32_t w) {
   return NEG ? (w & neg) : (w & ~neg);
 }
 template <bool NEG>
-__device__ __forceinline__ uint4 sign_class4(uint4 v) {
-  return make_uint4(sign_class<NEG>(v.x), sign_class<NEG>(v.y), sign_class<NEG>(v.z), sign_class<NEG>(v.w));
+__device__ __forceinline__ u32x4 sign_class4(u32x4 v) {
+  u32x4 r = {sign_class<NEG>(v.x), sign_class<NEG>(v.y), sign_class<NEG>(v.z), sign_class<NEG>(v.w)};
+  return r;
 }
 
+// One stage = a K slice of 256: 128 bytes = one whole cache line of every code row (a compute unit's vector cache
+// tracks a limited number of line requests, so fetching half lines would halve what it can pull from the L2).
+// LDS: two stage buffers of 64 KiB (A rows then B rows, 128 bytes per row). A stage is 4 k-steps x FM steps of FN
+// MFMAs; fragments are read two steps (A) / one k-step (B) ahead. The next stage is fetched into the other buffer
+// during the first half of a stage. The single barrier of a stage comes after step 13 of 16: by then every wave has
+// its last fragments of the current buffer and the next stage has landed; the two steps after it read ahead into the
+// next buffer.
 template <int WM, int WN, int FM, int FN, bool ASYM>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* __restrict__ Ac,
                                                                 const uint8_t* __restrict__ As,
@@ -45,10 +57,30 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
                                                                 int64_t M, int64_t N, int64_t K, int64_t ldc,
                                                                 int tiles_m, int tiles_n, int super_m) {
   using Cfg = TileCfg<WM, WN, FM, FN>;
-  __shared__ __attribute__((aligned(1024))) uint8_t lds0[Cfg::kStageBytes];
-  __shared__ __attribute__((aligned(1024))) uint8_t lds1[Cfg::kStageBytes];
-  __shared__ __attribute__((aligned(1024))) uint8_t lds2[Cfg::kStageBytes];
-  __shared__ __attribute__((aligned(1024))) uint8_t lds3[Cfg::kStageBytes];
+  constexpr int kWaves = Cfg::kWaves, kTileM = Cfg::kTileM, kTileN = Cfg::kTileN;
+  constexpr int kUnitsA = kTileM / 8, kUnitsB = kTileN / 8;  // direct-to-LDS loads (8 rows x 128 bytes) per stage
+  constexpr int kLoads = (kUnitsA + kUnitsB) / kWaves;       // per wave and stage
+  constexpr int kBytesA = kTileM * 128, kBytesB = kTileN * 128;
+  static_assert(kUnitsA % kWaves == 0 && kUnitsB % kWaves == 0 && kWaves % 2 == 0 && FM == 4 && FN == 4 &&
+                    kLoads == 16,
+                "the issue schedule below is written for 2 x 2 waves of 4 x 4 MFMA tiles");
+  // separate arrays per buffer and operand: the compiler can then tell that a direct-to-LDS load into one cannot
+  // touch what a fragment read of another returns, and does not serialise them
+  __shared__ __attribute__((aligned(1024))) uint8_t ldsA0[kBytesA];
+  __shared__ __attribute__((aligned(1024))) uint8_t ldsB0[kBytesB];
+  __shared__ __attribute__((aligned(1024))) uint8_t ldsA1[kBytesA];
+  __shared__ __attribute__((aligned(1024))) uint8_t ldsB1[kBytesB];
+
+#define lds0_A ldsA0
+#define lds0_B ldsB0
+#define lds1_A ldsA1
+#define lds1_B ldsB1
+  typedef __attribute__((address_space(3))) const uint8_t* lds_cptr_t;
+#define rd0_A ((lds_cptr_t)ldsA0)
+#define rd0_B ((lds_cptr_t)ldsB0)
+#define rd1_A ((lds_cptr_t)ldsA1)
+#define rd1_B ((lds_cptr_t)ldsB1)
+#define AMX_LDS_READ(P, OFF) (*reinterpret_cast<const __attribute__((address_space(3))) u32x4*>((P) + (OFF)))
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -57,8 +89,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   int tm, tn;
   if (!tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, super_m, tm, tn)) return;  // uniform, before any barrier
 
-  constexpr int kWaves = Cfg::kWaves, kFragsA = Cfg::kFragsA, kLoads = Cfg::kLoads, kTileM = Cfg::kTileM,
-                kTileN = Cfg::kTileN;
   constexpr int kScaleBytes = ASYM ? 2 : 1;                    // per group
   const int row_bytes = (int)(K >> 1);                         // codes per row
   const int srow_bytes = (int)(K >> 5) * kScaleBytes;          // scale bytes per row
@@ -76,18 +106,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   const __amdgpu_buffer_rsrc_t Bsr = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t*>(Bs + (b * N + (int64_t)tn * kTileN) * srow_bytes), 0, rows_b * srow_bytes, 0x00020000);
 
-  // Staging geometry. One direct-to-LDS load moves 16 rows x 64 bytes (4 lanes per row: the stage's 128 codes of that
-  // row), so every lane quad reads one aligned 64-byte segment of its row. Its LDS image is [16 rows][4 chunks of
-  // 16 bytes]; two loads make a row block of 32 rows x 64 bytes = 2 KiB. The chunk a lane fetches is permuted by the
-  // row (chunk = slot ^ ((row >> 2) & 3)) so that the fragment reads below (32 consecutive rows, one chunk each) fall
-  // on 16 distinct 16-byte bank groups per 16 lanes.
+  // Staging geometry. One direct-to-LDS load moves 8 rows x 128 bytes (8 lanes per row). Its LDS image is [8 rows]
+  // [8 chunks of 16 bytes]; the chunk a lane fetches is permuted by the row, chunk = slot ^ ((row >> 1) & 7), so that
+  // the fragment reads below (32 consecutive rows, one chunk each) fall on 16 distinct 16-byte bank groups per 16
+  // lanes. Load unit u = wave + kWaves * L covers tile rows 8u .. 8u+7, so (row >> 1) & 7 = 4 * (u & 1) + row_in_unit
+  // / 2, and u & 1 = wave & 1 for every unit of a wave.
   const int kb = lane >> 5;  // K block (of 32 codes) of this lane inside a 64-wide k-step
-  const int gather_off = (lane >> 2) * row_bytes + (((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+  const int gather_off = (lane >> 3) * row_bytes + (((lane & 7) ^ (4 * (wave & 1) + ((lane >> 4) & 3))) << 4);
   const int sgather_off = (lane & 31) * srow_bytes;
-  // fragment read offsets inside a row block for k-step 0 and 1: row r = lane % 32 holds chunk c at slot c ^ ((r>>2)&3)
+  // fragment read offset inside a row block (32 rows x 128 bytes) for k-step ks: chunk 2 ks + kb of row lane % 32
   const int rr = lane & 31;
-  const int offk0 = rr * 64 + (((0 + kb) ^ ((rr >> 2) & 3)) << 4);
-  const int offk1 = rr * 64 + (((2 + kb) ^ ((rr >> 2) & 3)) << 4);
+  const int frag_row = rr * 128, frag_swz = (rr >> 1) & 7;
+#define AMX_FRAG_OFF(KS) (frag_row + (((2 * (KS) + kb) ^ frag_swz) << 4))
 
   f32x16 acc[FM][FN];
 #pragma unroll
@@ -97,85 +127,72 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // Load L of this wave for stage ST: half row block f = wave + kWaves * L (row block f / 2, rows 16 * (f % 2) ..);
-  // f < kFragsA: operand A, otherwise B. Lands at DST + f KiB.
+  // Load L of this wave for stage ST: L < kUnitsA / kWaves: unit u = wave + kWaves * L of operand A, otherwise unit
+  // wave + kWaves * (L - kUnitsA / kWaves) of B. Lands at u KiB of the buffer DST##A / DST##B. Past the end of K the
+  // stage index is clamped by the caller: the data lands where nobody reads it.
 #define AMX_ISSUE_LOAD(L, ST, DST)                                                                              \
   {                                                                                                             \
-    const int f_ = wave + kWaves * (L);                                                                         \
-    if ((L) < kFragsA / kWaves)                                                                                 \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(Ar, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, gather_off,        \
-                                               f_ * 16 * row_bytes + (ST) * 64, 0, 0);                          \
-    else                                                                                                        \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(Br, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, gather_off,        \
-                                               (f_ - kFragsA) * 16 * row_bytes + (ST) * 64, 0, 0);              \
+    if ((L) < kUnitsA / kWaves) {                                                                               \
+      const int u_ = wave + kWaves * (L);                                                                       \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(Ar, (lds_ptr_t)(DST##A + u_ * 1024), 16, gather_off,             \
+                                               u_ * 8 * row_bytes + (ST) * 128, 0, 0);                          \
+    } else {                                                                                                    \
+      const int u_ = wave + kWaves * ((L) - kUnitsA / kWaves);                                                  \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(Br, (lds_ptr_t)(DST##B + u_ * 1024), 16, gather_off,             \
+                                               u_ * 8 * row_bytes + (ST) * 128, 0, 0);                          \
+    }                                                                                                           \
   }
 
-  // Scale words, per lane and row block, for a PAIR of stages (8 groups of this lane's row): symmetric = 8 bytes
-  // (one per group), asymmetric = 16 bytes ((pos, neg) per group). Two register sets alternate: pair P of stages
-  // (2P, 2P+1) lives in set P & 1 and is requested two stages ahead.
+  // Scale words of one stage (8 groups of this lane's row), per row block: symmetric = 8 bytes (one per group),
+  // asymmetric = 16 bytes ((pos, neg) per group). Two register sets alternate between stages.
   typedef uint32_t sword_t __attribute__((ext_vector_type(ASYM ? 4 : 2)));
   sword_t sa[2][FM], sb[2][FN];
-#define AMX_LOAD_SCALES(SET, PAIR)                                                                                  \
+#define AMX_LOAD_SCALES(SET, ST)                                                                                    \
   {                                                                                                                 \
     _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                                                \
       if constexpr (ASYM)                                                                                           \
         sa[SET][i] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b128(                             \
-                                                     Asr, sgather_off + (PAIR) * 16, (wm * FM + i) * 32 * srow_bytes, 0)); \
+                                                     Asr, sgather_off + (ST) * 16, (wm * FM + i) * 32 * srow_bytes, 0)); \
       else                                                                                                          \
         sa[SET][i] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b64(                              \
-                                                     Asr, sgather_off + (PAIR) * 8, (wm * FM + i) * 32 * srow_bytes, 0));  \
+                                                     Asr, sgather_off + (ST) * 8, (wm * FM + i) * 32 * srow_bytes, 0));  \
     }                                                                                                               \
     _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                                                \
       if constexpr (ASYM)                                                                                           \
         sb[SET][j] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b128(                             \
-                                                     Bsr, sgather_off + (PAIR) * 16, (wn * FN + j) * 32 * srow_bytes, 0)); \
+                                                     Bsr, sgather_off + (ST) * 16, (wn * FN + j) * 32 * srow_bytes, 0)); \
       else                                                                                                          \
         sb[SET][j] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b64(                              \
-                                                     Bsr, sgather_off + (PAIR) * 8, (wn * FN + j) * 32 * srow_bytes, 0));  \
+                                                     Bsr, sgather_off + (ST) * 8, (wn * FN + j) * 32 * srow_bytes, 0));  \
     }                                                                                                               \
   }
-  constexpr int kScaleLoads = FM + FN;  // per pair of stages
 
-  const int nstages = (int)(K >> 7);  // K is a multiple of 128 on this path
-#pragma unroll
-  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 0, lds0);
-#pragma unroll
-  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, (nstages > 1 ? 1 : 0), lds1);
-#pragma unroll
-  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, (nstages > 2 ? 2 : nstages - 1), lds2);
-  AMX_LOAD_SCALES(0, 0);
-  AMX_WAIT_VMCNT(kLoads + kScaleLoads);  // everything older than the stage-2 loads and the scale loads has landed
-  AMX_BARRIER();
-
-  uint4 aR[4], bR[2][FN];
-  const int baseA = (wm * FM) * 2 * kFragBytes;
-  const int baseB = (kFragsA + (wn * FN) * 2) * kFragBytes;
-  aR[0] = *reinterpret_cast<const uint4*>(lds0 + baseA + offk0);
-  aR[1] = *reinterpret_cast<const uint4*>(lds0 + baseA + 2 * kFragBytes + offk0);
-#pragma unroll
-  for (int j = 0; j < FN; ++j) bR[0][j] = *reinterpret_cast<const uint4*>(lds0 + baseB + j * 2 * kFragBytes + offk0);
-
-  // The MFMAs of step (KS, I) of stage Q (0 or 1) of a scale pair held in set SET. Scale byte selection:
-  // symmetric: word Q = bytes (g0 g1 g2 g3) of the stage, shifted by 8*kb; k-step KS uses byte 2*KS (opsel);
-  // asymmetric: word 2*Q + KS = bytes (p0 n0 p1 n1) of the k-step, shifted by 16*kb; pos = byte 0, neg = byte 1.
-#define AMX_MMA(SET, Q, KS, I)                                                                                       \
+  const int nfull = (int)(K >> 8);  // whole stages; K % 256 == 128 leaves half a stage for the end
+  u32x4 aR[4], bR[2][FN];
+  const int baseA = (wm * FM) * 4096;
+  const int baseB = (wn * FN) * 4096;
+  // The MFMAs of step (KS4, I) of a stage whose scale words are in set SET; k-step KS4 = 0..3 covers groups 2 KS4 and
+  // 2 KS4 + 1 of the stage. Scale byte selection:
+  // symmetric: word KS4 / 2 = bytes of 4 groups, shifted by 8*kb; the k-step uses byte OPS = 2 * (KS4 % 2) (opsel);
+  // asymmetric: word KS4 = bytes (p0 n0 p1 n1) of the k-step, shifted by 16*kb; pos = byte 0, neg = byte 1.
+#define AMX_MMA(SET, KS4, I, OPS)                                                                                       \
   {                                                                                                                  \
     if constexpr (!ASYM) {                                                                                           \
-      const int sav = (int)(sa[SET][I][Q] >> (8 * kb));                                                              \
-      const i32x8 av = as_operand(aR[((KS) * FM + (I)) & 3]);                                                        \
+      const int sav = (int)(sa[SET][I][(KS4) >> 1] >> (8 * kb));                                                     \
+      const i32x8 av = as_operand(aR[((KS4) * FM + (I)) & 3]);                                                       \
       _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                                               \
-        const int sbv = (int)(sb[SET][j][Q] >> (8 * kb));                                                            \
-        acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, as_operand(bR[(KS) & 1][j]), acc[I][j], 4,   \
-                                                                    4, 2 * (KS), sav, 2 * (KS), sbv);                \
+        const int sbv = (int)(sb[SET][j][(KS4) >> 1] >> (8 * kb));                                                   \
+        acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, as_operand(bR[(KS4) & 1][j]), acc[I][j], 4,  \
+                                                                    4, OPS, sav, OPS, sbv);                          \
       }                                                                                                              \
     } else {                                                                                                         \
-      const int sav = (int)(sa[SET][I][2 * (Q) + (KS)] >> (16 * kb));                                                \
-      const uint4 araw = aR[((KS) * FM + (I)) & 3];                                                                  \
+      const int sav = (int)(sa[SET][I][KS4] >> (16 * kb));                                                           \
+      const u32x4 araw = aR[((KS4) * FM + (I)) & 3];                                                                 \
       const i32x8 ap = as_operand(sign_class4<false>(araw)), an = as_operand(sign_class4<true>(araw));              \
       _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                                               \
-        const int sbv = (int)(sb[SET][j][2 * (Q) + (KS)] >> (16 * kb));                                              \
-        const i32x8 bp = as_operand(sign_class4<false>(bR[(KS) & 1][j])),                                            \
-                    bn = as_operand(sign_class4<true>(bR[(KS) & 1][j]));                                             \
+        const int sbv = (int)(sb[SET][j][KS4] >> (16 * kb));                                                         \
+        const i32x8 bp = as_operand(sign_class4<false>(bR[(KS4) & 1][j])),                                           \
+                    bn = as_operand(sign_class4<true>(bR[(KS4) & 1][j]));                                            \
         acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ap, bp, acc[I][j], 4, 4, 0, sav, 0, sbv);        \
         acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ap, bn, acc[I][j], 4, 4, 0, sav, 1, sbv);        \
         acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(an, bp, acc[I][j], 4, 4, 1, sav, 0, sbv);        \
@@ -184,56 +201,101 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
     }                                                                                                                \
   }
 
-  // Stage S = stage Q (0 / 1) of the scale pair in set SET; ring discipline as in gemm_bf16.hip. An even stage first
-  // requests the scale words of the next pair (stages S + 2, S + 3) into the other set, whose previous contents
-  // (stages S - 2, S - 1) are dead. Then each step reads fragments ahead, issues its share of the stage S + 3 loads and
-  // multiplies.
-#define AMX_STAGE(S, SET, Q, CUR, NXT, FETCH)                                                                     \
+  // Stage S (scale words in set SET; NXT: the arrays the next stage is loaded into; RC / RN: read pointers of this
+  // stage's and the next stage's arrays). Step t = 4 ks + i:
+  //   - reads the A fragment of step t + 2 and, at i = 0, 1, two B fragments of k-step ks + 1 (for the last k-step:
+  //     those of the next stage's first k-step, at i = 2, 3, i.e. after the barrier);
+  //   - steps 0..7 issue the 16 loads of stage S + 1 into NXT, two per step; step 0 also requests its scale words;
+  //   - after the MFMAs of step 13: wait for all loads and fragment reads of this wave, barrier.
+#define AMX_STAGE(S, SET, NXT, RC, RN)                                                                             \
   {                                                                                                               \
-    const int fetch_ = (S) + 3 < nstages ? (S) + 3 : nstages - 1;                                                 \
-    if constexpr ((Q) == 0) AMX_LOAD_SCALES((SET) ^ 1, ((S) >> 1) + 1);                                           \
-    _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                            \
+    const int next_ = (S) + 1 < nfull ? (S) + 1 : nfull - 1;                                                      \
+    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                                            \
       _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                                            \
         const int t = ks * FM + i;                                                                                \
+        constexpr int kLast = 4 * FM - 3; /* the step followed by the barrier */                                  \
         {                                                                                                         \
           const int t2 = t + 2, ks2 = t2 / FM, i2 = t2 % FM;                                                      \
-          const uint8_t* src_ = ks2 < 2 ? (CUR) : (NXT);                                                          \
-          aR[t2 & 3] = *reinterpret_cast<const uint4*>(src_ + baseA + i2 * 2 * kFragBytes +                       \
-                                                       ((ks2 & 1) ? offk1 : offk0));                              \
+          if (ks2 < 4)                                                                                            \
+            aR[t2 & 3] = AMX_LDS_READ(RC##A, baseA + i2 * 4096 + AMX_FRAG_OFF(ks2 & 3));                          \
+          else                                                                                                    \
+            aR[t2 & 3] = AMX_LDS_READ(RN##A, baseA + i2 * 4096 + AMX_FRAG_OFF(0));                                \
         }                                                                                                         \
-        _Pragma("unroll") for (int jj = 2 * i; jj < 2 * i + 2; ++jj) {                                            \
-          if (jj < FN) {                                                                                          \
-            const uint8_t* src_ = ks == 0 ? (CUR) : (NXT);                                                        \
-            bR[(ks + 1) & 1][jj] = *reinterpret_cast<const uint4*>(src_ + baseB + jj * 2 * kFragBytes +           \
-                                                                   (((ks + 1) & 1) ? offk1 : offk0));             \
-          }                                                                                                       \
+        if (ks < 3) {                                                                                             \
+          _Pragma("unroll") for (int jj = 2 * i; jj < 2 * i + 2; ++jj) if (jj < FN)                               \
+            bR[(ks + 1) & 1][jj] = AMX_LDS_READ(RC##B, baseB + jj * 4096 + AMX_FRAG_OFF(ks + 1));                 \
+        } else {                                                                                                  \
+          _Pragma("unroll") for (int jj = 2 * (i - 2); jj < 2 * (i - 2) + 2; ++jj) if (i >= 2 && jj < FN)         \
+            bR[0][jj] = AMX_LDS_READ(RN##B, baseB + jj * 4096 + AMX_FRAG_OFF(0));                                 \
         }                                                                                                         \
-        _Pragma("unroll") for (int l = t; l < kLoads; l += 2 * FM) AMX_ISSUE_LOAD(l, fetch_, FETCH);              \
-        if (ks == 0) AMX_MMA(SET, Q, 0, i) else AMX_MMA(SET, Q, 1, i);                                            \
+        if (t == 0) AMX_LOAD_SCALES((SET) ^ 1, next_);                                                            \
+        if (t < 8) {                                                                                              \
+          AMX_ISSUE_LOAD(2 * t, next_, NXT);                                                                      \
+          AMX_ISSUE_LOAD(2 * t + 1, next_, NXT);                                                                  \
+        }                                                                                                         \
+        /* (the scale-byte selector must be a literal: OPS = 2 * (ks % 2)) */                                     \
+        if ((ks & 1) == 0) AMX_MMA(SET, ks, i, 0) else AMX_MMA(SET, ks, i, 2);                                    \
+        if (t == kLast) {                                                                                         \
+          __builtin_amdgcn_s_waitcnt(0x0070); /* vmcnt(0) lgkmcnt(0) */                                           \
+          AMX_BARRIER();                                                                                          \
+        }                                                                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
       }                                                                                                           \
     }                                                                                                             \
-    /* younger than the stage S + 2 loads: this stage's scale loads (even stages) and its stage S + 3 loads */   \
-    AMX_WAIT_VMCNT(kLoads + ((Q) == 0 ? kScaleLoads : 0));                                                        \
-    AMX_BARRIER();                                                                                                \
   }
 
-  int s = 0;
-  for (; s + 4 <= nstages; s += 4) {
-    AMX_STAGE(s, 0, 0, lds0, lds1, lds3);
-    AMX_STAGE(s + 1, 0, 1, lds1, lds2, lds0);
-    AMX_STAGE(s + 2, 1, 0, lds2, lds3, lds1);
-    AMX_STAGE(s + 3, 1, 1, lds3, lds0, lds2);
+  if (nfull > 0) {
+    // prologue: stage 0
+#pragma unroll
+    for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 0, lds0_);
+    AMX_LOAD_SCALES(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0070);  // everything
+    AMX_BARRIER();
+    aR[0] = AMX_LDS_READ(rd0_A, baseA + AMX_FRAG_OFF(0));
+    aR[1] = AMX_LDS_READ(rd0_A, baseA + 4096 + AMX_FRAG_OFF(0));
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+      bR[0][j] = AMX_LDS_READ(rd0_B, baseB + j * 4096 + AMX_FRAG_OFF(0));
+    int s = 0;
+    for (; s + 2 <= nfull; s += 2) {
+      AMX_STAGE(s, 0, lds1_, rd0_, rd1_);
+      AMX_STAGE(s + 1, 1, lds0_, rd1_, rd0_);
+    }
+    if (s < nfull) AMX_STAGE(s, 0, lds1_, rd0_, rd1_);
+    __builtin_amdgcn_s_waitcnt(0x0070);  // this wave's last (unused) prefetches have landed, its reads are done
+    AMX_BARRIER();                       // ... and everybody else's: LDS is free
   }
-  // up to 3 remaining stages (K / 128 need not be a multiple of 4)
-  if (s < nstages) AMX_STAGE(s, 0, 0, lds0, lds1, lds3);
-  if (s + 1 < nstages) AMX_STAGE(s + 1, 0, 1, lds1, lds2, lds0);
-  if (s + 2 < nstages) AMX_STAGE(s + 2, 1, 0, lds2, lds3, lds1);
-  AMX_WAIT_VMCNT(0);  // nothing may still be writing this workgroup's LDS when it retires
+  if (K & 255) {
+    // The last 128 of K, not pipelined (once per tile): the loads fetch whole lines again, the second half of which
+    // belongs to the next row (or reads as zero past the tile's last row) and is not used.
+#pragma unroll
+    for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, nfull, lds0_);
+    AMX_LOAD_SCALES(0, nfull);
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    AMX_BARRIER();
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+        bR[ks & 1][j] = AMX_LDS_READ(rd0_B, baseB + j * 4096 + AMX_FRAG_OFF(ks));
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        aR[(ks * FM + i) & 3] = AMX_LDS_READ(rd0_A, baseA + i * 4096 + AMX_FRAG_OFF(ks));
+        if (ks == 0) AMX_MMA(0, ks, i, 0) else AMX_MMA(0, ks, i, 2);
+      }
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);  // nothing may still be writing this workgroup's LDS when it retires
 #undef AMX_STAGE
 #undef AMX_MMA
 #undef AMX_LOAD_SCALES
 #undef AMX_ISSUE_LOAD
+#undef AMX_FRAG_OFF
+#undef AMX_LDS_READ
+#undef lds0_A
+#undef lds0_B
+#undef lds1_A
+#undef lds1_B
 
   float* Cb = C + b * M * ldc;
 #pragma unroll
