@@ -12,14 +12,16 @@
 // FP16 range including subnormals (which both the packed multiply and the MFMA honour), so no product is rounded.
 // The bias of both operands is undone exactly by scaling the accumulators by 2^6 before they are stored.
 //
-// Structure. 256 threads = 4 waves compute a 256 x 256 tile (2 x 2 waves, each 4 x 4 MFMA tiles of 32x32).
+// Structure (fused kernel). 512 threads = 8 waves compute a 256 x 256 tile: wave w multiplies row half w / 4 and
+// column quarter w % 4 (4 x 2 MFMA tiles of 32x32) and expands rows of A (waves 0-3) or of B (waves 4-7); two waves
+// share a SIMD, so one wave's expansion runs under the other's MFMAs.
 //   raw ring  2 x 36 KiB: one stage = a K slice of 128: codes of the 256 A rows and 256 B rows (64 bytes per row,
 //             staged in 16-row x 64-byte direct-to-LDS loads, chunk-permuted for conflict-free reads) + scale bytes.
 //   expanded  2 x 32 KiB: one K slice of 32 as MFMA operand fragments (1 KiB = 64 lanes x 8 halves).
-// Per K slice q every wave (a) expands, per lane, one group (32 codes) of an A row and one of a B row of slice q+1 from
-// the raw stage into the other fragment buffer and (b) multiplies slice q; the two are interleaved instruction by
-// instruction (code pairs of 4-5 VALU instructions behind the 8-pass MFMAs). One barrier per slice; a raw stage is
-// refilled four slices before it is needed.
+// Per K slice q every lane expands one group (32 codes) of its row of slice q+1 from the raw stage into the other
+// fragment buffer while the wave multiplies slice q; the two are interleaved instruction by instruction. One barrier
+// per slice; a raw stage is refilled four slices before it is needed. A second kernel further down (hybrid) takes A
+// from an FP16 panel instead and expands only B.
 #include "device_formats.h"
 #include "gemm_common.h"
 
