@@ -276,11 +276,18 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t M, int64_t N
   e = expand_dispatch(scale_kind, asym, B_codes, B_scales, N, K, Np, Kp, batch, Bp, s);
   if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
-  static const int tile_cfg = getenv("AMXFP4_TILE") ? atoi(getenv("AMXFP4_TILE")) : 0;  // tuning experiments only
+  // Tile shape: 256 x 256 unless one side of the problem is much smaller than that (skinny outputs such as P.V with
+  // N = head size 128, or a handful of tokens); AMXFP4_TILE overrides the choice in tuning experiments.
+  static const int tile_env = getenv("AMXFP4_TILE") ? atoi(getenv("AMXFP4_TILE")) : -1;
+  const int tile_cfg = tile_env >= 0 ? tile_env : (M <= 64 ? 4 : (N <= 128 ? 3 : 0));
   if (tile_cfg == 1)
     e = launch_tiles<2, 4, 4, 2>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);
   else if (tile_cfg == 2)
     e = launch_tiles<4, 2, 2, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);
+  else if (tile_cfg == 3)
+    e = launch_tiles<4, 1, 2, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);  // 256 x 128
+  else if (tile_cfg == 4)
+    e = launch_tiles<1, 4, 2, 2>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);  // 64 x 256
   else
     e = launch_tiles<2, 2, 4, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, s);
   if (e != hipSuccess) return e;
