@@ -23,7 +23,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense BF16 MFMA
 PEAK_FP4_TFLOPS = 10100.0   # MI355X dense block-scaled FP4 MFMA (the metric's reference peak)
 # HBM bytes per GEMM-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see
 # profiles/gemm_bf16_c3_up_counters.md.
-MEASURED_TRAFFIC_BYTES = 3.29e9  # 2.82 GB fetched + 0.47 GB written
+MEASURED_TRAFFIC_BYTES = 3.43e9  # 2.96 GB fetched + 0.47 GB written
 
 
 # format name -> (scale kind, asymmetric, MFMA type issued by the GEMM, its dense peak in TFLOP/s)
