@@ -1,0 +1,75 @@
+/*
+ * libamxfp4 — glue operators of the decoder-layer workload.
+ *
+ * The paper quantizes every matrix multiplication of a transformer decoder layer (Sec. 5.1, evaluation setup: the
+ * linear projections and the two attention products Q.K^T and P.V) and leaves the operators between them in BF16.
+ * These entry points are those operators for a LLaMA-style layer, so that a whole layer can run through the
+ * quantized GEMM of amxfp4.h without leaving the device: they take the FP32 outputs of amxfp4_gemm and produce the
+ * BF16 operands of the next amxfp4_quantize. None of them is part of the paper's method.
+ *
+ * Conventions as in amxfp4.h: every data pointer is a DEVICE pointer owned by the caller, nothing is allocated or
+ * retained, calls are asynchronous on `stream` (hipStream_t as void*), arguments are validated on the host before
+ * any launch, the return value is an amx_status_t and the message is available from amxfp4_last_error().
+ * "bf16" buffers hold BF16 bit patterns (uint16); FP32 -> BF16 conversions round to nearest even.
+ */
+#ifndef AMXFP4_LAYER_H
+#define AMXFP4_LAYER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * RMS normalisation of each row: out[r, c] = bf16( x[r, c] * rsqrt(mean_c(x[r, :]^2) + eps) * weight[c] ), all
+ * arithmetic in FP32. x, out: [rows, dim] BF16, contiguous; weight: [dim] FP32. dim must be a multiple of 8 and at
+ * most 16384.
+ */
+int amxfp4_rmsnorm(const void* x_bf16, const float* weight, int64_t rows, int64_t dim, float eps, void* out_bf16,
+                   void* stream);
+
+/*
+ * Splits a token-major FP32 projection output into heads and (optionally) applies rotary position embedding.
+ * in: [seq, ld] FP32; head h occupies columns col0 + h * head_dim .. + head_dim - 1 of every row.
+ * out: [heads, seq, head_dim] BF16 (head-major, each head a contiguous [seq, head_dim] matrix).
+ * rotate != 0: the pair (i, i + head_dim / 2), i < head_dim / 2, of the token at position p = pos0 + row is rotated
+ * by the angle p * theta^(-2 i / head_dim) ("rotate-half" convention: out_i = x_i cos - x_{i+d/2} sin,
+ * out_{i+d/2} = x_{i+d/2} cos + x_i sin); the angle and its sine / cosine are evaluated in FP64.
+ * rotate == 0: plain conversion and re-layout (values). head_dim must be even and at most 256.
+ */
+int amxfp4_split_heads_rope(const float* in, int64_t seq, int64_t ld, int64_t col0, int64_t heads, int64_t head_dim,
+                            int32_t rotate, int64_t pos0, double theta, void* out_bf16, void* stream);
+
+/*
+ * Causal softmax of attention scores. scores: [batch, rows, cols] FP32, contiguous; row r of every batch entry
+ * belongs to the query at position r % cols (several query heads that share one key head may be stacked along the
+ * rows); it attends to key columns c <= r % cols. out[b, r, c] = bf16( exp(scale * (s[c] - max)) / sum ) over the
+ * allowed columns and exactly 0 elsewhere; FP32 arithmetic. cols at most 16384 and a multiple of 8.
+ */
+int amxfp4_softmax_causal(const float* scores, int64_t batch, int64_t rows, int64_t cols, float scale, void* out_bf16,
+                          void* stream);
+
+/*
+ * Gated activation of a fused gate / up projection: in [rows, 2 * width] FP32 with the gate in columns [0, width) and
+ * the up projection in [width, 2 * width); out[r, c] = bf16( silu(gate) * up ), silu(g) = g / (1 + exp(-g)), FP32.
+ * width must be a multiple of 4.
+ */
+int amxfp4_silu_mul(const float* gate_up, int64_t rows, int64_t width, void* out_bf16, void* stream);
+
+/* out = bf16( float(x) + y ): x, out [n] BF16, y [n] FP32 (residual connection after a projection). n % 4 == 0. */
+int amxfp4_residual_add(const void* x_bf16, const float* y, int64_t n, void* out_bf16, void* stream);
+
+/*
+ * Inverse of the head split for the attention output: in [groups, per_group * seq, head_dim] FP32, where row
+ * j * seq + s of group g is head g * per_group + j at token s; out [seq, groups * per_group * head_dim] BF16
+ * (token-major, head h in columns h * head_dim ..). head_dim % 4 == 0.
+ */
+int amxfp4_merge_heads(const float* in, int64_t groups, int64_t per_group, int64_t seq, int64_t head_dim,
+                       void* out_bf16, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMXFP4_LAYER_H */

@@ -1,4 +1,5 @@
-"""Thin ctypes binding of libamxfp4.so: the same entry points as include/amxfp4.h, taking torch CUDA tensors.
+"""Thin ctypes binding of libamxfp4.so: the same entry points as include/amxfp4.h and include/amxfp4_layer.h, taking
+torch CUDA tensors.
 
 Only argument marshalling happens here (pointers, sizes, the current HIP stream); every step of the path runs in
 the library's kernels. There is no fallback: if the library has not been built, or no GPU is present, calls raise.
@@ -51,6 +52,15 @@ def load():
     L.amxfp4_profile_next_gemm.restype = ctypes.c_int
     L.amxfp4_select_e5m2_kernel.argtypes = [ctypes.c_int32]
     L.amxfp4_select_e5m2_kernel.restype = ctypes.c_int
+    f32, f64, i32 = ctypes.c_float, ctypes.c_double, ctypes.c_int32
+    for name, args in (("amxfp4_rmsnorm", [vp, vp, i64, i64, f32, vp, vp]),
+                       ("amxfp4_split_heads_rope", [vp, i64, i64, i64, i64, i64, i32, i64, f64, vp, vp]),
+                       ("amxfp4_softmax_causal", [vp, i64, i64, i64, f32, vp, vp]),
+                       ("amxfp4_silu_mul", [vp, i64, i64, vp, vp]),
+                       ("amxfp4_residual_add", [vp, vp, i64, vp, vp]),
+                       ("amxfp4_merge_heads", [vp, i64, i64, i64, i64, vp, vp])):
+        getattr(L, name).argtypes = args
+        getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
 
@@ -154,4 +164,69 @@ def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, ba
     _check(_fn(fmt, "gemm", baseline)(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
                                       b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(), out.stride(-2), batch,
                                       ws_ptr, ws_len, _stream()))
+    return out
+
+
+# ---- glue operators of the decoder-layer workload (include/amxfp4_layer.h) ------------------------------------------
+
+def _bf16_out(shape, device):
+    return torch.empty(shape, dtype=torch.bfloat16, device=device)
+
+
+def rmsnorm(x, weight, eps):
+    """x [rows, dim] BF16, weight [dim] FP32 -> BF16 [rows, dim]."""
+    _need_cuda(x, weight)
+    assert x.is_contiguous() and x.dtype == torch.bfloat16 and weight.dtype == torch.float32
+    out = _bf16_out(x.shape, x.device)
+    _check(load().amxfp4_rmsnorm(x.data_ptr(), weight.data_ptr(), x.shape[0], x.shape[1], eps, out.data_ptr(),
+                                 _stream()))
+    return out
+
+
+def split_heads_rope(proj, col0, heads, head_dim, rotate, pos0=0, theta=10000.0):
+    """proj [seq, ld] FP32 (a projection output) -> BF16 [heads, seq, head_dim], rotary embedding if `rotate`."""
+    _need_cuda(proj)
+    assert proj.dtype == torch.float32 and proj.dim() == 2 and proj.stride(1) == 1
+    seq = proj.shape[0]
+    out = _bf16_out((heads, seq, head_dim), proj.device)
+    _check(load().amxfp4_split_heads_rope(proj.data_ptr(), seq, proj.stride(0), col0, heads, head_dim,
+                                          1 if rotate else 0, pos0, theta, out.data_ptr(), _stream()))
+    return out
+
+
+def softmax_causal(scores, scale):
+    """scores [batch, rows, cols] FP32 (row r = query position r % cols) -> BF16 probabilities, masked entries 0."""
+    _need_cuda(scores)
+    assert scores.dtype == torch.float32 and scores.dim() == 3 and scores.is_contiguous()
+    out = _bf16_out(scores.shape, scores.device)
+    _check(load().amxfp4_softmax_causal(scores.data_ptr(), scores.shape[0], scores.shape[1], scores.shape[2], scale,
+                                        out.data_ptr(), _stream()))
+    return out
+
+
+def silu_mul(gate_up):
+    """gate_up [rows, 2 * width] FP32 (gate | up) -> BF16 [rows, width] = silu(gate) * up."""
+    _need_cuda(gate_up)
+    assert gate_up.dtype == torch.float32 and gate_up.is_contiguous()
+    rows, width = gate_up.shape[0], gate_up.shape[1] // 2
+    out = _bf16_out((rows, width), gate_up.device)
+    _check(load().amxfp4_silu_mul(gate_up.data_ptr(), rows, width, out.data_ptr(), _stream()))
+    return out
+
+
+def residual_add(x, y):
+    """BF16 x + FP32 y -> BF16, same shape."""
+    _need_cuda(x, y)
+    assert x.dtype == torch.bfloat16 and y.dtype == torch.float32 and x.is_contiguous() and y.is_contiguous()
+    out = _bf16_out(x.shape, x.device)
+    _check(load().amxfp4_residual_add(x.data_ptr(), y.data_ptr(), x.numel(), out.data_ptr(), _stream()))
+    return out
+
+
+def merge_heads(o, groups, per_group, seq, head_dim):
+    """o [groups, per_group * seq, head_dim] FP32 -> BF16 [seq, groups * per_group * head_dim] (token-major)."""
+    _need_cuda(o)
+    assert o.dtype == torch.float32 and o.is_contiguous()
+    out = _bf16_out((seq, groups * per_group * head_dim), o.device)
+    _check(load().amxfp4_merge_heads(o.data_ptr(), groups, per_group, seq, head_dim, out.data_ptr(), _stream()))
     return out

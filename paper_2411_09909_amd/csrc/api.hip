@@ -49,6 +49,16 @@ int hip_fail(hipError_t e, const char* what) {
   return fail(AMX_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+}  // namespace
+
+namespace amx {
+// the same thread-local status message for the entry points defined in other files
+int report_error(int code, const char* msg) { return fail(code, "%s", msg); }
+int report_hip_error(hipError_t e, const char* what) { return hip_fail(e, what); }
+}  // namespace amx
+
+namespace {
+
 int quantize_impl(amx_format_t f, const void* x, int64_t rows, int64_t K, int64_t row_stride, int64_t k_stride,
                   uint8_t* codes, uint8_t* scales, void* stream) {
   if (int rc = check_format(&f)) return rc;

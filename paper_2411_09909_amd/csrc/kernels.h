@@ -16,6 +16,10 @@ constexpr int kPanelK = 128;
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 
+// api.hip: status reporting shared by all entry points (thread-local message behind amxfp4_last_error)
+int report_error(int code, const char* msg);
+int report_hip_error(hipError_t e, const char* what);
+
 // cast.hip
 hipError_t launch_quantize_contig(int scale_kind, bool asym, const uint16_t* x, int64_t rows, int64_t K,
                                   int64_t row_stride, uint8_t* codes, uint8_t* scales, hipStream_t s);

@@ -1,0 +1,105 @@
+"""One LLaMA-style decoder layer (grouped-query attention, rotary embedding, gated MLP) whose seven matrix
+multiplications all go through the quantized path: every operand is cast with amxfp4_quantize and multiplied with
+amxfp4_gemm (Sec. 5.1: the linear projections and both attention products are quantized, the rest stays BF16).
+
+This module only sequences library calls; the arithmetic is in libamxfp4 (binding.py marshals the arguments).
+Shapes for a sequence of S tokens, H query heads, G key/value heads (H = G * per), head size D, model width W = H * D,
+MLP width F:
+  qkv    = cast(rmsnorm(x)) . Wqkv^T                  [S, W + 2 G D]
+  scores = cast(rope(q)) . cast(rope(k))^T            batch G, [per * S, S]   (the `per` query heads that share a key
+                                                                                head are stacked along the rows)
+  o      = cast(softmax(scores)) . cast(v)^T          batch G, [per * S, D]   (P grouped along the keys, V cast down
+                                                                                its columns)
+  x2     = x + cast(merge(o)) . Wo^T
+  out    = x2 + cast(silu(g) * u) . Wd^T,  (g | u) = cast(rmsnorm(x2)) . Wgu^T
+"""
+import math
+from dataclasses import dataclass
+
+import torch
+
+from . import binding
+
+
+@dataclass
+class LayerConfig:
+    d_model: int = 4096
+    n_heads: int = 32
+    n_kv_heads: int = 8
+    head_dim: int = 128
+    d_ff: int = 14336
+    eps: float = 1e-5
+    rope_theta: float = 500000.0
+
+
+WEIGHT_SHAPES = lambda c: {  # noqa: E731  (name -> [out features, in features])
+    "wq": (c.n_heads * c.head_dim, c.d_model), "wk": (c.n_kv_heads * c.head_dim, c.d_model),
+    "wv": (c.n_kv_heads * c.head_dim, c.d_model), "wo": (c.d_model, c.n_heads * c.head_dim),
+    "wg": (c.d_ff, c.d_model), "wu": (c.d_ff, c.d_model), "wd": (c.d_model, c.d_ff)}
+
+
+class DecoderLayer:
+    """weights: dict name -> BF16 CUDA tensor (WEIGHT_SHAPES) plus "norm1" / "norm2" FP32 [d_model]. The weights are
+    cast once here (they are static in inference); forward() casts the activations."""
+
+    def __init__(self, cfg, weights, fmt, baseline=False):
+        self.cfg, self.fmt, self.baseline = cfg, fmt, baseline
+        q = lambda w: binding.quantize(fmt, w.contiguous(), baseline=baseline)  # noqa: E731
+        self.wqkv = q(torch.cat([weights["wq"], weights["wk"], weights["wv"]], 0))
+        self.wo = q(weights["wo"])
+        self.wgu = q(torch.cat([weights["wg"], weights["wu"]], 0))
+        self.wd = q(weights["wd"])
+        self.norm1, self.norm2 = weights["norm1"].contiguous(), weights["norm2"].contiguous()
+        self._ws = None
+
+    def _gemm(self, a, b):
+        fmt = self.fmt
+        batch = a[0].shape[0] if a[0].dim() == 3 else 1
+        need = binding.gemm_workspace_bytes(fmt, a[0].shape[-2], b[0].shape[-2], a[0].shape[-1] * 2, batch)
+        if need and (self._ws is None or self._ws.numel() < need):
+            self._ws = torch.empty(need, dtype=torch.uint8, device=a[0].device)
+        return binding.gemm(fmt, a[0], a[1], b[0], b[1], workspace=self._ws if need else None, baseline=self.baseline)
+
+    def _cast(self, x, k_axis=-1):
+        return binding.quantize(self.fmt, x, k_axis=k_axis, baseline=self.baseline)
+
+    def forward(self, x, pos0=0):
+        c = self.cfg
+        S, G, D = x.shape[0], c.n_kv_heads, c.head_dim
+        per = c.n_heads // G
+        nsc = self.wqkv[1].shape[2:]  # () or (2,): scale entries per group
+
+        h = binding.rmsnorm(x, self.norm1, c.eps)
+        qkv = self._gemm(self._cast(h), self.wqkv)
+        q = binding.split_heads_rope(qkv, 0, c.n_heads, D, True, pos0, c.rope_theta)
+        k = binding.split_heads_rope(qkv, c.n_heads * D, G, D, True, pos0, c.rope_theta)
+        v = binding.split_heads_rope(qkv, (c.n_heads + G) * D, G, D, False)
+
+        qc, qs = self._cast(q.view(c.n_heads * S, D))
+        kc, ks = self._cast(k.view(G * S, D))
+        scores = self._gemm((qc.view(G, per * S, D // 2), qs.view(G, per * S, D // 32, *nsc)),
+                            (kc.view(G, S, D // 2), ks.view(G, S, D // 32, *nsc)))
+        p = binding.softmax_causal(scores, 1.0 / math.sqrt(D))
+        del scores
+        pc, ps = self._cast(p.view(G * per * S, S))
+        del p
+        vc = torch.empty((G, D, S // 2), dtype=torch.uint8, device=x.device)
+        vs = torch.empty((G, D, S // 32) + tuple(nsc), dtype=torch.uint8, device=x.device)
+        for g in range(G):  # V of one head is [S, D]; its groups run down the columns (along the keys)
+            binding.quantize(self.fmt, v[g], k_axis=0, codes=vc[g], scales=vs[g], baseline=self.baseline)
+        o = self._gemm((pc.view(G, per * S, S // 2), ps.view(G, per * S, S // 32, *nsc)), (vc, vs))
+        attn = binding.merge_heads(o, G, per, S, D)
+
+        x2 = binding.residual_add(x, self._gemm(self._cast(attn), self.wo))
+        h2 = binding.rmsnorm(x2, self.norm2, c.eps)
+        act = binding.silu_mul(self._gemm(self._cast(h2), self.wgu))
+        return binding.residual_add(x2, self._gemm(self._cast(act), self.wd))
+
+    def matmul_flops(self, S):
+        """2 * M * N * K summed over the seven quantized matmuls (attention products counted in full, no causal
+        skipping: that is what runs)."""
+        c = self.cfg
+        W, F, kv = c.n_heads * c.head_dim, c.d_ff, c.n_kv_heads * c.head_dim
+        lin = S * c.d_model * (W + 2 * kv) + S * W * c.d_model + S * c.d_model * 2 * F + S * F * c.d_model
+        att = 2 * c.n_heads * S * S * c.head_dim
+        return 2.0 * (lin + att)

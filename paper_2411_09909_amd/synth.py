@@ -117,3 +117,23 @@ def linear_operands(name, seed=0, M=None, N=None):
     else:
         x = activations(m, c["K"], seed, c["n_outlier"], c["outlier_gain"], c["shift"])
     return x, weights(n, c["K"], seed)
+
+
+def layer_weights(cfg, seed=0, stream=20):
+    """Random-init weights of one decoder layer: projection matrices ~ N(0, 0.02) as BF16 bits ([out, in]), RMSNorm
+    gains 1 + 0.1 N(0,1) as float32. cfg: d_model, n_heads, n_kv_heads, head_dim, d_ff."""
+    shapes = {"wq": (cfg.n_heads * cfg.head_dim, cfg.d_model), "wk": (cfg.n_kv_heads * cfg.head_dim, cfg.d_model),
+              "wv": (cfg.n_kv_heads * cfg.head_dim, cfg.d_model), "wo": (cfg.d_model, cfg.n_heads * cfg.head_dim),
+              "wg": (cfg.d_ff, cfg.d_model), "wu": (cfg.d_ff, cfg.d_model), "wd": (cfg.d_model, cfg.d_ff)}
+    w = {}
+    for i, (name, shape) in enumerate(shapes.items()):
+        w[name] = weights(shape[0], shape[1], seed, stream=stream + i)
+    rng = _rng(seed, stream + 10)
+    w["norm1"] = (1.0 + 0.1 * rng.standard_normal(cfg.d_model)).astype(np.float32)
+    w["norm2"] = (1.0 + 0.1 * rng.standard_normal(cfg.d_model)).astype(np.float32)
+    return w
+
+
+def layer_input(seq, d_model, seed=0, n_outlier=4, outlier_gain=20.0):
+    """Hidden states entering a decoder layer: N(0,1) with a few outlier channels, BF16 bits [seq, d_model]."""
+    return activations(seq, d_model, seed, n_outlier, outlier_gain, shift=0.0, stream=31)

@@ -9,7 +9,7 @@ import pytest
 from paper_2411_09909_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "amxfp4.h")
+HEADERS = [os.path.join(ROOT, "include", n) for n in ("amxfp4.h", "amxfp4_layer.h")]
 
 
 @pytest.fixture(scope="module")
@@ -21,7 +21,7 @@ def lib():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b((?:amxfp4|mxfp4)_[a-z_0-9]+)\s*\(", text)))
 
@@ -30,7 +30,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"amxfp4_quantize", "amxfp4_dequantize", "amxfp4_gemm", "mxfp4_quantize", "mxfp4_dequantize",
             "mxfp4_gemm", "amxfp4_last_error", "amxfp4_codes_bytes", "amxfp4_scales_bytes",
-            "amxfp4_gemm_workspace_bytes"} <= set(names)
+            "amxfp4_gemm_workspace_bytes", "amxfp4_rmsnorm", "amxfp4_split_heads_rope", "amxfp4_softmax_causal",
+            "amxfp4_silu_mul", "amxfp4_residual_add", "amxfp4_merge_heads"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -99,3 +100,17 @@ def test_binding_refuses_host_tensors(lib):
     f = binding.make_format()
     with pytest.raises(binding.AmxError):
         binding.quantize(f, torch.zeros(4, 64, dtype=torch.bfloat16))
+
+
+def test_layer_operators_reject_bad_arguments(lib):
+    p = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
+    assert lib.amxfp4_rmsnorm(None, p, 4, 64, 1e-5, p, None) == -1
+    assert lib.amxfp4_rmsnorm(p, p, 4, 60, 1e-5, p, None) == -1           # dim % 8
+    assert lib.amxfp4_rmsnorm(p, p, 4, 32768, 1e-5, p, None) == -1        # dim too large
+    assert lib.amxfp4_split_heads_rope(p, 8, 100, 0, 2, 64, 1, 0, 10000.0, p, None) == -1   # ld < heads * head_dim
+    assert lib.amxfp4_split_heads_rope(p, 8, 128, 0, 2, 64, 1, 0, 0.5, p, None) == -1       # theta <= 1
+    assert lib.amxfp4_softmax_causal(p, 1, 8, 20, 1.0, p, None) == -1     # cols % 8
+    assert lib.amxfp4_silu_mul(p, 4, 6, p, None) == -1
+    assert lib.amxfp4_residual_add(p, p, 6, p, None) == -1
+    assert lib.amxfp4_merge_heads(p, 2, 2, 8, 6, p, None) == -1
+    assert b"merge_heads" in lib.amxfp4_last_error()

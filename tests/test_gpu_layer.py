@@ -1,0 +1,108 @@
+"""GPU parity of the decoder-layer glue operators and of a whole (cut-down) decoder layer against the oracle.
+
+Operator outputs are BF16. The kernels compute in FP32 (rotary angles in FP64) and round once; the oracle rounds the
+float64 result once. The two can therefore differ by one BF16 step where the value lies within FP32 rounding error
+of a BF16 rounding boundary: the tests allow a difference of at most one BF16 step on at most 0.2 % of the elements
+and require bit equality elsewhere (measured mismatch rates are printed in the assertion messages)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer_ref as L
+from oracle import ref
+from paper_2411_09909_amd import binding, layer, synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def bf16_steps(a_bits, b_bits):
+    """distance in BF16 steps between two bit patterns of equal sign (or across zero)"""
+    def key(b):
+        b = b.astype(np.int32)
+        return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+    return np.abs(key(np.asarray(a_bits)) - key(np.asarray(b_bits)))
+
+
+def assert_bf16_close(got, want, what, max_frac=2e-3):
+    got = got.view(torch.int16).cpu().numpy().view(np.uint16)
+    d = bf16_steps(got, want)
+    assert d.max() <= 1, "%s: %d BF16 steps apart" % (what, d.max())
+    frac = float((d != 0).mean())
+    assert frac <= max_frac, "%s: %.4f of the elements differ by one step" % (what, frac)
+
+
+def dev_f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda()
+
+
+def test_rmsnorm():
+    x = synth.activations(300, 4096, seed=1, n_outlier=4, outlier_gain=30.0)
+    w = (1 + 0.1 * np.random.default_rng(1).standard_normal(4096)).astype(np.float32)
+    assert_bf16_close(binding.rmsnorm(G.to_dev_bf16(x), dev_f32(w), 1e-5), L.rmsnorm(x, w, 1e-5), "rmsnorm")
+    x = synth.activations(5, 8, seed=2, n_outlier=1, outlier_gain=3.0)  # smallest width
+    w = np.ones(8, np.float32)
+    assert_bf16_close(binding.rmsnorm(G.to_dev_bf16(x), dev_f32(w), 1e-6), L.rmsnorm(x, w, 1e-6), "rmsnorm small")
+
+
+@pytest.mark.parametrize("rotate", [True, False])
+def test_split_heads_rope(rotate):
+    rng = np.random.default_rng(3)
+    seq, heads, d = 257, 5, 128
+    proj = (rng.standard_normal((seq, 64 + heads * d + 32)) * 4).astype(np.float32)
+    got = binding.split_heads_rope(dev_f32(proj), 64, heads, d, rotate, pos0=8000, theta=500000.0)
+    want = L.split_heads_rope(proj, 64, heads, d, rotate, pos0=8000, theta=500000.0)
+    assert got.shape == (heads, seq, d)
+    assert_bf16_close(got, want, "split_heads_rope")
+    if not rotate:  # a pure conversion: FP32 -> BF16 is the same rounding on both sides
+        assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16), want)
+
+
+def test_softmax_causal():
+    rng = np.random.default_rng(4)
+    batch, per, seq = 2, 4, 264
+    s = (rng.standard_normal((batch, per * seq, seq)) * 30).astype(np.float32)
+    got = binding.softmax_causal(dev_f32(s), 0.08838834764831845)
+    want = L.softmax_causal(s, 0.08838834764831845)
+    assert_bf16_close(got, want, "softmax_causal", max_frac=5e-3)
+    # masked entries are exactly zero
+    rows = np.arange(per * seq) % seq
+    masked = np.arange(seq)[None, :] > rows[:, None]
+    assert np.all(got.view(torch.int16).cpu().numpy()[:, masked] == 0)
+
+
+def test_silu_mul_residual_add_merge_heads():
+    rng = np.random.default_rng(5)
+    gu = (rng.standard_normal((130, 2 * 1028)) * 3).astype(np.float32)
+    assert_bf16_close(binding.silu_mul(dev_f32(gu)), L.silu_mul(gu), "silu_mul")
+    x = synth.activations(77, 512, seed=6, n_outlier=2, outlier_gain=10.0)
+    y = rng.standard_normal((77, 512)).astype(np.float32)
+    got = binding.residual_add(G.to_dev_bf16(x), dev_f32(y))
+    assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16), L.residual_add(x, y))  # one FP32 add
+    o = rng.standard_normal((2, 3 * 50, 64)).astype(np.float32)
+    got = binding.merge_heads(dev_f32(o), 2, 3, 50, 64)
+    assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16), L.merge_heads(o, 2, 3, 50, 64))
+
+
+@pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.E8M0_FLOOR, 0)])
+def test_decoder_layer_cut_down(scale, asym):
+    """A layer with the real head size and grouped-query structure but small widths (the oracle runs it in seconds).
+    Quantization makes the layer output a discontinuous function of its intermediates: where an intermediate BF16
+    value differs by one step between the two sides (see above), codes of that group may change, so the outputs are
+    compared in norm, relative to the layer's own update (output - input)."""
+    cfg = layer.LayerConfig(d_model=512, n_heads=4, n_kv_heads=2, head_dim=128, d_ff=1024)
+    S = 256
+    w = synth.layer_weights(cfg, seed=0)
+    x = synth.layer_input(S, cfg.d_model, seed=0)
+    fmt = binding.make_format(scale, asym)
+    wd = {k: (dev_f32(v) if v.dtype == np.float32 else G.to_dev_bf16(v)) for k, v in w.items()}
+    lay = layer.DecoderLayer(cfg, wd, fmt)
+    out = lay.forward(G.to_dev_bf16(x))
+    torch.cuda.synchronize()
+    got = L.f64_from_bf16(out.view(torch.int16).cpu().numpy().view(np.uint16))
+    want = L.f64_from_bf16(L.decoder_layer(x, w, cfg, scale, asym))
+    upd = want - L.f64_from_bf16(x)
+    err = np.linalg.norm(got - want) / np.linalg.norm(upd)
+    assert err <= 2e-2, "layer output differs from the oracle by %.4f of the layer's update" % err
+    exact = float((got == want).mean())
+    assert exact >= 0.9, "only %.3f of the output elements are bit-identical" % exact
