@@ -21,6 +21,7 @@ sys.path.insert(0, ROOT)
 WORKLOAD = "c3_70b_up_4096x8192x28672"
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense BF16 MFMA
 PEAK_FP4_TFLOPS = 10100.0   # MI355X dense block-scaled FP4 MFMA (the metric's reference peak)
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense block-scaled FP8 MFMA
 # HBM bytes per GEMM-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see
 # profiles/gemm_bf16_c3_up_counters.md.
 MEASURED_TRAFFIC_BYTES = 3.43e9  # 2.96 GB fetched + 0.47 GB written
@@ -31,7 +32,7 @@ FORMATS = {
     "amxfp4_e5m2": (2, True, "bf16", PEAK_BF16_TFLOPS),    # the paper's AMXFP4: FP8-E5M2 asymmetric scales
     "mxfp4_e5m2": (2, False, "bf16", PEAK_BF16_TFLOPS),    # the paper's "MXFP4" rows: FP8-E5M2 symmetric scale
     "mxfp4_e8m0": (0, False, "fp4", PEAK_FP4_TFLOPS),      # OCP MXFP4 (power-of-two scale, exponent floored)
-    "amxfp4_e8m0": (0, True, "fp4", PEAK_FP4_TFLOPS),      # asymmetric power-of-two scales: sign-split, 4 MFMAs/block
+    "amxfp4_e8m0": (0, True, "fp8", PEAK_FP8_TFLOPS),      # asymmetric power-of-two scales merged into E5M2 elements
 }
 
 
@@ -170,7 +171,7 @@ def main():
     value = flops / r["t_step"] / 1e12
     achieved = flops / (r["kern_ms"] * 1e-3) / 1e12
     cast_bytes = M * K * 2 + M * K // 2 + M * (K // 32) * (2 if r["asym"] else 1)
-    kernel_name = "gemm_fp4_kernel" if r["mfma"] == "fp4" else {"panel": "gemm_bf16_kernel", "hybrid":
+    kernel_name = "gemm_fp4_kernel" if r["mfma"] == "fp4" else "gemm_fp8m_kernel" if r["mfma"] == "fp8" else {"panel": "gemm_bf16_kernel", "hybrid":
                   "gemm_e5m2_hybrid_kernel", "fused": "gemm_e5m2_kernel"}[args.e5m2_kernel]
     out = {
         "metric": "AMXFP4 cast+GEMM TFLOPS at 4096x8192x28672", "value": round(value, 2), "unit": "TFLOP/s",

@@ -150,6 +150,18 @@ int amxfp4_profile_next_gemm(void* start_event, void* stop_event);
  */
 int amxfp4_select_e5m2_kernel(int32_t which);
 
+/*
+ * Tuning aid: the GEMM for ASYMMETRIC power-of-two scales (Sec. 4.2, "PoT") exists in two kernels:
+ *   0  each group merged into E5M2 elements elem * 2^(s_class - anchor) with one anchor scale max(s_p, s_n), one
+ *      block-scaled FP8 MFMA per block (default; any K; needs the workspace). Exact unless the two scales of a group
+ *      differ by more than 2^13: then the small class is flushed to zero (below 1e-4 of that group's magnitude);
+ *   1  each operand split by sign into two MXFP4 operands, four block-scaled FP4 MFMAs per block (exact; K a multiple
+ *      of 128, other K fall back to 0; no workspace).
+ * Process-wide, affects amxfp4_gemm_workspace_bytes, starts from the environment variable AMXFP4_POT_PATH =
+ * merged | split. Returns AMX_OK, or AMX_ERR_INVALID_ARG for another value.
+ */
+int amxfp4_select_pot_kernel(int32_t which);
+
 #ifdef __cplusplus
 }
 #endif

@@ -52,6 +52,8 @@ def load():
     L.amxfp4_profile_next_gemm.restype = ctypes.c_int
     L.amxfp4_select_e5m2_kernel.argtypes = [ctypes.c_int32]
     L.amxfp4_select_e5m2_kernel.restype = ctypes.c_int
+    L.amxfp4_select_pot_kernel.argtypes = [ctypes.c_int32]
+    L.amxfp4_select_pot_kernel.restype = ctypes.c_int
     f32, f64, i32 = ctypes.c_float, ctypes.c_double, ctypes.c_int32
     for name, args in (("amxfp4_rmsnorm", [vp, vp, i64, i64, f32, vp, vp]),
                        ("amxfp4_split_heads_rope", [vp, i64, i64, i64, i64, i64, i32, i64, f64, vp, vp]),
@@ -108,6 +110,14 @@ def select_e5m2_kernel(which):
     """Chooses among the three GEMM kernels for FP8-E5M2 scales ("panel" | "hybrid" | "fused", or 0 | 1 | 2);
     process-wide, also changes gemm_workspace_bytes."""
     _check(load().amxfp4_select_e5m2_kernel(E5M2_KERNELS.get(which, which)))
+
+
+POT_KERNELS = {"merged": 0, "split": 1}
+
+
+def select_pot_kernel(which):
+    """Chooses between the two GEMM kernels for asymmetric power-of-two scales ("merged" | "split", or 0 | 1)."""
+    _check(load().amxfp4_select_pot_kernel(POT_KERNELS.get(which, which)))
 
 
 def _fn(fmt, name, baseline):

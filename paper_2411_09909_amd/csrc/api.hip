@@ -120,6 +120,21 @@ E5m2Path e5m2_path(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
   return kPathPanel;
 }
 
+// Asymmetric power-of-two scales have two kernels (amxfp4_select_pot_kernel in the header): the groups merged into
+// E5M2 elements with one anchor scale on the block-scaled FP8 MFMA (default; any K; workspace), or split by sign into
+// four FP4 MFMAs per block (K a multiple of 128; no workspace).
+std::atomic<int>& pot_choice() {
+  static std::atomic<int> choice([] {
+    const char* v = getenv("AMXFP4_POT_PATH");
+    return v && strcmp(v, "split") == 0 ? 1 : 0;
+  }());
+  return choice;
+}
+bool uses_merged_pot(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
+  if (!f.asymmetric || (f.scale != AMX_SCALE_E8M0_FLOOR && f.scale != AMX_SCALE_E8M0_ROUND)) return false;
+  return pot_choice().load(std::memory_order_relaxed) == 0 || !amx::fp4_path_supported(M, N, K);
+}
+
 int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
               const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch, void* workspace,
               size_t workspace_bytes, void* stream) {
@@ -139,6 +154,11 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
   }
   const amx::KernelTimer timer = g_timer;
   g_timer = amx::KernelTimer();
+  if (uses_merged_pot(f, M, N, K)) {
+    hipError_t e = amx::launch_gemm_fp8m_path(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace,
+                                              reinterpret_cast<hipStream_t>(stream), timer);
+    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
+  }
   if (uses_fp4_mfma(f, M, N, K)) {
     hipError_t e = amx::launch_gemm_fp4_path(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc,
                                              batch, reinterpret_cast<hipStream_t>(stream), timer);
@@ -178,6 +198,12 @@ int amxfp4_select_e5m2_kernel(int32_t which) {
   return AMX_OK;
 }
 
+int amxfp4_select_pot_kernel(int32_t which) {
+  if (which < 0 || which > 1) return fail(AMX_ERR_INVALID_ARG, "no such kernel: %d", (int)which);
+  pot_choice().store(which, std::memory_order_relaxed);
+  return AMX_OK;
+}
+
 int amxfp4_profile_next_gemm(void* start_event, void* stop_event) {
   g_timer.start = reinterpret_cast<hipEvent_t>(start_event);
   g_timer.stop = reinterpret_cast<hipEvent_t>(stop_event);
@@ -196,6 +222,7 @@ size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
 
 size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch) {
   if (!fmt || M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
+  if (uses_merged_pot(*fmt, M, N, K)) return amx::fp8m_path_workspace_bytes(M, N, K, batch);
   if (uses_fp4_mfma(*fmt, M, N, K)) return 0;
   const E5m2Path path = e5m2_path(*fmt, M, N, K);
   if (path == kPathFused) return 0;

@@ -49,6 +49,13 @@ hipError_t launch_gemm_fp4_path(bool asym, int64_t M, int64_t N, int64_t K, cons
                                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
                                 int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer);
 
+// gemm_fp8m.hip: asymmetric power-of-two scales merged per group into E5M2 elements + one anchor scale, block-scaled
+// FP8 MFMA (workspace: the merged panels)
+size_t fp8m_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
+hipError_t launch_gemm_fp8m_path(int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
+                                 const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch,
+                                 void* workspace, hipStream_t s, const KernelTimer& timer);
+
 // gemm_e5m2.hip: FP8-E5M2 scales, dequantization fused into the FP16-MFMA kernel (no workspace)
 bool e5m2_fused_supported(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm_e5m2_fused(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,

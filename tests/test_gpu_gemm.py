@@ -140,3 +140,53 @@ def test_alternative_e5m2_kernels_batched_and_llm_shape(alternative_e5m2_kernel)
     Cr = ref.gemm(shp(ac, 130), shp(as_, 130), shp(bc, 200), shp(bs, 200), 32, ref.FP8_E5M2, 1)
     assert C.shape == (3, 130, 200)
     assert G.rel_fro(C, Cr) <= TOL
+
+
+@pytest.fixture
+def split_pot_kernel():
+    """The sign-split FP4 kernel for asymmetric power-of-two scales (the merged FP8 kernel is the default)."""
+    from paper_2411_09909_amd import binding
+    binding.select_pot_kernel("split")
+    yield
+    binding.select_pot_kernel("merged")
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 1024, 1024), (257, 255, 384), (300, 520, 1280), (100, 200, 160)])
+def test_sign_split_kernel_for_asymmetric_power_of_two_scales(split_pot_kernel, M, N, K):
+    """K = 160 is not a multiple of 128: the split kernel does not take it and the call falls back to merging."""
+    a = synth.activations(M, K, seed=M + K, n_outlier=1, outlier_gain=60.0)
+    b = synth.weights(N, K, seed=N)
+    ac, as_ = ref.quantize(a, 32, ref.E8M0_FLOOR, 1)
+    bc, bs = ref.quantize(b, 32, ref.E8M0_FLOOR, 1)
+    C = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1)
+    assert G.rel_fro(C, ref.gemm(ac, as_, bc, bs, 32, ref.E8M0_FLOOR, 1)) <= TOL
+
+
+def test_merged_kernel_with_far_apart_sign_scales():
+    """Groups whose positive and negative scales are far apart. The merged kernel keeps both classes in one E5M2
+    operand: up to 2^13 apart every element is represented exactly, beyond that the small class is flushed; in both
+    cases the products of the small class are tiny next to those of the large one, and the block-scaled MFMA adds the
+    products of a block in a fixed-point window below the largest of them, which costs up to ~6e-5 (measured: 0 for a
+    gap of 2^4, 1.8e-5 for 2^8, 5.4e-5 for 2^12). All of it must stay far inside the tolerance; the sign-split kernel
+    multiplies the classes separately and is exact on the same operands."""
+    from paper_2411_09909_amd import binding
+    rng = np.random.default_rng(7)
+    M, N, K = 96, 160, 256
+    mag = np.abs(rng.standard_normal((M, K))).astype(np.float32) + 0.1
+    a = mag.copy()
+    a[:, 1::2] *= -1.0                            # alternate signs
+    a[:, 0::2] *= np.float32(2.0 ** 10)           # positives 2^10 above the negatives ...
+    a[: M // 2, 1::2] *= np.float32(2.0 ** -10)   # ... and 2^20 above in half of the rows
+    b = synth.weights(N, K, seed=3)
+    ac, as_ = ref.quantize(synth.f32_to_bf16_bits(a), 32, ref.E8M0_FLOOR, 1)
+    bc, bs = ref.quantize(b, 32, ref.E8M0_FLOOR, 1)
+    Cr = ref.gemm(ac, as_, bc, bs, 32, ref.E8M0_FLOOR, 1)
+    C = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1)
+    assert G.rel_fro(C, Cr) <= 1e-4
+    assert max(G.rel_fro(C[i], Cr[i]) for i in range(M)) <= 2e-4
+    binding.select_pot_kernel("split")
+    try:
+        Cs = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1)
+    finally:
+        binding.select_pot_kernel("merged")
+    assert G.rel_fro(Cs, Cr) <= 1e-6
