@@ -19,7 +19,6 @@
 namespace amx {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch) {
   const int64_t Kp = round_up(K, kPanelK);
@@ -210,23 +209,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t*
 #undef AMX_STAGE
 #undef AMX_ISSUE_LOAD
 
-  // C tile: accumulator register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 block
-  float* Cb = C + b * M * ldc;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int64_t col = (int64_t)tn * Cfg::kTileN + (wn * FN + j) * 32 + (lane & 31);
-      const int64_t row0 = (int64_t)tm * Cfg::kTileM + (wm * FM + i) * 32 + 4 * (lane >> 5);
-      if (col < N) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int64_t row = row0 + 8 * (v >> 2) + (v & 3);
-          if (row < M) __builtin_nontemporal_store(acc[i][j][v], Cb + row * ldc + col);
-        }
-      }
-    }
-  }
+  store_c_tiles<FM, FN>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * Cfg::kTileM + wm * FM * 32,
+                        (int64_t)tn * Cfg::kTileN + wn * FN * 32);
 }
 
 template <int SK, bool ASYM, bool F16 = false>

@@ -30,7 +30,6 @@ namespace amx {
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kE5Tile = 256;            // tile edge (rows of A and of B per workgroup)
 constexpr int kRawCodes = kE5Tile * 64;  // bytes of one operand's codes per raw stage (K = 128)
@@ -292,23 +291,8 @@ __global__ __launch_bounds__(512) void gemm_e5m2_kernel(const uint8_t* __restric
 #undef AMX_RAW_READ
 #undef AMX_ISSUE_RAW
 
-  // C tile (accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32); 2^6 undoes the operand bias
-  float* Cb = C + b * M * ldc;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int64_t col = (int64_t)tn * kE5Tile + (wn * FN + j) * 32 + (lane & 31);
-      const int64_t row0 = (int64_t)tm * kE5Tile + (wm * FM + i) * 32 + 4 * (lane >> 5);
-      if (col < N) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int64_t row = row0 + 8 * (v >> 2) + (v & 3);
-          if (row < M) __builtin_nontemporal_store(acc[i][j][v] * 64.0f, Cb + row * ldc + col);
-        }
-      }
-    }
-  }
+  store_c_tiles<FM, FN, 6 /* 2^6 undoes the operand bias */>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * kE5Tile + wm * FM * 32,
+                        (int64_t)tn * kE5Tile + wn * FN * 32);
 }
 
 bool e5m2_fused_supported(int64_t M, int64_t N, int64_t K) {
@@ -580,23 +564,8 @@ __global__ __launch_bounds__(256) void gemm_e5m2_hybrid_kernel(const uint16_t* _
 #undef AMX_ISSUE_RAW
 #undef AMX_ISSUE_A
 
-  // C tile (accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32); 2^6 undoes the operand bias
-  float* Cb = C + b * M * ldc;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int64_t col = (int64_t)tn * kE5Tile + (wn * FN + j) * 32 + (lane & 31);
-      const int64_t row0 = (int64_t)tm * kE5Tile + (wm * FM + i) * 32 + 4 * (lane >> 5);
-      if (col < N) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int64_t row = row0 + 8 * (v >> 2) + (v & 3);
-          if (row < M) __builtin_nontemporal_store(acc[i][j][v] * 64.0f, Cb + row * ldc + col);
-        }
-      }
-    }
-  }
+  store_c_tiles<FM, FN, 6 /* 2^6 undoes the operand bias */>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * kE5Tile + wm * FM * 32,
+                        (int64_t)tn * kE5Tile + wn * FN * 32);
 }
 
 bool e5m2_hybrid_supported(int64_t M, int64_t N, int64_t K) {

@@ -23,7 +23,6 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 // information which LDS array it reads (a struct of four words is read as four loads, three of which lose it, and the
 // compiler then waits for every direct-to-LDS load in flight before each read)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ i32x8 as_operand(u32x4 v) {
   i32x8 r = {(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};  // FP4 uses the first 4 of the 8 operand registers
@@ -297,22 +296,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
 #undef lds1_A
 #undef lds1_B
 
-  float* Cb = C + b * M * ldc;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int64_t col = (int64_t)tn * kTileN + (wn * FN + j) * 32 + (lane & 31);
-      const int64_t row0 = (int64_t)tm * kTileM + (wm * FM + i) * 32 + 4 * (lane >> 5);
-      if (col < N) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int64_t row = row0 + 8 * (v >> 2) + (v & 3);
-          if (row < M) __builtin_nontemporal_store(acc[i][j][v], Cb + row * ldc + col);
-        }
-      }
-    }
-  }
+  store_c_tiles<FM, FN>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * kTileM + wm * FM * 32,
+                        (int64_t)tn * kTileN + wn * FN * 32);
 }
 
 bool fp4_path_supported(int64_t M, int64_t N, int64_t K) {

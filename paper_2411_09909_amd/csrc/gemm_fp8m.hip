@@ -27,7 +27,6 @@ namespace amx {
 
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kMergeK = 256;  // K padding of the merged panels (4 stages of 64)
 
@@ -246,23 +245,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp8m_kernel(const uint8_t* 
 #undef AMX_LOAD_ANCHORS
 #undef AMX_ISSUE_LOAD
 
-  // C tile: accumulator register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 block
-  float* Cb = C + b * M * ldc;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int64_t col = (int64_t)tn * Cfg::kTileN + (wn * FN + j) * 32 + (lane & 31);
-      const int64_t row0 = (int64_t)tm * Cfg::kTileM + (wm * FM + i) * 32 + 4 * (lane >> 5);
-      if (col < N) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int64_t row = row0 + 8 * (v >> 2) + (v & 3);
-          if (row < M) __builtin_nontemporal_store(acc[i][j][v], Cb + row * ldc + col);
-        }
-      }
-    }
-  }
+  store_c_tiles<FM, FN>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * Cfg::kTileM + wm * FM * 32,
+                        (int64_t)tn * Cfg::kTileN + wn * FN * 32);
 }
 
 hipError_t launch_gemm_fp8m_path(int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
