@@ -33,6 +33,7 @@ FORMATS = {
     "mxfp4_e5m2": (2, False, "bf16", PEAK_BF16_TFLOPS),    # the paper's "MXFP4" rows: FP8-E5M2 symmetric scale
     "mxfp4_e8m0": (0, False, "fp4", PEAK_FP4_TFLOPS),      # OCP MXFP4 (power-of-two scale, exponent floored)
     "amxfp4_e8m0": (0, True, "fp8", PEAK_FP8_TFLOPS),      # asymmetric power-of-two scales merged into E5M2 elements
+    "amxfp4_e4m3": (3, True, "bf16", PEAK_BF16_TFLOPS),    # the 4-exponent-bit FP8 scale of the paper's Sec. 4.2
 }
 
 
@@ -88,6 +89,8 @@ def main():
     ap.add_argument("--workload", default=WORKLOAD)
     ap.add_argument("--format", default="amxfp4_e5m2", choices=sorted(FORMATS),
                     help="operand format of the timed step (default: the paper's AMXFP4)")
+    ap.add_argument("--group-size", type=int, default=32, choices=[16, 32, 64, 128],
+                    help="elements per scale group (the headline metric is group 32; the others run on the BF16 MFMA)")
     ap.add_argument("--e5m2-kernel", default="panel", choices=["panel", "hybrid", "fused"],
                     help="which of the library's kernels for FP8-E5M2 scales runs the timed GEMM (default: panel)")
     ap.add_argument("--variants", action="store_true",
@@ -123,11 +126,14 @@ def main():
         """Times `steps` steps (cast X + GEMM against pre-cast W) in the given format; returns a dict of timings.
         e5m2_kernel: which of the library's three kernels for FP8-E5M2 scales multiplies (ignored by other formats)."""
         kind, asym, mfma, peak = FORMATS[name]
+        gs = args.group_size
+        if gs != 32:
+            mfma, peak, e5m2_kernel = "bf16", PEAK_BF16_TFLOPS, "panel"
         if kind == 2 and e5m2_kernel != "panel":
             mfma = "f16"
         binding.select_e5m2_kernel(e5m2_kernel)
-        fmt = binding.make_format(kind, asym)
-        nsc = (M, K // 32, 2) if asym else (M, K // 32)
+        fmt = binding.make_format(kind, asym, gs)
+        nsc = (M, K // gs, 2) if asym else (M, K // gs)
         xc = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
         xs = torch.empty(nsc, dtype=torch.uint8, device=dev)
         need = binding.gemm_workspace_bytes(fmt, M, N, K)
@@ -170,20 +176,20 @@ def main():
     ms_per_step = r["t_step"] * 1e3
     value = flops / r["t_step"] / 1e12
     achieved = flops / (r["kern_ms"] * 1e-3) / 1e12
-    cast_bytes = M * K * 2 + M * K // 2 + M * (K // 32) * (2 if r["asym"] else 1)
+    cast_bytes = M * K * 2 + M * K // 2 + M * (K // args.group_size) * (2 if r["asym"] else 1)
     kernel_name = "gemm_fp4_kernel" if r["mfma"] == "fp4" else "gemm_fp8m_kernel" if r["mfma"] == "fp8" else {"panel": "gemm_bf16_kernel", "hybrid":
-                  "gemm_e5m2_hybrid_kernel", "fused": "gemm_e5m2_kernel"}[args.e5m2_kernel]
+                  "gemm_e5m2_hybrid_kernel", "fused": "gemm_e5m2_kernel"}[args.e5m2_kernel if args.group_size == 32 else "panel"]
     out = {
         "metric": "AMXFP4 cast+GEMM TFLOPS at 4096x8192x28672", "value": round(value, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": r["mfma"], "data": "synthetic",
-        "config": {"workload": args.workload, "M": M, "N": N, "K": K, "format": args.format, "group_size": 32,
-                   "e5m2_kernel": args.e5m2_kernel if FORMATS[args.format][0] == 2 else None,
+        "config": {"workload": args.workload, "M": M, "N": N, "K": K, "format": args.format, "group_size": args.group_size,
+                   "e5m2_kernel": args.e5m2_kernel if FORMATS[args.format][0] == 2 and args.group_size == 32 else None,
                    "step": "amxfp4_quantize(X) + amxfp4_gemm(Xq, Wq), W pre-cast"},
         "roofline": {"bound": "mfma", "kernel": kernel_name, "achieved": round(achieved, 2),
                      "peak": r["peak"], "unit": "TFLOP/s", "frac": round(achieved / r["peak"], 4),
                      "traffic": MEASURED_TRAFFIC_BYTES if args.format == "amxfp4_e5m2" and args.workload == WORKLOAD
-                     and args.e5m2_kernel == "panel" else None, "kernel_ms": round(r["kern_ms"], 4)},
+                     and args.e5m2_kernel == "panel" and args.group_size == 32 else None, "kernel_ms": round(r["kern_ms"], 4)},
         "frac_of_fp4_mfma_peak": round(value / PEAK_FP4_TFLOPS, 4),
         "breakdown_ms": {"cast_x": round(r["t_cast_x"] * 1e3, 4),
                          "gemm_call": round(ms_per_step - r["t_cast_x"] * 1e3, 4),

@@ -4,12 +4,13 @@
  *
  * Formats (paper Sec. 2.1, Sec. 4.2 Eq. 1, Sec. 4.3, Appendix B Algorithm 1 and the table of MX-compliant formats):
  *   element   FP4 E2M1: 1 sign, 2 exponent (bias 1), 1 mantissa bit; magnitudes {0, .5, 1, 1.5, 2, 3, 4, 6}.
- *   group     `group_size` consecutive elements along the contraction axis K share the scale(s) (32 in MX).
+ *   group     `group_size` consecutive elements along the contraction axis K share the scale(s): 32 in MX and in
+ *             the paper's format; 16, 64 and 128 are the other points of its group-size study (Sec. 5.3, Table 5).
  *   MXFP4     one scale S per group;            x_hat = (-1)^s * elem * S
  *   AMXFP4    two scales (S_p, S_n) per group;  x_hat = (-1)^s * elem * (s == 0 ? S_p : S_n)         (Eq. 1)
  *   scale     8 bits: E8M0 power of two (Algorithm 1, exponent floored), or FP8 E5M2 (Sec. 4.2 "FP8";
  *             this is the format the paper calls AMXFP4 when asymmetric and "MXFP4" in its result tables when
- *             symmetric).
+ *             symmetric), or FP8 E4M3 (Sec. 4.2: the FP8 scale with one more mantissa bit and less range).
  *   product   every elementwise product in a dot product carries the scale pair picked by the signs of its
  *             two factors (Sec. 4.3); accumulation is FP32 on the GPU.
  *
@@ -18,6 +19,7 @@
  *   symmetric formats use amax = max(amax_p, amax_n) for both classes.
  *   E5M2      S_c = round-to-nearest-even onto the non-negative E5M2 values of the real quotient amax_c / 6,
  *             saturating at 57344, subnormals kept;
+ *   E4M3      the same onto the non-negative E4M3 values (OCP FP8: bias 7, largest finite value 448);
  *   E8M0      S_c = 2^(floor(log2 amax_c) - 2)  (S_c byte 0 when amax_c == 0);
  *   element   magnitude = round-to-nearest (ties to the even code) of min(|x| / S_c, 6) onto the E2M1 grid,
  *             0 when S_c == 0; sign bit copied from the input's IEEE sign bit.
@@ -26,7 +28,8 @@
  *   codes     row-major [rows][K/2] bytes; byte b holds element 2b in bits 3:0 and element 2b+1 in bits 7:4;
  *             nibble = s e1 e0 m.
  *   scales    asymmetric: row-major [rows][K/group_size][2] bytes = (S_p, S_n); symmetric: [rows][K/group_size].
- *             E5M2 byte = 0eeeeemm, bias 15, subnormals m * 2^-16.  E8M0 byte = exponent + 127.
+ *             E5M2 byte = 0eeeeemm, bias 15, subnormals m * 2^-16.  E4M3 byte = 0eeeemmm, bias 7, subnormals
+ *             m * 2^-9.  E8M0 byte = exponent + 127.
  *
  * Conventions for every entry point below:
  *   - all data pointers are DEVICE pointers owned by the caller unless stated otherwise; the library never
@@ -50,7 +53,7 @@ extern "C" {
 typedef enum {
   AMX_OK = 0,
   AMX_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, K not a multiple of the group, bad enum, misalignment */
-  AMX_ERR_UNSUPPORTED = -2, /* a legal format this GPU library does not implement (group_size != 32, E4M3 scale, ...) */
+  AMX_ERR_UNSUPPORTED = -2, /* a legal format this GPU library does not implement (group_size not 16, 32, 64 or 128) */
   AMX_ERR_WORKSPACE = -3,   /* workspace missing or smaller than amxfp4_gemm_workspace_bytes() */
   AMX_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed */
 } amx_status_t;
@@ -63,11 +66,11 @@ typedef enum {
   AMX_SCALE_E8M0_FLOOR = 0, /* OCP MX power-of-two scale, exponent floored (Appendix B, Algorithm 1) */
   AMX_SCALE_E8M0_ROUND = 1, /* power-of-two scale with the exponent rounded instead of floored (Appendix B, "Floor vs. Round") */
   AMX_SCALE_FP8_E5M2 = 2,   /* FP8 scale with a 5-bit exponent, the paper's choice (Sec. 4.2 "FP8") */
-  AMX_SCALE_FP8_E4M3 = 3    /* FP8 scale with a 4-bit exponent (Sec. 4.2 ablation); not implemented on the GPU */
+  AMX_SCALE_FP8_E4M3 = 3    /* FP8 scale with a 4-bit exponent and 3 mantissa bits (Sec. 4.2; the group scale of NVFP4 in Sec. 5.3) */
 } amx_scale_t;
 
 typedef struct {
-  int32_t group_size; /* elements per group along K (Sec. 2.1: 32). The GPU library implements 32 only. */
+  int32_t group_size; /* elements per group along K: 16, 32 (Sec. 2.1), 64 or 128; must divide K */
   int32_t elem;       /* amx_elem_t */
   int32_t scale;      /* amx_scale_t */
   int32_t asymmetric; /* 1 = AMXFP4: sign-dependent scale pair (Eq. 1); 0 = MXFP4: one scale per group */
@@ -89,7 +92,7 @@ size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N
  *               k_stride == 1 is the contiguous case (16-byte aligned base, row_stride % 8 == 0);
  *               row_stride == 1 with k_stride >= rows quantizes along a strided axis (groups run down a column,
  *               e.g. V in softmax(P).V, grouped along the key sequence).
- *   rows, K     operand shape; K % group_size == 0.
+ *   rows, K     operand shape; K % group_size == 0 and K % 32 == 0.
  *   codes       device out, amxfp4_codes_bytes() bytes, 16-byte aligned.
  *   scales      device out, amxfp4_scales_bytes() bytes, 4-byte aligned.
  */
@@ -111,6 +114,8 @@ int amxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8
  *   B_codes/B_scales   [batch][N][K] operand, K contiguous (C = A . B^T).
  *   C                  device out, [batch][M][ldc] floats, ldc >= N; columns >= N are not touched.
  *   batch              number of independent back-to-back problems (attention heads), >= 1.
+ *   Groups of 32 with power-of-two scales run on the block-scaled FP4 / FP8 matrix instructions; FP8 scales and the
+ *   other group sizes are multiplied as exact BF16 operands (element * scale has at most 6 significant bits).
  *   workspace          device scratch of at least amxfp4_gemm_workspace_bytes() bytes, 256-byte aligned;
  *                      contents are undefined afterwards. May be NULL when the required size is 0.
  */
@@ -140,7 +145,7 @@ int amxfp4_profile_next_gemm(void* start_event, void* stop_event);
 
 /*
  * Tuning aid (not part of the method): the GEMM for FP8-E5M2 scales (Sec. 4.2) exists in three kernels that compute
- * the same product and differ only in where the operands are dequantized:
+ * the same product and differ only in where the operands are dequantized (groups of 32; other sizes always use 0):
  *   0  both operands expanded to BF16 panels in the workspace, BF16 MFMA over them (default; any K);
  *   1  A expanded to an FP16 panel, B dequantized inside the FP16 MFMA kernel (K a multiple of 128);
  *   2  both operands dequantized inside the kernel, no workspace (K a multiple of 128).
@@ -151,7 +156,8 @@ int amxfp4_profile_next_gemm(void* start_event, void* stop_event);
 int amxfp4_select_e5m2_kernel(int32_t which);
 
 /*
- * Tuning aid: the GEMM for ASYMMETRIC power-of-two scales (Sec. 4.2, "PoT") exists in two kernels:
+ * Tuning aid: the GEMM for ASYMMETRIC power-of-two scales (Sec. 4.2, "PoT") of 32-element groups exists in two
+ * kernels:
  *   0  each group merged into E5M2 elements elem * 2^(s_class - anchor) with one anchor scale max(s_p, s_n), one
  *      block-scaled FP8 MFMA per block (default; any K; needs the workspace). Exact unless the two scales of a group
  *      differ by more than 2^13: then the small class is flushed to zero (below 1e-4 of that group's magnitude);

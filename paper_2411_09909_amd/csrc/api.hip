@@ -31,15 +31,18 @@ int check_format(const amx_format_t* f) {
     return fail(AMX_ERR_INVALID_ARG, "unknown scale format %d", f->scale);
   if (f->asymmetric != 0 && f->asymmetric != 1) return fail(AMX_ERR_INVALID_ARG, "asymmetric must be 0 or 1");
   if (f->group_size == 0 || f->group_size < -1) return fail(AMX_ERR_INVALID_ARG, "bad group_size %d", f->group_size);
-  if (f->group_size != 32) return fail(AMX_ERR_UNSUPPORTED, "the GPU library implements group_size 32 only");
-  if (f->scale == AMX_SCALE_FP8_E4M3) return fail(AMX_ERR_UNSUPPORTED, "E4M3 scales are not implemented on the GPU");
+  if (f->group_size != 16 && f->group_size != 32 && f->group_size != 64 && f->group_size != 128)
+    return fail(AMX_ERR_UNSUPPORTED, "the GPU library implements group sizes 16, 32, 64 and 128 (got %d)",
+                f->group_size);
   return AMX_OK;
 }
 
-int check_shape(int64_t rows, int64_t K) {
+int check_shape(const amx_format_t& f, int64_t rows, int64_t K) {
   if (rows <= 0 || K <= 0) return fail(AMX_ERR_INVALID_ARG, "rows and K must be positive (got %lld, %lld)",
                                        (long long)rows, (long long)K);
-  if (K % 32 != 0) return fail(AMX_ERR_INVALID_ARG, "K = %lld is not a multiple of the group size 32", (long long)K);
+  if (K % f.group_size != 0 || K % 32 != 0)
+    return fail(AMX_ERR_INVALID_ARG, "K = %lld is not a multiple of the group size %d and of 32", (long long)K,
+                f.group_size);
   return AMX_OK;
 }
 
@@ -62,7 +65,7 @@ namespace {
 int quantize_impl(amx_format_t f, const void* x, int64_t rows, int64_t K, int64_t row_stride, int64_t k_stride,
                   uint8_t* codes, uint8_t* scales, void* stream) {
   if (int rc = check_format(&f)) return rc;
-  if (int rc = check_shape(rows, K)) return rc;
+  if (int rc = check_shape(f, rows, K)) return rc;
   if (!x || !codes || !scales) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
   if (!aligned(codes, 16) || !aligned(scales, 4)) return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales 4-byte alignment");
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
@@ -70,12 +73,12 @@ int quantize_impl(amx_format_t f, const void* x, int64_t rows, int64_t K, int64_
   if (k_stride == 1) {
     if (row_stride < K || row_stride % 8 != 0 || !aligned(x, 16))
       return fail(AMX_ERR_INVALID_ARG, "contiguous cast needs row_stride >= K, row_stride %% 8 == 0 and a 16-byte aligned base");
-    hipError_t e = amx::launch_quantize_contig(f.scale, f.asymmetric != 0, xb, rows, K, row_stride, codes, scales, s);
+    hipError_t e = amx::launch_quantize_contig(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, row_stride, codes, scales, s);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "quantize launch");
   }
   if (row_stride == 1 && k_stride >= rows) {
     if (!aligned(x, 2)) return fail(AMX_ERR_INVALID_ARG, "x must be 2-byte aligned");
-    hipError_t e = amx::launch_quantize_strided(f.scale, f.asymmetric != 0, xb, rows, K, k_stride, codes, scales, s);
+    hipError_t e = amx::launch_quantize_strided(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, k_stride, codes, scales, s);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "strided quantize launch");
   }
   return fail(AMX_ERR_INVALID_ARG, "unsupported strides: need k_stride == 1, or row_stride == 1 with k_stride >= rows");
@@ -84,20 +87,20 @@ int quantize_impl(amx_format_t f, const void* x, int64_t rows, int64_t K, int64_
 int dequantize_impl(amx_format_t f, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K, void* out,
                     int32_t out_dtype, void* stream) {
   if (int rc = check_format(&f)) return rc;
-  if (int rc = check_shape(rows, K)) return rc;
+  if (int rc = check_shape(f, rows, K)) return rc;
   if (!codes || !scales || !out) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
   if (out_dtype != 0 && out_dtype != 1) return fail(AMX_ERR_INVALID_ARG, "out_dtype must be 0 (f32) or 1 (bf16)");
   if (!aligned(codes, 4) || !aligned(scales, 2) || !aligned(out, 16))
     return fail(AMX_ERR_INVALID_ARG, "misaligned pointer");
-  hipError_t e = amx::launch_dequantize(f.scale, f.asymmetric != 0, codes, scales, rows, K, out, out_dtype,
+  hipError_t e = amx::launch_dequantize(f.scale, f.asymmetric != 0, f.group_size, codes, scales, rows, K, out, out_dtype,
                                         reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? AMX_OK : hip_fail(e, "dequantize launch");
 }
 
-// Power-of-two scales go to the block-scaled FP4 matrix instruction (codes and scales consumed as they are); FP8
-// scales, and shapes that path does not take, go through exact BF16 expansion.
+// Power-of-two scales of 32-element groups go to the block-scaled matrix instructions (whose blocks are 32 long); FP8
+// scales, other group sizes, and shapes those paths do not take, go through exact BF16 expansion.
 bool uses_fp4_mfma(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  return (f.scale == AMX_SCALE_E8M0_FLOOR || f.scale == AMX_SCALE_E8M0_ROUND) && amx::fp4_path_supported(M, N, K);
+  return f.group_size == 32 && (f.scale == AMX_SCALE_E8M0_FLOOR || f.scale == AMX_SCALE_E8M0_ROUND) && amx::fp4_path_supported(M, N, K);
 }
 
 // FP8-E5M2 scales have three kernels (amxfp4_select_e5m2_kernel in the header); shapes one does not take use the
@@ -113,7 +116,7 @@ std::atomic<int>& e5m2_choice() {
   return choice;
 }
 E5m2Path e5m2_path(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  if (f.scale != AMX_SCALE_FP8_E5M2) return kPathPanel;
+  if (f.scale != AMX_SCALE_FP8_E5M2 || f.group_size != 32) return kPathPanel;
   const int want = e5m2_choice().load(std::memory_order_relaxed);
   if (want == kPathFused && amx::e5m2_fused_supported(M, N, K)) return kPathFused;
   if (want == kPathHybrid && amx::e5m2_hybrid_supported(M, N, K)) return kPathHybrid;
@@ -131,7 +134,7 @@ std::atomic<int>& pot_choice() {
   return choice;
 }
 bool uses_merged_pot(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  if (!f.asymmetric || (f.scale != AMX_SCALE_E8M0_FLOOR && f.scale != AMX_SCALE_E8M0_ROUND)) return false;
+  if (!f.asymmetric || f.group_size != 32 || (f.scale != AMX_SCALE_E8M0_FLOOR && f.scale != AMX_SCALE_E8M0_ROUND)) return false;
   return pot_choice().load(std::memory_order_relaxed) == 0 || !amx::fp4_path_supported(M, N, K);
 }
 
@@ -139,7 +142,7 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
               const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch, void* workspace,
               size_t workspace_bytes, void* stream) {
   if (int rc = check_format(&f)) return rc;
-  if (int rc = check_shape(M, K)) return rc;
+  if (int rc = check_shape(f, M, K)) return rc;
   if (N <= 0 || batch <= 0) return fail(AMX_ERR_INVALID_ARG, "N and batch must be positive");
   if (ldc < N) return fail(AMX_ERR_INVALID_ARG, "ldc < N");
   if (!A_codes || !A_scales || !B_codes || !B_scales || !C) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
@@ -175,7 +178,7 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
                                                 ldc, batch, workspace, reinterpret_cast<hipStream_t>(stream), timer);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
   }
-  hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales,
+  hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, f.group_size, M, N, K, A_codes, A_scales, B_codes, B_scales,
                                             C, ldc, batch, workspace, reinterpret_cast<hipStream_t>(stream), timer);
   return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
 }

@@ -10,7 +10,8 @@ namespace amx {
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 
-// Value of a scale byte as an exact float. E5M2 is the upper byte of an IEEE half (subnormals included);
+// Value of a scale byte as an exact float. E5M2 is the upper byte of an IEEE half (subnormals included); E4M3 has
+// exponent bias 7 and subnormals m * 2^-9 (the sign bit of either FP8 byte is never set by the cast and is ignored);
 // E8M0 is a bare exponent with bias 127 (byte 0 = 2^-127, an FP32 subnormal).
 template <int SCALE_KIND>
 __device__ __forceinline__ float scale_value(uint32_t byte) {
@@ -19,6 +20,10 @@ __device__ __forceinline__ float scale_value(uint32_t byte) {
     const uint32_t e = (byte >> 2) & 31u, m = byte & 3u;
     if (e == 0) return (float)m * 1.52587890625e-05f;  // m * 2^-16
     return u2f(((e + 112u) << 23) | (m << 21));
+  } else if constexpr (SCALE_KIND == kScaleE4M3) {
+    const uint32_t e = (byte >> 3) & 15u, m = byte & 7u;
+    if (e == 0) return (float)m * 0.001953125f;  // m * 2^-9
+    return u2f(((e + 120u) << 23) | (m << 20));
   } else {
     return byte == 0 ? u2f(0x00400000u) : u2f(byte << 23);  // 2^(byte-127)
   }

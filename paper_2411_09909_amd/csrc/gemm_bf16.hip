@@ -2,7 +2,9 @@
 // sign-asymmetric formats (Eq. 1, Sec. 4.3).
 //
 // A dequantized element is elem * S_class with elem in {0,.5,1,1.5,2,3,4,6} and S = (1 + m/4) * 2^e: up to 5
-// significant bits (3 * 7 = 21), which FP8/FP6/FP4 MFMA operands cannot hold but BF16 holds exactly. The GEMM is
+// significant bits (3 * 7 = 21; 6 bits with the 3 mantissa bits of an E4M3 scale, 3 * 15 = 45), which FP8/FP6/FP4
+// MFMA operands cannot hold but BF16 holds exactly. Groups of 16, 64 or 128 elements, which do not match the 32-long
+// blocks of the block-scaled instructions, also come here whatever their scale format. The GEMM is
 // therefore run on the BF16 MFMA (v_mfma_f32_32x32x16_bf16) with exact operands and FP32 accumulation:
 //
 //   1. expand kernel: codes + scale pair -> BF16, written into "fragment-major" panels in the workspace:
@@ -35,30 +37,43 @@ size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch)
 template <int SCALE_KIND, bool ASYM, bool F16>
 __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__ codes,
                                                      const uint8_t* __restrict__ scales, int64_t R, int64_t K,
-                                                     int64_t Rp, int64_t Kp, uint16_t* __restrict__ panel) {
+                                                     int64_t Rp, int64_t Kp, int gs_log2,
+                                                     uint16_t* __restrict__ panel) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t rb = blockIdx.y;
   const int64_t slice = (int64_t)blockIdx.x * 4 + wave;  // 64-wide K slice
   if (slice * 64 >= Kp) return;
   const int64_t r = rb * 32 + (lane & 31);
-  const int64_t g = slice * 2 + (lane >> 5);
-  const int64_t G = K >> 5;
+  const int64_t g = slice * 2 + (lane >> 5);  // the lane's block of 32 elements
   const int64_t b = blockIdx.z;
   uint32_t w[4] = {0, 0, 0, 0};
-  float s_pos = 0.f, s_neg = 0.f;
-  if (r < R && g < G) {
+  // scales of the first and of the second 16 elements of the block (they differ only for groups of 16)
+  float s_pos[2] = {0.f, 0.f}, s_neg[2] = {0.f, 0.f};
+  if (r < R && g < (K >> 5)) {
     const uint4 c = *reinterpret_cast<const uint4*>(codes + (b * R + r) * (K >> 1) + g * 16);
     w[0] = c.x, w[1] = c.y, w[2] = c.z, w[3] = c.w;
-    if constexpr (ASYM) {
-      const uint32_t sb = *reinterpret_cast<const uint16_t*>(scales + ((b * R + r) * G + g) * 2);
-      s_pos = scale_value<SCALE_KIND>(sb & 255u);
-      s_neg = scale_value<SCALE_KIND>(sb >> 8);
-    } else {
-      s_pos = s_neg = scale_value<SCALE_KIND>(scales[(b * R + r) * G + g]);
+    const int64_t row_groups = (b * R + r) * (K >> gs_log2);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      if (h == 1 && gs_log2 != 4) {
+        s_pos[1] = s_pos[0], s_neg[1] = s_neg[0];
+        break;
+      }
+      const int64_t gi = row_groups + ((g * 32 + h * 16) >> gs_log2);
+      if constexpr (ASYM) {
+        const uint32_t sb = *reinterpret_cast<const uint16_t*>(scales + gi * 2);
+        s_pos[h] = scale_value<SCALE_KIND>(sb & 255u);
+        s_neg[h] = scale_value<SCALE_KIND>(sb >> 8);
+      } else {
+        s_pos[h] = s_neg[h] = scale_value<SCALE_KIND>(scales[gi]);
+      }
     }
   }
-  s_pos *= F16 ? 0.0625f : 0.5f;
-  s_neg *= F16 ? -0.0625f : -0.5f;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    s_pos[h] *= F16 ? 0.0625f : 0.5f;
+    s_neg[h] *= F16 ? -0.0625f : -0.5f;
+  }
   uint16_t* dst = panel + ((b * (Rp >> 5) + rb) * (Kp >> 4) + slice * 4 + (lane >> 5) * 2) * 512;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {  // t-th run of 8 elements of the group: k block (t / 2), half (t % 2)
@@ -66,12 +81,12 @@ __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const uint32_t n0 = (w[t] >> (8 * j)) & 15u, n1 = (w[t] >> (8 * j + 4)) & 15u;
-      const float v0 = (float)e2m1_twice(n0 & 7u) * ((n0 & 8u) ? s_neg : s_pos);
-      const float v1 = (float)e2m1_twice(n1 & 7u) * ((n1 & 8u) ? s_neg : s_pos);
+      const float v0 = (float)e2m1_twice(n0 & 7u) * ((n0 & 8u) ? s_neg[t >> 1] : s_pos[t >> 1]);
+      const float v1 = (float)e2m1_twice(n1 & 7u) * ((n1 & 8u) ? s_neg[t >> 1] : s_pos[t >> 1]);
       if constexpr (F16)
         o[j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(v0, v1));  // exact, see above
       else
-        o[j] = (f2u(v0) >> 16) | (f2u(v1) & 0xFFFF0000u);  // truncation is exact: <= 5 significant bits
+        o[j] = (f2u(v0) >> 16) | (f2u(v1) & 0xFFFF0000u);  // truncation is exact: <= 6 significant bits
     }
     *reinterpret_cast<uint4*>(dst + (t >> 1) * 512 + ((t & 1) * 32 + (lane & 31)) * 8) =
         make_uint4(o[0], o[1], o[2], o[3]);
@@ -215,25 +230,29 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t*
 
 template <int SK, bool ASYM, bool F16 = false>
 static hipError_t launch_expand(const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K, int64_t Rp,
-                                int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s) {
+                                int64_t Kp, int gs_log2, int64_t batch, uint16_t* panel, hipStream_t s) {
   hipLaunchKernelGGL((expand_kernel<SK, ASYM, F16>), dim3((unsigned)((Kp + 255) / 256), (unsigned)(Rp / 32), (unsigned)batch),
-                     dim3(256), 0, s, codes, scales, R, K, Rp, Kp, panel);
+                     dim3(256), 0, s, codes, scales, R, K, Rp, Kp, gs_log2, panel);
   return hipGetLastError();
 }
 
-static hipError_t expand_dispatch(int scale_kind, bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R,
-                                  int64_t K, int64_t Rp, int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s) {
+static hipError_t expand_dispatch(int scale_kind, bool asym, int gs_log2, const uint8_t* codes, const uint8_t* scales,
+                                  int64_t R, int64_t K, int64_t Rp, int64_t Kp, int64_t batch, uint16_t* panel,
+                                  hipStream_t s) {
   if (scale_kind == kScaleE5M2)
-    return asym ? launch_expand<kScaleE5M2, true>(codes, scales, R, K, Rp, Kp, batch, panel, s)
-                : launch_expand<kScaleE5M2, false>(codes, scales, R, K, Rp, Kp, batch, panel, s);
-  return asym ? launch_expand<kScaleE8M0Floor, true>(codes, scales, R, K, Rp, Kp, batch, panel, s)
-              : launch_expand<kScaleE8M0Floor, false>(codes, scales, R, K, Rp, Kp, batch, panel, s);
+    return asym ? launch_expand<kScaleE5M2, true>(codes, scales, R, K, Rp, Kp, gs_log2, batch, panel, s)
+                : launch_expand<kScaleE5M2, false>(codes, scales, R, K, Rp, Kp, gs_log2, batch, panel, s);
+  if (scale_kind == kScaleE4M3)
+    return asym ? launch_expand<kScaleE4M3, true>(codes, scales, R, K, Rp, Kp, gs_log2, batch, panel, s)
+                : launch_expand<kScaleE4M3, false>(codes, scales, R, K, Rp, Kp, gs_log2, batch, panel, s);
+  return asym ? launch_expand<kScaleE8M0Floor, true>(codes, scales, R, K, Rp, Kp, gs_log2, batch, panel, s)
+              : launch_expand<kScaleE8M0Floor, false>(codes, scales, R, K, Rp, Kp, gs_log2, batch, panel, s);
 }
 
 hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K,
                                   int64_t Rp, int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s) {
-  return asym ? launch_expand<kScaleE5M2, true, true>(codes, scales, R, K, Rp, Kp, batch, panel, s)
-              : launch_expand<kScaleE5M2, false, true>(codes, scales, R, K, Rp, Kp, batch, panel, s);
+  return asym ? launch_expand<kScaleE5M2, true, true>(codes, scales, R, K, Rp, Kp, 5, batch, panel, s)
+              : launch_expand<kScaleE5M2, false, true>(codes, scales, R, K, Rp, Kp, 5, batch, panel, s);
 }
 
 template <int WM, int WN, int FM, int FN>
@@ -248,16 +267,18 @@ static hipError_t launch_tiles(const uint16_t* Ap, const uint16_t* Bp, float* C,
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
-                                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
-                                 int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
-                                 const KernelTimer& timer) {
+hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, int64_t M, int64_t N, int64_t K,
+                                 const uint8_t* A_codes, const uint8_t* A_scales, const uint8_t* B_codes,
+                                 const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch, void* workspace,
+                                 hipStream_t s, const KernelTimer& timer) {
+  const int gs_log2 = group_size == 16 ? 4 : group_size == 32 ? 5 : group_size == 64 ? 6 : group_size == 128 ? 7 : -1;
+  if (gs_log2 < 0 || K % group_size != 0 || K % 32 != 0) return hipErrorInvalidValue;
   const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows), Kp = round_up(K, kPanelK);
   uint16_t* Ap = reinterpret_cast<uint16_t*>(workspace);
   uint16_t* Bp = Ap + batch * Mp * Kp;
-  hipError_t e = expand_dispatch(scale_kind, asym, A_codes, A_scales, M, K, Mp, Kp, batch, Ap, s);
+  hipError_t e = expand_dispatch(scale_kind, asym, gs_log2, A_codes, A_scales, M, K, Mp, Kp, batch, Ap, s);
   if (e != hipSuccess) return e;
-  e = expand_dispatch(scale_kind, asym, B_codes, B_scales, N, K, Np, Kp, batch, Bp, s);
+  e = expand_dispatch(scale_kind, asym, gs_log2, B_codes, B_scales, N, K, Np, Kp, batch, Bp, s);
   if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
   // Tile shape: 256 x 256 unless one side of the problem is much smaller than that (skinny outputs such as P.V with

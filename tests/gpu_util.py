@@ -15,15 +15,15 @@ def to_dev_u8(a):
     return torch.from_numpy(np.ascontiguousarray(a, np.uint8)).cuda()
 
 
-def gpu_quantize(bits, scale, asym, k_axis=-1, baseline=False):
-    fmt = binding.make_format(scale, asym)
+def gpu_quantize(bits, scale, asym, k_axis=-1, baseline=False, group_size=32):
+    fmt = binding.make_format(scale, asym, group_size)
     c, s = binding.quantize(fmt, to_dev_bf16(bits), k_axis=k_axis, baseline=baseline)
     torch.cuda.synchronize()
     return c.cpu().numpy(), s.cpu().numpy()
 
 
-def gpu_gemm(ac, as_, bc, bs, scale, asym, baseline=False):
-    fmt = binding.make_format(scale, asym)
+def gpu_gemm(ac, as_, bc, bs, scale, asym, baseline=False, group_size=32):
+    fmt = binding.make_format(scale, asym, group_size)
     C = binding.gemm(fmt, to_dev_u8(ac), to_dev_u8(as_), to_dev_u8(bc), to_dev_u8(bs), baseline=baseline)
     torch.cuda.synchronize()
     return C.cpu().numpy()

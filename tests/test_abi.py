@@ -80,10 +80,13 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert _q(lib, ok, p, 4, 64, 64, 1, ctypes.c_void_p(0x1001), p) == -1   # misaligned codes
     assert _q(lib, ok, p, 4, 64, 3, 2, p, p) == -1           # unsupported stride combination
     assert b"stride" in lib.amxfp4_last_error()
-    for bad, code in [(binding.AmxFormat(16, 0, 2, 1), -2), (binding.AmxFormat(32, 0, 3, 1), -2),
+    for bad, code in [(binding.AmxFormat(8, 0, 2, 1), -2), (binding.AmxFormat(-1, 0, 3, 1), -2),
+                      (binding.AmxFormat(48, 0, 2, 1), -2), (binding.AmxFormat(-2, 0, 2, 1), -1),
                       (binding.AmxFormat(32, 1, 2, 1), -1), (binding.AmxFormat(32, 0, 7, 1), -1),
                       (binding.AmxFormat(0, 0, 2, 1), -1), (binding.AmxFormat(32, 0, 2, 5), -1)]:
         assert _q(lib, bad, p, 4, 64, 64, 1, p, p) == code
+    assert _q(lib, binding.AmxFormat(128, 0, 2, 1), p, 4, 64, 64, 1, p, p) == -1   # K smaller than one group of 128
+    assert _q(lib, binding.AmxFormat(16, 0, 2, 1), p, 4, 48, 48, 1, p, p) == -1    # whole groups of 16, but K % 32 != 0
     assert lib.amxfp4_quantize(None, p, 4, 64, 64, 1, p, p, None) == -1
     assert lib.amxfp4_dequantize(ctypes.byref(ok), p, p, 4, 64, p, 2, None) == -1      # bad out_dtype
     # GEMM: workspace too small / missing, ldc < N
