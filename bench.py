@@ -63,6 +63,58 @@ class HipEvents:
             self.hip.hipEventDestroy(b)
 
 
+def measured_peaks(binding, torch, xd, wd, dev, iterations=30000):
+    """What this machine sustains, beside the datasheet peaks: register-resident MFMA loops (no memory traffic) on
+    all-zero operands and on operand bits taken from the workload (quantized X and W of the bench: dequantized BF16
+    values, the same rounded to FP8-E5M2, and the packed FP4 codes), and a 1 GiB streaming copy."""
+    fmt = binding.make_format(binding.FP8_E5M2, True)
+    rows = 256 * 16 // (xd.shape[1] // 2) + 1   # enough rows for 256 lanes x 16 bytes of codes
+    xc, xs = binding.quantize(fmt, xd[:max(rows, 8)])
+    wc, ws = binding.quantize(fmt, wd[:max(rows, 8)])
+    xh = binding.dequantize(fmt, xc, xs, torch.bfloat16).flatten()
+    wh = binding.dequantize(fmt, wc, ws, torch.bfloat16).flatten()
+
+    def lanes(a_bytes, b_bytes, width):
+        buf = torch.zeros((256, 64), dtype=torch.uint8, device=dev)
+        buf[:, 0:width] = a_bytes[:256 * width].view(256, width)
+        buf[:, 32:32 + width] = b_bytes[:256 * width].view(256, width)
+        return buf
+
+    operands = {
+        "bf16": lanes(xh.view(torch.uint8), wh.view(torch.uint8), 16),
+        "fp8": lanes(xh.to(torch.float8_e5m2).view(torch.uint8), wh.to(torch.float8_e5m2).view(torch.uint8), 32),
+        "fp4": lanes(xc.flatten(), wc.flatten(), 16),
+    }
+    zeros = torch.zeros((256, 64), dtype=torch.uint8, device=dev)
+    sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+    res = {"unit": "TFLOP/s", "mfma_loop": {}}
+    for kind, datasheet in (("bf16", PEAK_BF16_TFLOPS), ("fp8", PEAK_FP8_TFLOPS), ("fp4", PEAK_FP4_TFLOPS)):
+        row = {"datasheet": datasheet}
+        for label, op in (("zero_operands", zeros), ("workload_operands", operands[kind])):
+            binding.peak_mfma(kind, op, 200, sink)  # module load, not timed
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            flops = binding.peak_mfma(kind, op, iterations, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            row[label] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+        res["mfma_loop"][kind] = row
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    binding.peak_copy(src, dst)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        binding.peak_copy(src, dst)
+    e1.record()
+    torch.cuda.synchronize()
+    res["copy_1GiB"] = {"GB_per_s_read_plus_write": round(5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1),
+                        "datasheet": 8000.0}
+    return res
+
+
 def cpu_baseline(x_bits, w_bits, K, sample_m=2048, sample_n=14336):
     """The oracle as it stands (oracle/amxfp4_ref.c: scalar C, FP64 accumulate, OpenMP over rows), timed on a slab of
     the same operands: quantize sample_m rows of X and sample_n rows of W, then the sample_m x sample_n x K GEMM."""
@@ -95,6 +147,8 @@ def main():
                     help="which of the library's kernels for FP8-E5M2 scales runs the timed GEMM (default: panel)")
     ap.add_argument("--variants", action="store_true",
                     help="also time the other formats (MXFP4 baselines, power-of-two scales) and list them")
+    ap.add_argument("--no-measured-peaks", action="store_true",
+                    help="skip the register-resident MFMA loops and the streaming copy reported as measured_peaks")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (the known-size reference that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -210,6 +264,8 @@ def main():
                                      "gemm_kernel_ms": round(v["kern_ms"], 4),
                                      "kernel_frac_of_mfma_peak": round(flops / (v["kern_ms"] * 1e-3) / 1e12 /
                                                                        v["peak"], 4)}
+    if not args.no_measured_peaks:
+        out["measured_peaks"] = measured_peaks(binding, torch, xd, wd, dev)
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)

@@ -55,6 +55,10 @@ def load():
     L.amxfp4_select_pot_kernel.argtypes = [ctypes.c_int32]
     L.amxfp4_select_pot_kernel.restype = ctypes.c_int
     f32, f64, i32 = ctypes.c_float, ctypes.c_double, ctypes.c_int32
+    L.amxfp4_peak_mfma.argtypes = [i32, vp, i32, vp, ctypes.POINTER(f64), vp]
+    L.amxfp4_peak_mfma.restype = ctypes.c_int
+    L.amxfp4_peak_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.amxfp4_peak_copy.restype = ctypes.c_int
     for name, args in (("amxfp4_rmsnorm", [vp, vp, i64, i64, f32, vp, vp]),
                        ("amxfp4_split_heads_rope", [vp, i64, i64, i64, i64, i64, i32, i64, f64, vp, vp]),
                        ("amxfp4_softmax_causal", [vp, i64, i64, i64, f32, vp, vp]),
@@ -118,6 +122,30 @@ POT_KERNELS = {"merged": 0, "split": 1}
 def select_pot_kernel(which):
     """Chooses between the two GEMM kernels for asymmetric power-of-two scales ("merged" | "split", or 0 | 1)."""
     _check(load().amxfp4_select_pot_kernel(POT_KERNELS.get(which, which)))
+
+
+PEAK_MFMA = {"bf16": 0, "fp8": 1, "fp4": 2}
+
+
+def peak_mfma(mfma, operand, iterations, sink):
+    """Launches the register-resident MFMA loop ("bf16" | "fp8" | "fp4") on the current stream; operand: 16384-byte
+    CUDA tensor, sink: float32 CUDA tensor of 512 * 256 elements. Returns the floating-point operations it performs."""
+    _need_cuda(operand, sink)
+    if operand.numel() * operand.element_size() < 16384 or sink.numel() < 512 * 256 or sink.dtype != torch.float32:
+        raise AmxError("peak_mfma: operand needs 16384 bytes, sink 512 * 256 float32")
+    flops = ctypes.c_double()
+    _check(load().amxfp4_peak_mfma(PEAK_MFMA[mfma], operand.data_ptr(), int(iterations), sink.data_ptr(),
+                                   ctypes.byref(flops), _stream()))
+    return flops.value
+
+
+def peak_copy(src, dst):
+    """Streaming copy src -> dst (CUDA tensors of equal byte size, a multiple of 16) on the current stream."""
+    _need_cuda(src, dst)
+    n = src.numel() * src.element_size()
+    if n != dst.numel() * dst.element_size() or not (src.is_contiguous() and dst.is_contiguous()):
+        raise AmxError("peak_copy: contiguous buffers of equal size needed")
+    _check(load().amxfp4_peak_copy(src.data_ptr(), dst.data_ptr(), n, _stream()))
 
 
 def _fn(fmt, name, baseline):

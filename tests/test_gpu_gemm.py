@@ -190,3 +190,22 @@ def test_merged_kernel_with_far_apart_sign_scales():
     finally:
         binding.select_pot_kernel("merged")
     assert G.rel_fro(Cs, Cr) <= 1e-6
+
+
+def test_measurement_aids_run_and_copy_is_a_copy():
+    """The peak probes are measurement aids; here only: they launch, finish, report their operation count, and the
+    streaming copy copies (ragged size: not a multiple of the grid)."""
+    import torch
+    from paper_2411_09909_amd import binding
+    op = torch.randint(0, 256, (16384,), dtype=torch.uint8, device="cuda")
+    sink = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+    for kind, k in (("bf16", 16), ("fp8", 64), ("fp4", 64)):
+        assert binding.peak_mfma(kind, op, 3, sink) == 2.0 * 32 * 32 * k * 16 * 3 * 4 * 512
+    torch.cuda.synchronize()
+    src = torch.randint(0, 256, (16 * 100003,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    binding.peak_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    with pytest.raises(binding.AmxError):
+        binding.peak_copy(src[:24], dst[:24])
