@@ -16,7 +16,10 @@
  *     nearest E5M2 value; power-of-two scales: 2^(floor(log2 amax) - 2) (Algorithm 1, emax_elem = 2), or with the
  *     exponent rounded (Appendix B "Floor vs. Round");
  *   - the product of two AMXFP4 numbers uses the scales selected by their two signs (Sec. 4.3); the GEMM is the
- *     plain sum over k of those products, accumulated in double, rounded once to float.
+ *     plain sum over k of those products, accumulated in double, rounded once to float;
+ *   - double scaling (Sec. 5.3: NVFP4 and its asymmetric variant ANVFP4 put a tensor-wise FP32 scale under a
+ *     group-wise FP8 E4M3 scale of 16-element groups): the *_scaled functions below. The paper names the scheme and
+ *     gives no arithmetic for it; the reading taken here is written at those functions       — parity unpinned
  *
  * Readings of points the paper leaves open (each is repeated in the repository's design notes):
  *   - ties in both roundings go to the even code / even mantissa (OCP MX default)               — parity unpinned
@@ -52,11 +55,11 @@ enum { SC_E8M0_FLOOR = 0, SC_E8M0_ROUND = 1, SC_E5M2 = 2, SC_E4M3 = 3 };
 /* E2M1 magnitudes by 3-bit code e1 e0 m: exponent bias 1, code 1 is the subnormal 0.5 (Sec. 2.1). */
 static const double kE2M1[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
 
-static double bf16_to_double(uint16_t b) {
+static float bf16_to_float(uint16_t b) {
   uint32_t u = (uint32_t)b << 16;
   float f;
   memcpy(&f, &u, 4);
-  return (double)f;
+  return f;
 }
 
 /* ---------------------------------------------------------------- scales ---------------------------------- */
@@ -145,10 +148,46 @@ static int check_format(const ref_format_t* f, int64_t K, int64_t* gs_out) {
   return 0;
 }
 
-int amxfp4_quantize_ref(const ref_format_t* fmt, const uint16_t* x_bf16, int64_t rows, int64_t K,
-                        int64_t row_stride, int64_t k_stride, uint8_t* codes, uint8_t* scales) {
+/*
+ * Tensor-wise scale of the double-scaling scheme (Sec. 5.3). Reading: the tensor scale maps the tensor's largest
+ * magnitude onto the largest value a group scale times an element can express, 448 * 6 = 2688 (448 = largest E4M3
+ * value, 6 = largest E2M1 value), so that the group scales use the top of the E4M3 range:
+ *   out[0] = S_t = float(amax_tensor) / 2688 in single precision, not below 2^-96 (so that 1 / S_t is finite);
+ *   out[1] = R_t = 1 / S_t in single precision, the factor the cast multiplies by.
+ * An all-zero tensor gives S_t = R_t = 1. x_hat = elem * S_group * S_t.
+ */
+int amxfp4_tensor_scale_ref(const uint16_t* x_bf16, int64_t rows, int64_t K, int64_t row_stride, int64_t k_stride,
+                            float* out) {
+  if (!x_bf16 || !out || rows <= 0 || K <= 0) return -1;
+  float amax = 0.0f;
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t k = 0; k < K; ++k) {
+      float v = fabsf(bf16_to_float(x_bf16[r * row_stride + k * k_stride]));
+      if (v > amax) amax = v;
+    }
+  if (amax == 0.0f) {
+    out[0] = out[1] = 1.0f;
+    return 0;
+  }
+  volatile float st = amax / 2688.0f; /* volatile: one rounding to single precision, no wider intermediate */
+  if (st < 0x1p-96f) st = 0x1p-96f;
+  volatile float rt = 1.0f / st;
+  out[0] = st;
+  out[1] = rt;
+  return 0;
+}
+
+/*
+ * Direct cast with a tensor-wise scale (Sec. 5.3 double scaling; tensor_rcp = 1 is the plain cast of Algorithm 1 /
+ * Eq. 1, for which the multiplication below is exact). Reading: every element is first multiplied by R_t in single
+ * precision, y = float(x * R_t) (one rounding), and the group-wise algorithm then runs on the y values exactly as
+ * it runs on BF16 values; the sign class is the sign bit of x.
+ */
+int amxfp4_quantize_scaled_ref(const ref_format_t* fmt, const uint16_t* x_bf16, int64_t rows, int64_t K,
+                               int64_t row_stride, int64_t k_stride, float tensor_rcp, uint8_t* codes,
+                               uint8_t* scales) {
   int64_t gs;
-  if (check_format(fmt, K, &gs) || !x_bf16 || !codes || !scales || rows <= 0) return -1;
+  if (check_format(fmt, K, &gs) || !x_bf16 || !codes || !scales || rows <= 0 || !(tensor_rcp > 0.0f)) return -1;
   const int64_t G = K / gs;
   const int ns = fmt->asymmetric ? 2 : 1;
   memset(codes, 0, (size_t)(rows * K / 2));
@@ -160,7 +199,8 @@ int amxfp4_quantize_ref(const ref_format_t* fmt, const uint16_t* x_bf16, int64_t
       double amax_p = 0.0, amax_n = 0.0;
       for (int64_t i = 0; i < gs; ++i) {
         uint16_t b = xg[i * k_stride];
-        double v = bf16_to_double(b);
+        volatile float y = bf16_to_float(b) * tensor_rcp; /* one rounding to single precision */
+        double v = (double)y;
         if (b & 0x8000) {
           if (-v > amax_n) amax_n = -v;
         } else {
@@ -182,7 +222,8 @@ int amxfp4_quantize_ref(const ref_format_t* fmt, const uint16_t* x_bf16, int64_t
       for (int64_t i = 0; i < gs; ++i) {
         uint16_t b = xg[i * k_stride];
         int neg = (b & 0x8000) != 0;
-        double a = fabs(bf16_to_double(b));
+        volatile float y = bf16_to_float(b) * tensor_rcp;
+        double a = fabs((double)y);
         uint8_t code = (uint8_t)((neg << 3) | amxfp4_elem_encode_ref(a, neg ? S_n : S_p));
         int64_t k = g * gs + i;
         codes[r * (K / 2) + k / 2] |= (uint8_t)(code << (4 * (k & 1)));
@@ -190,6 +231,11 @@ int amxfp4_quantize_ref(const ref_format_t* fmt, const uint16_t* x_bf16, int64_t
     }
   }
   return 0;
+}
+
+int amxfp4_quantize_ref(const ref_format_t* fmt, const uint16_t* x_bf16, int64_t rows, int64_t K,
+                        int64_t row_stride, int64_t k_stride, uint8_t* codes, uint8_t* scales) {
+  return amxfp4_quantize_scaled_ref(fmt, x_bf16, rows, K, row_stride, k_stride, 1.0f, codes, scales);
 }
 
 /* ---------------------------------------------------------------- dequantize ------------------------------ */
@@ -220,9 +266,11 @@ int amxfp4_dequantize_ref(const ref_format_t* fmt, const uint8_t* codes, const u
 /* ---------------------------------------------------------------- GEMM ------------------------------------ */
 
 /* C[b][i][j] = float( sum_k A_hat[b][i][k] * B_hat[b][j][k] ), sum in double in index order (Sec. 4.3). */
-int amxfp4_gemm_ref(const ref_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
-                    const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
-                    int64_t batch) {
+/* With tensor-wise scales (Sec. 5.3): x_hat = elem * S_group * S_t, so the sum is multiplied by the two tensor
+ * scales (in double) before the single rounding to float. */
+int amxfp4_gemm_scaled_ref(const ref_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                           const uint8_t* A_scales, float A_tensor_scale, const uint8_t* B_codes,
+                           const uint8_t* B_scales, float B_tensor_scale, float* C, int64_t ldc, int64_t batch) {
   int64_t gs;
   if (check_format(fmt, K, &gs) || !A_codes || !A_scales || !B_codes || !B_scales || !C || M <= 0 || N <= 0 ||
       ldc < N || batch <= 0)
@@ -246,13 +294,19 @@ int amxfp4_gemm_ref(const ref_format_t* fmt, int64_t M, int64_t N, int64_t K, co
         const double* a = Ah + i * K;
         const double* bb = Bh + j * K;
         for (int64_t k = 0; k < K; ++k) acc += a[k] * bb[k];
-        C[(b * M + i) * ldc + j] = (float)acc;
+        C[(b * M + i) * ldc + j] = (float)(acc * (double)A_tensor_scale * (double)B_tensor_scale);
       }
     }
   }
   free(Ah);
   free(Bh);
   return 0;
+}
+
+int amxfp4_gemm_ref(const ref_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                    const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
+                    int64_t batch) {
+  return amxfp4_gemm_scaled_ref(fmt, M, N, K, A_codes, A_scales, 1.0f, B_codes, B_scales, 1.0f, C, ldc, batch);
 }
 
 /* Number of threads the loops above use. */

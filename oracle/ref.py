@@ -47,6 +47,15 @@ def lib():
         L.amxfp4_gemm_ref.argtypes = [ctypes.POINTER(RefFormat), i64, i64, i64, u8p, u8p, u8p, u8p, ctypes.c_void_p,
                                       i64, i64]
         L.amxfp4_gemm_ref.restype = ctypes.c_int
+        f32 = ctypes.c_float
+        L.amxfp4_quantize_scaled_ref.argtypes = [ctypes.POINTER(RefFormat), ctypes.c_void_p, i64, i64, i64, i64, f32,
+                                                 u8p, u8p]
+        L.amxfp4_quantize_scaled_ref.restype = ctypes.c_int
+        L.amxfp4_gemm_scaled_ref.argtypes = [ctypes.POINTER(RefFormat), i64, i64, i64, u8p, u8p, f32, u8p, u8p, f32,
+                                             ctypes.c_void_p, i64, i64]
+        L.amxfp4_gemm_scaled_ref.restype = ctypes.c_int
+        L.amxfp4_tensor_scale_ref.argtypes = [ctypes.c_void_p, i64, i64, i64, i64, ctypes.c_void_p]
+        L.amxfp4_tensor_scale_ref.restype = ctypes.c_int
         L.amxfp4_scale_encode_ref.argtypes = [ctypes.c_int32, ctypes.c_double]
         L.amxfp4_scale_encode_ref.restype = ctypes.c_uint8
         L.amxfp4_scale_decode_ref.argtypes = [ctypes.c_int32, ctypes.c_uint8]
@@ -66,9 +75,21 @@ def _groups(K, group_size):
     return 1 if group_size == -1 else K // group_size
 
 
-def quantize(x_bf16, group_size=32, scale=FP8_E5M2, asymmetric=True, k_axis=-1):
+def tensor_scale(x_bf16):
+    """Tensor-wise scale pair (S_t, R_t = 1 / S_t) of the double-scaling scheme (Sec. 5.3), as numpy float32."""
+    assert x_bf16.dtype == np.uint16 and x_bf16.ndim == 2
+    out = np.zeros(2, np.float32)
+    rc = lib().amxfp4_tensor_scale_ref(x_bf16.ctypes.data, x_bf16.shape[0], x_bf16.shape[1], x_bf16.strides[0] // 2,
+                                       x_bf16.strides[1] // 2, out.ctypes.data)
+    if rc:
+        raise ValueError("amxfp4_tensor_scale_ref failed: %d" % rc)
+    return out[0], out[1]
+
+
+def quantize(x_bf16, group_size=32, scale=FP8_E5M2, asymmetric=True, k_axis=-1, tensor_rcp=1.0):
     """x_bf16: 2-D uint16 array of BF16 bit patterns, any strides. Groups run along `k_axis` (-1: along rows'
-    elements; 0: down the columns, i.e. the operand is x.T). Returns (codes [rows, K/2] u8, scales u8)."""
+    elements; 0: down the columns, i.e. the operand is x.T). tensor_rcp: the factor R_t of a tensor-wise scale
+    (Sec. 5.3), 1 for none. Returns (codes [rows, K/2] u8, scales u8)."""
     assert x_bf16.dtype == np.uint16 and x_bf16.ndim == 2
     xv = x_bf16 if k_axis in (-1, 1) else x_bf16.T
     rows, K = xv.shape
@@ -78,15 +99,16 @@ def quantize(x_bf16, group_size=32, scale=FP8_E5M2, asymmetric=True, k_axis=-1):
     codes = np.zeros((rows, K // 2), np.uint8)
     scales = np.zeros((rows, G, ns) if asymmetric else (rows, G), np.uint8)
     f = _fmt(group_size, scale, asymmetric)
-    rc = lib().amxfp4_quantize_ref(ctypes.byref(f), xv.ctypes.data, rows, K, rs, ks, codes.ctypes.data,
-                                   scales.ctypes.data)
+    rc = lib().amxfp4_quantize_scaled_ref(ctypes.byref(f), xv.ctypes.data, rows, K, rs, ks,
+                                          ctypes.c_float(float(np.float32(tensor_rcp))), codes.ctypes.data,
+                                          scales.ctypes.data)
     if rc:
-        raise ValueError("amxfp4_quantize_ref failed: %d" % rc)
+        raise ValueError("amxfp4_quantize_scaled_ref failed: %d" % rc)
     return codes, scales
 
 
-def dequantize(codes, scales, group_size=32, scale=FP8_E5M2, asymmetric=True):
-    """Returns float64 [rows, K]."""
+def dequantize(codes, scales, group_size=32, scale=FP8_E5M2, asymmetric=True, tensor_scale=1.0):
+    """Returns float64 [rows, K] (times the tensor-wise scale S_t of Sec. 5.3, exact in float64)."""
     codes = np.ascontiguousarray(codes, np.uint8)
     scales = np.ascontiguousarray(scales, np.uint8)
     rows, K = codes.shape[0], codes.shape[1] * 2
@@ -95,11 +117,13 @@ def dequantize(codes, scales, group_size=32, scale=FP8_E5M2, asymmetric=True):
     rc = lib().amxfp4_dequantize_ref(ctypes.byref(f), codes.ctypes.data, scales.ctypes.data, rows, K, out.ctypes.data)
     if rc:
         raise ValueError("amxfp4_dequantize_ref failed: %d" % rc)
-    return out
+    return out if tensor_scale == 1.0 else out * np.float64(np.float32(tensor_scale))
 
 
-def gemm(a_codes, a_scales, b_codes, b_scales, group_size=32, scale=FP8_E5M2, asymmetric=True):
-    """a_codes [M, K/2] or [batch, M, K/2]; b_codes [N, K/2] or [batch, N, K/2]. Returns float32 C = A_hat.B_hat^T."""
+def gemm(a_codes, a_scales, b_codes, b_scales, group_size=32, scale=FP8_E5M2, asymmetric=True, a_tensor_scale=1.0,
+         b_tensor_scale=1.0):
+    """a_codes [M, K/2] or [batch, M, K/2]; b_codes [N, K/2] or [batch, N, K/2]. Returns float32 C = A_hat.B_hat^T
+    (operands times their tensor-wise scales S_t of Sec. 5.3, 1 for none)."""
     a_codes = np.ascontiguousarray(a_codes, np.uint8)
     b_codes = np.ascontiguousarray(b_codes, np.uint8)
     a_scales = np.ascontiguousarray(a_scales, np.uint8)
@@ -110,10 +134,12 @@ def gemm(a_codes, a_scales, b_codes, b_scales, group_size=32, scale=FP8_E5M2, as
     N = b_codes.shape[-2]
     C = np.empty((batch, M, N), np.float32)
     f = _fmt(group_size, scale, asymmetric)
-    rc = lib().amxfp4_gemm_ref(ctypes.byref(f), M, N, K, a_codes.ctypes.data, a_scales.ctypes.data,
-                               b_codes.ctypes.data, b_scales.ctypes.data, C.ctypes.data, N, batch)
+    rc = lib().amxfp4_gemm_scaled_ref(ctypes.byref(f), M, N, K, a_codes.ctypes.data, a_scales.ctypes.data,
+                                      ctypes.c_float(float(np.float32(a_tensor_scale))), b_codes.ctypes.data,
+                                      b_scales.ctypes.data, ctypes.c_float(float(np.float32(b_tensor_scale))),
+                                      C.ctypes.data, N, batch)
     if rc:
-        raise ValueError("amxfp4_gemm_ref failed: %d" % rc)
+        raise ValueError("amxfp4_gemm_scaled_ref failed: %d" % rc)
     return C if batched else C[0]
 
 

@@ -95,3 +95,24 @@ def dequant_fraction(codes, scales, kind, asymmetric, group_size):
             row.append(-v if neg else v)
         out.append(row)
     return out
+
+
+def f32_round_fraction(q):
+    """The IEEE single-precision number nearest to the rational q (ties to even), as a Fraction; subnormals kept,
+    no overflow handling (callers stay in range)."""
+    if q == 0:
+        return Fraction(0)
+    s, a = (-1 if q < 0 else 1), abs(q)
+    e = 0
+    while Fraction(2) ** (e + 1) <= a:
+        e += 1
+    while Fraction(2) ** e > a:
+        e -= 1
+    e = max(e, -126)
+    quantum = Fraction(2) ** (e - 23)
+    n = a / quantum
+    lo = n.numerator // n.denominator
+    rem = n - lo
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    return s * lo * quantum
