@@ -34,7 +34,11 @@ FORMATS = {
     "mxfp4_e8m0": (0, False, "fp4", PEAK_FP4_TFLOPS),      # OCP MXFP4 (power-of-two scale, exponent floored)
     "amxfp4_e8m0": (0, True, "fp8", PEAK_FP8_TFLOPS),      # asymmetric power-of-two scales merged into E5M2 elements
     "amxfp4_e4m3": (3, True, "bf16", PEAK_BF16_TFLOPS),    # the 4-exponent-bit FP8 scale of the paper's Sec. 4.2
+    # Sec. 5.3 double scaling: groups of 16, E4M3 group scale, tensor-wise FP32 scale (its amax pass is in the step)
+    "nvfp4": (3, False, "bf16", PEAK_BF16_TFLOPS),
+    "anvfp4": (3, True, "bf16", PEAK_BF16_TFLOPS),
 }
+DOUBLE_SCALED = ("nvfp4", "anvfp4")
 
 
 class HipEvents:
@@ -180,7 +184,8 @@ def main():
         """Times `steps` steps (cast X + GEMM against pre-cast W) in the given format; returns a dict of timings.
         e5m2_kernel: which of the library's three kernels for FP8-E5M2 scales multiplies (ignored by other formats)."""
         kind, asym, mfma, peak = FORMATS[name]
-        gs = args.group_size
+        scaled = name in DOUBLE_SCALED
+        gs = 16 if scaled else args.group_size
         if gs != 32:
             mfma, peak, e5m2_kernel = "bf16", PEAK_BF16_TFLOPS, "panel"
         if kind == 2 and e5m2_kernel != "panel":
@@ -190,20 +195,29 @@ def main():
         nsc = (M, K // gs, 2) if asym else (M, K // gs)
         xc = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
         xs = torch.empty(nsc, dtype=torch.uint8, device=dev)
-        need = binding.gemm_workspace_bytes(fmt, M, N, K)
+        need = (binding.load().amxfp4_gemm_scaled_workspace_bytes(ctypes.byref(fmt), M, N, K, 1) if scaled
+                else binding.gemm_workspace_bytes(fmt, M, N, K))
         ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else None
-        binding.quantize(fmt, xd, codes=xc, scales=xs)  # first launch of this kernel: module load, not timed
+        xp = torch.empty(2, dtype=torch.float32, device=dev) if scaled else None
+
+        def cast_x():
+            if scaled:
+                binding.tensor_scale(xd, out=xp)
+            binding.quantize(fmt, xd, codes=xc, scales=xs, tensor_pair=xp)
+
+        cast_x()  # first launch of these kernels: module load, not timed
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        wc, wsc = binding.quantize(fmt, wd)  # weights: cast once, outside the timed step
+        wp = binding.tensor_scale(wd) if scaled else None
+        wc, wsc = binding.quantize(fmt, wd, tensor_pair=wp)  # weights: cast once, outside the timed step
         torch.cuda.synchronize()
         t_cast_w = time.perf_counter() - t0
 
         def step(pair=None):
-            binding.quantize(fmt, xd, codes=xc, scales=xs)
+            cast_x()
             if pair is not None:
                 binding.profile_next_gemm(pair[0], pair[1])
-            binding.gemm(fmt, xc, xs, wc, wsc, out=C, workspace=ws)
+            binding.gemm(fmt, xc, xs, wc, wsc, out=C, workspace=ws, a_pair=xp, b_pair=wp)
 
         for _ in range(warmup):
             step()
@@ -219,7 +233,7 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            binding.quantize(fmt, xd, codes=xc, scales=xs)
+            cast_x()
         torch.cuda.synchronize()
         t_cast_x = (time.perf_counter() - t0) / steps
         binding.select_e5m2_kernel("panel")
@@ -230,14 +244,17 @@ def main():
     ms_per_step = r["t_step"] * 1e3
     value = flops / r["t_step"] / 1e12
     achieved = flops / (r["kern_ms"] * 1e-3) / 1e12
-    cast_bytes = M * K * 2 + M * K // 2 + M * (K // args.group_size) * (2 if r["asym"] else 1)
+    scaled = args.format in DOUBLE_SCALED   # the tensor-wise maximum reads X once more
+    cast_bytes = (M * K * 2 * (2 if scaled else 1) + M * K // 2 +
+                  M * (K // (16 if scaled else args.group_size)) * (2 if r["asym"] else 1))
     kernel_name = "gemm_fp4_kernel" if r["mfma"] == "fp4" else "gemm_fp8m_kernel" if r["mfma"] == "fp8" else {"panel": "gemm_bf16_kernel", "hybrid":
                   "gemm_e5m2_hybrid_kernel", "fused": "gemm_e5m2_kernel"}[args.e5m2_kernel if args.group_size == 32 else "panel"]
     out = {
         "metric": "AMXFP4 cast+GEMM TFLOPS at 4096x8192x28672", "value": round(value, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": r["mfma"], "data": "synthetic",
-        "config": {"workload": args.workload, "M": M, "N": N, "K": K, "format": args.format, "group_size": args.group_size,
+        "config": {"workload": args.workload, "M": M, "N": N, "K": K, "format": args.format, "group_size": 16 if args.format in DOUBLE_SCALED else args.group_size,
+                   "tensor_scale": args.format in DOUBLE_SCALED,
                    "e5m2_kernel": args.e5m2_kernel if FORMATS[args.format][0] == 2 and args.group_size == 32 else None,
                    "step": "amxfp4_quantize(X) + amxfp4_gemm(Xq, Wq), W pre-cast"},
         "roofline": {"bound": "mfma", "kernel": kernel_name, "achieved": round(achieved, 2),

@@ -136,6 +136,37 @@ int mxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const u
                int64_t batch, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Double scaling (Sec. 5.3: NVFP4 and its asymmetric variant ANVFP4 combine a tensor-wise FP32 scale with a group-wise
+ * FP8-E4M3 scale of 16-element groups; any format of this library can be combined with the tensor-wise scale). The
+ * paper names the scheme and gives no arithmetic; this library's definition:
+ *   tensor scale   S_t = amax / 2688 in FP32, amax = largest magnitude of the tensor, 2688 = 448 * 6 = the largest
+ *                  E4M3 group scale times the largest element, so the group scales use the top of their range;
+ *                  never below 2^-96; R_t = 1 / S_t in FP32 (both correctly rounded); an all-zero tensor gives 1, 1.
+ *   cast           y = x * R_t in FP32 (one rounding per element), then the group-wise rule at the top of this file
+ *                  applied to the y values (real-number quotients y_max / 6 and y / S, sign class = sign bit of x).
+ *   value          x_hat = elem * S_group * S_t; the GEMM multiplies the accumulated sum by S_t(A) * S_t(B) in FP32.
+ * scale_pair: DEVICE pointer to two floats {S_t, R_t}, 8-byte aligned. amxfp4_tensor_scale writes it (stream-ordered,
+ * no host synchronisation; the pair also serves as its scratch), the other calls read it when they execute.
+ *
+ * amxfp4_tensor_scale: x_bf16 [rows][K] BF16 with rows row_stride apart (K % 8 == 0, row_stride % 8 == 0, 16-byte
+ *   aligned base; the maximum does not depend on which axis is later grouped).
+ * amxfp4_quantize_scaled / amxfp4_dequantize_scaled (FP32 output only: the product is rounded once) /
+ *   amxfp4_gemm_scaled: as the calls without the suffix, plus the scale pair(s). The scaled GEMM always multiplies
+ *   exact BF16 operands and needs a workspace of amxfp4_gemm_scaled_workspace_bytes().
+ */
+int amxfp4_tensor_scale(const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride, float* scale_pair,
+                        void* stream);
+int amxfp4_quantize_scaled(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
+                           int64_t k_stride, const float* scale_pair, uint8_t* codes, uint8_t* scales, void* stream);
+int amxfp4_dequantize_scaled(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows,
+                             int64_t K, const float* scale_pair, float* out, void* stream);
+size_t amxfp4_gemm_scaled_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch);
+int amxfp4_gemm_scaled(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                       const uint8_t* A_scales, const float* A_scale_pair, const uint8_t* B_codes,
+                       const uint8_t* B_scales, const float* B_scale_pair, float* C, int64_t ldc, int64_t batch,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid (not part of the method): arms a pair of caller-owned hipEvent_t (passed as void*) for the NEXT
  * amxfp4_gemm / mxfp4_gemm call made on this host thread. That call records `start` on its stream immediately before
  * and `stop` immediately after the launch of its matrix-multiply kernel (the MFMA main loop, excluding the operand

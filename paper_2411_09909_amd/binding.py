@@ -55,6 +55,14 @@ def load():
     L.amxfp4_select_pot_kernel.argtypes = [ctypes.c_int32]
     L.amxfp4_select_pot_kernel.restype = ctypes.c_int
     f32, f64, i32 = ctypes.c_float, ctypes.c_double, ctypes.c_int32
+    L.amxfp4_tensor_scale.argtypes = [vp, i64, i64, i64, vp, vp]
+    L.amxfp4_quantize_scaled.argtypes = [fp, vp, i64, i64, i64, i64, vp, vp, vp, vp]
+    L.amxfp4_dequantize_scaled.argtypes = [fp, vp, vp, i64, i64, vp, vp, vp]
+    L.amxfp4_gemm_scaled.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, i64, i64, vp, ctypes.c_size_t, vp]
+    for name in ("amxfp4_tensor_scale", "amxfp4_quantize_scaled", "amxfp4_dequantize_scaled", "amxfp4_gemm_scaled"):
+        getattr(L, name).restype = ctypes.c_int
+    L.amxfp4_gemm_scaled_workspace_bytes.argtypes = [fp, i64, i64, i64, i64]
+    L.amxfp4_gemm_scaled_workspace_bytes.restype = ctypes.c_size_t
     L.amxfp4_peak_mfma.argtypes = [i32, vp, i32, vp, ctypes.POINTER(f64), vp]
     L.amxfp4_peak_mfma.restype = ctypes.c_int
     L.amxfp4_peak_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
@@ -152,9 +160,28 @@ def _fn(fmt, name, baseline):
     return getattr(load(), ("mxfp4_" if baseline else "amxfp4_") + name)
 
 
-def quantize(fmt, x, k_axis=-1, codes=None, scales=None, baseline=False):
+def tensor_scale(x, out=None):
+    """Tensor-wise scale of the double-scaling scheme: x 2-D BF16 CUDA tensor with contiguous rows -> float32 CUDA
+    tensor {S_t, 1 / S_t} (computed on the device, stream-ordered)."""
+    _need_cuda(x)
+    assert x.dim() == 2 and x.element_size() == 2 and x.stride(1) == 1
+    if out is None:
+        out = torch.empty(2, dtype=torch.float32, device=x.device)
+    _check(load().amxfp4_tensor_scale(x.data_ptr(), x.shape[0], x.shape[1], x.stride(0), out.data_ptr(), _stream()))
+    return out
+
+
+def _pair_ptr(pair):
+    _need_cuda(pair)
+    if pair.dtype != torch.float32 or pair.numel() < 2 or not pair.is_contiguous():
+        raise AmxError("a tensor-scale pair is a contiguous float32 CUDA tensor of two elements")
+    return pair.data_ptr()
+
+
+def quantize(fmt, x, k_axis=-1, codes=None, scales=None, baseline=False, tensor_pair=None):
     """x: 2-D BF16 (or uint16 bit pattern) CUDA tensor. k_axis=-1: groups along each row (rows contiguous in K);
-    k_axis=0: groups run down the columns (operand = x.T, strided cast). Returns (codes u8 [rows, K/2], scales u8)."""
+    k_axis=0: groups run down the columns (operand = x.T, strided cast). tensor_pair: result of tensor_scale() for
+    the double-scaling cast. Returns (codes u8 [rows, K/2], scales u8)."""
     _need_cuda(x)
     assert x.dim() == 2 and x.element_size() == 2
     if k_axis in (-1, 1):
@@ -169,22 +196,36 @@ def quantize(fmt, x, k_axis=-1, codes=None, scales=None, baseline=False):
     if scales is None:
         shape = (rows, K // fmt.group_size, 2) if asym else (rows, K // fmt.group_size)
         scales = torch.empty(shape, dtype=torch.uint8, device=x.device)
+    if tensor_pair is not None:
+        if baseline:
+            raise AmxError("the mxfp4_* baseline calls take no tensor-wise scale; clear fmt.asymmetric instead")
+        _check(load().amxfp4_quantize_scaled(ctypes.byref(fmt), x.data_ptr(), rows, K, row_stride, k_stride,
+                                             _pair_ptr(tensor_pair), codes.data_ptr(), scales.data_ptr(), _stream()))
+        return codes, scales
     _check(_fn(fmt, "quantize", baseline)(ctypes.byref(fmt), x.data_ptr(), rows, K, row_stride, k_stride,
                                           codes.data_ptr(), scales.data_ptr(), _stream()))
     return codes, scales
 
 
-def dequantize(fmt, codes, scales, out_dtype=torch.float32, baseline=False):
+def dequantize(fmt, codes, scales, out_dtype=torch.float32, baseline=False, tensor_pair=None):
     _need_cuda(codes, scales)
     rows, K = codes.shape[0], codes.shape[1] * 2
     out = torch.empty((rows, K), dtype=out_dtype, device=codes.device)
+    if tensor_pair is not None:
+        if baseline or out_dtype != torch.float32:
+            raise AmxError("the scaled dequantize writes float32 and has no mxfp4_* twin")
+        _check(load().amxfp4_dequantize_scaled(ctypes.byref(fmt), codes.data_ptr(), scales.data_ptr(), rows, K,
+                                               _pair_ptr(tensor_pair), out.data_ptr(), _stream()))
+        return out
     _check(_fn(fmt, "dequantize", baseline)(ctypes.byref(fmt), codes.data_ptr(), scales.data_ptr(), rows, K,
                                             out.data_ptr(), 1 if out_dtype == torch.bfloat16 else 0, _stream()))
     return out
 
 
-def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, baseline=False):
-    """a_codes [M, K/2] or [batch, M, K/2]; b_codes [N, K/2] or [batch, N, K/2] (contiguous). Returns FP32 C."""
+def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, baseline=False, a_pair=None,
+         b_pair=None):
+    """a_codes [M, K/2] or [batch, M, K/2]; b_codes [N, K/2] or [batch, N, K/2] (contiguous). a_pair / b_pair: the
+    operands' tensor_scale() results (both or neither). Returns FP32 C."""
     _need_cuda(a_codes, a_scales, b_codes, b_scales)
     batched = a_codes.dim() == 3
     batch = a_codes.shape[0] if batched else 1
@@ -194,11 +235,20 @@ def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, ba
         assert t.is_contiguous()
     if out is None:
         out = torch.empty((batch, M, N) if batched else (M, N), dtype=torch.float32, device=a_codes.device)
-    need = gemm_workspace_bytes(fmt, M, N, K, batch)
+    scaled = a_pair is not None or b_pair is not None
+    if scaled and (a_pair is None or b_pair is None or baseline):
+        raise AmxError("the scaled GEMM needs both tensor-scale pairs and has no mxfp4_* twin")
+    need = (load().amxfp4_gemm_scaled_workspace_bytes(ctypes.byref(fmt), M, N, K, batch) if scaled
+            else gemm_workspace_bytes(fmt, M, N, K, batch))
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    if scaled:
+        _check(load().amxfp4_gemm_scaled(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
+                                         _pair_ptr(a_pair), b_codes.data_ptr(), b_scales.data_ptr(), _pair_ptr(b_pair),
+                                         out.data_ptr(), out.stride(-2), batch, ws_ptr, ws_len, _stream()))
+        return out
     _check(_fn(fmt, "gemm", baseline)(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
                                       b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(), out.stride(-2), batch,
                                       ws_ptr, ws_len, _stream()))

@@ -63,7 +63,7 @@ int report_hip_error(hipError_t e, const char* what) { return hip_fail(e, what);
 namespace {
 
 int quantize_impl(amx_format_t f, const void* x, int64_t rows, int64_t K, int64_t row_stride, int64_t k_stride,
-                  uint8_t* codes, uint8_t* scales, void* stream) {
+                  const float* tensor_pair, uint8_t* codes, uint8_t* scales, void* stream) {
   if (int rc = check_format(&f)) return rc;
   if (int rc = check_shape(f, rows, K)) return rc;
   if (!x || !codes || !scales) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
@@ -73,26 +73,29 @@ int quantize_impl(amx_format_t f, const void* x, int64_t rows, int64_t K, int64_
   if (k_stride == 1) {
     if (row_stride < K || row_stride % 8 != 0 || !aligned(x, 16))
       return fail(AMX_ERR_INVALID_ARG, "contiguous cast needs row_stride >= K, row_stride %% 8 == 0 and a 16-byte aligned base");
-    hipError_t e = amx::launch_quantize_contig(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, row_stride, codes, scales, s);
+    hipError_t e = amx::launch_quantize_contig(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, row_stride, tensor_pair, codes,
+                                               scales, s);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "quantize launch");
   }
   if (row_stride == 1 && k_stride >= rows) {
     if (!aligned(x, 2)) return fail(AMX_ERR_INVALID_ARG, "x must be 2-byte aligned");
-    hipError_t e = amx::launch_quantize_strided(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, k_stride, codes, scales, s);
+    hipError_t e = amx::launch_quantize_strided(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, k_stride, tensor_pair, codes,
+                                                scales, s);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "strided quantize launch");
   }
   return fail(AMX_ERR_INVALID_ARG, "unsupported strides: need k_stride == 1, or row_stride == 1 with k_stride >= rows");
 }
 
-int dequantize_impl(amx_format_t f, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K, void* out,
-                    int32_t out_dtype, void* stream) {
+int dequantize_impl(amx_format_t f, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
+                    const float* tensor_pair, void* out, int32_t out_dtype, void* stream) {
   if (int rc = check_format(&f)) return rc;
   if (int rc = check_shape(f, rows, K)) return rc;
   if (!codes || !scales || !out) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
   if (out_dtype != 0 && out_dtype != 1) return fail(AMX_ERR_INVALID_ARG, "out_dtype must be 0 (f32) or 1 (bf16)");
   if (!aligned(codes, 4) || !aligned(scales, 2) || !aligned(out, 16))
     return fail(AMX_ERR_INVALID_ARG, "misaligned pointer");
-  hipError_t e = amx::launch_dequantize(f.scale, f.asymmetric != 0, f.group_size, codes, scales, rows, K, out, out_dtype,
+  hipError_t e = amx::launch_dequantize(f.scale, f.asymmetric != 0, f.group_size, codes, scales, rows, K, tensor_pair, out,
+                                        out_dtype,
                                         reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? AMX_OK : hip_fail(e, "dequantize launch");
 }
@@ -138,9 +141,12 @@ bool uses_merged_pot(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
   return pot_choice().load(std::memory_order_relaxed) == 0 || !amx::fp4_path_supported(M, N, K);
 }
 
+// A_pair / B_pair: device {S_t, 1 / S_t} of the operands' tensor-wise scales (Sec. 5.3), both null for none. Scaled
+// products always take the BF16 expansion path, whose kernel has the scaling epilogue.
 int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
-              const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch, void* workspace,
-              size_t workspace_bytes, void* stream) {
+              const float* A_pair, const uint8_t* B_codes, const uint8_t* B_scales, const float* B_pair, float* C,
+              int64_t ldc, int64_t batch, void* workspace, size_t workspace_bytes, void* stream) {
+  const bool scaled = A_pair != nullptr;
   if (int rc = check_format(&f)) return rc;
   if (int rc = check_shape(f, M, K)) return rc;
   if (N <= 0 || batch <= 0) return fail(AMX_ERR_INVALID_ARG, "N and batch must be positive");
@@ -149,7 +155,8 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
   if (!aligned(A_codes, 16) || !aligned(B_codes, 16) || !aligned(A_scales, 4) || !aligned(B_scales, 4) ||
       !aligned(C, 4))
     return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales and C 4-byte alignment");
-  const size_t need = amxfp4_gemm_workspace_bytes(&f, M, N, K, batch);
+  const size_t need = scaled ? amx::bf16_path_workspace_bytes(M, N, K, batch)
+                             : amxfp4_gemm_workspace_bytes(&f, M, N, K, batch);
   if (need > 0) {
     if (!workspace || workspace_bytes < need)
       return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
@@ -157,17 +164,17 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
   }
   const amx::KernelTimer timer = g_timer;
   g_timer = amx::KernelTimer();
-  if (uses_merged_pot(f, M, N, K)) {
+  if (!scaled && uses_merged_pot(f, M, N, K)) {
     hipError_t e = amx::launch_gemm_fp8m_path(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace,
                                               reinterpret_cast<hipStream_t>(stream), timer);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
   }
-  if (uses_fp4_mfma(f, M, N, K)) {
+  if (!scaled && uses_fp4_mfma(f, M, N, K)) {
     hipError_t e = amx::launch_gemm_fp4_path(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc,
                                              batch, reinterpret_cast<hipStream_t>(stream), timer);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
   }
-  const E5m2Path path = e5m2_path(f, M, N, K);
+  const E5m2Path path = scaled ? kPathPanel : e5m2_path(f, M, N, K);
   if (path == kPathFused) {
     hipError_t e = amx::launch_gemm_e5m2_fused(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc,
                                                batch, reinterpret_cast<hipStream_t>(stream), timer);
@@ -179,7 +186,8 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
   }
   hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, f.group_size, M, N, K, A_codes, A_scales, B_codes, B_scales,
-                                            C, ldc, batch, workspace, reinterpret_cast<hipStream_t>(stream), timer);
+                                            A_pair, B_pair, C, ldc, batch, workspace,
+                                            reinterpret_cast<hipStream_t>(stream), timer);
   return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
 }
 
@@ -236,41 +244,83 @@ size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N
 int amxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
                     int64_t k_stride, uint8_t* codes, uint8_t* scales, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  return quantize_impl(*fmt, x_bf16, rows, K, row_stride, k_stride, codes, scales, stream);
+  return quantize_impl(*fmt, x_bf16, rows, K, row_stride, k_stride, nullptr, codes, scales, stream);
 }
 
 int amxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
                       void* out, int32_t out_dtype, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  return dequantize_impl(*fmt, codes, scales, rows, K, out, out_dtype, stream);
+  return dequantize_impl(*fmt, codes, scales, rows, K, nullptr, out, out_dtype, stream);
 }
 
 int amxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
                 int64_t batch, void* workspace, size_t workspace_bytes, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  return gemm_impl(*fmt, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, workspace_bytes,
+  return gemm_impl(*fmt, M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc, batch, workspace, workspace_bytes,
                    stream);
 }
 
 int mxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
                    int64_t k_stride, uint8_t* codes, uint8_t* scales, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  return quantize_impl(symmetric(fmt), x_bf16, rows, K, row_stride, k_stride, codes, scales, stream);
+  return quantize_impl(symmetric(fmt), x_bf16, rows, K, row_stride, k_stride, nullptr, codes, scales, stream);
 }
 
 int mxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
                      void* out, int32_t out_dtype, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  return dequantize_impl(symmetric(fmt), codes, scales, rows, K, out, out_dtype, stream);
+  return dequantize_impl(symmetric(fmt), codes, scales, rows, K, nullptr, out, out_dtype, stream);
 }
 
 int mxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
                int64_t batch, void* workspace, size_t workspace_bytes, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  return gemm_impl(symmetric(fmt), M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace,
+  return gemm_impl(symmetric(fmt), M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc, batch,
+                   workspace,
                    workspace_bytes, stream);
+}
+
+int amxfp4_tensor_scale(const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride, float* scale_pair,
+                        void* stream) {
+  if (!x_bf16 || !scale_pair) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
+  if (rows <= 0 || K <= 0 || K % 8 != 0) return fail(AMX_ERR_INVALID_ARG, "rows and K must be positive, K a multiple of 8");
+  if (row_stride < K || row_stride % 8 != 0 || !aligned(x_bf16, 16) || !aligned(scale_pair, 8))
+    return fail(AMX_ERR_INVALID_ARG, "need row_stride >= K, row_stride %% 8 == 0, a 16-byte aligned tensor and an 8-byte aligned pair");
+  hipError_t e = amx::launch_tensor_scale(reinterpret_cast<const uint16_t*>(x_bf16), rows, K, row_stride, scale_pair,
+                                          reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AMX_OK : hip_fail(e, "tensor scale launch");
+}
+
+int amxfp4_quantize_scaled(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
+                           int64_t k_stride, const float* scale_pair, uint8_t* codes, uint8_t* scales, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  if (!scale_pair || !aligned(scale_pair, 8)) return fail(AMX_ERR_INVALID_ARG, "scale_pair is NULL or misaligned");
+  return quantize_impl(*fmt, x_bf16, rows, K, row_stride, k_stride, scale_pair, codes, scales, stream);
+}
+
+int amxfp4_dequantize_scaled(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows,
+                             int64_t K, const float* scale_pair, float* out, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  if (!scale_pair || !aligned(scale_pair, 8)) return fail(AMX_ERR_INVALID_ARG, "scale_pair is NULL or misaligned");
+  return dequantize_impl(*fmt, codes, scales, rows, K, scale_pair, out, 0, stream);
+}
+
+size_t amxfp4_gemm_scaled_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch) {
+  if (!fmt || M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
+  return amx::bf16_path_workspace_bytes(M, N, K, batch);
+}
+
+int amxfp4_gemm_scaled(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                       const uint8_t* A_scales, const float* A_scale_pair, const uint8_t* B_codes,
+                       const uint8_t* B_scales, const float* B_scale_pair, float* C, int64_t ldc, int64_t batch,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  if (!A_scale_pair || !B_scale_pair || !aligned(A_scale_pair, 8) || !aligned(B_scale_pair, 8))
+    return fail(AMX_ERR_INVALID_ARG, "a scale pair is NULL or misaligned");
+  return gemm_impl(*fmt, M, N, K, A_codes, A_scales, A_scale_pair, B_codes, B_scales, B_scale_pair, C, ldc, batch,
+                   workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -1,16 +1,17 @@
 // Direct-cast quantization BF16 -> AMXFP4 / MXFP4 (Appendix B Algorithm 1, generalised by Sec. 4.2 Eq. 1 to a
 // sign-dependent pair of shared scales) and the matching dequantization (Eq. 1). Group sizes 16, 32, 64, 128 along K
 // (Sec. 5.3 / Table 5 compare them; 32 is the paper's choice); scale formats FP8 E5M2 (the paper's), FP8 E4M3 and
-// E8M0 with the exponent floored or rounded.
+// E8M0 with the exponent floored or rounded; optionally a tensor-wise FP32 scale underneath (Sec. 5.3, the double
+// scaling of NVFP4 / ANVFP4): elements are multiplied by its reciprocal in FP32 first and the cast runs on those.
 //
 // Contiguous cast: one lane owns 8 consecutive BF16 (one 128-bit load); the GS / 8 lanes next to each other own one
 // group. Group extrema are found with packed 16-bit integer max (non-negative BF16 patterns order like integers) and
 // DPP permutes inside the group. Every decision comes out as exact arithmetic would give it:
 //   - an FP8 scale is the correctly rounded FP32 quotient amax/6 rounded once more to 3 (E5M2) or 4 (E4M3)
-//     significant bits; the quotient of an 8-bit significand by 3 is either exact or far (>= 2^-13 relative) from
-//     every midpoint of that grid, so the two-step rounding equals rounding the real quotient;
-//   - the element quotient x / S is formed to within an ulp (exactly when representable, see quotient()) and rounded
-//     to E2M1 by the hardware conversion v_cvt_scalef32_pk_fp4_f32.
+//     significant bits, which equals rounding the real quotient (see fp8_scale());
+//   - the element quotient x / S is formed correctly rounded away from FP32 midpoints and exactly when representable,
+//     which keeps it on the right side of every E2M1 boundary (see quotient()), and rounded to E2M1 by the hardware
+//     conversion v_cvt_scalef32_pk_fp4_f32.
 // Strided cast (groups down a column, for V in P.V): one lane per (row, group), the same arithmetic.
 #include "device_formats.h"
 
@@ -42,58 +43,61 @@ __device__ __forceinline__ uint32_t group_max_u32(uint32_t v, int lpg_log2) {
   return v;
 }
 
-// Shared scale of one sign class: its byte, and the pair (S, R) the element step divides with: S = the scale as a float (exact), R ~ 1/S (0 if S is 0). Power-of-two scales need only R, which is exact.
+// FP8 shared scale (MBITS mantissa bits, smallest normal exponent EMIN, exponent bias BIAS, largest value maxv) of a
+// sign class with largest magnitude amax >= 0 (any FP32 number): the real quotient amax / 6 (6 = largest E2M1
+// magnitude) rounded to nearest, ties to even, saturating, subnormals kept. q is the correctly rounded FP32 quotient;
+// adding 1.5 * 2^(e+23-MBITS) rounds it to a multiple of 2^(e-MBITS) in the FP32 adder. The two-step rounding equals
+// rounding the real quotient: neighbouring FP32 values of amax are 4 or 8 ulps of q apart, so their quotients differ
+// by 2/3 or 4/3 ulp of q, and q lands on a midpoint of the FP8 grid only when amax / 6 is that midpoint exactly.
+template <int MBITS, int EMIN, int BIAS>
+__device__ __forceinline__ uint32_t fp8_scale(float amax, float maxv, float& S, float& R) {
+  const float q = __fdiv_rn(amax, 6.0f);
+  int e = (int)(f2u(q) >> 23) - 127;
+  e = e < EMIN ? EMIN : e;  // subnormals share the spacing of the lowest normal binade
+  const float magic = u2f(((uint32_t)(e + 23 - MBITS + 127) << 23) | 0x00400000u);
+  float r = (q + magic) - magic;
+  r = fminf(r, maxv);
+  const uint32_t rb = f2u(r);
+  // normal: exponent and MBITS mantissa bits of the float; below 2^EMIN: m * 2^(EMIN - MBITS)
+  const float min_normal = u2f((uint32_t)(EMIN + 127) << 23), to_int = u2f((uint32_t)(MBITS - EMIN + 127) << 23);
+  const uint32_t byte = r >= min_normal
+                            ? ((((rb >> 23) - (uint32_t)(127 - BIAS)) << MBITS) | ((rb >> (23 - MBITS)) & ((1u << MBITS) - 1u)))
+                            : (uint32_t)(r * to_int);
+  S = r;
+  R = r > 0.f ? __builtin_amdgcn_rcpf(r) : 0.f;
+  return byte;
+}
+
+// Shared scale of one sign class with largest magnitude amax (a non-negative float): its byte, and the pair (S, R)
+// the element step divides with: S = the scale as a float (exact), R ~ 1/S (0 if S is 0). Power-of-two scales need
+// only R, which is exact.
 template <int SCALE_KIND>
-__device__ __forceinline__ uint32_t encode_scale_sr(uint32_t amax_bits, float& S, float& R) {
+__device__ __forceinline__ uint32_t encode_scale_sr(float amax, float& S, float& R) {
   if constexpr (SCALE_KIND == kScaleE5M2) {
-    const float amax = u2f(amax_bits << 16);
-    const float q = __fdiv_rn(amax, 6.0f);  // 6 = largest E2M1 magnitude
-    int e = (int)(f2u(q) >> 23) - 127;
-    e = e < -14 ? -14 : e;  // E5M2 subnormals share the spacing of the lowest normal binade
-    // adding 1.5 * 2^(e+21) rounds q to a multiple of 2^(e-2) (nearest, ties to even) in the FP32 adder
-    const float magic = u2f(((uint32_t)(e + 21 + 127) << 23) | 0x00400000u);
-    float r = (q + magic) - magic;
-    r = fminf(r, 57344.0f);
-    const uint32_t rb = f2u(r);
-    // normal: exponent and two mantissa bits of the float; below 2^-14: m * 2^-16 with m = 0..3
-    const uint32_t byte =
-        r >= 6.103515625e-05f ? ((((rb >> 23) - 112u) << 2) | ((rb >> 21) & 3u)) : (uint32_t)(r * 65536.0f);
-    S = r;
-    R = r > 0.f ? __builtin_amdgcn_rcpf(r) : 0.f;
-    return byte;
+    return fp8_scale<2, -14, 15>(amax, 57344.0f, S, R);
   } else if constexpr (SCALE_KIND == kScaleE4M3) {
-    const float amax = u2f(amax_bits << 16);
-    const float q = __fdiv_rn(amax, 6.0f);
-    int e = (int)(f2u(q) >> 23) - 127;
-    e = e < -6 ? -6 : e;  // E4M3 subnormals share the spacing of the lowest normal binade (2^-6)
-    // adding 1.5 * 2^(e+20) rounds q to a multiple of 2^(e-3) (nearest, ties to even) in the FP32 adder
-    const float magic = u2f(((uint32_t)(e + 20 + 127) << 23) | 0x00400000u);
-    float r = (q + magic) - magic;
-    r = fminf(r, 448.0f);  // largest finite E4M3 value (byte 0x7E)
-    const uint32_t rb = f2u(r);
-    // normal: exponent (bias 7) and three mantissa bits of the float; below 2^-6: m * 2^-9 with m = 0..7
-    const uint32_t byte = r >= 0.015625f ? ((((rb >> 23) - 120u) << 3) | ((rb >> 20) & 7u)) : (uint32_t)(r * 512.0f);
-    S = r;
-    R = r > 0.f ? __builtin_amdgcn_rcpf(r) : 0.f;
-    return byte;
+    return fp8_scale<3, -6, 7>(amax, 448.0f, S, R);  // 448 = largest finite E4M3 value (byte 0x7E)
   } else {
-    const uint32_t e8 = amax_bits >> 7, m7 = amax_bits & 127u;
+    const uint32_t bits = f2u(amax), e8 = bits >> 23, m23 = bits & 0x7FFFFFu;
     int b = (int)e8 - 2;
-    if constexpr (SCALE_KIND == kScaleE8M0Round) b += (m7 >= 54u) ? 1 : 0;  // significand above sqrt(2)
+    // exponent rounded instead of floored: one more when the significand exceeds sqrt(2) = 1 + 3474675.3 / 2^23
+    if constexpr (SCALE_KIND == kScaleE8M0Round) b += (m23 >= 3474676u) ? 1 : 0;
     b = b < 0 ? 0 : b;
-    if (amax_bits == 0) b = 0;
+    if (bits == 0) b = 0;
     S = 0.f;                                // unused
     R = u2f((uint32_t)(254 - b) << 23);     // 2^(127 - b) = 1 / scale
     return (uint32_t)b;
   }
 }
 
-// x / S for the element step, as a float that rounds to the same E2M1 code as the real quotient:
+// x / S for the element step (x any FP32 number), as a float that rounds to the same E2M1 code as the real quotient:
 //  - power-of-two scale: x * R is exact;
-//  - FP8 scale: one Newton step on z0 = x * R with the exact residual x - z0 * S (an FMA) gives the quotient to well
-//    within an ulp, and exactly when it is representable. Rounding boundaries of E2M1 are representable, and a
-//    quotient of an 8-bit by a 3- or 4-bit significand that is not on a boundary is at least 2^-12 (relative) away,
-//    so the conversion below decides as exact arithmetic would. S = 0: R = 0 and the result is a zero with x's sign.
+//  - FP8 scale: one Newton step on z0 = x * R with the exact residual x - z0 * S (an FMA) gives the correctly rounded
+//    quotient except within 2^-20 ulp of a rounding midpoint of FP32, and the exact one when it is representable.
+//    The E2M1 rounding boundaries b are representable. If x / S is not b, x differs from b * S (at most 7
+//    significant bits) by at least an ulp of x, which is between 0.53 and 2 ulps of the quotient for the significands
+//    an FP8 scale can have (1/1.875 at worst): the quotient is at least 0.53 ulp from b, never rounds onto it, and the
+//    conversion below decides as exact arithmetic would. S = 0: R = 0 and the result is a zero with x's sign.
 template <int SCALE_KIND>
 __device__ __forceinline__ float quotient(float x, float S, float R) {
   const float z0 = x * R;
@@ -106,19 +110,18 @@ __device__ __forceinline__ float quotient(float x, float S, float R) {
   }
 }
 
-// Eight elements (four registers of two BF16 each, lower index in the low half) -> eight E2M1 codes, first element
-// in the lowest nibble. The E2M1 rounding itself (nearest, ties to even, saturating, sign kept on zero results) is
-// done by the packed FP32 -> FP4 conversion instruction.
+// Eight values (the class of each is its sign bit) -> eight E2M1 codes, first element in the lowest nibble. The E2M1
+// rounding itself (nearest, ties to even, saturating, sign kept on zero results) is done by the packed FP32 -> FP4
+// conversion instruction.
 template <int SCALE_KIND, bool ASYM>
-__device__ __forceinline__ uint32_t encode8(const uint32_t (&d)[4], float s_pos, float r_pos, float s_neg,
-                                            float r_neg) {
+__device__ __forceinline__ uint32_t encode8(const float (&y)[8], float s_pos, float r_pos, float s_neg, float r_neg) {
   uint32_t packed = 0;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const float x0 = u2f(d[j] << 16), x1 = u2f(d[j] & 0xFFFF0000u);
+    const float x0 = y[2 * j], x1 = y[2 * j + 1];
     float z0, z1;
     if constexpr (ASYM) {
-      const bool n0 = (d[j] & 0x8000u) != 0, n1 = (int32_t)d[j] < 0;
+      const bool n0 = (int32_t)f2u(x0) < 0, n1 = (int32_t)f2u(x1) < 0;
       z0 = quotient<SCALE_KIND>(x0, n0 ? s_neg : s_pos, n0 ? r_neg : r_pos);
       z1 = quotient<SCALE_KIND>(x1, n1 ? s_neg : s_pos, n1 ? r_neg : r_pos);
     } else {
@@ -134,12 +137,31 @@ __device__ __forceinline__ uint32_t encode8(const uint32_t (&d)[4], float s_pos,
   return packed;
 }
 
+// Largest magnitude per sign class over n floats, as bit patterns (non-negative floats order like integers).
+// Symmetric formats: both results are the largest magnitude overall.
+template <bool ASYM, int N>
+__device__ __forceinline__ void class_extrema(const float (&y)[N], uint32_t& amax_p, uint32_t& amax_n) {
+  amax_p = 0, amax_n = 0;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const uint32_t bits = f2u(y[i]), mag = bits & 0x7FFFFFFFu;
+    if (ASYM && (bits >> 31))
+      amax_n = mag > amax_n ? mag : amax_n;
+    else
+      amax_p = mag > amax_p ? mag : amax_p;
+  }
+  if constexpr (!ASYM) amax_n = amax_p;
+}
+
 // Contiguous cast. Thread block = 256 lanes arranged as (256 >> bx_log2) rows x (1 << bx_log2) chunks of 8 elements;
 // blockIdx.x walks the rows, blockIdx.y the chunks of a row. A group is 2^lpg_log2 neighbouring lanes; bx is a
 // multiple of that and so is the number of chunks in a row, hence a group is always whole and aligned in its wave.
-template <int SCALE_KIND, bool ASYM>
+// TENSOR_SCALED (Sec. 5.3, double scaling): every element is first multiplied by the tensor-wise factor
+// tensor_pair[1] in FP32 (one rounding) and the group-wise cast runs on those FP32 values.
+template <int SCALE_KIND, bool ASYM, bool TENSOR_SCALED>
 __global__ __launch_bounds__(256) void quantize_contig_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t K,
-                                                              int64_t row_stride, uint8_t* __restrict__ codes,
+                                                              int64_t row_stride, const float* __restrict__ tensor_pair,
+                                                              uint8_t* __restrict__ codes,
                                                               uint8_t* __restrict__ scales, int bx_log2,
                                                               int lpg_log2) {
   const int tx = threadIdx.x & ((1 << bx_log2) - 1), ty = threadIdx.x >> bx_log2;
@@ -148,32 +170,39 @@ __global__ __launch_bounds__(256) void quantize_contig_kernel(const uint16_t* __
   if (r >= rows || cc >= (int)(K >> 3)) return;
   const uint4 v = *reinterpret_cast<const uint4*>(x + r * row_stride + (int64_t)cc * 8);
   const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+  float y[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) y[2 * j] = u2f(d[j] << 16), y[2 * j + 1] = u2f(d[j] & 0xFFFF0000u);
   // group extrema (steps "max_i |V_i|" of Algorithm 1, split by sign for the asymmetric format)
   uint32_t amax_p, amax_n;
-  if constexpr (ASYM) {
+  if constexpr (TENSOR_SCALED) {
+    const float rt = tensor_pair[1];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) y[i] *= rt;
+    class_extrema<ASYM>(y, amax_p, amax_n);
+  } else if constexpr (ASYM) {
+    // BF16 patterns: packed 16-bit integer maxima; negative patterns (sign bit set) compare below zero as int16
     uint32_t p = pk_max_i16(pk_max_i16(d[0], d[1]), pk_max_i16(d[2], d[3]));
-    p = pk_max_i16(p, 0u);  // negative patterns (sign bit set) compare below zero as int16
+    p = pk_max_i16(p, 0u);
     uint32_t n = pk_max_i16(pk_max_i16(d[0] ^ 0x80008000u, d[1] ^ 0x80008000u),
                             pk_max_i16(d[2] ^ 0x80008000u, d[3] ^ 0x80008000u));
     n = pk_max_i16(n, 0u);
-    amax_p = (p & 0xFFFFu) > (p >> 16) ? (p & 0xFFFFu) : (p >> 16);
-    amax_n = (n & 0xFFFFu) > (n >> 16) ? (n & 0xFFFFu) : (n >> 16);
-    amax_p = group_max_u32(amax_p, lpg_log2);
-    amax_n = group_max_u32(amax_n, lpg_log2);
+    amax_p = ((p & 0xFFFFu) > (p >> 16) ? (p & 0xFFFFu) : (p >> 16)) << 16;
+    amax_n = ((n & 0xFFFFu) > (n >> 16) ? (n & 0xFFFFu) : (n >> 16)) << 16;
   } else {
     uint32_t a = pk_max_i16(pk_max_i16(d[0] & 0x7FFF7FFFu, d[1] & 0x7FFF7FFFu),
                             pk_max_i16(d[2] & 0x7FFF7FFFu, d[3] & 0x7FFF7FFFu));
-    amax_p = (a & 0xFFFFu) > (a >> 16) ? (a & 0xFFFFu) : (a >> 16);
-    amax_p = group_max_u32(amax_p, lpg_log2);
-    amax_n = amax_p;
+    amax_p = amax_n = ((a & 0xFFFFu) > (a >> 16) ? (a & 0xFFFFu) : (a >> 16)) << 16;
   }
+  amax_p = group_max_u32(amax_p, lpg_log2);
+  if constexpr (ASYM) amax_n = group_max_u32(amax_n, lpg_log2);
   float s_pos, r_pos, s_neg, r_neg;
-  const uint32_t sb_p = encode_scale_sr<SCALE_KIND>(amax_p, s_pos, r_pos);
+  const uint32_t sb_p = encode_scale_sr<SCALE_KIND>(u2f(amax_p), s_pos, r_pos);
   uint32_t sb_n = sb_p;
   s_neg = s_pos, r_neg = r_pos;
-  if constexpr (ASYM) sb_n = encode_scale_sr<SCALE_KIND>(amax_n, s_neg, r_neg);
+  if constexpr (ASYM) sb_n = encode_scale_sr<SCALE_KIND>(u2f(amax_n), s_neg, r_neg);
   *reinterpret_cast<uint32_t*>(codes + r * (K >> 1) + (int64_t)cc * 4) =
-      encode8<SCALE_KIND, ASYM>(d, s_pos, r_pos, s_neg, r_neg);
+      encode8<SCALE_KIND, ASYM>(y, s_pos, r_pos, s_neg, r_neg);
   if ((tx & ((1 << lpg_log2) - 1)) == 0) {
     const int64_t g = r * (K >> (lpg_log2 + 3)) + (cc >> lpg_log2);
     if constexpr (ASYM)
@@ -185,44 +214,41 @@ __global__ __launch_bounds__(256) void quantize_contig_kernel(const uint16_t* __
 
 // Groups run down a column: element (r, k) = x[r + k * k_stride]. One lane owns one (row, group) of GS elements;
 // consecutive lanes own consecutive rows, so each of the GS loads of a wave reads 128 contiguous bytes.
-template <int SCALE_KIND, bool ASYM, int GS>
+template <int SCALE_KIND, bool ASYM, bool TENSOR_SCALED, int GS>
 __global__ __launch_bounds__(256) void quantize_strided_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t K,
-                                                               int64_t k_stride, uint8_t* __restrict__ codes,
+                                                               int64_t k_stride, const float* __restrict__ tensor_pair,
+                                                               uint8_t* __restrict__ codes,
                                                                uint8_t* __restrict__ scales) {
   const int64_t G = K / GS;
   const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t g = blockIdx.y;
   if (r >= rows) return;
   const uint16_t* p = x + r + g * GS * k_stride;
-  uint32_t d[GS / 2];  // two elements per register, lower index in the low half
-  uint32_t amax_p = 0, amax_n = 0;
+  float rt = 1.0f;
+  if constexpr (TENSOR_SCALED) rt = tensor_pair[1];
+  float y[GS];
 #pragma unroll
-  for (int i = 0; i < GS; i += 2) {
-    const uint32_t b0 = p[i * k_stride], b1 = p[(i + 1) * k_stride];
-    d[i >> 1] = b0 | (b1 << 16);
-    const uint32_t m0 = b0 & 0x7FFFu, m1 = b1 & 0x7FFFu;
-    if (b0 & 0x8000u)
-      amax_n = m0 > amax_n ? m0 : amax_n;
-    else
-      amax_p = m0 > amax_p ? m0 : amax_p;
-    if (b1 & 0x8000u)
-      amax_n = m1 > amax_n ? m1 : amax_n;
-    else
-      amax_p = m1 > amax_p ? m1 : amax_p;
+  for (int i = 0; i < GS; ++i) {
+    y[i] = u2f((uint32_t)p[i * k_stride] << 16);
+    if constexpr (TENSOR_SCALED) y[i] *= rt;
   }
-  if constexpr (!ASYM) amax_p = amax_n = (amax_p > amax_n ? amax_p : amax_n);
+  uint32_t amax_p, amax_n;
+  class_extrema<ASYM>(y, amax_p, amax_n);
   float s_pos, r_pos, s_neg, r_neg;
-  const uint32_t sb_p = encode_scale_sr<SCALE_KIND>(amax_p, s_pos, r_pos);
+  const uint32_t sb_p = encode_scale_sr<SCALE_KIND>(u2f(amax_p), s_pos, r_pos);
   uint32_t sb_n = sb_p;
   s_neg = s_pos, r_neg = r_pos;
-  if constexpr (ASYM) sb_n = encode_scale_sr<SCALE_KIND>(amax_n, s_neg, r_neg);
+  if constexpr (ASYM) sb_n = encode_scale_sr<SCALE_KIND>(u2f(amax_n), s_neg, r_neg);
   uint32_t* out = reinterpret_cast<uint32_t*>(codes + r * (K >> 1) + g * (GS / 2));
 #pragma unroll
   for (int t = 0; t < GS / 16; ++t) {
-    const uint32_t lo[4] = {d[8 * t], d[8 * t + 1], d[8 * t + 2], d[8 * t + 3]};
-    const uint32_t hi[4] = {d[8 * t + 4], d[8 * t + 5], d[8 * t + 6], d[8 * t + 7]};
-    *reinterpret_cast<uint2*>(out + 2 * t) = make_uint2(encode8<SCALE_KIND, ASYM>(lo, s_pos, r_pos, s_neg, r_neg),
-                                                        encode8<SCALE_KIND, ASYM>(hi, s_pos, r_pos, s_neg, r_neg));
+    const float lo[8] = {y[16 * t], y[16 * t + 1], y[16 * t + 2], y[16 * t + 3],
+                         y[16 * t + 4], y[16 * t + 5], y[16 * t + 6], y[16 * t + 7]};
+    const float hi[8] = {y[16 * t + 8], y[16 * t + 9], y[16 * t + 10], y[16 * t + 11],
+                         y[16 * t + 12], y[16 * t + 13], y[16 * t + 14], y[16 * t + 15]};
+    *reinterpret_cast<uint2*>(out + 2 * t) =
+        make_uint2(encode8<SCALE_KIND, ASYM>(lo, s_pos, r_pos, s_neg, r_neg),
+                   encode8<SCALE_KIND, ASYM>(hi, s_pos, r_pos, s_neg, r_neg));
   }
   if constexpr (ASYM)
     *reinterpret_cast<uint16_t*>(scales + (r * G + g) * 2) = (uint16_t)(sb_p | (sb_n << 8));
@@ -230,11 +256,62 @@ __global__ __launch_bounds__(256) void quantize_strided_kernel(const uint16_t* _
     scales[r * G + g] = (uint8_t)sb_p;
 }
 
-// x_hat = (-1)^s * elem * S_class (Eq. 1). One lane expands 8 codes.
+// Tensor-wise scale (Sec. 5.3, double scaling): the largest magnitude of a BF16 tensor, then
+// S_t = amax / 2688 (2688 = 448 * 6 = largest E4M3 group scale times largest element), not below 2^-96, and
+// R_t = 1 / S_t, both correctly rounded FP32 divisions; an all-zero tensor gives 1, 1. pair[0] serves as the
+// accumulator of the maximum (bit pattern of a non-negative float) between the three launches.
+__global__ void tensor_amax_init_kernel(uint32_t* pair) {
+  pair[0] = 0u;
+  pair[1] = 0u;
+}
+
+__global__ __launch_bounds__(256) void tensor_amax_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t K,
+                                                          int64_t row_stride, uint32_t* __restrict__ pair) {
+  const int64_t chunks_per_row = K >> 3, total = rows * chunks_per_row;
+  uint32_t m = 0;  // two running 15-bit magnitudes
+  for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < total; c += (int64_t)gridDim.x * 256) {
+    const int64_t r = c / chunks_per_row, cc = c - r * chunks_per_row;
+    const uint4 v = *reinterpret_cast<const uint4*>(x + r * row_stride + cc * 8);
+    m = pk_max_i16(m, pk_max_i16(pk_max_i16(v.x & 0x7FFF7FFFu, v.y & 0x7FFF7FFFu),
+                                 pk_max_i16(v.z & 0x7FFF7FFFu, v.w & 0x7FFF7FFFu)));
+  }
+  uint32_t a = (m & 0xFFFFu) > (m >> 16) ? (m & 0xFFFFu) : (m >> 16);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const uint32_t o = (uint32_t)__shfl_xor((int)a, off, 64);
+    a = a > o ? a : o;
+  }
+  // one atomic per workgroup, and none when the running maximum already covers it (the maximum only grows, so a
+  // stale read can only cause a superfluous atomic)
+  __shared__ uint32_t wave_max[4];
+  if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) a = a > wave_max[w] ? a : wave_max[w];
+    a <<= 16;
+    if (a > __builtin_nontemporal_load(pair)) atomicMax(pair, a);
+  }
+}
+
+__global__ void tensor_scale_finalize_kernel(float* pair) {
+  const float amax = pair[0];  // the accumulated bit pattern is the float itself
+  float st = 1.0f, rt = 1.0f;
+  if (amax > 0.f) {
+    st = fmaxf(__fdiv_rn(amax, 2688.0f), 0x1p-96f);
+    rt = __fdiv_rn(1.0f, st);
+  }
+  pair[0] = st;
+  pair[1] = rt;
+}
+
+// x_hat = (-1)^s * elem * S_class (Eq. 1), times the tensor-wise scale tensor_pair[0] when that pointer is not null
+// (Sec. 5.3; FP32 output only: one rounding of the exact product). One lane expands 8 codes.
 template <int SCALE_KIND, bool ASYM, bool OUT_BF16>
 __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t* __restrict__ codes,
                                                          const uint8_t* __restrict__ scales, int64_t rows, int64_t K,
-                                                         int gs_log2, void* __restrict__ out) {
+                                                         int gs_log2, const float* __restrict__ tensor_pair,
+                                                         void* __restrict__ out) {
+  const float st = tensor_pair ? tensor_pair[0] : 1.0f;
   const int64_t chunks_per_row = K >> 3;
   const int64_t total = rows * chunks_per_row;
   for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < total; c += (int64_t)gridDim.x * 256) {
@@ -256,7 +333,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t* __restri
       const uint32_t n = (w >> (4 * j)) & 15u;
       const float mag2 = (float)e2m1_twice(n & 7u);  // 2 * |element|
       const float s = (n & 8u) ? -0.5f * s_neg : 0.5f * s_pos;
-      v[j] = mag2 * s;  // <= 5 significant bits: exact in FP32 and in BF16
+      v[j] = (mag2 * s) * st;  // elem * scale has <= 6 significant bits: exact in FP32 and in BF16
     }
     if constexpr (OUT_BF16) {
       uint32_t o[4];
@@ -282,7 +359,7 @@ static int group_log2(int64_t gs) { return gs == 16 ? 4 : gs == 32 ? 5 : gs == 6
 
 template <int SK, bool ASYM>
 static hipError_t launch_qc(const uint16_t* x, int64_t rows, int64_t K, int gs_log2, int64_t row_stride,
-                            uint8_t* codes, uint8_t* scales, hipStream_t s) {
+                            const float* tensor_pair, uint8_t* codes, uint8_t* scales, hipStream_t s) {
   // block shape: as many chunks of a row as fit (power of two, one group .. 256), the rest of the 256 lanes go to
   // more rows
   const int64_t chunks = K / 8;
@@ -290,9 +367,13 @@ static hipError_t launch_qc(const uint16_t* x, int64_t rows, int64_t K, int gs_l
   int bx_log2 = lpg_log2 < 2 ? 2 : lpg_log2;
   while (bx_log2 < 8 && (int64_t(1) << (bx_log2 + 1)) <= chunks) ++bx_log2;
   const int64_t bx = int64_t(1) << bx_log2, by = 256 >> bx_log2;
-  hipLaunchKernelGGL((quantize_contig_kernel<SK, ASYM>), dim3((unsigned)((rows + by - 1) / by),
-                     (unsigned)((chunks + bx - 1) / bx)), dim3(256), 0, s, x, rows, K, row_stride, codes, scales,
-                     bx_log2, lpg_log2);
+  const dim3 grid((unsigned)((rows + by - 1) / by), (unsigned)((chunks + bx - 1) / bx));
+  if (tensor_pair)
+    hipLaunchKernelGGL((quantize_contig_kernel<SK, ASYM, true>), grid, dim3(256), 0, s, x, rows, K, row_stride,
+                       tensor_pair, codes, scales, bx_log2, lpg_log2);
+  else
+    hipLaunchKernelGGL((quantize_contig_kernel<SK, ASYM, false>), grid, dim3(256), 0, s, x, rows, K, row_stride,
+                       tensor_pair, codes, scales, bx_log2, lpg_log2);
   return hipGetLastError();
 }
 
@@ -313,57 +394,76 @@ static hipError_t for_format(int scale_kind, bool asym, F&& f) {
 }
 
 hipError_t launch_quantize_contig(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, int64_t rows,
-                                  int64_t K, int64_t row_stride, uint8_t* codes, uint8_t* scales, hipStream_t s) {
+                                  int64_t K, int64_t row_stride, const float* tensor_pair, uint8_t* codes,
+                                  uint8_t* scales, hipStream_t s) {
   const int gl = group_log2(group_size);
   if (gl < 0 || K % group_size != 0) return hipErrorInvalidValue;
   return for_format(scale_kind, asym, [&]<int SK, bool ASYM>() {
-    return launch_qc<SK, ASYM>(x, rows, K, gl, row_stride, codes, scales, s);
+    return launch_qc<SK, ASYM>(x, rows, K, gl, row_stride, tensor_pair, codes, scales, s);
   });
 }
 
 template <int SK, bool ASYM, int GS>
-static hipError_t launch_qs(const uint16_t* x, int64_t rows, int64_t K, int64_t k_stride, uint8_t* codes,
-                            uint8_t* scales, hipStream_t s) {
-  hipLaunchKernelGGL((quantize_strided_kernel<SK, ASYM, GS>), dim3((unsigned)((rows + 255) / 256), (unsigned)(K / GS)),
-                     dim3(256), 0, s, x, rows, K, k_stride, codes, scales);
+static hipError_t launch_qs(const uint16_t* x, int64_t rows, int64_t K, int64_t k_stride, const float* tensor_pair,
+                            uint8_t* codes, uint8_t* scales, hipStream_t s) {
+  const dim3 grid((unsigned)((rows + 255) / 256), (unsigned)(K / GS));
+  if (tensor_pair)
+    hipLaunchKernelGGL((quantize_strided_kernel<SK, ASYM, true, GS>), grid, dim3(256), 0, s, x, rows, K, k_stride,
+                       tensor_pair, codes, scales);
+  else
+    hipLaunchKernelGGL((quantize_strided_kernel<SK, ASYM, false, GS>), grid, dim3(256), 0, s, x, rows, K, k_stride,
+                       tensor_pair, codes, scales);
   return hipGetLastError();
 }
 
 hipError_t launch_quantize_strided(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, int64_t rows,
-                                   int64_t K, int64_t k_stride, uint8_t* codes, uint8_t* scales, hipStream_t s) {
+                                   int64_t K, int64_t k_stride, const float* tensor_pair, uint8_t* codes,
+                                   uint8_t* scales, hipStream_t s) {
   const int gl = group_log2(group_size);
   if (gl < 0 || K % group_size != 0) return hipErrorInvalidValue;
   return for_format(scale_kind, asym, [&]<int SK, bool ASYM>() {
     switch (gl) {
-      case 4: return launch_qs<SK, ASYM, 16>(x, rows, K, k_stride, codes, scales, s);
-      case 5: return launch_qs<SK, ASYM, 32>(x, rows, K, k_stride, codes, scales, s);
-      case 6: return launch_qs<SK, ASYM, 64>(x, rows, K, k_stride, codes, scales, s);
-      default: return launch_qs<SK, ASYM, 128>(x, rows, K, k_stride, codes, scales, s);
+      case 4: return launch_qs<SK, ASYM, 16>(x, rows, K, k_stride, tensor_pair, codes, scales, s);
+      case 5: return launch_qs<SK, ASYM, 32>(x, rows, K, k_stride, tensor_pair, codes, scales, s);
+      case 6: return launch_qs<SK, ASYM, 64>(x, rows, K, k_stride, tensor_pair, codes, scales, s);
+      default: return launch_qs<SK, ASYM, 128>(x, rows, K, k_stride, tensor_pair, codes, scales, s);
     }
   });
 }
 
 template <int SK, bool ASYM>
 static hipError_t launch_dq(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K, int gs_log2,
-                            void* out, int out_dtype, hipStream_t s) {
+                            const float* tensor_pair, void* out, int out_dtype, hipStream_t s) {
   const dim3 grid(grid_for(rows * (K / 8)));
   if (out_dtype == 1)
     hipLaunchKernelGGL((dequantize_kernel<SK, ASYM, true>), grid, dim3(256), 0, s, codes, scales, rows, K, gs_log2,
-                       out);
+                       tensor_pair, out);
   else
     hipLaunchKernelGGL((dequantize_kernel<SK, ASYM, false>), grid, dim3(256), 0, s, codes, scales, rows, K, gs_log2,
-                       out);
+                       tensor_pair, out);
   return hipGetLastError();
 }
 
 hipError_t launch_dequantize(int scale_kind, bool asym, int64_t group_size, const uint8_t* codes,
-                             const uint8_t* scales, int64_t rows, int64_t K, void* out, int out_dtype, hipStream_t s) {
+                             const uint8_t* scales, int64_t rows, int64_t K, const float* tensor_pair, void* out,
+                             int out_dtype, hipStream_t s) {
   const int gl = group_log2(group_size);
   if (gl < 0 || K % group_size != 0) return hipErrorInvalidValue;
   // E8M0 floor and round share the byte encoding
   return for_format(scale_kind == kScaleE8M0Round ? kScaleE8M0Floor : scale_kind, asym, [&]<int SK, bool ASYM>() {
-    return launch_dq<SK, ASYM>(codes, scales, rows, K, gl, out, out_dtype, s);
+    return launch_dq<SK, ASYM>(codes, scales, rows, K, gl, tensor_pair, out, out_dtype, s);
   });
+}
+
+hipError_t launch_tensor_scale(const uint16_t* x, int64_t rows, int64_t K, int64_t row_stride, float* pair,
+                               hipStream_t s) {
+  uint32_t* acc = reinterpret_cast<uint32_t*>(pair);
+  hipLaunchKernelGGL(tensor_amax_init_kernel, dim3(1), dim3(1), 0, s, acc);
+  // 8 workgroups per CU, grid-stride: few atomics on the one accumulator
+  const int amax_blocks = grid_for(rows * (K / 8)) < 2048 ? grid_for(rows * (K / 8)) : 2048;
+  hipLaunchKernelGGL(tensor_amax_kernel, dim3(amax_blocks), dim3(256), 0, s, x, rows, K, row_stride, acc);
+  hipLaunchKernelGGL(tensor_scale_finalize_kernel, dim3(1), dim3(1), 0, s, pair);
+  return hipGetLastError();
 }
 
 }  // namespace amx

@@ -62,12 +62,14 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef float f32x16 __attribute__((ext_vector_type(16)));  // accumulator of one 32x32 MFMA tile
 
 // Stores a wave's FM x FN accumulator tiles of 32x32 into C (row-major, leading dimension ldc), multiplied by
-// 2^SCALE_LOG2 (0, or the power of two that undoes an operand bias). row_base / col_base: first row / column of the wave's tiles.
+// 2^SCALE_LOG2 (0, or the power of two that undoes an operand bias) and, with ALPHA, by the run-time factor alpha.
+// row_base / col_base: first row / column of the wave's tiles.
 // Accumulator register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its tile. Rows >= M and columns
 // >= N (partial tiles) are skipped. Non-temporal stores: C is not read again by the kernel.
-template <int FM, int FN, int SCALE_LOG2 = 0>
+template <int FM, int FN, int SCALE_LOG2 = 0, bool ALPHA = false>
 __device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[FM][FN], float* __restrict__ Cb, int64_t M,
-                                              int64_t N, int64_t ldc, int64_t row_base, int64_t col_base) {
+                                              int64_t N, int64_t ldc, int64_t row_base, int64_t col_base,
+                                              float alpha = 1.0f) {
   // the lane number is taken from the hardware again here rather than kept alive (or spilled) across the main loop
   const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
 #pragma unroll
@@ -83,6 +85,7 @@ __device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[FM][FN], float
           if (row < M) {
             float c = acc[i][j][v];
             if constexpr (SCALE_LOG2 != 0) c *= (float)(1 << SCALE_LOG2);
+            if constexpr (ALPHA) c *= alpha;
             __builtin_nontemporal_store(c, Cb + row * ldc + col);
           }
         }

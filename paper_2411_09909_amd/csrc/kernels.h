@@ -20,13 +20,19 @@ inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 int report_error(int code, const char* msg);
 int report_hip_error(hipError_t e, const char* what);
 
-// cast.hip (group_size: 16, 32, 64 or 128, dividing K)
+// cast.hip (group_size: 16, 32, 64 or 128, dividing K; tensor_pair: device {S_t, 1 / S_t} of a tensor-wise scale,
+// or null for none)
 hipError_t launch_quantize_contig(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, int64_t rows,
-                                  int64_t K, int64_t row_stride, uint8_t* codes, uint8_t* scales, hipStream_t s);
+                                  int64_t K, int64_t row_stride, const float* tensor_pair, uint8_t* codes,
+                                  uint8_t* scales, hipStream_t s);
 hipError_t launch_quantize_strided(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, int64_t rows,
-                                   int64_t K, int64_t k_stride, uint8_t* codes, uint8_t* scales, hipStream_t s);
+                                   int64_t K, int64_t k_stride, const float* tensor_pair, uint8_t* codes,
+                                   uint8_t* scales, hipStream_t s);
 hipError_t launch_dequantize(int scale_kind, bool asym, int64_t group_size, const uint8_t* codes,
-                             const uint8_t* scales, int64_t rows, int64_t K, void* out, int out_dtype, hipStream_t s);
+                             const uint8_t* scales, int64_t rows, int64_t K, const float* tensor_pair, void* out,
+                             int out_dtype, hipStream_t s);
+hipError_t launch_tensor_scale(const uint16_t* x, int64_t rows, int64_t K, int64_t row_stride, float* pair,
+                               hipStream_t s);
 
 // Optional event pair recorded around the matrix-multiply kernel of one GEMM call (measurement aid).
 struct KernelTimer {
@@ -36,8 +42,10 @@ struct KernelTimer {
 // gemm_bf16.hip
 size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
 hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, int64_t M, int64_t N, int64_t K,
-                                 const uint8_t* A_codes, const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
-                                 int64_t ldc, int64_t batch, void* workspace, hipStream_t s, const KernelTimer& timer);
+                                 const uint8_t* A_codes, const uint8_t* A_scales, const uint8_t* B_codes,
+                                 const uint8_t* B_scales, const float* A_tensor_pair, const float* B_tensor_pair,
+                                 float* C, int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
+                                 const KernelTimer& timer);
 
 // FP16 fragment-major panel (values biased by 2^-3) of an operand with FP8-E5M2 scales; layout as the BF16 panels
 hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K,

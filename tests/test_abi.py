@@ -117,3 +117,27 @@ def test_layer_operators_reject_bad_arguments(lib):
     assert lib.amxfp4_residual_add(p, p, 6, p, None) == -1
     assert lib.amxfp4_merge_heads(p, 2, 2, 8, 6, p, None) == -1
     assert b"merge_heads" in lib.amxfp4_last_error()
+
+
+def test_double_scaling_and_measurement_calls_reject_bad_arguments(lib):
+    ok = binding.make_format(binding.FP8_E4M3, True, 16)
+    p = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
+    assert lib.amxfp4_tensor_scale(None, 4, 64, 64, p, None) == -1
+    assert lib.amxfp4_tensor_scale(p, 4, 60, 64, p, None) == -1               # K % 8
+    assert lib.amxfp4_tensor_scale(p, 4, 64, 32, p, None) == -1               # row stride shorter than a row
+    assert lib.amxfp4_tensor_scale(p, 4, 64, 64, ctypes.c_void_p(0x1004), None) == -1   # misaligned pair
+    assert lib.amxfp4_quantize_scaled(ctypes.byref(ok), p, 4, 64, 64, 1, None, p, p, None) == -1
+    assert b"scale_pair" in lib.amxfp4_last_error()
+    assert lib.amxfp4_quantize_scaled(ctypes.byref(ok), p, 4, 48, 48, 1, p, p, p, None) == -1   # K % 32
+    assert lib.amxfp4_dequantize_scaled(ctypes.byref(ok), p, p, 4, 64, None, p, None) == -1
+    g = lib.amxfp4_gemm_scaled
+    assert g(ctypes.byref(ok), 64, 64, 64, p, p, None, p, p, p, p, 64, 1, p, 1 << 30, None) == -1   # one pair missing
+    assert g(ctypes.byref(ok), 64, 64, 64, p, p, p, p, p, p, p, 64, 1, None, 0, None) == -3         # no workspace
+    assert lib.amxfp4_gemm_scaled_workspace_bytes(ctypes.byref(ok), 64, 1024, 1024, 1) == (256 + 1024) * 1024 * 2
+    # a power-of-two format still gets the BF16 workspace when a tensor-wise scale is applied
+    pot = binding.make_format(binding.E8M0_FLOOR, False, 32)
+    assert lib.amxfp4_gemm_scaled_workspace_bytes(ctypes.byref(pot), 64, 1024, 1024, 1) == (256 + 1024) * 1024 * 2
+    flops = ctypes.c_double()
+    assert lib.amxfp4_peak_mfma(5, p, 10, p, ctypes.byref(flops), None) == -1
+    assert lib.amxfp4_peak_mfma(0, p, 0, p, ctypes.byref(flops), None) == -1
+    assert lib.amxfp4_peak_copy(p, p, 24, None) == -1
