@@ -178,10 +178,47 @@ int amxfp4_tensor_scale_ref(const uint16_t* x_bf16, int64_t rows, int64_t K, int
 }
 
 /*
+ * One group: y[0..gs) are the values to quantize (single-precision numbers, of which BF16 inputs are a subset); the
+ * sign class of an element is its IEEE sign bit. Writes the group's scale byte(s) to sc and ORs the element codes
+ * into the (pre-zeroed) code row at element positions k0, k0 + 1, ...
+ */
+static void quantize_group(const ref_format_t* fmt, const float* y, int64_t gs, uint8_t* code_row, int64_t k0,
+                           uint8_t* sc) {
+  /* step 1-2: largest positive value and largest |negative value| of the group */
+  double amax_p = 0.0, amax_n = 0.0;
+  for (int64_t i = 0; i < gs; ++i) {
+    double v = (double)y[i];
+    if (signbit(y[i])) {
+      if (-v > amax_n) amax_n = -v;
+    } else {
+      if (v > amax_p) amax_p = v;
+    }
+  }
+  if (!fmt->asymmetric) amax_p = amax_n = (amax_p > amax_n ? amax_p : amax_n);
+  /* step 3: shared scale(s) */
+  uint8_t sb_p = amxfp4_scale_encode_ref(fmt->scale, amax_p);
+  uint8_t sb_n = amxfp4_scale_encode_ref(fmt->scale, amax_n);
+  sc[0] = sb_p;
+  if (fmt->asymmetric) sc[1] = sb_n;
+  /* a class with no magnitude stores byte 0 and quantizes to magnitude 0; an FP8 scale that rounded to zero
+   * decodes to 0 and does the same */
+  double S_p = amax_p > 0.0 ? amxfp4_scale_decode_ref(fmt->scale, sb_p) : 0.0;
+  double S_n = amax_n > 0.0 ? amxfp4_scale_decode_ref(fmt->scale, sb_n) : 0.0;
+  /* step 4-5: element codes, two per byte, low nibble first */
+  for (int64_t i = 0; i < gs; ++i) {
+    int neg = signbit(y[i]) != 0;
+    double a = fabs((double)y[i]);
+    uint8_t code = (uint8_t)((neg << 3) | amxfp4_elem_encode_ref(a, neg ? S_n : S_p));
+    int64_t k = k0 + i;
+    code_row[k / 2] |= (uint8_t)(code << (4 * (k & 1)));
+  }
+}
+
+/*
  * Direct cast with a tensor-wise scale (Sec. 5.3 double scaling; tensor_rcp = 1 is the plain cast of Algorithm 1 /
  * Eq. 1, for which the multiplication below is exact). Reading: every element is first multiplied by R_t in single
  * precision, y = float(x * R_t) (one rounding), and the group-wise algorithm then runs on the y values exactly as
- * it runs on BF16 values; the sign class is the sign bit of x.
+ * it runs on BF16 values (the multiplication by R_t > 0 keeps the sign bit, also of zeros).
  */
 int amxfp4_quantize_scaled_ref(const ref_format_t* fmt, const uint16_t* x_bf16, int64_t rows, int64_t K,
                                int64_t row_stride, int64_t k_stride, float tensor_rcp, uint8_t* codes,
@@ -193,43 +230,33 @@ int amxfp4_quantize_scaled_ref(const ref_format_t* fmt, const uint16_t* x_bf16, 
   memset(codes, 0, (size_t)(rows * K / 2));
 #pragma omp parallel for schedule(static)
   for (int64_t r = 0; r < rows; ++r) {
+    float* y = (float*)malloc(sizeof(float) * (size_t)gs);
     for (int64_t g = 0; g < G; ++g) {
       const uint16_t* xg = x_bf16 + r * row_stride + g * gs * k_stride;
-      /* step 1-2: largest positive value and largest |negative value| of the group */
-      double amax_p = 0.0, amax_n = 0.0;
       for (int64_t i = 0; i < gs; ++i) {
-        uint16_t b = xg[i * k_stride];
-        volatile float y = bf16_to_float(b) * tensor_rcp; /* one rounding to single precision */
-        double v = (double)y;
-        if (b & 0x8000) {
-          if (-v > amax_n) amax_n = -v;
-        } else {
-          if (v > amax_p) amax_p = v;
-        }
+        volatile float yi = bf16_to_float(xg[i * k_stride]) * tensor_rcp; /* one rounding to single precision */
+        y[i] = yi;
       }
-      if (!fmt->asymmetric) amax_p = amax_n = (amax_p > amax_n ? amax_p : amax_n);
-      /* step 3: shared scale(s) */
-      uint8_t sb_p = amxfp4_scale_encode_ref(fmt->scale, amax_p);
-      uint8_t sb_n = amxfp4_scale_encode_ref(fmt->scale, amax_n);
-      uint8_t* sc = scales + (r * G + g) * ns;
-      sc[0] = sb_p;
-      if (fmt->asymmetric) sc[1] = sb_n;
-      /* a class with no magnitude stores byte 0 and quantizes to magnitude 0; an FP8 scale that rounded to zero
-       * decodes to 0 and does the same */
-      double S_p = amax_p > 0.0 ? amxfp4_scale_decode_ref(fmt->scale, sb_p) : 0.0;
-      double S_n = amax_n > 0.0 ? amxfp4_scale_decode_ref(fmt->scale, sb_n) : 0.0;
-      /* step 4-5: element codes, two per byte, low nibble first */
-      for (int64_t i = 0; i < gs; ++i) {
-        uint16_t b = xg[i * k_stride];
-        int neg = (b & 0x8000) != 0;
-        volatile float y = bf16_to_float(b) * tensor_rcp;
-        double a = fabs((double)y);
-        uint8_t code = (uint8_t)((neg << 3) | amxfp4_elem_encode_ref(a, neg ? S_n : S_p));
-        int64_t k = g * gs + i;
-        codes[r * (K / 2) + k / 2] |= (uint8_t)(code << (4 * (k & 1)));
-      }
+      quantize_group(fmt, y, gs, codes + r * (K / 2), g * gs, scales + (r * G + g) * ns);
     }
+    free(y);
   }
+  return 0;
+}
+
+/* The same group-wise cast of single-precision values y [rows][K] (contiguous). Used where the values to quantize
+ * are produced in single precision rather than read as BF16 (the attention probabilities of a fused softmax). */
+int amxfp4_quantize_f32_ref(const ref_format_t* fmt, const float* y, int64_t rows, int64_t K, uint8_t* codes,
+                            uint8_t* scales) {
+  int64_t gs;
+  if (check_format(fmt, K, &gs) || !y || !codes || !scales || rows <= 0) return -1;
+  const int64_t G = K / gs;
+  const int ns = fmt->asymmetric ? 2 : 1;
+  memset(codes, 0, (size_t)(rows * K / 2));
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t g = 0; g < G; ++g)
+      quantize_group(fmt, y + r * K + g * gs, gs, codes + r * (K / 2), g * gs, scales + (r * G + g) * ns);
   return 0;
 }
 

@@ -51,6 +51,8 @@ def lib():
         L.amxfp4_quantize_scaled_ref.argtypes = [ctypes.POINTER(RefFormat), ctypes.c_void_p, i64, i64, i64, i64, f32,
                                                  u8p, u8p]
         L.amxfp4_quantize_scaled_ref.restype = ctypes.c_int
+        L.amxfp4_quantize_f32_ref.argtypes = [ctypes.POINTER(RefFormat), ctypes.c_void_p, i64, i64, u8p, u8p]
+        L.amxfp4_quantize_f32_ref.restype = ctypes.c_int
         L.amxfp4_gemm_scaled_ref.argtypes = [ctypes.POINTER(RefFormat), i64, i64, i64, u8p, u8p, f32, u8p, u8p, f32,
                                              ctypes.c_void_p, i64, i64]
         L.amxfp4_gemm_scaled_ref.restype = ctypes.c_int
@@ -104,6 +106,21 @@ def quantize(x_bf16, group_size=32, scale=FP8_E5M2, asymmetric=True, k_axis=-1, 
                                           scales.ctypes.data)
     if rc:
         raise ValueError("amxfp4_quantize_scaled_ref failed: %d" % rc)
+    return codes, scales
+
+
+def quantize_f32(y, group_size=32, scale=FP8_E5M2, asymmetric=True):
+    """The group-wise cast of single-precision values: y 2-D float32, groups along each row. Returns (codes, scales)."""
+    y = np.ascontiguousarray(y, np.float32)
+    assert y.ndim == 2
+    rows, K = y.shape
+    G = _groups(K, group_size)
+    codes = np.zeros((rows, K // 2), np.uint8)
+    scales = np.zeros((rows, G, 2) if asymmetric else (rows, G), np.uint8)
+    f = _fmt(group_size, scale, asymmetric)
+    rc = lib().amxfp4_quantize_f32_ref(ctypes.byref(f), y.ctypes.data, rows, K, codes.ctypes.data, scales.ctypes.data)
+    if rc:
+        raise ValueError("amxfp4_quantize_f32_ref failed: %d" % rc)
     return codes, scales
 
 
