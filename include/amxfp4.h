@@ -167,6 +167,32 @@ int amxfp4_gemm_scaled(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Fused quantized attention. The paper quantizes both attention products (Sec. 5.1: Q.K^T and the attention map
+ * times V) and defines no fused kernel; this entry point computes them tile by tile without materialising the map.
+ * Per query head h (reading key/value head h / (q_heads / kv_heads)) and query i, over key tiles of 32 in ascending
+ * order:   s_j = scale * sum_d Q_hat[i, d] K_hat[j, d]   (causal != 0: keys j > i + Sk - Sq are masked; tiles without
+ * an unmasked key are skipped);   m' = max(m, max_j s_j);   p_j = exp(s_j - m') (0 when masked);
+ * l = l exp(m - m') + sum_j p_j;   p_hat = the 32 values p_j cast as ONE group of `fmt` and dequantized;
+ * O = O exp(m - m') + sum_j p_hat_j V_hat[j, :];   finally out[h, i, :] = O / l.   FP32 arithmetic outside the matrix
+ * products, whose operands are exact BF16 values. This is not the same number as quantizing the normalised map
+ * (amxfp4_gemm on a softmax output): the probabilities are cast relative to the running maximum.
+ *   Q_codes/Q_scales   [q_heads][Sq][head_dim] operand cast along head_dim (amxfp4_quantize, k_stride 1).
+ *   K_codes/K_scales   [kv_heads][Sk][head_dim] likewise.
+ *   V_codes/V_scales   [kv_heads][head_dim][Sk] operand: V^T, cast along the keys (amxfp4_quantize on each head's
+ *                      [Sk][head_dim] matrix with row_stride 1, k_stride head_dim).
+ *   out                device, [q_heads][Sq][head_dim] floats, 16-byte aligned.
+ *   fmt->group_size must be 32 and head_dim 128 (AMX_ERR_UNSUPPORTED otherwise); Sk % 32 == 0; causal needs Sk >= Sq.
+ *   workspace          at least amxfp4_attention_workspace_bytes() bytes, 256-byte aligned.
+ * amxfp4_profile_next_gemm also arms this call (events around the attention kernel proper).
+ */
+size_t amxfp4_attention_workspace_bytes(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq,
+                                        int64_t Sk, int64_t head_dim);
+int amxfp4_attention(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq, int64_t Sk,
+                     int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
+                     const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
+                     int32_t causal, float* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid (not part of the method): arms a pair of caller-owned hipEvent_t (passed as void*) for the NEXT
  * amxfp4_gemm / mxfp4_gemm call made on this host thread. That call records `start` on its stream immediately before
  * and `stop` immediately after the launch of its matrix-multiply kernel (the MFMA main loop, excluding the operand

@@ -63,6 +63,11 @@ def load():
         getattr(L, name).restype = ctypes.c_int
     L.amxfp4_gemm_scaled_workspace_bytes.argtypes = [fp, i64, i64, i64, i64]
     L.amxfp4_gemm_scaled_workspace_bytes.restype = ctypes.c_size_t
+    L.amxfp4_attention_workspace_bytes.argtypes = [fp, i64, i64, i64, i64, i64]
+    L.amxfp4_attention_workspace_bytes.restype = ctypes.c_size_t
+    L.amxfp4_attention.argtypes = [fp, i64, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, f32, i32, vp, vp,
+                                   ctypes.c_size_t, vp]
+    L.amxfp4_attention.restype = ctypes.c_int
     L.amxfp4_peak_mfma.argtypes = [i32, vp, i32, vp, ctypes.POINTER(f64), vp]
     L.amxfp4_peak_mfma.restype = ctypes.c_int
     L.amxfp4_peak_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
@@ -252,6 +257,30 @@ def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, ba
     _check(_fn(fmt, "gemm", baseline)(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
                                       b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(), out.stride(-2), batch,
                                       ws_ptr, ws_len, _stream()))
+    return out
+
+
+def attention(fmt, q_codes, q_scales, k_codes, k_scales, v_codes, v_scales, scale, causal=True, out=None,
+              workspace=None):
+    """Fused quantized attention. q_codes [Hq, Sq, D/2], k_codes [Hkv, Sk, D/2] (cast along D), v_codes
+    [Hkv, D, Sk/2] (each head's V cast along the keys, k_axis=0), scales to match. Returns FP32 [Hq, Sq, D]."""
+    ts = (q_codes, q_scales, k_codes, k_scales, v_codes, v_scales)
+    _need_cuda(*ts)
+    for t in ts:
+        assert t.is_contiguous()
+    Hq, Sq, D = q_codes.shape[0], q_codes.shape[1], q_codes.shape[2] * 2
+    Hkv, Sk = k_codes.shape[0], k_codes.shape[1]
+    assert k_codes.shape[2] * 2 == D and tuple(v_codes.shape) == (Hkv, D, Sk // 2)
+    if out is None:
+        out = torch.empty((Hq, Sq, D), dtype=torch.float32, device=q_codes.device)
+    need = load().amxfp4_attention_workspace_bytes(ctypes.byref(fmt), Hq, Hkv, Sq, Sk, D)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q_codes.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().amxfp4_attention(ctypes.byref(fmt), Hq, Hkv, Sq, Sk, D, q_codes.data_ptr(), q_scales.data_ptr(),
+                                   k_codes.data_ptr(), k_scales.data_ptr(), v_codes.data_ptr(), v_scales.data_ptr(),
+                                   float(scale), int(bool(causal)), out.data_ptr(), ws_ptr, ws_len, _stream()))
     return out
 
 

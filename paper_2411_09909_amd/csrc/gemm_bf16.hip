@@ -34,7 +34,11 @@ size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch)
 // lane = 32 * group_in_slice + row_in_block. The 16 fragments a workgroup writes are contiguous in the panel.
 // F16: the panel holds FP16 values biased by 2^-3 instead of BF16 (FP8-E5M2 scales only: every such value lies in
 // [2^-20, 43008] and has at most 5 significant bits, so it is an FP16 number, subnormals included).
-template <int SCALE_KIND, bool ASYM, bool F16>
+// PERMUTE: within every block of 32 along K, the fragment of k-step j (0, 1) holds, in lane half h, the elements
+// 16 j + 4 h + {0, 1, 2, 3, 8, 9, 10, 11} instead of 16 j + 8 h + {0 .. 7}. That is the order in which the rows of a
+// 32x32 MFMA accumulator sit in a lane's registers, so an accumulator tile can be fed back as the other operand of a
+// product over those rows without a transpose (the fused attention kernel multiplies probabilities with V this way).
+template <int SCALE_KIND, bool ASYM, bool F16, bool PERMUTE = false>
 __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__ codes,
                                                      const uint8_t* __restrict__ scales, int64_t R, int64_t K,
                                                      int64_t Rp, int64_t Kp, int gs_log2,
@@ -75,21 +79,29 @@ __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__
     s_neg[h] *= F16 ? -0.0625f : -0.5f;
   }
   uint16_t* dst = panel + ((b * (Rp >> 5) + rb) * (Kp >> 4) + slice * 4 + (lane >> 5) * 2) * 512;
+  uint32_t o[4][4];  // run t of 8 elements of the block -> 4 registers of 2 values
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {  // t-th run of 8 elements of the group: k block (t / 2), half (t % 2)
-    uint32_t o[4];
+  for (int t = 0; t < 4; ++t) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const uint32_t n0 = (w[t] >> (8 * j)) & 15u, n1 = (w[t] >> (8 * j + 4)) & 15u;
       const float v0 = (float)e2m1_twice(n0 & 7u) * ((n0 & 8u) ? s_neg[t >> 1] : s_pos[t >> 1]);
       const float v1 = (float)e2m1_twice(n1 & 7u) * ((n1 & 8u) ? s_neg[t >> 1] : s_pos[t >> 1]);
       if constexpr (F16)
-        o[j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(v0, v1));  // exact, see above
+        o[t][j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(v0, v1));  // exact, see above
       else
-        o[j] = (f2u(v0) >> 16) | (f2u(v1) & 0xFFFF0000u);  // truncation is exact: <= 6 significant bits
+        o[t][j] = (f2u(v0) >> 16) | (f2u(v1) & 0xFFFF0000u);  // truncation is exact: <= 6 significant bits
     }
-    *reinterpret_cast<uint4*>(dst + (t >> 1) * 512 + ((t & 1) * 32 + (lane & 31)) * 8) =
-        make_uint4(o[0], o[1], o[2], o[3]);
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {  // k block (t / 2), lane half (t % 2) of the block's two fragments
+    uint4 out;
+    if constexpr (PERMUTE)
+      out = make_uint4(o[t & 2][2 * (t & 1)], o[t & 2][2 * (t & 1) + 1], o[(t & 2) + 1][2 * (t & 1)],
+                       o[(t & 2) + 1][2 * (t & 1) + 1]);
+    else
+      out = make_uint4(o[t][0], o[t][1], o[t][2], o[t][3]);
+    *reinterpret_cast<uint4*>(dst + (t >> 1) * 512 + ((t & 1) * 32 + (lane & 31)) * 8) = out;
   }
 }
 
@@ -254,6 +266,23 @@ static hipError_t expand_dispatch(int scale_kind, bool asym, int gs_log2, const 
                 : launch_expand<kScaleE4M3, false>(codes, scales, R, K, Rp, Kp, gs_log2, batch, panel, s);
   return asym ? launch_expand<kScaleE8M0Floor, true>(codes, scales, R, K, Rp, Kp, gs_log2, batch, panel, s)
               : launch_expand<kScaleE8M0Floor, false>(codes, scales, R, K, Rp, Kp, gs_log2, batch, panel, s);
+}
+
+hipError_t launch_expand_bf16(int scale_kind, bool asym, int64_t group_size, const uint8_t* codes,
+                              const uint8_t* scales, int64_t R, int64_t K, int64_t Rp, int64_t Kp, int64_t batch,
+                              bool permute, uint16_t* panel, hipStream_t s) {
+  const int gs_log2 = group_size == 16 ? 4 : group_size == 32 ? 5 : group_size == 64 ? 6 : group_size == 128 ? 7 : -1;
+  if (gs_log2 < 0 || K % group_size != 0 || K % 32 != 0 || Rp % 32 != 0 || Kp % 64 != 0) return hipErrorInvalidValue;
+  if (!permute) return expand_dispatch(scale_kind, asym, gs_log2, codes, scales, R, K, Rp, Kp, batch, panel, s);
+  const dim3 grid((unsigned)((Kp + 255) / 256), (unsigned)(Rp / 32), (unsigned)batch);
+  auto go = [&]<int SK, bool ASYM>() {
+    hipLaunchKernelGGL((expand_kernel<SK, ASYM, false, true>), grid, dim3(256), 0, s, codes, scales, R, K, Rp, Kp,
+                       gs_log2, panel);
+    return hipGetLastError();
+  };
+  if (scale_kind == kScaleE5M2) return asym ? go.template operator()<kScaleE5M2, true>() : go.template operator()<kScaleE5M2, false>();
+  if (scale_kind == kScaleE4M3) return asym ? go.template operator()<kScaleE4M3, true>() : go.template operator()<kScaleE4M3, false>();
+  return asym ? go.template operator()<kScaleE8M0Floor, true>() : go.template operator()<kScaleE8M0Floor, false>();
 }
 
 hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K,

@@ -47,6 +47,19 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
                                  float* C, int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
                                  const KernelTimer& timer);
 
+// BF16 fragment-major panel [batch][Rp / 32][Kp / 16][64 lanes][8] of a quantized operand (rows >= R and columns >= K
+// zero; Rp % 32 == 0, Kp % 64 == 0). permute: the key order of the fused attention kernel's V operand (gemm_bf16.hip).
+hipError_t launch_expand_bf16(int scale_kind, bool asym, int64_t group_size, const uint8_t* codes,
+                              const uint8_t* scales, int64_t R, int64_t K, int64_t Rp, int64_t Kp, int64_t batch,
+                              bool permute, uint16_t* panel, hipStream_t s);
+
+// attention.hip: fused quantized attention, head dimension 128, groups of 32 (workspace: the three BF16 panels)
+size_t attention_workspace_bytes(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk);
+hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk,
+                                  const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
+                                  const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
+                                  int causal, float* out, void* workspace, hipStream_t s, const KernelTimer& timer);
+
 // FP16 fragment-major panel (values biased by 2^-3) of an operand with FP8-E5M2 scales; layout as the BF16 panels
 hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K,
                                   int64_t Rp, int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s);

@@ -1,0 +1,110 @@
+"""GPU parity of the fused quantized attention against its CPU oracle (oracle/attention_ref.py). The two sides
+evaluate exp in different precisions (FP32 hardware exp2 against float64), so a probability can, rarely, fall on the
+other side of a rounding boundary of the 4-bit cast; the outputs are therefore compared within a tolerance: relative
+Frobenius error <= 1e-3 overall (the tolerance of the matrix products) and <= 2e-2 on every single query row."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention_ref, ref
+from paper_2411_09909_amd import binding, synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+D = 128
+
+
+def heads(n, S, seed, gain=1.0):
+    x = synth.activations(n * S, D, seed=seed, n_outlier=2, outlier_gain=20.0)
+    return synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(x) * np.float32(gain)).reshape(n, S, D)
+
+
+def gpu_attention(q, k, v, scale, causal, scale_format, asym):
+    fmt = binding.make_format(scale_format, asym, 32)
+    Hq, Sq, _ = q.shape
+    Hkv, Sk, _ = k.shape
+    qc, qs = binding.quantize(fmt, G.to_dev_bf16(q.reshape(Hq * Sq, D)))
+    kc, ks = binding.quantize(fmt, G.to_dev_bf16(k.reshape(Hkv * Sk, D)))
+    vd = G.to_dev_bf16(v.reshape(Hkv * Sk, D)).view(Hkv, Sk, D)
+    vcs = [binding.quantize(fmt, vd[g], k_axis=0) for g in range(Hkv)]
+    vc, vs = torch.stack([t[0] for t in vcs]), torch.stack([t[1] for t in vcs])
+    ns = qs.shape[1:]
+    out = binding.attention(fmt, qc.view(Hq, Sq, -1), qs.view(Hq, Sq, *ns), kc.view(Hkv, Sk, -1),
+                            ks.view(Hkv, Sk, *ns), vc, vs, scale, causal)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def compare(out, want):
+    assert out.shape == want.shape and np.isfinite(out).all()
+    assert G.rel_fro(out, want) <= 1e-3
+    num = np.linalg.norm((out - want).reshape(-1, D).astype(np.float64), axis=1)
+    den = np.linalg.norm(want.reshape(-1, D).astype(np.float64), axis=1)
+    assert (num <= 2e-2 * den + 1e-30).all(), "worst row %g" % float((num / np.maximum(den, 1e-30)).max())
+
+
+FORMATS = [(ref.FP8_E5M2, 1), (ref.FP8_E5M2, 0), (ref.E8M0_FLOOR, 1), (ref.FP8_E4M3, 1), (ref.E8M0_ROUND, 0)]
+
+
+@pytest.mark.parametrize("scale_format,asym", FORMATS)
+@pytest.mark.parametrize("causal", [True, False])
+def test_square_attention_several_tiles(scale_format, asym, causal):
+    """Two query heads, 320 tokens: two workgroups per head (the second with two active waves), 10 key tiles."""
+    q, k, v = heads(2, 320, 1), heads(2, 320, 2), heads(2, 320, 3)
+    want = attention_ref.fused_attention(q, k, v, D ** -0.5, causal, scale_format, asym)
+    compare(gpu_attention(q, k, v, D ** -0.5, causal, scale_format, asym), want)
+
+
+@pytest.mark.parametrize("Hq,Hkv,Sq,Sk,causal", [(4, 2, 96, 96, True), (2, 1, 40, 128, True), (3, 3, 50, 64, False),
+                                                 (1, 1, 1, 32, True), (2, 2, 33, 96, True), (8, 2, 64, 160, False)])
+def test_grouped_heads_ragged_queries_and_longer_keys(Hq, Hkv, Sq, Sk, causal):
+    """Query heads sharing a key/value head; Sq not a multiple of 32 (padded query rows are not stored); Sq < Sk
+    (queries aligned to the end of the keys); Sk not a multiple of 64 (the V panel pads its key axis); one query."""
+    q, k, v = heads(Hq, Sq, 4), heads(Hkv, Sk, 5), heads(Hkv, Sk, 6)
+    want = attention_ref.fused_attention(q, k, v, D ** -0.5, causal)
+    compare(gpu_attention(q, k, v, D ** -0.5, causal, ref.FP8_E5M2, 1), want)
+
+
+def test_closed_forms_on_the_gpu():
+    """Q = 0: every probability is 1, cast to 0.9375 (scale RNE(1/6) = 0.15625, element 6); out[i] = 0.9375 * mean of
+    V_hat[0 .. i]. And scaled inputs: large scores (one dominant key per row) must not overflow."""
+    S = 96
+    q = np.zeros((1, S, D), np.uint16)
+    k, v = heads(1, S, 7), heads(1, S, 8)
+    out = gpu_attention(q, k, v, 0.1, True, ref.FP8_E5M2, 1)
+    vc, vs = ref.quantize(np.ascontiguousarray(v[0]), 32, ref.FP8_E5M2, 1, k_axis=0)
+    vh = ref.dequantize(vc, vs, 32, ref.FP8_E5M2, 1).T
+    want = 0.9375 * np.cumsum(vh, axis=0) / np.arange(1, S + 1)[:, None]
+    assert np.allclose(out[0], want, rtol=2e-6, atol=1e-6)
+    q, k = heads(1, S, 9, gain=30.0), heads(1, S, 10, gain=30.0)
+    want = attention_ref.fused_attention(q, k, v, D ** -0.5, True)
+    compare(gpu_attention(q, k, v, D ** -0.5, True, ref.FP8_E5M2, 1), want)
+
+
+def test_causality_on_the_gpu():
+    """Changing keys and values after position 40 leaves the output rows before 32 bit-identical (rows 32..39 share
+    their V group with the changed rows)."""
+    S = 128
+    q, k, v = heads(2, S, 11), heads(2, S, 12), heads(2, S, 13)
+    base = gpu_attention(q, k, v, D ** -0.5, True, ref.FP8_E5M2, 1)
+    k2, v2 = k.copy(), v.copy()
+    k2[:, 40:] = heads(2, S - 40, 14)
+    v2[:, 40:] ^= np.uint16(0x8000)
+    out = gpu_attention(q, k2, v2, D ** -0.5, True, ref.FP8_E5M2, 1)
+    assert np.array_equal(out[:, :32], base[:, :32]) and not np.array_equal(out[:, 40:], base[:, 40:])
+
+
+def test_invalid_arguments():
+    fmt = binding.make_format(ref.FP8_E5M2, 1, 32)
+    z = lambda *s: torch.zeros(s, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.AmxError):   # causal with fewer keys than queries
+        binding.attention(fmt, z(1, 64, 64), z(1, 64, 4, 2), z(1, 32, 64), z(1, 32, 4, 2), z(1, 128, 16), z(1, 128, 1, 2),
+                          0.1, True)
+    with pytest.raises(binding.AmxError):   # head dimension 64
+        binding.attention(fmt, z(1, 32, 32), z(1, 32, 2, 2), z(1, 32, 32), z(1, 32, 2, 2), z(1, 64, 16), z(1, 64, 1, 2),
+                          0.1, True)
+    f16 = binding.make_format(ref.FP8_E5M2, 1, 16)
+    with pytest.raises(binding.AmxError):   # groups of 16
+        binding.attention(f16, z(1, 32, 64), z(1, 32, 8, 2), z(1, 32, 64), z(1, 32, 8, 2), z(1, 128, 16),
+                          z(1, 128, 2, 2), 0.1, True)
