@@ -28,7 +28,8 @@ constexpr int kAttnWaves = 8;               // waves per workgroup, 32 queries e
 constexpr int kAttnQ = 32 * kAttnWaves;     // queries per workgroup
 constexpr int kAttnKFrags = kAttnD / 16;    // K fragments of one key tile (one per 16 of D)
 constexpr int kAttnVFrags = (kAttnD / 32) * 2;  // V^T fragments of one key tile: D / 32 row blocks x 2 k-steps
-static_assert(kAttnKFrags == kAttnWaves && kAttnVFrags == kAttnWaves, "one K and one V fragment per wave and tile");
+constexpr int kAttnLoads = kAttnKFrags / kAttnWaves;  // K (and V) fragments a wave brings in per key tile
+static_assert(kAttnKFrags == kAttnVFrags && kAttnKFrags % kAttnWaves == 0, "fragments must divide over the waves");
 
 template <int SCALE_KIND>
 __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
@@ -43,8 +44,15 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int h = blockIdx.y, g = h / kv_group;
-  const int q0 = blockIdx.x * kAttnQ, qw = q0 + wave * 32;
+  // Workgroups are dealt to the 8 XCDs round-robin by their linear id (x fastest). x walks the query heads, so every
+  // XCD gets the same mix of light and heavy query blocks of a causal problem, and (when the head count is a multiple
+  // of 8) a contiguous range of heads, i.e. heads that share a key/value head share an L2. y walks the query blocks,
+  // last block first: under a causal mask those have the most key tiles and should start first.
+  const int nheads = (int)gridDim.x;
+  const int h = (nheads & 7) == 0 ? (int)(blockIdx.x & 7) * (nheads >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+  const int g = h / kv_group;
+  const int qblock = (int)(gridDim.y - 1 - blockIdx.y);
+  const int q0 = qblock * kAttnQ, qw = q0 + wave * 32;
   const int off = Sk - Sq;  // causal: query i sees keys <= i + off
   const bool wave_active = qw < Sqp;
 
@@ -64,15 +72,16 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
   const __amdgpu_buffer_rsrc_t Vr =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(Vbase), 0, (int)(vfrags_head * kFragBytes), 0x00020000);
   const int lane_off = lane * 16;
-  const int v_frag_off = (wave >> 1) * (Skv / 16) + (wave & 1);  // this wave's V fragment: row block wave / 2, k-step wave % 2
 
-  // wave w brings K fragment w and V fragment w of tile T into stage (DK, DV)
+  // wave w brings K fragments w, w + kAttnWaves, .. and the V fragments of the same numbers (V fragment f = row block
+  // f / 2, k-step f % 2) of tile T into stage (DK, DV)
 #define AMX_ATTN_LOAD(T, DK, DV)                                                                                   \
-  {                                                                                                                \
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(Kr, (lds_ptr_t)((DK) + wave * kFragBytes), 16, lane_off,              \
-                                             ((T) * kAttnKFrags + wave) * kFragBytes, 0, 0);                       \
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(Vr, (lds_ptr_t)((DV) + wave * kFragBytes), 16, lane_off,              \
-                                             (v_frag_off + 2 * (T)) * kFragBytes, 0, 0);                           \
+  _Pragma("unroll") for (int i_ = 0; i_ < kAttnLoads; ++i_) {                                                      \
+    const int f_ = wave + kAttnWaves * i_;                                                                         \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(Kr, (lds_ptr_t)((DK) + f_ * kFragBytes), 16, lane_off,                \
+                                             ((T) * kAttnKFrags + f_) * kFragBytes, 0, 0);                         \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(Vr, (lds_ptr_t)((DV) + f_ * kFragBytes), 16, lane_off,                \
+                                             ((f_ >> 1) * (Skv / 16) + (f_ & 1) + 2 * (T)) * kFragBytes, 0, 0);    \
   }
 
   // this wave's 32 queries as the B operand of the first product: 8 k-steps over D, resident in registers
@@ -92,7 +101,7 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
   for (int db = 0; db < kAttnD / 32; ++db)
 #pragma unroll
     for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-  float m = -__builtin_inff(), l = 0.f;  // running maximum (in units of log2) and sum of this lane's query
+  float m = -__builtin_inff(), l = 0.f;  // running maximum (scaled score, in units of log2) and sum of this lane's query
   const int limit = causal ? qw + (lane & 31) + off : Sk - 1;  // last key this lane's query may attend to
   const int row_in_tile = 4 * (lane >> 5);                    // key of register v: 8 (v / 4) + row_in_tile + v % 4
 
@@ -115,28 +124,31 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
       mx = fmaxf(mx, x[v]);                                                                                        \
     }                                                                                                              \
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                                                        \
+    /* The subtraction below is exact 0 for the score that holds the maximum, so its probability is exactly 1, as \
+       in exact arithmetic (folding the scale into an FMA here would make it 1 - 2^-24 now and then, and a floored \
+       power-of-two scale of the tile would halve). */                                                            \
     const float m_new = fmaxf(m, mx);                                                                              \
     const float alpha = __builtin_amdgcn_exp2f(m - m_new);                                                         \
-    float psum = 0.f, pmax = 0.f;                                                                                  \
+    /* exp is monotonic: the largest probability of the tile is the one of the largest score */                   \
+    const float pmax = __builtin_amdgcn_exp2f(mx - m_new);                                                         \
+    float psum = 0.f;                                                                                              \
     _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                                               \
       x[v] = __builtin_amdgcn_exp2f(x[v] - m_new);                                                                 \
       psum += x[v];                                                                                                \
-      pmax = fmaxf(pmax, x[v]);                                                                                    \
     }                                                                                                              \
     psum += __shfl_xor(psum, 32, 64);                                                                              \
-    pmax = fmaxf(pmax, __shfl_xor(pmax, 32, 64));                                                                  \
     l = l * alpha + psum;                                                                                          \
     m = m_new;                                                                                                     \
-    /* cast the 32 probabilities of each query as one group and take the dequantized values as BF16 */            \
+    /* cast the 32 probabilities of each query as one group and take the dequantized values as BF16. The quotient \
+       p / S is taken as p * (1 / S): its error of an ulp or two is that of the hardware exp2 which produced p. */  \
     float S, R;                                                                                                    \
     (void)encode_scale_sr<SCALE_KIND>(pmax, S, R);                                                                 \
     uint32_t pb[8];                                                                                                \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
-      const float z0 = quotient<SCALE_KIND>(x[2 * i], S, R), z1 = quotient<SCALE_KIND>(x[2 * i + 1], S, R);        \
-      const uint32_t code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, z0, z1, 1.0f, 0);                         \
+      const uint32_t code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x[2 * i] * R, x[2 * i + 1] * R, 1.0f, 0); \
       const f32x2 e = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(code, 1.0f, 0);                                     \
       /* element * scale has at most 6 significant bits: the truncation to BF16 is exact */                       \
-      pb[i] = (f2u(e[0] * S) >> 16) | (f2u(e[1] * S) & 0xFFFF0000u);                                               \
+      pb[i] = __builtin_amdgcn_perm(f2u(e[1] * S), f2u(e[0] * S), 0x07060302u);                                    \
     }                                                                                                              \
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) { /* the maximum moved for some query: rescale */        \
       _Pragma("unroll") for (int db = 0; db < kAttnD / 32; ++db)                                                   \
@@ -195,7 +207,7 @@ template <int SK>
 static hipError_t launch_attn(const uint16_t* Qp, const uint16_t* Kp, const uint16_t* Vp, float* out, int64_t Hq,
                               int64_t Hkv, int64_t Sq, int64_t Sk, float scale, int causal, hipStream_t s) {
   const int64_t Sqp = round_up(Sq, 32);
-  const dim3 grid((unsigned)((Sqp + kAttnQ - 1) / kAttnQ), (unsigned)Hq);
+  const dim3 grid((unsigned)Hq, (unsigned)((Sqp + kAttnQ - 1) / kAttnQ));
   hipLaunchKernelGGL((attention_fused_kernel<SK>), grid, dim3(64 * kAttnWaves), 0, s, Qp, Kp, Vp, out, (int)Sq,
                      (int)Sk, (int)Sqp, (int)round_up(Sk, 64), (int)(Hq / Hkv), scale * 1.4426950408889634f, causal);
   return hipGetLastError();
