@@ -14,7 +14,7 @@ tensors of such a layer live; matmul outputs are FP32 as the library's GEMM retu
 """
 import numpy as np
 
-from . import ref
+from . import attention_ref, ref
 
 
 def bf16_from_f64(x):
@@ -92,9 +92,10 @@ def _matmul(a_bits, b_codes_scales, scale, asym):
     return ref.gemm(ac, as_, b_codes_scales[0], b_codes_scales[1], 32, scale, asym)
 
 
-def decoder_layer(x_bits, w, cfg, scale=ref.FP8_E5M2, asym=1, pos0=0):
+def decoder_layer(x_bits, w, cfg, scale=ref.FP8_E5M2, asym=1, pos0=0, fused_attention=False):
     """x_bits [S, d_model] BF16 bits; w: dict of BF16-bit weight matrices wq wk wv wo wg wu wd ([out, in]) and float32
     norm1 / norm2; cfg: object with d_model, n_heads, n_kv_heads, head_dim, d_ff, eps, rope_theta.
+    fused_attention: the tile-wise attention of attention_ref instead of the materialised, normalised map.
     Returns the layer output as BF16 bits [S, d_model]."""
     S, G, D, H = x_bits.shape[0], cfg.n_kv_heads, cfg.head_dim, cfg.n_heads
     per = H // G
@@ -108,6 +109,10 @@ def decoder_layer(x_bits, w, cfg, scale=ref.FP8_E5M2, asym=1, pos0=0):
     k = split_heads_rope(qkv, H * D, G, D, True, pos0, cfg.rope_theta)
     v = split_heads_rope(qkv, (H + G) * D, G, D, False)
 
+    if fused_attention:
+        o = attention_ref.fused_attention(q, k, v, 1.0 / np.sqrt(np.float64(D)), True, scale, asym)   # [H, S, D]
+        attn = merge_heads(o.reshape(G, per * S, D), G, per, S, D)
+        return _after_attention(x_bits, attn, w, cfg, wo, wgu, wd, scale, asym)
     qc, qs = ref.quantize(q.reshape(H * S, D), 32, scale, asym)
     kc, ks = ref.quantize(k.reshape(G * S, D), 32, scale, asym)
     nsc = qs.shape[2:]
@@ -119,7 +124,10 @@ def decoder_layer(x_bits, w, cfg, scale=ref.FP8_E5M2, asym=1, pos0=0):
     vc, vs = np.stack([t[0] for t in vcs]), np.stack([t[1] for t in vcs])
     o = ref.gemm(pc.reshape(G, per * S, -1), ps.reshape(G, per * S, S // 32, *nsc), vc, vs, 32, scale, asym)
     attn = merge_heads(o, G, per, S, D)
+    return _after_attention(x_bits, attn, w, cfg, wo, wgu, wd, scale, asym)
 
+
+def _after_attention(x_bits, attn, w, cfg, wo, wgu, wd, scale, asym):
     x2 = residual_add(x_bits, _matmul(attn, wo, scale, asym))
     h2 = rmsnorm(x2, w["norm2"], cfg.eps)
     act = silu_mul(_matmul(h2, wgu, scale, asym))

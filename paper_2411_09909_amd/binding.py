@@ -260,6 +260,10 @@ def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, ba
     return out
 
 
+def attention_workspace_bytes(fmt, q_heads, kv_heads, Sq, Sk, head_dim=128):
+    return int(load().amxfp4_attention_workspace_bytes(ctypes.byref(fmt), q_heads, kv_heads, Sq, Sk, head_dim))
+
+
 def attention(fmt, q_codes, q_scales, k_codes, k_scales, v_codes, v_scales, scale, causal=True, out=None,
               workspace=None):
     """Fused quantized attention. q_codes [Hq, Sq, D/2], k_codes [Hkv, Sk, D/2] (cast along D), v_codes
@@ -273,7 +277,7 @@ def attention(fmt, q_codes, q_scales, k_codes, k_scales, v_codes, v_scales, scal
     assert k_codes.shape[2] * 2 == D and tuple(v_codes.shape) == (Hkv, D, Sk // 2)
     if out is None:
         out = torch.empty((Hq, Sq, D), dtype=torch.float32, device=q_codes.device)
-    need = load().amxfp4_attention_workspace_bytes(ctypes.byref(fmt), Hq, Hkv, Sq, Sk, D)
+    need = attention_workspace_bytes(fmt, Hq, Hkv, Sq, Sk, D)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q_codes.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None

@@ -12,6 +12,9 @@ MLP width F:
                                                                                 its columns)
   x2     = x + cast(merge(o)) . Wo^T
   out    = x2 + cast(silu(g) * u) . Wd^T,  (g | u) = cast(rmsnorm(x2)) . Wgu^T
+With fused_attention=True the two attention products and the softmax between them are one call (binding.attention):
+the attention map is not materialised and its tiles are cast relative to the running row maximum, which gives
+slightly different numbers than casting the normalised map.
 """
 import math
 from dataclasses import dataclass
@@ -42,8 +45,8 @@ class DecoderLayer:
     """weights: dict name -> BF16 CUDA tensor (WEIGHT_SHAPES) plus "norm1" / "norm2" FP32 [d_model]. The weights are
     cast once here (they are static in inference); forward() casts the activations."""
 
-    def __init__(self, cfg, weights, fmt, baseline=False):
-        self.cfg, self.fmt, self.baseline = cfg, fmt, baseline
+    def __init__(self, cfg, weights, fmt, baseline=False, fused_attention=False):
+        self.cfg, self.fmt, self.baseline, self.fused_attention = cfg, fmt, baseline, fused_attention
         q = lambda w: binding.quantize(fmt, w.contiguous(), baseline=baseline)  # noqa: E731
         self.wqkv = q(torch.cat([weights["wq"], weights["wk"], weights["wv"]], 0))
         self.wo = q(weights["wo"])
@@ -77,19 +80,36 @@ class DecoderLayer:
 
         qc, qs = self._cast(q.view(c.n_heads * S, D))
         kc, ks = self._cast(k.view(G * S, D))
+        if self.fused_attention:
+            vc, vs = self._cast_v(v, nsc)
+            fmt = binding.make_format(self.fmt.scale, False, 32) if self.baseline else self.fmt
+            need = binding.attention_workspace_bytes(fmt, c.n_heads, G, S, S, D)
+            if self._ws is None or self._ws.numel() < need:
+                self._ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+            o = binding.attention(fmt, qc.view(c.n_heads, S, D // 2), qs.view(c.n_heads, S, D // 32, *nsc),
+                                  kc.view(G, S, D // 2), ks.view(G, S, D // 32, *nsc), vc, vs, 1.0 / math.sqrt(D),
+                                  True, workspace=self._ws)
+            return self._after_attention(x, binding.merge_heads(o.view(G, per * S, D), G, per, S, D))
         scores = self._gemm((qc.view(G, per * S, D // 2), qs.view(G, per * S, D // 32, *nsc)),
                             (kc.view(G, S, D // 2), ks.view(G, S, D // 32, *nsc)))
         p = binding.softmax_causal(scores, 1.0 / math.sqrt(D))
         del scores
         pc, ps = self._cast(p.view(G * per * S, S))
         del p
-        vc = torch.empty((G, D, S // 2), dtype=torch.uint8, device=x.device)
-        vs = torch.empty((G, D, S // 32) + tuple(nsc), dtype=torch.uint8, device=x.device)
+        vc, vs = self._cast_v(v, nsc)
+        o = self._gemm((pc.view(G, per * S, S // 2), ps.view(G, per * S, S // 32, *nsc)), (vc, vs))
+        return self._after_attention(x, binding.merge_heads(o, G, per, S, D))
+
+    def _cast_v(self, v, nsc):
+        G, S, D = v.shape
+        vc = torch.empty((G, D, S // 2), dtype=torch.uint8, device=v.device)
+        vs = torch.empty((G, D, S // 32) + tuple(nsc), dtype=torch.uint8, device=v.device)
         for g in range(G):  # V of one head is [S, D]; its groups run down the columns (along the keys)
             binding.quantize(self.fmt, v[g], k_axis=0, codes=vc[g], scales=vs[g], baseline=self.baseline)
-        o = self._gemm((pc.view(G, per * S, S // 2), ps.view(G, per * S, S // 32, *nsc)), (vc, vs))
-        attn = binding.merge_heads(o, G, per, S, D)
+        return vc, vs
 
+    def _after_attention(self, x, attn):
+        c = self.cfg
         x2 = binding.residual_add(x, self._gemm(self._cast(attn), self.wo))
         h2 = binding.rmsnorm(x2, self.norm2, c.eps)
         act = binding.silu_mul(self._gemm(self._cast(h2), self.wgu))

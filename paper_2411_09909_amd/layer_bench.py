@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--seq", type=int, default=8192)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--formats", default=",".join(FORMATS))
+    ap.add_argument("--fused-attention", action="store_true",
+                    help="one fused attention call instead of Q.K^T, softmax, cast and P.V with a materialised map")
     args = ap.parse_args()
     cfg = layer.LayerConfig()
     dev = torch.device("cuda:0")
@@ -74,11 +76,11 @@ def main():
     ref_out = bf16_reference(x, w, cfg).to(torch.float32)
     upd = (ref_out - x.to(torch.float32)).pow(2).mean().item()
     out = {"workload": "c5_llama3_8b_decoder_layer", "seq": args.seq, "d_model": cfg.d_model, "heads": cfg.n_heads,
-           "kv_heads": cfg.n_kv_heads, "d_ff": cfg.d_ff, "data": "synthetic, random-init weights",
+           "kv_heads": cfg.n_kv_heads, "d_ff": cfg.d_ff, "data": "synthetic, random-init weights", "fused_attention": args.fused_attention,
            "reference_update_mean_square": upd, "formats": {}}
     for name in args.formats.split(","):
         kind, asym = FORMATS[name]
-        lay = layer.DecoderLayer(cfg, w, binding.make_format(kind, asym))
+        lay = layer.DecoderLayer(cfg, w, binding.make_format(kind, asym), fused_attention=args.fused_attention)
         y = lay.forward(x)  # warm-up, also the output that is compared
         torch.cuda.synchronize()
         t0 = time.perf_counter()

@@ -141,3 +141,25 @@ def test_double_scaling_and_measurement_calls_reject_bad_arguments(lib):
     assert lib.amxfp4_peak_mfma(5, p, 10, p, ctypes.byref(flops), None) == -1
     assert lib.amxfp4_peak_mfma(0, p, 0, p, ctypes.byref(flops), None) == -1
     assert lib.amxfp4_peak_copy(p, p, 24, None) == -1
+
+
+def test_attention_rejects_bad_arguments(lib):
+    ok = binding.make_format(binding.FP8_E5M2, True, 32)
+    p = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
+    a = lib.amxfp4_attention
+
+    def call(fmt, hq, hkv, sq, sk, d, causal=1, scale=0.1, ws=p, ws_bytes=1 << 40):
+        return a(ctypes.byref(fmt), hq, hkv, sq, sk, d, p, p, p, p, p, p, scale, causal, p, ws, ws_bytes, None)
+
+    assert call(ok, 4, 3, 64, 64, 128) == -1            # query heads not a multiple of key/value heads
+    assert call(ok, 4, 2, 64, 48, 128) == -1            # Sk % 32
+    assert call(ok, 4, 2, 64, 32, 128) == -1            # causal with fewer keys than queries
+    assert call(ok, 4, 2, 64, 64, 64) == -2             # head size
+    assert call(binding.make_format(binding.FP8_E5M2, True, 16), 4, 2, 64, 64, 128) == -2   # group size
+    assert call(ok, 4, 2, 64, 64, 128, scale=0.0) == -1
+    assert call(ok, 4, 2, 64, 64, 128, causal=2) == -1
+    assert call(ok, 4, 2, 64, 64, 128, ws=None, ws_bytes=0) == -3
+    assert call(ok, 4, 2, 64, 64, 128, ws_bytes=16) == -3
+    need = lib.amxfp4_attention_workspace_bytes(ctypes.byref(ok), 4, 2, 50, 96, 128)
+    assert need == (4 * 64 + 2 * 96 + 2 * 128) * 128 * 2   # Q rows padded to 32, V keys padded to 64
+    assert lib.amxfp4_attention_workspace_bytes(ctypes.byref(ok), 4, 2, 50, 96, 64) == 0

@@ -84,8 +84,9 @@ def test_silu_mul_residual_add_merge_heads():
     assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16), L.merge_heads(o, 2, 3, 50, 64))
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.E8M0_FLOOR, 0)])
-def test_decoder_layer_cut_down(scale, asym):
+def test_decoder_layer_cut_down(scale, asym, fused):
     """A layer with the real head size and grouped-query structure but small widths (the oracle runs it in seconds).
     Quantization makes the layer output a discontinuous function of its intermediates: where an intermediate BF16
     value differs by one step between the two sides (see above), codes of that group may change, so the outputs are
@@ -96,11 +97,11 @@ def test_decoder_layer_cut_down(scale, asym):
     x = synth.layer_input(S, cfg.d_model, seed=0)
     fmt = binding.make_format(scale, asym)
     wd = {k: (dev_f32(v) if v.dtype == np.float32 else G.to_dev_bf16(v)) for k, v in w.items()}
-    lay = layer.DecoderLayer(cfg, wd, fmt)
+    lay = layer.DecoderLayer(cfg, wd, fmt, fused_attention=fused)
     out = lay.forward(G.to_dev_bf16(x))
     torch.cuda.synchronize()
     got = L.f64_from_bf16(out.view(torch.int16).cpu().numpy().view(np.uint16))
-    want = L.f64_from_bf16(L.decoder_layer(x, w, cfg, scale, asym))
+    want = L.f64_from_bf16(L.decoder_layer(x, w, cfg, scale, asym, fused_attention=fused))
     upd = want - L.f64_from_bf16(x)
     err = np.linalg.norm(got - want) / np.linalg.norm(upd)
     assert err <= 2e-2, "layer output differs from the oracle by %.4f of the layer's update" % err
