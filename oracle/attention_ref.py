@@ -30,34 +30,39 @@ from . import ref
 TILE = 32
 
 
-def fused_attention(q_bits, k_bits, v_bits, scale, causal=True, scale_format=ref.FP8_E5M2, asymmetric=True):
+def fused_attention(q_bits, k_bits, v_bits, scale, causal=True, scale_format=ref.FP8_E5M2, asymmetric=True,
+                    heads=None, rows=None):
     """q_bits [Hq, Sq, D], k_bits / v_bits [Hkv, Sk, D]: BF16 bit patterns (uint16); Hq a multiple of Hkv (query
-    head h reads key/value head h // (Hq // Hkv)). Returns float32 [Hq, Sq, D]."""
+    head h reads key/value head h // (Hq // Hkv)). Returns float32 [Hq, Sq, D]. heads / rows: compute only these
+    query heads / query positions (the other entries of the result stay 0): every output row depends on its own
+    query and on the keys and values only, so a sample of rows is computed exactly as in the full problem."""
     Hq, Sq, D = q_bits.shape
     Hkv, Sk, _ = k_bits.shape
     assert Hq % Hkv == 0 and Sk % TILE == 0 and D % 32 == 0
     per = Hq // Hkv
     out = np.zeros((Hq, Sq, D), np.float32)
-    kv = []
-    for g in range(Hkv):
+    heads = range(Hq) if heads is None else list(heads)
+    rows = range(Sq) if rows is None else list(rows)
+    kv = {}
+    for g in sorted({h // per for h in heads}):
         kc, ks = ref.quantize(np.ascontiguousarray(k_bits[g]), 32, scale_format, asymmetric)
         vc, vs = ref.quantize(np.ascontiguousarray(v_bits[g]), 32, scale_format, asymmetric, k_axis=0)  # [D, Sk]
-        kv.append((ref.dequantize(kc, ks, 32, scale_format, asymmetric),
-                   ref.dequantize(vc, vs, 32, scale_format, asymmetric).T))                    # [Sk, D] each
+        kv[g] = (ref.dequantize(kc, ks, 32, scale_format, asymmetric),
+                 ref.dequantize(vc, vs, 32, scale_format, asymmetric).T)                       # [Sk, D] each
     sc = np.float64(np.float32(scale))
-    for h in range(Hq):
+    for h in heads:
         qc, qs = ref.quantize(np.ascontiguousarray(q_bits[h]), 32, scale_format, asymmetric)
         qh = ref.dequantize(qc, qs, 32, scale_format, asymmetric)
         kh, vh = kv[h // per]
-        s_all = (qh @ kh.T) * sc                                                               # [Sq, Sk] float64
-        for i in range(Sq):
+        for i in rows:
+            s_row = (kh @ qh[i]) * sc                                                          # [Sk] float64
             last = i + (Sk - Sq) if causal else Sk - 1          # last key this query may attend to
             m, l, o = -np.inf, 0.0, np.zeros(D, np.float64)
             for t0 in range(0, Sk, TILE):
                 n_ok = min(TILE, last - t0 + 1)
                 if n_ok <= 0:
                     break
-                s = s_all[i, t0:t0 + TILE]
+                s = s_row[t0:t0 + TILE]
                 m_new = max(m, float(np.max(s[:n_ok])))
                 alpha = np.exp(m - m_new)                       # exp(-inf) = 0 on the first tile
                 p = np.zeros(TILE, np.float32)

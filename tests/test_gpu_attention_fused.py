@@ -108,3 +108,20 @@ def test_invalid_arguments():
     with pytest.raises(binding.AmxError):   # groups of 16
         binding.attention(f16, z(1, 32, 64), z(1, 32, 8, 2), z(1, 32, 64), z(1, 32, 8, 2), z(1, 128, 16),
                           z(1, 128, 2, 2), 0.1, True)
+
+
+@pytest.mark.parametrize("Hq,Hkv,S", [(32, 32, 4096), (32, 8, 8192)])
+def test_full_size_sampled_rows(Hq, Hkv, S):
+    """The attention workload at its full size (32 heads x 4096, and the decoder layer's 32 query / 8 key-value heads
+    x 8192) through the call the benchmark times; the oracle computes a sample of query rows (first and last rows of
+    the sequence, rows around workgroup and key-tile edges, random ones) of four heads, each exactly as in the full
+    problem."""
+    qb, _, _ = synth.attention_qkv(Hq, S, D, seed=0)
+    _, kb, vb = synth.attention_qkv(Hkv, S, D, seed=1)
+    out = gpu_attention(qb, kb, vb, D ** -0.5, True, ref.FP8_E5M2, 1)
+    rng = np.random.default_rng(2)
+    rows = sorted({0, 1, 31, 32, 255, 256, 257, S // 2 - 1, S // 2, S - 33, S - 1} | set(rng.choice(S, 12, replace=False).tolist()))
+    hs = [0, Hq // 4 + 1, Hq // 2 + 2, Hq - 1]
+    want = attention_ref.fused_attention(qb, kb, vb, D ** -0.5, True, ref.FP8_E5M2, 1, heads=hs, rows=rows)
+    got = out[np.ix_(hs, rows)]
+    compare(got, want[np.ix_(hs, rows)])
