@@ -118,11 +118,12 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
     const int key0 = (T) * 32 + row_in_tile;                                                                       \
     const bool diagonal = causal && (T) * 32 + 31 > qw + off; /* some key of the tile is masked for some query */ \
     float mx = -__builtin_inff();                                                                                  \
-    _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                                               \
-      x[v] = s[v] * scale_log2;                                                                                    \
-      if (diagonal && key0 + 8 * (v >> 2) + (v & 3) > limit) x[v] = -__builtin_inff();                             \
-      mx = fmaxf(mx, x[v]);                                                                                        \
+    _Pragma("unroll") for (int v = 0; v < 16; ++v) x[v] = s[v] * scale_log2;                                       \
+    if (diagonal) { /* uniform over the wave: most tiles skip the masking altogether */                           \
+      _Pragma("unroll") for (int v = 0; v < 16; ++v)                                                               \
+        if (key0 + 8 * (v >> 2) + (v & 3) > limit) x[v] = -__builtin_inff();                                       \
     }                                                                                                              \
+    _Pragma("unroll") for (int v = 0; v < 16; ++v) mx = fmaxf(mx, x[v]);                                           \
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                                                        \
     /* The subtraction below is exact 0 for the score that holds the maximum, so its probability is exactly 1, as \
        in exact arithmetic (folding the scale into an FMA here would make it 1 - 2^-24 now and then, and a floored \
