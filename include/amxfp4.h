@@ -39,6 +39,9 @@
  *   - arguments are validated on the host before anything is launched; on a non-zero return no output byte has
  *     been written. Inputs must be finite BF16 (NaN/Inf give unspecified codes but never an out-of-bounds access).
  *   - returns AMX_OK or a negative amx_status_t; amxfp4_last_error() gives a thread-local message.
+ *   - size limits (AMX_ERR_INVALID_ARG beyond them): K <= 2^20 for every operand; rows of a cast <= 2^31 - 1
+ *     (16 776 960 when the groups run down a strided axis); M and N of a GEMM <= 2^21 - 256; batch <= 65535.
+ *     Zero-sized operands are invalid arguments, not no-ops.
  */
 #ifndef AMXFP4_H
 #define AMXFP4_H

@@ -23,6 +23,13 @@ int fail(int code, const char* fmt, ...) {
   return code;
 }
 
+// Size limits (stated in include/amxfp4.h): K of any operand, rows of a cast, rows of a GEMM operand, batch entries.
+constexpr int64_t kMaxK = int64_t(1) << 20;
+constexpr int64_t kMaxCastRows = (int64_t(1) << 31) - 1;
+constexpr int64_t kMaxStridedRows = 65535 * 256;
+constexpr int64_t kMaxGemmRows = (int64_t(1) << 21) - 256;
+constexpr int64_t kMaxBatch = 65535;
+
 // Validates a format for the GPU library. Returns AMX_OK or a negative status (message set).
 int check_format(const amx_format_t* f) {
   if (!f) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
@@ -43,6 +50,10 @@ int check_shape(const amx_format_t& f, int64_t rows, int64_t K) {
   if (K % f.group_size != 0 || K % 32 != 0)
     return fail(AMX_ERR_INVALID_ARG, "K = %lld is not a multiple of the group size %d and of 32", (long long)K,
                 f.group_size);
+  // launch grids and 32-bit offsets inside the kernels are laid out for these bounds
+  if (K > kMaxK) return fail(AMX_ERR_INVALID_ARG, "K = %lld exceeds the supported maximum %lld", (long long)K, (long long)kMaxK);
+  if (rows > kMaxCastRows)
+    return fail(AMX_ERR_INVALID_ARG, "rows = %lld exceeds the supported maximum %lld", (long long)rows, (long long)kMaxCastRows);
   return AMX_OK;
 }
 
@@ -79,6 +90,9 @@ int quantize_impl(amx_format_t f, const void* x, int64_t rows, int64_t K, int64_
   }
   if (row_stride == 1 && k_stride >= rows) {
     if (!aligned(x, 2)) return fail(AMX_ERR_INVALID_ARG, "x must be 2-byte aligned");
+    if (rows > kMaxStridedRows)
+      return fail(AMX_ERR_INVALID_ARG, "rows = %lld exceeds the maximum %lld of the strided cast", (long long)rows,
+                  (long long)kMaxStridedRows);
     hipError_t e = amx::launch_quantize_strided(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, k_stride, tensor_pair, codes,
                                                 scales, s);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "strided quantize launch");
@@ -150,6 +164,9 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
   if (int rc = check_format(&f)) return rc;
   if (int rc = check_shape(f, M, K)) return rc;
   if (N <= 0 || batch <= 0) return fail(AMX_ERR_INVALID_ARG, "N and batch must be positive");
+  if (M > kMaxGemmRows || N > kMaxGemmRows || batch > kMaxBatch)
+    return fail(AMX_ERR_INVALID_ARG, "M and N may be at most %lld and batch at most %lld (got %lld, %lld, %lld)",
+                (long long)kMaxGemmRows, (long long)kMaxBatch, (long long)M, (long long)N, (long long)batch);
   if (ldc < N) return fail(AMX_ERR_INVALID_ARG, "ldc < N");
   if (!A_codes || !A_scales || !B_codes || !B_scales || !C) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
   if (!aligned(A_codes, 16) || !aligned(B_codes, 16) || !aligned(A_scales, 4) || !aligned(B_scales, 4) ||

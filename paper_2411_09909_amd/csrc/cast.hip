@@ -148,14 +148,15 @@ __global__ __launch_bounds__(256) void quantize_contig_kernel(const uint16_t* __
 
 // Groups run down a column: element (r, k) = x[r + k * k_stride]. One lane owns one (row, group) of GS elements;
 // consecutive lanes own consecutive rows, so each of the GS loads of a wave reads 128 contiguous bytes.
+// grid: (K / GS groups, ceil(rows / 256)).
 template <int SCALE_KIND, bool ASYM, bool TENSOR_SCALED, int GS>
 __global__ __launch_bounds__(256) void quantize_strided_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t K,
                                                                int64_t k_stride, const float* __restrict__ tensor_pair,
                                                                uint8_t* __restrict__ codes,
                                                                uint8_t* __restrict__ scales) {
   const int64_t G = K / GS;
-  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t g = blockIdx.y;
+  const int64_t r = (int64_t)blockIdx.y * 256 + threadIdx.x;
+  const int64_t g = blockIdx.x;
   if (r >= rows) return;
   const uint16_t* p = x + r + g * GS * k_stride;
   float rt = 1.0f;
@@ -340,7 +341,7 @@ hipError_t launch_quantize_contig(int scale_kind, bool asym, int64_t group_size,
 template <int SK, bool ASYM, int GS>
 static hipError_t launch_qs(const uint16_t* x, int64_t rows, int64_t K, int64_t k_stride, const float* tensor_pair,
                             uint8_t* codes, uint8_t* scales, hipStream_t s) {
-  const dim3 grid((unsigned)((rows + 255) / 256), (unsigned)(K / GS));
+  const dim3 grid((unsigned)(K / GS), (unsigned)((rows + 255) / 256));
   if (tensor_pair)
     hipLaunchKernelGGL((quantize_strided_kernel<SK, ASYM, true, GS>), grid, dim3(256), 0, s, x, rows, K, k_stride,
                        tensor_pair, codes, scales);

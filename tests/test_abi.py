@@ -88,6 +88,14 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert _q(lib, binding.AmxFormat(128, 0, 2, 1), p, 4, 64, 64, 1, p, p) == -1   # K smaller than one group of 128
     assert _q(lib, binding.AmxFormat(16, 0, 2, 1), p, 4, 48, 48, 1, p, p) == -1    # whole groups of 16, but K % 32 != 0
     assert lib.amxfp4_quantize(None, p, 4, 64, 64, 1, p, p, None) == -1
+    # size limits: K, rows of a cast, M / N / batch of a GEMM
+    big_k = (1 << 20) + 32
+    assert _q(lib, ok, p, 4, big_k, big_k, 1, p, p) == -1 and b"maximum" in lib.amxfp4_last_error()
+    assert _q(lib, ok, p, 1 << 31, 64, 64, 1, p, p) == -1
+    gg = lib.amxfp4_gemm
+    assert gg(ctypes.byref(ok), 1 << 21, 64, 64, p, p, p, p, p, 64, 1, p, 1 << 40, None) == -1
+    assert gg(ctypes.byref(ok), 64, 1 << 21, 64, p, p, p, p, p, 1 << 21, 1, p, 1 << 40, None) == -1
+    assert gg(ctypes.byref(ok), 64, 64, 64, p, p, p, p, p, 64, 65536, p, 1 << 40, None) == -1
     assert lib.amxfp4_dequantize(ctypes.byref(ok), p, p, 4, 64, p, 2, None) == -1      # bad out_dtype
     # GEMM: workspace too small / missing, ldc < N
     g = lib.amxfp4_gemm
