@@ -323,10 +323,23 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
   e = expand_dispatch(scale_kind, asym, gs_log2, B_codes, B_scales, N, K, Np, Kp, batch, Bp, s);
   if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
-  // Tile shape: 256 x 256 unless one side of the problem is much smaller than that (skinny outputs such as P.V with
-  // N = head size 128, or a handful of tokens); AMXFP4_TILE overrides the choice in tuning experiments.
+  // Tile shape. 256 x 256 (4 waves of 128 x 128) has the least operand traffic and LDS reads per MFMA and is what
+  // large problems use; a problem with fewer such tiles than the chip has CUs, or with one side much smaller than a
+  // tile, finishes sooner with 256 x 128 or 64 x 256 tiles that fill the CUs. The choice minimises
+  // (rounds of 256 workgroups) x (measured cost of one tile relative to a 256 x 256 one: 0.6 and 0.45), and leaves
+  // 256 x 256 only for a predicted gain of more than 15 %. AMXFP4_TILE overrides it in tuning experiments.
   static const int tile_env = getenv("AMXFP4_TILE") ? atoi(getenv("AMXFP4_TILE")) : -1;
-  const int tile_cfg = tile_env >= 0 ? tile_env : (M <= 64 ? 4 : (N <= 128 ? 3 : 0));
+  auto rounds = [&](int64_t tile_m, int64_t tile_n) {
+    const int64_t tiles = ((M + tile_m - 1) / tile_m) * ((N + tile_n - 1) / tile_n) * batch;
+    return (double)((tiles + 255) / 256);
+  };
+  const double est0 = rounds(256, 256), est3 = 0.6 * rounds(256, 128), est4 = 0.45 * rounds(64, 256);
+  int tile_cfg = 0;
+  if (est4 < 0.85 * est0 && est4 <= est3)
+    tile_cfg = 4;
+  else if (est3 < 0.85 * est0 && M > 128)  // (a 256-row tile on 128 rows or fewer is half empty: measured no gain)
+    tile_cfg = 3;
+  if (tile_env >= 0) tile_cfg = tile_env;
   if (tile_cfg == 1)
     e = launch_tiles<2, 4, 4, 2>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, s);
   else if (tile_cfg == 2)
