@@ -139,8 +139,9 @@ def cpu_baseline(x_bits, w_bits, K, sample_m=2048, sample_n=14336):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed steps; the chip needs about 0.1 s of this load to settle at its sustained rate")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", default=WORKLOAD)
     ap.add_argument("--format", default="amxfp4_e5m2", choices=sorted(FORMATS),
@@ -274,7 +275,7 @@ def main():
         for name, kern in cases:
             if name == args.format and kern == args.e5m2_kernel:
                 continue
-            v = run_format(name, max(3, args.steps // 2), 2, kern)
+            v = run_format(name, max(3, args.steps // 2), max(2, args.warmup // 2), kern)
             out["variants"][name if kern == "panel" else "%s[%s]" % (name, kern)] = {"value": round(flops / v["t_step"] / 1e12, 2), "unit": "TFLOP/s",
                                      "ms_per_step": round(v["t_step"] * 1e3, 4), "mfma": v["mfma"],
                                      "workspace_MB": round(v["workspace_bytes"] / 1e6, 1),
