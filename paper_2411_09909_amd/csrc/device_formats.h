@@ -16,14 +16,11 @@ __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 template <int SCALE_KIND>
 __device__ __forceinline__ float scale_value(uint32_t byte) {
   if constexpr (SCALE_KIND == kScaleE5M2) {
-    // half -> float by hand: exact for all 3-significant-bit values
-    const uint32_t e = (byte >> 2) & 31u, m = byte & 3u;
-    if (e == 0) return (float)m * 1.52587890625e-05f;  // m * 2^-16
-    return u2f(((e + 112u) << 23) | (m << 21));
+    // the byte is the upper byte of an IEEE half: the half -> float conversion is exact, subnormals included
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)((byte & 0x7Fu) << 8));
   } else if constexpr (SCALE_KIND == kScaleE4M3) {
-    const uint32_t e = (byte >> 3) & 15u, m = byte & 7u;
-    if (e == 0) return (float)m * 0.001953125f;  // m * 2^-9
-    return u2f(((e + 120u) << 23) | (m << 20));
+    // 0eeeemmm << 7 read as a half is (1 + m/8) * 2^(e - 15), or (m/8) * 2^-14 for e = 0: 2^8 times that is the value
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)((byte & 0x7Fu) << 7)) * 256.0f;
   } else {
     return byte == 0 ? u2f(0x00400000u) : u2f(byte << 23);  // 2^(byte-127)
   }

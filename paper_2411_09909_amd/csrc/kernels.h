@@ -53,6 +53,15 @@ hipError_t launch_expand_bf16(int scale_kind, bool asym, int64_t group_size, con
                               const uint8_t* scales, int64_t R, int64_t K, int64_t Rp, int64_t Kp, int64_t batch,
                               bool permute, uint16_t* panel, hipStream_t s);
 
+// gemm_skinny.hip: M <= 64, K a multiple of 256, groups of 32: B dequantized in registers straight from its codes
+// (workspace: the BF16 panel of A and, with several outer K slices, the partial tiles)
+bool skinny_path_supported(int64_t M, int64_t N, int64_t K);
+size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
+hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                                   const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
+                                   int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
+                                   const KernelTimer& timer);
+
 // attention.hip: fused quantized attention, head dimension 128, groups of 32 (workspace: the three BF16 panels)
 size_t attention_workspace_bytes(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk);
 hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk,

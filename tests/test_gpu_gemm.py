@@ -209,3 +209,52 @@ def test_measurement_aids_run_and_copy_is_a_copy():
     assert torch.equal(src, dst)
     with pytest.raises(binding.AmxError):
         binding.peak_copy(src[:24], dst[:24])
+
+
+SKINNY_FORMATS = [(ref.FP8_E5M2, 1), (ref.FP8_E5M2, 0), (ref.E8M0_FLOOR, 1), (ref.E8M0_FLOOR, 0), (ref.FP8_E4M3, 1),
+                  (ref.E8M0_ROUND, 1)]
+
+
+@pytest.mark.parametrize("scale,asym", SKINNY_FORMATS)
+@pytest.mark.parametrize("M,N,K", [(1, 1, 256), (7, 31, 512), (32, 100, 2304), (33, 4101, 1024), (64, 1000, 4096),
+                                   (16, 8192, 256), (64, 33, 8192)])
+def test_few_rows_against_many_columns(M, N, K, scale, asym):
+    """M <= 64 with K a multiple of 256: the kernel that dequantizes B in registers straight from its codes. One and
+    two row tiles, partial column tiles, one K block per workgroup up to many, with and without outer K slices."""
+    a = synth.activations(M, K, seed=M + K, n_outlier=1, outlier_gain=60.0)
+    b = synth.weights(N, K, seed=N)
+    ac, as_ = ref.quantize(a, 32, scale, asym)
+    bc, bs = ref.quantize(b, 32, scale, asym)
+    C = G.gpu_gemm(ac, as_, bc, bs, scale, asym)
+    Cr = ref.gemm(ac, as_, bc, bs, 32, scale, asym)
+    assert C.shape == (M, N)
+    assert G.rel_fro(C, Cr) <= TOL
+    assert np.allclose(C, Cr, rtol=1e-4, atol=1e-4 * np.abs(Cr).max())
+
+
+@pytest.mark.parametrize("asym", [1, 0])
+def test_few_rows_integer_exact_batched_and_repeatable(asym):
+    """Scales 1 and integer codes: exact integers below 2^24 in any summation order, so the result must equal the
+    oracle bit for bit; batch > 1; and two calls give identical bits (the K slices are added in a fixed order)."""
+    rng = np.random.default_rng(11)
+    batch, M, N, K = 3, 40, 70, 1024
+    mags = np.array([0, 2, 4, 5, 6, 7])
+
+    def operand(rows):
+        mag = rng.choice(mags, size=(batch, rows, K))
+        sgn = rng.integers(0, 2, size=(batch, rows, K))
+        nib = (mag | (sgn << 3)).astype(np.uint8)
+        shape = (batch, rows, K // 32, 2) if asym else (batch, rows, K // 32)
+        return (nib[..., 0::2] | (nib[..., 1::2] << 4)).astype(np.uint8), np.full(shape, 127, np.uint8)
+
+    ac, as_ = operand(M)
+    bc, bs = operand(N)
+    C1 = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, asym)
+    C2 = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, asym)
+    assert np.array_equal(C1, ref.gemm(ac, as_, bc, bs, 32, ref.E8M0_FLOOR, asym))
+    assert np.array_equal(C1, C2)
+    # real-valued operands: repeatable too
+    a = synth.activations(M, K, seed=1)
+    b = synth.weights(4000, K, seed=2)
+    qa, qb = ref.quantize(a, 32, ref.FP8_E5M2, asym), ref.quantize(b, 32, ref.FP8_E5M2, asym)
+    assert np.array_equal(G.gpu_gemm(*qa, *qb, ref.FP8_E5M2, asym), G.gpu_gemm(*qa, *qb, ref.FP8_E5M2, asym))
