@@ -326,18 +326,20 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
   // Tile shape. 256 x 256 (4 waves of 128 x 128) has the least operand traffic and LDS reads per MFMA and is what
   // large problems use; a problem with fewer such tiles than the chip has CUs, or with one side much smaller than a
   // tile, finishes sooner with 256 x 128 or 64 x 256 tiles that fill the CUs. The choice minimises
-  // (rounds of 256 workgroups) x (measured cost of one tile relative to a 256 x 256 one: 0.6 and 0.45), and leaves
+  // (rounds of 256 workgroups) x (measured cost of one tile relative to a 256 x 256 one: 0.6 and 0.4), and leaves
   // 256 x 256 only for a predicted gain of more than 15 %. AMXFP4_TILE overrides it in tuning experiments.
   static const int tile_env = getenv("AMXFP4_TILE") ? atoi(getenv("AMXFP4_TILE")) : -1;
   auto rounds = [&](int64_t tile_m, int64_t tile_n) {
     const int64_t tiles = ((M + tile_m - 1) / tile_m) * ((N + tile_n - 1) / tile_n) * batch;
     return (double)((tiles + 255) / 256);
   };
-  const double est0 = rounds(256, 256), est3 = 0.6 * rounds(256, 128), est4 = 0.45 * rounds(64, 256);
+  const double est0 = rounds(256, 256), est3 = 0.6 * rounds(256, 128), est4 = 0.4 * rounds(64, 256);
+  const bool ok4 = est4 < 0.85 * est0;
+  const bool ok3 = est3 < 0.85 * est0 && M > 256;  // (with a single row of 256-row tiles the 64-row tile was never worse)
   int tile_cfg = 0;
-  if (est4 < 0.85 * est0 && est4 <= est3)
+  if (ok4 && (!ok3 || est4 <= est3))
     tile_cfg = 4;
-  else if (est3 < 0.85 * est0 && M > 128)  // (a 256-row tile on 128 rows or fewer is half empty: measured no gain)
+  else if (ok3)
     tile_cfg = 3;
   if (tile_env >= 0) tile_cfg = tile_env;
   if (tile_cfg == 1)

@@ -1,4 +1,4 @@
-// Fully quantized GEMM (Sec. 4.3) for a small number of rows on the A side (M <= 64: a few tokens against a weight
+// Fully quantized GEMM (Sec. 4.3) for a small number of rows on the A side (M <= 128: a few tokens against a weight
 // matrix). Such a product is bound by reading the weights, and the point of 4-bit weights is that they are a quarter
 // of the BF16 bytes, so this kernel reads the packed codes and scales of B straight from memory, dequantizes them in
 // registers to exact BF16 (element * scale has at most 6 significant bits) and feeds the BF16 MFMA; only the small
@@ -44,7 +44,7 @@ __device__ __forceinline__ uint32_t dequant2(uint32_t word, float s_pos, float s
   return __builtin_amdgcn_perm(f2u(v1), f2u(v0), 0x07060302u);  // upper halves: (v0 low, v1 high)
 }
 
-constexpr int kSkinnyMaxM = 64;     // at most two 32-row MFMA tiles
+constexpr int kSkinnyMaxM = 128;    // at most four 32-row MFMA tiles
 constexpr int kSkinnyBlockK = 256;  // K block: 128 bytes of codes per row
 
 // Outer K slices for a problem with `groups` workgroups per slice and nblk K blocks: about 512 workgroups (two per CU,
@@ -266,8 +266,12 @@ hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t
   // E8M0 floor and round share the byte encoding
   const int sk = scale_kind == kScaleE8M0Round ? kScaleE8M0Floor : scale_kind;
   auto go = [&]<int SK, bool ASYM>() {
-    return Mp == 32 ? launch_skinny<SK, ASYM, 1>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s)
-                    : launch_skinny<SK, ASYM, 2>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
+    switch (Mp / 32) {
+      case 1: return launch_skinny<SK, ASYM, 1>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
+      case 2: return launch_skinny<SK, ASYM, 2>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
+      case 3: return launch_skinny<SK, ASYM, 3>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
+      default: return launch_skinny<SK, ASYM, 4>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
+    }
   };
   if (sk == kScaleE5M2)
     e = asym ? go.template operator()<kScaleE5M2, true>() : go.template operator()<kScaleE5M2, false>();
