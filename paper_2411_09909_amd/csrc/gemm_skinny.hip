@@ -5,8 +5,8 @@
 // A operand goes through a BF16 panel (expand_kernel). No operand of B is ever written back.
 //
 // Work split: one workgroup = 4 waves = 4 neighbouring tiles of 32 columns of C (32 rows of B each) over one outer K
-// slice. K is walked in blocks of 256. Per block the workgroup brings the A block (M x 256 BF16 = 16 fragments per 32
-// rows) into LDS once, by direct-to-LDS loads, double buffered; each lane owns one B row (lane % 32 of its wave's
+// slice. K is walked in blocks of 256. The workgroup brings the A operand into LDS once, by direct-to-LDS loads, in
+// half blocks (M x 128 BF16 = 8 fragments per 32 rows), double buffered; each lane owns one B row (lane % 32 of its wave's
 // tile) and loads that row's 128 bytes of codes (one cache line, fetched exactly once) and its 8 scale entries one
 // block ahead, then runs 16 k-steps of 16 from registers: lane half h = lane / 32 turns codes 16 j + 8 h .. + 7 of a
 // group into the 8 BF16 of its B fragment. With more than one outer slice the partial tiles go to the workspace and a
@@ -81,10 +81,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const uint16_t* __rest
                                                           int64_t M, int64_t N, int64_t K, int64_t ld_out,
                                                           int64_t batch_stride_out, int64_t slice_stride_out,
                                                           int blocks_per_slice) {
-  constexpr int kFragsPerBlock = MT * (kSkinnyBlockK / 16);  // A fragments of one K block
+  constexpr int kFragsPerHalf = MT * (kSkinnyBlockK / 32);  // A fragments of half a K block (8 k-steps)
   // two stages, separate arrays so that loads into one are known not to alias reads of the other
-  __shared__ __attribute__((aligned(1024))) uint8_t ldsA0[kFragsPerBlock * kFragBytes];
-  __shared__ __attribute__((aligned(1024))) uint8_t ldsA1[kFragsPerBlock * kFragBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t ldsA0[kFragsPerHalf * kFragBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t ldsA1[kFragsPerHalf * kFragBytes];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int h = lane >> 5;
@@ -115,13 +115,13 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const uint16_t* __rest
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
 
-  // wave w brings fragments w, w + 4, .. of A block I (of this slice) into stage DST: fragment f = row block f / 16,
-  // k-step f % 16
-#define AMX_SKINNY_LOAD_A(I, DST)                                                                                  \
-  _Pragma("unroll") for (int i_ = 0; i_ < kFragsPerBlock / 4; ++i_) {                                              \
+  // wave w brings fragments w, w + 4, .. of A half block HB (of this slice) into stage DST: fragment f = row block
+  // f / 8, k-step f % 8 of the half
+#define AMX_SKINNY_LOAD_A(HB, DST)                                                                                 \
+  _Pragma("unroll") for (int i_ = 0; i_ < kFragsPerHalf / 4; ++i_) {                                               \
     const int f_ = wave + 4 * i_;                                                                                  \
     __builtin_amdgcn_raw_ptr_buffer_load_lds(Ar, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, lane_off,               \
-                                             ((f_ >> 4) * kfrags + first_frag + (I) * 16 + (f_ & 15)) * kFragBytes, \
+                                             ((f_ >> 3) * kfrags + first_frag + (HB) * 8 + (f_ & 7)) * kFragBytes,  \
                                              0, 0);                                                                \
   }
   // this lane's row: one cache line of codes (8 groups) and the 8 scale entries of block I
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const uint16_t* __rest
     }                                                                                                              \
   }
   // The two k-steps of group GI (a literal: register arrays must not be indexed with a run-time value) of one block:
-  // A fragments from stage SRC, B from the registers W / S
+  // A fragments from stage SRC (the half block that holds the group), B from the registers W / S
 #define AMX_SKINNY_GROUP(SRC, W, S, GI)                                                                            \
   {                                                                                                                \
     float s_pos, s_neg;                                                                                            \
@@ -162,16 +162,19 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const uint16_t* __rest
                                                        dequant2<ASYM, 2>(word1, s_pos, s_neg),                     \
                                                        dequant2<ASYM, 3>(word1, s_pos, s_neg)});                   \
     _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                                            \
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>((SRC) + (mt * 16 + (GI) * 2) * kFragBytes + lane_off);    \
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>((SRC) + (mt * 16 + (GI) * 2 + 1) * kFragBytes + lane_off); \
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>((SRC) + (mt * 8 + ((GI) & 3) * 2) * kFragBytes + lane_off); \
+      const bf16x8 a1 =                                                                                            \
+          *reinterpret_cast<const bf16x8*>((SRC) + (mt * 8 + ((GI) & 3) * 2 + 1) * kFragBytes + lane_off);         \
       acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[mt], 0, 0, 0);                                 \
       acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[mt], 0, 0, 0);                                 \
     }                                                                                                              \
   }
-#define AMX_SKINNY_BLOCK(SRC, W, S)                                                                                \
+#define AMX_SKINNY_HALF0(SRC, W, S)                                                                                \
   AMX_SKINNY_GROUP(SRC, W, S, 0) AMX_SKINNY_GROUP(SRC, W, S, 1) AMX_SKINNY_GROUP(SRC, W, S, 2)                     \
-  AMX_SKINNY_GROUP(SRC, W, S, 3) AMX_SKINNY_GROUP(SRC, W, S, 4) AMX_SKINNY_GROUP(SRC, W, S, 5)                     \
-  AMX_SKINNY_GROUP(SRC, W, S, 6) AMX_SKINNY_GROUP(SRC, W, S, 7)
+  AMX_SKINNY_GROUP(SRC, W, S, 3)
+#define AMX_SKINNY_HALF1(SRC, W, S)                                                                                \
+  AMX_SKINNY_GROUP(SRC, W, S, 4) AMX_SKINNY_GROUP(SRC, W, S, 5) AMX_SKINNY_GROUP(SRC, W, S, 6)                     \
+  AMX_SKINNY_GROUP(SRC, W, S, 7)
 
   u32x4 w0[8], w1[8];
   uint32_t s0[4], s1[4];
@@ -179,26 +182,33 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const uint16_t* __rest
   AMX_SKINNY_LOAD_B(0, w0, s0);
   AMX_WAIT_VMCNT(0);
   AMX_BARRIER();
+  // Block i: its first half is multiplied from stage 0, its second from stage 1, with the codes in register set
+  // i % 2. Every step fetches what the next step needs (the other A stage; the next block's codes during a first half)
+  // and ends with a wait and a barrier, after which the stage it read may be refilled. All conditions are uniform.
   for (int i = 0; i < nb; i += 2) {
-    // block i is complete in stage 0 / registers set 0; block i + 1 is fetched while it is multiplied
-    if (i + 1 < nb) {
-      AMX_SKINNY_LOAD_A(i + 1, ldsA1);
-      AMX_SKINNY_LOAD_B(i + 1, w1, s1);
-    }
-    AMX_SKINNY_BLOCK(ldsA0, w0, s0);
+    AMX_SKINNY_LOAD_A(2 * i + 1, ldsA1);
+    if (i + 1 < nb) AMX_SKINNY_LOAD_B(i + 1, w1, s1);
+    AMX_SKINNY_HALF0(ldsA0, w0, s0);
     AMX_WAIT_VMCNT(0);
     AMX_BARRIER();
-    if (i + 1 < nb) {  // uniform over the workgroup
-      if (i + 2 < nb) {
-        AMX_SKINNY_LOAD_A(i + 2, ldsA0);
-        AMX_SKINNY_LOAD_B(i + 2, w0, s0);
-      }
-      AMX_SKINNY_BLOCK(ldsA1, w1, s1);
+    if (i + 1 < nb) AMX_SKINNY_LOAD_A(2 * i + 2, ldsA0);
+    AMX_SKINNY_HALF1(ldsA1, w0, s0);
+    AMX_WAIT_VMCNT(0);
+    AMX_BARRIER();
+    if (i + 1 < nb) {
+      AMX_SKINNY_LOAD_A(2 * i + 3, ldsA1);
+      if (i + 2 < nb) AMX_SKINNY_LOAD_B(i + 2, w0, s0);
+      AMX_SKINNY_HALF0(ldsA0, w1, s1);
+      AMX_WAIT_VMCNT(0);
+      AMX_BARRIER();
+      if (i + 2 < nb) AMX_SKINNY_LOAD_A(2 * i + 4, ldsA0);
+      AMX_SKINNY_HALF1(ldsA1, w1, s1);
       AMX_WAIT_VMCNT(0);
       AMX_BARRIER();
     }
   }
-#undef AMX_SKINNY_BLOCK
+#undef AMX_SKINNY_HALF1
+#undef AMX_SKINNY_HALF0
 #undef AMX_SKINNY_GROUP
 #undef AMX_SKINNY_LOAD_B
 #undef AMX_SKINNY_LOAD_A
