@@ -250,7 +250,7 @@ def main():
                   M * (K // (16 if scaled else args.group_size)) * (2 if r["asym"] else 1))
     kernel_name = "gemm_fp4_kernel" if r["mfma"] == "fp4" else "gemm_fp8m_kernel" if r["mfma"] == "fp8" else {"panel": "gemm_bf16_kernel", "hybrid":
                   "gemm_e5m2_hybrid_kernel", "fused": "gemm_e5m2_kernel"}[args.e5m2_kernel if args.group_size == 32 else "panel"]
-    if M <= 128 and K % 256 == 0 and args.group_size == 32 and args.format not in DOUBLE_SCALED:
+    if M <= 256 and K % 256 == 0 and args.group_size == 32 and args.format not in DOUBLE_SCALED:
         kernel_name = "gemm_skinny_kernel"  # few rows: B dequantized in registers straight from its codes
     out = {
         "metric": "AMXFP4 cast+GEMM TFLOPS at 4096x8192x28672", "value": round(value, 2), "unit": "TFLOP/s",

@@ -120,7 +120,7 @@ bool uses_fp4_mfma(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
   return f.group_size == 32 && (f.scale == AMX_SCALE_E8M0_FLOOR || f.scale == AMX_SCALE_E8M0_ROUND) && amx::fp4_path_supported(M, N, K);
 }
 
-// A few rows on the A side (M <= 128) with groups of 32: the weights-bound kernel that reads B's codes directly.
+// A few rows on the A side (M <= 256) with groups of 32: the weights-bound kernel that reads B's codes directly.
 bool uses_skinny(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
   return f.group_size == 32 && amx::skinny_path_supported(M, N, K);
 }

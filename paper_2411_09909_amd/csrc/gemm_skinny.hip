@@ -1,4 +1,4 @@
-// Fully quantized GEMM (Sec. 4.3) for a small number of rows on the A side (M <= 128: a few tokens against a weight
+// Fully quantized GEMM (Sec. 4.3) for a small number of rows on the A side (M <= 256: a few tokens against a weight
 // matrix). Such a product is bound by reading the weights, and the point of 4-bit weights is that they are a quarter
 // of the BF16 bytes, so this kernel reads the packed codes and scales of B straight from memory, dequantizes them in
 // registers to exact BF16 (element * scale has at most 6 significant bits) and feeds the BF16 MFMA; only the small
@@ -44,7 +44,7 @@ __device__ __forceinline__ uint32_t dequant2(uint32_t word, float s_pos, float s
   return __builtin_amdgcn_perm(f2u(v1), f2u(v0), 0x07060302u);  // upper halves: (v0 low, v1 high)
 }
 
-constexpr int kSkinnyMaxM = 128;    // at most four 32-row MFMA tiles
+constexpr int kSkinnyMaxM = 256;    // at most eight 32-row MFMA tiles
 constexpr int kSkinnyBlockK = 256;  // K block: 128 bytes of codes per row
 
 // Outer K slices for a problem with `groups` workgroups per slice and nblk K blocks: about 512 workgroups (two per CU,
@@ -57,13 +57,19 @@ static int skinny_outer_slices(int64_t groups, int64_t nblk, int& blocks_per_sli
   return (int)((nblk + blocks_per_slice - 1) / blocks_per_slice);
 }
 
+// 32-row tiles the kernel is instantiated for: 1 .. 4, 6, 8 (A's panel and the partial tiles are padded to that)
+static int skinny_row_tiles(int64_t M) {
+  const int t = (int)((M + 31) / 32);
+  return t <= 4 ? t : (t <= 6 ? 6 : 8);
+}
+
 bool skinny_path_supported(int64_t M, int64_t N, int64_t K) {
   static const bool enabled = !(getenv("AMXFP4_SKINNY") && atoi(getenv("AMXFP4_SKINNY")) == 0);
   return enabled && M <= kSkinnyMaxM && K % kSkinnyBlockK == 0 && N >= 1;
 }
 
 size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch) {
-  const int64_t Mp = round_up(M, 32);
+  const int64_t Mp = 32 * skinny_row_tiles(M);
   int bps;
   const int slices = skinny_outer_slices((N + 127) / 128 * batch, K / kSkinnyBlockK, bps);
   size_t bytes = (size_t)(batch * Mp * K * 2);                         // A panel
@@ -264,7 +270,7 @@ hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t
                                    int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
                                    const KernelTimer& timer) {
   if (!skinny_path_supported(M, N, K)) return hipErrorInvalidValue;
-  const int64_t Mp = round_up(M, 32);
+  const int64_t Mp = 32 * skinny_row_tiles(M);
   uint16_t* Ap = reinterpret_cast<uint16_t*>(workspace);
   const size_t panel_bytes = ((size_t)(batch * Mp * K * 2) + 255) / 256 * 256;
   float* partial = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(workspace) + panel_bytes);
@@ -276,11 +282,13 @@ hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t
   // E8M0 floor and round share the byte encoding
   const int sk = scale_kind == kScaleE8M0Round ? kScaleE8M0Floor : scale_kind;
   auto go = [&]<int SK, bool ASYM>() {
-    switch (Mp / 32) {
+    switch ((int)(Mp / 32)) {
       case 1: return launch_skinny<SK, ASYM, 1>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
       case 2: return launch_skinny<SK, ASYM, 2>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
       case 3: return launch_skinny<SK, ASYM, 3>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
-      default: return launch_skinny<SK, ASYM, 4>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
+      case 4: return launch_skinny<SK, ASYM, 4>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
+      case 6: return launch_skinny<SK, ASYM, 6>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
+      default: return launch_skinny<SK, ASYM, 8>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
     }
   };
   if (sk == kScaleE5M2)

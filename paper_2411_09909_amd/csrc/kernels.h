@@ -53,7 +53,7 @@ hipError_t launch_expand_bf16(int scale_kind, bool asym, int64_t group_size, con
                               const uint8_t* scales, int64_t R, int64_t K, int64_t Rp, int64_t Kp, int64_t batch,
                               bool permute, uint16_t* panel, hipStream_t s);
 
-// gemm_skinny.hip: M <= 128, K a multiple of 256, groups of 32: B dequantized in registers straight from its codes
+// gemm_skinny.hip: M <= 256, K a multiple of 256, groups of 32: B dequantized in registers straight from its codes
 // (workspace: the BF16 panel of A and, with several outer K slices, the partial tiles)
 bool skinny_path_supported(int64_t M, int64_t N, int64_t K);
 size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);

@@ -44,32 +44,33 @@ def test_size_queries(lib):
     assert binding.scales_bytes(g, 64, 1024) == 64 * 32
     assert binding.codes_bytes(f, 0, 1024) == 0
     # workspace: BF16 panels padded to 256 rows / 128 columns of K
-    assert binding.gemm_workspace_bytes(f, 200, 1024, 1024) == (256 + 1024) * 1024 * 2
+    assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == (512 + 1024) * 1024 * 2
     assert binding.gemm_workspace_bytes(f, 300, 10, 96, 2) == 2 * (512 + 256) * 128 * 2
     # power-of-two scales with K % 128 == 0 run on the FP4 MFMA straight from the caller's arrays: no workspace
-    assert binding.gemm_workspace_bytes(g, 200, 1024, 1024) == 0
+    assert binding.gemm_workspace_bytes(g, 300, 1024, 1024) == 0
     assert binding.gemm_workspace_bytes(g, 64, 1024, 96) == (256 + 1024) * 128 * 2
-    # M <= 128 with K % 256 == 0, any scale format: only A's panel (rows padded to 32) and, when K is cut into outer
+    # M <= 256 with K % 256 == 0, any scale format: only A's panel (rows padded to 32) and, when K is cut into outer
     # slices (here 4 blocks of 256 -> 4 slices, 8 workgroups each), the partial tiles
     for fmt in (f, g):
         assert binding.gemm_workspace_bytes(fmt, 64, 1024, 1024) == 64 * 1024 * 2 + 4 * 64 * 1024 * 4
         assert binding.gemm_workspace_bytes(fmt, 5, 28672 * 4, 256) == 32 * 256 * 2   # one K block: no slices
         assert binding.gemm_workspace_bytes(fmt, 100, 1024, 1024) == 128 * 1024 * 2 + 4 * 128 * 1024 * 4
+        assert binding.gemm_workspace_bytes(fmt, 130, 1024, 1024) == 192 * 1024 * 2 + 4 * 192 * 1024 * 4  # 5 -> 6 row tiles
 
 
 def test_e5m2_kernel_selection_changes_the_workspace(lib):
     f = binding.make_format(binding.FP8_E5M2, True)
     try:
         binding.select_e5m2_kernel("hybrid")   # only the A panel (FP16) lives in the workspace
-        assert binding.gemm_workspace_bytes(f, 200, 1024, 1024) == 256 * 1024 * 2
-        assert binding.gemm_workspace_bytes(f, 200, 1024, 96) == (256 + 1024) * 128 * 2  # K % 128 != 0: panel kernel
+        assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == 512 * 1024 * 2
+        assert binding.gemm_workspace_bytes(f, 300, 1024, 96) == (512 + 1024) * 128 * 2  # K % 128 != 0: panel kernel
         binding.select_e5m2_kernel("fused")
-        assert binding.gemm_workspace_bytes(f, 200, 1024, 1024) == 0
+        assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == 0
         with pytest.raises(binding.AmxError):
             binding.select_e5m2_kernel(7)
     finally:
         binding.select_e5m2_kernel("panel")
-    assert binding.gemm_workspace_bytes(f, 200, 1024, 1024) == (256 + 1024) * 1024 * 2
+    assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == (512 + 1024) * 1024 * 2
 
 
 def _q(lib, fmt, x, rows, K, rs, ks, codes, scales):

@@ -218,10 +218,11 @@ SKINNY_FORMATS = [(ref.FP8_E5M2, 1), (ref.FP8_E5M2, 0), (ref.E8M0_FLOOR, 1), (re
 @pytest.mark.parametrize("scale,asym", SKINNY_FORMATS)
 @pytest.mark.parametrize("M,N,K", [(1, 1, 256), (7, 31, 512), (32, 100, 2304), (33, 4101, 1024), (64, 1000, 4096),
                                    (16, 8192, 256), (64, 33, 8192), (65, 300, 512), (96, 129, 1024), (100, 4101, 2304),
-                                   (128, 257, 1024)])
+                                   (128, 257, 1024), (129, 300, 512), (192, 257, 1024), (200, 129, 256),
+                                   (256, 4101, 768)])
 def test_few_rows_against_many_columns(M, N, K, scale, asym):
-    """M <= 128 with K a multiple of 256: the kernel that dequantizes B in registers straight from its codes. One to
-    four row tiles, partial column tiles, one K block per workgroup up to many, with and without outer K slices."""
+    """M <= 256 with K a multiple of 256: the kernel that dequantizes B in registers straight from its codes. One to
+    eight row tiles, partial column tiles, one K block per workgroup up to many, with and without outer K slices."""
     a = synth.activations(M, K, seed=M + K, n_outlier=1, outlier_gain=60.0)
     b = synth.weights(N, K, seed=N)
     ac, as_ = ref.quantize(a, 32, scale, asym)
