@@ -252,18 +252,29 @@ def main():
                   "gemm_e5m2_hybrid_kernel", "fused": "gemm_e5m2_kernel"}[args.e5m2_kernel if args.group_size == 32 else "panel"]
     if M <= 256 and K % 256 == 0 and args.group_size == 32 and args.format not in DOUBLE_SCALED:
         kernel_name = "gemm_skinny_kernel"  # few rows: B dequantized in registers straight from its codes
+    if kernel_name == "gemm_skinny_kernel":
+        # a few rows against a weight matrix: bound by reading B's codes and scales (plus A's panel and C) from HBM
+        kbytes = N * K // 2 + N * (K // 32) * (2 if r["asym"] else 1) + ((M + 31) // 32 * 32) * K * 2 + M * N * 4
+        gbps = kbytes / (r["kern_ms"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s",
+                    "frac": round(gbps / 8000.0, 4), "traffic": None, "kernel_ms": round(r["kern_ms"], 4),
+                    "algorithmic_bytes": kbytes}
+    else:
+        roofline = {"bound": "mfma", "kernel": kernel_name, "achieved": round(achieved, 2), "peak": r["peak"],
+                    "unit": "TFLOP/s", "frac": round(achieved / r["peak"], 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES if args.format == "amxfp4_e5m2" and args.workload == WORKLOAD
+                    and args.e5m2_kernel == "panel" and args.group_size == 32 else None,
+                    "kernel_ms": round(r["kern_ms"], 4)}
     out = {
-        "metric": "AMXFP4 cast+GEMM TFLOPS at 4096x8192x28672", "value": round(value, 2), "unit": "TFLOP/s",
+        "metric": "AMXFP4 cast+GEMM TFLOPS at %dx%dx%d" % (M, K, N), "value": round(value, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": r["mfma"], "data": "synthetic",
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "format": args.format, "group_size": 16 if args.format in DOUBLE_SCALED else args.group_size,
                    "tensor_scale": args.format in DOUBLE_SCALED,
-                   "e5m2_kernel": args.e5m2_kernel if FORMATS[args.format][0] == 2 and args.group_size == 32 else None,
+                   "e5m2_kernel": ("packed_codes" if kernel_name == "gemm_skinny_kernel" else args.e5m2_kernel)
+                   if FORMATS[args.format][0] == 2 and args.group_size == 32 else None,
                    "step": "amxfp4_quantize(X) + amxfp4_gemm(Xq, Wq), W pre-cast"},
-        "roofline": {"bound": "mfma", "kernel": kernel_name, "achieved": round(achieved, 2),
-                     "peak": r["peak"], "unit": "TFLOP/s", "frac": round(achieved / r["peak"], 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES if args.format == "amxfp4_e5m2" and args.workload == WORKLOAD
-                     and args.e5m2_kernel == "panel" and args.group_size == 32 else None, "kernel_ms": round(r["kern_ms"], 4)},
+        "roofline": roofline,
         "frac_of_fp4_mfma_peak": round(value / PEAK_FP4_TFLOPS, 4),
         "breakdown_ms": {"cast_x": round(r["t_cast_x"] * 1e3, 4),
                          "gemm_call": round(ms_per_step - r["t_cast_x"] * 1e3, 4),

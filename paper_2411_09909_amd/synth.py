@@ -104,6 +104,9 @@ CONFIGS = {
     "c2_llama7b_mlp_up_2048x4096x11008": dict(M=2048, K=4096, N=11008, n_outlier=8, outlier_gain=60.0, shift=0.5),
     "c3_70b_up_4096x8192x28672": dict(M=4096, K=8192, N=28672, n_outlier=8, outlier_gain=100.0, shift=0.0),
     "c3_70b_down_4096x28672x8192": dict(M=4096, K=28672, N=8192, n_outlier=29, outlier_gain=100.0, glu=True),
+    # the same projections with a few tokens (decoding a batch of 32 sequences): weights-bound
+    "c3_70b_up_32tokens_32x8192x28672": dict(M=32, K=8192, N=28672, n_outlier=8, outlier_gain=100.0, shift=0.0),
+    "c3_70b_down_32tokens_32x28672x8192": dict(M=32, K=28672, N=8192, n_outlier=29, outlier_gain=100.0, glu=True),
 }
 
 
