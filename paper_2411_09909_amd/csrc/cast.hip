@@ -4,9 +4,13 @@
 // E8M0 with the exponent floored or rounded; optionally a tensor-wise FP32 scale underneath (Sec. 5.3, the double
 // scaling of NVFP4 / ANVFP4): elements are multiplied by its reciprocal in FP32 first and the cast runs on those.
 //
-// Contiguous cast: one lane owns 8 consecutive BF16 (one 128-bit load); the GS / 8 lanes next to each other own one
-// group. Group extrema are found with packed 16-bit integer max (non-negative BF16 patterns order like integers) and
-// DPP permutes inside the group. Every decision comes out as exact arithmetic would give it:
+// Contiguous cast: one lane owns 16 consecutive BF16 (two 128-bit loads); the GS / 16 lanes next to each other own
+// one group. Group extrema are found with packed 16-bit integer max (non-negative BF16 patterns order like integers)
+// and DPP permutes inside the group. Every decision comes out as exact arithmetic would give it. For BF16 elements
+// (the plain cast) a value that is not on a rounding boundary is at least 2^-9 of it away, which cheap arithmetic
+// resolves (the BF16 section of cast_math.h): scale = hardware FP8 conversion of amax * fl(1/6) snapped to 13 bits,
+// element = x * rcp(scale) rounded to binary16 and then to E2M1 by v_cvt_scalef32_pk_fp4_f16. For FP32 elements (a
+// tensor-wise scale underneath; values computed by another kernel) the general forms are used:
 //   - an FP8 scale is the correctly rounded FP32 quotient amax/6 rounded once more to 3 (E5M2) or 4 (E4M3)
 //     significant bits, which equals rounding the real quotient (see fp8_scale());
 //   - the element quotient x / S is formed correctly rounded away from FP32 midpoints and exactly when representable,
@@ -25,10 +29,13 @@ __device__ __forceinline__ uint32_t pk_max_i16(uint32_t a, uint32_t b) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
-// max over the 2^lpg_log2 (2, 4, 8 or 16) neighbouring lanes of a group; lpg_log2 is uniform
+// max over the 2^lpg_log2 (1, 2, 4 or 8) neighbouring lanes of a group; lpg_log2 is uniform
 __device__ __forceinline__ uint32_t group_max_u32(uint32_t v, int lpg_log2) {
-  uint32_t o = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
-  v = v > o ? v : o;
+  uint32_t o;
+  if (lpg_log2 >= 1) {
+    o = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
+    v = v > o ? v : o;
+  }
   if (lpg_log2 >= 2) {
     o = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
     v = v > o ? v : o;
@@ -37,10 +44,14 @@ __device__ __forceinline__ uint32_t group_max_u32(uint32_t v, int lpg_log2) {
     o = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x141, 0xF, 0xF, true);  // row_half_mirror: lane i <-> 7 - i of 8
     v = v > o ? v : o;
   }
-  if (lpg_log2 >= 4) {
-    o = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x140, 0xF, 0xF, true);  // row_mirror: lane i <-> 15 - i of 16
-    v = v > o ? v : o;
-  }
+  return v;
+}
+
+// the same with two non-negative 16-bit values per register, each half on its own
+__device__ __forceinline__ uint32_t group_max_pk16(uint32_t v, int lpg_log2) {
+  if (lpg_log2 >= 1) v = pk_max_i16(v, (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true));
+  if (lpg_log2 >= 2) v = pk_max_i16(v, (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true));
+  if (lpg_log2 >= 3) v = pk_max_i16(v, (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x141, 0xF, 0xF, true));
   return v;
 }
 
@@ -71,6 +82,36 @@ __device__ __forceinline__ uint32_t encode8(const float (&y)[8], float s_pos, fl
   return packed;
 }
 
+// Eight BF16 elements (four words, first element in the low half) -> eight E2M1 codes, for an FP8 or power-of-two
+// scale given by R ~ 1 / S per sign class (see the BF16 section of cast_math.h): x * R, rounded to binary16, is on the
+// same side of every E2M1 boundary as x / S and on it exactly when x / S is; the packed binary16 -> FP4 conversion
+// then rounds (nearest, ties to even, sign kept on zero results; it saturates, and a quotient beyond the binary16
+// range, which arrives as an infinity, also becomes 6).
+template <bool ASYM>
+__device__ __forceinline__ uint32_t encode8_bf16(const uint32_t (&d)[4], float r_pos, float r_neg) {
+  typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+  uint32_t packed = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float x0 = u2f(d[j] << 16), x1 = u2f(d[j] & 0xFFFF0000u);
+    float z0, z1;
+    if constexpr (ASYM) {
+      z0 = x0 * (x0 < 0.f ? r_neg : r_pos);  // (a negative zero takes r_pos and stays a negative zero)
+      z1 = x1 * (x1 < 0.f ? r_neg : r_pos);
+    } else {
+      z0 = x0 * r_pos;
+      z1 = x1 * r_pos;
+    }
+    const float2v z = {z0, z1};
+    const half2v h = __builtin_convertvector(z, half2v);
+    if (j == 0) packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f16(packed, h, 1.0f, 0);
+    if (j == 1) packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f16(packed, h, 1.0f, 1);
+    if (j == 2) packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f16(packed, h, 1.0f, 2);
+    if (j == 3) packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f16(packed, h, 1.0f, 3);
+  }
+  return packed;
+}
+
 // Largest magnitude per sign class over n floats, as bit patterns (non-negative floats order like integers).
 // Symmetric formats: both results are the largest magnitude overall.
 template <bool ASYM, int N>
@@ -87,58 +128,82 @@ __device__ __forceinline__ void class_extrema(const float (&y)[N], uint32_t& ama
   if constexpr (!ASYM) amax_n = amax_p;
 }
 
-// Contiguous cast. Thread block = 256 lanes arranged as (256 >> bx_log2) rows x (1 << bx_log2) chunks of 8 elements;
-// blockIdx.x walks the rows, blockIdx.y the chunks of a row. A group is 2^lpg_log2 neighbouring lanes; bx is a
-// multiple of that and so is the number of chunks in a row, hence a group is always whole and aligned in its wave.
+// Contiguous cast. One lane owns 16 consecutive BF16 (two 128-bit loads, one 64-bit store of codes). Thread block =
+// 256 lanes arranged as (256 >> bx_log2) rows x (1 << bx_log2) chunks of 16 elements; blockIdx.x walks the rows,
+// blockIdx.y the chunks of a row. A group is 2^lpg_log2 neighbouring lanes (1 lane for groups of 16 ... 8 lanes for
+// groups of 128); bx is a multiple of that and so is the number of chunks in a row, hence a group is always whole
+// and aligned in its wave.
 // TENSOR_SCALED (Sec. 5.3, double scaling): every element is first multiplied by the tensor-wise factor
 // tensor_pair[1] in FP32 (one rounding) and the group-wise cast runs on those FP32 values.
-template <int SCALE_KIND, bool ASYM, bool TENSOR_SCALED>
+// ONE_ROW: the launcher chose bx_log2 = 8 (a row has at least 256 chunks), so a thread block lies in one row and all
+// row arithmetic is uniform (scalar unit).
+template <int SCALE_KIND, bool ASYM, bool TENSOR_SCALED, bool ONE_ROW>
 __global__ __launch_bounds__(256) void quantize_contig_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t K,
                                                               int64_t row_stride, const float* __restrict__ tensor_pair,
                                                               uint8_t* __restrict__ codes,
                                                               uint8_t* __restrict__ scales, int bx_log2,
                                                               int lpg_log2) {
-  const int tx = threadIdx.x & ((1 << bx_log2) - 1), ty = threadIdx.x >> bx_log2;
-  const int64_t r = (int64_t)blockIdx.x * (256 >> bx_log2) + ty;
-  const int cc = (int)(blockIdx.y << bx_log2) + tx;  // chunk of 8 elements within the row
-  if (r >= rows || cc >= (int)(K >> 3)) return;
-  const uint4 v = *reinterpret_cast<const uint4*>(x + r * row_stride + (int64_t)cc * 8);
-  const uint32_t d[4] = {v.x, v.y, v.z, v.w};
-  float y[8];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) y[2 * j] = u2f(d[j] << 16), y[2 * j + 1] = u2f(d[j] & 0xFFFF0000u);
-  // group extrema (steps "max_i |V_i|" of Algorithm 1, split by sign for the asymmetric format)
-  uint32_t amax_p, amax_n;
+  const int tx = ONE_ROW ? (int)threadIdx.x : (int)threadIdx.x & ((1 << bx_log2) - 1);
+  const int ty = ONE_ROW ? 0 : (int)threadIdx.x >> bx_log2;
+  const int64_t r = ONE_ROW ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * (256 >> bx_log2) + ty;
+  const int cc = (int)(blockIdx.y << (ONE_ROW ? 8 : bx_log2)) + tx;  // chunk of 16 elements within the row
+  if (r >= rows || cc >= (int)(K >> 4)) return;
+  const uint4* src = reinterpret_cast<const uint4*>(x + r * row_stride + (int64_t)cc * 16);
+  const uint4 v0 = src[0], v1 = src[1];
+  const uint32_t d[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+  const uint32_t dlo[4] = {d[0], d[1], d[2], d[3]}, dhi[4] = {d[4], d[5], d[6], d[7]};
+  uint32_t code_lo, code_hi, sb_p, sb_n;
   if constexpr (TENSOR_SCALED) {
+    float y[16];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) y[2 * j] = u2f(d[j] << 16), y[2 * j + 1] = u2f(d[j] & 0xFFFF0000u);
     const float rt = tensor_pair[1];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) y[i] *= rt;
+    for (int i = 0; i < 16; ++i) y[i] *= rt;
+    // group extrema (steps "max_i |V_i|" of Algorithm 1, split by sign for the asymmetric format)
+    uint32_t amax_p, amax_n;
     class_extrema<ASYM>(y, amax_p, amax_n);
-  } else if constexpr (ASYM) {
-    // BF16 patterns: packed 16-bit integer maxima; negative patterns (sign bit set) compare below zero as int16
-    uint32_t p = pk_max_i16(pk_max_i16(d[0], d[1]), pk_max_i16(d[2], d[3]));
-    p = pk_max_i16(p, 0u);
-    uint32_t n = pk_max_i16(pk_max_i16(d[0] ^ 0x80008000u, d[1] ^ 0x80008000u),
-                            pk_max_i16(d[2] ^ 0x80008000u, d[3] ^ 0x80008000u));
-    n = pk_max_i16(n, 0u);
-    amax_p = ((p & 0xFFFFu) > (p >> 16) ? (p & 0xFFFFu) : (p >> 16)) << 16;
-    amax_n = ((n & 0xFFFFu) > (n >> 16) ? (n & 0xFFFFu) : (n >> 16)) << 16;
+    amax_p = group_max_u32(amax_p, lpg_log2);
+    if constexpr (ASYM) amax_n = group_max_u32(amax_n, lpg_log2);
+    float s_pos, r_pos, s_neg, r_neg;
+    sb_p = encode_scale_sr<SCALE_KIND>(u2f(amax_p), s_pos, r_pos);
+    sb_n = sb_p, s_neg = s_pos, r_neg = r_pos;
+    if constexpr (ASYM) sb_n = encode_scale_sr<SCALE_KIND>(u2f(amax_n), s_neg, r_neg);
+    const float ylo[8] = {y[0], y[1], y[2], y[3], y[4], y[5], y[6], y[7]};
+    const float yhi[8] = {y[8], y[9], y[10], y[11], y[12], y[13], y[14], y[15]};
+    code_lo = encode8<SCALE_KIND, ASYM>(ylo, s_pos, r_pos, s_neg, r_neg);
+    code_hi = encode8<SCALE_KIND, ASYM>(yhi, s_pos, r_pos, s_neg, r_neg);
   } else {
-    uint32_t a = pk_max_i16(pk_max_i16(d[0] & 0x7FFF7FFFu, d[1] & 0x7FFF7FFFu),
-                            pk_max_i16(d[2] & 0x7FFF7FFFu, d[3] & 0x7FFF7FFFu));
-    amax_p = amax_n = ((a & 0xFFFFu) > (a >> 16) ? (a & 0xFFFFu) : (a >> 16)) << 16;
+    // Group extrema on the BF16 patterns with packed 16-bit integer maxima: as int16 a negative number's pattern is
+    // below zero, so max(pattern, 0) keeps the non-negative elements and, after flipping the sign bits, the
+    // magnitudes of the negative ones. The asymmetric format carries both classes through the lane exchange in one
+    // register (positive class in the low half, negative in the high half).
+    uint32_t m;
+    if constexpr (ASYM) {
+      const uint32_t f = 0x80008000u;
+      const uint32_t p = pk_max_i16(pk_max_i16(pk_max_i16(d[0], d[1]), pk_max_i16(d[2], d[3])),
+                                    pk_max_i16(pk_max_i16(d[4], d[5]), pk_max_i16(d[6], d[7])));
+      const uint32_t n = pk_max_i16(pk_max_i16(pk_max_i16(d[0] ^ f, d[1] ^ f), pk_max_i16(d[2] ^ f, d[3] ^ f)),
+                                    pk_max_i16(pk_max_i16(d[4] ^ f, d[5] ^ f), pk_max_i16(d[6] ^ f, d[7] ^ f)));
+      const uint32_t pl = pk_max_i16(p, p >> 16), nh = pk_max_i16(n, n << 16);
+      m = pk_max_i16((pl & 0xFFFFu) | (nh & 0xFFFF0000u), 0u);
+    } else {
+      const uint32_t k = 0x7FFF7FFFu;
+      const uint32_t a = pk_max_i16(pk_max_i16(pk_max_i16(d[0] & k, d[1] & k), pk_max_i16(d[2] & k, d[3] & k)),
+                                    pk_max_i16(pk_max_i16(d[4] & k, d[5] & k), pk_max_i16(d[6] & k, d[7] & k)));
+      m = pk_max_i16(a, a >> 16) & 0xFFFFu;
+    }
+    m = group_max_pk16(m, lpg_log2);
+    float r_pos, r_neg;
+    sb_p = encode_scale_r_bf16<SCALE_KIND>(u2f(m << 16), r_pos);
+    sb_n = sb_p, r_neg = r_pos;
+    if constexpr (ASYM) sb_n = encode_scale_r_bf16<SCALE_KIND>(u2f(m & 0xFFFF0000u), r_neg);
+    code_lo = encode8_bf16<ASYM>(dlo, r_pos, r_neg);
+    code_hi = encode8_bf16<ASYM>(dhi, r_pos, r_neg);
   }
-  amax_p = group_max_u32(amax_p, lpg_log2);
-  if constexpr (ASYM) amax_n = group_max_u32(amax_n, lpg_log2);
-  float s_pos, r_pos, s_neg, r_neg;
-  const uint32_t sb_p = encode_scale_sr<SCALE_KIND>(u2f(amax_p), s_pos, r_pos);
-  uint32_t sb_n = sb_p;
-  s_neg = s_pos, r_neg = r_pos;
-  if constexpr (ASYM) sb_n = encode_scale_sr<SCALE_KIND>(u2f(amax_n), s_neg, r_neg);
-  *reinterpret_cast<uint32_t*>(codes + r * (K >> 1) + (int64_t)cc * 4) =
-      encode8<SCALE_KIND, ASYM>(y, s_pos, r_pos, s_neg, r_neg);
+  *reinterpret_cast<uint2*>(codes + r * (K >> 1) + (int64_t)cc * 8) = make_uint2(code_lo, code_hi);
   if ((tx & ((1 << lpg_log2) - 1)) == 0) {
-    const int64_t g = r * (K >> (lpg_log2 + 3)) + (cc >> lpg_log2);
+    const int64_t g = r * (K >> (lpg_log2 + 4)) + (cc >> lpg_log2);
     if constexpr (ASYM)
       *reinterpret_cast<uint16_t*>(scales + g * 2) = (uint16_t)(sb_p | (sb_n << 8));
     else
@@ -297,18 +362,20 @@ static hipError_t launch_qc(const uint16_t* x, int64_t rows, int64_t K, int gs_l
                             const float* tensor_pair, uint8_t* codes, uint8_t* scales, hipStream_t s) {
   // block shape: as many chunks of a row as fit (power of two, one group .. 256), the rest of the 256 lanes go to
   // more rows
-  const int64_t chunks = K / 8;
-  const int lpg_log2 = gs_log2 - 3;
-  int bx_log2 = lpg_log2 < 2 ? 2 : lpg_log2;
+  const int64_t chunks = K / 16;
+  const int lpg_log2 = gs_log2 - 4;
+  int bx_log2 = lpg_log2;
   while (bx_log2 < 8 && (int64_t(1) << (bx_log2 + 1)) <= chunks) ++bx_log2;
   const int64_t bx = int64_t(1) << bx_log2, by = 256 >> bx_log2;
   const dim3 grid((unsigned)((rows + by - 1) / by), (unsigned)((chunks + bx - 1) / bx));
+  auto launch = [&]<bool SCALED, bool ONE_ROW>() {
+    hipLaunchKernelGGL((quantize_contig_kernel<SK, ASYM, SCALED, ONE_ROW>), grid, dim3(256), 0, s, x, rows, K,
+                       row_stride, tensor_pair, codes, scales, bx_log2, lpg_log2);
+  };
   if (tensor_pair)
-    hipLaunchKernelGGL((quantize_contig_kernel<SK, ASYM, true>), grid, dim3(256), 0, s, x, rows, K, row_stride,
-                       tensor_pair, codes, scales, bx_log2, lpg_log2);
+    bx_log2 == 8 ? launch.template operator()<true, true>() : launch.template operator()<true, false>();
   else
-    hipLaunchKernelGGL((quantize_contig_kernel<SK, ASYM, false>), grid, dim3(256), 0, s, x, rows, K, row_stride,
-                       tensor_pair, codes, scales, bx_log2, lpg_log2);
+    bx_log2 == 8 ? launch.template operator()<false, true>() : launch.template operator()<false, false>();
   return hipGetLastError();
 }
 

@@ -73,4 +73,53 @@ __device__ __forceinline__ float quotient(float x, float S, float R) {
   }
 }
 
+// ---- BF16 inputs -----------------------------------------------------------------------------------------------
+// When the elements are BF16 numbers (8 significant bits) the exact decisions need less arithmetic, because a
+// quantity that is not exactly on a rounding boundary is far from it:
+//  - scale: a boundary t of the FP8 grid has MBITS + 2 significant bits, so 6 t is a multiple of the BF16 spacing
+//    around it and amax != 6 t implies |amax / 6 - t| >= 2^-8.5 t. The product amax * fl(1/6) (relative error below
+//    2^-22), snapped to 13 significant bits, therefore lies on the same side of every boundary as amax / 6, and
+//    lands on the boundary exactly when amax / 6 does; the hardware FP8 conversion (nearest, ties to even,
+//    subnormals kept) then rounds as the real quotient would be rounded.
+//  - element: an E2M1 boundary b times the scale has at most 7 significant bits, so x != b S implies
+//    |x / S - b| >= 2^-9 b. The product x * R with R = rcp(S) (relative error below 2^-21), rounded to binary16
+//    (11 significant bits), keeps its side of every boundary and is b exactly when x / S is; see encode8().
+
+typedef float float2v __attribute__((ext_vector_type(2)));
+
+// FP8 scale byte (MBITS = 2: E5M2, 3: E4M3) of a sign class whose largest magnitude amax is a BF16 number, and
+// R ~ 1 / scale (0 when the scale is 0).
+template <int MBITS>
+__device__ __forceinline__ uint32_t fp8_scale_bf16(float amax, float& R) {
+  const float q0 = amax * 0x1.555556p-3f;                               // ~ amax / 6
+  uint32_t qb = (f2u(q0) + 0x400u) & 0xFFFFF800u;                      // 13 significant bits
+  const uint32_t maxb = MBITS == 2 ? 0x47600000u : 0x43E00000u;         // 57344, 448: the largest finite scale
+  qb = qb < maxb ? qb : maxb;                                           // (non-negative floats order like integers)
+  const float q = u2f(qb);
+  uint32_t byte;
+  float S;
+  if constexpr (MBITS == 2) {
+    byte = (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(q, q, 0, false) & 0xFFu;
+    S = (float)__builtin_bit_cast(_Float16, (uint16_t)(byte << 8));
+  } else {
+    byte = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(q, q, 0, false) & 0xFFu;
+    S = (float)__builtin_bit_cast(_Float16, (uint16_t)(byte << 7)) * 256.0f;
+  }
+  R = byte ? __builtin_amdgcn_rcpf(S) : 0.f;
+  return byte;
+}
+
+// encode_scale_sr() for a BF16 amax: byte and R only (the element step needs no S).
+template <int SCALE_KIND>
+__device__ __forceinline__ uint32_t encode_scale_r_bf16(float amax, float& R) {
+  if constexpr (SCALE_KIND == kScaleE5M2) {
+    return fp8_scale_bf16<2>(amax, R);
+  } else if constexpr (SCALE_KIND == kScaleE4M3) {
+    return fp8_scale_bf16<3>(amax, R);
+  } else {
+    float S;
+    return encode_scale_sr<SCALE_KIND>(amax, S, R);
+  }
+}
+
 }  // namespace amx
