@@ -38,7 +38,11 @@ size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch)
 // 16 j + 4 h + {0, 1, 2, 3, 8, 9, 10, 11} instead of 16 j + 8 h + {0 .. 7}. That is the order in which the rows of a
 // 32x32 MFMA accumulator sit in a lane's registers, so an accumulator tile can be fed back as the other operand of a
 // product over those rows without a transpose (the fused attention kernel multiplies probabilities with V this way).
-template <int SCALE_KIND, bool ASYM, bool F16, bool PERMUTE = false>
+// HALF_LINE: within every block of 256 along K (8 groups), k-step s (0 .. 15) holds, in lane half h, the 8 elements
+// s % 4 of group 4 h + s / 4 instead of the 8 elements h of the 16 that follow 16 s: a lane half then draws all its
+// 16 k-steps from one contiguous half (64 bytes of codes) of the block. The few-rows kernel reads its B operand in
+// that order straight from the packed codes and needs A to match (a product sums over k in any order).
+template <int SCALE_KIND, bool ASYM, bool F16, bool PERMUTE = false, bool HALF_LINE = false>
 __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__ codes,
                                                      const uint8_t* __restrict__ scales, int64_t R, int64_t K,
                                                      int64_t Rp, int64_t Kp, int gs_log2,
@@ -92,6 +96,15 @@ __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__
       else
         o[t][j] = (f2u(v0) >> 16) | (f2u(v1) & 0xFFFF0000u);  // truncation is exact: <= 6 significant bits
     }
+  }
+  if constexpr (HALF_LINE) {
+    const int64_t blk = g >> 3;
+    const int gl = (int)(g & 7);
+    uint16_t* d2 = panel + ((b * (Rp >> 5) + rb) * (Kp >> 4) + blk * 16 + (gl & 3) * 4) * 512 +
+                   ((gl >> 2) * 32 + (lane & 31)) * 8;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) *reinterpret_cast<uint4*>(d2 + t * 512) = make_uint4(o[t][0], o[t][1], o[t][2], o[t][3]);
+    return;
   }
 #pragma unroll
   for (int t = 0; t < 4; ++t) {  // k block (t / 2), lane half (t % 2) of the block's two fragments
@@ -283,6 +296,23 @@ hipError_t launch_expand_bf16(int scale_kind, bool asym, int64_t group_size, con
   if (scale_kind == kScaleE5M2) return asym ? go.template operator()<kScaleE5M2, true>() : go.template operator()<kScaleE5M2, false>();
   if (scale_kind == kScaleE4M3) return asym ? go.template operator()<kScaleE4M3, true>() : go.template operator()<kScaleE4M3, false>();
   return asym ? go.template operator()<kScaleE8M0Floor, true>() : go.template operator()<kScaleE8M0Floor, false>();
+}
+
+hipError_t launch_expand_half_line(int scale_kind, bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R,
+                                   int64_t K, int64_t Rp, int64_t batch, uint16_t* panel, hipStream_t s) {
+  if (K % 256 != 0 || Rp % 32 != 0) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)(K / 256), (unsigned)(Rp / 32), (unsigned)batch);
+  auto go = [&]<int SK, bool ASYM, bool F16>() {
+    hipLaunchKernelGGL((expand_kernel<SK, ASYM, F16, false, true>), grid, dim3(256), 0, s, codes, scales, R, K, Rp, K,
+                       5, panel);
+    return hipGetLastError();
+  };
+  if (scale_kind == kScaleE5M2)
+    return asym ? go.template operator()<kScaleE5M2, true, true>() : go.template operator()<kScaleE5M2, false, true>();
+  if (scale_kind == kScaleE4M3)
+    return asym ? go.template operator()<kScaleE4M3, true, false>() : go.template operator()<kScaleE4M3, false, false>();
+  return asym ? go.template operator()<kScaleE8M0Floor, true, false>()
+              : go.template operator()<kScaleE8M0Floor, false, false>();
 }
 
 hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K,

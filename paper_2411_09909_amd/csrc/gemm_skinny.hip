@@ -1,16 +1,29 @@
 // Fully quantized GEMM (Sec. 4.3) for a small number of rows on the A side (M <= 256: a few tokens against a weight
 // matrix). Such a product is bound by reading the weights, and the point of 4-bit weights is that they are a quarter
 // of the BF16 bytes, so this kernel reads the packed codes and scales of B straight from memory, dequantizes them in
-// registers to exact BF16 (element * scale has at most 6 significant bits) and feeds the BF16 MFMA; only the small
-// A operand goes through a BF16 panel (expand_kernel). No operand of B is ever written back.
+// registers to exact 16-bit floats (element * scale has at most 6 significant bits) and feeds the 16-bit MFMA; only
+// the small A operand goes through a panel (expand_kernel). No operand of B is ever written back.
+// The dequantization is the kernel's bound (vector instructions per MFMA), so it uses packed 16-bit arithmetic where
+// the scale format allows it:
+//   FP8-E5M2 scales: FP16 operands biased by 2^-3 (every element * scale * 2^-3 lies in [2^-20, 43008] and has at most
+//     5 significant bits: an FP16 number, subnormals included). The scale byte is the upper byte of an FP16, so a pair
+//     of scales is one byte permute; v_cvt_scalef32_pk_f16_fp4 turns two codes into two FP16 elements / 8, a packed
+//     arithmetic shift of the sign bits selects the scale pair of each sign class and one packed multiply finishes.
+//     A comes from an FP16 panel with the same bias and the result is multiplied by 2^6.
+//   power-of-two scales: v_cvt_scalef32_pk_bf16_fp4 applies the scale itself (two codes -> two BF16 per instruction);
+//     the asymmetric format converts with both scales and selects per sign.
+//   FP8-E4M3 scales: FP32 conversion, multiply, truncate to BF16.
 //
-// Work split: one workgroup = 4 waves = 4 neighbouring tiles of 32 columns of C (32 rows of B each) over one outer K
-// slice. K is walked in blocks of 256. The workgroup brings the A operand into LDS once, by direct-to-LDS loads, in
-// half blocks (M x 128 BF16 = 8 fragments per 32 rows), double buffered; each lane owns one B row (lane % 32 of its wave's
-// tile) and loads that row's 128 bytes of codes (one cache line, fetched exactly once) and its 8 scale entries one
-// block ahead, then runs 16 k-steps of 16 from registers: lane half h = lane / 32 turns codes 16 j + 8 h .. + 7 of a
-// group into the 8 BF16 of its B fragment. With more than one outer slice the partial tiles go to the workspace and a
-// second kernel adds them in a fixed order (no atomics: results are reproducible).
+// Work split: one workgroup = 8 (4 with more than four row tiles) waves = neighbouring tiles of 32 columns of C (32
+// rows of B each) over one outer K slice. K is walked in blocks of 256. The workgroup brings the A operand into LDS
+// once, by direct-to-LDS loads, in stages of half a block (a whole block for one or two row tiles), double buffered.
+// Each lane owns half a B row's block: row lane % 32 of its wave's tile, groups 4 h .. 4 h + 3 for lane half
+// h = lane / 32, i.e. 64 contiguous bytes of codes (the two halves of a wave share every 128-byte cache line, fetched
+// once) and 4 scale entries, loaded one block ahead. It then runs the block's 16 k-steps from registers: k-step s
+// multiplies the 8 codes s % 4 of the lane's group s / 4. The k order this gives a block (half h of k-step s = the 8
+// elements s % 4 of group 4 h + s / 4) is not the natural one; the A panel is written in the same order
+// (expand_kernel<HALF_LINE>), and a sum over k does not depend on it. With more than one outer slice the partial tiles
+// go to the workspace and a second kernel adds them in a fixed order (no atomics: results are reproducible).
 #include <stdlib.h>
 
 #include "device_formats.h"
@@ -25,33 +38,112 @@ typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 typedef uint32_t u32x2_a4 __attribute__((ext_vector_type(2), aligned(4)));
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
 
-// Two FP4 codes (byte SEL of `word`) -> their dequantized values as a pair of BF16: the hardware FP4 -> FP32
-// conversion gives the signed elements, each is multiplied by the scale of its sign class (picked with the sign bit
-// smeared over the word) and the product, which has at most 6 significant bits, is truncated to BF16 exactly.
+// all ones in each 16-bit half whose sign bit is set
+__device__ __forceinline__ uint32_t pk_sign_mask(uint32_t v) {
+  uint32_t m = __builtin_bit_cast(uint32_t, __builtin_bit_cast(i16x2, v) >> (i16x2){15, 15});
+  // (an empty statement the optimiser cannot look through: otherwise the mask select that follows is rewritten into
+  // two compares, two conditional moves and a byte permute)
+  asm("" : "+v"(m));
+  return m;
+}
+
+// Eight FP4 codes (one word, first code in the lowest nibble) -> eight dequantized 16-bit floats, two per register.
+// The scale pair (s_pos, s_neg) comes as bit patterns whose meaning depends on the format (skinny_scales()).
+//
+// FP8-E5M2 scales, FP16 result biased by 2^-3: the pair holds each scale twice, as packed FP16.
 template <bool ASYM, int SEL>
-__device__ __forceinline__ uint32_t dequant2(uint32_t word, float s_pos, float s_neg) {
+__device__ __forceinline__ uint32_t dequant2_f16(uint32_t word, uint32_t s_pos, uint32_t s_neg) {
+  const f16x2 e = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(word, 0.125f, SEL);
+  uint32_t sc = s_pos;
+  if constexpr (ASYM) {
+    const uint32_t m = pk_sign_mask(__builtin_bit_cast(uint32_t, e));
+    sc = (s_neg & m) | (s_pos & ~m);
+  }
+  return __builtin_bit_cast(uint32_t, e * __builtin_bit_cast(f16x2, sc));
+}
+
+// Power-of-two scales, BF16 result: the pair holds floats whose exponent field is the scale byte (the conversion
+// reads only that field).
+template <bool ASYM, int SEL>
+__device__ __forceinline__ uint32_t dequant2_pot(uint32_t word, uint32_t s_pos, uint32_t s_neg) {
+  const uint32_t p = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, u2f(s_pos), SEL));
+  if constexpr (ASYM) {
+    const uint32_t n = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, u2f(s_neg), SEL));
+    const uint32_t m = pk_sign_mask(p);
+    return (n & m) | (p & ~m);
+  } else {
+    return p;
+  }
+}
+
+// Any other scale (FP8-E4M3), BF16 result: the pair holds the scales as floats; the hardware FP4 -> FP32 conversion
+// gives the signed elements, each is multiplied by the scale of its sign class and the product, which has at most 6
+// significant bits, is truncated to BF16 exactly.
+template <bool ASYM, int SEL>
+__device__ __forceinline__ uint32_t dequant2_f32(uint32_t word, uint32_t s_pos, uint32_t s_neg) {
   const f32x2 e = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(word, 1.0f, SEL);
   float v0, v1;
   if constexpr (ASYM) {
     const uint32_t m0 = (uint32_t)((int32_t)f2u(e[0]) >> 31), m1 = (uint32_t)((int32_t)f2u(e[1]) >> 31);
-    v0 = e[0] * u2f((f2u(s_neg) & m0) | (f2u(s_pos) & ~m0));
-    v1 = e[1] * u2f((f2u(s_neg) & m1) | (f2u(s_pos) & ~m1));
+    v0 = e[0] * u2f((s_neg & m0) | (s_pos & ~m0));
+    v1 = e[1] * u2f((s_neg & m1) | (s_pos & ~m1));
   } else {
-    v0 = e[0] * s_pos;
-    v1 = e[1] * s_pos;
+    v0 = e[0] * u2f(s_pos);
+    v1 = e[1] * u2f(s_pos);
   }
   return __builtin_amdgcn_perm(f2u(v1), f2u(v0), 0x07060302u);  // upper halves: (v0 low, v1 high)
 }
 
+template <int SCALE_KIND, bool ASYM>
+__device__ __forceinline__ u32x4 dequant_word(uint32_t word, uint32_t s_pos, uint32_t s_neg) {
+  if constexpr (SCALE_KIND == kScaleE5M2)
+    return u32x4{dequant2_f16<ASYM, 0>(word, s_pos, s_neg), dequant2_f16<ASYM, 1>(word, s_pos, s_neg),
+                 dequant2_f16<ASYM, 2>(word, s_pos, s_neg), dequant2_f16<ASYM, 3>(word, s_pos, s_neg)};
+  else if constexpr (SCALE_KIND == kScaleE8M0Floor)
+    return u32x4{dequant2_pot<ASYM, 0>(word, s_pos, s_neg), dequant2_pot<ASYM, 1>(word, s_pos, s_neg),
+                 dequant2_pot<ASYM, 2>(word, s_pos, s_neg), dequant2_pot<ASYM, 3>(word, s_pos, s_neg)};
+  else
+    return u32x4{dequant2_f32<ASYM, 0>(word, s_pos, s_neg), dequant2_f32<ASYM, 1>(word, s_pos, s_neg),
+                 dequant2_f32<ASYM, 2>(word, s_pos, s_neg), dequant2_f32<ASYM, 3>(word, s_pos, s_neg)};
+}
+
+// The scale pair of a lane's group GI (0 .. 3) from its scale registers (asymmetric: bytes pos, neg of the four
+// groups in S[0], S[1]; symmetric: the four bytes of S[0]), in the form dequant_word() takes.
+template <int SCALE_KIND, bool ASYM, int GI>
+__device__ __forceinline__ void skinny_scales(const uint32_t (&S)[2], uint32_t& s_pos, uint32_t& s_neg) {
+  constexpr uint32_t bp = ASYM ? 2 * (GI & 1) : GI, bn = ASYM ? bp + 1 : bp;
+  const uint32_t reg = S[ASYM ? GI >> 1 : 0];
+  if constexpr (SCALE_KIND == kScaleE5M2) {
+    // byte -> (byte << 8) in both halves; the cast never sets a scale's sign bit and it is ignored
+    s_pos = __builtin_amdgcn_perm(0u, reg, (bp << 24) | (0x0Cu << 16) | (bp << 8) | 0x0Cu) & 0x7F007F00u;
+    s_neg = ASYM ? __builtin_amdgcn_perm(0u, reg, (bn << 24) | (0x0Cu << 16) | (bn << 8) | 0x0Cu) & 0x7F007F00u : s_pos;
+  } else if constexpr (SCALE_KIND == kScaleE8M0Floor) {
+    s_pos = ((reg >> (8 * bp)) & 255u) << 23;
+    s_neg = ASYM ? ((reg >> (8 * bn)) & 255u) << 23 : s_pos;
+  } else {
+    s_pos = f2u(scale_value<SCALE_KIND>((reg >> (8 * bp)) & 255u));
+    s_neg = ASYM ? f2u(scale_value<SCALE_KIND>((reg >> (8 * bn)) & 255u)) : s_pos;
+  }
+}
+
 constexpr int kSkinnyMaxM = 256;    // at most eight 32-row MFMA tiles
 constexpr int kSkinnyBlockK = 256;  // K block: 128 bytes of codes per row
+// Waves per workgroup = 32-column tiles of C it covers: every workgroup reads the whole A slice, so wider workgroups
+// mean less A traffic; with more than four row tiles a wave needs more than the 256 registers an 8-wave workgroup
+// leaves it.
+constexpr int skinny_waves(int row_tiles) { return row_tiles <= 4 ? 8 : 4; }
 
 // Outer K slices for a problem with `groups` workgroups per slice and nblk K blocks: about 512 workgroups (two per CU,
 // 4 waves each) if the K blocks allow it. Returns the number of slices and sets the blocks per slice; every slice has
 // at least one block ((slices - 1) * blocks_per_slice < nblk).
 static int skinny_outer_slices(int64_t groups, int64_t nblk, int& blocks_per_slice) {
-  int64_t want = (512 + groups - 1) / groups;
+  static const int64_t target = getenv("AMXFP4_SKINNY_WGS") ? atoi(getenv("AMXFP4_SKINNY_WGS")) : 512;
+  int64_t want = (target + groups - 1) / groups;
   want = want < 1 ? 1 : (want > nblk ? nblk : want);
   blocks_per_slice = (int)((nblk + want - 1) / want);
   return (int)((nblk + blocks_per_slice - 1) / blocks_per_slice);
@@ -69,9 +161,9 @@ bool skinny_path_supported(int64_t M, int64_t N, int64_t K) {
 }
 
 size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch) {
-  const int64_t Mp = 32 * skinny_row_tiles(M);
+  const int64_t Mp = 32 * skinny_row_tiles(M), cols = 32 * skinny_waves(skinny_row_tiles(M));
   int bps;
-  const int slices = skinny_outer_slices((N + 127) / 128 * batch, K / kSkinnyBlockK, bps);
+  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, bps);
   size_t bytes = (size_t)(batch * Mp * K * 2);                         // A panel
   bytes = (bytes + 255) / 256 * 256;
   if (slices > 1) bytes += (size_t)(batch * slices * Mp * N * 4);      // partial tiles
@@ -79,15 +171,22 @@ size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batc
 }
 
 // grid: (ceil(N / 128), outer slices, batch); block 256 = 4 waves.
+// (B_codes, B_scales and out are deliberately not declared restrict: loads the compiler knows to be from memory nobody
+// writes may be moved across the barriers, down to their first use, which undoes the prefetch.)
 // out: C (ld_out = ldc) when gridDim.y == 1, else partials [batch][slice][MT * 32][N].
 template <int SCALE_KIND, bool ASYM, int MT>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const uint16_t* __restrict__ Ap,
-                                                          const uint8_t* __restrict__ B_codes,
-                                                          const uint8_t* __restrict__ B_scales, float* __restrict__ out,
+__global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(const uint16_t* __restrict__ Ap, const uint8_t* B_codes,
+                                                          const uint8_t* B_scales, float* out,
                                                           int64_t M, int64_t N, int64_t K, int64_t ld_out,
                                                           int64_t batch_stride_out, int64_t slice_stride_out,
                                                           int blocks_per_slice) {
-  constexpr int kFragsPerHalf = MT * (kSkinnyBlockK / 32);  // A fragments of half a K block (8 k-steps)
+  // One step of the main loop multiplies one A stage: half a K block (8 k-steps of 16), or a whole one when there are
+  // so few row tiles that half a block is too little work between two barriers to cover the latency of the loads
+  // that fill the other stage.
+  constexpr int kStageSteps = MT <= 2 ? 16 : 8;
+  constexpr int kSkinnyWaves = skinny_waves(MT);
+  constexpr int kFragsPerHalf = MT * kStageSteps;  // A fragments of one stage
+  constexpr bool kF16 = SCALE_KIND == kScaleE5M2;       // FP16 operands biased by 2^-3 each, else BF16
   // two stages, separate arrays so that loads into one are known not to alias reads of the other
   __shared__ __attribute__((aligned(1024))) uint8_t ldsA0[kFragsPerHalf * kFragBytes];
   __shared__ __attribute__((aligned(1024))) uint8_t ldsA1[kFragsPerHalf * kFragBytes];
@@ -95,7 +194,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const uint16_t* __rest
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int h = lane >> 5;
   const int64_t b = blockIdx.z;
-  const int64_t n = ((int64_t)blockIdx.x * 4 + wave) * 32 + (lane & 31);
+  const int64_t n = ((int64_t)blockIdx.x * kSkinnyWaves + wave) * 32 + (lane & 31);
   const bool valid = n < N;
   const int64_t G = K >> 5, nblk = K / kSkinnyBlockK;
   constexpr int kScaleBytes = ASYM ? 2 : 1;
@@ -104,9 +203,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const uint16_t* __rest
   const int nb = (int)((s_begin + blocks_per_slice < nblk ? s_begin + blocks_per_slice : nblk) - s_begin);  // >= 1
 
   const int64_t row = valid ? b * N + n : 0;  // (rows past N read row 0 and are discarded)
-  const uint8_t* codes_row = B_codes + row * (K >> 1) + s_begin * (kSkinnyBlockK / 2);
-  const uint8_t* scales_row = B_scales + (row * G + s_begin * 8) * kScaleBytes;
-  // A panel of this batch entry: [MT row blocks][K / 16 fragments][64 lanes][8 BF16]; raw buffer, reads past the end
+  // lane half h owns groups 4 h .. 4 h + 3 of every block: 64 contiguous bytes of codes, 4 scale entries
+  const uint8_t* codes_row = B_codes + row * (K >> 1) + s_begin * (kSkinnyBlockK / 2) + h * 64;
+  const uint8_t* scales_row = B_scales + (row * G + s_begin * 8 + h * 4) * kScaleBytes;
+  // A panel of this batch entry: [MT row blocks][K / 16 fragments][64 lanes][8 x 16 bit]; raw buffer, reads past the end
   // return zero
   const int kfrags = (int)(K >> 4);
   const __amdgpu_buffer_rsrc_t Ar = __builtin_amdgcn_make_buffer_rsrc(
@@ -121,101 +221,125 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const uint16_t* __rest
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
 
-  // wave w brings fragments w, w + 4, .. of A half block HB (of this slice) into stage DST: fragment f = row block
-  // f / 8, k-step f % 8 of the half
+  // wave w brings fragments w, w + 4, .. of A stage block HB (half or whole K block number HB of this slice) into
+  // stage DST: fragment f = row block f / kStageSteps, k-step f % kStageSteps of the stage block
 #define AMX_SKINNY_LOAD_A(HB, DST)                                                                                 \
-  _Pragma("unroll") for (int i_ = 0; i_ < kFragsPerHalf / 4; ++i_) {                                               \
-    const int f_ = wave + 4 * i_;                                                                                  \
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(Ar, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, lane_off,               \
-                                             ((f_ >> 3) * kfrags + first_frag + (HB) * 8 + (f_ & 7)) * kFragBytes,  \
-                                             0, 0);                                                                \
+  _Pragma("unroll") for (int i_ = 0; i_ < kFragsPerHalf / kSkinnyWaves; ++i_) {                                    \
+    const int f_ = wave + kSkinnyWaves * i_;                                                                       \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                                      \
+        Ar, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, lane_off,                                                    \
+        ((f_ / kStageSteps) * kfrags + first_frag + (HB) * kStageSteps + (f_ % kStageSteps)) * kFragBytes, 0, 0);  \
   }
-  // this lane's row: one cache line of codes (8 groups) and the 8 scale entries of block I
+  // this lane's half of its row's cache line of codes (4 groups) and the 4 scale entries of block I
 #define AMX_SKINNY_LOAD_B(I, W, S)                                                                                 \
   {                                                                                                                \
     const u32x4* csrc_ = reinterpret_cast<const u32x4*>(codes_row + (int64_t)(I) * (kSkinnyBlockK / 2));           \
     W[0] = csrc_[0], W[1] = csrc_[1], W[2] = csrc_[2], W[3] = csrc_[3];                                            \
-    W[4] = csrc_[4], W[5] = csrc_[5], W[6] = csrc_[6], W[7] = csrc_[7];                                            \
     if constexpr (ASYM) {                                                                                          \
-      const u32x4_a4 t_ = *reinterpret_cast<const u32x4_a4*>(scales_row + (int64_t)(I) * 16);                      \
-      S[0] = t_[0], S[1] = t_[1], S[2] = t_[2], S[3] = t_[3];                                                      \
+      const u32x2_a4 t_ = *reinterpret_cast<const u32x2_a4*>(scales_row + (int64_t)(I) * 16);                      \
+      S[0] = t_[0], S[1] = t_[1];                                                                                  \
     } else {                                                                                                       \
-      const u32x2_a4 t_ = *reinterpret_cast<const u32x2_a4*>(scales_row + (int64_t)(I) * 8);                       \
-      S[0] = t_[0], S[1] = t_[1], S[2] = 0, S[3] = 0;                                                              \
+      S[0] = *reinterpret_cast<const uint32_t*>(scales_row + (int64_t)(I) * 8), S[1] = 0;                          \
     }                                                                                                              \
   }
-  // The two k-steps of group GI (a literal: register arrays must not be indexed with a run-time value) of one block:
-  // A fragments from stage SRC (the half block that holds the group), B from the registers W / S
+  // The four k-steps of the lane's group GI (a literal: register arrays must not be indexed with a run-time value) of
+  // one block: k-step 4 GI + t multiplies word t of the group; A fragments from stage SRC, B from the registers W / S
+#ifdef AMX_SKINNY_PROBE_NOCOMPUTE
+#define AMX_SKINNY_GROUP(SRC, W, S, GI)                                                                            \
+  { acc[0][GI] += u2f((W[GI][0] ^ W[GI][1] ^ W[GI][2] ^ W[GI][3] ^ S[(GI) >> 1]) & 0x3FFFFFFFu); }
+#else
+#define AMX_SKINNY_KSTEP(SRC, WORD, KF)                                                                            \
+  {                                                                                                                \
+    const u32x4 q = dequant_word<SCALE_KIND, ASYM>(WORD, s_pos, s_neg);                                            \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                                            \
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>((SRC) + (mt * kStageSteps + (KF)) * kFragBytes + lane_off); \
+      if constexpr (kF16)                                                                                          \
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),                             \
+                                                         __builtin_bit_cast(f16x8, q), acc[mt], 0, 0, 0);          \
+      else                                                                                                         \
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, q), acc[mt], 0, 0, 0);     \
+    }                                                                                                              \
+  }
 #define AMX_SKINNY_GROUP(SRC, W, S, GI)                                                                            \
   {                                                                                                                \
-    float s_pos, s_neg;                                                                                            \
-    if constexpr (ASYM) {                                                                                          \
-      const uint32_t sb = (S[(GI) >> 1] >> (16 * ((GI) & 1))) & 0xFFFFu;                                           \
-      s_pos = scale_value<SCALE_KIND>(sb & 255u);                                                                  \
-      s_neg = scale_value<SCALE_KIND>(sb >> 8);                                                                    \
-    } else {                                                                                                       \
-      const uint32_t sb = (S[(GI) >> 2] >> (8 * ((GI) & 3))) & 255u;                                               \
-      s_pos = s_neg = scale_value<SCALE_KIND>(sb);                                                                 \
-    }                                                                                                              \
-    /* codes 16 j + 8 h .. + 7 of the group are word 2 j + h of its four */                                        \
-    const uint32_t word0 = h ? W[GI][1] : W[GI][0], word1 = h ? W[GI][3] : W[GI][2];                               \
-    const bf16x8 b0 = __builtin_bit_cast(bf16x8, u32x4{dequant2<ASYM, 0>(word0, s_pos, s_neg),                     \
-                                                       dequant2<ASYM, 1>(word0, s_pos, s_neg),                     \
-                                                       dequant2<ASYM, 2>(word0, s_pos, s_neg),                     \
-                                                       dequant2<ASYM, 3>(word0, s_pos, s_neg)});                   \
-    const bf16x8 b1 = __builtin_bit_cast(bf16x8, u32x4{dequant2<ASYM, 0>(word1, s_pos, s_neg),                     \
-                                                       dequant2<ASYM, 1>(word1, s_pos, s_neg),                     \
-                                                       dequant2<ASYM, 2>(word1, s_pos, s_neg),                     \
-                                                       dequant2<ASYM, 3>(word1, s_pos, s_neg)});                   \
-    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                                            \
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>((SRC) + (mt * 8 + ((GI) & 3) * 2) * kFragBytes + lane_off); \
-      const bf16x8 a1 =                                                                                            \
-          *reinterpret_cast<const bf16x8*>((SRC) + (mt * 8 + ((GI) & 3) * 2 + 1) * kFragBytes + lane_off);         \
-      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[mt], 0, 0, 0);                                 \
-      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[mt], 0, 0, 0);                                 \
-    }                                                                                                              \
+    uint32_t s_pos, s_neg;                                                                                         \
+    skinny_scales<SCALE_KIND, ASYM, GI>(S, s_pos, s_neg);                                                          \
+    constexpr int kf0 = ((GI) * 4) % kStageSteps; /* the group's first k-step within its stage */                  \
+    AMX_SKINNY_KSTEP(SRC, W[GI][0], kf0)                                                                           \
+    AMX_SKINNY_KSTEP(SRC, W[GI][1], kf0 + 1)                                                                       \
+    AMX_SKINNY_KSTEP(SRC, W[GI][2], kf0 + 2)                                                                       \
+    AMX_SKINNY_KSTEP(SRC, W[GI][3], kf0 + 3)                                                                       \
   }
-#define AMX_SKINNY_HALF0(SRC, W, S)                                                                                \
-  AMX_SKINNY_GROUP(SRC, W, S, 0) AMX_SKINNY_GROUP(SRC, W, S, 1) AMX_SKINNY_GROUP(SRC, W, S, 2)                     \
-  AMX_SKINNY_GROUP(SRC, W, S, 3)
-#define AMX_SKINNY_HALF1(SRC, W, S)                                                                                \
-  AMX_SKINNY_GROUP(SRC, W, S, 4) AMX_SKINNY_GROUP(SRC, W, S, 5) AMX_SKINNY_GROUP(SRC, W, S, 6)                     \
-  AMX_SKINNY_GROUP(SRC, W, S, 7)
+#endif
+#define AMX_SKINNY_HALF0(SRC, W, S) AMX_SKINNY_GROUP(SRC, W, S, 0) AMX_SKINNY_GROUP(SRC, W, S, 1)
+#define AMX_SKINNY_HALF1(SRC, W, S) AMX_SKINNY_GROUP(SRC, W, S, 2) AMX_SKINNY_GROUP(SRC, W, S, 3)
 
-  u32x4 w0[8], w1[8];
-  uint32_t s0[4], s1[4];
+  u32x4 w0[4], w1[4];
+  uint32_t s0[2], s1[2];
   AMX_SKINNY_LOAD_A(0, ldsA0);
   AMX_SKINNY_LOAD_B(0, w0, s0);
+  // The first block's registers are named as used here so that their loads complete in front of the loop: the
+  // compiler may otherwise sink them to their first use inside it, where waiting for them means waiting for nearly
+  // every load issued since (the next block's among them), in every iteration.
+  asm volatile("" ::"v"(w0[0]), "v"(w0[1]), "v"(w0[2]), "v"(w0[3]), "v"(s0[0]), "v"(s0[1]));
   AMX_WAIT_VMCNT(0);
   AMX_BARRIER();
-  // Block i: its first half is multiplied from stage 0, its second from stage 1, with the codes in register set
-  // i % 2. Every step fetches what the next step needs (the other A stage; the next block's codes during a first half)
-  // and ends with a wait and a barrier, after which the stage it read may be refilled. All conditions are uniform.
-  for (int i = 0; i < nb; i += 2) {
-    AMX_SKINNY_LOAD_A(2 * i + 1, ldsA1);
-    if (i + 1 < nb) AMX_SKINNY_LOAD_B(i + 1, w1, s1);
-    AMX_SKINNY_HALF0(ldsA0, w0, s0);
-    AMX_WAIT_VMCNT(0);
-    AMX_BARRIER();
-    if (i + 1 < nb) AMX_SKINNY_LOAD_A(2 * i + 2, ldsA0);
-    AMX_SKINNY_HALF1(ldsA1, w0, s0);
-    AMX_WAIT_VMCNT(0);
-    AMX_BARRIER();
-    if (i + 1 < nb) {
-      AMX_SKINNY_LOAD_A(2 * i + 3, ldsA1);
-      if (i + 2 < nb) AMX_SKINNY_LOAD_B(i + 2, w0, s0);
-      AMX_SKINNY_HALF0(ldsA0, w1, s1);
+  if constexpr (kStageSteps == 16) {
+    // Block i is multiplied from stage i % 2 with the codes in register set i % 2, while the loads of block i + 1
+    // fill the other stage and the other register set; each step ends with a wait and a barrier, after which the
+    // stage it read may be refilled. All conditions are uniform.
+    for (int i = 0; i < nb; i += 2) {
+      if (i + 1 < nb) {
+        AMX_SKINNY_LOAD_A(i + 1, ldsA1);
+        AMX_SKINNY_LOAD_B(i + 1, w1, s1);
+      }
+      AMX_SKINNY_HALF0(ldsA0, w0, s0);
+      AMX_SKINNY_HALF1(ldsA0, w0, s0);
       AMX_WAIT_VMCNT(0);
       AMX_BARRIER();
-      if (i + 2 < nb) AMX_SKINNY_LOAD_A(2 * i + 4, ldsA0);
-      AMX_SKINNY_HALF1(ldsA1, w1, s1);
+      if (i + 1 < nb) {
+        if (i + 2 < nb) {
+          AMX_SKINNY_LOAD_A(i + 2, ldsA0);
+          AMX_SKINNY_LOAD_B(i + 2, w0, s0);
+        }
+        AMX_SKINNY_HALF0(ldsA1, w1, s1);
+        AMX_SKINNY_HALF1(ldsA1, w1, s1);
+        AMX_WAIT_VMCNT(0);
+        AMX_BARRIER();
+      }
+    }
+  } else {
+    // Block i: its first half is multiplied from stage 0, its second from stage 1, with the codes in register set
+    // i % 2. Every step fetches what the next step needs (the other A stage; the next block's codes during a first
+    // half) and ends with a wait and a barrier, after which the stage it read may be refilled. All conditions are
+    // uniform.
+    for (int i = 0; i < nb; i += 2) {
+      AMX_SKINNY_LOAD_A(2 * i + 1, ldsA1);
+      if (i + 1 < nb) AMX_SKINNY_LOAD_B(i + 1, w1, s1);
+      AMX_SKINNY_HALF0(ldsA0, w0, s0);
       AMX_WAIT_VMCNT(0);
       AMX_BARRIER();
+      if (i + 1 < nb) AMX_SKINNY_LOAD_A(2 * i + 2, ldsA0);
+      AMX_SKINNY_HALF1(ldsA1, w0, s0);
+      AMX_WAIT_VMCNT(0);
+      AMX_BARRIER();
+      if (i + 1 < nb) {
+        AMX_SKINNY_LOAD_A(2 * i + 3, ldsA1);
+        if (i + 2 < nb) AMX_SKINNY_LOAD_B(i + 2, w0, s0);
+        AMX_SKINNY_HALF0(ldsA0, w1, s1);
+        AMX_WAIT_VMCNT(0);
+        AMX_BARRIER();
+        if (i + 2 < nb) AMX_SKINNY_LOAD_A(2 * i + 4, ldsA0);
+        AMX_SKINNY_HALF1(ldsA1, w1, s1);
+        AMX_WAIT_VMCNT(0);
+        AMX_BARRIER();
+      }
     }
   }
 #undef AMX_SKINNY_HALF1
 #undef AMX_SKINNY_HALF0
 #undef AMX_SKINNY_GROUP
+#undef AMX_SKINNY_KSTEP
 #undef AMX_SKINNY_LOAD_B
 #undef AMX_SKINNY_LOAD_A
 
@@ -228,7 +352,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const uint16_t* __rest
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int64_t r = mt * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-      if (r < row_limit) dst[r * ld_out] = acc[mt][v];
+      if (r < row_limit) dst[r * ld_out] = kF16 ? acc[mt][v] * 64.0f : acc[mt][v];  // undo the two biases
     }
 }
 
@@ -250,13 +374,14 @@ static hipError_t launch_skinny(const uint16_t* Ap, const uint8_t* Bc, const uin
                                 int64_t M, int64_t N, int64_t K, int64_t ldc, int64_t batch, int slices,
                                 int blocks_per_slice, hipStream_t s) {
   const int64_t Mp = MT * 32;
-  const dim3 grid((unsigned)((N + 127) / 128), (unsigned)slices, (unsigned)batch);
+  constexpr int kWaves = skinny_waves(MT), kCols = 32 * kWaves;
+  const dim3 grid((unsigned)((N + kCols - 1) / kCols), (unsigned)slices, (unsigned)batch);
   if (slices == 1) {
-    hipLaunchKernelGGL((gemm_skinny_kernel<SK, ASYM, MT>), grid, dim3(256), 0, s, Ap, Bc, Bs, C, M, N, K, ldc, M * ldc,
+    hipLaunchKernelGGL((gemm_skinny_kernel<SK, ASYM, MT>), grid, dim3(64 * kWaves), 0, s, Ap, Bc, Bs, C, M, N, K, ldc, M * ldc,
                        (int64_t)0, blocks_per_slice);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL((gemm_skinny_kernel<SK, ASYM, MT>), grid, dim3(256), 0, s, Ap, Bc, Bs, partial, M, N, K, N,
+  hipLaunchKernelGGL((gemm_skinny_kernel<SK, ASYM, MT>), grid, dim3(64 * kWaves), 0, s, Ap, Bc, Bs, partial, M, N, K, N,
                      (int64_t)slices * Mp * N, Mp * N, blocks_per_slice);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -275,8 +400,9 @@ hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t
   const size_t panel_bytes = ((size_t)(batch * Mp * K * 2) + 255) / 256 * 256;
   float* partial = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(workspace) + panel_bytes);
   int blocks_per_slice;
-  const int slices = skinny_outer_slices((N + 127) / 128 * batch, K / kSkinnyBlockK, blocks_per_slice);
-  hipError_t e = launch_expand_bf16(scale_kind, asym, 32, A_codes, A_scales, M, K, Mp, K, batch, false, Ap, s);
+  const int64_t cols = 32 * skinny_waves((int)(Mp / 32));
+  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, blocks_per_slice);
+  hipError_t e = launch_expand_half_line(scale_kind, asym, A_codes, A_scales, M, K, Mp, batch, Ap, s);
   if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
   // E8M0 floor and round share the byte encoding

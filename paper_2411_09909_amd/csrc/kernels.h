@@ -69,6 +69,11 @@ hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t
                                   const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
                                   int causal, float* out, void* workspace, hipStream_t s, const KernelTimer& timer);
 
+// The A panel of the few-rows kernel: 32-long groups, FP16 biased by 2^-3 for FP8-E5M2 scales and BF16 otherwise, the
+// k order within every block of 256 rearranged so that a lane half's 16 k-steps come from one half of the block
+// (gemm_bf16.hip, HALF_LINE). K % 256 == 0.
+hipError_t launch_expand_half_line(int scale_kind, bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R,
+                                   int64_t K, int64_t Rp, int64_t batch, uint16_t* panel, hipStream_t s);
 // FP16 fragment-major panel (values biased by 2^-3) of an operand with FP8-E5M2 scales; layout as the BF16 panels
 hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K,
                                   int64_t Rp, int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s);
