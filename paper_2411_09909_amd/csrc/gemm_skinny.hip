@@ -138,14 +138,26 @@ constexpr int kSkinnyBlockK = 256;  // K block: 128 bytes of codes per row
 // leaves it.
 constexpr int skinny_waves(int row_tiles) { return row_tiles <= 4 ? 8 : 4; }
 
-// Outer K slices for a problem with `groups` workgroups per slice and nblk K blocks: about 512 workgroups (two per CU,
-// 4 waves each) if the K blocks allow it. Returns the number of slices and sets the blocks per slice; every slice has
-// at least one block ((slices - 1) * blocks_per_slice < nblk).
-static int skinny_outer_slices(int64_t groups, int64_t nblk, int& blocks_per_slice) {
-  static const int64_t target = getenv("AMXFP4_SKINNY_WGS") ? atoi(getenv("AMXFP4_SKINNY_WGS")) : 512;
-  int64_t want = (target + groups - 1) / groups;
-  want = want < 1 ? 1 : (want > nblk ? nblk : want);
-  blocks_per_slice = (int)((nblk + want - 1) / want);
+// Outer K slices for a problem with `groups` workgroups per slice, nblk K blocks and Mp padded rows. A workgroup's
+// time is its number of K blocks; the chip runs 256 workgroups at a time (a second resident workgroup per CU mostly
+// waits for the same memory system), so a launch takes ceil(workgroups / 256) * blocks_per_slice block times, plus the
+// partial tiles every further slice writes and the reduction reads (16 Mp / K of the bytes of B per slice). The
+// cheapest count of at most 16 wins, the smaller one on ties. Returns the number of slices and sets the blocks per
+// slice; every slice has at least one block ((slices - 1) * blocks_per_slice < nblk).
+// AMXFP4_SKINNY_SLICES (tuning aid): forces the wanted count.
+static int skinny_outer_slices(int64_t groups, int64_t nblk, int64_t Mp, int& blocks_per_slice) {
+  static const int forced = getenv("AMXFP4_SKINNY_SLICES") ? atoi(getenv("AMXFP4_SKINNY_SLICES")) : 0;
+  const double b_time = (double)(groups * nblk) / 256.0, partial = 16.0 * (double)Mp / (double)(nblk * kSkinnyBlockK);
+  int64_t best = 1;
+  double best_cost = 1e300;
+  for (int64_t want = 1; want <= 16 && want <= nblk; ++want) {
+    const int64_t bps = (nblk + want - 1) / want, slices = (nblk + bps - 1) / bps;
+    const double rounds = (double)((groups * slices + 255) / 256);
+    const double cost = rounds * (double)bps + (slices > 1 ? b_time * partial * (double)slices : 0.0);
+    if (cost < best_cost - 1e-9) best_cost = cost, best = want;
+  }
+  if (forced > 0) best = forced < nblk ? forced : nblk;
+  blocks_per_slice = (int)((nblk + best - 1) / best);
   return (int)((nblk + blocks_per_slice - 1) / blocks_per_slice);
 }
 
@@ -163,7 +175,7 @@ bool skinny_path_supported(int64_t M, int64_t N, int64_t K) {
 size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch) {
   const int64_t Mp = 32 * skinny_row_tiles(M), cols = 32 * skinny_waves(skinny_row_tiles(M));
   int bps;
-  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, bps);
+  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, bps);
   size_t bytes = (size_t)(batch * Mp * K * 2);                         // A panel
   bytes = (bytes + 255) / 256 * 256;
   if (slices > 1) bytes += (size_t)(batch * slices * Mp * N * 4);      // partial tiles
@@ -401,7 +413,7 @@ hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t
   float* partial = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(workspace) + panel_bytes);
   int blocks_per_slice;
   const int64_t cols = 32 * skinny_waves((int)(Mp / 32));
-  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, blocks_per_slice);
+  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, blocks_per_slice);
   hipError_t e = launch_expand_half_line(scale_kind, asym, A_codes, A_scales, M, K, Mp, batch, Ap, s);
   if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
