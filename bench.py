@@ -252,6 +252,9 @@ def main():
                   "gemm_e5m2_hybrid_kernel", "fused": "gemm_e5m2_kernel"}[args.e5m2_kernel if args.group_size == 32 else "panel"]
     if M <= 256 and K % 256 == 0 and args.group_size == 32 and args.format not in DOUBLE_SCALED:
         kernel_name = "gemm_skinny_kernel"  # few rows: B dequantized in registers straight from its codes
+    dtype = r["mfma"]
+    if kernel_name == "gemm_skinny_kernel":
+        dtype = "f16" if FORMATS[args.format][0] == 2 else "bf16"  # the few-rows kernel's MFMA operand type
     if kernel_name == "gemm_skinny_kernel":
         # a few rows against a weight matrix: bound by reading B's codes and scales (plus A's panel and C) from HBM
         kbytes = N * K // 2 + N * (K // 32) * (2 if r["asym"] else 1) + ((M + 31) // 32 * 32) * K * 2 + M * N * 4
@@ -268,7 +271,7 @@ def main():
     out = {
         "metric": "AMXFP4 cast+GEMM TFLOPS at %dx%dx%d" % (M, K, N), "value": round(value, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": r["mfma"], "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "format": args.format, "group_size": 16 if args.format in DOUBLE_SCALED else args.group_size,
                    "tensor_scale": args.format in DOUBLE_SCALED,
                    "e5m2_kernel": ("packed_codes" if kernel_name == "gemm_skinny_kernel" else args.e5m2_kernel)
