@@ -256,10 +256,6 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(cons
   }
   // The four k-steps of the lane's group GI (a literal: register arrays must not be indexed with a run-time value) of
   // one block: k-step 4 GI + t multiplies word t of the group; A fragments from stage SRC, B from the registers W / S
-#ifdef AMX_SKINNY_PROBE_NOCOMPUTE
-#define AMX_SKINNY_GROUP(SRC, W, S, GI)                                                                            \
-  { acc[0][GI] += u2f((W[GI][0] ^ W[GI][1] ^ W[GI][2] ^ W[GI][3] ^ S[(GI) >> 1]) & 0x3FFFFFFFu); }
-#else
 #define AMX_SKINNY_KSTEP(SRC, WORD, KF)                                                                            \
   {                                                                                                                \
     const u32x4 q = dequant_word<SCALE_KIND, ASYM>(WORD, s_pos, s_neg);                                            \
@@ -282,7 +278,6 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(cons
     AMX_SKINNY_KSTEP(SRC, W[GI][2], kf0 + 2)                                                                       \
     AMX_SKINNY_KSTEP(SRC, W[GI][3], kf0 + 3)                                                                       \
   }
-#endif
 #define AMX_SKINNY_HALF0(SRC, W, S) AMX_SKINNY_GROUP(SRC, W, S, 0) AMX_SKINNY_GROUP(SRC, W, S, 1)
 #define AMX_SKINNY_HALF1(SRC, W, S) AMX_SKINNY_GROUP(SRC, W, S, 2) AMX_SKINNY_GROUP(SRC, W, S, 3)
 
