@@ -103,6 +103,16 @@ int amxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, i
                     int64_t k_stride, uint8_t* codes, uint8_t* scales, void* stream);
 
 /*
+ * The same cast over `batch` operands of one shape in one launch (the heads of an attention layer, Sec. 5.1: Q, K
+ * along the head dimension, V down the keys): operand b starts batch_stride elements after operand b - 1; codes and
+ * scales are written packed, [batch][rows][K/2] and [batch][rows][K/group_size]([2]). 1 <= batch <= 65535;
+ * batch_stride >= 0 and, for the contiguous case, a multiple of 8. Everything else as amxfp4_quantize.
+ */
+int amxfp4_quantize_batched(const amx_format_t* fmt, const void* x_bf16, int64_t batch, int64_t batch_stride,
+                            int64_t rows, int64_t K, int64_t row_stride, int64_t k_stride, uint8_t* codes,
+                            uint8_t* scales, void* stream);
+
+/*
  * Dequantization x_hat = (-1)^s * elem * S_class (Eq. 1), exact in both output types.
  *   out         device out, row-major [rows][K]; out_dtype 0 = float32, 1 = BF16 bit patterns.
  */

@@ -61,8 +61,7 @@ def main():
     def cast_qkv():
         binding.quantize(fmt, q.view(H * S, D), codes=qc, scales=qs)
         binding.quantize(fmt, k.view(G * S, D), codes=kc, scales=ks)
-        for g in range(G):
-            binding.quantize(fmt, v[g], k_axis=0, codes=vc[g], scales=vs[g])
+        binding.quantize_batched(fmt, v, k_axis=1, codes=vc, scales=vs)  # every head's V down its keys, one launch
 
     out_f = torch.empty((H, S, D), dtype=torch.float32, device=dev)
     ws_f = torch.empty(binding.attention_workspace_bytes(fmt, H, G, S, S, D), dtype=torch.uint8, device=dev)

@@ -48,6 +48,8 @@ def load():
         d.argtypes = [fp, vp, vp, i64, i64, vp, ctypes.c_int32, vp]
         g.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, i64, i64, vp, ctypes.c_size_t, vp]
         q.restype = d.restype = g.restype = ctypes.c_int
+    L.amxfp4_quantize_batched.argtypes = [fp, vp, i64, i64, i64, i64, i64, i64, vp, vp, vp]
+    L.amxfp4_quantize_batched.restype = ctypes.c_int
     L.amxfp4_profile_next_gemm.argtypes = [vp, vp]
     L.amxfp4_profile_next_gemm.restype = ctypes.c_int
     L.amxfp4_select_e5m2_kernel.argtypes = [ctypes.c_int32]
@@ -209,6 +211,29 @@ def quantize(fmt, x, k_axis=-1, codes=None, scales=None, baseline=False, tensor_
         return codes, scales
     _check(_fn(fmt, "quantize", baseline)(ctypes.byref(fmt), x.data_ptr(), rows, K, row_stride, k_stride,
                                           codes.data_ptr(), scales.data_ptr(), _stream()))
+    return codes, scales
+
+
+def quantize_batched(fmt, x, k_axis=-1, codes=None, scales=None):
+    """x: 3-D BF16 CUDA tensor [batch, ., .]; every x[b] is cast as quantize(fmt, x[b], k_axis) would, in one launch.
+    Returns (codes u8 [batch, rows, K/2], scales u8 [batch, rows, K/group_size(, 2)])."""
+    _need_cuda(x)
+    assert x.dim() == 3 and x.element_size() == 2
+    batch = x.shape[0]
+    if k_axis in (-1, 2):
+        rows, K = x.shape[1], x.shape[2]
+        row_stride, k_stride = x.stride(1), x.stride(2)
+    else:
+        K, rows = x.shape[1], x.shape[2]
+        k_stride, row_stride = x.stride(1), x.stride(2)
+    asym = bool(fmt.asymmetric)
+    if codes is None:
+        codes = torch.empty((batch, rows, K // 2), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        shape = (batch, rows, K // fmt.group_size, 2) if asym else (batch, rows, K // fmt.group_size)
+        scales = torch.empty(shape, dtype=torch.uint8, device=x.device)
+    _check(load().amxfp4_quantize_batched(ctypes.byref(fmt), x.data_ptr(), batch, x.stride(0), rows, K, row_stride,
+                                          k_stride, codes.data_ptr(), scales.data_ptr(), _stream()))
     return codes, scales
 
 

@@ -73,19 +73,23 @@ int report_hip_error(hipError_t e, const char* what) { return hip_fail(e, what);
 
 namespace {
 
-int quantize_impl(amx_format_t f, const void* x, int64_t rows, int64_t K, int64_t row_stride, int64_t k_stride,
-                  const float* tensor_pair, uint8_t* codes, uint8_t* scales, void* stream) {
+int quantize_impl(amx_format_t f, const void* x, int64_t batch, int64_t batch_stride, int64_t rows, int64_t K,
+                  int64_t row_stride, int64_t k_stride, const float* tensor_pair, uint8_t* codes, uint8_t* scales,
+                  void* stream) {
   if (int rc = check_format(&f)) return rc;
   if (int rc = check_shape(f, rows, K)) return rc;
+  if (batch < 1 || batch > kMaxBatch)
+    return fail(AMX_ERR_INVALID_ARG, "batch = %lld outside 1 .. %lld", (long long)batch, (long long)kMaxBatch);
+  if (batch > 1 && batch_stride < 0) return fail(AMX_ERR_INVALID_ARG, "negative batch_stride");
   if (!x || !codes || !scales) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
   if (!aligned(codes, 16) || !aligned(scales, 4)) return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales 4-byte alignment");
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   const uint16_t* xb = reinterpret_cast<const uint16_t*>(x);
   if (k_stride == 1) {
-    if (row_stride < K || row_stride % 8 != 0 || !aligned(x, 16))
-      return fail(AMX_ERR_INVALID_ARG, "contiguous cast needs row_stride >= K, row_stride %% 8 == 0 and a 16-byte aligned base");
-    hipError_t e = amx::launch_quantize_contig(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, row_stride, tensor_pair, codes,
-                                               scales, s);
+    if (row_stride < K || row_stride % 8 != 0 || !aligned(x, 16) || (batch > 1 && batch_stride % 8 != 0))
+      return fail(AMX_ERR_INVALID_ARG, "contiguous cast needs row_stride >= K, row_stride %% 8 == 0, batch_stride %% 8 == 0 and a 16-byte aligned base");
+    hipError_t e = amx::launch_quantize_contig(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, row_stride, batch,
+                                               batch_stride, tensor_pair, codes, scales, s);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "quantize launch");
   }
   if (row_stride == 1 && k_stride >= rows) {
@@ -93,8 +97,8 @@ int quantize_impl(amx_format_t f, const void* x, int64_t rows, int64_t K, int64_
     if (rows > kMaxStridedRows)
       return fail(AMX_ERR_INVALID_ARG, "rows = %lld exceeds the maximum %lld of the strided cast", (long long)rows,
                   (long long)kMaxStridedRows);
-    hipError_t e = amx::launch_quantize_strided(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, k_stride, tensor_pair, codes,
-                                                scales, s);
+    hipError_t e = amx::launch_quantize_strided(f.scale, f.asymmetric != 0, f.group_size, xb, rows, K, k_stride, batch,
+                                                batch_stride, tensor_pair, codes, scales, s);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "strided quantize launch");
   }
   return fail(AMX_ERR_INVALID_ARG, "unsupported strides: need k_stride == 1, or row_stride == 1 with k_stride >= rows");
@@ -273,7 +277,14 @@ size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N
 int amxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
                     int64_t k_stride, uint8_t* codes, uint8_t* scales, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  return quantize_impl(*fmt, x_bf16, rows, K, row_stride, k_stride, nullptr, codes, scales, stream);
+  return quantize_impl(*fmt, x_bf16, 1, 0, rows, K, row_stride, k_stride, nullptr, codes, scales, stream);
+}
+
+int amxfp4_quantize_batched(const amx_format_t* fmt, const void* x_bf16, int64_t batch, int64_t batch_stride,
+                            int64_t rows, int64_t K, int64_t row_stride, int64_t k_stride, uint8_t* codes,
+                            uint8_t* scales, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  return quantize_impl(*fmt, x_bf16, batch, batch_stride, rows, K, row_stride, k_stride, nullptr, codes, scales, stream);
 }
 
 int amxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
@@ -293,7 +304,7 @@ int amxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const 
 int mxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
                    int64_t k_stride, uint8_t* codes, uint8_t* scales, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  return quantize_impl(symmetric(fmt), x_bf16, rows, K, row_stride, k_stride, nullptr, codes, scales, stream);
+  return quantize_impl(symmetric(fmt), x_bf16, 1, 0, rows, K, row_stride, k_stride, nullptr, codes, scales, stream);
 }
 
 int mxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
@@ -326,7 +337,7 @@ int amxfp4_quantize_scaled(const amx_format_t* fmt, const void* x_bf16, int64_t 
                            int64_t k_stride, const float* scale_pair, uint8_t* codes, uint8_t* scales, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
   if (!scale_pair || !aligned(scale_pair, 8)) return fail(AMX_ERR_INVALID_ARG, "scale_pair is NULL or misaligned");
-  return quantize_impl(*fmt, x_bf16, rows, K, row_stride, k_stride, scale_pair, codes, scales, stream);
+  return quantize_impl(*fmt, x_bf16, 1, 0, rows, K, row_stride, k_stride, scale_pair, codes, scales, stream);
 }
 
 int amxfp4_dequantize_scaled(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows,

@@ -139,10 +139,15 @@ __device__ __forceinline__ void class_extrema(const float (&y)[N], uint32_t& ama
 // row arithmetic is uniform (scalar unit).
 template <int SCALE_KIND, bool ASYM, bool TENSOR_SCALED, bool ONE_ROW>
 __global__ __launch_bounds__(256) void quantize_contig_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t K,
-                                                              int64_t row_stride, const float* __restrict__ tensor_pair,
+                                                              int64_t row_stride, int64_t batch_stride,
+                                                              const float* __restrict__ tensor_pair,
                                                               uint8_t* __restrict__ codes,
                                                               uint8_t* __restrict__ scales, int bx_log2,
                                                               int lpg_log2) {
+  // blockIdx.z: batch entry (operands batch_stride elements apart; outputs packed one after the other)
+  x += (int64_t)blockIdx.z * batch_stride;
+  codes += (int64_t)blockIdx.z * rows * (K >> 1);
+  scales += (int64_t)blockIdx.z * rows * (K >> (lpg_log2 + 4)) * (ASYM ? 2 : 1);
   const int tx = ONE_ROW ? (int)threadIdx.x : (int)threadIdx.x & ((1 << bx_log2) - 1);
   const int ty = ONE_ROW ? 0 : (int)threadIdx.x >> bx_log2;
   const int64_t r = ONE_ROW ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * (256 >> bx_log2) + ty;
@@ -213,13 +218,17 @@ __global__ __launch_bounds__(256) void quantize_contig_kernel(const uint16_t* __
 
 // Groups run down a column: element (r, k) = x[r + k * k_stride]. One lane owns one (row, group) of GS elements;
 // consecutive lanes own consecutive rows, so each of the GS loads of a wave reads 128 contiguous bytes.
-// grid: (K / GS groups, ceil(rows / 256)).
+// grid: (K / GS groups, ceil(rows / 256), batch).
 template <int SCALE_KIND, bool ASYM, bool TENSOR_SCALED, int GS>
 __global__ __launch_bounds__(256) void quantize_strided_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t K,
-                                                               int64_t k_stride, const float* __restrict__ tensor_pair,
+                                                               int64_t k_stride, int64_t batch_stride,
+                                                               const float* __restrict__ tensor_pair,
                                                                uint8_t* __restrict__ codes,
                                                                uint8_t* __restrict__ scales) {
   const int64_t G = K / GS;
+  x += (int64_t)blockIdx.z * batch_stride;
+  codes += (int64_t)blockIdx.z * rows * (K >> 1);
+  scales += (int64_t)blockIdx.z * rows * G * (ASYM ? 2 : 1);
   const int64_t r = (int64_t)blockIdx.y * 256 + threadIdx.x;
   const int64_t g = blockIdx.x;
   if (r >= rows) return;
@@ -359,7 +368,8 @@ static int group_log2(int64_t gs) { return gs == 16 ? 4 : gs == 32 ? 5 : gs == 6
 
 template <int SK, bool ASYM>
 static hipError_t launch_qc(const uint16_t* x, int64_t rows, int64_t K, int gs_log2, int64_t row_stride,
-                            const float* tensor_pair, uint8_t* codes, uint8_t* scales, hipStream_t s) {
+                            int64_t batch, int64_t batch_stride, const float* tensor_pair, uint8_t* codes,
+                            uint8_t* scales, hipStream_t s) {
   // block shape: as many chunks of a row as fit (power of two, one group .. 256), the rest of the 256 lanes go to
   // more rows
   const int64_t chunks = K / 16;
@@ -367,10 +377,10 @@ static hipError_t launch_qc(const uint16_t* x, int64_t rows, int64_t K, int gs_l
   int bx_log2 = lpg_log2;
   while (bx_log2 < 8 && (int64_t(1) << (bx_log2 + 1)) <= chunks) ++bx_log2;
   const int64_t bx = int64_t(1) << bx_log2, by = 256 >> bx_log2;
-  const dim3 grid((unsigned)((rows + by - 1) / by), (unsigned)((chunks + bx - 1) / bx));
+  const dim3 grid((unsigned)((rows + by - 1) / by), (unsigned)((chunks + bx - 1) / bx), (unsigned)batch);
   auto launch = [&]<bool SCALED, bool ONE_ROW>() {
     hipLaunchKernelGGL((quantize_contig_kernel<SK, ASYM, SCALED, ONE_ROW>), grid, dim3(256), 0, s, x, rows, K,
-                       row_stride, tensor_pair, codes, scales, bx_log2, lpg_log2);
+                       row_stride, batch_stride, tensor_pair, codes, scales, bx_log2, lpg_log2);
   };
   if (tensor_pair)
     bx_log2 == 8 ? launch.template operator()<true, true>() : launch.template operator()<true, false>();
@@ -396,39 +406,40 @@ static hipError_t for_format(int scale_kind, bool asym, F&& f) {
 }
 
 hipError_t launch_quantize_contig(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, int64_t rows,
-                                  int64_t K, int64_t row_stride, const float* tensor_pair, uint8_t* codes,
-                                  uint8_t* scales, hipStream_t s) {
+                                  int64_t K, int64_t row_stride, int64_t batch, int64_t batch_stride,
+                                  const float* tensor_pair, uint8_t* codes, uint8_t* scales, hipStream_t s) {
   const int gl = group_log2(group_size);
   if (gl < 0 || K % group_size != 0) return hipErrorInvalidValue;
   return for_format(scale_kind, asym, [&]<int SK, bool ASYM>() {
-    return launch_qc<SK, ASYM>(x, rows, K, gl, row_stride, tensor_pair, codes, scales, s);
+    return launch_qc<SK, ASYM>(x, rows, K, gl, row_stride, batch, batch_stride, tensor_pair, codes, scales, s);
   });
 }
 
 template <int SK, bool ASYM, int GS>
-static hipError_t launch_qs(const uint16_t* x, int64_t rows, int64_t K, int64_t k_stride, const float* tensor_pair,
-                            uint8_t* codes, uint8_t* scales, hipStream_t s) {
-  const dim3 grid((unsigned)(K / GS), (unsigned)((rows + 255) / 256));
+static hipError_t launch_qs(const uint16_t* x, int64_t rows, int64_t K, int64_t k_stride, int64_t batch,
+                            int64_t batch_stride, const float* tensor_pair, uint8_t* codes, uint8_t* scales,
+                            hipStream_t s) {
+  const dim3 grid((unsigned)(K / GS), (unsigned)((rows + 255) / 256), (unsigned)batch);
   if (tensor_pair)
     hipLaunchKernelGGL((quantize_strided_kernel<SK, ASYM, true, GS>), grid, dim3(256), 0, s, x, rows, K, k_stride,
-                       tensor_pair, codes, scales);
+                       batch_stride, tensor_pair, codes, scales);
   else
     hipLaunchKernelGGL((quantize_strided_kernel<SK, ASYM, false, GS>), grid, dim3(256), 0, s, x, rows, K, k_stride,
-                       tensor_pair, codes, scales);
+                       batch_stride, tensor_pair, codes, scales);
   return hipGetLastError();
 }
 
 hipError_t launch_quantize_strided(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, int64_t rows,
-                                   int64_t K, int64_t k_stride, const float* tensor_pair, uint8_t* codes,
-                                   uint8_t* scales, hipStream_t s) {
+                                   int64_t K, int64_t k_stride, int64_t batch, int64_t batch_stride,
+                                   const float* tensor_pair, uint8_t* codes, uint8_t* scales, hipStream_t s) {
   const int gl = group_log2(group_size);
   if (gl < 0 || K % group_size != 0) return hipErrorInvalidValue;
   return for_format(scale_kind, asym, [&]<int SK, bool ASYM>() {
     switch (gl) {
-      case 4: return launch_qs<SK, ASYM, 16>(x, rows, K, k_stride, tensor_pair, codes, scales, s);
-      case 5: return launch_qs<SK, ASYM, 32>(x, rows, K, k_stride, tensor_pair, codes, scales, s);
-      case 6: return launch_qs<SK, ASYM, 64>(x, rows, K, k_stride, tensor_pair, codes, scales, s);
-      default: return launch_qs<SK, ASYM, 128>(x, rows, K, k_stride, tensor_pair, codes, scales, s);
+      case 4: return launch_qs<SK, ASYM, 16>(x, rows, K, k_stride, batch, batch_stride, tensor_pair, codes, scales, s);
+      case 5: return launch_qs<SK, ASYM, 32>(x, rows, K, k_stride, batch, batch_stride, tensor_pair, codes, scales, s);
+      case 6: return launch_qs<SK, ASYM, 64>(x, rows, K, k_stride, batch, batch_stride, tensor_pair, codes, scales, s);
+      default: return launch_qs<SK, ASYM, 128>(x, rows, K, k_stride, batch, batch_stride, tensor_pair, codes, scales, s);
     }
   });
 }

@@ -21,13 +21,13 @@ int report_error(int code, const char* msg);
 int report_hip_error(hipError_t e, const char* what);
 
 // cast.hip (group_size: 16, 32, 64 or 128, dividing K; tensor_pair: device {S_t, 1 / S_t} of a tensor-wise scale,
-// or null for none)
+// or null for none; batch operands batch_stride elements apart, their outputs packed one after the other)
 hipError_t launch_quantize_contig(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, int64_t rows,
-                                  int64_t K, int64_t row_stride, const float* tensor_pair, uint8_t* codes,
-                                  uint8_t* scales, hipStream_t s);
+                                  int64_t K, int64_t row_stride, int64_t batch, int64_t batch_stride,
+                                  const float* tensor_pair, uint8_t* codes, uint8_t* scales, hipStream_t s);
 hipError_t launch_quantize_strided(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, int64_t rows,
-                                   int64_t K, int64_t k_stride, const float* tensor_pair, uint8_t* codes,
-                                   uint8_t* scales, hipStream_t s);
+                                   int64_t K, int64_t k_stride, int64_t batch, int64_t batch_stride,
+                                   const float* tensor_pair, uint8_t* codes, uint8_t* scales, hipStream_t s);
 hipError_t launch_dequantize(int scale_kind, bool asym, int64_t group_size, const uint8_t* codes,
                              const uint8_t* scales, int64_t rows, int64_t K, const float* tensor_pair, void* out,
                              int out_dtype, hipStream_t s);

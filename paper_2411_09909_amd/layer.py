@@ -104,8 +104,9 @@ class DecoderLayer:
         G, S, D = v.shape
         vc = torch.empty((G, D, S // 2), dtype=torch.uint8, device=v.device)
         vs = torch.empty((G, D, S // 32) + tuple(nsc), dtype=torch.uint8, device=v.device)
-        for g in range(G):  # V of one head is [S, D]; its groups run down the columns (along the keys)
-            binding.quantize(self.fmt, v[g], k_axis=0, codes=vc[g], scales=vs[g], baseline=self.baseline)
+        # V of one head is [S, D]; its groups run down the columns (along the keys); all heads in one launch
+        fmt = binding.make_format(self.fmt.scale, False, self.fmt.group_size) if self.baseline else self.fmt
+        binding.quantize_batched(fmt, v, k_axis=1, codes=vc, scales=vs)
         return vc, vs
 
     def _after_attention(self, x, attn):

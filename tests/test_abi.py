@@ -120,6 +120,21 @@ def test_binding_refuses_host_tensors(lib):
         binding.quantize(f, torch.zeros(4, 64, dtype=torch.bfloat16))
 
 
+def test_batched_cast_rejects_bad_arguments(lib):
+    ok = binding.make_format(binding.FP8_E5M2, True, 32)
+    p = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
+    q = lib.amxfp4_quantize_batched
+    assert q(None, p, 2, 4096, 4, 64, 64, 1, p, p, None) == -1
+    assert q(ctypes.byref(ok), p, 0, 4096, 4, 64, 64, 1, p, p, None) == -1        # no operand
+    assert q(ctypes.byref(ok), p, 65536, 4096, 4, 64, 64, 1, p, p, None) == -1    # too many
+    assert b"batch" in lib.amxfp4_last_error()
+    assert q(ctypes.byref(ok), p, 2, -8, 4, 64, 64, 1, p, p, None) == -1          # negative batch stride
+    assert q(ctypes.byref(ok), p, 2, 4100, 4, 64, 64, 1, p, p, None) == -1        # contiguous: batch stride % 8
+    assert q(ctypes.byref(ok), p, 2, 4096, 4, 48, 48, 1, p, p, None) == -1        # K % 32
+    assert q(ctypes.byref(ok), p, 2, 4096, 4, 64, 2, 3, p, p, None) == -1         # unsupported strides
+    assert q(ctypes.byref(ok), None, 2, 4096, 4, 64, 64, 1, p, p, None) == -1
+
+
 def test_layer_operators_reject_bad_arguments(lib):
     p = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
     assert lib.amxfp4_rmsnorm(None, p, 4, 64, 1e-5, p, None) == -1

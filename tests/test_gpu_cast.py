@@ -111,6 +111,29 @@ def test_row_stride_and_strided_axis(scale, asym):
     assert np.array_equal(gc, rc) and np.array_equal(gs, rs)
 
 
+@pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.E8M0_FLOOR, 0)])
+def test_batched_cast_equals_the_oracle_per_operand(scale, asym):
+    """Several operands in one launch (the heads of an attention layer): along the rows (Q, K), down the columns (V),
+    and with a batch stride larger than an operand; every operand's codes and scales against the oracle."""
+    fmt = binding.make_format(scale, asym)
+    heads, seq, d = 5, 96, 128
+    x = np.stack([synth.activations(seq, d, seed=20 + h) for h in range(heads)])      # [heads, seq, d]
+    xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    c, s = binding.quantize_batched(fmt, xd)                                           # groups along d
+    for h in range(heads):
+        rc, rs = ref.quantize(x[h], 32, scale, asym)
+        assert np.array_equal(c[h].cpu().numpy(), rc) and np.array_equal(s[h].cpu().numpy(), rs)
+    c, s = binding.quantize_batched(fmt, xd, k_axis=1)                                 # groups down the 96 keys
+    assert tuple(c.shape) == (heads, d, seq // 2)
+    for h in range(heads):
+        rc, rs = ref.quantize(x[h], 32, scale, asym, k_axis=0)
+        assert np.array_equal(c[h].cpu().numpy(), rc) and np.array_equal(s[h].cpu().numpy(), rs)
+    c, s = binding.quantize_batched(fmt, xd[::2])                                      # batch stride = two operands
+    for i, h in enumerate(range(0, heads, 2)):
+        rc, rs = ref.quantize(x[h], 32, scale, asym)
+        assert np.array_equal(c[i].cpu().numpy(), rc) and np.array_equal(s[i].cpu().numpy(), rs)
+
+
 @pytest.mark.parametrize("scale,asym", FORMATS)
 def test_dequantize_exact(scale, asym):
     x = synth.activations(40, 288, seed=11)
