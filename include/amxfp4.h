@@ -129,9 +129,9 @@ int amxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8
  *   batch              number of independent back-to-back problems (attention heads), >= 1.
  *   Groups of 32 with power-of-two scales run on the block-scaled FP4 / FP8 matrix instructions; FP8 scales and the
  *   other group sizes are multiplied as exact BF16 operands (element * scale has at most 6 significant bits). With
- *   M <= 256, groups of 32 and K a multiple of 256, B is read as packed codes and dequantized in registers (the
- *   weights-bound case of a few tokens against a weight matrix); results do not depend on the kernel beyond the
- *   FP32 summation order.
+ *   M <= 256 (M <= 768 for batch == 1 and N * K >= 2^27), groups of 32 and K a multiple of 256, B is read as packed
+ *   codes and dequantized in registers to exact 16-bit floats (the weights-bound case of a few tokens against a
+ *   weight matrix); results do not depend on the kernel beyond the FP32 summation order.
  *   workspace          device scratch of at least amxfp4_gemm_workspace_bytes() bytes, 256-byte aligned;
  *                      contents are undefined afterwards. May be NULL when the required size is 0.
  */

@@ -124,9 +124,10 @@ bool uses_fp4_mfma(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
   return f.group_size == 32 && (f.scale == AMX_SCALE_E8M0_FLOOR || f.scale == AMX_SCALE_E8M0_ROUND) && amx::fp4_path_supported(M, N, K);
 }
 
-// A few rows on the A side (M <= 256) with groups of 32: the weights-bound kernel that reads B's codes directly.
-bool uses_skinny(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  return f.group_size == 32 && amx::skinny_path_supported(M, N, K);
+// A few rows on the A side (M <= 256; up to 768 for a single problem against a large B) with groups of 32: the
+// weights-bound kernel that reads B's codes directly.
+bool uses_skinny(const amx_format_t& f, int64_t M, int64_t N, int64_t K, int64_t batch) {
+  return f.group_size == 32 && amx::skinny_path_supported(M, N, K, batch);
 }
 
 // FP8-E5M2 scales have three kernels (amxfp4_select_e5m2_kernel in the header); shapes one does not take use the
@@ -190,7 +191,7 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
   }
   const amx::KernelTimer timer = g_timer;
   g_timer = amx::KernelTimer();
-  if (!scaled && uses_skinny(f, M, N, K)) {
+  if (!scaled && uses_skinny(f, M, N, K, batch)) {
     hipError_t e = amx::launch_gemm_skinny_path(f.scale, f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes,
                                                 B_scales, C, ldc, batch, workspace,
                                                 reinterpret_cast<hipStream_t>(stream), timer);
@@ -265,7 +266,7 @@ size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
 
 size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch) {
   if (!fmt || M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
-  if (uses_skinny(*fmt, M, N, K)) return amx::skinny_path_workspace_bytes(M, N, K, batch);
+  if (uses_skinny(*fmt, M, N, K, batch)) return amx::skinny_path_workspace_bytes(M, N, K, batch);
   if (uses_merged_pot(*fmt, M, N, K)) return amx::fp8m_path_workspace_bytes(M, N, K, batch);
   if (uses_fp4_mfma(*fmt, M, N, K)) return 0;
   const E5m2Path path = e5m2_path(*fmt, M, N, K);

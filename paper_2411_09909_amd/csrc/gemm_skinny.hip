@@ -167,19 +167,41 @@ static int skinny_row_tiles(int64_t M) {
   return t <= 4 ? t : (t <= 6 ? 6 : 8);
 }
 
-bool skinny_path_supported(int64_t M, int64_t N, int64_t K) {
+// More than kSkinnyMaxM rows (single problems only) run as row chunks of kSkinnyMaxM, one launch each over all of B:
+// up to kSkinnyMaxChunkedM rows against at least 2^27 weight elements that is still faster than expanding B to BF16
+// and streaming the panel (measured on 28672 x 8192 weights: 512 rows 0.30 against 0.48 ms, 768 rows 0.45 against
+// 0.49 ms; the second and third pass find the 132 MB of codes in the last-level cache).
+constexpr int kSkinnyMaxChunkedM = 768;
+
+bool skinny_path_supported(int64_t M, int64_t N, int64_t K, int64_t batch) {
   static const bool enabled = !(getenv("AMXFP4_SKINNY") && atoi(getenv("AMXFP4_SKINNY")) == 0);
-  return enabled && M <= kSkinnyMaxM && K % kSkinnyBlockK == 0 && N >= 1;
+  if (!enabled || K % kSkinnyBlockK != 0 || N < 1 || M < 1) return false;
+  return M <= kSkinnyMaxM || (batch == 1 && M <= kSkinnyMaxChunkedM && N * K >= (int64_t(1) << 27));
+}
+
+// padded rows of the A panel: full chunks of kSkinnyMaxM, the last one rounded up to its row tiles
+static int64_t skinny_panel_rows(int64_t M) {
+  const int64_t full = (M - 1) / kSkinnyMaxM;
+  return full * kSkinnyMaxM + 32 * skinny_row_tiles(M - full * kSkinnyMaxM);
+}
+
+// bytes of partial tiles one chunk of `rows` rows needs (0 with a single slice)
+static size_t skinny_partial_bytes(int64_t rows, int64_t N, int64_t K, int64_t batch) {
+  const int64_t Mp = 32 * skinny_row_tiles(rows), cols = 32 * skinny_waves(skinny_row_tiles(rows));
+  int bps;
+  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, bps);
+  return slices > 1 ? (size_t)(batch * slices * Mp * N * 4) : 0;
 }
 
 size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch) {
-  const int64_t Mp = 32 * skinny_row_tiles(M), cols = 32 * skinny_waves(skinny_row_tiles(M));
-  int bps;
-  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, bps);
-  size_t bytes = (size_t)(batch * Mp * K * 2);                         // A panel
+  size_t bytes = (size_t)(batch * skinny_panel_rows(M) * K * 2);  // A panel
   bytes = (bytes + 255) / 256 * 256;
-  if (slices > 1) bytes += (size_t)(batch * slices * Mp * N * 4);      // partial tiles
-  return bytes;
+  size_t partial = 0;  // the chunks run one after the other and share the partial tiles' space
+  for (int64_t r0 = 0; r0 < M; r0 += kSkinnyMaxM) {
+    const size_t p = skinny_partial_bytes(M - r0 < kSkinnyMaxM ? M - r0 : kSkinnyMaxM, N, K, batch);
+    partial = p > partial ? p : partial;
+  }
+  return bytes + partial;
 }
 
 // grid: (ceil(N / 128), outer slices, batch); block 256 = 4 waves.
@@ -401,36 +423,42 @@ hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t
                                    const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
                                    int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
                                    const KernelTimer& timer) {
-  if (!skinny_path_supported(M, N, K)) return hipErrorInvalidValue;
-  const int64_t Mp = 32 * skinny_row_tiles(M);
+  if (!skinny_path_supported(M, N, K, batch)) return hipErrorInvalidValue;
+  const int64_t Mp_all = skinny_panel_rows(M);
   uint16_t* Ap = reinterpret_cast<uint16_t*>(workspace);
-  const size_t panel_bytes = ((size_t)(batch * Mp * K * 2) + 255) / 256 * 256;
+  const size_t panel_bytes = ((size_t)(batch * Mp_all * K * 2) + 255) / 256 * 256;
   float* partial = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(workspace) + panel_bytes);
-  int blocks_per_slice;
-  const int64_t cols = 32 * skinny_waves((int)(Mp / 32));
-  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, blocks_per_slice);
-  hipError_t e = launch_expand_half_line(scale_kind, asym, A_codes, A_scales, M, K, Mp, batch, Ap, s);
+  hipError_t e = launch_expand_half_line(scale_kind, asym, A_codes, A_scales, M, K, Mp_all, batch, Ap, s);
   if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
   // E8M0 floor and round share the byte encoding
   const int sk = scale_kind == kScaleE8M0Round ? kScaleE8M0Floor : scale_kind;
-  auto go = [&]<int SK, bool ASYM>() {
-    switch ((int)(Mp / 32)) {
-      case 1: return launch_skinny<SK, ASYM, 1>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
-      case 2: return launch_skinny<SK, ASYM, 2>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
-      case 3: return launch_skinny<SK, ASYM, 3>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
-      case 4: return launch_skinny<SK, ASYM, 4>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
-      case 6: return launch_skinny<SK, ASYM, 6>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
-      default: return launch_skinny<SK, ASYM, 8>(Ap, B_codes, B_scales, C, partial, M, N, K, ldc, batch, slices, blocks_per_slice, s);
-    }
-  };
-  if (sk == kScaleE5M2)
-    e = asym ? go.template operator()<kScaleE5M2, true>() : go.template operator()<kScaleE5M2, false>();
-  else if (sk == kScaleE4M3)
-    e = asym ? go.template operator()<kScaleE4M3, true>() : go.template operator()<kScaleE4M3, false>();
-  else
-    e = asym ? go.template operator()<kScaleE8M0Floor, true>() : go.template operator()<kScaleE8M0Floor, false>();
-  if (e != hipSuccess) return e;
+  // row chunks (one unless M > kSkinnyMaxM, and then batch == 1): rows r0 .. r0 + rows - 1 of A's panel and of C
+  for (int64_t r0 = 0; r0 < M; r0 += kSkinnyMaxM) {
+    const int64_t rows = M - r0 < kSkinnyMaxM ? M - r0 : kSkinnyMaxM;
+    const int64_t Mp = 32 * skinny_row_tiles(rows), cols = 32 * skinny_waves((int)(Mp / 32));
+    int bps;
+    const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, bps);
+    const uint16_t* Ac = Ap + r0 * K;  // panel row blocks are contiguous: 32 rows x K values each
+    float* Cc = C + r0 * ldc;
+    auto go = [&]<int SK, bool ASYM>() {
+      switch ((int)(Mp / 32)) {
+        case 1: return launch_skinny<SK, ASYM, 1>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
+        case 2: return launch_skinny<SK, ASYM, 2>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
+        case 3: return launch_skinny<SK, ASYM, 3>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
+        case 4: return launch_skinny<SK, ASYM, 4>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
+        case 6: return launch_skinny<SK, ASYM, 6>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
+        default: return launch_skinny<SK, ASYM, 8>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
+      }
+    };
+    if (sk == kScaleE5M2)
+      e = asym ? go.template operator()<kScaleE5M2, true>() : go.template operator()<kScaleE5M2, false>();
+    else if (sk == kScaleE4M3)
+      e = asym ? go.template operator()<kScaleE4M3, true>() : go.template operator()<kScaleE4M3, false>();
+    else
+      e = asym ? go.template operator()<kScaleE8M0Floor, true>() : go.template operator()<kScaleE8M0Floor, false>();
+    if (e != hipSuccess) return e;
+  }
   if (timer.stop) e = hipEventRecord(timer.stop, s);
   return e;
 }

@@ -55,7 +55,7 @@ hipError_t launch_expand_bf16(int scale_kind, bool asym, int64_t group_size, con
 
 // gemm_skinny.hip: M <= 256, K a multiple of 256, groups of 32: B dequantized in registers straight from its codes
 // (workspace: the BF16 panel of A and, with several outer K slices, the partial tiles)
-bool skinny_path_supported(int64_t M, int64_t N, int64_t K);
+bool skinny_path_supported(int64_t M, int64_t N, int64_t K, int64_t batch);
 size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
 hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                                    const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,

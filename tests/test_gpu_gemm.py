@@ -234,6 +234,26 @@ def test_few_rows_against_many_columns(M, N, K, scale, asym):
     assert np.allclose(C, Cr, rtol=1e-4, atol=1e-4 * np.abs(Cr).max())
 
 
+@pytest.mark.parametrize("scale,asym,M", [(ref.FP8_E5M2, 1, 300), (ref.FP8_E5M2, 1, 600), (ref.E8M0_FLOOR, 0, 768)])
+def test_row_chunks_against_a_large_b(scale, asym, M):
+    """257 .. 768 rows against at least 2^27 weight elements run as row chunks of 256 through the few-rows kernel.
+    The oracle multiplies a sample of rows (first, last and both sides of every chunk boundary among them)."""
+    N, K = 16389, 8192
+    a = synth.activations(M, K, seed=M, n_outlier=2, outlier_gain=40.0)
+    b = synth.weights(N, K, seed=3)
+    ac, as_ = ref.quantize(a, 32, scale, asym)
+    bc, bs = ref.quantize(b, 32, scale, asym)
+    C = G.gpu_gemm(ac, as_, bc, bs, scale, asym)
+    assert C.shape == (M, N)
+    rows = sorted(set([0, 1, 255, 256, 257, 299, M - 1] + [r for r in (511, 512, 513) if r < M] +
+                      list(np.random.default_rng(M).integers(0, M, 12))))
+    Cr = ref.gemm(ac[rows], as_[rows], bc, bs, 32, scale, asym)
+    assert G.rel_fro(C[rows], Cr) <= TOL
+    assert np.allclose(C[rows], Cr, rtol=1e-4, atol=1e-4 * np.abs(Cr).max())
+    # the rows outside the sample: finite and of the same magnitude (nothing left unwritten or written twice)
+    assert np.isfinite(C).all() and abs(np.abs(C).mean() / np.abs(Cr).mean() - 1) < 0.2
+
+
 @pytest.mark.parametrize("asym", [1, 0])
 def test_few_rows_integer_exact_batched_and_repeatable(asym):
     """Scales 1 and integer codes: exact integers below 2^24 in any summation order, so the result must equal the
