@@ -204,16 +204,14 @@ size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batc
   return bytes + partial;
 }
 
-// grid: (ceil(N / 128), outer slices, batch); block 256 = 4 waves.
+// grid: (ceil(N / (32 * waves)), outer slices, batch); block = skinny_waves(MT) waves.
 // (B_codes, B_scales and out are deliberately not declared restrict: loads the compiler knows to be from memory nobody
 // writes may be moved across the barriers, down to their first use, which undoes the prefetch.)
 // out: C (ld_out = ldc) when gridDim.y == 1, else partials [batch][slice][MT * 32][N].
 template <int SCALE_KIND, bool ASYM, int MT>
-__global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(const uint16_t* __restrict__ Ap, const uint8_t* B_codes,
-                                                          const uint8_t* B_scales, float* out,
-                                                          int64_t M, int64_t N, int64_t K, int64_t ld_out,
-                                                          int64_t batch_stride_out, int64_t slice_stride_out,
-                                                          int blocks_per_slice) {
+__global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(
+    const uint16_t* __restrict__ Ap, const uint8_t* B_codes, const uint8_t* B_scales, float* out, int64_t M, int64_t N,
+    int64_t K, int64_t ld_out, int64_t batch_stride_out, int64_t slice_stride_out, int blocks_per_slice) {
   // One step of the main loop multiplies one A stage: half a K block (8 k-steps of 16), or a whole one when there are
   // so few row tiles that half a block is too little work between two barriers to cover the latency of the loads
   // that fill the other stage.
@@ -406,8 +404,8 @@ static hipError_t launch_skinny(const uint16_t* Ap, const uint8_t* Bc, const uin
   constexpr int kWaves = skinny_waves(MT), kCols = 32 * kWaves;
   const dim3 grid((unsigned)((N + kCols - 1) / kCols), (unsigned)slices, (unsigned)batch);
   if (slices == 1) {
-    hipLaunchKernelGGL((gemm_skinny_kernel<SK, ASYM, MT>), grid, dim3(64 * kWaves), 0, s, Ap, Bc, Bs, C, M, N, K, ldc, M * ldc,
-                       (int64_t)0, blocks_per_slice);
+    hipLaunchKernelGGL((gemm_skinny_kernel<SK, ASYM, MT>), grid, dim3(64 * kWaves), 0, s, Ap, Bc, Bs, C, M, N, K, ldc,
+                       M * ldc, (int64_t)0, blocks_per_slice);
     return hipGetLastError();
   }
   hipLaunchKernelGGL((gemm_skinny_kernel<SK, ASYM, MT>), grid, dim3(64 * kWaves), 0, s, Ap, Bc, Bs, partial, M, N, K, N,
@@ -442,13 +440,16 @@ hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t
     const uint16_t* Ac = Ap + r0 * K;  // panel row blocks are contiguous: 32 rows x K values each
     float* Cc = C + r0 * ldc;
     auto go = [&]<int SK, bool ASYM>() {
+      auto run = [&]<int MT>() {
+        return launch_skinny<SK, ASYM, MT>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
+      };
       switch ((int)(Mp / 32)) {
-        case 1: return launch_skinny<SK, ASYM, 1>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
-        case 2: return launch_skinny<SK, ASYM, 2>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
-        case 3: return launch_skinny<SK, ASYM, 3>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
-        case 4: return launch_skinny<SK, ASYM, 4>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
-        case 6: return launch_skinny<SK, ASYM, 6>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
-        default: return launch_skinny<SK, ASYM, 8>(Ac, B_codes, B_scales, Cc, partial, rows, N, K, ldc, batch, slices, bps, s);
+        case 1: return run.template operator()<1>();
+        case 2: return run.template operator()<2>();
+        case 3: return run.template operator()<3>();
+        case 4: return run.template operator()<4>();
+        case 6: return run.template operator()<6>();
+        default: return run.template operator()<8>();
       }
     };
     if (sk == kScaleE5M2)
