@@ -124,6 +124,7 @@ def cpu_baseline(x_bits, w_bits, K, sample_m=2048, sample_n=14336):
     the same operands: quantize sample_m rows of X and sample_n rows of W, then the sample_m x sample_n x K GEMM."""
     from oracle import ref
     xs, ws = x_bits[:sample_m], w_bits[:sample_n]
+    sample_m, sample_n = xs.shape[0], ws.shape[0]  # (workloads with fewer rows than the sample use all of them)
     ref.lib()  # compile / load outside the timed region
     t0 = time.perf_counter()
     xc, xsc = ref.quantize(xs)
