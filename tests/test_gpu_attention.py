@@ -1,5 +1,6 @@
-"""Fully quantized attention matmuls (BASELINE config 4, cut down): Q.K^T grouped along head_dim, softmax(P).V grouped
-along the key sequence (P strongly one-sided; V cast along a strided axis), heads as the GEMM batch."""
+"""Fully quantized attention matmuls (the attention workload, 32 heads of 128, cut down): Q.K^T grouped along
+head_dim, softmax(P).V grouped along the key sequence (P strongly one-sided; V cast along a strided axis), heads as
+the GEMM batch."""
 import numpy as np
 import pytest
 import torch
