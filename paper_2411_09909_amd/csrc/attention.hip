@@ -146,10 +146,18 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
     (void)encode_scale_sr<SCALE_KIND>(pmax, S, R);                                                                 \
     uint32_t pb[8];                                                                                                \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
-      const uint32_t code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x[2 * i] * R, x[2 * i + 1] * R, 1.0f, 0); \
-      const f32x2 e = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(code, 1.0f, 0);                                     \
-      /* element * scale has at most 6 significant bits: the truncation to BF16 is exact */                       \
-      pb[i] = __builtin_amdgcn_perm(f2u(e[1] * S), f2u(e[0] * S), 0x07060302u);                                    \
+      if constexpr (SCALE_KIND == kScaleE5M2 || SCALE_KIND == kScaleE4M3) {                                        \
+        const uint32_t code =                                                                                      \
+            __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x[2 * i] * R, x[2 * i + 1] * R, 1.0f, 0);                 \
+        const f32x2 e = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(code, 1.0f, 0);                                   \
+        /* element * scale has at most 6 significant bits: the truncation to BF16 is exact */                     \
+        pb[i] = __builtin_amdgcn_perm(f2u(e[1] * S), f2u(e[0] * S), 0x07060302u);                                  \
+      } else {                                                                                                     \
+        /* a power-of-two scale is applied by the conversions themselves (they read the exponent field of S: the  \
+           first divides by it, the second multiplies) */                                                          \
+        const uint32_t code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x[2 * i], x[2 * i + 1], S, 0);          \
+        pb[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(code, S, 0));               \
+      }                                                                                                            \
     }                                                                                                              \
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) { /* the maximum moved for some query: rescale */        \
       _Pragma("unroll") for (int db = 0; db < kAttnD / 32; ++db)                                                   \
