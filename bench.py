@@ -25,6 +25,9 @@ PEAK_FP8_TFLOPS = 5000.0    # MI355X dense block-scaled FP8 MFMA
 # HBM bytes per GEMM-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see
 # profiles/gemm_bf16_c3_up_counters.md.
 MEASURED_TRAFFIC_BYTES = 3.43e9  # 2.96 GB fetched + 0.47 GB written
+# the few-rows kernel on c3_70b_up_32tokens_32x8192x28672 (profiles/gemm_skinny_c3_up_32tokens_kernel_trace.md):
+# FETCH_SIZE 152.0 MB + WRITE_SIZE 7.3 MB per launch
+MEASURED_TRAFFIC_FEW_ROWS = 159.3e6
 
 
 # format name -> (scale kind, asymmetric, MFMA type issued by the GEMM, its dense peak in TFLOP/s)
@@ -261,7 +264,10 @@ def main():
         kbytes = N * K // 2 + N * (K // 32) * (2 if r["asym"] else 1) + ((M + 31) // 32 * 32) * K * 2 + M * N * 4
         gbps = kbytes / (r["kern_ms"] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s",
-                    "frac": round(gbps / 8000.0, 4), "traffic": None, "kernel_ms": round(r["kern_ms"], 4),
+                    "frac": round(gbps / 8000.0, 4),
+                    "traffic": MEASURED_TRAFFIC_FEW_ROWS if args.format == "amxfp4_e5m2" and args.group_size == 32
+                    and args.workload == "c3_70b_up_32tokens_32x8192x28672" else None,
+                    "kernel_ms": round(r["kern_ms"], 4),
                     "algorithmic_bytes": kbytes}
     else:
         roofline = {"bound": "mfma", "kernel": kernel_name, "achieved": round(achieved, 2), "peak": r["peak"],
