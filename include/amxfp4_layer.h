@@ -18,6 +18,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "amxfp4.h" /* amx_format_t, status codes */
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -57,6 +59,25 @@ int amxfp4_softmax_causal(const float* scores, int64_t batch, int64_t rows, int6
  * width must be a multiple of 4.
  */
 int amxfp4_silu_mul(const float* gate_up, int64_t rows, int64_t width, void* out_bf16, void* stream);
+
+/*
+ * The fused gate / up projection with the gated activation applied before anything is written: out[r, c] =
+ * bf16( silu(g) * u ) with (g | u) = the quantized product A . B^T of amxfp4_gemm (Sec. 4.3) and the arithmetic of
+ * amxfp4_silu_mul, bit for bit; the FP32 product never goes to memory.
+ *   A                  [M][K] quantized activations (codes, scales as for amxfp4_gemm).
+ *   B                  [2 * width][K] quantized weights with the rows of the gate and of the up projection INTERLEAVED
+ *                      in blocks of 32: rows 64 t .. 64 t + 31 are gate rows 32 t .. 32 t + 31, rows 64 t + 32 ..
+ *                      64 t + 63 the up rows of the same indices. width % 32 == 0.
+ *   out_bf16           device out, [M][ld_out] BF16 bit patterns, ld_out >= width.
+ *   workspace          at least amxfp4_gemm_silu_mul_workspace_bytes() bytes, 256-byte aligned; may be NULL when
+ *                      that is 0. The product runs on the tiled kernel of the format (block-scaled matrix
+ *                      instructions for power-of-two scales of 32-groups, exact BF16 operands otherwise), whatever M.
+ * Status codes as amxfp4_gemm.
+ */
+size_t amxfp4_gemm_silu_mul_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K);
+int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K, const uint8_t* A_codes,
+                         const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, void* out_bf16,
+                         int64_t ld_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /* out = bf16( float(x) + y ): x, out [n] BF16, y [n] FP32 (residual connection after a projection). n % 4 == 0. */
 int amxfp4_residual_add(const void* x_bf16, const float* y, int64_t n, void* out_bf16, void* stream);

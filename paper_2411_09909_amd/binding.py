@@ -48,6 +48,10 @@ def load():
         d.argtypes = [fp, vp, vp, i64, i64, vp, ctypes.c_int32, vp]
         g.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, i64, i64, vp, ctypes.c_size_t, vp]
         q.restype = d.restype = g.restype = ctypes.c_int
+    L.amxfp4_gemm_silu_mul_workspace_bytes.argtypes = [fp, i64, i64, i64]
+    L.amxfp4_gemm_silu_mul_workspace_bytes.restype = ctypes.c_size_t
+    L.amxfp4_gemm_silu_mul.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, i64, vp, ctypes.c_size_t, vp]
+    L.amxfp4_gemm_silu_mul.restype = ctypes.c_int
     L.amxfp4_quantize_batched.argtypes = [fp, vp, i64, i64, i64, i64, i64, i64, vp, vp, vp]
     L.amxfp4_quantize_batched.restype = ctypes.c_int
     L.amxfp4_profile_next_gemm.argtypes = [vp, vp]
@@ -235,6 +239,35 @@ def quantize_batched(fmt, x, k_axis=-1, codes=None, scales=None):
     _check(load().amxfp4_quantize_batched(ctypes.byref(fmt), x.data_ptr(), batch, x.stride(0), rows, K, row_stride,
                                           k_stride, codes.data_ptr(), scales.data_ptr(), _stream()))
     return codes, scales
+
+
+def interleave_gate_up(gate, up):
+    """Rows of the two [width, K] projection matrices interleaved in blocks of 32, the order gemm_silu_mul() wants."""
+    width, K = gate.shape
+    assert up.shape == gate.shape and width % 32 == 0
+    return torch.stack([gate.view(width // 32, 32, K), up.view(width // 32, 32, K)], 1).reshape(2 * width, K)
+
+
+def gemm_silu_mul_workspace_bytes(fmt, M, width, K):
+    return int(load().amxfp4_gemm_silu_mul_workspace_bytes(ctypes.byref(fmt), M, width, K))
+
+
+def gemm_silu_mul(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None):
+    """bf16(silu(g) * u) of the fused gate / up projection (g | u) = A . B^T, B's rows interleaved as by
+    interleave_gate_up() before they were cast. Returns [M, width] BF16."""
+    _need_cuda(a_codes, a_scales, b_codes, b_scales)
+    M, K = a_codes.shape[0], a_codes.shape[1] * 2
+    width = b_codes.shape[0] // 2
+    if out is None:
+        out = torch.empty((M, width), dtype=torch.bfloat16, device=a_codes.device)
+    need = gemm_silu_mul_workspace_bytes(fmt, M, width, K)
+    if need and (workspace is None or workspace.numel() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)
+    _check(load().amxfp4_gemm_silu_mul(ctypes.byref(fmt), M, width, K, a_codes.data_ptr(), a_scales.data_ptr(),
+                                       b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(), out.stride(0),
+                                       workspace.data_ptr() if need else None, workspace.numel() if need else 0,
+                                       _stream()))
+    return out
 
 
 def dequantize(fmt, codes, scales, out_dtype=torch.float32, baseline=False, tensor_pair=None):

@@ -8,6 +8,7 @@
 #include <atomic>
 
 #include "../../include/amxfp4.h"
+#include "../../include/amxfp4_layer.h"
 #include "kernels.h"
 
 namespace {
@@ -224,6 +225,13 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
   return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
 }
 
+// The gated GEMM runs on the tiled kernels only (the block-scaled ones for power-of-two scales, else the BF16 panels).
+size_t glu_workspace_bytes(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
+  if (uses_merged_pot(f, M, N, K)) return amx::fp8m_path_workspace_bytes(M, N, K, 1);
+  if (uses_fp4_mfma(f, M, N, K)) return 0;
+  return amx::bf16_path_workspace_bytes(M, N, K, 1);
+}
+
 amx_format_t symmetric(const amx_format_t* f) {
   amx_format_t g = *f;
   g.asymmetric = 0;
@@ -286,6 +294,56 @@ int amxfp4_quantize_batched(const amx_format_t* fmt, const void* x_bf16, int64_t
                             uint8_t* scales, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
   return quantize_impl(*fmt, x_bf16, batch, batch_stride, rows, K, row_stride, k_stride, nullptr, codes, scales, stream);
+}
+
+size_t amxfp4_gemm_silu_mul_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K) {
+  if (!fmt) return 0;
+  amx_format_t f = *fmt;
+  if (check_format(&f) || check_shape(f, M, K) || width <= 0 || width % 32 != 0 || 2 * width > kMaxGemmRows ||
+      M > kMaxGemmRows)
+    return 0;
+  return glu_workspace_bytes(f, M, 2 * width, K);
+}
+
+int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K, const uint8_t* A_codes,
+                         const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, void* out_bf16,
+                         int64_t ld_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  amx_format_t f = *fmt;
+  if (int rc = check_format(&f)) return rc;
+  if (int rc = check_shape(f, M, K)) return rc;
+  if (width <= 0 || width % 32 != 0) return fail(AMX_ERR_INVALID_ARG, "gemm_silu_mul: width must be a positive multiple of 32");
+  if (M > kMaxGemmRows || 2 * width > kMaxGemmRows)
+    return fail(AMX_ERR_INVALID_ARG, "gemm_silu_mul: M and 2 * width may be at most %lld", (long long)kMaxGemmRows);
+  if (ld_out < width) return fail(AMX_ERR_INVALID_ARG, "gemm_silu_mul: ld_out < width");
+  if (!A_codes || !A_scales || !B_codes || !B_scales || !out_bf16) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
+  if (!aligned(A_codes, 16) || !aligned(B_codes, 16) || !aligned(A_scales, 4) || !aligned(B_scales, 4) ||
+      !aligned(out_bf16, 2))
+    return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales 4-byte, out 2-byte alignment");
+  const size_t need = glu_workspace_bytes(f, M, 2 * width, K);
+  if (need > 0) {
+    if (!workspace || workspace_bytes < need)
+      return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
+    if (!aligned(workspace, 256)) return fail(AMX_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  }
+  const amx::KernelTimer timer = g_timer;
+  g_timer = amx::KernelTimer();
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  float* out = reinterpret_cast<float*>(out_bf16);
+  if (uses_merged_pot(f, M, 2 * width, K)) {
+    hipError_t e = amx::launch_gemm_fp8m_path(M, 2 * width, K, A_codes, A_scales, B_codes, B_scales, out, ld_out, 1,
+                                              workspace, hs, timer, true);
+    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
+  }
+  if (uses_fp4_mfma(f, M, 2 * width, K)) {
+    hipError_t e = amx::launch_gemm_fp4_path(f.asymmetric != 0, M, 2 * width, K, A_codes, A_scales, B_codes, B_scales,
+                                             out, ld_out, 1, hs, timer, true);
+    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
+  }
+  hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, f.group_size, M, 2 * width, K, A_codes, A_scales,
+                                            B_codes, B_scales, nullptr, nullptr, reinterpret_cast<float*>(out_bf16),
+                                            ld_out, 1, workspace, reinterpret_cast<hipStream_t>(stream), timer, true);
+  return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
 }
 
 int amxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,

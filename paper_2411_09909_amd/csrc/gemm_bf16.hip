@@ -123,7 +123,9 @@ __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__
 
 // SCALED: the result is multiplied by the product of the operands' tensor-wise scales alpha_a[0] * alpha_b[0]
 // (Sec. 5.3, double scaling), read from device memory after the main loop.
-template <int WM, int WN, int FM, int FN, bool SCALED>
+// GLU: the gated-activation epilogue of store_glu_tiles() instead of the FP32 store: C is then the BF16 output
+// [M][ldc] with N / 2 columns.
+template <int WM, int WN, int FM, int FN, bool SCALED, bool GLU = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t* __restrict__ Ap,
                                                                  const uint16_t* __restrict__ Bp, float* __restrict__ C,
                                                                  int64_t M, int64_t N, int64_t Mp, int64_t Np,
@@ -252,7 +254,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t*
 #undef AMX_STAGE
 #undef AMX_ISSUE_LOAD
 
-  if constexpr (SCALED)
+  if constexpr (GLU)
+    store_glu_tiles<FM, FN>(acc, reinterpret_cast<uint16_t*>(C) + b * M * ldc, M, N >> 1, ldc,
+                            (int64_t)tm * Cfg::kTileM + wm * FM * 32, (int64_t)tn * Cfg::kTileN + wn * FN * 32);
+  else if constexpr (SCALED)
     store_c_tiles<FM, FN, 0, true>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * Cfg::kTileM + wm * FM * 32,
                                    (int64_t)tn * Cfg::kTileN + wn * FN * 32, alpha_a[0] * alpha_b[0]);
   else
@@ -324,12 +329,16 @@ hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t
 template <int WM, int WN, int FM, int FN>
 static hipError_t launch_tiles(const uint16_t* Ap, const uint16_t* Bp, float* C, int64_t M, int64_t N, int64_t Mp,
                                int64_t Np, int64_t Kp, int64_t ldc, int64_t batch, const float* alpha_a,
-                               const float* alpha_b, hipStream_t s) {
+                               const float* alpha_b, bool glu, hipStream_t s) {
   using Cfg = TileCfg<WM, WN, FM, FN>;
   const int tiles_m = (int)((M + Cfg::kTileM - 1) / Cfg::kTileM), tiles_n = (int)((N + Cfg::kTileN - 1) / Cfg::kTileN);
   int super_m;
   const unsigned grid = supertile_grid(tiles_m, tiles_n, super_m);
-  if (alpha_a && alpha_b)
+  if (glu)
+    hipLaunchKernelGGL((gemm_bf16_kernel<WM, WN, FM, FN, false, true>), dim3(grid, 1, (unsigned)batch),
+                       dim3(Cfg::kThreads), 0, s, Ap, Bp, C, M, N, Mp, Np, Kp, ldc, tiles_m, tiles_n, super_m, alpha_a,
+                       alpha_b);
+  else if (alpha_a && alpha_b)
     hipLaunchKernelGGL((gemm_bf16_kernel<WM, WN, FM, FN, true>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0,
                        s, Ap, Bp, C, M, N, Mp, Np, Kp, ldc, tiles_m, tiles_n, super_m, alpha_a, alpha_b);
   else
@@ -342,7 +351,7 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
                                  const uint8_t* A_codes, const uint8_t* A_scales, const uint8_t* B_codes,
                                  const uint8_t* B_scales, const float* A_tensor_pair, const float* B_tensor_pair,
                                  float* C, int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
-                                 const KernelTimer& timer) {
+                                 const KernelTimer& timer, bool glu) {
   const int gs_log2 = group_size == 16 ? 4 : group_size == 32 ? 5 : group_size == 64 ? 6 : group_size == 128 ? 7 : -1;
   if (gs_log2 < 0 || K % group_size != 0 || K % 32 != 0) return hipErrorInvalidValue;
   const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows), Kp = round_up(K, kPanelK);
@@ -373,15 +382,15 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
     tile_cfg = 3;
   if (tile_env >= 0) tile_cfg = tile_env;
   if (tile_cfg == 1)
-    e = launch_tiles<2, 4, 4, 2>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, s);
+    e = launch_tiles<2, 4, 4, 2>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, glu, s);
   else if (tile_cfg == 2)
-    e = launch_tiles<4, 2, 2, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, s);
+    e = launch_tiles<4, 2, 2, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, glu, s);
   else if (tile_cfg == 3)
-    e = launch_tiles<4, 1, 2, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, s);  // 256 x 128
+    e = launch_tiles<4, 1, 2, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, glu, s);  // 256 x 128
   else if (tile_cfg == 4)
-    e = launch_tiles<1, 4, 2, 2>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, s);  // 64 x 256
+    e = launch_tiles<1, 4, 2, 2>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, glu, s);  // 64 x 256
   else
-    e = launch_tiles<2, 2, 4, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, s);
+    e = launch_tiles<2, 2, 4, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, glu, s);
   if (e != hipSuccess) return e;
   if (timer.stop) e = hipEventRecord(timer.stop, s);
   return e;

@@ -9,6 +9,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "layer_math.h"
 
 namespace amx {
 
@@ -88,6 +89,34 @@ __device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[FM][FN], float
             if constexpr (ALPHA) c *= alpha;
             __builtin_nontemporal_store(c, Cb + row * ldc + col);
           }
+        }
+      }
+    }
+  }
+}
+
+// The gated-activation epilogue: the wave's column tiles come in pairs (gate columns, up columns: the B operand's rows
+// are interleaved in blocks of 32), and out[row][c] = bf16(silu(gate) * up) for the 32 columns c of each pair, the
+// arithmetic of the separate operator (layer_math.h). out is row-major BF16 with leading dimension ld and n_out
+// columns; col_base is the first (interleaved) column of the wave's tiles, a multiple of 64.
+template <int FM, int FN>
+__device__ __forceinline__ void store_glu_tiles(const f32x16 (&acc)[FM][FN], uint16_t* __restrict__ out, int64_t M,
+                                                int64_t n_out, int64_t ld, int64_t row_base, int64_t col_base) {
+  static_assert(FN % 2 == 0, "column tiles come in (gate, up) pairs");
+  const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  const int64_t col0 = (col_base >> 1) + (lane & 31);
+  // row by row, the pairs of a row one after the other: their 64-byte pieces are neighbours in memory
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    const int64_t row0 = row_base + i * 32 + 4 * (lane >> 5);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int64_t row = row0 + 8 * (v >> 2) + (v & 3);
+      if (row < M) {
+#pragma unroll
+        for (int j = 0; j < FN; j += 2) {
+          const int64_t col = col0 + (j >> 1) * 32;
+          if (col < n_out) out[row * ld + col] = (uint16_t)bf16_rne(silu_mul_value(acc[i][j][v], acc[i][j + 1][v]));
         }
       }
     }

@@ -48,7 +48,8 @@ __device__ __forceinline__ u32x4 sign_class4(u32x4 v) {
 // during the first half of a stage. The single barrier of a stage comes after step 13 of 16: by then every wave has
 // its last fragments of the current buffer and the next stage has landed; the two steps after it read ahead into the
 // next buffer.
-template <int WM, int WN, int FM, int FN, bool ASYM>
+// GLU: the gated-activation epilogue of store_glu_tiles() (gemm_common.h); C is then the BF16 output [M][ldc].
+template <int WM, int WN, int FM, int FN, bool ASYM, bool GLU = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* __restrict__ Ac,
                                                                 const uint8_t* __restrict__ As,
                                                                 const uint8_t* __restrict__ Bc,
@@ -296,8 +297,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
 #undef lds1_A
 #undef lds1_B
 
-  store_c_tiles<FM, FN>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * kTileM + wm * FM * 32,
-                        (int64_t)tn * kTileN + wn * FN * 32);
+  if constexpr (GLU)
+    store_glu_tiles<FM, FN>(acc, reinterpret_cast<uint16_t*>(C) + b * M * ldc, M, N >> 1, ldc,
+                            (int64_t)tm * kTileM + wm * FM * 32, (int64_t)tn * kTileN + wn * FN * 32);
+  else
+    store_c_tiles<FM, FN>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * kTileM + wm * FM * 32,
+                          (int64_t)tn * kTileN + wn * FN * 32);
 }
 
 bool fp4_path_supported(int64_t M, int64_t N, int64_t K) {
@@ -309,15 +314,19 @@ bool fp4_path_supported(int64_t M, int64_t N, int64_t K) {
 template <bool ASYM>
 static hipError_t launch_fp4(int64_t M, int64_t N, int64_t K, const uint8_t* Ac, const uint8_t* As, const uint8_t* Bc,
                              const uint8_t* Bs, float* C, int64_t ldc, int64_t batch, hipStream_t s,
-                             const KernelTimer& timer) {
+                             const KernelTimer& timer, bool glu) {
   using Cfg = TileCfg<2, 2, 4, 4>;
   const int tiles_m = (int)((M + Cfg::kTileM - 1) / Cfg::kTileM), tiles_n = (int)((N + Cfg::kTileN - 1) / Cfg::kTileN);
   int super_m;
   const unsigned grid = supertile_grid(tiles_m, tiles_n, super_m);
   hipError_t e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
-  hipLaunchKernelGGL((gemm_fp4_kernel<2, 2, 4, 4, ASYM>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s, Ac,
-                     As, Bc, Bs, C, M, N, K, ldc, tiles_m, tiles_n, super_m);
+  if (glu)
+    hipLaunchKernelGGL((gemm_fp4_kernel<2, 2, 4, 4, ASYM, true>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads),
+                       0, s, Ac, As, Bc, Bs, C, M, N, K, ldc, tiles_m, tiles_n, super_m);
+  else
+    hipLaunchKernelGGL((gemm_fp4_kernel<2, 2, 4, 4, ASYM>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s,
+                       Ac, As, Bc, Bs, C, M, N, K, ldc, tiles_m, tiles_n, super_m);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (timer.stop) e = hipEventRecord(timer.stop, s);
   return e;
@@ -325,9 +334,9 @@ static hipError_t launch_fp4(int64_t M, int64_t N, int64_t K, const uint8_t* Ac,
 
 hipError_t launch_gemm_fp4_path(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
-                                int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer) {
-  return asym ? launch_fp4<true>(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, s, timer)
-              : launch_fp4<false>(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, s, timer);
+                                int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer, bool glu) {
+  return asym ? launch_fp4<true>(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, s, timer, glu)
+              : launch_fp4<false>(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, s, timer, glu);
 }
 
 }  // namespace amx

@@ -87,7 +87,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const uint8_t* __restrict__ 
   anchors[(((b * (Rp >> 5) + rb) * (Kp >> 8) + blockIdx.x) * 64 + lane) * 4 + wave] = (uint8_t)anchor;
 }
 
-template <int WM, int WN, int FM, int FN>
+// GLU: the gated-activation epilogue of store_glu_tiles() (gemm_common.h); C is then the BF16 output [M][ldc].
+template <int WM, int WN, int FM, int FN, bool GLU = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_fp8m_kernel(const uint8_t* __restrict__ Ap,
                                                                  const uint8_t* __restrict__ Asc,
                                                                  const uint8_t* __restrict__ Bp,
@@ -245,13 +246,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp8m_kernel(const uint8_t* 
 #undef AMX_LOAD_ANCHORS
 #undef AMX_ISSUE_LOAD
 
-  store_c_tiles<FM, FN>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * Cfg::kTileM + wm * FM * 32,
-                        (int64_t)tn * Cfg::kTileN + wn * FN * 32);
+  if constexpr (GLU)
+    store_glu_tiles<FM, FN>(acc, reinterpret_cast<uint16_t*>(C) + b * M * ldc, M, N >> 1, ldc,
+                            (int64_t)tm * Cfg::kTileM + wm * FM * 32, (int64_t)tn * Cfg::kTileN + wn * FN * 32);
+  else
+    store_c_tiles<FM, FN>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * Cfg::kTileM + wm * FM * 32,
+                          (int64_t)tn * Cfg::kTileN + wn * FN * 32);
 }
 
 hipError_t launch_gemm_fp8m_path(int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
                                  const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch,
-                                 void* workspace, hipStream_t s, const KernelTimer& timer) {
+                                 void* workspace, hipStream_t s, const KernelTimer& timer, bool glu) {
   const int64_t Kp = round_up(K, kMergeK), Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows);
   uint8_t* Ap = reinterpret_cast<uint8_t*>(workspace);
   uint8_t* Bp = Ap + batch * merged_panel_bytes(Mp, Kp);
@@ -268,8 +273,12 @@ hipError_t launch_gemm_fp8m_path(int64_t M, int64_t N, int64_t K, const uint8_t*
   int super_m;
   const unsigned grid = supertile_grid(tiles_m, tiles_n, super_m);
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
-  hipLaunchKernelGGL((gemm_fp8m_kernel<2, 2, 4, 4>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s, Ap, Asc,
-                     Bp, Bsc, C, M, N, Mp, Np, Kp, ldc, tiles_m, tiles_n, super_m);
+  if (glu)
+    hipLaunchKernelGGL((gemm_fp8m_kernel<2, 2, 4, 4, true>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s,
+                       Ap, Asc, Bp, Bsc, C, M, N, Mp, Np, Kp, ldc, tiles_m, tiles_n, super_m);
+  else
+    hipLaunchKernelGGL((gemm_fp8m_kernel<2, 2, 4, 4>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s, Ap,
+                       Asc, Bp, Bsc, C, M, N, Mp, Np, Kp, ldc, tiles_m, tiles_n, super_m);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (timer.stop) e = hipEventRecord(timer.stop, s);
   return e;

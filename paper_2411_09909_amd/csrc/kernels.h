@@ -39,13 +39,13 @@ struct KernelTimer {
   hipEvent_t start = nullptr, stop = nullptr;
 };
 
-// gemm_bf16.hip
+// gemm_bf16.hip (glu: the gated-activation epilogue; C is then the BF16 output [M][ldc] of N / 2 columns)
 size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
 hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, int64_t M, int64_t N, int64_t K,
                                  const uint8_t* A_codes, const uint8_t* A_scales, const uint8_t* B_codes,
                                  const uint8_t* B_scales, const float* A_tensor_pair, const float* B_tensor_pair,
                                  float* C, int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
-                                 const KernelTimer& timer);
+                                 const KernelTimer& timer, bool glu = false);
 
 // BF16 fragment-major panel [batch][Rp / 32][Kp / 16][64 lanes][8] of a quantized operand (rows >= R and columns >= K
 // zero; Rp % 32 == 0, Kp % 64 == 0). permute: the key order of the fused attention kernel's V operand (gemm_bf16.hip).
@@ -78,18 +78,19 @@ hipError_t launch_expand_half_line(int scale_kind, bool asym, const uint8_t* cod
 hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K,
                                   int64_t Rp, int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s);
 
-// gemm_fp4.hip: power-of-two scales on the block-scaled FP4 MFMA (no workspace)
+// gemm_fp4.hip: power-of-two scales on the block-scaled FP4 MFMA (no workspace). glu here and below: as for the
+// BF16 path
 bool fp4_path_supported(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm_fp4_path(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
-                                int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer);
+                                int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer, bool glu = false);
 
 // gemm_fp8m.hip: asymmetric power-of-two scales merged per group into E5M2 elements + one anchor scale, block-scaled
 // FP8 MFMA (workspace: the merged panels)
 size_t fp8m_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
 hipError_t launch_gemm_fp8m_path(int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
                                  const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch,
-                                 void* workspace, hipStream_t s, const KernelTimer& timer);
+                                 void* workspace, hipStream_t s, const KernelTimer& timer, bool glu = false);
 
 // gemm_e5m2.hip: FP8-E5M2 scales, dequantization fused into the FP16-MFMA kernel (no workspace)
 bool e5m2_fused_supported(int64_t M, int64_t N, int64_t K);

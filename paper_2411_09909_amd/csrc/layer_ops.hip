@@ -6,16 +6,10 @@
 #include "../../include/amxfp4_layer.h"
 #include "device_formats.h"
 #include "kernels.h"
+#include "layer_math.h"
 
 namespace amx {
 namespace {
-
-// FP32 -> BF16 bit pattern, round to nearest even (finite inputs)
-__device__ __forceinline__ uint32_t bf16_rne(float f) {
-  const uint32_t u = f2u(f);
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-__device__ __forceinline__ uint32_t pack2(float a, float b) { return bf16_rne(a) | (bf16_rne(b) << 16); }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -169,7 +163,7 @@ __global__ __launch_bounds__(256) void silu_mul_kernel(const float* __restrict__
   const float gg[4] = {g.x, g.y, g.z, g.w}, uu[4] = {u.x, u.y, u.z, u.w};
   float o[4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) o[j] = gg[j] / (1.0f + expf(-gg[j])) * uu[j];
+  for (int j = 0; j < 4; ++j) o[j] = silu_mul_value(gg[j], uu[j]);
   *reinterpret_cast<uint2*>(out + r * width + c) = make_uint2(pack2(o[0], o[1]), pack2(o[2], o[3]));
 }
 

@@ -45,12 +45,17 @@ class DecoderLayer:
     """weights: dict name -> BF16 CUDA tensor (WEIGHT_SHAPES) plus "norm1" / "norm2" FP32 [d_model]. The weights are
     cast once here (they are static in inference); forward() casts the activations."""
 
-    def __init__(self, cfg, weights, fmt, baseline=False, fused_attention=False):
+    def __init__(self, cfg, weights, fmt, baseline=False, fused_attention=False, fused_glu=None):
         self.cfg, self.fmt, self.baseline, self.fused_attention = cfg, fmt, baseline, fused_attention
+        # the gate / up projection with the gated activation in its epilogue (the FP32 product is never written)
+        if fused_glu is None:
+            fused_glu = cfg.d_ff % 32 == 0
+        self.fused_glu = fused_glu
         q = lambda w: binding.quantize(fmt, w.contiguous(), baseline=baseline)  # noqa: E731
         self.wqkv = q(torch.cat([weights["wq"], weights["wk"], weights["wv"]], 0))
         self.wo = q(weights["wo"])
-        self.wgu = q(torch.cat([weights["wg"], weights["wu"]], 0))
+        self.wgu = q(binding.interleave_gate_up(weights["wg"], weights["wu"]) if fused_glu
+                     else torch.cat([weights["wg"], weights["wu"]], 0))
         self.wd = q(weights["wd"])
         self.norm1, self.norm2 = weights["norm1"].contiguous(), weights["norm2"].contiguous()
         self._ws = None
@@ -113,7 +118,15 @@ class DecoderLayer:
         c = self.cfg
         x2 = binding.residual_add(x, self._gemm(self._cast(attn), self.wo))
         h2 = binding.rmsnorm(x2, self.norm2, c.eps)
-        act = binding.silu_mul(self._gemm(self._cast(h2), self.wgu))
+        if self.fused_glu:
+            hc = self._cast(h2)
+            fmt = binding.make_format(self.fmt.scale, False, self.fmt.group_size) if self.baseline else self.fmt
+            need = binding.gemm_silu_mul_workspace_bytes(fmt, hc[0].shape[0], c.d_ff, c.d_model)
+            if need and (self._ws is None or self._ws.numel() < need):
+                self._ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+            act = binding.gemm_silu_mul(fmt, hc[0], hc[1], self.wgu[0], self.wgu[1], workspace=self._ws)
+        else:
+            act = binding.silu_mul(self._gemm(self._cast(h2), self.wgu))
         return binding.residual_add(x2, self._gemm(self._cast(act), self.wd))
 
     def matmul_flops(self, S):

@@ -135,6 +135,25 @@ def test_batched_cast_rejects_bad_arguments(lib):
     assert q(ctypes.byref(ok), None, 2, 4096, 4, 64, 64, 1, p, p, None) == -1
 
 
+def test_gated_gemm_rejects_bad_arguments(lib):
+    ok = binding.make_format(binding.FP8_E5M2, True, 32)
+    p = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
+    g = lib.amxfp4_gemm_silu_mul
+    big = ctypes.c_size_t(1 << 40)
+    assert g(None, 64, 64, 64, p, p, p, p, p, 64, p, big, None) == -1
+    assert g(ctypes.byref(ok), 64, 48, 64, p, p, p, p, p, 64, p, big, None) == -1      # width % 32
+    assert g(ctypes.byref(ok), 64, 64, 48, p, p, p, p, p, 64, p, big, None) == -1      # K % 32
+    assert g(ctypes.byref(ok), 64, 64, 64, p, p, p, p, p, 32, p, big, None) == -1      # ld_out < width
+    assert g(ctypes.byref(ok), 64, 64, 64, p, p, p, p, None, 64, p, big, None) == -1   # no output
+    assert g(ctypes.byref(ok), 64, 64, 64, p, p, p, p, p, 64, None, 0, None) == -3     # no workspace
+    assert g(ctypes.byref(ok), 64, 64, 64, p, p, p, p, p, 64, p, 16, None) == -3       # too small
+    q = lib.amxfp4_gemm_silu_mul_workspace_bytes
+    assert q(ctypes.byref(ok), 64, 64, 64) == (256 + 256) * 128 * 2                    # both BF16 panels, padded
+    pot = binding.make_format(binding.E8M0_FLOOR, False, 32)
+    assert q(ctypes.byref(pot), 64, 64, 128) == 0                                      # codes go to the FP4 MFMA as they are
+    assert q(ctypes.byref(ok), 64, 48, 64) == 0 and q(None, 64, 64, 64) == 0
+
+
 def test_layer_operators_reject_bad_arguments(lib):
     p = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
     assert lib.amxfp4_rmsnorm(None, p, 4, 64, 1e-5, p, None) == -1

@@ -84,6 +84,36 @@ def test_silu_mul_residual_add_merge_heads():
     assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16), L.merge_heads(o, 2, 3, 50, 64))
 
 
+@pytest.mark.parametrize("scale,asym,M,width,K", [(ref.FP8_E5M2, 1, 300, 160, 512), (ref.FP8_E5M2, 0, 40, 96, 256),
+                                                  (ref.FP8_E4M3, 1, 513, 288, 384), (ref.E8M0_FLOOR, 1, 70, 32, 128),
+                                                  (ref.E8M0_FLOOR, 1, 290, 192, 512), (ref.E8M0_FLOOR, 0, 333, 96, 640),
+                                                  (ref.E8M0_ROUND, 0, 257, 64, 96)])
+def test_gemm_with_gated_activation_epilogue(scale, asym, M, width, K):
+    """The gate / up projection with silu(g) * u applied in the GEMM's epilogue: bit-identical to the two calls it
+    replaces whenever those multiply on the same kernel, and equal to the oracle's gated activation of the oracle's
+    product up to the BF16 steps an FP32 accumulation difference can cause."""
+    fmt = binding.make_format(scale, asym)
+    a = synth.activations(M, K, seed=M, n_outlier=1, outlier_gain=30.0)
+    wg, wu = synth.weights(width, K, seed=1), synth.weights(width, K, seed=2)
+    ac, as_ = binding.quantize(fmt, G.to_dev_bf16(a))
+    inter = binding.interleave_gate_up(G.to_dev_bf16(wg), G.to_dev_bf16(wu)).contiguous()
+    ic, is_ = binding.quantize(fmt, inter)
+    got = binding.gemm_silu_mul(fmt, ac, as_, ic, is_)
+    torch.cuda.synchronize()
+    assert tuple(got.shape) == (M, width)
+    got_bits = got.view(torch.int16).cpu().numpy().view(np.uint16)
+    # the same product through the plain GEMM on the panel kernel, then the separate operator
+    cc, cs = binding.quantize(fmt, torch.cat([G.to_dev_bf16(wg), G.to_dev_bf16(wu)], 0).contiguous())
+    need = binding.gemm_silu_mul_workspace_bytes(fmt, M, width, K)
+    if M > 256:  # (with fewer rows the plain GEMM takes the few-rows kernel, whose sums run in another order)
+        two = binding.silu_mul(binding.gemm(fmt, ac, as_, cc, cs))
+        assert torch.equal(two.view(torch.int16), got.view(torch.int16))
+    qa = ref.quantize(a, 32, scale, asym)
+    gu = ref.gemm(*qa, *ref.quantize(np.concatenate([wg, wu], 0), 32, scale, asym), 32, scale, asym)
+    assert_bf16_close(got, L.silu_mul(gu.astype(np.float32)), "gemm_silu_mul")
+    assert got_bits.shape == (M, width) and (need > 0 or scale in (ref.E8M0_FLOOR, ref.E8M0_ROUND))
+
+
 @pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.E8M0_FLOOR, 0)])
 def test_decoder_layer_cut_down(scale, asym, fused):
