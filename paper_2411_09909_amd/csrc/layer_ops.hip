@@ -73,31 +73,36 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* __restrict
   }
 }
 
-// one thread per (token, head, pair i < head_dim / 2)
+// One thread per (token, pair i < head_dim / 2) and chunk of kRopeHeads heads (blockIdx.y): the angle of a pair does
+// not depend on the head, so its FP64 sine and cosine are computed once per thread and reused for the chunk.
+constexpr int kRopeHeads = 8;
 __global__ __launch_bounds__(256) void split_heads_rope_kernel(const float* __restrict__ in, int64_t seq, int64_t ld,
                                                                int64_t col0, int64_t heads, int half, int rotate,
                                                                int64_t pos0, double log_theta,
                                                                uint16_t* __restrict__ out) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t total = seq * heads * half;
-  if (idx >= total) return;
+  if (idx >= seq * half) return;
   const int i = (int)(idx % half);
-  const int64_t h = (idx / half) % heads;
-  const int64_t s = idx / ((int64_t)half * heads);
-  const float* p = in + s * ld + col0 + h * 2 * half;
-  const float x1 = p[i], x2 = p[i + half];
-  float o1 = x1, o2 = x2;
+  const int64_t s = idx / half;
+  double sn = 0.0, cs = 1.0;
   if (rotate) {
     // angle = pos * theta^(-2 i / head_dim), in FP64 so that it does not depend on how the power is evaluated
     const double ang = (double)(pos0 + s) * exp(-log_theta * (double)i / (double)half);
-    double sn, cs;
     sincos(ang, &sn, &cs);
-    o1 = (float)((double)x1 * cs - (double)x2 * sn);
-    o2 = (float)((double)x2 * cs + (double)x1 * sn);
   }
-  uint16_t* q = out + (h * seq + s) * 2 * half;
-  q[i] = (uint16_t)bf16_rne(o1);
-  q[i + half] = (uint16_t)bf16_rne(o2);
+  const int64_t h0 = (int64_t)blockIdx.y * kRopeHeads, h1 = h0 + kRopeHeads < heads ? h0 + kRopeHeads : heads;
+  for (int64_t h = h0; h < h1; ++h) {
+    const float* p = in + s * ld + col0 + h * 2 * half;
+    const float x1 = p[i], x2 = p[i + half];
+    float o1 = x1, o2 = x2;
+    if (rotate) {
+      o1 = (float)((double)x1 * cs - (double)x2 * sn);
+      o2 = (float)((double)x2 * cs + (double)x1 * sn);
+    }
+    uint16_t* q = out + (h * seq + s) * 2 * half;
+    q[i] = (uint16_t)bf16_rne(o1);
+    q[i + half] = (uint16_t)bf16_rne(o2);
+  }
 }
 
 // one block per score row; a thread holds up to kSmMaxChunks runs of 8 columns
@@ -225,9 +230,10 @@ int amxfp4_split_heads_rope(const float* in, int64_t seq, int64_t ld, int64_t co
       ld < col0 + heads * head_dim || pos0 < 0)
     return report_error(AMX_ERR_INVALID_ARG, "split_heads_rope: bad shape");
   if (rotate && !(theta > 1.0)) return report_error(AMX_ERR_INVALID_ARG, "split_heads_rope: theta must exceed 1");
-  const int64_t threads = seq * heads * (head_dim / 2);
-  if (threads > (int64_t)0x7FFFFFFF * 256) return report_error(AMX_ERR_UNSUPPORTED, "split_heads_rope: too large");
-  hipLaunchKernelGGL(split_heads_rope_kernel, dim3(blocks_for(threads)), dim3(256), 0,
+  const int64_t threads = seq * (head_dim / 2), head_chunks = (heads + kRopeHeads - 1) / kRopeHeads;
+  if (threads > (int64_t)0x7FFFFFFF * 256 || head_chunks > 65535)
+    return report_error(AMX_ERR_UNSUPPORTED, "split_heads_rope: too large");
+  hipLaunchKernelGGL(split_heads_rope_kernel, dim3(blocks_for(threads), (unsigned)head_chunks), dim3(256), 0,
                      reinterpret_cast<hipStream_t>(stream), in, seq, ld, col0, heads, (int)(head_dim / 2),
                      (int)(rotate != 0), pos0, rotate ? log(theta) : 0.0, reinterpret_cast<uint16_t*>(out_bf16));
   return done("split_heads_rope launch");
