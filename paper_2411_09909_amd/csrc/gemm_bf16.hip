@@ -254,10 +254,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t*
 #undef AMX_STAGE
 #undef AMX_ISSUE_LOAD
 
-  if constexpr (GLU)
-    store_glu_tiles<FM, FN>(acc, reinterpret_cast<uint16_t*>(C) + b * M * ldc, M, N >> 1, ldc,
+  if constexpr (GLU) {
+    // every wave is past its last fragment read: the operand stages become the waves' transposition space
+    static_assert(glu_stage_bytes<FM, FN>() * ((Cfg::kWaves + 3) / 4) <= Cfg::kStageBytes, "stage too small");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    AMX_BARRIER();
+    const int w = wm * WN + wn;
+    uint8_t* stage = ((w & 3) == 0 ? lds0 : (w & 3) == 1 ? lds1 : (w & 3) == 2 ? lds2 : lds3) +
+                     (w >> 2) * glu_stage_bytes<FM, FN>();
+    store_glu_tiles<FM, FN>(acc, stage, reinterpret_cast<uint16_t*>(C) + b * M * ldc, M, N >> 1, ldc,
                             (int64_t)tm * Cfg::kTileM + wm * FM * 32, (int64_t)tn * Cfg::kTileN + wn * FN * 32);
-  else if constexpr (SCALED)
+  } else if constexpr (SCALED)
     store_c_tiles<FM, FN, 0, true>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * Cfg::kTileM + wm * FM * 32,
                                    (int64_t)tn * Cfg::kTileN + wn * FN * 32, alpha_a[0] * alpha_b[0]);
   else

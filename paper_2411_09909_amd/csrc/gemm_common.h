@@ -99,27 +99,63 @@ __device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[FM][FN], float
 // are interleaved in blocks of 32), and out[row][c] = bf16(silu(gate) * up) for the 32 columns c of each pair, the
 // arithmetic of the separate operator (layer_math.h). out is row-major BF16 with leading dimension ld and n_out
 // columns; col_base is the first (interleaved) column of the wave's tiles, a multiple of 64.
+// A lane holds single elements of 16 rows per tile, which would make 2-byte stores; the wave therefore transposes its
+// result through `stage`, LDS of its own of at least glu_stage_bytes<FM, FN>() bytes (the operand stages, free once
+// every wave of the workgroup is past its last fragment read), and stores 16 bytes per lane, whole rows of the
+// wave's columns at a time. Needs out 16-byte aligned and ld % 8 == 0; otherwise (and for the columns of a partial
+// last chunk) it stores element by element.
 template <int FM, int FN>
-__device__ __forceinline__ void store_glu_tiles(const f32x16 (&acc)[FM][FN], uint16_t* __restrict__ out, int64_t M,
-                                                int64_t n_out, int64_t ld, int64_t row_base, int64_t col_base) {
+constexpr int glu_stage_bytes() {
+  return FM * 32 * ((FN / 2) * 64 + 16);
+}
+
+template <int FM, int FN>
+__device__ __forceinline__ void store_glu_tiles(const f32x16 (&acc)[FM][FN], uint8_t* stage, uint16_t* __restrict__ out,
+                                                int64_t M, int64_t n_out, int64_t ld, int64_t row_base,
+                                                int64_t col_base) {
   static_assert(FN % 2 == 0, "column tiles come in (gate, up) pairs");
+  constexpr int kCols = (FN / 2) * 32, kPitch = kCols * 2 + 16;  // bytes per staged row (padded against bank conflicts)
   const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-  const int64_t col0 = (col_base >> 1) + (lane & 31);
-  // row by row, the pairs of a row one after the other: their 64-byte pieces are neighbours in memory
+  const int64_t col0 = col_base >> 1;
+  const bool wide = (reinterpret_cast<uintptr_t>(out) & 15) == 0 && (ld & 7) == 0 && col0 + kCols <= n_out;
+  if (!wide) {
 #pragma unroll
-  for (int i = 0; i < FM; ++i) {
-    const int64_t row0 = row_base + i * 32 + 4 * (lane >> 5);
+    for (int i = 0; i < FM; ++i) {
+      const int64_t row0 = row_base + i * 32 + 4 * (lane >> 5);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int64_t row = row0 + 8 * (v >> 2) + (v & 3);
-      if (row < M) {
+      for (int v = 0; v < 16; ++v) {
+        const int64_t row = row0 + 8 * (v >> 2) + (v & 3);
+        if (row < M) {
 #pragma unroll
-        for (int j = 0; j < FN; j += 2) {
-          const int64_t col = col0 + (j >> 1) * 32;
-          if (col < n_out) out[row * ld + col] = (uint16_t)bf16_rne(silu_mul_value(acc[i][j][v], acc[i][j + 1][v]));
+          for (int j = 0; j < FN; j += 2) {
+            const int64_t col = col0 + (j >> 1) * 32 + (lane & 31);
+            if (col < n_out) out[row * ld + col] = (uint16_t)bf16_rne(silu_mul_value(acc[i][j][v], acc[i][j + 1][v]));
+          }
         }
       }
     }
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+#pragma unroll
+      for (int j = 0; j < FN; j += 2)
+        *reinterpret_cast<uint16_t*>(stage + r * kPitch + ((j >> 1) * 32 + (lane & 31)) * 2) =
+            (uint16_t)bf16_rne(silu_mul_value(acc[i][j][v], acc[i][j + 1][v]));
+    }
+  // (LDS executes a wave's accesses in order: the reads below see the writes above)
+  constexpr int kChunks = kCols / 8;            // 16-byte chunks per row
+  constexpr int kRowsPerPass = 64 / kChunks;    // rows one store instruction covers
+  const int chunk = lane % kChunks, rsub = lane / kChunks;
+#pragma unroll
+  for (int r0 = 0; r0 < FM * 32; r0 += kRowsPerPass) {
+    const int r = r0 + rsub;
+    const int64_t row = row_base + r;
+    const uint4 val = *reinterpret_cast<const uint4*>(stage + r * kPitch + chunk * 16);
+    if (row < M) *reinterpret_cast<uint4*>(out + row * ld + col0 + chunk * 8) = val;
   }
 }
 

@@ -246,10 +246,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp8m_kernel(const uint8_t* 
 #undef AMX_LOAD_ANCHORS
 #undef AMX_ISSUE_LOAD
 
-  if constexpr (GLU)
-    store_glu_tiles<FM, FN>(acc, reinterpret_cast<uint16_t*>(C) + b * M * ldc, M, N >> 1, ldc,
+  if constexpr (GLU) {
+    // every wave is past its last fragment read: the operand stages become the waves' transposition space
+    static_assert(Cfg::kWaves <= 4 && glu_stage_bytes<FM, FN>() <= Cfg::kStageBytes, "stage too small");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    AMX_BARRIER();
+    const int w = wm * WN + wn;
+    uint8_t* stage = w == 0 ? lds0 : w == 1 ? lds1 : w == 2 ? lds2 : lds3;
+    store_glu_tiles<FM, FN>(acc, stage, reinterpret_cast<uint16_t*>(C) + b * M * ldc, M, N >> 1, ldc,
                             (int64_t)tm * Cfg::kTileM + wm * FM * 32, (int64_t)tn * Cfg::kTileN + wn * FN * 32);
-  else
+  } else
     store_c_tiles<FM, FN>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * Cfg::kTileM + wm * FM * 32,
                           (int64_t)tn * Cfg::kTileN + wn * FN * 32);
 }
