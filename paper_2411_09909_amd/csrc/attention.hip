@@ -143,19 +143,25 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
     /* cast the 32 probabilities of each query as one group and take the dequantized values as BF16. The quotient \
        p / S is taken as p * (1 / S): its error of an ulp or two is that of the hardware exp2 which produced p. */  \
     float S, R;                                                                                                    \
-    (void)encode_scale_sr<SCALE_KIND>(pmax, S, R);                                                                 \
+    if constexpr (SCALE_KIND == kScaleE5M2 || SCALE_KIND == kScaleE4M3) {                                          \
+      fp8_scale_inexact<SCALE_KIND>(pmax, S, R); /* pmax <= 1: no saturation */                                   \
+    } else {                                                                                                       \
+      (void)encode_scale_sr<SCALE_KIND>(pmax, S, R);                                                               \
+    }                                                                                                              \
     uint32_t pb[8];                                                                                                \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
       if constexpr (SCALE_KIND == kScaleE5M2 || SCALE_KIND == kScaleE4M3) {                                        \
-        const uint32_t code =                                                                                      \
-            __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x[2 * i] * R, x[2 * i + 1] * R, 1.0f, 0);                 \
+        /* the conversion replaces byte 0 of its first operand, the only byte read below: any register will do,  \
+           and one that dies here saves the move of a zero */                                                      \
+        const float z0 = x[2 * i] * R, z1 = x[2 * i + 1] * R;                                                      \
+        const uint32_t code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(f2u(z0), z0, z1, 1.0f, 0);                  \
         const f32x2 e = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(code, 1.0f, 0);                                   \
         /* element * scale has at most 6 significant bits: the truncation to BF16 is exact */                     \
         pb[i] = __builtin_amdgcn_perm(f2u(e[1] * S), f2u(e[0] * S), 0x07060302u);                                  \
       } else {                                                                                                     \
         /* a power-of-two scale is applied by the conversions themselves (they read the exponent field of S: the  \
            first divides by it, the second multiplies) */                                                          \
-        const uint32_t code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x[2 * i], x[2 * i + 1], S, 0);          \
+        const uint32_t code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(f2u(x[2 * i]), x[2 * i], x[2 * i + 1], S, 0); \
         pb[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(code, S, 0));               \
       }                                                                                                            \
     }                                                                                                              \

@@ -122,4 +122,24 @@ __device__ __forceinline__ uint32_t encode_scale_r_bf16(float amax, float& R) {
   }
 }
 
+// FP8 scale of a magnitude that is itself only accurate to an ulp or two (a probability out of the hardware exp2):
+// S = the hardware FP8 conversion (nearest, ties to even, subnormals kept) of amax * fl(1/6), R ~ 1 / S (0 when S is
+// 0). amax must be small enough for amax / 6 to be a finite scale (probabilities are at most 1). Against the exact
+// quotient the product is off by one more ulp of FP32, which moves the rounded scale only where the inexact amax
+// already could.
+template <int SCALE_KIND>
+__device__ __forceinline__ void fp8_scale_inexact(float amax, float& S, float& R) {
+  static_assert(SCALE_KIND == kScaleE5M2 || SCALE_KIND == kScaleE4M3, "FP8 scales only");
+  const float q = amax * 0x1.555556p-3f;
+  uint32_t byte;
+  if constexpr (SCALE_KIND == kScaleE5M2) {
+    byte = (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(q, q, 0, false) & 0xFFu;
+    S = (float)__builtin_bit_cast(_Float16, (uint16_t)(byte << 8));
+  } else {
+    byte = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(q, q, 0, false) & 0xFFu;
+    S = (float)__builtin_bit_cast(_Float16, (uint16_t)(byte << 7)) * 256.0f;
+  }
+  R = byte ? __builtin_amdgcn_rcpf(S) : 0.f;
+}
+
 }  // namespace amx
