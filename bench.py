@@ -26,8 +26,8 @@ PEAK_FP8_TFLOPS = 5000.0    # MI355X dense block-scaled FP8 MFMA
 # profiles/gemm_bf16_c3_up_counters.md.
 MEASURED_TRAFFIC_BYTES = 3.43e9  # 2.96 GB fetched + 0.47 GB written
 # the few-rows kernel on c3_70b_up_32tokens_32x8192x28672 (profiles/gemm_skinny_c3_up_32tokens_kernel_trace.md):
-# FETCH_SIZE 152.0 MB + WRITE_SIZE 7.3 MB per launch
-MEASURED_TRAFFIC_FEW_ROWS = 159.3e6
+# FETCH_SIZE 139.8 MB + WRITE_SIZE 3.7 MB per launch
+MEASURED_TRAFFIC_FEW_ROWS = 143.5e6
 
 
 # format name -> (scale kind, asymmetric, MFMA type issued by the GEMM, its dense peak in TFLOP/s)

@@ -15,8 +15,10 @@
 //   FP8-E4M3 scales: FP32 conversion, multiply, truncate to BF16.
 //
 // Work split: one workgroup = 8 (4 with more than four row tiles) waves = neighbouring tiles of 32 columns of C (32
-// rows of B each) over one outer K slice. K is walked in blocks of 256. The workgroup brings the A operand into LDS
-// once, by direct-to-LDS loads, in stages of half a block (a whole block for one or two row tiles), double buffered.
+// rows of B each) over one outer K slice; with a single row tile (M <= 32) two waves share a column tile and take
+// alternate K blocks. K is walked in blocks of 256. The workgroup brings the A operand into LDS
+// once, by direct-to-LDS loads, in stages of half a block (a whole block per wave of a column tile for one or two row
+// tiles), double buffered.
 // Each lane owns half a B row's block: row lane % 32 of its wave's tile, groups 4 h .. 4 h + 3 for lane half
 // h = lane / 32, i.e. 64 contiguous bytes of codes (the two halves of a wave share every 128-byte cache line, fetched
 // once) and 4 scale entries, loaded one block ahead. It then runs the block's 16 k-steps from registers: k-step s
@@ -137,6 +139,14 @@ constexpr int kSkinnyBlockK = 256;  // K block: 128 bytes of codes per row
 // mean less A traffic; with more than four row tiles a wave needs more than the 256 registers an 8-wave workgroup
 // leaves it.
 constexpr int skinny_waves(int row_tiles) { return row_tiles <= 4 ? 8 : 4; }
+// K phases inside a workgroup. With a single row tile a wave holds little (16 accumulators, one block of codes) and
+// two workgroups fit a compute unit: there, two waves share each 32-column tile and take alternate K blocks, and
+// their sums are added through LDS at the end (a fixed order, no further traffic to memory). The same number of
+// waves then needs half the outer K slices (measured, 32 x 28672 x 8192: 43.1 -> 40.2 us for the call, with one
+// slice and no partial tiles instead of two; four phases in workgroups of 16 waves were no faster).
+constexpr int skinny_k_phases(int row_tiles) { return row_tiles == 1 ? 2 : 1; }
+// columns of C a workgroup covers
+constexpr int skinny_cols(int row_tiles) { return 32 * skinny_waves(row_tiles) / skinny_k_phases(row_tiles); }
 
 // Outer K slices for a problem with `groups` workgroups per slice, nblk K blocks and Mp padded rows. A workgroup's
 // time is its number of K blocks; the chip runs 256 workgroups at a time (a second resident workgroup per CU mostly
@@ -187,7 +197,7 @@ static int64_t skinny_panel_rows(int64_t M) {
 
 // bytes of partial tiles one chunk of `rows` rows needs (0 with a single slice)
 static size_t skinny_partial_bytes(int64_t rows, int64_t N, int64_t K, int64_t batch) {
-  const int64_t Mp = 32 * skinny_row_tiles(rows), cols = 32 * skinny_waves(skinny_row_tiles(rows));
+  const int64_t Mp = 32 * skinny_row_tiles(rows), cols = skinny_cols(skinny_row_tiles(rows));
   int bps;
   const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, bps);
   return slices > 1 ? (size_t)(batch * slices * Mp * N * 4) : 0;
@@ -204,7 +214,7 @@ size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batc
   return bytes + partial;
 }
 
-// grid: (ceil(N / (32 * waves)), outer slices, batch); block = skinny_waves(MT) waves.
+// grid: (ceil(N / skinny_cols(MT)), outer slices, batch); block = skinny_waves(MT) waves.
 // (B_codes, B_scales and out are deliberately not declared restrict: loads the compiler knows to be from memory nobody
 // writes may be moved across the barriers, down to their first use, which undoes the prefetch.)
 // out: C (ld_out = ldc) when gridDim.y == 1, else partials [batch][slice][MT * 32][N].
@@ -217,7 +227,10 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(
   // that fill the other stage.
   constexpr int kStageSteps = MT <= 2 ? 16 : 8;
   constexpr int kSkinnyWaves = skinny_waves(MT);
-  constexpr int kFragsPerHalf = MT * kStageSteps;  // A fragments of one stage
+  constexpr int KP = skinny_k_phases(MT);               // waves per column tile; wave (tile ct, phase ph)
+  constexpr int kSubFrags = MT * kStageSteps;           // A fragments of one K block (or half block) of a stage
+  constexpr int kFragsPerHalf = kSubFrags * KP;         // A fragments of one stage: one block per phase
+  static_assert(KP == 1 || kStageSteps == 16, "K phases take whole blocks");
   constexpr bool kF16 = SCALE_KIND == kScaleE5M2;       // FP16 operands biased by 2^-3 each, else BF16
   // two stages, separate arrays so that loads into one are known not to alias reads of the other
   __shared__ __attribute__((aligned(1024))) uint8_t ldsA0[kFragsPerHalf * kFragBytes];
@@ -225,8 +238,9 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int h = lane >> 5;
+  const int ct = wave / KP, ph = wave % KP;
   const int64_t b = blockIdx.z;
-  const int64_t n = ((int64_t)blockIdx.x * kSkinnyWaves + wave) * 32 + (lane & 31);
+  const int64_t n = ((int64_t)blockIdx.x * (kSkinnyWaves / KP) + ct) * 32 + (lane & 31);
   const bool valid = n < N;
   const int64_t G = K >> 5, nblk = K / kSkinnyBlockK;
   constexpr int kScaleBytes = ASYM ? 2 : 1;
@@ -245,6 +259,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(
       const_cast<uint8_t*>(reinterpret_cast<const uint8_t*>(Ap) + b * (int64_t)MT * kfrags * kFragBytes), 0,
       MT * kfrags * kFragBytes, 0x00020000);
   const int lane_off = lane * 16;
+  const int a_off = lane_off + ph * kSubFrags * kFragBytes;  // this wave's block within a stage
   const int first_frag = (int)s_begin * (kSkinnyBlockK / 16);
 
   f32x16 acc[MT];
@@ -253,14 +268,19 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
 
-  // wave w brings fragments w, w + 4, .. of A stage block HB (half or whole K block number HB of this slice) into
-  // stage DST: fragment f = row block f / kStageSteps, k-step f % kStageSteps of the stage block
+  // wave w brings fragments w, w + waves, .. of A stage block HB into stage DST. A stage block is KP consecutive
+  // K blocks of this slice (one per phase; half a block or a whole one when KP is 1); fragment f of the stage =
+  // block f / kSubFrags of them, row block (f % kSubFrags) / kStageSteps, k-step f % kStageSteps. Blocks past the
+  // end of the slice (the last stage block of an odd count) are not loaded and not read.
 #define AMX_SKINNY_LOAD_A(HB, DST)                                                                                 \
   _Pragma("unroll") for (int i_ = 0; i_ < kFragsPerHalf / kSkinnyWaves; ++i_) {                                    \
-    const int f_ = wave + kSkinnyWaves * i_;                                                                       \
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                                      \
-        Ar, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, lane_off,                                                    \
-        ((f_ / kStageSteps) * kfrags + first_frag + (HB) * kStageSteps + (f_ % kStageSteps)) * kFragBytes, 0, 0);  \
+    const int f_ = wave + kSkinnyWaves * i_, sub_ = f_ / kSubFrags, r_ = f_ % kSubFrags;                           \
+    if (KP == 1 || (HB) * KP + sub_ < nb)                                                                          \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                                    \
+          Ar, (lds_ptr_t)((DST) + f_ * kFragBytes), 16, lane_off,                                                  \
+          ((r_ / kStageSteps) * kfrags + first_frag + ((HB) * KP + sub_) * kStageSteps + (r_ % kStageSteps)) *     \
+              kFragBytes,                                                                                          \
+          0, 0);                                                                                                   \
   }
   // this lane's half of its row's cache line of codes (4 groups) and the 4 scale entries of block I
 #define AMX_SKINNY_LOAD_B(I, W, S)                                                                                 \
@@ -280,7 +300,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(
   {                                                                                                                \
     const u32x4 q = dequant_word<SCALE_KIND, ASYM>(WORD, s_pos, s_neg);                                            \
     _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                                            \
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>((SRC) + (mt * kStageSteps + (KF)) * kFragBytes + lane_off); \
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>((SRC) + (mt * kStageSteps + (KF)) * kFragBytes + a_off);   \
       if constexpr (kF16)                                                                                          \
         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),                             \
                                                          __builtin_bit_cast(f16x8, q), acc[mt], 0, 0, 0);          \
@@ -304,7 +324,8 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(
   u32x4 w0[4], w1[4];
   uint32_t s0[2], s1[2];
   AMX_SKINNY_LOAD_A(0, ldsA0);
-  AMX_SKINNY_LOAD_B(0, w0, s0);
+  // (a phase without a first block, in a slice of a single block, loads block 0 and does not use it)
+  AMX_SKINNY_LOAD_B(ph < nb ? ph : 0, w0, s0);
   // The first block's registers are named as used here so that their loads complete in front of the loop: the
   // compiler may otherwise sink them to their first use inside it, where waiting for them means waiting for nearly
   // every load issued since (the next block's among them), in every iteration.
@@ -312,25 +333,31 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(
   AMX_WAIT_VMCNT(0);
   AMX_BARRIER();
   if constexpr (kStageSteps == 16) {
-    // Block i is multiplied from stage i % 2 with the codes in register set i % 2, while the loads of block i + 1
-    // fill the other stage and the other register set; each step ends with a wait and a barrier, after which the
-    // stage it read may be refilled. All conditions are uniform.
-    for (int i = 0; i < nb; i += 2) {
-      if (i + 1 < nb) {
+    // Step i multiplies stage block i (this wave: K block i KP + ph of the slice) from stage i % 2 with the codes in
+    // register set i % 2, while the loads of step i + 1 fill the other stage and the other register set; each step
+    // ends with a wait and a barrier, after which the stage it read may be refilled. All conditions are uniform
+    // over the wave, those around the barriers over the workgroup.
+    const int steps = (nb + KP - 1) / KP;
+    for (int i = 0; i < steps; i += 2) {
+      if (i + 1 < steps) {
         AMX_SKINNY_LOAD_A(i + 1, ldsA1);
-        AMX_SKINNY_LOAD_B(i + 1, w1, s1);
+        if ((i + 1) * KP + ph < nb) AMX_SKINNY_LOAD_B((i + 1) * KP + ph, w1, s1);
       }
-      AMX_SKINNY_HALF0(ldsA0, w0, s0);
-      AMX_SKINNY_HALF1(ldsA0, w0, s0);
+      if (i * KP + ph < nb) {
+        AMX_SKINNY_HALF0(ldsA0, w0, s0);
+        AMX_SKINNY_HALF1(ldsA0, w0, s0);
+      }
       AMX_WAIT_VMCNT(0);
       AMX_BARRIER();
-      if (i + 1 < nb) {
-        if (i + 2 < nb) {
+      if (i + 1 < steps) {
+        if (i + 2 < steps) {
           AMX_SKINNY_LOAD_A(i + 2, ldsA0);
-          AMX_SKINNY_LOAD_B(i + 2, w0, s0);
+          if ((i + 2) * KP + ph < nb) AMX_SKINNY_LOAD_B((i + 2) * KP + ph, w0, s0);
         }
-        AMX_SKINNY_HALF0(ldsA1, w1, s1);
-        AMX_SKINNY_HALF1(ldsA1, w1, s1);
+        if ((i + 1) * KP + ph < nb) {
+          AMX_SKINNY_HALF0(ldsA1, w1, s1);
+          AMX_SKINNY_HALF1(ldsA1, w1, s1);
+        }
         AMX_WAIT_VMCNT(0);
         AMX_BARRIER();
       }
@@ -370,6 +397,28 @@ __global__ __launch_bounds__(64 * skinny_waves(MT)) void gemm_skinny_kernel(
 #undef AMX_SKINNY_LOAD_B
 #undef AMX_SKINNY_LOAD_A
 
+  if constexpr (KP > 1) {
+    // the phases' sums of a column tile, added in ascending phase order through the first stage's memory (every
+    // wave is past the last barrier of the loop, nothing reads the stages any more)
+    static_assert((KP - 1) * (kSkinnyWaves / KP) * MT * 16 * 64 * 4 <= kFragsPerHalf * kFragBytes, "stage too small");
+    float* red = reinterpret_cast<float*>(ldsA0);
+    if (ph != 0) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          red[((((ph - 1) * (kSkinnyWaves / KP) + ct) * MT + mt) * 16 + v) * 64 + lane] = acc[mt][v];
+    }
+    __syncthreads();
+    if (ph != 0) return;
+#pragma unroll
+    for (int p = 1; p < KP; ++p)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          acc[mt][v] += red[((((p - 1) * (kSkinnyWaves / KP) + ct) * MT + mt) * 16 + v) * 64 + lane];
+  }
   // register v of row tile mt is row 32 mt + 8 (v / 4) + 4 h + v % 4, column n
   if (!valid) return;
   float* dst = out + b * batch_stride_out + (int64_t)blockIdx.y * slice_stride_out + n;
@@ -401,7 +450,7 @@ static hipError_t launch_skinny(const uint16_t* Ap, const uint8_t* Bc, const uin
                                 int64_t M, int64_t N, int64_t K, int64_t ldc, int64_t batch, int slices,
                                 int blocks_per_slice, hipStream_t s) {
   const int64_t Mp = MT * 32;
-  constexpr int kWaves = skinny_waves(MT), kCols = 32 * kWaves;
+  constexpr int kWaves = skinny_waves(MT), kCols = skinny_cols(MT);
   const dim3 grid((unsigned)((N + kCols - 1) / kCols), (unsigned)slices, (unsigned)batch);
   if (slices == 1) {
     hipLaunchKernelGGL((gemm_skinny_kernel<SK, ASYM, MT>), grid, dim3(64 * kWaves), 0, s, Ap, Bc, Bs, C, M, N, K, ldc,
@@ -434,7 +483,7 @@ hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t
   // row chunks (one unless M > kSkinnyMaxM, and then batch == 1): rows r0 .. r0 + rows - 1 of A's panel and of C
   for (int64_t r0 = 0; r0 < M; r0 += kSkinnyMaxM) {
     const int64_t rows = M - r0 < kSkinnyMaxM ? M - r0 : kSkinnyMaxM;
-    const int64_t Mp = 32 * skinny_row_tiles(rows), cols = 32 * skinny_waves((int)(Mp / 32));
+    const int64_t Mp = 32 * skinny_row_tiles(rows), cols = skinny_cols((int)(Mp / 32));
     int bps;
     const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, bps);
     const uint16_t* Ac = Ap + r0 * K;  // panel row blocks are contiguous: 32 rows x K values each

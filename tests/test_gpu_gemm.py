@@ -216,13 +216,14 @@ SKINNY_FORMATS = [(ref.FP8_E5M2, 1), (ref.FP8_E5M2, 0), (ref.E8M0_FLOOR, 1), (re
 
 
 @pytest.mark.parametrize("scale,asym", SKINNY_FORMATS)
-@pytest.mark.parametrize("M,N,K", [(1, 1, 256), (7, 31, 512), (32, 100, 2304), (33, 4101, 1024), (64, 1000, 4096),
+@pytest.mark.parametrize("M,N,K", [(1, 1, 256), (7, 31, 512), (32, 100, 2304), (20, 300, 5376), (33, 4101, 1024), (64, 1000, 4096),
                                    (16, 8192, 256), (64, 33, 8192), (65, 300, 512), (96, 129, 1024), (100, 4101, 2304),
                                    (128, 257, 1024), (129, 300, 512), (192, 257, 1024), (200, 129, 256),
                                    (256, 4101, 768)])
 def test_few_rows_against_many_columns(M, N, K, scale, asym):
     """M <= 256 with K a multiple of 256: the kernel that dequantizes B in registers straight from its codes. One to
-    eight row tiles, partial column tiles, one K block per workgroup up to many, with and without outer K slices."""
+    eight row tiles, partial column tiles, one K block per workgroup up to many, with and without outer K slices; up to
+    32 rows, where two waves share a column tile and take alternate K blocks: one block, even and odd counts."""
     a = synth.activations(M, K, seed=M + K, n_outlier=1, outlier_gain=60.0)
     b = synth.weights(N, K, seed=N)
     ac, as_ = ref.quantize(a, 32, scale, asym)
@@ -254,12 +255,14 @@ def test_row_chunks_against_a_large_b(scale, asym, M):
     assert np.isfinite(C).all() and abs(np.abs(C).mean() / np.abs(Cr).mean() - 1) < 0.2
 
 
+@pytest.mark.parametrize("M", [40, 24])
 @pytest.mark.parametrize("asym", [1, 0])
-def test_few_rows_integer_exact_batched_and_repeatable(asym):
+def test_few_rows_integer_exact_batched_and_repeatable(asym, M):
     """Scales 1 and integer codes: exact integers below 2^24 in any summation order, so the result must equal the
-    oracle bit for bit; batch > 1; and two calls give identical bits (the K slices are added in a fixed order)."""
+    oracle bit for bit; batch > 1; and two calls give identical bits (the K slices, and with one row tile the two
+    waves' halves of a slice, are added in a fixed order)."""
     rng = np.random.default_rng(11)
-    batch, M, N, K = 3, 40, 70, 1024
+    batch, N, K = 3, 70, 1024
     mags = np.array([0, 2, 4, 5, 6, 7])
 
     def operand(rows):
