@@ -79,6 +79,21 @@ int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int6
                          const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, void* out_bf16,
                          int64_t ld_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * amxfp4_rmsnorm followed by amxfp4_quantize of its result (Appendix B Algorithm 1 / Sec. 4.2 Eq. 1, as amxfp4_quantize
+ * along the row), in one pass: the normalised BF16 row is cast in registers and never written. Optionally with the
+ * residual addition of amxfp4_residual_add in front: y != NULL adds the FP32 row y to x first, writes the BF16 sum to
+ * sum_out_bf16 (the residual stream a later addition needs) and normalises that sum. codes [rows][dim / 2] and scales
+ * (layout of amxfp4_quantize) come out bit for bit as from the separate calls.
+ *   fmt        group_size 16, 32 or 64 dividing dim (AMX_ERR_UNSUPPORTED otherwise); dim <= 16384
+ *   x_bf16     [rows][dim] BF16, contiguous; y [rows][dim] FP32 or NULL; sum_out_bf16 [rows][dim] BF16, non-NULL
+ *              exactly when y is (it may be x itself: every element is read before it is written, by the same lane)
+ *   weight     [dim] FP32. x, y, sum_out, weight, codes: 16-byte aligned; scales: 4-byte aligned.
+ */
+int amxfp4_rmsnorm_quantize(const amx_format_t* fmt, const void* x_bf16, const float* y, void* sum_out_bf16,
+                            const float* weight, int64_t rows, int64_t dim, float eps, uint8_t* codes, uint8_t* scales,
+                            void* stream);
+
 /* out = bf16( float(x) + y ): x, out [n] BF16, y [n] FP32 (residual connection after a projection). n % 4 == 0. */
 int amxfp4_residual_add(const void* x_bf16, const float* y, int64_t n, void* out_bf16, void* stream);
 

@@ -83,7 +83,8 @@ def load():
                        ("amxfp4_softmax_causal", [vp, i64, i64, i64, f32, vp, vp]),
                        ("amxfp4_silu_mul", [vp, i64, i64, vp, vp]),
                        ("amxfp4_residual_add", [vp, vp, i64, vp, vp]),
-                       ("amxfp4_merge_heads", [vp, i64, i64, i64, i64, vp, vp])):
+                       ("amxfp4_merge_heads", [vp, i64, i64, i64, i64, vp, vp]),
+                       ("amxfp4_rmsnorm_quantize", [fp, vp, vp, vp, vp, i64, i64, f32, vp, vp, vp])):
         getattr(L, name).argtypes = args
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -360,6 +361,26 @@ def rmsnorm(x, weight, eps):
     _check(load().amxfp4_rmsnorm(x.data_ptr(), weight.data_ptr(), x.shape[0], x.shape[1], eps, out.data_ptr(),
                                  _stream()))
     return out
+
+
+def rmsnorm_quantize(fmt, x, weight, eps, y=None):
+    """quantize(fmt, rmsnorm(x, weight, eps)) in one pass; with y (FP32, the shape of x) the residual addition first:
+    returns (codes, scales), or (x + y as BF16, codes, scales) when y is given."""
+    _need_cuda(x, weight)
+    assert x.is_contiguous() and x.dtype == torch.bfloat16 and weight.dtype == torch.float32 and x.dim() == 2
+    rows, dim = x.shape
+    codes = torch.empty((rows, dim // 2), dtype=torch.uint8, device=x.device)
+    shape = (rows, dim // fmt.group_size, 2) if fmt.asymmetric else (rows, dim // fmt.group_size)
+    scales = torch.empty(shape, dtype=torch.uint8, device=x.device)
+    total = None
+    if y is not None:
+        _need_cuda(y)
+        assert y.is_contiguous() and y.dtype == torch.float32 and y.shape == x.shape
+        total = _bf16_out(x.shape, x.device)
+    _check(load().amxfp4_rmsnorm_quantize(ctypes.byref(fmt), x.data_ptr(), y.data_ptr() if y is not None else None,
+                                          total.data_ptr() if y is not None else None, weight.data_ptr(), rows, dim,
+                                          eps, codes.data_ptr(), scales.data_ptr(), _stream()))
+    return (codes, scales) if y is None else (total, codes, scales)
 
 
 def split_heads_rope(proj, col0, heads, head_dim, rotate, pos0=0, theta=10000.0):

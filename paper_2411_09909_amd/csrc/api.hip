@@ -305,6 +305,29 @@ size_t amxfp4_gemm_silu_mul_workspace_bytes(const amx_format_t* fmt, int64_t M, 
   return glu_workspace_bytes(f, M, 2 * width, K);
 }
 
+int amxfp4_rmsnorm_quantize(const amx_format_t* fmt, const void* x_bf16, const float* y, void* sum_out_bf16,
+                            const float* weight, int64_t rows, int64_t dim, float eps, uint8_t* codes, uint8_t* scales,
+                            void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  amx_format_t f = *fmt;
+  if (int rc = check_format(&f)) return rc;
+  if (int rc = check_shape(f, rows, dim)) return rc;
+  if (!amx::rmsnorm_quantize_supported(f.group_size, dim))
+    return fail(AMX_ERR_UNSUPPORTED, "rmsnorm_quantize: groups of 16, 32 or 64 and dim <= 16384 only");
+  if (rows > 0x7FFFFFFF) return fail(AMX_ERR_INVALID_ARG, "rmsnorm_quantize: too many rows");
+  if (!x_bf16 || !weight || !codes || !scales) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
+  if ((y != nullptr) != (sum_out_bf16 != nullptr))
+    return fail(AMX_ERR_INVALID_ARG, "rmsnorm_quantize: y and sum_out_bf16 go together");
+  if (!aligned(x_bf16, 16) || !aligned(weight, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
+      (y && (!aligned(y, 16) || !aligned(sum_out_bf16, 16))))
+    return fail(AMX_ERR_INVALID_ARG, "x, y, sum_out, weight and codes need 16-byte, scales 4-byte alignment");
+  hipError_t e = amx::launch_rmsnorm_quantize(f.scale, f.asymmetric != 0, f.group_size,
+                                              reinterpret_cast<const uint16_t*>(x_bf16), y,
+                                              reinterpret_cast<uint16_t*>(sum_out_bf16), weight, rows, dim, eps, codes,
+                                              scales, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AMX_OK : hip_fail(e, "rmsnorm_quantize launch");
+}
+
 int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K, const uint8_t* A_codes,
                          const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, void* out_bf16,
                          int64_t ld_out, void* workspace, size_t workspace_bytes, void* stream) {

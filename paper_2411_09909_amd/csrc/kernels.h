@@ -69,6 +69,13 @@ hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t
                                   const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
                                   int causal, float* out, void* workspace, hipStream_t s, const KernelTimer& timer);
 
+// layer_ops.hip: RMS normalisation (after an optional residual addition y, whose BF16 sum goes to sum_out) with the
+// cast of the normalised row fused in; groups of 16, 32 or 64 dividing dim <= 16384
+bool rmsnorm_quantize_supported(int64_t group_size, int64_t dim);
+hipError_t launch_rmsnorm_quantize(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, const float* y,
+                                   uint16_t* sum_out, const float* weight, int64_t rows, int64_t dim, float eps,
+                                   uint8_t* codes, uint8_t* scales, hipStream_t s);
+
 // The A panel of the few-rows kernel: 32-long groups, FP16 biased by 2^-3 for FP8-E5M2 scales and BF16 otherwise, the
 // k order within every block of 256 rearranged so that a lane half's 16 k-steps come from one half of the block
 // (gemm_bf16.hip, HALF_LINE). K % 256 == 0.

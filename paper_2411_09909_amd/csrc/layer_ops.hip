@@ -4,6 +4,7 @@
 // BF16) in, BF16 out, FP32 arithmetic, 128-bit accesses.
 #include "../../include/amxfp4.h"
 #include "../../include/amxfp4_layer.h"
+#include "cast_core.h"
 #include "device_formats.h"
 #include "kernels.h"
 #include "layer_math.h"
@@ -69,6 +70,75 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* __restrict
 #pragma unroll
       for (int j = 0; j < 4; ++j) o[j] = pack2(v[c][2 * j] * inv * ww[2 * j], v[c][2 * j + 1] * inv * ww[2 * j + 1]);
       *reinterpret_cast<uint4*>(out + row * dim + (int64_t)ci * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  }
+}
+
+// rmsnorm_kernel with the cast of its result fused in (and, with ADD, the residual addition in front of it): the
+// element-to-lane mapping, the order of the sum of squares and every rounding are those of residual_add_kernel and
+// rmsnorm_kernel, so the BF16 row that is cast here, in registers, is bit for bit the row those two kernels would
+// have written, and the codes and scales are what amxfp4_quantize makes of it (cast_core.h). A group of the cast is
+// 2^lanes_log2 neighbouring lanes of 8 elements each; dim is a multiple of the group size, so the lanes of a group
+// are all inside the row or all outside.
+// (x and sum_out are not declared restrict: they may be the same buffer, each lane reads its elements before it writes
+// them and nobody else touches them)
+template <int SCALE_KIND, bool ASYM, bool ADD>
+__global__ __launch_bounds__(256) void rmsnorm_quantize_kernel(const uint16_t* x, const float* __restrict__ y,
+                                                               uint16_t* sum_out,
+                                                               const float* __restrict__ w, int64_t dim, float eps,
+                                                               int lanes_log2, uint8_t* __restrict__ codes,
+                                                               uint8_t* __restrict__ scales) {
+  __shared__ float red[4];
+  const int64_t row = blockIdx.x;
+  const int chunks = (int)(dim >> 3);
+  float v[kRmsMaxChunks][8];
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < kRmsMaxChunks; ++c) {
+    const int ci = threadIdx.x + 256 * c;
+    if (ci < chunks) {
+      const uint4 u = *reinterpret_cast<const uint4*>(x + row * dim + (int64_t)ci * 8);
+      uint32_t d[4] = {u.x, u.y, u.z, u.w};
+      if constexpr (ADD) {
+        const float4 y0 = *reinterpret_cast<const float4*>(y + row * dim + (int64_t)ci * 8);
+        const float4 y1 = *reinterpret_cast<const float4*>(y + row * dim + (int64_t)ci * 8 + 4);
+        const float yy[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          d[j] = pack2(u2f(d[j] << 16) + yy[2 * j], u2f(d[j] & 0xFFFF0000u) + yy[2 * j + 1]);
+        *reinterpret_cast<uint4*>(sum_out + row * dim + (int64_t)ci * 8) = make_uint4(d[0], d[1], d[2], d[3]);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[c][2 * j] = u2f(d[j] << 16);
+        v[c][2 * j + 1] = u2f(d[j] & 0xFFFF0000u);
+        ss += v[c][2 * j] * v[c][2 * j] + v[c][2 * j + 1] * v[c][2 * j + 1];
+      }
+    }
+  }
+  ss = block_reduce<false>(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)dim + eps);
+  const int64_t groups_per_row = dim >> (lanes_log2 + 3);
+#pragma unroll
+  for (int c = 0; c < kRmsMaxChunks; ++c) {
+    const int ci = threadIdx.x + 256 * c;
+    if (ci < chunks) {
+      const float4 w0 = *reinterpret_cast<const float4*>(w + (int64_t)ci * 8);
+      const float4 w1 = *reinterpret_cast<const float4*>(w + (int64_t)ci * 8 + 4);
+      const float ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+      uint32_t o[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o[j] = pack2(v[c][2 * j] * inv * ww[2 * j], v[c][2 * j + 1] * inv * ww[2 * j + 1]);
+      uint32_t code[1], sb_p, sb_n;
+      cast_words_bf16<SCALE_KIND, ASYM, 8>(o, lanes_log2, code, sb_p, sb_n);
+      *reinterpret_cast<uint32_t*>(codes + row * (dim >> 1) + (int64_t)ci * 4) = code[0];
+      if ((threadIdx.x & ((1 << lanes_log2) - 1)) == 0) {
+        const int64_t g = row * groups_per_row + (ci >> lanes_log2);
+        if constexpr (ASYM)
+          *reinterpret_cast<uint16_t*>(scales + g * 2) = (uint16_t)(sb_p | (sb_n << 8));
+        else
+          scales[g] = (uint8_t)sb_p;
+      }
     }
   }
 }
@@ -205,6 +275,37 @@ int done(const char* what) {
 }
 
 }  // namespace
+
+bool rmsnorm_quantize_supported(int64_t group_size, int64_t dim) {
+  return (group_size == 16 || group_size == 32 || group_size == 64) && dim > 0 && dim % group_size == 0 &&
+         dim <= 256 * 8 * kRmsMaxChunks;
+}
+
+hipError_t launch_rmsnorm_quantize(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, const float* y,
+                                   uint16_t* sum_out, const float* weight, int64_t rows, int64_t dim, float eps,
+                                   uint8_t* codes, uint8_t* scales, hipStream_t s) {
+  if (!rmsnorm_quantize_supported(group_size, dim)) return hipErrorInvalidValue;
+  const int lanes_log2 = group_size == 16 ? 1 : group_size == 32 ? 2 : 3;
+  auto go = [&]<int SK, bool ASYM>() {
+    if (y)
+      hipLaunchKernelGGL((rmsnorm_quantize_kernel<SK, ASYM, true>), dim3((unsigned)rows), dim3(256), 0, s, x, y, sum_out,
+                         weight, dim, eps, lanes_log2, codes, scales);
+    else
+      hipLaunchKernelGGL((rmsnorm_quantize_kernel<SK, ASYM, false>), dim3((unsigned)rows), dim3(256), 0, s, x, y,
+                         sum_out, weight, dim, eps, lanes_log2, codes, scales);
+    return hipGetLastError();
+  };
+  switch (scale_kind) {
+    case kScaleE5M2: return asym ? go.template operator()<kScaleE5M2, true>() : go.template operator()<kScaleE5M2, false>();
+    case kScaleE4M3: return asym ? go.template operator()<kScaleE4M3, true>() : go.template operator()<kScaleE4M3, false>();
+    case kScaleE8M0Floor:
+      return asym ? go.template operator()<kScaleE8M0Floor, true>() : go.template operator()<kScaleE8M0Floor, false>();
+    case kScaleE8M0Round:
+      return asym ? go.template operator()<kScaleE8M0Round, true>() : go.template operator()<kScaleE8M0Round, false>();
+    default: return hipErrorInvalidValue;
+  }
+}
+
 }  // namespace amx
 
 using namespace amx;

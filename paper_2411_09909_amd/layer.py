@@ -45,8 +45,12 @@ class DecoderLayer:
     """weights: dict name -> BF16 CUDA tensor (WEIGHT_SHAPES) plus "norm1" / "norm2" FP32 [d_model]. The weights are
     cast once here (they are static in inference); forward() casts the activations."""
 
-    def __init__(self, cfg, weights, fmt, baseline=False, fused_attention=False, fused_glu=None):
+    def __init__(self, cfg, weights, fmt, baseline=False, fused_attention=False, fused_glu=None, fused_norm=None):
         self.cfg, self.fmt, self.baseline, self.fused_attention = cfg, fmt, baseline, fused_attention
+        # the two normalisations cast their result in registers (and the second adds the residual first): same bits
+        if fused_norm is None:
+            fused_norm = fmt.group_size in (16, 32, 64) and cfg.d_model <= 16384
+        self.fused_norm = fused_norm
         # the gate / up projection with the gated activation in its epilogue (the FP32 product is never written)
         if fused_glu is None:
             fused_glu = cfg.d_ff % 32 == 0
@@ -68,6 +72,10 @@ class DecoderLayer:
             self._ws = torch.empty(need, dtype=torch.uint8, device=a[0].device)
         return binding.gemm(fmt, a[0], a[1], b[0], b[1], workspace=self._ws if need else None, baseline=self.baseline)
 
+    def _plain_fmt(self):
+        """the format for the entry points that have no mxfp4_* twin: symmetric when this layer is the baseline"""
+        return binding.make_format(self.fmt.scale, False, self.fmt.group_size) if self.baseline else self.fmt
+
     def _cast(self, x, k_axis=-1):
         return binding.quantize(self.fmt, x, k_axis=k_axis, baseline=self.baseline)
 
@@ -77,8 +85,10 @@ class DecoderLayer:
         per = c.n_heads // G
         nsc = self.wqkv[1].shape[2:]  # () or (2,): scale entries per group
 
-        h = binding.rmsnorm(x, self.norm1, c.eps)
-        qkv = self._gemm(self._cast(h), self.wqkv)
+        if self.fused_norm:
+            qkv = self._gemm(binding.rmsnorm_quantize(self._plain_fmt(), x, self.norm1, c.eps), self.wqkv)
+        else:
+            qkv = self._gemm(self._cast(binding.rmsnorm(x, self.norm1, c.eps)), self.wqkv)
         q = binding.split_heads_rope(qkv, 0, c.n_heads, D, True, pos0, c.rope_theta)
         k = binding.split_heads_rope(qkv, c.n_heads * D, G, D, True, pos0, c.rope_theta)
         v = binding.split_heads_rope(qkv, (c.n_heads + G) * D, G, D, False)
@@ -116,17 +126,20 @@ class DecoderLayer:
 
     def _after_attention(self, x, attn):
         c = self.cfg
-        x2 = binding.residual_add(x, self._gemm(self._cast(attn), self.wo))
-        h2 = binding.rmsnorm(x2, self.norm2, c.eps)
+        if self.fused_norm:
+            x2, *hc = binding.rmsnorm_quantize(self._plain_fmt(), x, self.norm2, c.eps,
+                                               y=self._gemm(self._cast(attn), self.wo))
+        else:
+            x2 = binding.residual_add(x, self._gemm(self._cast(attn), self.wo))
+            hc = self._cast(binding.rmsnorm(x2, self.norm2, c.eps))
         if self.fused_glu:
-            hc = self._cast(h2)
-            fmt = binding.make_format(self.fmt.scale, False, self.fmt.group_size) if self.baseline else self.fmt
+            fmt = self._plain_fmt()
             need = binding.gemm_silu_mul_workspace_bytes(fmt, hc[0].shape[0], c.d_ff, c.d_model)
             if need and (self._ws is None or self._ws.numel() < need):
                 self._ws = torch.empty(need, dtype=torch.uint8, device=x.device)
             act = binding.gemm_silu_mul(fmt, hc[0], hc[1], self.wgu[0], self.wgu[1], workspace=self._ws)
         else:
-            act = binding.silu_mul(self._gemm(self._cast(h2), self.wgu))
+            act = binding.silu_mul(self._gemm(hc, self.wgu))
         return binding.residual_add(x2, self._gemm(self._cast(act), self.wd))
 
     def matmul_flops(self, S):

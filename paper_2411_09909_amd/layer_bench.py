@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--formats", default=",".join(FORMATS))
     ap.add_argument("--fused-attention", action="store_true",
                     help="one fused attention call instead of Q.K^T, softmax, cast and P.V with a materialised map")
+    ap.add_argument("--separate-norm", action="store_true",
+                    help="residual addition, RMS normalisation and cast as three calls instead of one")
     args = ap.parse_args()
     cfg = layer.LayerConfig()
     dev = torch.device("cuda:0")
@@ -80,7 +82,8 @@ def main():
            "reference_update_mean_square": upd, "formats": {}}
     for name in args.formats.split(","):
         kind, asym = FORMATS[name]
-        lay = layer.DecoderLayer(cfg, w, binding.make_format(kind, asym), fused_attention=args.fused_attention)
+        lay = layer.DecoderLayer(cfg, w, binding.make_format(kind, asym), fused_attention=args.fused_attention,
+                                 fused_norm=False if args.separate_norm else None)
         y = lay.forward(x)  # warm-up, also the output that is compared
         torch.cuda.synchronize()
         t0 = time.perf_counter()

@@ -31,7 +31,8 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"amxfp4_quantize", "amxfp4_dequantize", "amxfp4_gemm", "mxfp4_quantize", "mxfp4_dequantize",
             "mxfp4_gemm", "amxfp4_last_error", "amxfp4_codes_bytes", "amxfp4_scales_bytes",
             "amxfp4_gemm_workspace_bytes", "amxfp4_rmsnorm", "amxfp4_split_heads_rope", "amxfp4_softmax_causal",
-            "amxfp4_silu_mul", "amxfp4_residual_add", "amxfp4_merge_heads"} <= set(names)
+            "amxfp4_silu_mul", "amxfp4_residual_add", "amxfp4_merge_heads", "amxfp4_rmsnorm_quantize",
+            "amxfp4_gemm_silu_mul"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -166,6 +167,23 @@ def test_layer_operators_reject_bad_arguments(lib):
     assert lib.amxfp4_residual_add(p, p, 6, p, None) == -1
     assert lib.amxfp4_merge_heads(p, 2, 2, 8, 6, p, None) == -1
     assert b"merge_heads" in lib.amxfp4_last_error()
+
+
+def test_fused_normalisation_and_cast_rejects_bad_arguments(lib):
+    p = ctypes.c_void_p(4096)
+    q = lib.amxfp4_rmsnorm_quantize
+    f = binding.make_format(binding.FP8_E5M2, True)
+    fr = ctypes.byref(f)
+    assert q(None, p, None, None, p, 4, 4096, 1e-5, p, p, None) == -1
+    assert q(fr, None, None, None, p, 4, 4096, 1e-5, p, p, None) == -1
+    assert q(fr, p, None, None, p, 0, 4096, 1e-5, p, p, None) == -1           # no rows
+    assert q(fr, p, None, None, p, 4, 4080, 1e-5, p, p, None) == -1           # dim % group size
+    assert q(fr, p, None, None, p, 4, 32768, 1e-5, p, p, None) == -2          # dim too large
+    assert q(fr, p, p, None, p, 4, 4096, 1e-5, p, p, None) == -1              # y without sum_out
+    assert q(fr, p, None, p, p, 4, 4096, 1e-5, p, p, None) == -1              # sum_out without y
+    assert q(fr, ctypes.c_void_p(4104), None, None, p, 4, 4096, 1e-5, p, p, None) == -1   # misaligned x
+    g = binding.make_format(binding.FP8_E5M2, True, 128)
+    assert q(ctypes.byref(g), p, None, None, p, 4, 4096, 1e-5, p, p, None) == -2          # groups of 128
 
 
 def test_double_scaling_and_measurement_calls_reject_bad_arguments(lib):

@@ -114,6 +114,42 @@ def test_gemm_with_gated_activation_epilogue(scale, asym, M, width, K):
     assert got_bits.shape == (M, width) and (need > 0 or scale in (ref.E8M0_FLOOR, ref.E8M0_ROUND))
 
 
+@pytest.mark.parametrize("with_residual", [False, True])
+@pytest.mark.parametrize("scale,asym,gs,rows,dim", [(ref.FP8_E5M2, 1, 32, 300, 4096), (ref.FP8_E5M2, 0, 32, 5, 64),
+                                                    (ref.E8M0_FLOOR, 1, 32, 33, 2080), (ref.FP8_E4M3, 1, 16, 40, 4128),
+                                                    (ref.E8M0_ROUND, 0, 64, 9, 16384), (ref.FP8_E5M2, 1, 64, 70, 8192)])
+def test_rmsnorm_with_the_cast_fused_in(scale, asym, gs, rows, dim, with_residual):
+    """RMS normalisation (after an optional residual addition) with the cast of its result in the same kernel. Against
+    the oracle: the normalised row can differ from the oracle's by one BF16 step on a few elements (see above), which changes the codes of those elements and, where it is a
+    group's largest, a scale: codes and scale bytes must agree on all but 1 % of the entries and the dequantized
+    rows to 1 % in norm. Against the three separate calls on the GPU: the same bits everywhere."""
+    rng = np.random.default_rng(rows + dim)
+    x = synth.activations(rows, dim, seed=rows, n_outlier=min(4, dim // 16), outlier_gain=30.0)
+    w = (1 + 0.1 * rng.standard_normal(dim)).astype(np.float32)
+    y = rng.standard_normal((rows, dim)).astype(np.float32) if with_residual else None
+    fmt = binding.make_format(scale, asym, gs)
+    got = binding.rmsnorm_quantize(fmt, G.to_dev_bf16(x), dev_f32(w), 1e-5, y=None if y is None else dev_f32(y))
+    torch.cuda.synchronize()
+    total_bits = x
+    if with_residual:
+        total_bits = L.residual_add(x, y)
+        # (one FP32 addition, then the BF16 rounding: against the oracle's single rounding of the exact sum this is a
+        # double rounding, which moves a result that lands on a BF16 tie, a few elements in a million)
+        assert_bf16_close(got[0], total_bits, "residual sum", max_frac=1e-4)
+        got = got[1:]
+    codes, scales = got[0].cpu().numpy(), got[1].cpu().numpy()
+    wc, ws = ref.quantize(L.rmsnorm(total_bits, w, 1e-5), gs, scale, asym)
+    assert codes.shape == wc.shape and scales.shape == ws.shape
+    nib = lambda c: np.stack([c & 15, c >> 4], -1)  # noqa: E731
+    assert float((nib(codes) != nib(wc)).mean()) <= 1e-2 and float((scales != ws).mean()) <= 1e-2
+    a, b = ref.dequantize(codes, scales, gs, scale, asym), ref.dequantize(wc, ws, gs, scale, asym)
+    assert G.rel_fro(a, b) <= 1e-2
+    # the separate operators
+    base = G.to_dev_bf16(x) if y is None else binding.residual_add(G.to_dev_bf16(x), dev_f32(y))
+    sc, ss = binding.quantize(fmt, binding.rmsnorm(base, dev_f32(w), 1e-5))
+    assert torch.equal(sc, got[0]) and torch.equal(ss, got[1])
+
+
 @pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.E8M0_FLOOR, 0)])
 def test_decoder_layer_cut_down(scale, asym, fused):
