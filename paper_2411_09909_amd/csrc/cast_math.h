@@ -83,7 +83,8 @@ __device__ __forceinline__ float quotient(float x, float S, float R) {
 //    subnormals kept) then rounds as the real quotient would be rounded.
 //  - element: an E2M1 boundary b times the scale has at most 7 significant bits, so x != b S implies
 //    |x / S - b| >= 2^-9 b. The product x * R with R = rcp(S) (relative error below 2^-21), rounded to binary16
-//    (11 significant bits), keeps its side of every boundary and is b exactly when x / S is; see encode8().
+//    (11 significant bits), keeps its side of every boundary and is b exactly when x / S is; see encode8_bf16()
+//    in cast_core.h.
 
 typedef float float2v __attribute__((ext_vector_type(2)));
 

@@ -1,7 +1,7 @@
 """The cast kernel's arithmetic for BF16 inputs, modelled step by step in NumPy float32 and checked against the
 oracle on every input: the GPU kernel does not divide exactly, it multiplies by reciprocals and snaps, and the claim
 is that this decides every scale byte and every E2M1 code as exact arithmetic does (Appendix B Algorithm 1 with the
-FP8 scale of Sec. 4.2). The model below follows csrc/cast_math.h (fp8_scale_bf16) and csrc/cast.hip (encode8_bf16):
+FP8 scale of Sec. 4.2). The model below follows csrc/cast_math.h (fp8_scale_bf16) and csrc/cast_core.h (encode8_bf16):
 
   scale:    q0 = fl32(amax * fl32(1/6)); snap q0 to 13 significant bits (integer add 0x400, mask); clamp to the
             largest finite scale; round to the FP8 grid (nearest, ties to even, subnormals kept);
