@@ -89,13 +89,17 @@ def measured_peaks(binding, torch, xd, wd, dev, iterations=30000):
 
     operands = {
         "bf16": lanes(xh.view(torch.uint8), wh.view(torch.uint8), 16),
+        # the same values in FP16, each operand biased by 2^-3 as the kernels that use the FP16 MFMA hold them
+        "f16": lanes((xh.float() * 0.125).to(torch.float16).view(torch.uint8),
+                     (wh.float() * 0.125).to(torch.float16).view(torch.uint8), 16),
         "fp8": lanes(xh.to(torch.float8_e5m2).view(torch.uint8), wh.to(torch.float8_e5m2).view(torch.uint8), 32),
         "fp4": lanes(xc.flatten(), wc.flatten(), 16),
     }
     zeros = torch.zeros((256, 64), dtype=torch.uint8, device=dev)
     sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
     res = {"unit": "TFLOP/s", "mfma_loop": {}}
-    for kind, datasheet in (("bf16", PEAK_BF16_TFLOPS), ("fp8", PEAK_FP8_TFLOPS), ("fp4", PEAK_FP4_TFLOPS)):
+    for kind, datasheet in (("bf16", PEAK_BF16_TFLOPS), ("f16", PEAK_BF16_TFLOPS), ("fp8", PEAK_FP8_TFLOPS),
+                            ("fp4", PEAK_FP4_TFLOPS)):
         row = {"datasheet": datasheet}
         for label, op in (("zero_operands", zeros), ("workload_operands", operands[kind])):
             binding.peak_mfma(kind, op, 200, sink)  # module load, not timed

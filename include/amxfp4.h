@@ -247,7 +247,8 @@ int amxfp4_select_pot_kernel(int32_t which);
  * amxfp4_peak_mfma runs a register-resident loop of matrix instructions (512 workgroups of 4 waves, 16 independent
  * 32x32 accumulator tiles per wave, `iterations` rounds, no memory traffic inside the loop) and writes the number of
  * floating-point operations it performs to the HOST double *flops; the caller times the call on `stream`.
- *   mfma       0 = BF16 32x32x16, 1 = block-scaled FP8 (E5M2) 32x32x64, 2 = block-scaled FP4 32x32x64 (unit scales).
+ *   mfma       0 = BF16 32x32x16, 1 = block-scaled FP8 (E5M2) 32x32x64, 2 = block-scaled FP4 32x32x64 (unit scales),
+ *              3 = FP16 32x32x16.
  *   operand    device, 16384 bytes, 16-byte aligned: lane t of a workgroup takes bytes 64t .. 64t+31 as its A and
  *              64t+32 .. 64t+63 as its B operand registers (BF16 and FP4 use the first 16 of each). The sustained
  *              rate depends on these bits (clock management), so pass zeros for the best case and a slice of a real

@@ -144,7 +144,7 @@ def select_pot_kernel(which):
     _check(load().amxfp4_select_pot_kernel(POT_KERNELS.get(which, which)))
 
 
-PEAK_MFMA = {"bf16": 0, "fp8": 1, "fp4": 2}
+PEAK_MFMA = {"bf16": 0, "fp8": 1, "fp4": 2, "f16": 3}
 
 
 def peak_mfma(mfma, operand, iterations, sink):
