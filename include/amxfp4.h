@@ -209,6 +209,16 @@ int amxfp4_attention(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads,
                      int32_t causal, float* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * amxfp4_attention with the output rounded to BF16 (nearest even) and written token-major: out_bf16 [Sq][q_heads *
+ * head_dim] BF16 bit patterns, head h in columns h * head_dim .. — the operand of the output projection's cast, bit
+ * for bit what amxfp4_merge_heads (amxfp4_layer.h) makes of amxfp4_attention's FP32 result. Everything else as above.
+ */
+int amxfp4_attention_merged(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq, int64_t Sk,
+                            int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
+                            const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
+                            int32_t causal, void* out_bf16, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid (not part of the method): arms a pair of caller-owned hipEvent_t (passed as void*) for the NEXT
  * amxfp4_gemm / mxfp4_gemm call made on this host thread. That call records `start` on its stream immediately before
  * and `stop` immediately after the launch of its matrix-multiply kernel (the MFMA main loop, excluding the operand

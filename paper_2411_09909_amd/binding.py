@@ -74,6 +74,8 @@ def load():
     L.amxfp4_attention.argtypes = [fp, i64, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, f32, i32, vp, vp,
                                    ctypes.c_size_t, vp]
     L.amxfp4_attention.restype = ctypes.c_int
+    L.amxfp4_attention_merged.argtypes = L.amxfp4_attention.argtypes
+    L.amxfp4_attention_merged.restype = ctypes.c_int
     L.amxfp4_peak_mfma.argtypes = [i32, vp, i32, vp, ctypes.POINTER(f64), vp]
     L.amxfp4_peak_mfma.restype = ctypes.c_int
     L.amxfp4_peak_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
@@ -324,9 +326,10 @@ def attention_workspace_bytes(fmt, q_heads, kv_heads, Sq, Sk, head_dim=128):
 
 
 def attention(fmt, q_codes, q_scales, k_codes, k_scales, v_codes, v_scales, scale, causal=True, out=None,
-              workspace=None):
+              workspace=None, merged=False):
     """Fused quantized attention. q_codes [Hq, Sq, D/2], k_codes [Hkv, Sk, D/2] (cast along D), v_codes
-    [Hkv, D, Sk/2] (each head's V cast along the keys, k_axis=0), scales to match. Returns FP32 [Hq, Sq, D]."""
+    [Hkv, D, Sk/2] (each head's V cast along the keys, k_axis=0), scales to match. Returns FP32 [Hq, Sq, D], or with
+    merged=True the same values as BF16 [Sq, Hq * D] (token-major, heads side by side)."""
     ts = (q_codes, q_scales, k_codes, k_scales, v_codes, v_scales)
     _need_cuda(*ts)
     for t in ts:
@@ -335,15 +338,18 @@ def attention(fmt, q_codes, q_scales, k_codes, k_scales, v_codes, v_scales, scal
     Hkv, Sk = k_codes.shape[0], k_codes.shape[1]
     assert k_codes.shape[2] * 2 == D and tuple(v_codes.shape) == (Hkv, D, Sk // 2)
     if out is None:
-        out = torch.empty((Hq, Sq, D), dtype=torch.float32, device=q_codes.device)
+        out = (_bf16_out((Sq, Hq * D), q_codes.device) if merged
+               else torch.empty((Hq, Sq, D), dtype=torch.float32, device=q_codes.device))
+    assert out.is_contiguous() and out.dtype == (torch.bfloat16 if merged else torch.float32)
     need = attention_workspace_bytes(fmt, Hq, Hkv, Sq, Sk, D)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q_codes.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(load().amxfp4_attention(ctypes.byref(fmt), Hq, Hkv, Sq, Sk, D, q_codes.data_ptr(), q_scales.data_ptr(),
-                                   k_codes.data_ptr(), k_scales.data_ptr(), v_codes.data_ptr(), v_scales.data_ptr(),
-                                   float(scale), int(bool(causal)), out.data_ptr(), ws_ptr, ws_len, _stream()))
+    call = load().amxfp4_attention_merged if merged else load().amxfp4_attention
+    _check(call(ctypes.byref(fmt), Hq, Hkv, Sq, Sk, D, q_codes.data_ptr(), q_scales.data_ptr(), k_codes.data_ptr(),
+                k_scales.data_ptr(), v_codes.data_ptr(), v_scales.data_ptr(), float(scale), int(bool(causal)),
+                out.data_ptr(), ws_ptr, ws_len, _stream()))
     return out
 
 

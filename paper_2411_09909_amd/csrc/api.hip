@@ -451,10 +451,11 @@ size_t amxfp4_attention_workspace_bytes(const amx_format_t* fmt, int64_t q_heads
   return amx::attention_workspace_bytes(q_heads, kv_heads, Sq, Sk);
 }
 
-int amxfp4_attention(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq, int64_t Sk,
+static int attention_impl(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq, int64_t Sk,
                      int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
                      const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
-                     int32_t causal, float* out, void* workspace, size_t workspace_bytes, void* stream) {
+                     int32_t causal, void* out, bool merged_bf16, void* workspace, size_t workspace_bytes,
+                          void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
   if (int rc = check_format(fmt)) return rc;
   if (fmt->group_size != 32) return fail(AMX_ERR_UNSUPPORTED, "the fused attention takes groups of 32 (one group per key tile)");
@@ -478,9 +479,25 @@ int amxfp4_attention(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads,
   const amx::KernelTimer timer = g_timer;
   g_timer = amx::KernelTimer();
   hipError_t e = amx::launch_attention_fused(fmt->scale, fmt->asymmetric != 0, q_heads, kv_heads, Sq, Sk, Q_codes,
-                                             Q_scales, K_codes, K_scales, V_codes, V_scales, scale, causal, out,
-                                             workspace, reinterpret_cast<hipStream_t>(stream), timer);
+                                             Q_scales, K_codes, K_scales, V_codes, V_scales, scale, causal,
+                                             reinterpret_cast<float*>(out), merged_bf16, workspace, reinterpret_cast<hipStream_t>(stream), timer);
   return e == hipSuccess ? AMX_OK : hip_fail(e, "attention launch");
+}
+
+int amxfp4_attention(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq, int64_t Sk,
+                     int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
+                     const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
+                     int32_t causal, float* out, void* workspace, size_t workspace_bytes, void* stream) {
+  return attention_impl(fmt, q_heads, kv_heads, Sq, Sk, head_dim, Q_codes, Q_scales, K_codes, K_scales, V_codes,
+                        V_scales, scale, causal, out, false, workspace, workspace_bytes, stream);
+}
+
+int amxfp4_attention_merged(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq, int64_t Sk,
+                            int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
+                            const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
+                            int32_t causal, void* out_bf16, void* workspace, size_t workspace_bytes, void* stream) {
+  return attention_impl(fmt, q_heads, kv_heads, Sq, Sk, head_dim, Q_codes, Q_scales, K_codes, K_scales, V_codes,
+                        V_scales, scale, causal, out_bf16, true, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -34,7 +34,8 @@ static_assert(kAttnKFrags == kAttnVFrags && kAttnKFrags % kAttnWaves == 0, "frag
 template <int SCALE_KIND>
 __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
     const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Kp, const uint16_t* __restrict__ Vp,
-    float* __restrict__ out, int Sq, int Sk, int Sqp, int Skv, int kv_group, float scale_log2, int causal) {
+    float* __restrict__ out, int Sq, int Sk, int Sqp, int Skv, int kv_group, float scale_log2, int causal,
+    int merged_bf16) {
   // two stages of (K tile, V tile), separate arrays so that loads into one stage are known not to alias reads of the
   // other
   __shared__ __attribute__((aligned(1024))) uint8_t ldsK0[kAttnKFrags * kFragBytes];
@@ -198,9 +199,20 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
 #undef AMX_ATTN_TILE
 #undef AMX_ATTN_LOAD
 
-  // out[h][query][d] = O^T[d][query] / l; register 4c + r of row block db is d = 32 db + 8 c + 4 (lane / 32) + r
+  // out[h][query][d] = O^T[d][query] / l; register 4c + r of row block db is d = 32 db + 8 c + 4 (lane / 32) + r.
+  // merged_bf16: the same values rounded to BF16 and written token-major, out[query][h * D + d] (the layout the output
+  // projection's cast reads: no head-merge pass over an FP32 copy).
   const int q = qw + (lane & 31);
-  if (wave_active && q < Sq) {
+  if (wave_active && q < Sq && merged_bf16) {
+    const float inv = 1.0f / l;
+    uint16_t* dst = reinterpret_cast<uint16_t*>(out) + ((int64_t)q * nheads + h) * kAttnD + row_in_tile;
+#pragma unroll
+    for (int db = 0; db < kAttnD / 32; ++db)
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        *reinterpret_cast<uint2*>(dst + db * 32 + c * 8) = make_uint2(
+            pack2(o[db][4 * c] * inv, o[db][4 * c + 1] * inv), pack2(o[db][4 * c + 2] * inv, o[db][4 * c + 3] * inv));
+  } else if (wave_active && q < Sq) {
     const float inv = 1.0f / l;
     float* dst = out + ((int64_t)h * Sq + q) * kAttnD + row_in_tile;
 #pragma unroll
@@ -220,18 +232,21 @@ size_t attention_workspace_bytes(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk
 
 template <int SK>
 static hipError_t launch_attn(const uint16_t* Qp, const uint16_t* Kp, const uint16_t* Vp, float* out, int64_t Hq,
-                              int64_t Hkv, int64_t Sq, int64_t Sk, float scale, int causal, hipStream_t s) {
+                              int64_t Hkv, int64_t Sq, int64_t Sk, float scale, int causal, int merged_bf16,
+                              hipStream_t s) {
   const int64_t Sqp = round_up(Sq, 32);
   const dim3 grid((unsigned)Hq, (unsigned)((Sqp + kAttnQ - 1) / kAttnQ));
   hipLaunchKernelGGL((attention_fused_kernel<SK>), grid, dim3(64 * kAttnWaves), 0, s, Qp, Kp, Vp, out, (int)Sq,
-                     (int)Sk, (int)Sqp, (int)round_up(Sk, 64), (int)(Hq / Hkv), scale * 1.4426950408889634f, causal);
+                     (int)Sk, (int)Sqp, (int)round_up(Sk, 64), (int)(Hq / Hkv), scale * 1.4426950408889634f, causal,
+                     merged_bf16);
   return hipGetLastError();
 }
 
 hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk,
                                   const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
                                   const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
-                                  int causal, float* out, void* workspace, hipStream_t s, const KernelTimer& timer) {
+                                  int causal, float* out, bool merged_bf16, void* workspace, hipStream_t s,
+                                  const KernelTimer& timer) {
   const int64_t Sqp = round_up(Sq, 32);
   uint16_t* Qp = reinterpret_cast<uint16_t*>(workspace);
   uint16_t* Kp = Qp + Hq * Sqp * kAttnD;
@@ -245,10 +260,10 @@ hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t
   if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
   switch (scale_kind) {
-    case kScaleE5M2: e = launch_attn<kScaleE5M2>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, s); break;
-    case kScaleE4M3: e = launch_attn<kScaleE4M3>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, s); break;
-    case kScaleE8M0Floor: e = launch_attn<kScaleE8M0Floor>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, s); break;
-    case kScaleE8M0Round: e = launch_attn<kScaleE8M0Round>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, s); break;
+    case kScaleE5M2: e = launch_attn<kScaleE5M2>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
+    case kScaleE4M3: e = launch_attn<kScaleE4M3>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
+    case kScaleE8M0Floor: e = launch_attn<kScaleE8M0Floor>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
+    case kScaleE8M0Round: e = launch_attn<kScaleE8M0Round>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;

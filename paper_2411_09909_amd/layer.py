@@ -101,10 +101,11 @@ class DecoderLayer:
             need = binding.attention_workspace_bytes(fmt, c.n_heads, G, S, S, D)
             if self._ws is None or self._ws.numel() < need:
                 self._ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+            # (the kernel writes its output merged and in BF16: what merge_heads would make of the FP32 result)
             o = binding.attention(fmt, qc.view(c.n_heads, S, D // 2), qs.view(c.n_heads, S, D // 32, *nsc),
                                   kc.view(G, S, D // 2), ks.view(G, S, D // 32, *nsc), vc, vs, 1.0 / math.sqrt(D),
-                                  True, workspace=self._ws)
-            return self._after_attention(x, binding.merge_heads(o.view(G, per * S, D), G, per, S, D))
+                                  True, workspace=self._ws, merged=True)
+            return self._after_attention(x, o)
         scores = self._gemm((qc.view(G, per * S, D // 2), qs.view(G, per * S, D // 32, *nsc)),
                             (kc.view(G, S, D // 2), ks.view(G, S, D // 32, *nsc)))
         p = binding.softmax_causal(scores, 1.0 / math.sqrt(D))

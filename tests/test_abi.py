@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported(lib):
             "mxfp4_gemm", "amxfp4_last_error", "amxfp4_codes_bytes", "amxfp4_scales_bytes",
             "amxfp4_gemm_workspace_bytes", "amxfp4_rmsnorm", "amxfp4_split_heads_rope", "amxfp4_softmax_causal",
             "amxfp4_silu_mul", "amxfp4_residual_add", "amxfp4_merge_heads", "amxfp4_rmsnorm_quantize",
-            "amxfp4_gemm_silu_mul"} <= set(names)
+            "amxfp4_gemm_silu_mul", "amxfp4_attention", "amxfp4_attention_merged"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 

@@ -82,6 +82,29 @@ def test_closed_forms_on_the_gpu():
     compare(gpu_attention(q, k, v, D ** -0.5, True, ref.FP8_E5M2, 1), want)
 
 
+@pytest.mark.parametrize("Hq,Hkv,Sq,Sk,causal", [(8, 2, 300, 320, True), (3, 3, 33, 64, False)])
+def test_merged_bf16_output(Hq, Hkv, Sq, Sk, causal):
+    """amxfp4_attention_merged: the same kernel writing BF16 token-major; bit for bit the head merge of the FP32 result
+    (which the tests above compare with the oracle)."""
+    q, k, v = heads(Hq, Sq, 21), heads(Hkv, Sk, 22), heads(Hkv, Sk, 23)
+    fmt = binding.make_format(ref.FP8_E5M2, 1, 32)
+    qc, qs = binding.quantize(fmt, G.to_dev_bf16(q.reshape(Hq * Sq, D)))
+    kc, ks = binding.quantize(fmt, G.to_dev_bf16(k.reshape(Hkv * Sk, D)))
+    vc, vs = binding.quantize_batched(fmt, G.to_dev_bf16(v.reshape(Hkv * Sk, D)).view(Hkv, Sk, D), k_axis=1)
+    args = (fmt, qc.view(Hq, Sq, -1), qs.view(Hq, Sq, D // 32, 2), kc.view(Hkv, Sk, -1), ks.view(Hkv, Sk, D // 32, 2),
+            vc, vs, D ** -0.5, causal)
+    plain = binding.attention(*args)
+    merged = binding.attention(*args, merged=True)
+    torch.cuda.synchronize()
+    assert tuple(merged.shape) == (Sq, Hq * D) and merged.dtype == torch.bfloat16
+    want = binding.merge_heads(plain.view(Hq, Sq, D), Hq, 1, Sq, D)
+    assert torch.equal(merged.view(torch.int16), want.view(torch.int16))
+    # and against the oracle directly, rounded the same way
+    ora = attention_ref.fused_attention(q, k, v, D ** -0.5, causal)
+    got = merged.float().cpu().numpy().reshape(Sq, Hq, D).transpose(1, 0, 2)
+    assert G.rel_fro(got, ora) <= 5e-3   # BF16 rounding of the output on top of the kernel's tolerance
+
+
 def test_causality_on_the_gpu():
     """Changing keys and values after position 40 leaves the output rows before 32 bit-identical (rows 32..39 share
     their V group with the changed rows)."""
