@@ -199,13 +199,13 @@ def main():
             mfma, peak, e5m2_kernel = "bf16", PEAK_BF16_TFLOPS, "panel"
         if kind == 2 and e5m2_kernel != "panel":
             mfma = "f16"
-        binding.select_e5m2_kernel(e5m2_kernel)
+        opts = None if scaled else binding.gemm_options(e5m2_kernel=e5m2_kernel)
         fmt = binding.make_format(kind, asym, gs)
         nsc = (M, K // gs, 2) if asym else (M, K // gs)
         xc = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
         xs = torch.empty(nsc, dtype=torch.uint8, device=dev)
         need = (binding.load().amxfp4_gemm_scaled_workspace_bytes(ctypes.byref(fmt), M, N, K, 1) if scaled
-                else binding.gemm_workspace_bytes(fmt, M, N, K))
+                else binding.gemm_workspace_bytes(fmt, M, N, K, options=opts))
         ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else None
         xp = torch.empty(2, dtype=torch.float32, device=dev) if scaled else None
 
@@ -226,7 +226,7 @@ def main():
             cast_x()
             if pair is not None:
                 binding.profile_next_gemm(pair[0], pair[1])
-            binding.gemm(fmt, xc, xs, wc, wsc, out=C, workspace=ws, a_pair=xp, b_pair=wp)
+            binding.gemm(fmt, xc, xs, wc, wsc, out=C, workspace=ws, a_pair=xp, b_pair=wp, options=opts)
 
         for _ in range(warmup):
             step()
@@ -245,7 +245,6 @@ def main():
             cast_x()
         torch.cuda.synchronize()
         t_cast_x = (time.perf_counter() - t0) / steps
-        binding.select_e5m2_kernel("panel")
         return {"t_step": t_total / steps, "kern_ms": kern_ms, "t_cast_x": t_cast_x, "t_cast_w": t_cast_w,
                 "mfma": mfma, "peak": peak, "asym": asym, "workspace_bytes": need}
 

@@ -20,6 +20,11 @@ class AmxFormat(ctypes.Structure):
                 ("asymmetric", ctypes.c_int32)]
 
 
+class AmxGemmOptions(ctypes.Structure):
+    _fields_ = [("e5m2_kernel", ctypes.c_int32), ("pot_kernel", ctypes.c_int32), ("tile", ctypes.c_int32),
+                ("few_rows", ctypes.c_int32)]
+
+
 class AmxError(RuntimeError):
     pass
 
@@ -56,10 +61,11 @@ def load():
     L.amxfp4_quantize_batched.restype = ctypes.c_int
     L.amxfp4_profile_next_gemm.argtypes = [vp, vp]
     L.amxfp4_profile_next_gemm.restype = ctypes.c_int
-    L.amxfp4_select_e5m2_kernel.argtypes = [ctypes.c_int32]
-    L.amxfp4_select_e5m2_kernel.restype = ctypes.c_int
-    L.amxfp4_select_pot_kernel.argtypes = [ctypes.c_int32]
-    L.amxfp4_select_pot_kernel.restype = ctypes.c_int
+    op = ctypes.POINTER(AmxGemmOptions)
+    L.amxfp4_gemm_workspace_bytes_ex.argtypes = [fp, op, i64, i64, i64, i64]
+    L.amxfp4_gemm_workspace_bytes_ex.restype = ctypes.c_size_t
+    L.amxfp4_gemm_ex.argtypes = [fp, op, i64, i64, i64, vp, vp, vp, vp, vp, i64, i64, vp, ctypes.c_size_t, vp]
+    L.amxfp4_gemm_ex.restype = ctypes.c_int
     f32, f64, i32 = ctypes.c_float, ctypes.c_double, ctypes.c_int32
     L.amxfp4_tensor_scale.argtypes = [vp, i64, i64, i64, vp, vp]
     L.amxfp4_quantize_scaled.argtypes = [fp, vp, i64, i64, i64, i64, vp, vp, vp, vp]
@@ -120,30 +126,27 @@ def scales_bytes(fmt, rows, K):
     return load().amxfp4_scales_bytes(ctypes.byref(fmt), rows, K)
 
 
-def gemm_workspace_bytes(fmt, M, N, K, batch=1):
-    return load().amxfp4_gemm_workspace_bytes(ctypes.byref(fmt), M, N, K, batch)
+E5M2_KERNELS = {"panel": 0, "hybrid": 1, "fused": 2}
+POT_KERNELS = {"merged": 0, "split": 1}
+TILES = {"auto": 0, "256x256": 1, "256x128": 2, "64x256": 3}
+
+
+def gemm_options(e5m2_kernel="panel", pot_kernel="merged", tile="auto", few_rows=0):
+    """The per-call kernel choice of amxfp4_gemm_ex (names or the header's integers); few_rows: 0 = where it applies,
+    -1 = never, n > 0 = with n outer K slices."""
+    return AmxGemmOptions(E5M2_KERNELS.get(e5m2_kernel, e5m2_kernel), POT_KERNELS.get(pot_kernel, pot_kernel),
+                          TILES.get(tile, tile), int(few_rows))
+
+
+def gemm_workspace_bytes(fmt, M, N, K, batch=1, options=None):
+    if options is None:
+        return load().amxfp4_gemm_workspace_bytes(ctypes.byref(fmt), M, N, K, batch)
+    return load().amxfp4_gemm_workspace_bytes_ex(ctypes.byref(fmt), ctypes.byref(options), M, N, K, batch)
 
 
 def profile_next_gemm(start_event, stop_event):
     """Arms raw hipEvent_t handles (ints) around the matrix-multiply kernel of the next gemm() call."""
     _check(load().amxfp4_profile_next_gemm(start_event, stop_event))
-
-
-E5M2_KERNELS = {"panel": 0, "hybrid": 1, "fused": 2}
-
-
-def select_e5m2_kernel(which):
-    """Chooses among the three GEMM kernels for FP8-E5M2 scales ("panel" | "hybrid" | "fused", or 0 | 1 | 2);
-    process-wide, also changes gemm_workspace_bytes."""
-    _check(load().amxfp4_select_e5m2_kernel(E5M2_KERNELS.get(which, which)))
-
-
-POT_KERNELS = {"merged": 0, "split": 1}
-
-
-def select_pot_kernel(which):
-    """Chooses between the two GEMM kernels for asymmetric power-of-two scales ("merged" | "split", or 0 | 1)."""
-    _check(load().amxfp4_select_pot_kernel(POT_KERNELS.get(which, which)))
 
 
 PEAK_MFMA = {"bf16": 0, "fp8": 1, "fp4": 2, "f16": 3}
@@ -289,9 +292,10 @@ def dequantize(fmt, codes, scales, out_dtype=torch.float32, baseline=False, tens
 
 
 def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, baseline=False, a_pair=None,
-         b_pair=None):
+         b_pair=None, options=None):
     """a_codes [M, K/2] or [batch, M, K/2]; b_codes [N, K/2] or [batch, N, K/2] (contiguous). a_pair / b_pair: the
-    operands' tensor_scale() results (both or neither). Returns FP32 C."""
+    operands' tensor_scale() results (both or neither). options: gemm_options() for amxfp4_gemm_ex. out: FP32
+    [.., M, ldc >= N] with contiguous rows. Returns FP32 C."""
     _need_cuda(a_codes, a_scales, b_codes, b_scales)
     batched = a_codes.dim() == 3
     batch = a_codes.shape[0] if batched else 1
@@ -304,8 +308,10 @@ def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, ba
     scaled = a_pair is not None or b_pair is not None
     if scaled and (a_pair is None or b_pair is None or baseline):
         raise AmxError("the scaled GEMM needs both tensor-scale pairs and has no mxfp4_* twin")
+    if options is not None and (scaled or baseline):
+        raise AmxError("kernel options go with the plain amxfp4_gemm only (clear fmt.asymmetric for the baseline)")
     need = (load().amxfp4_gemm_scaled_workspace_bytes(ctypes.byref(fmt), M, N, K, batch) if scaled
-            else gemm_workspace_bytes(fmt, M, N, K, batch))
+            else gemm_workspace_bytes(fmt, M, N, K, batch, options))
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
@@ -314,6 +320,11 @@ def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, ba
         _check(load().amxfp4_gemm_scaled(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
                                          _pair_ptr(a_pair), b_codes.data_ptr(), b_scales.data_ptr(), _pair_ptr(b_pair),
                                          out.data_ptr(), out.stride(-2), batch, ws_ptr, ws_len, _stream()))
+        return out
+    if options is not None:
+        _check(load().amxfp4_gemm_ex(ctypes.byref(fmt), ctypes.byref(options), M, N, K, a_codes.data_ptr(),
+                                     a_scales.data_ptr(), b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(),
+                                     out.stride(-2), batch, ws_ptr, ws_len, _stream()))
         return out
     _check(_fn(fmt, "gemm", baseline)(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
                                       b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(), out.stride(-2), batch,

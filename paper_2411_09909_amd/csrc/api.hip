@@ -5,8 +5,6 @@
 #include <stdlib.h>
 #include <string.h>
 
-#include <atomic>
-
 #include "../../include/amxfp4.h"
 #include "../../include/amxfp4_layer.h"
 #include "kernels.h"
@@ -131,48 +129,66 @@ bool uses_skinny(const amx_format_t& f, int64_t M, int64_t N, int64_t K, int64_t
   return f.group_size == 32 && amx::skinny_path_supported(M, N, K, batch);
 }
 
-// FP8-E5M2 scales have three kernels (amxfp4_select_e5m2_kernel in the header); shapes one does not take use the
-// panel kernel.
-enum E5m2Path : int { kPathPanel = 0, kPathHybrid = 1, kPathFused = 2 };
-std::atomic<int>& e5m2_choice() {
-  static std::atomic<int> choice([] {
-    const char* v = getenv("AMXFP4_GEMM_PATH");
-    if (v && strcmp(v, "fused") == 0) return (int)kPathFused;
-    if (v && strcmp(v, "hybrid") == 0) return (int)kPathHybrid;
-    return (int)kPathPanel;
-  }());
-  return choice;
-}
-E5m2Path e5m2_path(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  if (f.scale != AMX_SCALE_FP8_E5M2 || f.group_size != 32) return kPathPanel;
-  const int want = e5m2_choice().load(std::memory_order_relaxed);
-  if (want == kPathFused && amx::e5m2_fused_supported(M, N, K)) return kPathFused;
-  if (want == kPathHybrid && amx::e5m2_hybrid_supported(M, N, K)) return kPathHybrid;
-  return kPathPanel;
+// What one GEMM call runs: resolved ONCE per call from the format, the shape and the caller's options, and used for
+// both the workspace requirement and the dispatch (a kernel that does not take the shape falls back to the default).
+enum GemmKernel : int { kGemmSkinny, kGemmFp8Merged, kGemmFp4, kGemmE5m2Fused, kGemmE5m2Hybrid, kGemmPanel };
+struct GemmPlan {
+  GemmKernel kernel;
+  int tile;           // BF16-panel kernel: AMX_TILE_*
+  int skinny_slices;  // few-rows kernel: forced outer K slices, 0 = cost model
+};
+
+int check_options(const amx_gemm_options_t* o) {
+  if (!o) return AMX_OK;
+  if (o->e5m2_kernel < AMX_E5M2_PANEL || o->e5m2_kernel > AMX_E5M2_FUSED)
+    return fail(AMX_ERR_INVALID_ARG, "options: no such e5m2_kernel %d", (int)o->e5m2_kernel);
+  if (o->pot_kernel < AMX_POT_MERGED_FP8 || o->pot_kernel > AMX_POT_SPLIT_FP4)
+    return fail(AMX_ERR_INVALID_ARG, "options: no such pot_kernel %d", (int)o->pot_kernel);
+  if (o->tile < AMX_TILE_AUTO || o->tile > AMX_TILE_64x256)
+    return fail(AMX_ERR_INVALID_ARG, "options: no such tile %d", (int)o->tile);
+  if (o->few_rows < -1 || o->few_rows > 16)
+    return fail(AMX_ERR_INVALID_ARG, "options: few_rows must be -1, 0 or a slice count up to 16 (got %d)", (int)o->few_rows);
+  return AMX_OK;
 }
 
-// Asymmetric power-of-two scales have two kernels (amxfp4_select_pot_kernel in the header): the groups merged into
-// E5M2 elements with one anchor scale on the block-scaled FP8 MFMA (default; any K; workspace), or split by sign into
-// four FP4 MFMAs per block (K a multiple of 128; no workspace).
-std::atomic<int>& pot_choice() {
-  static std::atomic<int> choice([] {
-    const char* v = getenv("AMXFP4_POT_PATH");
-    return v && strcmp(v, "split") == 0 ? 1 : 0;
-  }());
-  return choice;
+// scaled: the tensor-wise double scaling (Sec. 5.3), which only the BF16-panel kernel's epilogue applies.
+GemmPlan plan_gemm(const amx_format_t& f, const amx_gemm_options_t* o, bool scaled, int64_t M, int64_t N, int64_t K,
+                   int64_t batch) {
+  static const amx_gemm_options_t kDefaults = {0, 0, 0, 0};
+  const amx_gemm_options_t& opt = o ? *o : kDefaults;
+  GemmPlan p = {kGemmPanel, opt.tile, opt.few_rows > 0 ? opt.few_rows : 0};
+  if (scaled) return p;
+  if (opt.few_rows >= 0 && uses_skinny(f, M, N, K, batch)) return p.kernel = kGemmSkinny, p;
+  const bool pot32 = f.group_size == 32 && (f.scale == AMX_SCALE_E8M0_FLOOR || f.scale == AMX_SCALE_E8M0_ROUND);
+  if (pot32 && f.asymmetric && (opt.pot_kernel == AMX_POT_MERGED_FP8 || !amx::fp4_path_supported(M, N, K)))
+    return p.kernel = kGemmFp8Merged, p;
+  if (uses_fp4_mfma(f, M, N, K)) return p.kernel = kGemmFp4, p;
+  if (f.scale == AMX_SCALE_FP8_E5M2 && f.group_size == 32) {
+    if (opt.e5m2_kernel == AMX_E5M2_FUSED && amx::e5m2_fused_supported(M, N, K)) return p.kernel = kGemmE5m2Fused, p;
+    if (opt.e5m2_kernel == AMX_E5M2_HYBRID && amx::e5m2_hybrid_supported(M, N, K)) return p.kernel = kGemmE5m2Hybrid, p;
+  }
+  return p;
 }
-bool uses_merged_pot(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  if (!f.asymmetric || f.group_size != 32 || (f.scale != AMX_SCALE_E8M0_FLOOR && f.scale != AMX_SCALE_E8M0_ROUND)) return false;
-  return pot_choice().load(std::memory_order_relaxed) == 0 || !amx::fp4_path_supported(M, N, K);
+
+size_t plan_workspace_bytes(const GemmPlan& p, int64_t M, int64_t N, int64_t K, int64_t batch) {
+  switch (p.kernel) {
+    case kGemmSkinny: return amx::skinny_path_workspace_bytes(M, N, K, batch, p.skinny_slices);
+    case kGemmFp8Merged: return amx::fp8m_path_workspace_bytes(M, N, K, batch);
+    case kGemmFp4: case kGemmE5m2Fused: return 0;
+    case kGemmE5m2Hybrid: return amx::e5m2_hybrid_workspace_bytes(M, K, batch);
+    default: return amx::bf16_path_workspace_bytes(M, N, K, batch);
+  }
 }
 
 // A_pair / B_pair: device {S_t, 1 / S_t} of the operands' tensor-wise scales (Sec. 5.3), both null for none. Scaled
 // products always take the BF16 expansion path, whose kernel has the scaling epilogue.
-int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
-              const float* A_pair, const uint8_t* B_codes, const uint8_t* B_scales, const float* B_pair, float* C,
-              int64_t ldc, int64_t batch, void* workspace, size_t workspace_bytes, void* stream) {
+int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+              const uint8_t* A_scales, const float* A_pair, const uint8_t* B_codes, const uint8_t* B_scales,
+              const float* B_pair, float* C, int64_t ldc, int64_t batch, void* workspace, size_t workspace_bytes,
+              void* stream) {
   const bool scaled = A_pair != nullptr;
   if (int rc = check_format(&f)) return rc;
+  if (int rc = check_options(opts)) return rc;
   if (int rc = check_shape(f, M, K)) return rc;
   if (N <= 0 || batch <= 0) return fail(AMX_ERR_INVALID_ARG, "N and batch must be positive");
   if (M > kMaxGemmRows || N > kMaxGemmRows || batch > kMaxBatch)
@@ -183,8 +199,8 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
   if (!aligned(A_codes, 16) || !aligned(B_codes, 16) || !aligned(A_scales, 4) || !aligned(B_scales, 4) ||
       !aligned(C, 4))
     return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales and C 4-byte alignment");
-  const size_t need = scaled ? amx::bf16_path_workspace_bytes(M, N, K, batch)
-                             : amxfp4_gemm_workspace_bytes(&f, M, N, K, batch);
+  const GemmPlan plan = plan_gemm(f, opts, scaled, M, N, K, batch);
+  const size_t need = plan_workspace_bytes(plan, M, N, K, batch);
   if (need > 0) {
     if (!workspace || workspace_bytes < need)
       return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
@@ -192,44 +208,43 @@ int gemm_impl(amx_format_t f, int64_t M, int64_t N, int64_t K, const uint8_t* A_
   }
   const amx::KernelTimer timer = g_timer;
   g_timer = amx::KernelTimer();
-  if (!scaled && uses_skinny(f, M, N, K, batch)) {
-    hipError_t e = amx::launch_gemm_skinny_path(f.scale, f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes,
-                                                B_scales, C, ldc, batch, workspace,
-                                                reinterpret_cast<hipStream_t>(stream), timer);
-    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  const bool asym = f.asymmetric != 0;
+  hipError_t e;
+  switch (plan.kernel) {
+    case kGemmSkinny:
+      e = amx::launch_gemm_skinny_path(f.scale, asym, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch,
+                                       workspace, plan.skinny_slices, hs, timer);
+      break;
+    case kGemmFp8Merged:
+      e = amx::launch_gemm_fp8m_path(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, hs, timer);
+      break;
+    case kGemmFp4:
+      e = amx::launch_gemm_fp4_path(asym, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, hs, timer);
+      break;
+    case kGemmE5m2Fused:
+      e = amx::launch_gemm_e5m2_fused(asym, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, hs, timer);
+      break;
+    case kGemmE5m2Hybrid:
+      e = amx::launch_gemm_e5m2_hybrid(asym, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace,
+                                       hs, timer);
+      break;
+    default:
+      e = amx::launch_gemm_bf16_path(f.scale, asym, f.group_size, M, N, K, A_codes, A_scales, B_codes, B_scales, A_pair,
+                                     B_pair, C, ldc, batch, workspace, plan.tile, hs, timer);
   }
-  if (!scaled && uses_merged_pot(f, M, N, K)) {
-    hipError_t e = amx::launch_gemm_fp8m_path(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace,
-                                              reinterpret_cast<hipStream_t>(stream), timer);
-    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
-  }
-  if (!scaled && uses_fp4_mfma(f, M, N, K)) {
-    hipError_t e = amx::launch_gemm_fp4_path(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc,
-                                             batch, reinterpret_cast<hipStream_t>(stream), timer);
-    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
-  }
-  const E5m2Path path = scaled ? kPathPanel : e5m2_path(f, M, N, K);
-  if (path == kPathFused) {
-    hipError_t e = amx::launch_gemm_e5m2_fused(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc,
-                                               batch, reinterpret_cast<hipStream_t>(stream), timer);
-    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
-  }
-  if (path == kPathHybrid) {
-    hipError_t e = amx::launch_gemm_e5m2_hybrid(f.asymmetric != 0, M, N, K, A_codes, A_scales, B_codes, B_scales, C,
-                                                ldc, batch, workspace, reinterpret_cast<hipStream_t>(stream), timer);
-    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
-  }
-  hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, f.group_size, M, N, K, A_codes, A_scales, B_codes, B_scales,
-                                            A_pair, B_pair, C, ldc, batch, workspace,
-                                            reinterpret_cast<hipStream_t>(stream), timer);
   return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
 }
 
 // The gated GEMM runs on the tiled kernels only (the block-scaled ones for power-of-two scales, else the BF16 panels).
+GemmPlan plan_glu(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
+  static const amx_gemm_options_t kTiledOnly = {0, 0, 0, -1};
+  GemmPlan p = plan_gemm(f, &kTiledOnly, false, M, N, K, 1);
+  if (p.kernel != kGemmFp8Merged && p.kernel != kGemmFp4) p.kernel = kGemmPanel;
+  return p;
+}
 size_t glu_workspace_bytes(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  if (uses_merged_pot(f, M, N, K)) return amx::fp8m_path_workspace_bytes(M, N, K, 1);
-  if (uses_fp4_mfma(f, M, N, K)) return 0;
-  return amx::bf16_path_workspace_bytes(M, N, K, 1);
+  return plan_workspace_bytes(plan_glu(f, M, N, K), M, N, K, 1);
 }
 
 amx_format_t symmetric(const amx_format_t* f) {
@@ -243,18 +258,6 @@ amx_format_t symmetric(const amx_format_t* f) {
 extern "C" {
 
 const char* amxfp4_last_error(void) { return g_err; }
-
-int amxfp4_select_e5m2_kernel(int32_t which) {
-  if (which < kPathPanel || which > kPathFused) return fail(AMX_ERR_INVALID_ARG, "no such kernel: %d", (int)which);
-  e5m2_choice().store(which, std::memory_order_relaxed);
-  return AMX_OK;
-}
-
-int amxfp4_select_pot_kernel(int32_t which) {
-  if (which < 0 || which > 1) return fail(AMX_ERR_INVALID_ARG, "no such kernel: %d", (int)which);
-  pot_choice().store(which, std::memory_order_relaxed);
-  return AMX_OK;
-}
 
 int amxfp4_profile_next_gemm(void* start_event, void* stop_event) {
   g_timer.start = reinterpret_cast<hipEvent_t>(start_event);
@@ -272,15 +275,14 @@ size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
   return (size_t)(rows * (K / fmt->group_size) * (fmt->asymmetric ? 2 : 1));
 }
 
+size_t amxfp4_gemm_workspace_bytes_ex(const amx_format_t* fmt, const amx_gemm_options_t* opts, int64_t M, int64_t N,
+                                      int64_t K, int64_t batch) {
+  if (!fmt || M <= 0 || N <= 0 || K <= 0 || batch <= 0 || check_options(opts)) return 0;
+  return plan_workspace_bytes(plan_gemm(*fmt, opts, false, M, N, K, batch), M, N, K, batch);
+}
+
 size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch) {
-  if (!fmt || M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
-  if (uses_skinny(*fmt, M, N, K, batch)) return amx::skinny_path_workspace_bytes(M, N, K, batch);
-  if (uses_merged_pot(*fmt, M, N, K)) return amx::fp8m_path_workspace_bytes(M, N, K, batch);
-  if (uses_fp4_mfma(*fmt, M, N, K)) return 0;
-  const E5m2Path path = e5m2_path(*fmt, M, N, K);
-  if (path == kPathFused) return 0;
-  if (path == kPathHybrid) return amx::e5m2_hybrid_workspace_bytes(M, K, batch);
-  return amx::bf16_path_workspace_bytes(M, N, K, batch);
+  return amxfp4_gemm_workspace_bytes_ex(fmt, nullptr, M, N, K, batch);
 }
 
 int amxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
@@ -353,19 +355,21 @@ int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int6
   g_timer = amx::KernelTimer();
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
   float* out = reinterpret_cast<float*>(out_bf16);
-  if (uses_merged_pot(f, M, 2 * width, K)) {
+  const GemmKernel glu_kernel = plan_glu(f, M, 2 * width, K).kernel;
+  if (glu_kernel == kGemmFp8Merged) {
     hipError_t e = amx::launch_gemm_fp8m_path(M, 2 * width, K, A_codes, A_scales, B_codes, B_scales, out, ld_out, 1,
                                               workspace, hs, timer, true);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
   }
-  if (uses_fp4_mfma(f, M, 2 * width, K)) {
+  if (glu_kernel == kGemmFp4) {
     hipError_t e = amx::launch_gemm_fp4_path(f.asymmetric != 0, M, 2 * width, K, A_codes, A_scales, B_codes, B_scales,
                                              out, ld_out, 1, hs, timer, true);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
   }
   hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, f.group_size, M, 2 * width, K, A_codes, A_scales,
                                             B_codes, B_scales, nullptr, nullptr, reinterpret_cast<float*>(out_bf16),
-                                            ld_out, 1, workspace, reinterpret_cast<hipStream_t>(stream), timer, true);
+                                            ld_out, 1, workspace, AMX_TILE_AUTO, reinterpret_cast<hipStream_t>(stream), timer,
+                                            true);
   return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
 }
 
@@ -379,8 +383,16 @@ int amxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const 
                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
                 int64_t batch, void* workspace, size_t workspace_bytes, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  return gemm_impl(*fmt, M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc, batch, workspace, workspace_bytes,
-                   stream);
+  return gemm_impl(*fmt, nullptr, M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc, batch, workspace,
+                   workspace_bytes, stream);
+}
+
+int amxfp4_gemm_ex(const amx_format_t* fmt, const amx_gemm_options_t* opts, int64_t M, int64_t N, int64_t K,
+                   const uint8_t* A_codes, const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales,
+                   float* C, int64_t ldc, int64_t batch, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  return gemm_impl(*fmt, opts, M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc, batch, workspace,
+                   workspace_bytes, stream);
 }
 
 int mxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
@@ -399,9 +411,8 @@ int mxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const u
                const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
                int64_t batch, void* workspace, size_t workspace_bytes, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  return gemm_impl(symmetric(fmt), M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc, batch,
-                   workspace,
-                   workspace_bytes, stream);
+  return gemm_impl(symmetric(fmt), nullptr, M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc,
+                   batch, workspace, workspace_bytes, stream);
 }
 
 int amxfp4_tensor_scale(const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride, float* scale_pair,
@@ -441,8 +452,8 @@ int amxfp4_gemm_scaled(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K,
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
   if (!A_scale_pair || !B_scale_pair || !aligned(A_scale_pair, 8) || !aligned(B_scale_pair, 8))
     return fail(AMX_ERR_INVALID_ARG, "a scale pair is NULL or misaligned");
-  return gemm_impl(*fmt, M, N, K, A_codes, A_scales, A_scale_pair, B_codes, B_scales, B_scale_pair, C, ldc, batch,
-                   workspace, workspace_bytes, stream);
+  return gemm_impl(*fmt, nullptr, M, N, K, A_codes, A_scales, A_scale_pair, B_codes, B_scales, B_scale_pair, C, ldc,
+                   batch, workspace, workspace_bytes, stream);
 }
 
 size_t amxfp4_attention_workspace_bytes(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq,

@@ -13,7 +13,6 @@
 //      Rows are padded to a multiple of 256 and K to a multiple of 128 with zeros.
 //   2. GEMM kernel: every operand fragment is one contiguous KiB in the workspace, so staging global -> LDS is a
 //      linear copy and LDS -> register reads are conflict-free 128-bit reads at lane * 16.
-#include <stdlib.h>
 
 #include "device_formats.h"
 #include "gemm_common.h"
@@ -357,7 +356,7 @@ static hipError_t launch_tiles(const uint16_t* Ap, const uint16_t* Bp, float* C,
 hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, int64_t M, int64_t N, int64_t K,
                                  const uint8_t* A_codes, const uint8_t* A_scales, const uint8_t* B_codes,
                                  const uint8_t* B_scales, const float* A_tensor_pair, const float* B_tensor_pair,
-                                 float* C, int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
+                                 float* C, int64_t ldc, int64_t batch, void* workspace, int tile, hipStream_t s,
                                  const KernelTimer& timer, bool glu) {
   const int gs_log2 = group_size == 16 ? 4 : group_size == 32 ? 5 : group_size == 64 ? 6 : group_size == 128 ? 7 : -1;
   if (gs_log2 < 0 || K % group_size != 0 || K % 32 != 0) return hipErrorInvalidValue;
@@ -373,28 +372,20 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
   // large problems use; a problem with fewer such tiles than the chip has CUs, or with one side much smaller than a
   // tile, finishes sooner with 256 x 128 or 64 x 256 tiles that fill the CUs. The choice minimises
   // (rounds of 256 workgroups) x (measured cost of one tile relative to a 256 x 256 one: 0.6 and 0.4), and leaves
-  // 256 x 256 only for a predicted gain of more than 15 %. AMXFP4_TILE overrides it in tuning experiments.
-  static const int tile_env = getenv("AMXFP4_TILE") ? atoi(getenv("AMXFP4_TILE")) : -1;
+  // 256 x 256 only for a predicted gain of more than 15 %. A caller's option (tile != 0) overrides it.
   auto rounds = [&](int64_t tile_m, int64_t tile_n) {
     const int64_t tiles = ((M + tile_m - 1) / tile_m) * ((N + tile_n - 1) / tile_n) * batch;
     return (double)((tiles + 255) / 256);
   };
-  const double est0 = rounds(256, 256), est3 = 0.6 * rounds(256, 128), est4 = 0.4 * rounds(64, 256);
-  const bool ok4 = est4 < 0.85 * est0;
-  const bool ok3 = est3 < 0.85 * est0 && M > 256;  // (with a single row of 256-row tiles the 64-row tile was never worse)
-  int tile_cfg = 0;
-  if (ok4 && (!ok3 || est4 <= est3))
-    tile_cfg = 4;
-  else if (ok3)
-    tile_cfg = 3;
-  if (tile_env >= 0) tile_cfg = tile_env;
-  if (tile_cfg == 1)
-    e = launch_tiles<2, 4, 4, 2>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, glu, s);
-  else if (tile_cfg == 2)
-    e = launch_tiles<4, 2, 2, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, glu, s);
-  else if (tile_cfg == 3)
+  if (tile == 0) {
+    const double est1 = rounds(256, 256), est2 = 0.6 * rounds(256, 128), est3 = 0.4 * rounds(64, 256);
+    const bool ok3 = est3 < 0.85 * est1;
+    const bool ok2 = est2 < 0.85 * est1 && M > 256;  // (with a single row of 256-row tiles the 64-row tile was never worse)
+    tile = ok3 && (!ok2 || est3 <= est2) ? 3 : ok2 ? 2 : 1;
+  }
+  if (tile == 2)
     e = launch_tiles<4, 1, 2, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, glu, s);  // 256 x 128
-  else if (tile_cfg == 4)
+  else if (tile == 3)
     e = launch_tiles<1, 4, 2, 2>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, glu, s);  // 64 x 256
   else
     e = launch_tiles<2, 2, 4, 4>(Ap, Bp, C, M, N, Mp, Np, Kp, ldc, batch, A_tensor_pair, B_tensor_pair, glu, s);

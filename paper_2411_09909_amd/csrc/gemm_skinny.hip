@@ -26,7 +26,6 @@
 // elements s % 4 of group 4 h + s / 4) is not the natural one; the A panel is written in the same order
 // (expand_kernel<HALF_LINE>), and a sum over k does not depend on it. With more than one outer slice the partial tiles
 // go to the workspace and a second kernel adds them in a fixed order (no atomics: results are reproducible).
-#include <stdlib.h>
 
 #include "device_formats.h"
 #include "gemm_common.h"
@@ -155,9 +154,8 @@ constexpr int skinny_cols(int row_tiles) { return 32 * skinny_waves(row_tiles) /
 // partial tiles every further slice writes and the reduction reads (16 Mp / K of the bytes of B per slice). The
 // cheapest count of at most 16 wins, the smaller one on ties. Returns the number of slices and sets the blocks per
 // slice; every slice has at least one block ((slices - 1) * blocks_per_slice < nblk).
-// AMXFP4_SKINNY_SLICES (tuning aid): forces the wanted count.
-static int skinny_outer_slices(int64_t groups, int64_t nblk, int64_t Mp, int& blocks_per_slice) {
-  static const int forced = getenv("AMXFP4_SKINNY_SLICES") ? atoi(getenv("AMXFP4_SKINNY_SLICES")) : 0;
+// forced > 0 (a caller's tuning option) takes the place of the model's count.
+static int skinny_outer_slices(int64_t groups, int64_t nblk, int64_t Mp, int forced, int& blocks_per_slice) {
   const double b_time = (double)(groups * nblk) / 256.0, partial = 16.0 * (double)Mp / (double)(nblk * kSkinnyBlockK);
   int64_t best = 1;
   double best_cost = 1e300;
@@ -185,8 +183,7 @@ static int skinny_row_tiles(int64_t M) {
 constexpr int kSkinnyMaxChunkedM = 768;
 
 bool skinny_path_supported(int64_t M, int64_t N, int64_t K, int64_t batch) {
-  static const bool enabled = !(getenv("AMXFP4_SKINNY") && atoi(getenv("AMXFP4_SKINNY")) == 0);
-  if (!enabled || K % kSkinnyBlockK != 0 || N < 1 || M < 1) return false;
+  if (K % kSkinnyBlockK != 0 || N < 1 || M < 1) return false;
   return M <= kSkinnyMaxM || (batch == 1 && M <= kSkinnyMaxChunkedM && N * K >= (int64_t(1) << 27));
 }
 
@@ -197,19 +194,19 @@ static int64_t skinny_panel_rows(int64_t M) {
 }
 
 // bytes of partial tiles one chunk of `rows` rows needs (0 with a single slice)
-static size_t skinny_partial_bytes(int64_t rows, int64_t N, int64_t K, int64_t batch) {
+static size_t skinny_partial_bytes(int64_t rows, int64_t N, int64_t K, int64_t batch, int forced_slices) {
   const int64_t Mp = 32 * skinny_row_tiles(rows), cols = skinny_cols(skinny_row_tiles(rows));
   int bps;
-  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, bps);
+  const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, forced_slices, bps);
   return slices > 1 ? (size_t)(batch * slices * Mp * N * 4) : 0;
 }
 
-size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch) {
+size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch, int forced_slices) {
   size_t bytes = (size_t)(batch * skinny_panel_rows(M) * K * 2);  // A panel
   bytes = (bytes + 255) / 256 * 256;
   size_t partial = 0;  // the chunks run one after the other and share the partial tiles' space
   for (int64_t r0 = 0; r0 < M; r0 += kSkinnyMaxM) {
-    const size_t p = skinny_partial_bytes(M - r0 < kSkinnyMaxM ? M - r0 : kSkinnyMaxM, N, K, batch);
+    const size_t p = skinny_partial_bytes(M - r0 < kSkinnyMaxM ? M - r0 : kSkinnyMaxM, N, K, batch, forced_slices);
     partial = p > partial ? p : partial;
   }
   return bytes + partial;
@@ -469,7 +466,7 @@ static hipError_t launch_skinny(const uint16_t* Ap, const uint8_t* Bc, const uin
 
 hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                                    const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
-                                   int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
+                                   int64_t ldc, int64_t batch, void* workspace, int forced_slices, hipStream_t s,
                                    const KernelTimer& timer) {
   if (!skinny_path_supported(M, N, K, batch)) return hipErrorInvalidValue;
   const int64_t Mp_all = skinny_panel_rows(M);
@@ -486,7 +483,7 @@ hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t
     const int64_t rows = M - r0 < kSkinnyMaxM ? M - r0 : kSkinnyMaxM;
     const int64_t Mp = 32 * skinny_row_tiles(rows), cols = skinny_cols((int)(Mp / 32));
     int bps;
-    const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, bps);
+    const int slices = skinny_outer_slices((N + cols - 1) / cols * batch, K / kSkinnyBlockK, Mp, forced_slices, bps);
     const uint16_t* Ac = Ap + r0 * K;  // panel row blocks are contiguous: 32 rows x K values each
     float* Cc = C + r0 * ldc;
     auto go = [&]<int SK, bool ASYM>() {

@@ -39,12 +39,13 @@ struct KernelTimer {
   hipEvent_t start = nullptr, stop = nullptr;
 };
 
-// gemm_bf16.hip (glu: the gated-activation epilogue; C is then the BF16 output [M][ldc] of N / 2 columns)
+// gemm_bf16.hip (glu: the gated-activation epilogue; C is then the BF16 output [M][ldc] of N / 2 columns;
+// tile: 0 = chosen by a cost model over the shape, 1 = 256 x 256, 2 = 256 x 128, 3 = 64 x 256)
 size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
 hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, int64_t M, int64_t N, int64_t K,
                                  const uint8_t* A_codes, const uint8_t* A_scales, const uint8_t* B_codes,
                                  const uint8_t* B_scales, const float* A_tensor_pair, const float* B_tensor_pair,
-                                 float* C, int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
+                                 float* C, int64_t ldc, int64_t batch, void* workspace, int tile, hipStream_t s,
                                  const KernelTimer& timer, bool glu = false);
 
 // BF16 fragment-major panel [batch][Rp / 32][Kp / 16][64 lanes][8] of a quantized operand (rows >= R and columns >= K
@@ -54,12 +55,13 @@ hipError_t launch_expand_bf16(int scale_kind, bool asym, int64_t group_size, con
                               bool permute, uint16_t* panel, hipStream_t s);
 
 // gemm_skinny.hip: M <= 256, K a multiple of 256, groups of 32: B dequantized in registers straight from its codes
-// (workspace: the BF16 panel of A and, with several outer K slices, the partial tiles)
+// (workspace: the BF16 panel of A and, with several outer K slices, the partial tiles; forced_slices: 0 = the number
+// of outer K slices comes from a cost model, n > 0 = n of them, at most K / 256)
 bool skinny_path_supported(int64_t M, int64_t N, int64_t K, int64_t batch);
-size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
+size_t skinny_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch, int forced_slices);
 hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                                    const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
-                                   int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
+                                   int64_t ldc, int64_t batch, void* workspace, int forced_slices, hipStream_t s,
                                    const KernelTimer& timer);
 
 // attention.hip: fused quantized attention, head dimension 128, groups of 32 (workspace: the three BF16 panels).

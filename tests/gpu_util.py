@@ -22,9 +22,11 @@ def gpu_quantize(bits, scale, asym, k_axis=-1, baseline=False, group_size=32):
     return c.cpu().numpy(), s.cpu().numpy()
 
 
-def gpu_gemm(ac, as_, bc, bs, scale, asym, baseline=False, group_size=32):
+def gpu_gemm(ac, as_, bc, bs, scale, asym, baseline=False, group_size=32, options=None):
+    """options: binding.gemm_options(...) for a per-call kernel choice (amxfp4_gemm_ex), None for amxfp4_gemm."""
     fmt = binding.make_format(scale, asym, group_size)
-    C = binding.gemm(fmt, to_dev_u8(ac), to_dev_u8(as_), to_dev_u8(bc), to_dev_u8(bs), baseline=baseline)
+    C = binding.gemm(fmt, to_dev_u8(ac), to_dev_u8(as_), to_dev_u8(bc), to_dev_u8(bs), baseline=baseline,
+                     options=options)
     torch.cuda.synchronize()
     return C.cpu().numpy()
 

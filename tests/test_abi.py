@@ -59,19 +59,49 @@ def test_size_queries(lib):
         assert binding.gemm_workspace_bytes(fmt, 130, 1024, 1024) == 192 * 1024 * 2 + 4 * 192 * 1024 * 4  # 5 -> 6 row tiles
 
 
-def test_e5m2_kernel_selection_changes_the_workspace(lib):
+def test_kernel_options_are_per_call_and_the_workspace_query_is_pure(lib):
+    """The kernel choice travels with the call (amx_gemm_options_t): the workspace query is a function of its arguments
+    alone, and a query with other options in between does not change what the default query returns."""
     f = binding.make_format(binding.FP8_E5M2, True)
-    try:
-        binding.select_e5m2_kernel("hybrid")   # only the A panel (FP16) lives in the workspace
-        assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == 512 * 1024 * 2
-        assert binding.gemm_workspace_bytes(f, 300, 1024, 96) == (512 + 1024) * 128 * 2  # K % 128 != 0: panel kernel
-        binding.select_e5m2_kernel("fused")
-        assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == 0
-        with pytest.raises(binding.AmxError):
-            binding.select_e5m2_kernel(7)
-    finally:
-        binding.select_e5m2_kernel("panel")
-    assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == (512 + 1024) * 1024 * 2
+    default = (512 + 1024) * 1024 * 2
+    assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == default
+    hybrid = binding.gemm_options(e5m2_kernel="hybrid")   # only the A panel (FP16) lives in the workspace
+    assert binding.gemm_workspace_bytes(f, 300, 1024, 1024, options=hybrid) == 512 * 1024 * 2
+    assert binding.gemm_workspace_bytes(f, 300, 1024, 96, options=hybrid) == (512 + 1024) * 128 * 2  # K % 128 != 0: panel
+    assert binding.gemm_workspace_bytes(f, 300, 1024, 1024, options=binding.gemm_options(e5m2_kernel="fused")) == 0
+    assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == default
+    assert binding.gemm_workspace_bytes(f, 300, 1024, 1024, options=binding.gemm_options()) == default
+    # asymmetric power-of-two scales: merged FP8 panels (1 byte per element + anchors) or the sign-split FP4 kernel
+    g = binding.make_format(binding.E8M0_FLOOR, True)
+    merged = (512 + 1024) * 1024 + (512 + 1024) // 32 * (1024 // 256) * 256
+    assert binding.gemm_workspace_bytes(g, 300, 1024, 1024) == merged
+    assert binding.gemm_workspace_bytes(g, 300, 1024, 1024, options=binding.gemm_options(pot_kernel="split")) == 0
+    # few rows: without that kernel the panel path's workspace; with a forced slice count its partial tiles
+    assert binding.gemm_workspace_bytes(f, 64, 1024, 1024, options=binding.gemm_options(few_rows=-1)) == (256 + 1024) * 1024 * 2
+    assert binding.gemm_workspace_bytes(f, 64, 1024, 1024, options=binding.gemm_options(few_rows=2)) == 64 * 1024 * 2 + 2 * 64 * 1024 * 4
+    assert binding.gemm_workspace_bytes(f, 64, 1024, 1024, options=binding.gemm_options(few_rows=1)) == 64 * 1024 * 2
+    # unknown option values: no size, and the call itself is an invalid-argument error before anything is touched
+    p = ctypes.c_void_p(0x1000)
+    for bad in (binding.AmxGemmOptions(3, 0, 0, 0), binding.AmxGemmOptions(0, 2, 0, 0), binding.AmxGemmOptions(0, 0, 4, 0),
+                binding.AmxGemmOptions(0, 0, 0, 17), binding.AmxGemmOptions(0, 0, 0, -2), binding.AmxGemmOptions(-1, 0, 0, 0)):
+        assert binding.gemm_workspace_bytes(f, 300, 1024, 1024, options=bad) == 0
+        assert lib.amxfp4_gemm_ex(ctypes.byref(f), ctypes.byref(bad), 64, 64, 64, p, p, p, p, p, 64, 1, p, 1 << 30,
+                                  None) == -1
+        assert b"options" in lib.amxfp4_last_error()
+    # NULL options = defaults
+    assert lib.amxfp4_gemm_workspace_bytes_ex(ctypes.byref(f), None, 300, 1024, 1024, 1) == default
+
+
+def test_no_environment_reads_and_no_process_wide_selectors():
+    """The boundary keeps no process-wide choice: the sources read no environment variable and export no selector."""
+    import glob
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for path in glob.glob(os.path.join(root, "paper_2411_09909_amd", "csrc", "*")):
+        text = open(path).read()
+        assert "getenv" not in text and "std::atomic" not in text, path
+    header = open(os.path.join(root, "include", "amxfp4.h")).read()
+    assert "amxfp4_select_" not in header
 
 
 def _q(lib, fmt, x, rows, K, rs, ks, codes, scales):

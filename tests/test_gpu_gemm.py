@@ -106,12 +106,11 @@ def test_mxfp4_baseline_gemm():
 
 @pytest.fixture(params=["hybrid", "fused"])
 def alternative_e5m2_kernel(request):
-    """The two other kernels for FP8-E5M2 scales (dequantization inside the GEMM kernel); the default one is what
-    every other test in this file runs."""
+    """Per-call options for the two other kernels for FP8-E5M2 scales (dequantization inside the GEMM kernel); the
+    default one is what every other test in this file runs. The few-rows kernel is switched off so that the small
+    shapes reach them too."""
     from paper_2411_09909_amd import binding
-    binding.select_e5m2_kernel(request.param)
-    yield request.param
-    binding.select_e5m2_kernel("panel")
+    return binding.gemm_options(e5m2_kernel=request.param, few_rows=-1)
 
 
 @pytest.mark.parametrize("asym", [1, 0])
@@ -122,13 +121,13 @@ def test_alternative_e5m2_kernels(alternative_e5m2_kernel, M, N, K, asym):
     b = synth.weights(N, K, seed=N)
     ac, as_ = ref.quantize(a, 32, ref.FP8_E5M2, asym)
     bc, bs = ref.quantize(b, 32, ref.FP8_E5M2, asym)
-    C = G.gpu_gemm(ac, as_, bc, bs, ref.FP8_E5M2, asym)
+    C = G.gpu_gemm(ac, as_, bc, bs, ref.FP8_E5M2, asym, options=alternative_e5m2_kernel)
     assert G.rel_fro(C, ref.gemm(ac, as_, bc, bs, 32, ref.FP8_E5M2, asym)) <= TOL
 
 
 def test_alternative_e5m2_kernels_batched_and_llm_shape(alternative_e5m2_kernel):
     ac, as_, bc, bs = quantized("c3_70b_up_4096x8192x28672", ref.FP8_E5M2, 1, M=300, N=520)
-    C = G.gpu_gemm(ac, as_, bc, bs, ref.FP8_E5M2, 1)
+    C = G.gpu_gemm(ac, as_, bc, bs, ref.FP8_E5M2, 1, options=alternative_e5m2_kernel)
     assert G.rel_fro(C, ref.gemm(ac, as_, bc, bs, 32, ref.FP8_E5M2, 1)) <= TOL
     # batch of 3 independent problems (heads)
     a = synth.activations(3 * 130, 256, seed=5, n_outlier=1, outlier_gain=20.0)
@@ -136,7 +135,8 @@ def test_alternative_e5m2_kernels_batched_and_llm_shape(alternative_e5m2_kernel)
     ac, as_ = ref.quantize(a, 32, ref.FP8_E5M2, 1)
     bc, bs = ref.quantize(b, 32, ref.FP8_E5M2, 1)
     shp = lambda t, r: t.reshape((3, r) + t.shape[1:])
-    C = G.gpu_gemm(shp(ac, 130), shp(as_, 130), shp(bc, 200), shp(bs, 200), ref.FP8_E5M2, 1)
+    C = G.gpu_gemm(shp(ac, 130), shp(as_, 130), shp(bc, 200), shp(bs, 200), ref.FP8_E5M2, 1,
+                   options=alternative_e5m2_kernel)
     Cr = ref.gemm(shp(ac, 130), shp(as_, 130), shp(bc, 200), shp(bs, 200), 32, ref.FP8_E5M2, 1)
     assert C.shape == (3, 130, 200)
     assert G.rel_fro(C, Cr) <= TOL
@@ -144,11 +144,10 @@ def test_alternative_e5m2_kernels_batched_and_llm_shape(alternative_e5m2_kernel)
 
 @pytest.fixture
 def split_pot_kernel():
-    """The sign-split FP4 kernel for asymmetric power-of-two scales (the merged FP8 kernel is the default)."""
+    """Per-call options for the sign-split FP4 kernel for asymmetric power-of-two scales (the merged FP8 kernel is the
+    default), with the few-rows kernel switched off so that the small shapes reach it."""
     from paper_2411_09909_amd import binding
-    binding.select_pot_kernel("split")
-    yield
-    binding.select_pot_kernel("merged")
+    return binding.gemm_options(pot_kernel="split", few_rows=-1)
 
 
 @pytest.mark.parametrize("M,N,K", [(64, 1024, 1024), (257, 255, 384), (300, 520, 1280), (100, 200, 160)])
@@ -158,7 +157,7 @@ def test_sign_split_kernel_for_asymmetric_power_of_two_scales(split_pot_kernel, 
     b = synth.weights(N, K, seed=N)
     ac, as_ = ref.quantize(a, 32, ref.E8M0_FLOOR, 1)
     bc, bs = ref.quantize(b, 32, ref.E8M0_FLOOR, 1)
-    C = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1)
+    C = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1, options=split_pot_kernel)
     assert G.rel_fro(C, ref.gemm(ac, as_, bc, bs, 32, ref.E8M0_FLOOR, 1)) <= TOL
 
 
@@ -184,11 +183,7 @@ def test_merged_kernel_with_far_apart_sign_scales():
     C = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1)
     assert G.rel_fro(C, Cr) <= 1e-4
     assert max(G.rel_fro(C[i], Cr[i]) for i in range(M)) <= 2e-4
-    binding.select_pot_kernel("split")
-    try:
-        Cs = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1)
-    finally:
-        binding.select_pot_kernel("merged")
+    Cs = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1, options=binding.gemm_options(pot_kernel="split", few_rows=-1))
     assert G.rel_fro(Cs, Cr) <= 1e-6
 
 
