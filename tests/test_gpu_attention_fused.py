@@ -37,11 +37,22 @@ def gpu_attention(q, k, v, scale, causal, scale_format, asym):
 
 
 def compare(out, want):
+    """The kernel evaluates exp in FP32 with the hardware's exp2, the oracle in float64: the outputs agree to FP32
+    rounding unless a probability lands on the other side of a rounding boundary of its 4-bit cast, which moves that
+    query row by up to a percent or so. Measured on the inputs of this file (all formats, the full-size samples
+    included): overall error 1.1e-7 .. 2.0e-7, worst row 2.1e-6, no such flip. The bounds: 1e-5 per row (5 x the
+    measured worst) on all but at most 0.5 % of the rows, which may carry a flip and stay within 2e-2; 2e-6 overall
+    when no row carries one, 1e-3 in any case."""
     assert out.shape == want.shape and np.isfinite(out).all()
-    assert G.rel_fro(out, want) <= 1e-3
     num = np.linalg.norm((out - want).reshape(-1, D).astype(np.float64), axis=1)
     den = np.linalg.norm(want.reshape(-1, D).astype(np.float64), axis=1)
-    assert (num <= 2e-2 * den + 1e-30).all(), "worst row %g" % float((num / np.maximum(den, 1e-30)).max())
+    rel = num / np.maximum(den, 1e-30)
+    overall = G.rel_fro(out, want)
+    print("fused attention %s: overall %.3g, worst row %.3g" % (out.shape, overall, float(rel.max())))
+    flipped = rel > 1e-5
+    assert flipped.sum() <= max(1, int(0.005 * rel.size)), "%d of %d rows beyond 1e-5" % (flipped.sum(), rel.size)
+    assert (rel <= 2e-2).all(), "worst row %g" % float(rel.max())
+    assert overall <= (1e-3 if flipped.any() else 2e-6)
 
 
 FORMATS = [(ref.FP8_E5M2, 1), (ref.FP8_E5M2, 0), (ref.E8M0_FLOOR, 1), (ref.FP8_E4M3, 1), (ref.E8M0_ROUND, 0)]

@@ -15,6 +15,12 @@ from tests import gpu_util as G
 
 pytestmark = pytest.mark.gpu
 
+# Whole-layer bounds: error relative to the layer's update, share of bit-identical output elements. Measured over the
+# ten layer cases below: six are bit-identical to the oracle throughout; the others, where one intermediate BF16 value
+# a step off changed some codes downstream, reach 0.0016 .. 0.0033 of the update with 99.74 .. 99.87 % of the elements
+# identical. The bounds are about twice the worst of those.
+LAYER_ERR, LAYER_EXACT = 7e-3, 0.995
+
 
 def bf16_steps(a_bits, b_bits):
     """distance in BF16 steps between two bit patterns of equal sign (or across zero)"""
@@ -120,9 +126,9 @@ def test_gemm_with_gated_activation_epilogue(scale, asym, M, width, K):
                                                     (ref.E8M0_ROUND, 0, 64, 9, 16384), (ref.FP8_E5M2, 1, 64, 70, 8192)])
 def test_rmsnorm_with_the_cast_fused_in(scale, asym, gs, rows, dim, with_residual):
     """RMS normalisation (after an optional residual addition) with the cast of its result in the same kernel. Against
-    the oracle: the normalised row can differ from the oracle's by one BF16 step on a few elements (see above), which changes the codes of those elements and, where it is a
-    group's largest, a scale: codes and scale bytes must agree on all but 1 % of the entries and the dequantized
-    rows to 1 % in norm. Against the three separate calls on the GPU: the same bits everywhere."""
+    the oracle: the normalised row can differ from the oracle's by one BF16 step on a few elements (see above), which
+    changes the codes of those elements and, where it is a group's largest, a scale: codes and scale bytes must agree
+    on all but 1e-4 of the entries and the dequantized rows to 1e-3 in norm (measured values beside the assertions). Against the three separate calls on the GPU: the same bits everywhere."""
     rng = np.random.default_rng(rows + dim)
     x = synth.activations(rows, dim, seed=rows, n_outlier=min(4, dim // 16), outlier_gain=30.0)
     w = (1 + 0.1 * rng.standard_normal(dim)).astype(np.float32)
@@ -141,24 +147,20 @@ def test_rmsnorm_with_the_cast_fused_in(scale, asym, gs, rows, dim, with_residua
     wc, ws = ref.quantize(L.rmsnorm(total_bits, w, 1e-5), gs, scale, asym)
     assert codes.shape == wc.shape and scales.shape == ws.shape
     nib = lambda c: np.stack([c & 15, c >> 4], -1)  # noqa: E731
-    assert float((nib(codes) != nib(wc)).mean()) <= 1e-2 and float((scales != ws).mean()) <= 1e-2
     a, b = ref.dequantize(codes, scales, gs, scale, asym), ref.dequantize(wc, ws, gs, scale, asym)
-    assert G.rel_fro(a, b) <= 1e-2
+    print("rmsnorm_quantize %dx%d gs %d scale %d: codes differ %.2e, scales %.2e, dequantized rows %.2e"
+          % (rows, dim, gs, scale, float((nib(codes) != nib(wc)).mean()), float((scales != ws).mean()), G.rel_fro(a, b)))
+    # measured: ten of the twelve cases identical to the oracle; 300 x 4096 with the residual: 6 codes of 1.2 M
+    # (4.9e-6), one scale byte of 76 800 (1.3e-5), dequantized rows 4.4e-4 apart
+    assert float((nib(codes) != nib(wc)).mean()) <= 1e-4 and float((scales != ws).mean()) <= 1e-4
+    assert G.rel_fro(a, b) <= 1e-3
     # the separate operators
     base = G.to_dev_bf16(x) if y is None else binding.residual_add(G.to_dev_bf16(x), dev_f32(y))
     sc, ss = binding.quantize(fmt, binding.rmsnorm(base, dev_f32(w), 1e-5))
     assert torch.equal(sc, got[0]) and torch.equal(ss, got[1])
 
 
-@pytest.mark.parametrize("fused", [False, True])
-@pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.E8M0_FLOOR, 0)])
-def test_decoder_layer_cut_down(scale, asym, fused):
-    """A layer with the real head size and grouped-query structure but small widths (the oracle runs it in seconds).
-    Quantization makes the layer output a discontinuous function of its intermediates: where an intermediate BF16
-    value differs by one step between the two sides (see above), codes of that group may change, so the outputs are
-    compared in norm, relative to the layer's own update (output - input)."""
-    cfg = layer.LayerConfig(d_model=512, n_heads=4, n_kv_heads=2, head_dim=128, d_ff=1024)
-    S = 256
+def run_layer(cfg, S, scale, asym, fused):
     w = synth.layer_weights(cfg, seed=0)
     x = synth.layer_input(S, cfg.d_model, seed=0)
     fmt = binding.make_format(scale, asym)
@@ -170,6 +172,34 @@ def test_decoder_layer_cut_down(scale, asym, fused):
     want = L.f64_from_bf16(L.decoder_layer(x, w, cfg, scale, asym, fused_attention=fused))
     upd = want - L.f64_from_bf16(x)
     err = np.linalg.norm(got - want) / np.linalg.norm(upd)
-    assert err <= 2e-2, "layer output differs from the oracle by %.4f of the layer's update" % err
     exact = float((got == want).mean())
-    assert exact >= 0.9, "only %.3f of the output elements are bit-identical" % exact
+    print("layer d=%d S=%d scale=%d asym=%d fused=%d: error %.5f of the update, %.4f of the elements bit-identical"
+          % (cfg.d_model, S, scale, asym, fused, err, exact))
+    return err, exact
+
+
+@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.E8M0_FLOOR, 0)])
+def test_decoder_layer_cut_down(scale, asym, fused):
+    """A layer with the real head size and grouped-query structure but small widths (the oracle runs it in seconds).
+    Quantization makes the layer output a discontinuous function of its intermediates: where an intermediate BF16
+    value differs by one step between the two sides (see above), codes of that group may change, so the outputs are
+    compared in norm, relative to the layer's own update (output - input). With 256 tokens every linear layer runs on
+    the few-rows kernel."""
+    cfg = layer.LayerConfig(d_model=512, n_heads=4, n_kv_heads=2, head_dim=128, d_ff=1024)
+    err, exact = run_layer(cfg, 256, scale, asym, fused)
+    assert err <= LAYER_ERR, "layer output differs from the oracle by %.4f of the layer's update" % err
+    assert exact >= LAYER_EXACT, "only %.3f of the output elements are bit-identical" % exact
+
+
+@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.E8M0_FLOOR, 0), (ref.E8M0_FLOOR, 1)])
+def test_decoder_layer_on_the_tiled_kernels(scale, asym, fused):
+    """The same comparison with 640 tokens and twice the widths: M = 640 (2.5 tiles of 256 rows) sends the four linear
+    layers, the gated GEMM and the attention products through the kernels a full-size layer uses: BF16 panels for the
+    FP8-E5M2 scales, the block-scaled FP4 kernel for OCP MXFP4, the merged FP8 kernel for asymmetric power-of-two
+    scales; d_ff = 2816 = 11 tiles of 256 columns."""
+    cfg = layer.LayerConfig(d_model=1024, n_heads=8, n_kv_heads=2, head_dim=128, d_ff=2816)
+    err, exact = run_layer(cfg, 640, scale, asym, fused)
+    assert err <= LAYER_ERR, "layer output differs from the oracle by %.4f of the layer's update" % err
+    assert exact >= LAYER_EXACT, "only %.3f of the output elements are bit-identical" % exact
