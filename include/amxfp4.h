@@ -143,6 +143,28 @@ int amxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const 
                 int64_t batch, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * amxfp4_gemm for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation. Same product, same kernels and same results as
+ * amxfp4_gemm (bit for bit), but the scratch the kernels need (operand panels, partial tiles) is a static device
+ * array inside the library instead of a caller's workspace. The call allocates and frees nothing.
+ *   limit      amxfp4_gemm_workspace_bytes(fmt, M, N, K, batch) must not exceed AMXFP4_GEMM_STATIC_BYTES (16 MiB),
+ *              else AMX_ERR_WORKSPACE and nothing is launched. That covers the few-rows (decoding) shapes
+ *              against any weight matrix, every shape of the power-of-two symmetric format (which needs no scratch),
+ *              and small prefill products; large products on the BF16-panel path need amxfp4_gemm.
+ *   sharing    every call on a GPU uses that GPU's one array, whose contents are undefined between calls (each call
+ *              overwrites what it reads; nothing needs to start at zero). Calls that may execute at the same time on
+ *              one GPU (different streams, or replays of two captured graphs) race on it: keep them on one stream.
+ *   set-up     the array's device address is looked up on the first call on each GPU (no allocation; each GPU holds
+ *              its own copy from the moment the library's code is loaded there until the process ends). Make that
+ *              first call outside stream capture.
+ * Arguments as amxfp4_gemm, without the workspace.
+ */
+#define AMXFP4_GEMM_STATIC_BYTES ((size_t)16 << 20)
+int amxfp4_gemm_static(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                       const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
+                       int64_t batch, void* stream);
+
+/*
  * MXFP4 symmetric baseline: the same three calls with `asymmetric` forced to 0 (one scale per group, Sec. 2.1 /
  * Algorithm 1 with the scale format taken from fmt->scale). All other arguments as above.
  */

@@ -66,6 +66,8 @@ def load():
     L.amxfp4_gemm_workspace_bytes_ex.restype = ctypes.c_size_t
     L.amxfp4_gemm_ex.argtypes = [fp, op, i64, i64, i64, vp, vp, vp, vp, vp, i64, i64, vp, ctypes.c_size_t, vp]
     L.amxfp4_gemm_ex.restype = ctypes.c_int
+    L.amxfp4_gemm_static.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, i64, i64, vp]
+    L.amxfp4_gemm_static.restype = ctypes.c_int
     f32, f64, i32 = ctypes.c_float, ctypes.c_double, ctypes.c_int32
     L.amxfp4_tensor_scale.argtypes = [vp, i64, i64, i64, vp, vp]
     L.amxfp4_quantize_scaled.argtypes = [fp, vp, i64, i64, i64, i64, vp, vp, vp, vp]
@@ -329,6 +331,22 @@ def gemm(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, ba
     _check(_fn(fmt, "gemm", baseline)(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
                                       b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(), out.stride(-2), batch,
                                       ws_ptr, ws_len, _stream()))
+    return out
+
+
+GEMM_STATIC_BYTES = 16 << 20  # AMXFP4_GEMM_STATIC_BYTES of include/amxfp4.h
+
+
+def gemm_static(fmt, a_codes, a_scales, b_codes, b_scales, out):
+    """amxfp4_gemm_static: the product into the caller's `out` (FP32 [.., M, ldc >= N], rows contiguous) with the
+    library's static scratch; nothing is allocated here or in the library."""
+    _need_cuda(a_codes, a_scales, b_codes, b_scales, out)
+    batch = a_codes.shape[0] if a_codes.dim() == 3 else 1
+    M, K = a_codes.shape[-2], a_codes.shape[-1] * 2
+    N = b_codes.shape[-2]
+    _check(load().amxfp4_gemm_static(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
+                                     b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(), out.stride(-2), batch,
+                                     _stream()))
     return out
 
 

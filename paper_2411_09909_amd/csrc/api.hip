@@ -5,9 +5,17 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/amxfp4.h"
 #include "../../include/amxfp4_layer.h"
 #include "kernels.h"
+
+// Scratch of amxfp4_gemm_static, the entry point for callers that cannot allocate: device memory that exists from
+// the moment the code object is loaded on a GPU until the process ends, one copy per GPU. Host code never uses this
+// name as an address (it is a host-side stand-in): static_scratch() below asks the runtime for the device address.
+constexpr size_t kStaticScratchBytes = AMXFP4_GEMM_STATIC_BYTES;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -60,6 +68,27 @@ bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p
 
 int hip_fail(hipError_t e, const char* what) {
   return fail(AMX_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Device address of `scratch` on the current GPU, looked up once per device (every GPU holds its own copy of the
+// array at its own address) and kept: a cache of addresses that never change, not a setting.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(AMX_ERR_UNSUPPORTED, "device ordinal %d beyond %d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return AMX_OK;
 }
 
 }  // namespace
@@ -393,6 +422,25 @@ int amxfp4_gemm_ex(const amx_format_t* fmt, const amx_gemm_options_t* opts, int6
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
   return gemm_impl(*fmt, opts, M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc, batch, workspace,
                    workspace_bytes, stream);
+}
+
+int amxfp4_gemm_static(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                       const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc,
+                       int64_t batch, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  // the size check comes first, on the host, from the same plan amxfp4_gemm would follow
+  if (int rc = check_format(fmt)) return rc;
+  if (int rc = check_shape(*fmt, M, K)) return rc;
+  if (N <= 0 || batch <= 0 || M > kMaxGemmRows || N > kMaxGemmRows || batch > kMaxBatch)
+    return fail(AMX_ERR_INVALID_ARG, "N and batch must be positive and M, N, batch within the limits of amxfp4_gemm");
+  const size_t need = plan_workspace_bytes(plan_gemm(*fmt, nullptr, false, M, N, K, batch), M, N, K, batch);
+  if (need > kStaticScratchBytes)
+    return fail(AMX_ERR_WORKSPACE, "this product needs %zu bytes of scratch; the static array holds %zu (use amxfp4_gemm "
+                "with a workspace)", need, kStaticScratchBytes);
+  void* ptr = nullptr;
+  if (int rc = static_scratch(&ptr)) return rc;
+  return gemm_impl(*fmt, nullptr, M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc, batch, ptr,
+                   kStaticScratchBytes, stream);
 }
 
 int mxfp4_quantize(const amx_format_t* fmt, const void* x_bf16, int64_t rows, int64_t K, int64_t row_stride,
