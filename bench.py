@@ -159,7 +159,10 @@ def main():
     ap.add_argument("--e5m2-kernel", default="panel", choices=["panel", "hybrid", "fused"],
                     help="which of the library's kernels for FP8-E5M2 scales runs the timed GEMM (default: panel)")
     ap.add_argument("--variants", action="store_true",
-                    help="also time the other formats (MXFP4 baselines, power-of-two scales) and list them")
+                    help="time every other format and kernel as well (the block-scaled formats are always listed)")
+    ap.add_argument("--no-variants", action="store_true", help="only the headline format")
+    ap.add_argument("--no-cast-bandwidth", action="store_true",
+                    help="skip the cast's bandwidth measurement over rotating buffers")
     ap.add_argument("--no-measured-peaks", action="store_true",
                     help="skip the register-resident MFMA loops and the streaming copy reported as measured_peaks")
     ap.add_argument("--calib-copy", action="store_true",
@@ -189,17 +192,20 @@ def main():
     C = torch.empty((M, N), dtype=torch.float32, device=dev)
     flops = 2.0 * M * N * K
 
-    def run_format(name, steps, warmup, e5m2_kernel="panel"):
+    def run_format(name, steps, warmup, e5m2_kernel="panel", pot_kernel="merged"):
         """Times `steps` steps (cast X + GEMM against pre-cast W) in the given format; returns a dict of timings.
-        e5m2_kernel: which of the library's three kernels for FP8-E5M2 scales multiplies (ignored by other formats)."""
+        e5m2_kernel: which of the library's three kernels for FP8-E5M2 scales multiplies; pot_kernel: which of the
+        kernels for asymmetric power-of-two scales (both ignored by the other formats)."""
         kind, asym, mfma, peak = FORMATS[name]
+        if name == "amxfp4_e8m0" and pot_kernel == "split":
+            mfma, peak = "fp4", PEAK_FP4_TFLOPS
         scaled = name in DOUBLE_SCALED
         gs = 16 if scaled else args.group_size
         if gs != 32:
             mfma, peak, e5m2_kernel = "bf16", PEAK_BF16_TFLOPS, "panel"
         if kind == 2 and e5m2_kernel != "panel":
             mfma = "f16"
-        opts = None if scaled else binding.gemm_options(e5m2_kernel=e5m2_kernel)
+        opts = None if scaled else binding.gemm_options(e5m2_kernel=e5m2_kernel, pot_kernel=pot_kernel)
         fmt = binding.make_format(kind, asym, gs)
         nsc = (M, K // gs, 2) if asym else (M, K // gs)
         xc = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
@@ -248,6 +254,47 @@ def main():
         return {"t_step": t_total / steps, "kern_ms": kern_ms, "t_cast_x": t_cast_x, "t_cast_w": t_cast_w,
                 "mfma": mfma, "peak": peak, "asym": asym, "workspace_bytes": need}
 
+    def cast_bandwidth(name, reps=20):
+        """The cast of X timed three ways, as GB/s of algorithmic bytes (2 B read + 0.5 B codes + scale bytes per
+        element): on ONE buffer re-cast back to back, whose 67 MB stay in the 256 MB last-level cache between launches
+        ("cached"); rotating over enough distinct copies of X that more than 512 MB pass between two casts of the
+        same buffer, so every read comes from HBM ("hbm"); and the cast of the weights, 470 MB read per launch
+        ("weights")."""
+        kind, asym, _, _ = FORMATS[name]
+        gs = 16 if name in DOUBLE_SCALED else args.group_size
+        fmt = binding.make_format(kind, asym, gs)
+        x_bytes = M * K * 2
+        copies = max(2, -(-(640 << 20) // x_bytes))   # ceil(640 MiB / |X|): 10 copies of the 64 MiB headline X
+        xs_rot = [xd.clone() for _ in range(copies)]
+        codes = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+        scales = torch.empty((M, K // gs, 2) if asym else (M, K // gs), dtype=torch.uint8, device=dev)
+
+        def timed(fn, n):
+            fn(0)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(n):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e-3 / n
+
+        def per_elem(rows):
+            return rows * K * 2 + rows * K // 2 + rows * (K // gs) * (2 if asym else 1)
+
+        t_cached = timed(lambda i: binding.quantize(fmt, xd, codes=codes, scales=scales), reps)
+        t_hbm = timed(lambda i: binding.quantize(fmt, xs_rot[i % copies], codes=codes, scales=scales), reps * 2)
+        wcodes = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+        wscales = torch.empty((N, K // gs, 2) if asym else (N, K // gs), dtype=torch.uint8, device=dev)
+        t_w = timed(lambda i: binding.quantize(fmt, wd, codes=wcodes, scales=wscales), 5)
+        return {"unit": "GB/s of algorithmic bytes (2.5625 B per element for the asymmetric format)",
+                "x_cached": round(per_elem(M) / t_cached / 1e9, 1), "x_cached_us": round(t_cached * 1e6, 2),
+                "x_hbm": round(per_elem(M) / t_hbm / 1e9, 1), "x_hbm_us": round(t_hbm * 1e6, 2),
+                "x_hbm_rotation": "%d buffers, %.0f MB" % (copies, copies * x_bytes / 1e6),
+                "weights": round(per_elem(N) / t_w / 1e9, 1), "weights_us": round(t_w * 1e6, 1),
+                "frac_of_hbm_peak": round(per_elem(M) / t_hbm / 1e9 / 8000.0, 4)}
+
     r = run_format(args.format, args.steps, args.warmup, args.e5m2_kernel)
     ms_per_step = r["t_step"] * 1e3
     value = flops / r["t_step"] / 1e12
@@ -292,22 +339,33 @@ def main():
         "breakdown_ms": {"cast_x": round(r["t_cast_x"] * 1e3, 4),
                          "gemm_call": round(ms_per_step - r["t_cast_x"] * 1e3, 4),
                          "gemm_mfma_kernel": round(r["kern_ms"], 4), "cast_w_once": round(r["t_cast_w"] * 1e3, 3)},
-        "cast_x_gbps": round(cast_bytes / r["t_cast_x"] / 1e9, 1),
+        # the cast inside the timed step re-reads one buffer that the last-level cache holds: a cached figure
+        "cast_x_gbps_cached_in_step": round(cast_bytes / r["t_cast_x"] / 1e9, 1),
     }
+    if not args.no_cast_bandwidth:
+        out["cast_bandwidth"] = cast_bandwidth(args.format)
+    # The formats that run on the block-scaled matrix instructions are part of every run (about ten steps each): OCP
+    # MXFP4 and the asymmetric power-of-two format, each with its GEMM kernel's time and fraction of the peak of the
+    # MFMA type it issues. --variants adds the rest.
+    cases = [("mxfp4_e8m0", "panel", "merged"), ("amxfp4_e8m0", "panel", "merged"), ("amxfp4_e8m0", "panel", "split")]
     if args.variants:
-        out["variants"] = {}
-        cases = [(name, "panel") for name in sorted(FORMATS)]
-        cases += [(name, k) for name in ("amxfp4_e5m2", "mxfp4_e5m2") for k in ("hybrid", "fused")]
-        for name, kern in cases:
-            if name == args.format and kern == args.e5m2_kernel:
-                continue
-            v = run_format(name, max(3, args.steps // 2), max(2, args.warmup // 2), kern)
-            out["variants"][name if kern == "panel" else "%s[%s]" % (name, kern)] = {"value": round(flops / v["t_step"] / 1e12, 2), "unit": "TFLOP/s",
-                                     "ms_per_step": round(v["t_step"] * 1e3, 4), "mfma": v["mfma"],
-                                     "workspace_MB": round(v["workspace_bytes"] / 1e6, 1),
-                                     "gemm_kernel_ms": round(v["kern_ms"], 4),
-                                     "kernel_frac_of_mfma_peak": round(flops / (v["kern_ms"] * 1e-3) / 1e12 /
-                                                                       v["peak"], 4)}
+        cases += [(name, "panel", "merged") for name in sorted(FORMATS) if name not in ("mxfp4_e8m0", "amxfp4_e8m0")]
+        cases += [(name, k, "merged") for name in ("amxfp4_e5m2", "mxfp4_e5m2") for k in ("hybrid", "fused")]
+    if args.no_variants or args.group_size != 32:
+        cases = []
+    v_steps = max(3, min(args.steps, 10)) if not args.variants else max(3, args.steps // 2)
+    v_warm = max(2, min(args.warmup, 5)) if not args.variants else max(2, args.warmup // 2)
+    for name, kern, pot in cases:
+        if name == args.format and kern == args.e5m2_kernel and pot == "merged":
+            continue
+        v = run_format(name, v_steps, v_warm, kern, pot)
+        label = name + ("[%s]" % kern if kern != "panel" else "") + ("[%s]" % pot if pot != "merged" else "")
+        out.setdefault("variants", {})[label] = {
+            "value": round(flops / v["t_step"] / 1e12, 2), "unit": "TFLOP/s",
+            "frac_of_fp4_mfma_peak": round(flops / v["t_step"] / 1e12 / PEAK_FP4_TFLOPS, 4),
+            "ms_per_step": round(v["t_step"] * 1e3, 4), "steps": v_steps, "mfma": v["mfma"],
+            "workspace_MB": round(v["workspace_bytes"] / 1e6, 1), "gemm_kernel_ms": round(v["kern_ms"], 4),
+            "kernel_frac_of_mfma_peak": round(flops / (v["kern_ms"] * 1e-3) / 1e12 / v["peak"], 4)}
     if not args.no_measured_peaks:
         out["measured_peaks"] = measured_peaks(binding, torch, xd, wd, dev)
     if args.calib_copy:

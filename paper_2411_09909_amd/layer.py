@@ -143,11 +143,15 @@ class DecoderLayer:
             act = binding.silu_mul(self._gemm(hc, self.wgu))
         return binding.residual_add(x2, self._gemm(self._cast(act), self.wd))
 
-    def matmul_flops(self, S):
-        """2 * M * N * K summed over the seven quantized matmuls (attention products counted in full, no causal
-        skipping: that is what runs)."""
+    def matmul_flops(self, S, nominal=False):
+        """2 * M * N * K summed over the seven quantized matmuls, counting what this layer EXECUTES: with the
+        materialised map both attention products run in full (no causal skipping); the fused attention skips the key
+        tiles of 32 that lie wholly behind the causal mask of a block of 32 queries, so a head multiplies
+        S * (S + 32) / 2 query-key pairs instead of S * S. nominal=True counts the attention products in full
+        whatever runs (the figure a dense-attention layer would be credited with)."""
         c = self.cfg
         W, F, kv = c.n_heads * c.head_dim, c.d_ff, c.n_kv_heads * c.head_dim
         lin = S * c.d_model * (W + 2 * kv) + S * W * c.d_model + S * c.d_model * 2 * F + S * F * c.d_model
-        att = 2 * c.n_heads * S * S * c.head_dim
+        pairs = S * (S + 32) // 2 if (self.fused_attention and not nominal) else S * S
+        att = 2 * c.n_heads * pairs * c.head_dim
         return 2.0 * (lin + att)

@@ -4,7 +4,8 @@ layer (torch matmuls in BF16, FP32 softmax) on the same random-init weights and 
 
     python -m paper_2411_09909_amd.layer_bench [--seq 8192] [--steps 5]
 
-Prints one JSON object: per format the time of a forward pass, useful TFLOP/s over the seven quantized matmuls, and
+Prints one JSON object: per format the time of a forward pass, TFLOP/s over the flops the seven quantized matmuls
+execute (the fused attention skips key tiles behind the causal mask; the dense-attention credit is listed beside it), and
 the mean squared error of the layer output against the BF16 reference (lower is better; the paper's argument is that
 the asymmetric scales lower it at equal bit width, Sec. 4.2 / Table 2 for model-level perplexity).
 """
@@ -93,7 +94,11 @@ def main():
         dt = (time.perf_counter() - t0) / args.steps
         mse = (y.to(torch.float32) - ref_out).pow(2).mean().item()
         out["formats"][name] = {"ms_per_layer": round(dt * 1e3, 3),
+                                # flops the layer executes (the fused attention skips the masked key tiles) ...
                                 "matmul_TFLOPs": round(lay.matmul_flops(args.seq) / dt / 1e12, 1),
+                                # ... and with the attention products counted in full whatever runs
+                                "matmul_TFLOPs_dense_attention_credit": round(
+                                    lay.matmul_flops(args.seq, nominal=True) / dt / 1e12, 1),
                                 "mse_vs_bf16": mse, "mse_over_update": mse / upd}
         del lay, y
         torch.cuda.empty_cache()
