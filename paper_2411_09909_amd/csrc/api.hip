@@ -199,11 +199,12 @@ GemmPlan plan_gemm(const amx_format_t& f, const amx_gemm_options_t* o, bool scal
   return p;
 }
 
-size_t plan_workspace_bytes(const GemmPlan& p, int64_t M, int64_t N, int64_t K, int64_t batch) {
+size_t plan_workspace_bytes(const GemmPlan& p, bool asym, int64_t M, int64_t N, int64_t K, int64_t batch) {
   switch (p.kernel) {
     case kGemmSkinny: return amx::skinny_path_workspace_bytes(M, N, K, batch, p.skinny_slices);
     case kGemmFp8Merged: return amx::fp8m_path_workspace_bytes(M, N, K, batch);
-    case kGemmFp4: case kGemmE5m2Fused: return 0;
+    case kGemmFp4: return amx::fp4_path_workspace_bytes(asym, M, N, K, batch);
+    case kGemmE5m2Fused: return 0;
     case kGemmE5m2Hybrid: return amx::e5m2_hybrid_workspace_bytes(M, K, batch);
     default: return amx::bf16_path_workspace_bytes(M, N, K, batch);
   }
@@ -229,7 +230,7 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
       !aligned(C, 4))
     return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales and C 4-byte alignment");
   const GemmPlan plan = plan_gemm(f, opts, scaled, M, N, K, batch);
-  const size_t need = plan_workspace_bytes(plan, M, N, K, batch);
+  const size_t need = plan_workspace_bytes(plan, f.asymmetric != 0, M, N, K, batch);
   if (need > 0) {
     if (!workspace || workspace_bytes < need)
       return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
@@ -249,7 +250,8 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
       e = amx::launch_gemm_fp8m_path(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, hs, timer);
       break;
     case kGemmFp4:
-      e = amx::launch_gemm_fp4_path(asym, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, hs, timer);
+      e = amx::launch_gemm_fp4_path(asym, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, hs,
+                                    timer);
       break;
     case kGemmE5m2Fused:
       e = amx::launch_gemm_e5m2_fused(asym, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, hs, timer);
@@ -273,7 +275,7 @@ GemmPlan plan_glu(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
   return p;
 }
 size_t glu_workspace_bytes(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  return plan_workspace_bytes(plan_glu(f, M, N, K), M, N, K, 1);
+  return plan_workspace_bytes(plan_glu(f, M, N, K), f.asymmetric != 0, M, N, K, 1);
 }
 
 amx_format_t symmetric(const amx_format_t* f) {
@@ -307,7 +309,7 @@ size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
 size_t amxfp4_gemm_workspace_bytes_ex(const amx_format_t* fmt, const amx_gemm_options_t* opts, int64_t M, int64_t N,
                                       int64_t K, int64_t batch) {
   if (!fmt || M <= 0 || N <= 0 || K <= 0 || batch <= 0 || check_options(opts)) return 0;
-  return plan_workspace_bytes(plan_gemm(*fmt, opts, false, M, N, K, batch), M, N, K, batch);
+  return plan_workspace_bytes(plan_gemm(*fmt, opts, false, M, N, K, batch), fmt->asymmetric != 0, M, N, K, batch);
 }
 
 size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch) {
@@ -392,7 +394,7 @@ int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int6
   }
   if (glu_kernel == kGemmFp4) {
     hipError_t e = amx::launch_gemm_fp4_path(f.asymmetric != 0, M, 2 * width, K, A_codes, A_scales, B_codes, B_scales,
-                                             out, ld_out, 1, hs, timer, true);
+                                             out, ld_out, 1, workspace, hs, timer, true);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
   }
   hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, f.group_size, M, 2 * width, K, A_codes, A_scales,
@@ -433,7 +435,7 @@ int amxfp4_gemm_static(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K,
   if (int rc = check_shape(*fmt, M, K)) return rc;
   if (N <= 0 || batch <= 0 || M > kMaxGemmRows || N > kMaxGemmRows || batch > kMaxBatch)
     return fail(AMX_ERR_INVALID_ARG, "N and batch must be positive and M, N, batch within the limits of amxfp4_gemm");
-  const size_t need = plan_workspace_bytes(plan_gemm(*fmt, nullptr, false, M, N, K, batch), M, N, K, batch);
+  const size_t need = plan_workspace_bytes(plan_gemm(*fmt, nullptr, false, M, N, K, batch), fmt->asymmetric != 0, M, N, K, batch);
   if (need > kStaticScratchBytes)
     return fail(AMX_ERR_WORKSPACE, "this product needs %zu bytes of scratch; the static array holds %zu (use amxfp4_gemm "
                 "with a workspace)", need, kStaticScratchBytes);

@@ -10,9 +10,15 @@
 //
 // Operand fragment of the instruction for FP4: lane l holds row l%32, K block l/32 (32 codes = 16 bytes, element k in
 // bits 4k+3:4k), and supplies the scale byte of that (row, K block) in a VGPR byte picked by the instruction's opsel.
-// The canonical code layout already has those 16 bytes contiguous, so tiles are staged straight from the caller's
-// arrays by direct-to-LDS buffer loads with per-lane offsets (no re-layout pass, no workspace).
-// One stage = K slice of 128 (2 MFMA k-steps of 64): same byte count and LDS ring as the BF16 kernel.
+// The canonical code layout already has those 16 bytes contiguous, so the code tiles are staged straight from the
+// caller's arrays by direct-to-LDS buffer loads with per-lane offsets (no re-layout of the codes).
+// The scale bytes are different: a lane needs the 8 bytes of ITS row for the stage, and in the canonical layout the 32
+// rows of a fragment lie a whole scale row apart, so a wave's fetch would touch 32 cache lines for 256 useful bytes,
+// 256 line requests per wave and stage against the 128 of the codes themselves. That gather kept the vector memory
+// path busy and the matrix pipe waiting (measured: the kernel with nothing but its MFMAs and these loads took 0.40 ms
+// at the headline shape, 0.31 ms with the loads taken out). A small pass (scale_pack_kernel) therefore re-lays the
+// scale bytes into the workspace in the order the waves read them, and a wave fetches the scales of its four row
+// blocks for a stage with two (asymmetric: four) fully coalesced 16-byte loads.
 #include "device_formats.h"
 #include "gemm_common.h"
 
@@ -41,6 +47,46 @@ __device__ __forceinline__ u32x4 sign_class4(u32x4 v) {
   return r;
 }
 
+// Packed scales: [batch][rows / 128][stage = K / 256][row r of 32][row block i of 4][8 groups][1 or 2 bytes]. Entry
+// (r, i) of row group q is row 128 q + 32 i + r; rows beyond the operand and groups beyond K hold byte 0 (2^-127: the
+// products of the zero codes staged for them vanish). A wave (128 rows) reads one stage as 1 or 2 KiB, contiguous.
+constexpr int kScaleRows = 128;
+constexpr int fp4_scale_stage_bytes(bool asym) { return 32 * 4 * 8 * (asym ? 2 : 1); }
+
+static int64_t fp4_packed_scale_bytes(bool asym, int64_t rows, int64_t K) {
+  return (round_up(rows, kPanelRows) / kScaleRows) * ((K + 255) / 256) * fp4_scale_stage_bytes(asym);
+}
+
+size_t fp4_path_workspace_bytes(bool asym, int64_t M, int64_t N, int64_t K, int64_t batch) {
+  return (size_t)(batch * (fp4_packed_scale_bytes(asym, M, K) + fp4_packed_scale_bytes(asym, N, K)));
+}
+
+// grid: (ceil(rows_p * stages / 256), 1, batch); one thread per (row, stage), stages fastest so that a wave reads
+// consecutive bytes of a scale row. SB: bytes per group (1 symmetric, 2 asymmetric).
+template <int SB>
+__global__ __launch_bounds__(256) void scale_pack_kernel(const uint8_t* __restrict__ scales, int64_t R, int64_t G,
+                                                         int64_t Rp, int nstages, uint8_t* __restrict__ packed) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= Rp * nstages) return;
+  const int64_t row = idx / nstages, b = blockIdx.z;
+  const int st = (int)(idx - row * nstages);
+  uint32_t w[2 * SB] = {};
+  if (row < R) {
+    // (scale rows are 4-byte aligned: G is a multiple of 4)
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(scales + ((b * R + row) * G + (int64_t)st * 8) * SB);
+    const int words = (int)((G - (int64_t)st * 8 >= 8 ? 8 : G - (int64_t)st * 8) * SB / 4);
+#pragma unroll
+    for (int i = 0; i < 2 * SB; ++i)
+      if (i < words) w[i] = src[i];
+  }
+  const int64_t q = row / kScaleRows;
+  const int i = (int)(row % kScaleRows) / 32, r = (int)(row % 32);
+  uint32_t* dst = reinterpret_cast<uint32_t*>(packed + ((b * (Rp / kScaleRows) + q) * nstages + st) * (32 * 4 * 8 * SB) +
+                                              (r * 4 + i) * 8 * SB);
+#pragma unroll
+  for (int j = 0; j < 2 * SB; ++j) dst[j] = w[j];
+}
+
 // One stage = a K slice of 256: 128 bytes = one whole cache line of every code row (a compute unit's vector cache
 // tracks a limited number of line requests, so fetching half lines would halve what it can pull from the L2).
 // LDS: two stage buffers of 64 KiB (A rows then B rows, 128 bytes per row). A stage is 4 k-steps x FM steps of FN
@@ -51,9 +97,9 @@ __device__ __forceinline__ u32x4 sign_class4(u32x4 v) {
 // GLU: the gated-activation epilogue of store_glu_tiles() (gemm_common.h); C is then the BF16 output [M][ldc].
 template <int WM, int WN, int FM, int FN, bool ASYM, bool GLU = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* __restrict__ Ac,
-                                                                const uint8_t* __restrict__ As,
+                                                                const uint8_t* __restrict__ Asp,
                                                                 const uint8_t* __restrict__ Bc,
-                                                                const uint8_t* __restrict__ Bs, float* __restrict__ C,
+                                                                const uint8_t* __restrict__ Bsp, float* __restrict__ C,
                                                                 int64_t M, int64_t N, int64_t K, int64_t ldc,
                                                                 int tiles_m, int tiles_n, int super_m) {
   using Cfg = TileCfg<WM, WN, FM, FN>;
@@ -89,9 +135,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   int tm, tn;
   if (!tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, super_m, tm, tn)) return;  // uniform, before any barrier
 
-  constexpr int kScaleBytes = ASYM ? 2 : 1;                    // per group
   const int row_bytes = (int)(K >> 1);                         // codes per row
-  const int srow_bytes = (int)(K >> 5) * kScaleBytes;          // scale bytes per row
+  const int nstages_all = (int)((K + 255) >> 8);               // stages of the packed scales (the last may be half)
   const int rows_a = (int)(M - (int64_t)tm * kTileM < kTileM ? M - (int64_t)tm * kTileM : kTileM);
   const int rows_b = (int)(N - (int64_t)tn * kTileN < kTileN ? N - (int64_t)tn * kTileN : kTileN);
 
@@ -101,10 +146,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
       const_cast<uint8_t*>(Ac + (b * M + (int64_t)tm * kTileM) * row_bytes), 0, rows_a * row_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t Br = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t*>(Bc + (b * N + (int64_t)tn * kTileN) * row_bytes), 0, rows_b * row_bytes, 0x00020000);
+  // packed scales of this wave's 128 rows of either operand: [stage][32 rows][4 row blocks][8 groups] entries
+  constexpr int kStageScaleBytes = fp4_scale_stage_bytes(ASYM);
+  const int64_t groups_m = (int64_t)tiles_m * (kTileM / kScaleRows), groups_n = (int64_t)tiles_n * (kTileN / kScaleRows);
   const __amdgpu_buffer_rsrc_t Asr = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t*>(As + (b * M + (int64_t)tm * kTileM) * srow_bytes), 0, rows_a * srow_bytes, 0x00020000);
+      const_cast<uint8_t*>(Asp + ((b * groups_m + (int64_t)tm * (kTileM / kScaleRows) + wm) * nstages_all) *
+                                     kStageScaleBytes),
+      0, nstages_all * kStageScaleBytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t Bsr = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t*>(Bs + (b * N + (int64_t)tn * kTileN) * srow_bytes), 0, rows_b * srow_bytes, 0x00020000);
+      const_cast<uint8_t*>(Bsp + ((b * groups_n + (int64_t)tn * (kTileN / kScaleRows) + wn) * nstages_all) *
+                                     kStageScaleBytes),
+      0, nstages_all * kStageScaleBytes, 0x00020000);
 
   // Staging geometry. One direct-to-LDS load moves 8 rows x 128 bytes (8 lanes per row). Its LDS image is [8 rows]
   // [8 chunks of 16 bytes]; the chunk a lane fetches is permuted by the row, chunk = slot ^ ((row >> 1) & 7), so that
@@ -113,7 +165,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   // / 2, and u & 1 = wave & 1 for every unit of a wave.
   const int kb = lane >> 5;  // K block (of 32 codes) of this lane inside a 64-wide k-step
   const int gather_off = (lane >> 3) * row_bytes + (((lane & 7) ^ (4 * (wave & 1) + ((lane >> 4) & 3))) << 4);
-  const int sgather_off = (lane & 31) * srow_bytes;
+  const int sgather_off = (lane & 31) * (kStageScaleBytes / 32);  // this lane's row inside a stage of packed scales
   // fragment read offset inside a row block (32 rows x 128 bytes) for k-step ks: chunk 2 ks + kb of row lane % 32
   const int rr = lane & 31;
   const int frag_row = rr * 128, frag_swz = (rr >> 1) & 7;
@@ -144,27 +196,28 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   }
 
   // Scale words of one stage (8 groups of this lane's row), per row block: symmetric = 8 bytes (one per group),
-  // asymmetric = 16 bytes ((pos, neg) per group). Two register sets alternate between stages.
+  // asymmetric = 16 bytes ((pos, neg) per group); the four row blocks of a wave lie side by side in the packed array,
+  // so a lane fetches them with two (four) 16-byte loads. Two register sets alternate between stages.
+  static_assert(FM == 4 && FN == 4, "the packed scales hold four row blocks per wave");
   typedef uint32_t sword_t __attribute__((ext_vector_type(ASYM ? 4 : 2)));
   sword_t sa[2][FM], sb[2][FN];
-#define AMX_LOAD_SCALES(SET, ST)                                                                                    \
+#define AMX_LOAD_SCALES_OF(DSTV, RSRC, ST)                                                                          \
   {                                                                                                                 \
-    _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                                                \
-      if constexpr (ASYM)                                                                                           \
-        sa[SET][i] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b128(                             \
-                                                     Asr, sgather_off + (ST) * 16, (wm * FM + i) * 32 * srow_bytes, 0)); \
-      else                                                                                                          \
-        sa[SET][i] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b64(                              \
-                                                     Asr, sgather_off + (ST) * 8, (wm * FM + i) * 32 * srow_bytes, 0));  \
+    if constexpr (ASYM) {                                                                                           \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) DSTV[i] = __builtin_bit_cast(                                   \
+          sword_t, __builtin_amdgcn_raw_buffer_load_b128(RSRC, sgather_off + i * 16, (ST) * kStageScaleBytes, 0));  \
+    } else {                                                                                                        \
+      _Pragma("unroll") for (int i = 0; i < 4; i += 2) {                                                            \
+        const u32x4 w_ = __builtin_bit_cast(                                                                        \
+            u32x4, __builtin_amdgcn_raw_buffer_load_b128(RSRC, sgather_off + i * 8, (ST) * kStageScaleBytes, 0));   \
+        DSTV[i][0] = w_.x, DSTV[i][1] = w_.y, DSTV[i + 1][0] = w_.z, DSTV[i + 1][1] = w_.w;                         \
+      }                                                                                                             \
     }                                                                                                               \
-    _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                                                \
-      if constexpr (ASYM)                                                                                           \
-        sb[SET][j] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b128(                             \
-                                                     Bsr, sgather_off + (ST) * 16, (wn * FN + j) * 32 * srow_bytes, 0)); \
-      else                                                                                                          \
-        sb[SET][j] = __builtin_bit_cast(sword_t, __builtin_amdgcn_raw_buffer_load_b64(                              \
-                                                     Bsr, sgather_off + (ST) * 8, (wn * FN + j) * 32 * srow_bytes, 0));  \
-    }                                                                                                               \
+  }
+#define AMX_LOAD_SCALES(SET, ST)             \
+  {                                          \
+    AMX_LOAD_SCALES_OF(sa[SET], Asr, ST);    \
+    AMX_LOAD_SCALES_OF(sb[SET], Bsr, ST);    \
   }
 
   const int nfull = (int)(K >> 8);  // whole stages; K % 256 == 128 leaves half a stage for the end
@@ -289,6 +342,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
 #undef AMX_STAGE
 #undef AMX_MMA
 #undef AMX_LOAD_SCALES
+#undef AMX_LOAD_SCALES_OF
 #undef AMX_ISSUE_LOAD
 #undef AMX_FRAG_OFF
 #undef AMX_LDS_READ
@@ -320,20 +374,31 @@ bool fp4_path_supported(int64_t M, int64_t N, int64_t K) {
 
 template <bool ASYM>
 static hipError_t launch_fp4(int64_t M, int64_t N, int64_t K, const uint8_t* Ac, const uint8_t* As, const uint8_t* Bc,
-                             const uint8_t* Bs, float* C, int64_t ldc, int64_t batch, hipStream_t s,
+                             const uint8_t* Bs, float* C, int64_t ldc, int64_t batch, void* workspace, hipStream_t s,
                              const KernelTimer& timer, bool glu) {
   using Cfg = TileCfg<2, 2, 4, 4>;
   const int tiles_m = (int)((M + Cfg::kTileM - 1) / Cfg::kTileM), tiles_n = (int)((N + Cfg::kTileN - 1) / Cfg::kTileN);
   int super_m;
   const unsigned grid = supertile_grid(tiles_m, tiles_n, super_m);
-  hipError_t e;
+  // the scale bytes of both operands, re-laid in the order the waves fetch them
+  constexpr int SB = ASYM ? 2 : 1;
+  const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows), G = K >> 5;
+  const int nstages = (int)((K + 255) / 256);
+  uint8_t* Asp = reinterpret_cast<uint8_t*>(workspace);
+  uint8_t* Bsp = Asp + batch * fp4_packed_scale_bytes(ASYM, M, K);
+  hipLaunchKernelGGL((scale_pack_kernel<SB>), dim3((unsigned)((Mp * nstages + 255) / 256), 1, (unsigned)batch),
+                     dim3(256), 0, s, As, M, G, Mp, nstages, Asp);
+  hipLaunchKernelGGL((scale_pack_kernel<SB>), dim3((unsigned)((Np * nstages + 255) / 256), 1, (unsigned)batch),
+                     dim3(256), 0, s, Bs, N, G, Np, nstages, Bsp);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
   if (glu)
     hipLaunchKernelGGL((gemm_fp4_kernel<2, 2, 4, 4, ASYM, true>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads),
-                       0, s, Ac, As, Bc, Bs, C, M, N, K, ldc, tiles_m, tiles_n, super_m);
+                       0, s, Ac, Asp, Bc, Bsp, C, M, N, K, ldc, tiles_m, tiles_n, super_m);
   else
     hipLaunchKernelGGL((gemm_fp4_kernel<2, 2, 4, 4, ASYM>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s,
-                       Ac, As, Bc, Bs, C, M, N, K, ldc, tiles_m, tiles_n, super_m);
+                       Ac, Asp, Bc, Bsp, C, M, N, K, ldc, tiles_m, tiles_n, super_m);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (timer.stop) e = hipEventRecord(timer.stop, s);
   return e;
@@ -341,9 +406,10 @@ static hipError_t launch_fp4(int64_t M, int64_t N, int64_t K, const uint8_t* Ac,
 
 hipError_t launch_gemm_fp4_path(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
-                                int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer, bool glu) {
-  return asym ? launch_fp4<true>(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, s, timer, glu)
-              : launch_fp4<false>(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, s, timer, glu);
+                                int64_t ldc, int64_t batch, void* workspace, hipStream_t s, const KernelTimer& timer,
+                                bool glu) {
+  return asym ? launch_fp4<true>(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, s, timer, glu)
+              : launch_fp4<false>(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, s, timer, glu);
 }
 
 }  // namespace amx

@@ -89,12 +89,14 @@ hipError_t launch_expand_half_line(int scale_kind, bool asym, const uint8_t* cod
 hipError_t launch_expand_f16_e5m2(bool asym, const uint8_t* codes, const uint8_t* scales, int64_t R, int64_t K,
                                   int64_t Rp, int64_t Kp, int64_t batch, uint16_t* panel, hipStream_t s);
 
-// gemm_fp4.hip: power-of-two scales on the block-scaled FP4 MFMA (no workspace). glu here and below: as for the
-// BF16 path
+// gemm_fp4.hip: power-of-two scales on the block-scaled FP4 MFMA (workspace: the scale bytes re-laid in the order the
+// waves fetch them). glu here and below: as for the BF16 path
 bool fp4_path_supported(int64_t M, int64_t N, int64_t K);
+size_t fp4_path_workspace_bytes(bool asym, int64_t M, int64_t N, int64_t K, int64_t batch);
 hipError_t launch_gemm_fp4_path(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
                                 const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, float* C,
-                                int64_t ldc, int64_t batch, hipStream_t s, const KernelTimer& timer, bool glu = false);
+                                int64_t ldc, int64_t batch, void* workspace, hipStream_t s, const KernelTimer& timer,
+                                bool glu = false);
 
 // gemm_fp8m.hip: asymmetric power-of-two scales merged per group into E5M2 elements + one anchor scale, block-scaled
 // FP8 MFMA (workspace: the merged panels)

@@ -47,8 +47,10 @@ def test_size_queries(lib):
     # workspace: BF16 panels padded to 256 rows / 128 columns of K
     assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == (512 + 1024) * 1024 * 2
     assert binding.gemm_workspace_bytes(f, 300, 10, 96, 2) == 2 * (512 + 256) * 128 * 2
-    # power-of-two scales with K % 128 == 0 run on the FP4 MFMA straight from the caller's arrays: no workspace
-    assert binding.gemm_workspace_bytes(g, 300, 1024, 1024) == 0
+    # power-of-two scales with K % 128 == 0 run on the FP4 MFMA with the codes read in place; the workspace holds the
+    # scale bytes re-laid per 128 rows (padded to 256) and K stage of 256: 1 KiB each
+    assert binding.gemm_workspace_bytes(g, 300, 1024, 1024) == (512 + 1024) // 128 * 4 * 1024
+    assert binding.gemm_workspace_bytes(g, 300, 1024, 384, 3) == 3 * (512 + 1024) // 128 * 2 * 1024
     assert binding.gemm_workspace_bytes(g, 64, 1024, 96) == (256 + 1024) * 128 * 2
     # M <= 256 with K % 256 == 0, any scale format: only A's panel (rows padded to 32) and, when K is cut into outer
     # slices (here 4 blocks of 256 -> 4 slices, 8 workgroups each), the partial tiles
@@ -75,7 +77,8 @@ def test_kernel_options_are_per_call_and_the_workspace_query_is_pure(lib):
     g = binding.make_format(binding.E8M0_FLOOR, True)
     merged = (512 + 1024) * 1024 + (512 + 1024) // 32 * (1024 // 256) * 256
     assert binding.gemm_workspace_bytes(g, 300, 1024, 1024) == merged
-    assert binding.gemm_workspace_bytes(g, 300, 1024, 1024, options=binding.gemm_options(pot_kernel="split")) == 0
+    assert (binding.gemm_workspace_bytes(g, 300, 1024, 1024, options=binding.gemm_options(pot_kernel="split"))
+            == (512 + 1024) // 128 * 4 * 2048)   # the sign-split FP4 kernel: re-laid scale pairs only
     # few rows: without that kernel the panel path's workspace; with a forced slice count its partial tiles
     assert binding.gemm_workspace_bytes(f, 64, 1024, 1024, options=binding.gemm_options(few_rows=-1)) == (256 + 1024) * 1024 * 2
     assert binding.gemm_workspace_bytes(f, 64, 1024, 1024, options=binding.gemm_options(few_rows=2)) == 64 * 1024 * 2 + 2 * 64 * 1024 * 4
@@ -181,7 +184,7 @@ def test_gated_gemm_rejects_bad_arguments(lib):
     q = lib.amxfp4_gemm_silu_mul_workspace_bytes
     assert q(ctypes.byref(ok), 64, 64, 64) == (256 + 256) * 128 * 2                    # both BF16 panels, padded
     pot = binding.make_format(binding.E8M0_FLOOR, False, 32)
-    assert q(ctypes.byref(pot), 64, 64, 128) == 0                                      # codes go to the FP4 MFMA as they are
+    assert q(ctypes.byref(pot), 64, 64, 128) == (256 + 256) // 128 * 1024                # FP4 MFMA: re-laid scale bytes only
     assert q(ctypes.byref(ok), 64, 48, 64) == 0 and q(None, 64, 64, 64) == 0
 
 
