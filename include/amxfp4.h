@@ -43,7 +43,7 @@
  *     only state is per host thread (the message of amxfp4_last_error and the event pair armed by
  *     amxfp4_profile_next_gemm), so the entry points may be called from several threads at once.
  *   - size limits (AMX_ERR_INVALID_ARG beyond them): K <= 2^20 for every operand; rows of a cast <= 2^31 - 1
- *     (16 776 960 when the groups run down a strided axis); M and N of a GEMM <= 2^21 - 256; batch <= 65535.
+ *     (16 776 960 when the groups run down a strided axis); M and N of a GEMM <= 2^21 - 256, ldc <= 2^22; batch <= 65535.
  *     Zero-sized operands are invalid arguments, not no-ops.
  */
 #ifndef AMXFP4_H

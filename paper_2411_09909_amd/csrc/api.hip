@@ -36,6 +36,7 @@ constexpr int64_t kMaxCastRows = (int64_t(1) << 31) - 1;
 constexpr int64_t kMaxStridedRows = 65535 * 256;
 constexpr int64_t kMaxGemmRows = (int64_t(1) << 21) - 256;
 constexpr int64_t kMaxBatch = 65535;
+constexpr int64_t kMaxLdc = int64_t(1) << 22;  // the kernels address a wave's window of C with 32-bit byte offsets
 
 // Validates a format for the GPU library. Returns AMX_OK or a negative status (message set).
 int check_format(const amx_format_t* f) {
@@ -225,6 +226,7 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
     return fail(AMX_ERR_INVALID_ARG, "M and N may be at most %lld and batch at most %lld (got %lld, %lld, %lld)",
                 (long long)kMaxGemmRows, (long long)kMaxBatch, (long long)M, (long long)N, (long long)batch);
   if (ldc < N) return fail(AMX_ERR_INVALID_ARG, "ldc < N");
+  if (ldc > kMaxLdc) return fail(AMX_ERR_INVALID_ARG, "ldc = %lld exceeds the supported maximum %lld", (long long)ldc, (long long)kMaxLdc);
   if (!A_codes || !A_scales || !B_codes || !B_scales || !C) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
   if (!aligned(A_codes, 16) || !aligned(B_codes, 16) || !aligned(A_scales, 4) || !aligned(B_scales, 4) ||
       !aligned(C, 4))

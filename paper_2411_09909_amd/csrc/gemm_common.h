@@ -66,30 +66,42 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));  // accumulator of on
 // 2^SCALE_LOG2 (0, or the power of two that undoes an operand bias) and, with ALPHA, by the run-time factor alpha.
 // row_base / col_base: first row / column of the wave's tiles.
 // Accumulator register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its tile. Rows >= M and columns
-// >= N (partial tiles) are skipped. Non-temporal stores: C is not read again by the kernel.
+// >= N (partial tiles) are not written. Non-temporal stores: C is not read again by the kernel.
+// Addressing: one raw buffer over the wave's window of C, from its first element to the last valid element of its last
+// valid row. The row of a store is a scalar offset (a compile-time multiple of the row pitch), the column and the lane
+// half's row offset a per-lane offset computed once per column tile, so a store costs one scalar addition; the hardware
+// drops whatever falls beyond the window (the range check covers the scalar offset too: probed), which takes care of
+// the rows >= M, and lanes whose column is >= N are given an offset beyond any window. Needs ldc <= 2^22 (the entry
+// points check it): 128 rows of that pitch stay below 2^31 bytes. (The first version computed a 64-bit address and a
+// row comparison per element: 13 vector instructions, among them a 64-bit multiplication, for every store, 11 us per
+// 256 x 256 tile, a sixth of the FP4 kernel's time.)
 template <int FM, int FN, int SCALE_LOG2 = 0, bool ALPHA = false>
 __device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[FM][FN], float* __restrict__ Cb, int64_t M,
                                               int64_t N, int64_t ldc, int64_t row_base, int64_t col_base,
                                               float alpha = 1.0f) {
+  const int64_t rows_left = M - row_base, cols_left = N - col_base;  // uniform over the wave
+  if (rows_left <= 0 || cols_left <= 0) return;
+  const int rows_valid = rows_left < FM * 32 ? (int)rows_left : FM * 32;
+  const int cols_valid = cols_left < FN * 32 ? (int)cols_left : FN * 32;
+  const uint32_t pitch = (uint32_t)ldc * 4u;
+  const __amdgpu_buffer_rsrc_t window = __builtin_amdgcn_make_buffer_rsrc(
+      Cb + row_base * ldc + col_base, 0, (int)((uint32_t)(rows_valid - 1) * pitch + (uint32_t)cols_valid * 4u), 0x00020000);
   // the lane number is taken from the hardware again here rather than kept alive (or spilled) across the main loop
   const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
 #pragma unroll
-  for (int i = 0; i < FM; ++i) {
+  for (int j = 0; j < FN; ++j) {
+    const int col = j * 32 + (lane & 31);
+    const uint32_t lane_off = col < cols_valid ? (uint32_t)col * 4u + (uint32_t)(4 * (lane >> 5)) * pitch : 0x80000000u;
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int64_t col = col_base + j * 32 + (lane & 31);
-      const int64_t row0 = row_base + i * 32 + 4 * (lane >> 5);
-      if (col < N) {
+    for (int i = 0; i < FM; ++i) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int64_t row = row0 + 8 * (v >> 2) + (v & 3);
-          if (row < M) {
-            float c = acc[i][j][v];
-            if constexpr (SCALE_LOG2 != 0) c *= (float)(1 << SCALE_LOG2);
-            if constexpr (ALPHA) c *= alpha;
-            __builtin_nontemporal_store(c, Cb + row * ldc + col);
-          }
-        }
+      for (int v = 0; v < 16; ++v) {
+        float c = acc[i][j][v];
+        if constexpr (SCALE_LOG2 != 0) c *= (float)(1 << SCALE_LOG2);
+        if constexpr (ALPHA) c *= alpha;
+        const uint32_t row_off = (uint32_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * pitch;
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, c), window, (int)lane_off, (int)row_off,
+                                              2 /* non-temporal */);
       }
     }
   }

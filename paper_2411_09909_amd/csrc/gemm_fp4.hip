@@ -258,11 +258,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   // stage's and the next stage's arrays). Step t = 4 ks + i:
   //   - reads the A fragment of step t + 2 and, at i = 0, 1, two B fragments of k-step ks + 1 (for the last k-step:
   //     those of the next stage's first k-step, at i = 2, 3, i.e. after the barrier);
-  //   - steps 0..7 issue the 16 loads of stage S + 1 into NXT, two per step; step 0 also requests its scale words;
+  //   - the 16 loads of stage S + 1 are spread over twelve steps so that the vector memory path is never asked for
+  //     more than it delivers: the buffer they go to is free as soon as the barrier of stage S - 1 has passed, so the
+  //     first four are issued in the last two steps of stage S - 1 (as loads 0..3 of stage S + 2 into CUR here), the
+  //     next four in steps 0 and 1 of this stage and the last eight one per step in steps 2..9; step 0 also requests
+  //     the scale words;
   //   - after the MFMAs of step 13: wait for all loads and fragment reads of this wave, barrier.
-#define AMX_STAGE(S, SET, NXT, RC, RN)                                                                             \
+#define AMX_STAGE(S, SET, CUR, NXT, RC, RN)                                                                            \
   {                                                                                                               \
     const int next_ = (S) + 1 < nfull ? (S) + 1 : nfull - 1;                                                      \
+    const int next2_ = (S) + 2 < nfull ? (S) + 2 : nfull - 1;                                                     \
     _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                                            \
       _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                                            \
         const int t = ks * FM + i;                                                                                \
@@ -282,9 +287,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
             bR[0][jj] = AMX_LDS_READ(RN##B, baseB + jj * 4096 + AMX_FRAG_OFF(0));                                 \
         }                                                                                                         \
         if (t == 0) AMX_LOAD_SCALES((SET) ^ 1, next_);                                                            \
-        if (t < 8) {                                                                                              \
-          AMX_ISSUE_LOAD(2 * t, next_, NXT);                                                                      \
-          AMX_ISSUE_LOAD(2 * t + 1, next_, NXT);                                                                  \
+        if (t < 2) {                                                                                              \
+          AMX_ISSUE_LOAD(4 + 2 * t, next_, NXT);                                                                  \
+          AMX_ISSUE_LOAD(5 + 2 * t, next_, NXT);                                                                  \
+        } else if (t < 10) {                                                                                      \
+          AMX_ISSUE_LOAD(6 + t, next_, NXT);                                                                      \
+        } else if (t > kLast) {                                                                                   \
+          AMX_ISSUE_LOAD(2 * (t - kLast - 1), next2_, CUR);                                                       \
+          AMX_ISSUE_LOAD(2 * (t - kLast - 1) + 1, next2_, CUR);                                                   \
         }                                                                                                         \
         /* (the scale-byte selector must be a literal: OPS = 2 * (ks % 2)) */                                     \
         if ((ks & 1) == 0) AMX_MMA(SET, ks, i, 0) else AMX_MMA(SET, ks, i, 2);                                    \
@@ -309,12 +319,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
 #pragma unroll
     for (int j = 0; j < FN; ++j)
       bR[0][j] = AMX_LDS_READ(rd0_B, baseB + j * 4096 + AMX_FRAG_OFF(0));
+    {  // the first four loads of stage 1 (the stages issue loads 4..15 of their successor themselves)
+      const int st1_ = nfull > 1 ? 1 : 0;
+#pragma unroll
+      for (int l = 0; l < 4; ++l) AMX_ISSUE_LOAD(l, st1_, lds1_);
+    }
     int s = 0;
     for (; s + 2 <= nfull; s += 2) {
-      AMX_STAGE(s, 0, lds1_, rd0_, rd1_);
-      AMX_STAGE(s + 1, 1, lds0_, rd1_, rd0_);
+      AMX_STAGE(s, 0, lds0_, lds1_, rd0_, rd1_);
+      AMX_STAGE(s + 1, 1, lds1_, lds0_, rd1_, rd0_);
     }
-    if (s < nfull) AMX_STAGE(s, 0, lds1_, rd0_, rd1_);
+    if (s < nfull) AMX_STAGE(s, 0, lds0_, lds1_, rd0_, rd1_);
     __builtin_amdgcn_s_waitcnt(0x0070);  // this wave's last (unused) prefetches have landed, its reads are done
     AMX_BARRIER();                       // ... and everybody else's: LDS is free
   }
