@@ -61,30 +61,44 @@ size_t fp4_path_workspace_bytes(bool asym, int64_t M, int64_t N, int64_t K, int6
   return (size_t)(batch * (fp4_packed_scale_bytes(asym, M, K) + fp4_packed_scale_bytes(asym, N, K)));
 }
 
-// grid: (ceil(rows_p * stages / 256), 1, batch); one thread per (row, stage), stages fastest so that a wave reads
-// consecutive bytes of a scale row. SB: bytes per group (1 symmetric, 2 asymmetric).
+// One operand of the re-layout: canonical scales [batch][R][G][SB] -> packed (Rp rows, a multiple of 128).
+struct ScalePackJob {
+  const uint8_t* scales;
+  uint8_t* packed;
+  int64_t R, Rp;
+  int blocks;  // workgroups of this operand per batch entry: (Rp / 128) * ceil(stages / 16)
+};
+
+// grid: (jobA.blocks + jobB.blocks, 1, batch); block 256. A workgroup re-lays 128 rows x 16 stages: it reads the
+// 128 * SB bytes those stages occupy in each of its rows (whole cache lines, 4 bytes per thread and load), turns them
+// through LDS and writes 16 stages of packed scales, contiguous. SB: bytes per group (1 symmetric, 2 asymmetric).
 template <int SB>
-__global__ __launch_bounds__(256) void scale_pack_kernel(const uint8_t* __restrict__ scales, int64_t R, int64_t G,
-                                                         int64_t Rp, int nstages, uint8_t* __restrict__ packed) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= Rp * nstages) return;
-  const int64_t row = idx / nstages, b = blockIdx.z;
-  const int st = (int)(idx - row * nstages);
-  uint32_t w[2 * SB] = {};
-  if (row < R) {
-    // (scale rows are 4-byte aligned: G is a multiple of 4)
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(scales + ((b * R + row) * G + (int64_t)st * 8) * SB);
-    const int words = (int)((G - (int64_t)st * 8 >= 8 ? 8 : G - (int64_t)st * 8) * SB / 4);
-#pragma unroll
-    for (int i = 0; i < 2 * SB; ++i)
-      if (i < words) w[i] = src[i];
+__global__ __launch_bounds__(256) void scale_pack_kernel(ScalePackJob ja, ScalePackJob jb, int64_t G, int nstages) {
+  constexpr int kRowWords = 16 * 8 * SB / 4;  // 32-bit words of 16 stages of one row
+  __shared__ uint32_t turn[kScaleRows][kRowWords + 1];
+  const bool second = (int)blockIdx.x >= ja.blocks;
+  const ScalePackJob& job = second ? jb : ja;
+  const int blk = (int)blockIdx.x - (second ? ja.blocks : 0);
+  const int chunks = (nstages + 15) / 16;
+  const int64_t q = blk / chunks, b = blockIdx.z;
+  const int st0 = (blk % chunks) * 16;
+  const int64_t row_words = G * SB / 4;  // (scale rows are whole words: G is a multiple of 4)
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(job.scales) + b * job.R * row_words;
+  for (int idx = threadIdx.x; idx < kScaleRows * kRowWords; idx += 256) {
+    const int r = idx / kRowWords, w = idx % kRowWords;
+    const int64_t row = q * kScaleRows + r, word = (int64_t)st0 * (8 * SB / 4) + w;
+    turn[r][w] = (row < job.R && word < row_words) ? src[row * row_words + word] : 0u;
   }
-  const int64_t q = row / kScaleRows;
-  const int i = (int)(row % kScaleRows) / 32, r = (int)(row % 32);
-  uint32_t* dst = reinterpret_cast<uint32_t*>(packed + ((b * (Rp / kScaleRows) + q) * nstages + st) * (32 * 4 * 8 * SB) +
-                                              (r * 4 + i) * 8 * SB);
-#pragma unroll
-  for (int j = 0; j < 2 * SB; ++j) dst[j] = w[j];
+  __syncthreads();
+  // packed: [q][stage][r 32][i 4][8 * SB bytes]; one 8 * SB-byte entry = 2 * SB words
+  constexpr int kEntryWords = 2 * SB, kStageWords = 32 * 4 * kEntryWords;
+  uint32_t* dst = reinterpret_cast<uint32_t*>(job.packed) + ((b * (job.Rp / kScaleRows) + q) * nstages + st0) * kStageWords;
+  const int stages_here = nstages - st0 < 16 ? nstages - st0 : 16;
+  for (int idx = threadIdx.x; idx < stages_here * kStageWords; idx += 256) {
+    const int st = idx / kStageWords, e = (idx % kStageWords) / kEntryWords, w = idx % kEntryWords;
+    const int r = e >> 2, i = e & 3;
+    dst[idx] = turn[i * 32 + r][st * kEntryWords + w];
+  }
 }
 
 // One stage = a K slice of 256: 128 bytes = one whole cache line of every code row (a compute unit's vector cache
@@ -401,10 +415,11 @@ static hipError_t launch_fp4(int64_t M, int64_t N, int64_t K, const uint8_t* Ac,
   const int nstages = (int)((K + 255) / 256);
   uint8_t* Asp = reinterpret_cast<uint8_t*>(workspace);
   uint8_t* Bsp = Asp + batch * fp4_packed_scale_bytes(ASYM, M, K);
-  hipLaunchKernelGGL((scale_pack_kernel<SB>), dim3((unsigned)((Mp * nstages + 255) / 256), 1, (unsigned)batch),
-                     dim3(256), 0, s, As, M, G, Mp, nstages, Asp);
-  hipLaunchKernelGGL((scale_pack_kernel<SB>), dim3((unsigned)((Np * nstages + 255) / 256), 1, (unsigned)batch),
-                     dim3(256), 0, s, Bs, N, G, Np, nstages, Bsp);
+  const int chunks = (nstages + 15) / 16;
+  const ScalePackJob ja = {As, Asp, M, Mp, (int)(Mp / kScaleRows) * chunks};
+  const ScalePackJob jb = {Bs, Bsp, N, Np, (int)(Np / kScaleRows) * chunks};
+  hipLaunchKernelGGL((scale_pack_kernel<SB>), dim3((unsigned)(ja.blocks + jb.blocks), 1, (unsigned)batch), dim3(256),
+                     0, s, ja, jb, G, nstages);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
