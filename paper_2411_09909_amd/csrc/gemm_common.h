@@ -74,7 +74,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));  // accumulator of on
 // the rows >= M, and lanes whose column is >= N are given an offset beyond any window. Needs ldc <= 2^22 (the entry
 // points check it): 128 rows of that pitch stay below 2^31 bytes. (The first version computed a 64-bit address and a
 // row comparison per element: 13 vector instructions, among them a 64-bit multiplication, for every store, 11 us per
-// 256 x 256 tile, a sixth of the FP4 kernel's time.)
+// 256 x 256 tile, a sixth of the FP4 kernel's time. Wider stores do not pay: with the accumulators transposed so that
+// a lane holds four consecutive columns and stores 16 bytes, a store covers 32 rows x 32 bytes instead of two whole
+// 128-byte lines, and the same tile took 36 us to store instead of 7.)
 template <int FM, int FN, int SCALE_LOG2 = 0, bool ALPHA = false>
 __device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[FM][FN], float* __restrict__ Cb, int64_t M,
                                               int64_t N, int64_t ldc, int64_t row_base, int64_t col_base,

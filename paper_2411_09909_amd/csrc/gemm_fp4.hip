@@ -215,24 +215,26 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   static_assert(FM == 4 && FN == 4, "the packed scales hold four row blocks per wave");
   typedef uint32_t sword_t __attribute__((ext_vector_type(ASYM ? 4 : 2)));
   sword_t sa[2][FM], sb[2][FN];
-#define AMX_LOAD_SCALES_OF(DSTV, RSRC, ST)                                                                          \
+  // part P (0, 1) of the scale fetch of one operand: the row blocks 2 P and 2 P + 1
+#define AMX_LOAD_SCALES_PART(DSTV, RSRC, ST, P)                                                                     \
   {                                                                                                                 \
     if constexpr (ASYM) {                                                                                           \
-      _Pragma("unroll") for (int i = 0; i < 4; ++i) DSTV[i] = __builtin_bit_cast(                                   \
+      _Pragma("unroll") for (int i = 2 * (P); i < 2 * (P) + 2; ++i) DSTV[i] = __builtin_bit_cast(                   \
           sword_t, __builtin_amdgcn_raw_buffer_load_b128(RSRC, sgather_off + i * 16, (ST) * kStageScaleBytes, 0));  \
     } else {                                                                                                        \
-      _Pragma("unroll") for (int i = 0; i < 4; i += 2) {                                                            \
-        const u32x4 w_ = __builtin_bit_cast(                                                                        \
-            u32x4, __builtin_amdgcn_raw_buffer_load_b128(RSRC, sgather_off + i * 8, (ST) * kStageScaleBytes, 0));   \
-        DSTV[i][0] = w_.x, DSTV[i][1] = w_.y, DSTV[i + 1][0] = w_.z, DSTV[i + 1][1] = w_.w;                         \
-      }                                                                                                             \
+      const u32x4 w_ = __builtin_bit_cast(                                                                          \
+          u32x4, __builtin_amdgcn_raw_buffer_load_b128(RSRC, sgather_off + (P) * 16, (ST) * kStageScaleBytes, 0));  \
+      DSTV[2 * (P)][0] = w_.x, DSTV[2 * (P)][1] = w_.y, DSTV[2 * (P) + 1][0] = w_.z, DSTV[2 * (P) + 1][1] = w_.w;   \
     }                                                                                                               \
   }
-#define AMX_LOAD_SCALES(SET, ST)             \
-  {                                          \
-    AMX_LOAD_SCALES_OF(sa[SET], Asr, ST);    \
-    AMX_LOAD_SCALES_OF(sb[SET], Bsr, ST);    \
+#define AMX_LOAD_SCALES(SET, ST)                  \
+  {                                               \
+    AMX_LOAD_SCALES_PART(sa[SET], Asr, ST, 0);    \
+    AMX_LOAD_SCALES_PART(sa[SET], Asr, ST, 1);    \
+    AMX_LOAD_SCALES_PART(sb[SET], Bsr, ST, 0);    \
+    AMX_LOAD_SCALES_PART(sb[SET], Bsr, ST, 1);    \
   }
+  constexpr int kScaleLoads = ASYM ? 8 : 4;  // vector loads of one AMX_LOAD_SCALES
 
   const int nfull = (int)(K >> 8);  // whole stages; K % 256 == 128 leaves half a stage for the end
   u32x4 aR[4], bR[2][FN];
@@ -242,50 +244,67 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   // 2 KS4 + 1 of the stage. Scale byte selection:
   // symmetric: word KS4 / 2 = bytes of 4 groups, shifted by 8*kb; the k-step uses byte OPS = 2 * (KS4 % 2) (opsel);
   // asymmetric: word KS4 = bytes (p0 n0 p1 n1) of the k-step, shifted by 16*kb; pos = byte 0, neg = byte 1.
-#define AMX_MMA(SET, KS4, I, OPS)                                                                                       \
+#define AMX_MMA1(SET, KS4, I, J, OPS)                                                                                \
   {                                                                                                                  \
     if constexpr (!ASYM) {                                                                                           \
       const int sav = (int)(sa[SET][I][(KS4) >> 1] >> (8 * kb));                                                     \
-      const i32x8 av = as_operand(aR[((KS4) * FM + (I)) & 3]);                                                       \
-      _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                                               \
-        const int sbv = (int)(sb[SET][j][(KS4) >> 1] >> (8 * kb));                                                   \
-        acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, as_operand(bR[(KS4) & 1][j]), acc[I][j], 4,  \
-                                                                    4, OPS, sav, OPS, sbv);                          \
-      }                                                                                                              \
+      const int sbv = (int)(sb[SET][J][(KS4) >> 1] >> (8 * kb));                                                     \
+      acc[I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as_operand(aR[((KS4) * FM + (I)) & 3]),            \
+                                                                  as_operand(bR[(KS4) & 1][J]), acc[I][J], 4, 4, OPS, \
+                                                                  sav, OPS, sbv);                                    \
     } else {                                                                                                         \
       const int sav = (int)(sa[SET][I][KS4] >> (16 * kb));                                                           \
+      const int sbv = (int)(sb[SET][J][KS4] >> (16 * kb));                                                           \
       const u32x4 araw = aR[((KS4) * FM + (I)) & 3];                                                                 \
       const i32x8 ap = as_operand(sign_class4<false>(araw)), an = as_operand(sign_class4<true>(araw));              \
-      _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                                               \
-        const int sbv = (int)(sb[SET][j][KS4] >> (16 * kb));                                                         \
-        const i32x8 bp = as_operand(sign_class4<false>(bR[(KS4) & 1][j])),                                           \
-                    bn = as_operand(sign_class4<true>(bR[(KS4) & 1][j]));                                            \
-        acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ap, bp, acc[I][j], 4, 4, 0, sav, 0, sbv);        \
-        acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ap, bn, acc[I][j], 4, 4, 0, sav, 1, sbv);        \
-        acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(an, bp, acc[I][j], 4, 4, 1, sav, 0, sbv);        \
-        acc[I][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(an, bn, acc[I][j], 4, 4, 1, sav, 1, sbv);        \
-      }                                                                                                              \
+      const i32x8 bp = as_operand(sign_class4<false>(bR[(KS4) & 1][J])),                                             \
+                  bn = as_operand(sign_class4<true>(bR[(KS4) & 1][J]));                                              \
+      acc[I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ap, bp, acc[I][J], 4, 4, 0, sav, 0, sbv);          \
+      acc[I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ap, bn, acc[I][J], 4, 4, 0, sav, 1, sbv);          \
+      acc[I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(an, bp, acc[I][J], 4, 4, 1, sav, 0, sbv);          \
+      acc[I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(an, bn, acc[I][J], 4, 4, 1, sav, 1, sbv);          \
     }                                                                                                                \
   }
+#define AMX_MMA(SET, KS4, I, OPS) \
+  { _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_) AMX_MMA1(SET, KS4, I, j_, OPS); }
+  /* (the scale-byte selector must be a literal: OPS = 2 * (ks % 2)) */
+#define AMX_SLOT_MMA(SET, KS4, I, J) \
+  { if (((KS4) & 1) == 0) AMX_MMA1(SET, KS4, I, J, 0) else AMX_MMA1(SET, KS4, I, J, 2); }
 
-  // Stage S (scale words in set SET; NXT: the arrays the next stage is loaded into; RC / RN: read pointers of this
-  // stage's and the next stage's arrays). Step t = 4 ks + i:
-  //   - reads the A fragment of step t + 2 and, at i = 0, 1, two B fragments of k-step ks + 1 (for the last k-step:
-  //     those of the next stage's first k-step, at i = 2, 3, i.e. after the barrier);
-  //   - the 16 loads of stage S + 1 are spread over twelve steps so that the vector memory path is never asked for
-  //     more than it delivers: the buffer they go to is free as soon as the barrier of stage S - 1 has passed, so the
-  //     first four are issued in the last two steps of stage S - 1 (as loads 0..3 of stage S + 2 into CUR here), the
-  //     next four in steps 0 and 1 of this stage and the last eight one per step in steps 2..9; step 0 also requests
-  //     the scale words;
-  //   - after the MFMAs of step 13: wait for all loads and fragment reads of this wave, barrier.
-#define AMX_STAGE(S, SET, CUR, NXT, RC, RN)                                                                            \
+  // Stage S (scale words in set SET; CUR / NXT: the arrays of this and of the next stage as load destinations; RC /
+  // RN: their read pointers). Step t = 4 ks + i multiplies A row block i with the four B row blocks of k-step ks: four
+  // slots of one MFMA (asymmetric: four) each. A wave issues in order and has its SIMD to itself, so whatever stands
+  // between two MFMAs must fit into the 32 cycles the first one occupies the matrix pipe: everything else a step does
+  // is therefore dealt out over its slots, at most two memory instructions in front of any MFMA (with all of a
+  // step's loads and fragment reads in front of its first MFMA every direct-to-LDS load cost the pipe about 58
+  // idle cycles, a third of the main loop):
+  //   - slot 0: the A fragment of step t + 2 (read ahead; the last two steps read into the next stage's arrays);
+  //   - slots 1, 2 of the steps i = 0, 1 (i = 2, 3 in the last k-step, after the barrier, from the next stage's
+  //     arrays): the four B fragments of the next k-step;
+  //   - the 16 direct-to-LDS loads of stage S + 1 are spread over twelve steps: the arrays they go to are free once
+  //     the barrier of stage S - 1 has passed, so four are issued in the last two steps of stage S - 1 (as loads 0..3
+  //     of stage S + 2 into CUR here), four in steps 0 and 1 and eight in steps 2..9, in the slots without a B read;
+  //   - steps 10 and 11: the scale words of stage S + 1 (A's, then B's) into the other register set;
+  //   - after step 13: wait for the direct-to-LDS loads (not for the scale words, which are younger) and for this
+  //     wave's fragment reads, barrier: every wave has its last fragments of CUR and stage S + 1 has landed.
+#define AMX_DMA(T, WHICH, CUR, NXT)                                                                                      \
+  {                                                                                                               \
+    if ((T) < 2) AMX_ISSUE_LOAD(4 + 2 * (T) + (WHICH), next_, NXT)                                                \
+    else if ((T) < 10) AMX_ISSUE_LOAD(6 + (T), next_, NXT)                                                        \
+    else AMX_ISSUE_LOAD(2 * ((T) - kLast - 1) + (WHICH), next2_, CUR)                                             \
+  }
+#define AMX_STAGE(S, SET, CUR, NXT, RC, RN)                                                                        \
   {                                                                                                               \
     const int next_ = (S) + 1 < nfull ? (S) + 1 : nfull - 1;                                                      \
     const int next2_ = (S) + 2 < nfull ? (S) + 2 : nfull - 1;                                                     \
+    constexpr int kLast = 4 * FM - 3; /* the step followed by the barrier */                                      \
     _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                                            \
       _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                                            \
         const int t = ks * FM + i;                                                                                \
-        constexpr int kLast = 4 * FM - 3; /* the step followed by the barrier */                                  \
+        const bool b_reads = ks < 3 ? i < 2 : i >= 2;                                                             \
+        const int jj = ks < 3 ? 2 * i : 2 * (i - 2);                                                              \
+        const int dma = t < 2 ? 2 : t < 10 ? 1 : t > kLast ? 2 : 0; /* direct-to-LDS loads of this step */        \
+        /* slot 0 */                                                                                              \
         {                                                                                                         \
           const int t2 = t + 2, ks2 = t2 / FM, i2 = t2 % FM;                                                      \
           if (ks2 < 4)                                                                                            \
@@ -293,27 +312,39 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
           else                                                                                                    \
             aR[t2 & 3] = AMX_LDS_READ(RN##A, baseA + i2 * 4096 + AMX_FRAG_OFF(0));                                \
         }                                                                                                         \
-        if (ks < 3) {                                                                                             \
-          _Pragma("unroll") for (int jj = 2 * i; jj < 2 * i + 2; ++jj) if (jj < FN)                               \
-            bR[(ks + 1) & 1][jj] = AMX_LDS_READ(RC##B, baseB + jj * 4096 + AMX_FRAG_OFF(ks + 1));                 \
-        } else {                                                                                                  \
-          _Pragma("unroll") for (int jj = 2 * (i - 2); jj < 2 * (i - 2) + 2; ++jj) if (i >= 2 && jj < FN)         \
-            bR[0][jj] = AMX_LDS_READ(RN##B, baseB + jj * 4096 + AMX_FRAG_OFF(0));                                 \
+        if (b_reads && dma == 2) AMX_DMA(t, 1, CUR, NXT);                                                                   \
+        AMX_SLOT_MMA(SET, ks, i, 0);                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
+        /* slot 1 */                                                                                              \
+        if (b_reads) {                                                                                            \
+          if (ks < 3) bR[(ks + 1) & 1][jj] = AMX_LDS_READ(RC##B, baseB + jj * 4096 + AMX_FRAG_OFF(ks + 1));       \
+          else bR[0][jj] = AMX_LDS_READ(RN##B, baseB + jj * 4096 + AMX_FRAG_OFF(0));                              \
+        } else if (dma >= 1) {                                                                                    \
+          AMX_DMA(t, 0, CUR, NXT);                                                                                          \
+        } else if (t == 10) {                                                                                     \
+          AMX_LOAD_SCALES_PART(sa[(SET) ^ 1], Asr, next_, 0);                                                     \
+        } else if (t == 11) {                                                                                     \
+          AMX_LOAD_SCALES_PART(sb[(SET) ^ 1], Bsr, next_, 0);                                                     \
         }                                                                                                         \
-        if (t == 0) AMX_LOAD_SCALES((SET) ^ 1, next_);                                                            \
-        if (t < 2) {                                                                                              \
-          AMX_ISSUE_LOAD(4 + 2 * t, next_, NXT);                                                                  \
-          AMX_ISSUE_LOAD(5 + 2 * t, next_, NXT);                                                                  \
-        } else if (t < 10) {                                                                                      \
-          AMX_ISSUE_LOAD(6 + t, next_, NXT);                                                                      \
-        } else if (t > kLast) {                                                                                   \
-          AMX_ISSUE_LOAD(2 * (t - kLast - 1), next2_, CUR);                                                       \
-          AMX_ISSUE_LOAD(2 * (t - kLast - 1) + 1, next2_, CUR);                                                   \
+        AMX_SLOT_MMA(SET, ks, i, 1);                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
+        /* slot 2 */                                                                                              \
+        if (b_reads) {                                                                                            \
+          if (ks < 3) bR[(ks + 1) & 1][jj + 1] = AMX_LDS_READ(RC##B, baseB + (jj + 1) * 4096 + AMX_FRAG_OFF(ks + 1)); \
+          else bR[0][jj + 1] = AMX_LDS_READ(RN##B, baseB + (jj + 1) * 4096 + AMX_FRAG_OFF(0));                    \
+        } else if (t == 10) {                                                                                     \
+          AMX_LOAD_SCALES_PART(sa[(SET) ^ 1], Asr, next_, 1);                                                     \
+        } else if (t == 11) {                                                                                     \
+          AMX_LOAD_SCALES_PART(sb[(SET) ^ 1], Bsr, next_, 1);                                                     \
         }                                                                                                         \
-        /* (the scale-byte selector must be a literal: OPS = 2 * (ks % 2)) */                                     \
-        if ((ks & 1) == 0) AMX_MMA(SET, ks, i, 0) else AMX_MMA(SET, ks, i, 2);                                    \
+        AMX_SLOT_MMA(SET, ks, i, 2);                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
+        /* slot 3 */                                                                                              \
+        if (b_reads && dma >= 1) AMX_DMA(t, 0, CUR, NXT);                                                                   \
+        AMX_SLOT_MMA(SET, ks, i, 3);                                                                              \
         if (t == kLast) {                                                                                         \
-          __builtin_amdgcn_s_waitcnt(0x0070); /* vmcnt(0) lgkmcnt(0) */                                           \
+          /* vmcnt(kScaleLoads) lgkmcnt(0): all but the youngest vector loads, which are the scale words */       \
+          __builtin_amdgcn_s_waitcnt(0x0070 | kScaleLoads);                                                       \
           AMX_BARRIER();                                                                                          \
         }                                                                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
@@ -369,9 +400,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp4_kernel(const uint8_t* _
   }
   __builtin_amdgcn_s_waitcnt(0x0070);  // nothing may still be writing this workgroup's LDS when it retires
 #undef AMX_STAGE
+#undef AMX_DMA
+#undef AMX_SLOT_MMA
 #undef AMX_MMA
+#undef AMX_MMA1
 #undef AMX_LOAD_SCALES
-#undef AMX_LOAD_SCALES_OF
+#undef AMX_LOAD_SCALES_PART
 #undef AMX_ISSUE_LOAD
 #undef AMX_FRAG_OFF
 #undef AMX_LDS_READ
