@@ -74,9 +74,12 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));  // accumulator of on
 // the rows >= M, and lanes whose column is >= N are given an offset beyond any window. Needs ldc <= 2^22 (the entry
 // points check it): 128 rows of that pitch stay below 2^31 bytes. (The first version computed a 64-bit address and a
 // row comparison per element: 13 vector instructions, among them a 64-bit multiplication, for every store, 11 us per
-// 256 x 256 tile, a sixth of the FP4 kernel's time. Wider stores do not pay: with the accumulators transposed so that
-// a lane holds four consecutive columns and stores 16 bytes, a store covers 32 rows x 32 bytes instead of two whole
-// 128-byte lines, and the same tile took 36 us to store instead of 7.)
+// 256 x 256 tile, a sixth of the FP4 kernel's time. What is left, 6-7 us per tile, is the write path itself: 256 KiB
+// per compute unit, all compute units at once. Two wider forms were measured and dropped: with the accumulators
+// transposed (B as the instruction's first operand) a lane holds four consecutive columns and stores 16 bytes, but a
+// store then covers 32 rows x 32 bytes instead of two whole 128-byte lines and the tile took 36 us; with the tiles
+// turned through LDS so that a lane stores 16 bytes of a whole row (64 store instructions per wave instead of 256)
+// it took the same 7 us as this form.)
 template <int FM, int FN, int SCALE_LOG2 = 0, bool ALPHA = false>
 __device__ __forceinline__ void store_c_tiles(const f32x16 (&acc)[FM][FN], float* __restrict__ Cb, int64_t M,
                                               int64_t N, int64_t ldc, int64_t row_base, int64_t col_base,
