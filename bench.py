@@ -35,7 +35,7 @@ FORMATS = {
     "amxfp4_e5m2": (2, True, "bf16", PEAK_BF16_TFLOPS),    # the paper's AMXFP4: FP8-E5M2 asymmetric scales
     "mxfp4_e5m2": (2, False, "bf16", PEAK_BF16_TFLOPS),    # the paper's "MXFP4" rows: FP8-E5M2 symmetric scale
     "mxfp4_e8m0": (0, False, "fp4", PEAK_FP4_TFLOPS),      # OCP MXFP4 (power-of-two scale, exponent floored)
-    "amxfp4_e8m0": (0, True, "fp8", PEAK_FP8_TFLOPS),      # asymmetric power-of-two scales merged into E5M2 elements
+    "amxfp4_e8m0": (0, True, "fp6", PEAK_FP4_TFLOPS),      # asymmetric power-of-two scales merged into FP6 (FP4 rate)
     "amxfp4_e4m3": (3, True, "bf16", PEAK_BF16_TFLOPS),    # the 4-exponent-bit FP8 scale of the paper's Sec. 4.2
     # Sec. 5.3 double scaling: groups of 16, E4M3 group scale, tensor-wise FP32 scale (its amax pass is in the step)
     "nvfp4": (3, False, "bf16", PEAK_BF16_TFLOPS),
@@ -158,6 +158,8 @@ def main():
                     help="elements per scale group (the headline metric is group 32; the others run on the BF16 MFMA)")
     ap.add_argument("--e5m2-kernel", default="panel", choices=["panel", "hybrid", "fused"],
                     help="which of the library's kernels for FP8-E5M2 scales runs the timed GEMM (default: panel)")
+    ap.add_argument("--pot-kernel", default="merged_fp6", choices=["merged_fp6", "merged_fp8", "split"],
+                    help="which of the library's kernels for asymmetric power-of-two scales runs the timed GEMM")
     ap.add_argument("--variants", action="store_true",
                     help="time every other format and kernel as well (the block-scaled formats are always listed)")
     ap.add_argument("--no-variants", action="store_true", help="only the headline format")
@@ -192,13 +194,15 @@ def main():
     C = torch.empty((M, N), dtype=torch.float32, device=dev)
     flops = 2.0 * M * N * K
 
-    def run_format(name, steps, warmup, e5m2_kernel="panel", pot_kernel="merged"):
+    def run_format(name, steps, warmup, e5m2_kernel="panel", pot_kernel="merged_fp6"):
         """Times `steps` steps (cast X + GEMM against pre-cast W) in the given format; returns a dict of timings.
         e5m2_kernel: which of the library's three kernels for FP8-E5M2 scales multiplies; pot_kernel: which of the
         kernels for asymmetric power-of-two scales (both ignored by the other formats)."""
         kind, asym, mfma, peak = FORMATS[name]
         if name == "amxfp4_e8m0" and pot_kernel == "split":
             mfma, peak = "fp4", PEAK_FP4_TFLOPS
+        if name == "amxfp4_e8m0" and pot_kernel == "merged_fp8":
+            mfma, peak = "fp8", PEAK_FP8_TFLOPS
         scaled = name in DOUBLE_SCALED
         gs = 16 if scaled else args.group_size
         if gs != 32:
@@ -295,14 +299,14 @@ def main():
                 "weights": round(per_elem(N) / t_w / 1e9, 1), "weights_us": round(t_w * 1e6, 1),
                 "frac_of_hbm_peak": round(per_elem(M) / t_hbm / 1e9 / 8000.0, 4)}
 
-    r = run_format(args.format, args.steps, args.warmup, args.e5m2_kernel)
+    r = run_format(args.format, args.steps, args.warmup, args.e5m2_kernel, args.pot_kernel)
     ms_per_step = r["t_step"] * 1e3
     value = flops / r["t_step"] / 1e12
     achieved = flops / (r["kern_ms"] * 1e-3) / 1e12
     scaled = args.format in DOUBLE_SCALED   # the tensor-wise maximum reads X once more
     cast_bytes = (M * K * 2 * (2 if scaled else 1) + M * K // 2 +
                   M * (K // (16 if scaled else args.group_size)) * (2 if r["asym"] else 1))
-    kernel_name = "gemm_fp4_kernel" if r["mfma"] == "fp4" else "gemm_fp8m_kernel" if r["mfma"] == "fp8" else {"panel": "gemm_bf16_kernel", "hybrid":
+    kernel_name = "gemm_fp4_kernel" if r["mfma"] == "fp4" else "gemm_fp8m_kernel" if r["mfma"] == "fp8" else "gemm_fp6m_kernel" if r["mfma"] == "fp6" else {"panel": "gemm_bf16_kernel", "hybrid":
                   "gemm_e5m2_hybrid_kernel", "fused": "gemm_e5m2_kernel"}[args.e5m2_kernel if args.group_size == 32 else "panel"]
     if M <= 256 and K % 256 == 0 and args.group_size == 32 and args.format not in DOUBLE_SCALED:
         kernel_name = "gemm_skinny_kernel"  # few rows: B dequantized in registers straight from its codes
@@ -347,19 +351,20 @@ def main():
     # The formats that run on the block-scaled matrix instructions are part of every run (about ten steps each): OCP
     # MXFP4 and the asymmetric power-of-two format, each with its GEMM kernel's time and fraction of the peak of the
     # MFMA type it issues. --variants adds the rest.
-    cases = [("mxfp4_e8m0", "panel", "merged"), ("amxfp4_e8m0", "panel", "merged"), ("amxfp4_e8m0", "panel", "split")]
+    cases = [("mxfp4_e8m0", "panel", "merged_fp6"), ("amxfp4_e8m0", "panel", "merged_fp6"),
+             ("amxfp4_e8m0", "panel", "merged_fp8"), ("amxfp4_e8m0", "panel", "split")]
     if args.variants:
-        cases += [(name, "panel", "merged") for name in sorted(FORMATS) if name not in ("mxfp4_e8m0", "amxfp4_e8m0")]
-        cases += [(name, k, "merged") for name in ("amxfp4_e5m2", "mxfp4_e5m2") for k in ("hybrid", "fused")]
+        cases += [(name, "panel", "merged_fp6") for name in sorted(FORMATS) if name not in ("mxfp4_e8m0", "amxfp4_e8m0")]
+        cases += [(name, k, "merged_fp6") for name in ("amxfp4_e5m2", "mxfp4_e5m2") for k in ("hybrid", "fused")]
     if args.no_variants or args.group_size != 32:
         cases = []
     v_steps = max(3, min(args.steps, 10)) if not args.variants else max(3, args.steps // 2)
     v_warm = max(2, min(args.warmup, 5)) if not args.variants else max(2, args.warmup // 2)
     for name, kern, pot in cases:
-        if name == args.format and kern == args.e5m2_kernel and pot == "merged":
+        if name == args.format and kern == args.e5m2_kernel and pot == args.pot_kernel:
             continue
         v = run_format(name, v_steps, v_warm, kern, pot)
-        label = name + ("[%s]" % kern if kern != "panel" else "") + ("[%s]" % pot if pot != "merged" else "")
+        label = name + ("[%s]" % kern if kern != "panel" else "") + ("[%s]" % pot if pot != "merged_fp6" else "")
         out.setdefault("variants", {})[label] = {
             "value": round(flops / v["t_step"] / 1e12, 2), "unit": "TFLOP/s",
             "frac_of_fp4_mfma_peak": round(flops / v["t_step"] / 1e12 / PEAK_FP4_TFLOPS, 4),

@@ -89,7 +89,8 @@ const char* amxfp4_last_error(void);
 size_t amxfp4_codes_bytes(const amx_format_t* fmt, int64_t rows, int64_t K);
 /* Size in bytes of the scale array: rows*(K/group_size)*(asymmetric ? 2 : 1). 0 on invalid arguments. */
 size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K);
-/* Device scratch amxfp4_gemm needs for `batch` problems of shape M x N x K in this format (may be 0). */
+/* Device scratch amxfp4_gemm needs for `batch` problems of shape M x N x K in this format (may be 0): operand panels
+ * for the formats multiplied as 16-bit, FP6 or FP8 values, the re-laid scale bytes for the FP4 kernels. */
 size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, int64_t batch);
 
 /*
@@ -149,8 +150,9 @@ int amxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const 
  * array inside the library instead of a caller's workspace. The call allocates and frees nothing.
  *   limit      amxfp4_gemm_workspace_bytes(fmt, M, N, K, batch) must not exceed AMXFP4_GEMM_STATIC_BYTES (16 MiB),
  *              else AMX_ERR_WORKSPACE and nothing is launched. That covers the few-rows (decoding) shapes
- *              against any weight matrix, every shape of the power-of-two symmetric format (which needs no scratch),
- *              and small prefill products; large products on the BF16-panel path need amxfp4_gemm.
+ *              against any weight matrix, the power-of-two symmetric format up to 5 * 10^8 operand elements (its
+ *              scratch is only the re-laid scale bytes, one per 32 elements of either operand), and small
+ *              prefill products; large products on the BF16-panel path need amxfp4_gemm.
  *   sharing    every call on a GPU uses that GPU's one array, whose contents are undefined between calls (each call
  *              overwrites what it reads; nothing needs to start at zero). Calls that may execute at the same time on
  *              one GPU (different streams, or replays of two captured graphs) race on it: keep them on one stream.
@@ -262,15 +264,23 @@ int amxfp4_profile_next_gemm(void* start_event, void* stop_event);
  *                   AMX_E5M2_HYBRID  A expanded to an FP16 panel, B dequantized inside the FP16 MFMA kernel (K % 128 == 0);
  *                   AMX_E5M2_FUSED   both operands dequantized inside the kernel, no workspace (K % 128 == 0).
  *   pot_kernel    asymmetric power-of-two scales, groups of 32 (Sec. 4.2 "PoT"):
- *                   AMX_POT_MERGED_FP8  each group merged into E5M2 elements elem * 2^(s_class - anchor) with one anchor
- *                                    scale max(s_p, s_n): one block-scaled FP8 MFMA per block (any K; workspace). An
+ *                   AMX_POT_MERGED_FP6  each group merged into ONE FP6 (E3M2) operand block, elem * 2^(s_class - anchor),
+ *                                    which is exact while the two scale exponents of the group differ by at most 5;
+ *                                    a group position where some row's scales lie further apart is written twice
+ *                                    along K, once per sign class, so nothing is ever rounded or dropped except a
+ *                                    class whose scale byte is 0 (2^-127: what the cast writes for a class without
+ *                                    elements). Block-scaled MFMA at the FP4 rate (default; any K; workspace sized for
+ *                                    the worst case, every position split in both operands: about 3 bytes per element);
+ *                   AMX_POT_SPLIT_FP4   each operand split by sign into two MXFP4 operands, four block-scaled FP4 MFMAs
+ *                                    per block (exact; K % 128 == 0; workspace: the re-laid scale bytes only);
+ *                   AMX_POT_MERGED_FP8  each group merged into E5M2 elements with one anchor scale max(s_p, s_n): one
+ *                                    block-scaled FP8 MFMA per block (any K; 1 byte per element of workspace). An
  *                                    element whose class scale lies more than 2^13 below the anchor is flushed to zero
- *                                    (less than 1e-4 of its group's largest magnitude). The instruction adds the
+ *                                    (less than 1e-4 of its group's largest magnitude), and the instruction adds the
  *                                    products of a block in a fixed-point window below the largest product, so a sum
  *                                    whose classes cancel can carry an absolute error of about 2^-22 of that largest
- *                                    product: far inside the 1e-3 tolerance in norm, not bit-exact;
- *                   AMX_POT_SPLIT_FP4   each operand split by sign into two MXFP4 operands, four block-scaled FP4 MFMAs
- *                                    per block (exact; K % 128 == 0; no workspace).
+ *                                    product: far inside the 1e-3 tolerance in norm, not bit-exact. The gated GEMM
+ *                                    (amxfp4_gemm_silu_mul) uses this kernel.
  *   tile          workgroup tile of the BF16-panel kernel: AMX_TILE_AUTO (a cost model over the shape), or
  *                 AMX_TILE_256x256 / AMX_TILE_256x128 / AMX_TILE_64x256 on any shape.
  *   few_rows      the kernel that reads B as packed codes (M <= 256, or <= 768 against a large B; K % 256 == 0):
@@ -279,7 +289,7 @@ int amxfp4_profile_next_gemm(void* start_event, void* stop_event);
  * A kernel that does not take the shape or format falls back to the default one. Unknown values: AMX_ERR_INVALID_ARG.
  */
 enum { AMX_E5M2_PANEL = 0, AMX_E5M2_HYBRID = 1, AMX_E5M2_FUSED = 2 };
-enum { AMX_POT_MERGED_FP8 = 0, AMX_POT_SPLIT_FP4 = 1 };
+enum { AMX_POT_MERGED_FP6 = 0, AMX_POT_SPLIT_FP4 = 1, AMX_POT_MERGED_FP8 = 2 };
 enum { AMX_TILE_AUTO = 0, AMX_TILE_256x256 = 1, AMX_TILE_256x128 = 2, AMX_TILE_64x256 = 3 };
 typedef struct {
   int32_t e5m2_kernel;

@@ -129,11 +129,11 @@ def scales_bytes(fmt, rows, K):
 
 
 E5M2_KERNELS = {"panel": 0, "hybrid": 1, "fused": 2}
-POT_KERNELS = {"merged": 0, "split": 1}
+POT_KERNELS = {"merged_fp6": 0, "split": 1, "merged_fp8": 2}
 TILES = {"auto": 0, "256x256": 1, "256x128": 2, "64x256": 3}
 
 
-def gemm_options(e5m2_kernel="panel", pot_kernel="merged", tile="auto", few_rows=0):
+def gemm_options(e5m2_kernel="panel", pot_kernel="merged_fp6", tile="auto", few_rows=0):
     """The per-call kernel choice of amxfp4_gemm_ex (names or the header's integers); few_rows: 0 = where it applies,
     -1 = never, n > 0 = with n outer K slices."""
     return AmxGemmOptions(E5M2_KERNELS.get(e5m2_kernel, e5m2_kernel), POT_KERNELS.get(pot_kernel, pot_kernel),

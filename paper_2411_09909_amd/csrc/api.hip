@@ -161,7 +161,7 @@ bool uses_skinny(const amx_format_t& f, int64_t M, int64_t N, int64_t K, int64_t
 
 // What one GEMM call runs: resolved ONCE per call from the format, the shape and the caller's options, and used for
 // both the workspace requirement and the dispatch (a kernel that does not take the shape falls back to the default).
-enum GemmKernel : int { kGemmSkinny, kGemmFp8Merged, kGemmFp4, kGemmE5m2Fused, kGemmE5m2Hybrid, kGemmPanel };
+enum GemmKernel : int { kGemmSkinny, kGemmFp8Merged, kGemmFp6Merged, kGemmFp4, kGemmE5m2Fused, kGemmE5m2Hybrid, kGemmPanel };
 struct GemmPlan {
   GemmKernel kernel;
   int tile;           // BF16-panel kernel: AMX_TILE_*
@@ -172,7 +172,7 @@ int check_options(const amx_gemm_options_t* o) {
   if (!o) return AMX_OK;
   if (o->e5m2_kernel < AMX_E5M2_PANEL || o->e5m2_kernel > AMX_E5M2_FUSED)
     return fail(AMX_ERR_INVALID_ARG, "options: no such e5m2_kernel %d", (int)o->e5m2_kernel);
-  if (o->pot_kernel < AMX_POT_MERGED_FP8 || o->pot_kernel > AMX_POT_SPLIT_FP4)
+  if (o->pot_kernel < AMX_POT_MERGED_FP6 || o->pot_kernel > AMX_POT_MERGED_FP8)
     return fail(AMX_ERR_INVALID_ARG, "options: no such pot_kernel %d", (int)o->pot_kernel);
   if (o->tile < AMX_TILE_AUTO || o->tile > AMX_TILE_64x256)
     return fail(AMX_ERR_INVALID_ARG, "options: no such tile %d", (int)o->tile);
@@ -190,8 +190,11 @@ GemmPlan plan_gemm(const amx_format_t& f, const amx_gemm_options_t* o, bool scal
   if (scaled) return p;
   if (opt.few_rows >= 0 && uses_skinny(f, M, N, K, batch)) return p.kernel = kGemmSkinny, p;
   const bool pot32 = f.group_size == 32 && (f.scale == AMX_SCALE_E8M0_FLOOR || f.scale == AMX_SCALE_E8M0_ROUND);
-  if (pot32 && f.asymmetric && (opt.pot_kernel == AMX_POT_MERGED_FP8 || !amx::fp4_path_supported(M, N, K)))
+  if (pot32 && f.asymmetric) {
+    if (opt.pot_kernel == AMX_POT_SPLIT_FP4 && amx::fp4_path_supported(M, N, K)) return p.kernel = kGemmFp4, p;
+    if (opt.pot_kernel != AMX_POT_MERGED_FP8 && amx::fp6m_path_supported(M, N, K)) return p.kernel = kGemmFp6Merged, p;
     return p.kernel = kGemmFp8Merged, p;
+  }
   if (uses_fp4_mfma(f, M, N, K)) return p.kernel = kGemmFp4, p;
   if (f.scale == AMX_SCALE_FP8_E5M2 && f.group_size == 32) {
     if (opt.e5m2_kernel == AMX_E5M2_FUSED && amx::e5m2_fused_supported(M, N, K)) return p.kernel = kGemmE5m2Fused, p;
@@ -204,6 +207,7 @@ size_t plan_workspace_bytes(const GemmPlan& p, bool asym, int64_t M, int64_t N, 
   switch (p.kernel) {
     case kGemmSkinny: return amx::skinny_path_workspace_bytes(M, N, K, batch, p.skinny_slices);
     case kGemmFp8Merged: return amx::fp8m_path_workspace_bytes(M, N, K, batch);
+    case kGemmFp6Merged: return amx::fp6m_path_workspace_bytes(M, N, K, batch);
     case kGemmFp4: return amx::fp4_path_workspace_bytes(asym, M, N, K, batch);
     case kGemmE5m2Fused: return 0;
     case kGemmE5m2Hybrid: return amx::e5m2_hybrid_workspace_bytes(M, K, batch);
@@ -251,6 +255,9 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
     case kGemmFp8Merged:
       e = amx::launch_gemm_fp8m_path(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, hs, timer);
       break;
+    case kGemmFp6Merged:
+      e = amx::launch_gemm_fp6m_path(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, hs, timer);
+      break;
     case kGemmFp4:
       e = amx::launch_gemm_fp4_path(asym, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, hs,
                                     timer);
@@ -271,7 +278,7 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
 
 // The gated GEMM runs on the tiled kernels only (the block-scaled ones for power-of-two scales, else the BF16 panels).
 GemmPlan plan_glu(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  static const amx_gemm_options_t kTiledOnly = {0, 0, 0, -1};
+  static const amx_gemm_options_t kTiledOnly = {0, AMX_POT_MERGED_FP8, 0, -1};  // (the FP6 kernel has no gated epilogue)
   GemmPlan p = plan_gemm(f, &kTiledOnly, false, M, N, K, 1);
   if (p.kernel != kGemmFp8Merged && p.kernel != kGemmFp4) p.kernel = kGemmPanel;
   return p;

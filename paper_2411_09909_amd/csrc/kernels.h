@@ -105,6 +105,15 @@ hipError_t launch_gemm_fp8m_path(int64_t M, int64_t N, int64_t K, const uint8_t*
                                  const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch,
                                  void* workspace, hipStream_t s, const KernelTimer& timer, bool glu = false);
 
+// gemm_fp6m.hip: asymmetric power-of-two scales merged per group into FP6 (E3M2) elements + one anchor scale, block-
+// scaled MFMA at the FP4 rate; group positions whose scales lie too far apart for one FP6 operand are written twice
+// along K, split by sign (workspace: merged panels sized for the worst case, anchors, the split plan)
+bool fp6m_path_supported(int64_t M, int64_t N, int64_t K);
+size_t fp6m_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch);
+hipError_t launch_gemm_fp6m_path(int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
+                                 const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch,
+                                 void* workspace, hipStream_t s, const KernelTimer& timer);
+
 // gemm_e5m2.hip: FP8-E5M2 scales, dequantization fused into the FP16-MFMA kernel (no workspace)
 bool e5m2_fused_supported(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm_e5m2_fused(bool asym, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,

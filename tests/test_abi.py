@@ -73,10 +73,14 @@ def test_kernel_options_are_per_call_and_the_workspace_query_is_pure(lib):
     assert binding.gemm_workspace_bytes(f, 300, 1024, 1024, options=binding.gemm_options(e5m2_kernel="fused")) == 0
     assert binding.gemm_workspace_bytes(f, 300, 1024, 1024) == default
     assert binding.gemm_workspace_bytes(f, 300, 1024, 1024, options=binding.gemm_options()) == default
-    # asymmetric power-of-two scales: merged FP8 panels (1 byte per element + anchors) or the sign-split FP4 kernel
+    # asymmetric power-of-two scales: merged FP6 panels sized for the worst case (every group position split in both
+    # operands: 2 G K steps of 1536 bytes per 32 rows, padded to a multiple of 12) + anchors + split flags + plan;
+    # merged FP8 panels (1 byte per element + anchors); or the sign-split FP4 kernel
     g = binding.make_format(binding.E8M0_FLOOR, True)
+    fp6 = 48 * 72 * 1536 + 48 * 18 * 256 + 256 + 256
+    assert binding.gemm_workspace_bytes(g, 300, 1024, 1024) == fp6
     merged = (512 + 1024) * 1024 + (512 + 1024) // 32 * (1024 // 256) * 256
-    assert binding.gemm_workspace_bytes(g, 300, 1024, 1024) == merged
+    assert binding.gemm_workspace_bytes(g, 300, 1024, 1024, options=binding.gemm_options(pot_kernel="merged_fp8")) == merged
     assert (binding.gemm_workspace_bytes(g, 300, 1024, 1024, options=binding.gemm_options(pot_kernel="split"))
             == (512 + 1024) // 128 * 4 * 2048)   # the sign-split FP4 kernel: re-laid scale pairs only
     # few rows: without that kernel the panel path's workspace; with a forced slice count its partial tiles
@@ -85,7 +89,7 @@ def test_kernel_options_are_per_call_and_the_workspace_query_is_pure(lib):
     assert binding.gemm_workspace_bytes(f, 64, 1024, 1024, options=binding.gemm_options(few_rows=1)) == 64 * 1024 * 2
     # unknown option values: no size, and the call itself is an invalid-argument error before anything is touched
     p = ctypes.c_void_p(0x1000)
-    for bad in (binding.AmxGemmOptions(3, 0, 0, 0), binding.AmxGemmOptions(0, 2, 0, 0), binding.AmxGemmOptions(0, 0, 4, 0),
+    for bad in (binding.AmxGemmOptions(3, 0, 0, 0), binding.AmxGemmOptions(0, 3, 0, 0), binding.AmxGemmOptions(0, 0, 4, 0),
                 binding.AmxGemmOptions(0, 0, 0, 17), binding.AmxGemmOptions(0, 0, 0, -2), binding.AmxGemmOptions(-1, 0, 0, 0)):
         assert binding.gemm_workspace_bytes(f, 300, 1024, 1024, options=bad) == 0
         assert lib.amxfp4_gemm_ex(ctypes.byref(f), ctypes.byref(bad), 64, 64, 64, p, p, p, p, p, 64, 1, p, 1 << 30,

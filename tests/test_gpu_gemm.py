@@ -161,8 +161,8 @@ def test_sign_split_kernel_for_asymmetric_power_of_two_scales(split_pot_kernel, 
     assert G.rel_fro(C, ref.gemm(ac, as_, bc, bs, 32, ref.E8M0_FLOOR, 1)) <= TOL
 
 
-def test_merged_kernel_with_far_apart_sign_scales():
-    """Groups whose positive and negative scales are far apart. The merged kernel keeps both classes in one E5M2
+def test_merged_fp8_kernel_with_far_apart_sign_scales():
+    """Groups whose positive and negative scales are far apart. The merged FP8 kernel keeps both classes in one E5M2
     operand: up to 2^13 apart every element is represented exactly, beyond that the small class is flushed; in both
     cases the products of the small class are tiny next to those of the large one, and the block-scaled MFMA adds the
     products of a block in a fixed-point window below the largest of them, which costs up to ~6e-5 (measured: 0 for a
@@ -180,9 +180,12 @@ def test_merged_kernel_with_far_apart_sign_scales():
     ac, as_ = ref.quantize(synth.f32_to_bf16_bits(a), 32, ref.E8M0_FLOOR, 1)
     bc, bs = ref.quantize(b, 32, ref.E8M0_FLOOR, 1)
     Cr = ref.gemm(ac, as_, bc, bs, 32, ref.E8M0_FLOOR, 1)
-    C = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1)
+    C = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1, options=binding.gemm_options(pot_kernel="merged_fp8", few_rows=-1))
     assert G.rel_fro(C, Cr) <= 1e-4
     assert max(G.rel_fro(C[i], Cr[i]) for i in range(M)) <= 2e-4
+    # the default (FP6 operands, these positions split by sign) is exact on the same operands
+    Cd = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1, options=binding.gemm_options(few_rows=-1))
+    assert G.rel_fro(Cd, Cr) <= 1e-6
     Cs = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1, options=binding.gemm_options(pot_kernel="split", few_rows=-1))
     assert G.rel_fro(Cs, Cr) <= 1e-6
 

@@ -57,7 +57,8 @@ KERNELS = [
     ("fused", ref.FP8_E5M2, 1, 32, dict(e5m2_kernel="fused", few_rows=-1), [(1, 300, 270, 384), (2, 257, 31, 128)]),
     ("block-scaled FP4", ref.E8M0_FLOOR, 0, 32, dict(few_rows=-1), [(1, 300, 270, 384), (2, 257, 31, 128)]),
     ("sign-split FP4", ref.E8M0_FLOOR, 1, 32, dict(pot_kernel="split", few_rows=-1), [(1, 300, 270, 384), (2, 257, 31, 128)]),
-    ("merged FP8", ref.E8M0_FLOOR, 1, 32, dict(few_rows=-1), [(1, 300, 270, 160), (2, 257, 31, 96)]),
+    ("merged FP8", ref.E8M0_FLOOR, 1, 32, dict(pot_kernel="merged_fp8", few_rows=-1), [(1, 300, 270, 160), (2, 257, 31, 96)]),
+    ("merged FP6", ref.E8M0_FLOOR, 1, 32, dict(pot_kernel="merged_fp6", few_rows=-1), [(1, 300, 270, 160), (2, 257, 31, 96)]),
     ("few rows, one K slice", ref.FP8_E5M2, 1, 32, dict(few_rows=1), [(1, 5, 70, 512), (2, 33, 100, 256), (1, 200, 45, 512)]),
     ("few rows, K slices", ref.FP8_E5M2, 1, 32, dict(few_rows=2), [(1, 5, 70, 512), (2, 100, 100, 1024), (1, 250, 33, 512)]),
     ("few rows, power-of-two scales", ref.E8M0_FLOOR, 1, 32, dict(few_rows=3), [(1, 31, 65, 768)]),

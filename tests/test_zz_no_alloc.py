@@ -46,7 +46,7 @@ PAIRS = [
     (ref.FP8_E5M2, 1, (1, 64, 1024, 1024), (1, 5, 70, 512)),
     # BF16-panel kernel: both operands' panels (padded rows and K are rewritten as zeros by every call)
     (ref.FP8_E5M2, 1, (1, 600, 700, 1056), (2, 257, 130, 160)),
-    # merged FP8 kernel: merged panels + anchor words
+    # merged FP6 kernel: merged panels, anchor words, split flags and plan
     (ref.E8M0_FLOOR, 1, (1, 600, 700, 1056), (1, 300, 31, 96)),
     # few rows against a weight-matrix-sized B (32 tokens, 8 MB of weights): the decoding shape this call is for
     (ref.FP8_E5M2, 1, (1, 32, 4096, 4096), (1, 1, 4096, 4096)),
@@ -61,7 +61,7 @@ def test_static_scratch_gemm_matches_the_workspace_gemm(scale, asym, first, seco
 
 def test_static_scratch_gemm_rejects_what_does_not_fit():
     """The headline product needs 537 MB of panels: refused on the host, nothing launched, the output untouched. The
-    same shape in the power-of-two symmetric format needs no scratch and is accepted (checked on a smaller N)."""
+    same K in the power-of-two symmetric format needs only its re-laid scale bytes and is accepted."""
     lib = binding.load()
     fmt = binding.make_format(binding.FP8_E5M2, True)
     assert binding.gemm_workspace_bytes(fmt, 4096, 28672, 8192) > binding.GEMM_STATIC_BYTES
