@@ -279,8 +279,7 @@ int amxfp4_profile_next_gemm(void* start_event, void* stop_event);
  *                                    (less than 1e-4 of its group's largest magnitude), and the instruction adds the
  *                                    products of a block in a fixed-point window below the largest product, so a sum
  *                                    whose classes cancel can carry an absolute error of about 2^-22 of that largest
- *                                    product: far inside the 1e-3 tolerance in norm, not bit-exact. The gated GEMM
- *                                    (amxfp4_gemm_silu_mul) uses this kernel.
+ *                                    product: far inside the 1e-3 tolerance in norm, not bit-exact.
  *   tile          workgroup tile of the BF16-panel kernel: AMX_TILE_AUTO (a cost model over the shape), or
  *                 AMX_TILE_256x256 / AMX_TILE_256x128 / AMX_TILE_64x256 on any shape.
  *   few_rows      the kernel that reads B as packed codes (M <= 256, or <= 768 against a large B; K % 256 == 0):

@@ -278,9 +278,9 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
 
 // The gated GEMM runs on the tiled kernels only (the block-scaled ones for power-of-two scales, else the BF16 panels).
 GemmPlan plan_glu(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
-  static const amx_gemm_options_t kTiledOnly = {0, AMX_POT_MERGED_FP8, 0, -1};  // (the FP6 kernel has no gated epilogue)
+  static const amx_gemm_options_t kTiledOnly = {0, AMX_POT_MERGED_FP6, 0, -1};
   GemmPlan p = plan_gemm(f, &kTiledOnly, false, M, N, K, 1);
-  if (p.kernel != kGemmFp8Merged && p.kernel != kGemmFp4) p.kernel = kGemmPanel;
+  if (p.kernel != kGemmFp6Merged && p.kernel != kGemmFp8Merged && p.kernel != kGemmFp4) p.kernel = kGemmPanel;
   return p;
 }
 size_t glu_workspace_bytes(const amx_format_t& f, int64_t M, int64_t N, int64_t K) {
@@ -398,6 +398,11 @@ int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int6
   const GemmKernel glu_kernel = plan_glu(f, M, 2 * width, K).kernel;
   if (glu_kernel == kGemmFp8Merged) {
     hipError_t e = amx::launch_gemm_fp8m_path(M, 2 * width, K, A_codes, A_scales, B_codes, B_scales, out, ld_out, 1,
+                                              workspace, hs, timer, true);
+    return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
+  }
+  if (glu_kernel == kGemmFp6Merged) {
+    hipError_t e = amx::launch_gemm_fp6m_path(M, 2 * width, K, A_codes, A_scales, B_codes, B_scales, out, ld_out, 1,
                                               workspace, hs, timer, true);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
   }

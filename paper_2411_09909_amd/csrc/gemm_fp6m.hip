@@ -282,7 +282,8 @@ __global__ __launch_bounds__(256) void fp6_merge_kernel(Fp6MergeJob ja, Fp6Merge
 // arrays form the ring: while stage S is multiplied, stage S + 1 is complete in LDS (fragment reads run ahead into it)
 // and stages S + 2 .. S + 5 are in flight as direct-to-LDS loads (the panels are fragment-major, so staging is a linear
 // copy of 1 KiB pieces). One barrier per stage.
-template <int WM, int WN, int FM, int FN>
+// GLU: the gated-activation epilogue of store_glu_tiles() (gemm_common.h); C is then the BF16 output [M][ldc].
+template <int WM, int WN, int FM, int FN, bool GLU = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* __restrict__ Ap,
                                                                  const uint8_t* __restrict__ Asc,
                                                                  const uint8_t* __restrict__ Bp,
@@ -470,8 +471,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* 
 #undef AMX_ISSUE_LOAD
 #undef AMX_SRC
 
-  store_c_tiles<FM, FN>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * (32 * FM * WM) + wm * FM * 32,
-                        (int64_t)tn * (32 * FN * WN) + wn * FN * 32);
+  if constexpr (GLU) {
+    // every wave is past its last fragment read: four of the operand stages become the waves' transposition space
+    static_assert(kWaves <= 4 && glu_stage_bytes<FM, FN>() <= kStageBytes, "stage too small");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    AMX_BARRIER();
+    const int w = wm * WN + wn;
+    uint8_t* stage = w == 0 ? lds0 : w == 1 ? lds1 : w == 2 ? lds2 : lds3;
+    store_glu_tiles<FM, FN>(acc, stage, reinterpret_cast<uint16_t*>(C) + b * M * ldc, M, N >> 1, ldc,
+                            (int64_t)tm * (32 * FM * WM) + wm * FM * 32, (int64_t)tn * (32 * FN * WN) + wn * FN * 32);
+  } else
+    store_c_tiles<FM, FN>(acc, C + b * M * ldc, M, N, ldc, (int64_t)tm * (32 * FM * WM) + wm * FM * 32,
+                          (int64_t)tn * (32 * FN * WN) + wn * FN * 32);
 }
 
 bool fp6m_path_supported(int64_t M, int64_t N, int64_t K) {
@@ -481,7 +492,7 @@ bool fp6m_path_supported(int64_t M, int64_t N, int64_t K) {
 
 hipError_t launch_gemm_fp6m_path(int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
                                  const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch,
-                                 void* workspace, hipStream_t s, const KernelTimer& timer) {
+                                 void* workspace, hipStream_t s, const KernelTimer& timer, bool glu) {
   const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows), G = K >> 5;
   const int64_t max_steps = fp6_max_steps(K);
   uint8_t* Ap = reinterpret_cast<uint8_t*>(workspace);
@@ -509,9 +520,15 @@ hipError_t launch_gemm_fp6m_path(int64_t M, int64_t N, int64_t K, const uint8_t*
   int super_m;
   const unsigned grid = supertile_grid(tiles_m, tiles_n, super_m);
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
-  hipLaunchKernelGGL((gemm_fp6m_kernel<2, 2, 4, 4>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s, Ap, Asc,
-                     Bp, Bsc, plan, plan_stride, steps_offset, C, M, N, Mp, Np, (int)max_steps, ldc, tiles_m, tiles_n,
-                     super_m);
+  const int steps_cap = (int)max_steps;
+  if (glu)
+    hipLaunchKernelGGL((gemm_fp6m_kernel<2, 2, 4, 4, true>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s,
+                       Ap, Asc, Bp, Bsc, plan, plan_stride, steps_offset, C, M, N, Mp, Np, steps_cap, ldc, tiles_m,
+                       tiles_n, super_m);
+  else
+    hipLaunchKernelGGL((gemm_fp6m_kernel<2, 2, 4, 4>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s, Ap,
+                       Asc, Bp, Bsc, plan, plan_stride, steps_offset, C, M, N, Mp, Np, steps_cap, ldc, tiles_m, tiles_n,
+                       super_m);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (timer.stop) e = hipEventRecord(timer.stop, s);
   return e;

@@ -190,6 +190,45 @@ def test_merged_fp8_kernel_with_far_apart_sign_scales():
     assert G.rel_fro(Cs, Cr) <= 1e-6
 
 
+@pytest.mark.parametrize("gap", [8, 10])
+def test_merged_fp8_kernel_with_cancelling_sign_classes(gap):
+    """The error of the merged FP8 kernel is relative to the largest product of a 32-block, not to the block's sum, so
+    the hard case is a block whose positive and negative classes cancel. Every group of A holds one positive element
+    128 (scale 2^5, code 4) and negatives of magnitude <= 6 * 2^(5 - gap - 2); B weights the positive element with
+    0.5 and the negatives with 4 or 6, so that at a gap of 2^8 the sums come out at 1/60 of the summed magnitudes (at
+    2^10 the negatives can only take a third of the positive product away). Per row and in norm the result must stay inside
+    the tolerance; the sign-split and FP6 kernels are exact on the same operands."""
+    from paper_2411_09909_amd import binding
+    rng = np.random.default_rng(gap)
+    M, N, K = 64, 96, 256
+    unit = np.float32(2.0 ** (5 - gap))               # the negative class's scale
+    a = np.zeros((M, K), np.float32)
+    b = np.zeros((N, K), np.float32)
+    for g in range(K // 32):
+        a[:, 32 * g] = 128.0
+        n_neg = 23 if gap == 8 else 31
+        for i in range(M):
+            idx = 32 * g + 1 + rng.choice(31, n_neg, replace=False)
+            a[i, idx] = -6.0 * unit * rng.choice([1.0, 0.5, 0.75], n_neg).astype(np.float32)
+        b[:, 32 * g] = 0.5
+        b[:, 32 * g + 1:32 * g + 32] = rng.choice([4.0, 6.0], (N, 31)).astype(np.float32)
+    ac, as_ = ref.quantize(synth.f32_to_bf16_bits(a), 32, ref.E8M0_FLOOR, 1)
+    bc, bs = ref.quantize(synth.f32_to_bf16_bits(b), 32, ref.E8M0_FLOOR, 1)
+    assert int(as_[0, 0, 0]) - int(as_[0, 0, 1]) == gap   # the two scale exponents really are `gap` apart
+    Cr = ref.gemm(ac, as_, bc, bs, 32, ref.E8M0_FLOOR, 1)
+    terms = np.abs(ref.dequantize(ac, as_, 32, ref.E8M0_FLOOR, 1)) @ np.abs(ref.dequantize(bc, bs, 32, ref.E8M0_FLOOR, 1)).T
+    cancel = float(np.abs(Cr).mean() / np.abs(terms).mean())
+    C = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1, options=binding.gemm_options(pot_kernel="merged_fp8", few_rows=-1))
+    worst_row = max(G.rel_fro(C[i], Cr[i]) for i in range(M))
+    print("gap 2^%d: sums are %.4f of the summed magnitudes; merged FP8 error %.3g, worst row %.3g"
+          % (gap, cancel, G.rel_fro(C, Cr), worst_row))
+    assert cancel < (0.05 if gap == 8 else 0.8)
+    assert G.rel_fro(C, Cr) <= TOL and worst_row <= TOL
+    for kernel in ("merged_fp6", "split"):
+        Ce = G.gpu_gemm(ac, as_, bc, bs, ref.E8M0_FLOOR, 1, options=binding.gemm_options(pot_kernel=kernel, few_rows=-1))
+        assert G.rel_fro(Ce, Cr) <= 1e-6, kernel
+
+
 def test_measurement_aids_run_and_copy_is_a_copy():
     """The peak probes are measurement aids; here only: they launch, finish, report their operation count, and the
     streaming copy copies (ragged size: not a multiple of the grid)."""

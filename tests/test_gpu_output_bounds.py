@@ -105,7 +105,7 @@ def test_scaled_gemm_writes_only_its_window():
 def test_gated_gemm_writes_only_its_window(M, width, K, pad, scale, asym):
     """The GEMM with the gated activation as its epilogue writes BF16: through LDS with 16-byte stores when the output
     allows it (pad 8: leading dimension a multiple of 8), element by element otherwise (pad 3), on all three tiled
-    kernels (BF16 panels, block-scaled FP4, merged FP8)."""
+    kernels (BF16 panels, block-scaled FP4, merged FP6)."""
     import ctypes
     a = synth.activations(M, K, seed=M, n_outlier=1, outlier_gain=30.0)
     wg, wu = synth.weights(width, K, seed=3), synth.weights(width, K, seed=4)
