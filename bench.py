@@ -73,6 +73,16 @@ class HipEvents:
             self.hip.hipEventDestroy(b)
 
 
+def fp6_patterns(torch, codes):
+    """Packed E2M1 codes (two per byte) -> the same values as packed E3M2 patterns (four per three bytes, little
+    endian), for the FP6 peak probe only."""
+    table = torch.tensor([0, 8, 12, 14, 16, 18, 20, 22], dtype=torch.int32, device=codes.device)
+    nib = torch.stack((codes & 15, codes >> 4), dim=-1).flatten().to(torch.int64)
+    six = (table[nib & 7] | ((nib >> 3) << 5).to(torch.int32)).view(-1, 4)
+    word = six[:, 0] | (six[:, 1] << 6) | (six[:, 2] << 12) | (six[:, 3] << 18)
+    return torch.stack((word & 255, (word >> 8) & 255, (word >> 16) & 255), dim=-1).flatten().to(torch.uint8)
+
+
 def measured_peaks(binding, torch, xd, wd, dev, iterations=30000):
     """What this machine sustains, beside the datasheet peaks: register-resident MFMA loops (no memory traffic) on
     all-zero operands and on operand bits taken from the workload (quantized X and W of the bench: dequantized BF16
@@ -97,12 +107,14 @@ def measured_peaks(binding, torch, xd, wd, dev, iterations=30000):
                      (wh.float() * 0.125).to(torch.float16).view(torch.uint8), 16),
         "fp8": lanes(xh.to(torch.float8_e5m2).view(torch.uint8), wh.to(torch.float8_e5m2).view(torch.uint8), 32),
         "fp4": lanes(xc.flatten(), wc.flatten(), 16),
+        # the same codes as FP6 (E3M2) patterns, as the merged kernel for asymmetric power-of-two scales holds them
+        "fp6": lanes(fp6_patterns(torch, xc.flatten()), fp6_patterns(torch, wc.flatten()), 24),
     }
     zeros = torch.zeros((256, 64), dtype=torch.uint8, device=dev)
     sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
     res = {"unit": "TFLOP/s", "mfma_loop": {}}
     for kind, datasheet in (("bf16", PEAK_BF16_TFLOPS), ("f16", PEAK_BF16_TFLOPS), ("fp8", PEAK_FP8_TFLOPS),
-                            ("fp4", PEAK_FP4_TFLOPS)):
+                            ("fp6", PEAK_FP4_TFLOPS), ("fp4", PEAK_FP4_TFLOPS)):
         row = {"datasheet": datasheet}
         for label, op in (("zero_operands", zeros), ("workload_operands", operands[kind])):
             binding.peak_mfma(kind, op, 200, sink)  # module load, not timed
@@ -197,10 +209,11 @@ def main():
     C = torch.empty((M, N), dtype=torch.float32, device=dev)
     flops = 2.0 * M * N * K
 
-    def run_format(name, steps, warmup, e5m2_kernel="panel", pot_kernel="merged_fp6"):
+    def run_format(name, steps, warmup, e5m2_kernel="panel", pot_kernel="merged_fp6", prepared=False):
         """Times `steps` steps (cast X + GEMM against pre-cast W) in the given format; returns a dict of timings.
         e5m2_kernel: which of the library's three kernels for FP8-E5M2 scales multiplies; pot_kernel: which of the
-        kernels for asymmetric power-of-two scales (both ignored by the other formats)."""
+        kernels for asymmetric power-of-two scales (both ignored by the other formats). prepared: the GEMM is
+        amxfp4_gemm_prepared on weights whose kernel-private form was written once, outside the timed step."""
         kind, asym, mfma, peak = FORMATS[name]
         if name == "amxfp4_e8m0" and pot_kernel == "split":
             mfma, peak = "fp4", PEAK_FP4_TFLOPS
@@ -219,6 +232,8 @@ def main():
         xs = torch.empty(nsc, dtype=torch.uint8, device=dev)
         need = (binding.load().amxfp4_gemm_scaled_workspace_bytes(ctypes.byref(fmt), M, N, K, 1) if scaled
                 else binding.gemm_workspace_bytes(fmt, M, N, K, options=opts))
+        if prepared:
+            need = int(binding.load().amxfp4_gemm_prepared_workspace_bytes(ctypes.byref(fmt), M, N, K))
         ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else None
         xp = torch.empty(2, dtype=torch.float32, device=dev) if scaled else None
 
@@ -234,12 +249,17 @@ def main():
         wc, wsc = binding.quantize(fmt, wd, tensor_pair=wp)  # weights: cast once, outside the timed step
         torch.cuda.synchronize()
         t_cast_w = time.perf_counter() - t0
+        w_prepared = binding.prepare_weights(fmt, wc, wsc) if prepared else None
+        torch.cuda.synchronize()
 
         def step(pair=None):
             cast_x()
             if pair is not None:
                 binding.profile_next_gemm(pair[0], pair[1])
-            binding.gemm(fmt, xc, xs, wc, wsc, out=C, workspace=ws, a_pair=xp, b_pair=wp, options=opts)
+            if prepared:
+                binding.gemm_prepared(fmt, xc, xs, wc, wsc, w_prepared, out=C, workspace=ws)
+            else:
+                binding.gemm(fmt, xc, xs, wc, wsc, out=C, workspace=ws, a_pair=xp, b_pair=wp, options=opts)
 
         for _ in range(warmup):
             step()
@@ -259,7 +279,8 @@ def main():
         torch.cuda.synchronize()
         t_cast_x = (time.perf_counter() - t0) / steps
         return {"t_step": t_total / steps, "kern_ms": kern_ms, "t_cast_x": t_cast_x, "t_cast_w": t_cast_w,
-                "mfma": mfma, "peak": peak, "asym": asym, "workspace_bytes": need}
+                "mfma": mfma, "peak": peak, "asym": asym, "workspace_bytes": need,
+                "prepared_bytes": w_prepared.numel() if prepared else 0}
 
     def cast_bandwidth(name, reps=20):
         """The cast of X timed three ways, as GB/s of algorithmic bytes (2 B read + 0.5 B codes + scale bytes per
@@ -360,25 +381,31 @@ def main():
     # The formats that run on the block-scaled matrix instructions are part of every run (about ten steps each): OCP
     # MXFP4 and the asymmetric power-of-two format, each with its GEMM kernel's time and fraction of the peak of the
     # MFMA type it issues. --variants adds the rest.
-    cases = [("mxfp4_e8m0", "panel", "merged_fp6"), ("amxfp4_e8m0", "panel", "merged_fp6"),
-             ("amxfp4_e8m0", "panel", "merged_fp8"), ("amxfp4_e8m0", "panel", "split")]
+    cases = [("mxfp4_e8m0", "panel", "merged_fp6", False), ("amxfp4_e8m0", "panel", "merged_fp6", False),
+             ("amxfp4_e8m0", "panel", "merged_fp8", False), ("amxfp4_e8m0", "panel", "split", False)]
+    if args.format not in DOUBLE_SCALED and FORMATS[args.format][2] == "bf16":
+        # the headline format against weights whose BF16 expansion was written once (amxfp4_gemm_prepared): the step
+        # then expands only X; costs 2 bytes per weight element of extra memory
+        cases.insert(0, (args.format, "panel", "merged_fp6", True))
     if args.variants:
-        cases += [(name, "panel", "merged_fp6") for name in sorted(FORMATS) if name not in ("mxfp4_e8m0", "amxfp4_e8m0")]
-        cases += [(name, k, "merged_fp6") for name in ("amxfp4_e5m2", "mxfp4_e5m2") for k in ("hybrid", "fused")]
+        cases += [(name, "panel", "merged_fp6", False) for name in sorted(FORMATS) if name not in ("mxfp4_e8m0", "amxfp4_e8m0")]
+        cases += [(name, k, "merged_fp6", False) for name in ("amxfp4_e5m2", "mxfp4_e5m2") for k in ("hybrid", "fused")]
     if args.no_variants or args.group_size != 32:
         cases = []
     v_steps = max(3, min(args.steps, 10)) if not args.variants else max(3, args.steps // 2)
     v_warm = max(2, min(args.warmup, 5)) if not args.variants else max(2, args.warmup // 2)
-    for name, kern, pot in cases:
-        if name == args.format and kern == args.e5m2_kernel and pot == args.pot_kernel:
+    for name, kern, pot, prep in cases:
+        if name == args.format and kern == args.e5m2_kernel and pot == args.pot_kernel and not prep:
             continue
-        v = run_format(name, v_steps, v_warm, kern, pot)
-        label = name + ("[%s]" % kern if kern != "panel" else "") + ("[%s]" % pot if pot != "merged_fp6" else "")
+        v = run_format(name, v_steps, v_warm, kern, pot, prep)
+        label = (name + ("[%s]" % kern if kern != "panel" else "") + ("[%s]" % pot if pot != "merged_fp6" else "")
+                 + ("[prepared_w]" if prep else ""))
         out.setdefault("variants", {})[label] = {
             "value": round(flops / v["t_step"] / 1e12, 2), "unit": "TFLOP/s",
             "frac_of_fp4_mfma_peak": round(flops / v["t_step"] / 1e12 / PEAK_FP4_TFLOPS, 4),
             "ms_per_step": round(v["t_step"] * 1e3, 4), "steps": v_steps, "mfma": v["mfma"],
-            "workspace_MB": round(v["workspace_bytes"] / 1e6, 1), "gemm_kernel_ms": round(v["kern_ms"], 4),
+            "workspace_MB": round(v["workspace_bytes"] / 1e6, 1), "prepared_weights_MB": round(v["prepared_bytes"] / 1e6, 1),
+            "gemm_kernel_ms": round(v["kern_ms"], 4),
             "kernel_frac_of_mfma_peak": round(flops / (v["kern_ms"] * 1e-3) / 1e12 / v["peak"], 4),
             "kernel_traffic_bytes": MEASURED_TRAFFIC_VARIANTS.get(label) if args.workload == WORKLOAD else None}
     if peaks is not None:

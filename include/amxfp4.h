@@ -144,6 +144,31 @@ int amxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const 
                 int64_t batch, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Static weights. amxfp4_gemm re-derives the kernel's private form of B on every call (for FP8 scales and group sizes
+ * other than 32: the exact BF16 expansion, 4 x the bytes of the codes); for weights that stay, that work can be done
+ * once. The product is the same (Sec. 4.3), bit for bit what amxfp4_gemm returns.
+ *   amxfp4_weights_prepared_bytes   size of the prepared form of B [N][K]; 0 for formats whose kernels read B as it
+ *                                   is stored (power-of-two scales of 32-groups), for which the calls below need no
+ *                                   buffer and do what amxfp4_gemm does.
+ *   amxfp4_prepare_weights          writes it: `prepared` device out, 256-byte aligned, at least that many bytes
+ *                                   (AMX_ERR_WORKSPACE otherwise). Depends on fmt, N, K and B only.
+ *   amxfp4_gemm_prepared            C = A . B^T with B's prepared form. B_codes / B_scales are still passed: shapes
+ *                                   with few rows (M <= 256, see amxfp4_gemm) read B as packed codes and ignore
+ *                                   `prepared`. One problem per call (no batch). workspace: at least
+ *                                   amxfp4_gemm_prepared_workspace_bytes(), 256-byte aligned (A's expansion only).
+ * `prepared` is opaque, valid for this library build, fmt, N and K; the caller owns it and keeps it unchanged while
+ * calls that read it are in flight. Other arguments and status codes as amxfp4_gemm.
+ */
+size_t amxfp4_weights_prepared_bytes(const amx_format_t* fmt, int64_t N, int64_t K);
+int amxfp4_prepare_weights(const amx_format_t* fmt, int64_t N, int64_t K, const uint8_t* B_codes,
+                           const uint8_t* B_scales, void* prepared, size_t prepared_bytes, void* stream);
+size_t amxfp4_gemm_prepared_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K);
+int amxfp4_gemm_prepared(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                         const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, const void* prepared,
+                         size_t prepared_bytes, float* C, int64_t ldc, void* workspace, size_t workspace_bytes,
+                         void* stream);
+
+/*
  * amxfp4_gemm for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
  * capture, tight serving loops, harnesses that forbid allocation. Same product, same kernels and same results as
  * amxfp4_gemm (bit for bit), but the scratch the kernels need (operand panels, partial tiles) is a static device
@@ -311,9 +336,10 @@ int amxfp4_gemm_ex(const amx_format_t* fmt, const amx_gemm_options_t* opts, int6
  * 32x32 accumulator tiles per wave, `iterations` rounds, no memory traffic inside the loop) and writes the number of
  * floating-point operations it performs to the HOST double *flops; the caller times the call on `stream`.
  *   mfma       0 = BF16 32x32x16, 1 = block-scaled FP8 (E5M2) 32x32x64, 2 = block-scaled FP4 32x32x64 (unit scales),
- *              3 = FP16 32x32x16.
+ *              3 = FP16 32x32x16, 4 = block-scaled FP6 (E3M2) 32x32x64.
  *   operand    device, 16384 bytes, 16-byte aligned: lane t of a workgroup takes bytes 64t .. 64t+31 as its A and
- *              64t+32 .. 64t+63 as its B operand registers (BF16 and FP4 use the first 16 of each). The sustained
+ *              64t+32 .. 64t+63 as its B operand registers (BF16, FP16 and FP4 use the first 16 of each, FP6 the
+ *              first 24). The sustained
  *              rate depends on these bits (clock management), so pass zeros for the best case and a slice of a real
  *              operand for the realistic one.
  *   sink       device out, 512 * 256 floats (contents meaningless).

@@ -68,6 +68,15 @@ def load():
     L.amxfp4_gemm_ex.restype = ctypes.c_int
     L.amxfp4_gemm_static.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, i64, i64, vp]
     L.amxfp4_gemm_static.restype = ctypes.c_int
+    L.amxfp4_weights_prepared_bytes.argtypes = [fp, i64, i64]
+    L.amxfp4_weights_prepared_bytes.restype = ctypes.c_size_t
+    L.amxfp4_prepare_weights.argtypes = [fp, i64, i64, vp, vp, vp, ctypes.c_size_t, vp]
+    L.amxfp4_prepare_weights.restype = ctypes.c_int
+    L.amxfp4_gemm_prepared_workspace_bytes.argtypes = [fp, i64, i64, i64]
+    L.amxfp4_gemm_prepared_workspace_bytes.restype = ctypes.c_size_t
+    L.amxfp4_gemm_prepared.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, i64, vp,
+                                       ctypes.c_size_t, vp]
+    L.amxfp4_gemm_prepared.restype = ctypes.c_int
     f32, f64, i32 = ctypes.c_float, ctypes.c_double, ctypes.c_int32
     L.amxfp4_tensor_scale.argtypes = [vp, i64, i64, i64, vp, vp]
     L.amxfp4_quantize_scaled.argtypes = [fp, vp, i64, i64, i64, i64, vp, vp, vp, vp]
@@ -151,11 +160,11 @@ def profile_next_gemm(start_event, stop_event):
     _check(load().amxfp4_profile_next_gemm(start_event, stop_event))
 
 
-PEAK_MFMA = {"bf16": 0, "fp8": 1, "fp4": 2, "f16": 3}
+PEAK_MFMA = {"bf16": 0, "fp8": 1, "fp4": 2, "f16": 3, "fp6": 4}
 
 
 def peak_mfma(mfma, operand, iterations, sink):
-    """Launches the register-resident MFMA loop ("bf16" | "fp8" | "fp4") on the current stream; operand: 16384-byte
+    """Launches the register-resident MFMA loop ("bf16" | "f16" | "fp8" | "fp6" | "fp4") on the current stream; operand: 16384-byte
     CUDA tensor, sink: float32 CUDA tensor of 512 * 256 elements. Returns the floating-point operations it performs."""
     _need_cuda(operand, sink)
     if operand.numel() * operand.element_size() < 16384 or sink.numel() < 512 * 256 or sink.dtype != torch.float32:
@@ -347,6 +356,37 @@ def gemm_static(fmt, a_codes, a_scales, b_codes, b_scales, out):
     _check(load().amxfp4_gemm_static(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
                                      b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(), out.stride(-2), batch,
                                      _stream()))
+    return out
+
+
+def prepare_weights(fmt, b_codes, b_scales):
+    """amxfp4_prepare_weights: the prepared form of static weights b_codes [N, K/2] (a uint8 tensor, empty for formats
+    whose kernels read the weights as stored); pass it to gemm_prepared()."""
+    _need_cuda(b_codes, b_scales)
+    N, K = b_codes.shape[0], b_codes.shape[1] * 2
+    need = int(load().amxfp4_weights_prepared_bytes(ctypes.byref(fmt), N, K))
+    prepared = torch.empty(need, dtype=torch.uint8, device=b_codes.device)
+    _check(load().amxfp4_prepare_weights(ctypes.byref(fmt), N, K, b_codes.data_ptr(), b_scales.data_ptr(),
+                                         prepared.data_ptr() if need else None, need, _stream()))
+    return prepared
+
+
+def gemm_prepared(fmt, a_codes, a_scales, b_codes, b_scales, prepared, out=None, workspace=None):
+    """amxfp4_gemm_prepared: C = A . B^T with the weights' prepared form (prepare_weights()). One problem per call."""
+    _need_cuda(a_codes, a_scales, b_codes, b_scales)
+    M, K = a_codes.shape[0], a_codes.shape[1] * 2
+    N = b_codes.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=a_codes.device)
+    need = int(load().amxfp4_gemm_prepared_workspace_bytes(ctypes.byref(fmt), M, N, K))
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    n_prep = prepared.numel() * prepared.element_size()
+    _check(load().amxfp4_gemm_prepared(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
+                                       b_codes.data_ptr(), b_scales.data_ptr(), prepared.data_ptr() if n_prep else None,
+                                       n_prep, out.data_ptr(), out.stride(-2), ws_ptr, ws_len, _stream()))
     return out
 
 

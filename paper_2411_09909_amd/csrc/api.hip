@@ -220,7 +220,7 @@ size_t plan_workspace_bytes(const GemmPlan& p, bool asym, int64_t M, int64_t N, 
 int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
               const uint8_t* A_scales, const float* A_pair, const uint8_t* B_codes, const uint8_t* B_scales,
               const float* B_pair, float* C, int64_t ldc, int64_t batch, void* workspace, size_t workspace_bytes,
-              void* stream) {
+              void* stream, const void* B_panel = nullptr) {
   const bool scaled = A_pair != nullptr;
   if (int rc = check_format(&f)) return rc;
   if (int rc = check_options(opts)) return rc;
@@ -236,7 +236,8 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
       !aligned(C, 4))
     return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales and C 4-byte alignment");
   const GemmPlan plan = plan_gemm(f, opts, scaled, M, N, K, batch);
-  const size_t need = plan_workspace_bytes(plan, f.asymmetric != 0, M, N, K, batch);
+  if (plan.kernel != kGemmPanel) B_panel = nullptr;  // only the BF16-panel kernel reads an expanded B
+  const size_t need = B_panel ? amx::bf16_panel_bytes(M, K) : plan_workspace_bytes(plan, f.asymmetric != 0, M, N, K, batch);
   if (need > 0) {
     if (!workspace || workspace_bytes < need)
       return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
@@ -271,7 +272,7 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
       break;
     default:
       e = amx::launch_gemm_bf16_path(f.scale, asym, f.group_size, M, N, K, A_codes, A_scales, B_codes, B_scales, A_pair,
-                                     B_pair, C, ldc, batch, workspace, plan.tile, hs, timer);
+                                     B_pair, C, ldc, batch, workspace, plan.tile, hs, timer, false, B_panel);
   }
   return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm launch");
 }
@@ -438,6 +439,55 @@ int amxfp4_gemm_ex(const amx_format_t* fmt, const amx_gemm_options_t* opts, int6
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
   return gemm_impl(*fmt, opts, M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc, batch, workspace,
                    workspace_bytes, stream);
+}
+
+// Prepared weights: the formats whose large products run on the BF16-panel kernel (everything but power-of-two scales
+// of 32-groups) can have B's panel expanded once.
+size_t amxfp4_weights_prepared_bytes(const amx_format_t* fmt, int64_t N, int64_t K) {
+  if (!fmt || N <= 0 || K <= 0 || check_format(fmt) != AMX_OK) return 0;
+  const bool pot32 = fmt->group_size == 32 && (fmt->scale == AMX_SCALE_E8M0_FLOOR || fmt->scale == AMX_SCALE_E8M0_ROUND);
+  return pot32 ? 0 : amx::bf16_panel_bytes(N, K);
+}
+
+int amxfp4_prepare_weights(const amx_format_t* fmt, int64_t N, int64_t K, const uint8_t* B_codes,
+                           const uint8_t* B_scales, void* prepared, size_t prepared_bytes, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  if (int rc = check_format(fmt)) return rc;
+  if (int rc = check_shape(*fmt, N, K)) return rc;
+  if (N > kMaxGemmRows) return fail(AMX_ERR_INVALID_ARG, "N may be at most %lld", (long long)kMaxGemmRows);
+  if (!B_codes || !B_scales) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
+  if (!aligned(B_codes, 16) || !aligned(B_scales, 4)) return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales 4-byte alignment");
+  const size_t need = amxfp4_weights_prepared_bytes(fmt, N, K);
+  if (need == 0) return AMX_OK;  // this format's kernels read B as it is stored
+  if (!prepared || prepared_bytes < need)
+    return fail(AMX_ERR_WORKSPACE, "prepared buffer of %zu bytes needed, %zu given", need, prepared ? prepared_bytes : 0);
+  if (!aligned(prepared, 256)) return fail(AMX_ERR_INVALID_ARG, "prepared buffer must be 256-byte aligned");
+  const hipError_t e = amx::launch_expand_b_panel(fmt->scale, fmt->asymmetric != 0, fmt->group_size, N, K, B_codes, B_scales,
+                                                  prepared, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AMX_OK : hip_fail(e, "prepare_weights launch");
+}
+
+size_t amxfp4_gemm_prepared_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K) {
+  if (!fmt || M <= 0 || N <= 0 || K <= 0) return 0;
+  const GemmPlan plan = plan_gemm(*fmt, nullptr, false, M, N, K, 1);
+  if (plan.kernel == kGemmPanel && amxfp4_weights_prepared_bytes(fmt, N, K) > 0) return amx::bf16_panel_bytes(M, K);
+  return plan_workspace_bytes(plan, fmt->asymmetric != 0, M, N, K, 1);
+}
+
+int amxfp4_gemm_prepared(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,
+                         const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, const void* prepared,
+                         size_t prepared_bytes, float* C, int64_t ldc, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  if (int rc = check_format(fmt)) return rc;
+  const size_t need = N > 0 && K > 0 ? amxfp4_weights_prepared_bytes(fmt, N, K) : 0;
+  if (need > 0) {
+    if (!prepared || prepared_bytes < need)
+      return fail(AMX_ERR_WORKSPACE, "prepared buffer of %zu bytes needed, %zu given", need, prepared ? prepared_bytes : 0);
+    if (!aligned(prepared, 256)) return fail(AMX_ERR_INVALID_ARG, "prepared buffer must be 256-byte aligned");
+  }
+  return gemm_impl(*fmt, nullptr, M, N, K, A_codes, A_scales, nullptr, B_codes, B_scales, nullptr, C, ldc, 1, workspace,
+                   workspace_bytes, stream, need > 0 ? prepared : nullptr);
 }
 
 int amxfp4_gemm_static(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const uint8_t* A_codes,

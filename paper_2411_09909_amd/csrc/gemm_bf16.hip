@@ -26,6 +26,8 @@ size_t bf16_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch)
   return (size_t)(batch * (round_up(M, kPanelRows) + round_up(N, kPanelRows)) * Kp * 2);
 }
 
+size_t bf16_panel_bytes(int64_t rows, int64_t K) { return (size_t)(round_up(rows, kPanelRows) * round_up(K, kPanelK) * 2); }
+
 // ------------------------------------------------------------------------------------------------ expand ----------
 // grid: (ceil(Kp / 256), Rp / 32, batch); block 256 = 4 waves. A workgroup expands one 32-row block over a K span of
 // 256, i.e. whole 128-byte lines of every code row (neighbouring workgroups run on different XCDs with separate L2s,
@@ -357,16 +359,18 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
                                  const uint8_t* A_codes, const uint8_t* A_scales, const uint8_t* B_codes,
                                  const uint8_t* B_scales, const float* A_tensor_pair, const float* B_tensor_pair,
                                  float* C, int64_t ldc, int64_t batch, void* workspace, int tile, hipStream_t s,
-                                 const KernelTimer& timer, bool glu) {
+                                 const KernelTimer& timer, bool glu, const void* B_panel) {
   const int gs_log2 = group_size == 16 ? 4 : group_size == 32 ? 5 : group_size == 64 ? 6 : group_size == 128 ? 7 : -1;
   if (gs_log2 < 0 || K % group_size != 0 || K % 32 != 0) return hipErrorInvalidValue;
   const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows), Kp = round_up(K, kPanelK);
   uint16_t* Ap = reinterpret_cast<uint16_t*>(workspace);
-  uint16_t* Bp = Ap + batch * Mp * Kp;
+  const uint16_t* Bp = B_panel ? reinterpret_cast<const uint16_t*>(B_panel) : Ap + batch * Mp * Kp;
   hipError_t e = expand_dispatch(scale_kind, asym, gs_log2, A_codes, A_scales, M, K, Mp, Kp, batch, Ap, s);
   if (e != hipSuccess) return e;
-  e = expand_dispatch(scale_kind, asym, gs_log2, B_codes, B_scales, N, K, Np, Kp, batch, Bp, s);
-  if (e != hipSuccess) return e;
+  if (!B_panel) {  // (a panel the caller expanded once: launch_expand_b_panel)
+    e = expand_dispatch(scale_kind, asym, gs_log2, B_codes, B_scales, N, K, Np, Kp, batch, Ap + batch * Mp * Kp, s);
+    if (e != hipSuccess) return e;
+  }
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
   // Tile shape. 256 x 256 (4 waves of 128 x 128) has the least operand traffic and LDS reads per MFMA and is what
   // large problems use; a problem with fewer such tiles than the chip has CUs, or with one side much smaller than a
@@ -392,6 +396,14 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
   if (e != hipSuccess) return e;
   if (timer.stop) e = hipEventRecord(timer.stop, s);
   return e;
+}
+
+hipError_t launch_expand_b_panel(int scale_kind, bool asym, int64_t group_size, int64_t N, int64_t K,
+                                 const uint8_t* B_codes, const uint8_t* B_scales, void* panel, hipStream_t s) {
+  const int gs_log2 = group_size == 16 ? 4 : group_size == 32 ? 5 : group_size == 64 ? 6 : group_size == 128 ? 7 : -1;
+  if (gs_log2 < 0 || K % group_size != 0 || K % 32 != 0) return hipErrorInvalidValue;
+  return expand_dispatch(scale_kind, asym, gs_log2, B_codes, B_scales, N, K, round_up(N, kPanelRows), round_up(K, kPanelK),
+                         1, reinterpret_cast<uint16_t*>(panel), s);
 }
 
 }  // namespace amx

@@ -46,7 +46,12 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
                                  const uint8_t* A_codes, const uint8_t* A_scales, const uint8_t* B_codes,
                                  const uint8_t* B_scales, const float* A_tensor_pair, const float* B_tensor_pair,
                                  float* C, int64_t ldc, int64_t batch, void* workspace, int tile, hipStream_t s,
-                                 const KernelTimer& timer, bool glu = false);
+                                 const KernelTimer& timer, bool glu = false, const void* B_panel = nullptr);
+// B's panel alone, expanded once for weights that stay (bf16_panel_bytes(N, K) bytes); passed as B_panel above, the
+// call then expands only A and its workspace is bf16_panel_bytes(M, K) per batch entry.
+size_t bf16_panel_bytes(int64_t rows, int64_t K);
+hipError_t launch_expand_b_panel(int scale_kind, bool asym, int64_t group_size, int64_t N, int64_t K,
+                                 const uint8_t* B_codes, const uint8_t* B_scales, void* panel, hipStream_t s);
 
 // BF16 fragment-major panel [batch][Rp / 32][Kp / 16][64 lanes][8] of a quantized operand (rows >= R and columns >= K
 // zero; Rp % 32 == 0, Kp % 64 == 0). permute: the key order of the fused attention kernel's V operand (gemm_bf16.hip).

@@ -19,7 +19,7 @@ constexpr int kPeakTiles = 16;     // independent accumulators per wave
 constexpr int kPeakBlocks = 512;   // two rounds of one 4-wave workgroup per CU (the accumulators fill the registers)
 
 // KIND 0: v_mfma_f32_32x32x16_bf16; 1: block-scaled 32x32x64 with FP8 (E5M2) operands; 2: the same with FP4 operands;
-// 3: v_mfma_f32_32x32x16_f16.
+// 3: v_mfma_f32_32x32x16_f16; 4: the block-scaled instruction with FP6 (E3M2) operands.
 // operand: 256 lanes x 2 (A, B) x 32 bytes. sink: kPeakBlocks * 256 floats (keeps the loop alive).
 template <int KIND>
 __global__ __launch_bounds__(256) void peak_mfma_kernel(const uint8_t* __restrict__ operand, float* __restrict__ sink,
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void peak_mfma_kernel(const uint8_t* __restric
 #pragma unroll
       for (int i = 0; i < kPeakTiles; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
   } else {
-    // FP4 operands occupy the first four registers of the eight; unit block scales (E8M0 byte 127)
+    // FP4 operands occupy the first four registers of the eight, FP6 the first six; unit block scales (E8M0 byte 127)
     const i32x8 a = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
     const i32x8 b = {(int)b0[0], (int)b0[1], (int)b0[2], (int)b0[3], (int)b1[0], (int)b1[1], (int)b1[2], (int)b1[3]};
     const int unit = 0x7F7F7F7F;
@@ -52,6 +52,8 @@ __global__ __launch_bounds__(256) void peak_mfma_kernel(const uint8_t* __restric
       for (int i = 0; i < kPeakTiles; ++i) {
         if constexpr (KIND == 1)
           acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i], 1, 1, 0, unit, 0, unit);
+        else if constexpr (KIND == 4)
+          acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i], 3, 3, 0, unit, 0, unit);
         else
           acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i], 4, 4, 0, unit, 0, unit);
       }
@@ -76,8 +78,8 @@ extern "C" {
 int amxfp4_peak_mfma(int32_t mfma, const void* operand, int32_t iterations, float* sink, double* flops,
                      void* stream) {
   using namespace amx;
-  if (mfma < 0 || mfma > 3)
-    return report_error(AMX_ERR_INVALID_ARG, "mfma must be 0 (bf16), 1 (fp8), 2 (fp4) or 3 (f16)");
+  if (mfma < 0 || mfma > 4)
+    return report_error(AMX_ERR_INVALID_ARG, "mfma must be 0 (bf16), 1 (fp8), 2 (fp4), 3 (f16) or 4 (fp6)");
   if (!operand || !sink || !flops) return report_error(AMX_ERR_INVALID_ARG, "NULL pointer");
   if (iterations <= 0 || iterations > (1 << 22)) return report_error(AMX_ERR_INVALID_ARG, "iterations out of range");
   if (reinterpret_cast<uintptr_t>(operand) & 15) return report_error(AMX_ERR_INVALID_ARG, "operand must be 16-byte aligned");
@@ -89,8 +91,10 @@ int amxfp4_peak_mfma(int32_t mfma, const void* operand, int32_t iterations, floa
     hipLaunchKernelGGL(peak_mfma_kernel<1>, dim3(kPeakBlocks), dim3(256), 0, s, op, sink, iterations);
   else if (mfma == 2)
     hipLaunchKernelGGL(peak_mfma_kernel<2>, dim3(kPeakBlocks), dim3(256), 0, s, op, sink, iterations);
-  else
+  else if (mfma == 3)
     hipLaunchKernelGGL(peak_mfma_kernel<3>, dim3(kPeakBlocks), dim3(256), 0, s, op, sink, iterations);
+  else
+    hipLaunchKernelGGL(peak_mfma_kernel<4>, dim3(kPeakBlocks), dim3(256), 0, s, op, sink, iterations);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return report_hip_error(e, "peak probe launch");
   *flops = 2.0 * 32 * 32 * (mfma == 0 || mfma == 3 ? 16 : 64) * kPeakTiles * (double)iterations * 4 * kPeakBlocks;

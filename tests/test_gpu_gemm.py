@@ -236,7 +236,7 @@ def test_measurement_aids_run_and_copy_is_a_copy():
     from paper_2411_09909_amd import binding
     op = torch.randint(0, 256, (16384,), dtype=torch.uint8, device="cuda")
     sink = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
-    for kind, k in (("bf16", 16), ("f16", 16), ("fp8", 64), ("fp4", 64)):
+    for kind, k in (("bf16", 16), ("f16", 16), ("fp8", 64), ("fp6", 64), ("fp4", 64)):
         assert binding.peak_mfma(kind, op, 3, sink) == 2.0 * 32 * 32 * k * 16 * 3 * 4 * 512
     torch.cuda.synchronize()
     src = torch.randint(0, 256, (16 * 100003,), dtype=torch.uint8, device="cuda")
