@@ -249,7 +249,8 @@ int amxfp4_gemm_scaled(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K,
  *   V_codes/V_scales   [kv_heads][head_dim][Sk] operand: V^T, cast along the keys (amxfp4_quantize on each head's
  *                      [Sk][head_dim] matrix with row_stride 1, k_stride head_dim).
  *   out                device, [q_heads][Sq][head_dim] floats, 16-byte aligned.
- *   fmt->group_size must be 32 and head_dim 128 (AMX_ERR_UNSUPPORTED otherwise); Sk % 32 == 0; causal needs Sk >= Sq.
+ *   fmt->group_size must be 32 and head_dim 128 or 64 (AMX_ERR_UNSUPPORTED otherwise); Sk % 32 == 0; causal needs
+ *   Sk >= Sq.
  *   workspace          at least amxfp4_attention_workspace_bytes() bytes, 256-byte aligned.
  * amxfp4_profile_next_gemm also arms this call (events around the attention kernel proper).
  */

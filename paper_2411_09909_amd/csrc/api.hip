@@ -572,8 +572,8 @@ int amxfp4_gemm_scaled(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K,
 
 size_t amxfp4_attention_workspace_bytes(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq,
                                         int64_t Sk, int64_t head_dim) {
-  if (!fmt || q_heads <= 0 || kv_heads <= 0 || Sq <= 0 || Sk <= 0 || head_dim != 128) return 0;
-  return amx::attention_workspace_bytes(q_heads, kv_heads, Sq, Sk);
+  if (!fmt || q_heads <= 0 || kv_heads <= 0 || Sq <= 0 || Sk <= 0 || (head_dim != 128 && head_dim != 64)) return 0;
+  return amx::attention_workspace_bytes(q_heads, kv_heads, Sq, Sk, head_dim);
 }
 
 static int attention_impl(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq, int64_t Sk,
@@ -584,7 +584,8 @@ static int attention_impl(const amx_format_t* fmt, int64_t q_heads, int64_t kv_h
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
   if (int rc = check_format(fmt)) return rc;
   if (fmt->group_size != 32) return fail(AMX_ERR_UNSUPPORTED, "the fused attention takes groups of 32 (one group per key tile)");
-  if (head_dim != 128) return fail(AMX_ERR_UNSUPPORTED, "the fused attention is built for head_dim 128 (got %lld)", (long long)head_dim);
+  if (head_dim != 128 && head_dim != 64)
+    return fail(AMX_ERR_UNSUPPORTED, "the fused attention is built for head_dim 128 and 64 (got %lld)", (long long)head_dim);
   if (q_heads <= 0 || kv_heads <= 0 || q_heads % kv_heads != 0 || q_heads > 65535)
     return fail(AMX_ERR_INVALID_ARG, "q_heads must be a positive multiple of kv_heads (at most 65535)");
   if (Sq <= 0 || Sk <= 0 || Sk % 32 != 0 || Sk > (1 << 20) || Sq > (1 << 20))
@@ -597,13 +598,13 @@ static int attention_impl(const amx_format_t* fmt, int64_t q_heads, int64_t kv_h
   if (!aligned(Q_codes, 16) || !aligned(K_codes, 16) || !aligned(V_codes, 16) || !aligned(Q_scales, 2) ||
       !aligned(K_scales, 2) || !aligned(V_scales, 2) || !aligned(out, 16))
     return fail(AMX_ERR_INVALID_ARG, "codes and out need 16-byte, scales 2-byte alignment");
-  const size_t need = amx::attention_workspace_bytes(q_heads, kv_heads, Sq, Sk);
+  const size_t need = amx::attention_workspace_bytes(q_heads, kv_heads, Sq, Sk, head_dim);
   if (!workspace || workspace_bytes < need)
     return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
   if (!aligned(workspace, 256)) return fail(AMX_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
   const amx::KernelTimer timer = g_timer;
   g_timer = amx::KernelTimer();
-  hipError_t e = amx::launch_attention_fused(fmt->scale, fmt->asymmetric != 0, q_heads, kv_heads, Sq, Sk, Q_codes,
+  hipError_t e = amx::launch_attention_fused(fmt->scale, fmt->asymmetric != 0, q_heads, kv_heads, Sq, Sk, head_dim, Q_codes,
                                              Q_scales, K_codes, K_scales, V_codes, V_scales, scale, causal,
                                              reinterpret_cast<float*>(out), merged_bf16, workspace, reinterpret_cast<hipStream_t>(stream), timer);
   return e == hipSuccess ? AMX_OK : hip_fail(e, "attention launch");

@@ -23,19 +23,21 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kAttnD = 128;                 // head dimension
 constexpr int kAttnWaves = 8;               // waves per workgroup, 32 queries each
 constexpr int kAttnQ = 32 * kAttnWaves;     // queries per workgroup
-constexpr int kAttnKFrags = kAttnD / 16;    // K fragments of one key tile (one per 16 of D)
-constexpr int kAttnVFrags = (kAttnD / 32) * 2;  // V^T fragments of one key tile: D / 32 row blocks x 2 k-steps
-constexpr int kAttnLoads = kAttnKFrags / kAttnWaves;  // K (and V) fragments a wave brings in per key tile
-static_assert(kAttnKFrags == kAttnVFrags && kAttnKFrags % kAttnWaves == 0, "fragments must divide over the waves");
 
-template <int SCALE_KIND>
+// kAttnD: the head dimension, 128 or 64. A key tile is kAttnD / 16 K fragments (one per 16 of D) and as many V^T
+// fragments (D / 32 row blocks x 2 k-steps), dealt over the eight waves: one K and one V fragment each for 128, one
+// fragment each (waves 0-3 K, waves 4-7 V) for 64.
+template <int SCALE_KIND, int kAttnD>
 __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
     const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Kp, const uint16_t* __restrict__ Vp,
     float* __restrict__ out, int Sq, int Sk, int Sqp, int Skv, int kv_group, float scale_log2, int causal,
     int merged_bf16) {
+  static_assert(kAttnD == 128 || kAttnD == 64, "head dimension");
+  constexpr int kAttnKFrags = kAttnD / 16, kAttnVFrags = (kAttnD / 32) * 2;
+  static_assert(kAttnKFrags == kAttnVFrags && (kAttnKFrags % kAttnWaves == 0 || 2 * kAttnKFrags == kAttnWaves),
+                "fragments must divide over the waves");
   // two stages of (K tile, V tile), separate arrays so that loads into one stage are known not to alias reads of the
   // other
   __shared__ __attribute__((aligned(1024))) uint8_t ldsK0[kAttnKFrags * kFragBytes];
@@ -77,13 +79,24 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
   // wave w brings K fragments w, w + kAttnWaves, .. and the V fragments of the same numbers (V fragment f = row block
   // f / 2, k-step f % 2) of tile T into stage (DK, DV)
 #define AMX_ATTN_LOAD(T, DK, DV)                                                                                   \
-  _Pragma("unroll") for (int i_ = 0; i_ < kAttnLoads; ++i_) {                                                      \
-    const int f_ = wave + kAttnWaves * i_;                                                                         \
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(Kr, (lds_ptr_t)((DK) + f_ * kFragBytes), 16, lane_off,                \
-                                             ((T) * kAttnKFrags + f_) * kFragBytes, 0, 0);                         \
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(Vr, (lds_ptr_t)((DV) + f_ * kFragBytes), 16, lane_off,                \
-                                             ((f_ >> 1) * (Skv / 16) + (f_ & 1) + 2 * (T)) * kFragBytes, 0, 0);    \
-  }
+  do {                                                                                                             \
+    if constexpr (kAttnKFrags >= kAttnWaves) {                                                                     \
+      _Pragma("unroll") for (int i_ = 0; i_ < kAttnKFrags / kAttnWaves; ++i_) {                                    \
+        const int f_ = wave + kAttnWaves * i_;                                                                     \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(Kr, (lds_ptr_t)((DK) + f_ * kFragBytes), 16, lane_off,            \
+                                                 ((T) * kAttnKFrags + f_) * kFragBytes, 0, 0);                     \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(Vr, (lds_ptr_t)((DV) + f_ * kFragBytes), 16, lane_off,            \
+                                                 ((f_ >> 1) * (Skv / 16) + (f_ & 1) + 2 * (T)) * kFragBytes, 0, 0);\
+      }                                                                                                            \
+    } else if (wave < kAttnKFrags) { /* uniform over the wave */                                                   \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(Kr, (lds_ptr_t)((DK) + wave * kFragBytes), 16, lane_off,            \
+                                               ((T) * kAttnKFrags + wave) * kFragBytes, 0, 0);                     \
+    } else {                                                                                                       \
+      const int f_ = wave - kAttnKFrags;                                                                           \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(Vr, (lds_ptr_t)((DV) + f_ * kFragBytes), 16, lane_off,              \
+                                               ((f_ >> 1) * (Skv / 16) + (f_ & 1) + 2 * (T)) * kFragBytes, 0, 0);  \
+    }                                                                                                              \
+  } while (0)
 
   // this wave's 32 queries as the B operand of the first product: 8 k-steps over D, resident in registers
   bf16x8 qf[kAttnKFrags];
@@ -226,23 +239,24 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
   }
 }
 
-size_t attention_workspace_bytes(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk) {
-  return (size_t)((Hq * round_up(Sq, 32) + Hkv * Sk + Hkv * round_up(Sk, 64)) * kAttnD * 2);
+size_t attention_workspace_bytes(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk, int64_t head_dim) {
+  return (size_t)((Hq * round_up(Sq, 32) + Hkv * Sk + Hkv * round_up(Sk, 64)) * head_dim * 2);
 }
 
-template <int SK>
+template <int SK, int kAttnD>
 static hipError_t launch_attn(const uint16_t* Qp, const uint16_t* Kp, const uint16_t* Vp, float* out, int64_t Hq,
                               int64_t Hkv, int64_t Sq, int64_t Sk, float scale, int causal, int merged_bf16,
                               hipStream_t s) {
   const int64_t Sqp = round_up(Sq, 32);
   const dim3 grid((unsigned)Hq, (unsigned)((Sqp + kAttnQ - 1) / kAttnQ));
-  hipLaunchKernelGGL((attention_fused_kernel<SK>), grid, dim3(64 * kAttnWaves), 0, s, Qp, Kp, Vp, out, (int)Sq,
+  hipLaunchKernelGGL((attention_fused_kernel<SK, kAttnD>), grid, dim3(64 * kAttnWaves), 0, s, Qp, Kp, Vp, out, (int)Sq,
                      (int)Sk, (int)Sqp, (int)round_up(Sk, 64), (int)(Hq / Hkv), scale * 1.4426950408889634f, causal,
                      merged_bf16);
   return hipGetLastError();
 }
 
-hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk,
+template <int kAttnD>
+static hipError_t launch_attention_fused_d(int scale_kind, bool asym, int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk,
                                   const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
                                   const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
                                   int causal, float* out, bool merged_bf16, void* workspace, hipStream_t s,
@@ -260,15 +274,29 @@ hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t
   if (e != hipSuccess) return e;
   if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
   switch (scale_kind) {
-    case kScaleE5M2: e = launch_attn<kScaleE5M2>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
-    case kScaleE4M3: e = launch_attn<kScaleE4M3>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
-    case kScaleE8M0Floor: e = launch_attn<kScaleE8M0Floor>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
-    case kScaleE8M0Round: e = launch_attn<kScaleE8M0Round>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
+    case kScaleE5M2: e = launch_attn<kScaleE5M2, kAttnD>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
+    case kScaleE4M3: e = launch_attn<kScaleE4M3, kAttnD>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
+    case kScaleE8M0Floor: e = launch_attn<kScaleE8M0Floor, kAttnD>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
+    case kScaleE8M0Round: e = launch_attn<kScaleE8M0Round, kAttnD>(Qp, Kp, Vp, out, Hq, Hkv, Sq, Sk, scale, causal, merged_bf16, s); break;
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;
   if (timer.stop) e = hipEventRecord(timer.stop, s);
   return e;
+}
+
+hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk,
+                                  int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales,
+                                  const uint8_t* K_codes, const uint8_t* K_scales, const uint8_t* V_codes,
+                                  const uint8_t* V_scales, float scale, int causal, float* out, bool merged_bf16,
+                                  void* workspace, hipStream_t s, const KernelTimer& timer) {
+  if (head_dim == 128)
+    return launch_attention_fused_d<128>(scale_kind, asym, Hq, Hkv, Sq, Sk, Q_codes, Q_scales, K_codes, K_scales, V_codes,
+                                         V_scales, scale, causal, out, merged_bf16, workspace, s, timer);
+  if (head_dim == 64)
+    return launch_attention_fused_d<64>(scale_kind, asym, Hq, Hkv, Sq, Sk, Q_codes, Q_scales, K_codes, K_scales, V_codes,
+                                        V_scales, scale, causal, out, merged_bf16, workspace, s, timer);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace amx

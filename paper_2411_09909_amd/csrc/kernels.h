@@ -69,14 +69,14 @@ hipError_t launch_gemm_skinny_path(int scale_kind, bool asym, int64_t M, int64_t
                                    int64_t ldc, int64_t batch, void* workspace, int forced_slices, hipStream_t s,
                                    const KernelTimer& timer);
 
-// attention.hip: fused quantized attention, head dimension 128, groups of 32 (workspace: the three BF16 panels).
-// merged_bf16: out is BF16 [Sq][Hq * 128] (token-major) instead of FP32 [Hq][Sq][128]
-size_t attention_workspace_bytes(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk);
+// attention.hip: fused quantized attention, head dimension 128 or 64, groups of 32 (workspace: the three BF16 panels).
+// merged_bf16: out is BF16 [Sq][Hq * head_dim] (token-major) instead of FP32 [Hq][Sq][head_dim]
+size_t attention_workspace_bytes(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk, int64_t head_dim);
 hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk,
-                                  const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
-                                  const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
-                                  int causal, float* out, bool merged_bf16, void* workspace, hipStream_t s,
-                                  const KernelTimer& timer);
+                                  int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales,
+                                  const uint8_t* K_codes, const uint8_t* K_scales, const uint8_t* V_codes,
+                                  const uint8_t* V_scales, float scale, int causal, float* out, bool merged_bf16,
+                                  void* workspace, hipStream_t s, const KernelTimer& timer);
 
 // layer_ops.hip: RMS normalisation (after an optional residual addition y, whose BF16 sum goes to sum_out) with the
 // cast of the normalised row fused in; groups of 16, 32 or 64 dividing dim <= 16384

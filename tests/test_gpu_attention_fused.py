@@ -15,14 +15,14 @@ pytestmark = pytest.mark.gpu
 D = 128
 
 
-def heads(n, S, seed, gain=1.0):
-    x = synth.activations(n * S, D, seed=seed, n_outlier=2, outlier_gain=20.0)
-    return synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(x) * np.float32(gain)).reshape(n, S, D)
+def heads(n, S, seed, gain=1.0, d=D):
+    x = synth.activations(n * S, d, seed=seed, n_outlier=2, outlier_gain=20.0)
+    return synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(x) * np.float32(gain)).reshape(n, S, d)
 
 
 def gpu_attention(q, k, v, scale, causal, scale_format, asym):
     fmt = binding.make_format(scale_format, asym, 32)
-    Hq, Sq, _ = q.shape
+    Hq, Sq, D = q.shape   # (the head dimension of this call, 128 or 64)
     Hkv, Sk, _ = k.shape
     qc, qs = binding.quantize(fmt, G.to_dev_bf16(q.reshape(Hq * Sq, D)))
     kc, ks = binding.quantize(fmt, G.to_dev_bf16(k.reshape(Hkv * Sk, D)))
@@ -44,8 +44,9 @@ def compare(out, want):
     measured worst) on all but at most 0.5 % of the rows, which may carry a flip and stay within 2e-2; 2e-6 overall
     when no row carries one, 1e-3 in any case."""
     assert out.shape == want.shape and np.isfinite(out).all()
-    num = np.linalg.norm((out - want).reshape(-1, D).astype(np.float64), axis=1)
-    den = np.linalg.norm(want.reshape(-1, D).astype(np.float64), axis=1)
+    d = out.shape[-1]
+    num = np.linalg.norm((out - want).reshape(-1, d).astype(np.float64), axis=1)
+    den = np.linalg.norm(want.reshape(-1, d).astype(np.float64), axis=1)
     rel = num / np.maximum(den, 1e-30)
     overall = G.rel_fro(out, want)
     print("fused attention %s: overall %.3g, worst row %.3g" % (out.shape, overall, float(rel.max())))
@@ -75,6 +76,41 @@ def test_grouped_heads_ragged_queries_and_longer_keys(Hq, Hkv, Sq, Sk, causal):
     q, k, v = heads(Hq, Sq, 4), heads(Hkv, Sk, 5), heads(Hkv, Sk, 6)
     want = attention_ref.fused_attention(q, k, v, D ** -0.5, causal)
     compare(gpu_attention(q, k, v, D ** -0.5, causal, ref.FP8_E5M2, 1), want)
+
+
+@pytest.mark.parametrize("scale_format,asym", FORMATS)
+@pytest.mark.parametrize("Hq,Hkv,Sq,Sk,causal", [(2, 2, 320, 320, True), (4, 2, 70, 160, True), (3, 1, 33, 96, False),
+                                                 (1, 1, 1, 64, True)])
+def test_head_dimension_64(Hq, Hkv, Sq, Sk, causal, scale_format, asym):
+    """The same kernel instantiated for heads of 64: four K and four V fragments per key tile, one per wave (waves 0-3
+    bring in K, waves 4-7 V), two groups of 32 along the head dimension."""
+    q, k, v = heads(Hq, Sq, 31, d=64), heads(Hkv, Sk, 32, d=64), heads(Hkv, Sk, 33, d=64)
+    want = attention_ref.fused_attention(q, k, v, 64 ** -0.5, causal, scale_format, asym)
+    compare(gpu_attention(q, k, v, 64 ** -0.5, causal, scale_format, asym), want)
+
+
+def test_head_dimension_64_merged_output_and_long_sequence():
+    """Heads of 64 at a length with many key tiles and several workgroups per head, written merged (BF16, token-major):
+    bit for bit the head merge of the FP32 result; sampled rows of that against the oracle."""
+    Hq, Hkv, S, d = 8, 2, 2048, 64
+    q, _, _ = synth.attention_qkv(Hq, S, d, seed=3)
+    _, k, v = synth.attention_qkv(Hkv, S, d, seed=4)
+    fmt = binding.make_format(ref.FP8_E5M2, 1, 32)
+    qc, qs = binding.quantize(fmt, G.to_dev_bf16(q.reshape(Hq * S, d)))
+    kc, ks = binding.quantize(fmt, G.to_dev_bf16(k.reshape(Hkv * S, d)))
+    vc, vs = binding.quantize_batched(fmt, G.to_dev_bf16(v.reshape(Hkv * S, d)).view(Hkv, S, d), k_axis=1)
+    args = (fmt, qc.view(Hq, S, -1), qs.view(Hq, S, d // 32, 2), kc.view(Hkv, S, -1), ks.view(Hkv, S, d // 32, 2),
+            vc, vs, d ** -0.5, True)
+    plain = binding.attention(*args)
+    merged = binding.attention(*args, merged=True)
+    torch.cuda.synchronize()
+    assert tuple(plain.shape) == (Hq, S, d) and tuple(merged.shape) == (S, Hq * d)
+    want_merged = binding.merge_heads(plain.view(Hq, S, d), Hq, 1, S, d)
+    assert torch.equal(merged.view(torch.int16), want_merged.view(torch.int16))
+    rows = [0, 31, 32, 255, 256, 1023, 1024, S - 33, S - 1]
+    hs = [0, 3, Hq - 1]
+    want = attention_ref.fused_attention(q, k, v, d ** -0.5, True, ref.FP8_E5M2, 1, heads=hs, rows=rows)
+    compare(plain.cpu().numpy()[np.ix_(hs, rows)], want[np.ix_(hs, rows)])
 
 
 def test_closed_forms_on_the_gpu():
@@ -135,8 +171,8 @@ def test_invalid_arguments():
     with pytest.raises(binding.AmxError):   # causal with fewer keys than queries
         binding.attention(fmt, z(1, 64, 64), z(1, 64, 4, 2), z(1, 32, 64), z(1, 32, 4, 2), z(1, 128, 16), z(1, 128, 1, 2),
                           0.1, True)
-    with pytest.raises(binding.AmxError):   # head dimension 64
-        binding.attention(fmt, z(1, 32, 32), z(1, 32, 2, 2), z(1, 32, 32), z(1, 32, 2, 2), z(1, 64, 16), z(1, 64, 1, 2),
+    with pytest.raises(binding.AmxError):   # head dimension 32
+        binding.attention(fmt, z(1, 32, 16), z(1, 32, 1, 2), z(1, 32, 16), z(1, 32, 1, 2), z(1, 32, 16), z(1, 32, 1, 2),
                           0.1, True)
     f16 = binding.make_format(ref.FP8_E5M2, 1, 16)
     with pytest.raises(binding.AmxError):   # groups of 16
