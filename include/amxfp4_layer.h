@@ -45,6 +45,19 @@ int amxfp4_split_heads_rope(const float* in, int64_t seq, int64_t ld, int64_t co
                             int32_t rotate, int64_t pos0, double theta, void* out_bf16, void* stream);
 
 /*
+ * amxfp4_split_heads_rope with rotate != 0 followed by amxfp4_quantize of every head along head_dim (Appendix B
+ * Algorithm 1 / Sec. 4.2 Eq. 1; Sec. 5.1 quantizes the operands of Q.K^T), in one pass: the rotated BF16 heads are
+ * never written. codes [heads][seq][head_dim / 2] and scales [heads][seq][head_dim / 32] (x 2 when asymmetric) come out
+ * bit for bit as from the two separate calls: the Q and K operands of amxfp4_attention.
+ *   fmt        group_size 32 (AMX_ERR_UNSUPPORTED otherwise); head_dim 64, 128, 192 or 256
+ *   in         [seq][ld] FP32, 16-byte aligned, ld and col0 multiples of 4; other arguments as amxfp4_split_heads_rope
+ *   codes      device out, 4-byte aligned; scales device out, 2-byte aligned
+ */
+int amxfp4_split_heads_rope_quantize(const amx_format_t* fmt, const float* in, int64_t seq, int64_t ld, int64_t col0,
+                                     int64_t heads, int64_t head_dim, int64_t pos0, double theta, uint8_t* codes,
+                                     uint8_t* scales, void* stream);
+
+/*
  * Causal softmax of attention scores. scores: [batch, rows, cols] FP32, contiguous; row r of every batch entry
  * belongs to the query at position r % cols (several query heads that share one key head may be stacked along the
  * rows); it attends to key columns c <= r % cols. out[b, r, c] = bf16( exp(scale * (s[c] - max)) / sum ) over the

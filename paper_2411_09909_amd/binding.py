@@ -99,6 +99,7 @@ def load():
     L.amxfp4_peak_copy.restype = ctypes.c_int
     for name, args in (("amxfp4_rmsnorm", [vp, vp, i64, i64, f32, vp, vp]),
                        ("amxfp4_split_heads_rope", [vp, i64, i64, i64, i64, i64, i32, i64, f64, vp, vp]),
+                       ("amxfp4_split_heads_rope_quantize", [fp, vp, i64, i64, i64, i64, i64, i64, f64, vp, vp, vp]),
                        ("amxfp4_softmax_causal", [vp, i64, i64, i64, f32, vp, vp]),
                        ("amxfp4_silu_mul", [vp, i64, i64, vp, vp]),
                        ("amxfp4_residual_add", [vp, vp, i64, vp, vp]),
@@ -467,6 +468,21 @@ def split_heads_rope(proj, col0, heads, head_dim, rotate, pos0=0, theta=10000.0)
     _check(load().amxfp4_split_heads_rope(proj.data_ptr(), seq, proj.stride(0), col0, heads, head_dim,
                                           1 if rotate else 0, pos0, theta, out.data_ptr(), _stream()))
     return out
+
+
+def split_heads_rope_quantize(fmt, proj, col0, heads, head_dim, pos0=0, theta=10000.0):
+    """split_heads_rope(rotate=True) followed by quantize() along head_dim, in one launch: (codes [heads, seq,
+    head_dim / 2], scales [heads, seq, head_dim / 32(, 2)]), the Q or K operand of attention()."""
+    _need_cuda(proj)
+    assert proj.dtype == torch.float32 and proj.dim() == 2 and proj.stride(1) == 1
+    seq = proj.shape[0]
+    codes = torch.empty((heads, seq, head_dim // 2), dtype=torch.uint8, device=proj.device)
+    scales = torch.empty((heads, seq, head_dim // 32) + ((2,) if fmt.asymmetric else ()), dtype=torch.uint8,
+                         device=proj.device)
+    _check(load().amxfp4_split_heads_rope_quantize(ctypes.byref(fmt), proj.data_ptr(), seq, proj.stride(0), col0, heads,
+                                                   head_dim, pos0, theta, codes.data_ptr(), scales.data_ptr(),
+                                                   _stream()))
+    return codes, scales
 
 
 def softmax_causal(scores, scale):

@@ -175,6 +175,64 @@ __global__ __launch_bounds__(256) void split_heads_rope_kernel(const float* __re
   }
 }
 
+// split_heads_rope_kernel (rotate) followed by the cast of its result along the head dimension, in one pass: the
+// rotated BF16 heads are never written. One thread per (token, run of 8 dimensions d0 .. d0 + 7 below head_dim / 2)
+// and chunk of kRopeHeads heads: it forms the 8 outputs at d0 .. and the 8 at d0 + head_dim / 2 .. (they share their
+// angles), each run is one lane's share of a group of 32, and the four neighbouring threads of a group exchange their
+// extrema as the cast kernel's lanes do (cast_core.h). head_dim % 64 == 0, so a group never straddles the two halves
+// and the threads of a token are a whole number of quads. Same arithmetic as the two separate kernels: same bits.
+template <int SCALE_KIND, bool ASYM>
+__global__ __launch_bounds__(256) void rope_quantize_kernel(const float* __restrict__ in, int64_t seq, int64_t ld,
+                                                            int64_t col0, int64_t heads, int half, int64_t pos0,
+                                                            double log_theta, uint8_t* __restrict__ codes,
+                                                            uint8_t* __restrict__ scales) {
+  const int runs = half >> 3;  // threads per token
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= seq * runs) return;  // (whole quads: seq * runs is a multiple of 4)
+  const int j = (int)(idx % runs);
+  const int64_t s = idx / runs;
+  double sn[8], cs[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const double ang = (double)(pos0 + s) * exp(-log_theta * (double)(8 * j + e) / (double)half);
+    sincos(ang, &sn[e], &cs[e]);
+  }
+  const int groups = half >> 4;  // groups of 32 per head
+  const int64_t h0 = (int64_t)blockIdx.y * kRopeHeads, h1 = h0 + kRopeHeads < heads ? h0 + kRopeHeads : heads;
+  for (int64_t h = h0; h < h1; ++h) {
+    const float* p = in + s * ld + col0 + h * 2 * half + 8 * j;
+    const float4 a0 = *reinterpret_cast<const float4*>(p), a1 = *reinterpret_cast<const float4*>(p + 4);
+    const float4 b0 = *reinterpret_cast<const float4*>(p + half), b1 = *reinterpret_cast<const float4*>(p + half + 4);
+    const float x1[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+    const float x2[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+    float o1[8], o2[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      o1[e] = (float)((double)x1[e] * cs[e] - (double)x2[e] * sn[e]);
+      o2[e] = (float)((double)x2[e] * cs[e] + (double)x1[e] * sn[e]);
+    }
+    const uint32_t d1[4] = {pack2(o1[0], o1[1]), pack2(o1[2], o1[3]), pack2(o1[4], o1[5]), pack2(o1[6], o1[7])};
+    const uint32_t d2[4] = {pack2(o2[0], o2[1]), pack2(o2[2], o2[3]), pack2(o2[4], o2[5]), pack2(o2[6], o2[7])};
+    uint32_t c1[1], c2[1], p1, n1, p2, n2;
+    cast_words_bf16<SCALE_KIND, ASYM, 8>(d1, 2, c1, p1, n1);
+    cast_words_bf16<SCALE_KIND, ASYM, 8>(d2, 2, c2, p2, n2);
+    const int64_t row = h * seq + s;
+    uint8_t* crow = codes + row * half;  // head_dim / 2 bytes of codes per row
+    *reinterpret_cast<uint32_t*>(crow + 4 * j) = c1[0];
+    *reinterpret_cast<uint32_t*>(crow + (half >> 1) + 4 * j) = c2[0];
+    if ((j & 3) == 0) {
+      const int64_t g1 = row * groups + (j >> 2), g2 = g1 + (groups >> 1);
+      if constexpr (ASYM) {
+        *reinterpret_cast<uint16_t*>(scales + g1 * 2) = (uint16_t)(p1 | (n1 << 8));
+        *reinterpret_cast<uint16_t*>(scales + g2 * 2) = (uint16_t)(p2 | (n2 << 8));
+      } else {
+        scales[g1] = (uint8_t)p1;
+        scales[g2] = (uint8_t)p2;
+      }
+    }
+  }
+}
+
 // one block per score row; a thread holds up to kSmMaxChunks runs of 8 columns
 constexpr int kSmMaxChunks = 8;  // 16384 columns
 __global__ __launch_bounds__(256) void softmax_causal_kernel(const float* __restrict__ s, int64_t rows, int64_t cols,
@@ -338,6 +396,45 @@ int amxfp4_split_heads_rope(const float* in, int64_t seq, int64_t ld, int64_t co
                      reinterpret_cast<hipStream_t>(stream), in, seq, ld, col0, heads, (int)(head_dim / 2),
                      (int)(rotate != 0), pos0, rotate ? log(theta) : 0.0, reinterpret_cast<uint16_t*>(out_bf16));
   return done("split_heads_rope launch");
+}
+
+int amxfp4_split_heads_rope_quantize(const amx_format_t* fmt, const float* in, int64_t seq, int64_t ld, int64_t col0,
+                                     int64_t heads, int64_t head_dim, int64_t pos0, double theta, uint8_t* codes,
+                                     uint8_t* scales, void* stream) {
+  if (!fmt || !in || !codes || !scales) return report_error(AMX_ERR_INVALID_ARG, "split_heads_rope_quantize: NULL pointer");
+  if (fmt->elem != AMX_ELEM_FP4_E2M1 || fmt->scale < AMX_SCALE_E8M0_FLOOR || fmt->scale > AMX_SCALE_FP8_E4M3 ||
+      (fmt->asymmetric != 0 && fmt->asymmetric != 1))
+    return report_error(AMX_ERR_INVALID_ARG, "split_heads_rope_quantize: bad format");
+  if (fmt->group_size != 32) return report_error(AMX_ERR_UNSUPPORTED, "split_heads_rope_quantize: groups of 32 only");
+  if (seq <= 0 || heads <= 0 || head_dim <= 0 || col0 < 0 || ld < col0 + heads * head_dim || pos0 < 0)
+    return report_error(AMX_ERR_INVALID_ARG, "split_heads_rope_quantize: bad shape");
+  if (head_dim % 64 || head_dim > 256)
+    return report_error(AMX_ERR_UNSUPPORTED, "split_heads_rope_quantize: head_dim must be 64, 128, 192 or 256");
+  if (!(theta > 1.0)) return report_error(AMX_ERR_INVALID_ARG, "split_heads_rope_quantize: theta must exceed 1");
+  if (!aligned16(in) || ld % 4 || col0 % 4 || (reinterpret_cast<uintptr_t>(codes) & 3) || (reinterpret_cast<uintptr_t>(scales) & 1))
+    return report_error(AMX_ERR_INVALID_ARG, "split_heads_rope_quantize: in must be 16-byte aligned with ld and col0 multiples "
+                        "of 4, codes 4-byte and scales 2-byte aligned");
+  const int64_t threads = seq * (head_dim / 16), head_chunks = (heads + kRopeHeads - 1) / kRopeHeads;
+  if (threads > (int64_t)0x7FFFFFFF * 256 || head_chunks > 65535)
+    return report_error(AMX_ERR_UNSUPPORTED, "split_heads_rope_quantize: too large");
+  const dim3 grid(blocks_for(threads), (unsigned)head_chunks);
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  const int half = (int)(head_dim / 2);
+  const double lt = log(theta);
+  auto go = [&]<int SK, bool ASYM>() {
+    hipLaunchKernelGGL((rope_quantize_kernel<SK, ASYM>), grid, dim3(256), 0, hs, in, seq, ld, col0, heads, half, pos0, lt,
+                       codes, scales);
+  };
+  const bool asym = fmt->asymmetric != 0;
+  switch (fmt->scale) {
+    case AMX_SCALE_FP8_E5M2: asym ? go.template operator()<kScaleE5M2, true>() : go.template operator()<kScaleE5M2, false>(); break;
+    case AMX_SCALE_FP8_E4M3: asym ? go.template operator()<kScaleE4M3, true>() : go.template operator()<kScaleE4M3, false>(); break;
+    case AMX_SCALE_E8M0_FLOOR:
+      asym ? go.template operator()<kScaleE8M0Floor, true>() : go.template operator()<kScaleE8M0Floor, false>();
+      break;
+    default: asym ? go.template operator()<kScaleE8M0Round, true>() : go.template operator()<kScaleE8M0Round, false>();
+  }
+  return done("split_heads_rope_quantize launch");
 }
 
 int amxfp4_softmax_causal(const float* scores, int64_t batch, int64_t rows, int64_t cols, float scale, void* out_bf16,

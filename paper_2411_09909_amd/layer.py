@@ -45,8 +45,13 @@ class DecoderLayer:
     """weights: dict name -> BF16 CUDA tensor (WEIGHT_SHAPES) plus "norm1" / "norm2" FP32 [d_model]. The weights are
     cast once here (they are static in inference); forward() casts the activations."""
 
-    def __init__(self, cfg, weights, fmt, baseline=False, fused_attention=False, fused_glu=None, fused_norm=None):
+    def __init__(self, cfg, weights, fmt, baseline=False, fused_attention=False, fused_glu=None, fused_norm=None,
+                 fused_rope=None):
         self.cfg, self.fmt, self.baseline, self.fused_attention = cfg, fmt, baseline, fused_attention
+        # the rotary embedding casts its result (Q and K never exist as BF16 tensors): same bits
+        if fused_rope is None:
+            fused_rope = fmt.group_size == 32 and cfg.head_dim % 64 == 0 and cfg.head_dim <= 256
+        self.fused_rope = fused_rope
         # the two normalisations cast their result in registers (and the second adds the residual first): same bits
         if fused_norm is None:
             fused_norm = fmt.group_size in (16, 32, 64) and cfg.d_model <= 16384
@@ -89,12 +94,16 @@ class DecoderLayer:
             qkv = self._gemm(binding.rmsnorm_quantize(self._plain_fmt(), x, self.norm1, c.eps), self.wqkv)
         else:
             qkv = self._gemm(self._cast(binding.rmsnorm(x, self.norm1, c.eps)), self.wqkv)
-        q = binding.split_heads_rope(qkv, 0, c.n_heads, D, True, pos0, c.rope_theta)
-        k = binding.split_heads_rope(qkv, c.n_heads * D, G, D, True, pos0, c.rope_theta)
         v = binding.split_heads_rope(qkv, (c.n_heads + G) * D, G, D, False)
-
-        qc, qs = self._cast(q.view(c.n_heads * S, D))
-        kc, ks = self._cast(k.view(G * S, D))
+        if self.fused_rope:
+            # rotary embedding and the cast of Q and K along the head dimension in one launch each (same bits)
+            qc, qs = binding.split_heads_rope_quantize(self._plain_fmt(), qkv, 0, c.n_heads, D, pos0, c.rope_theta)
+            kc, ks = binding.split_heads_rope_quantize(self._plain_fmt(), qkv, c.n_heads * D, G, D, pos0, c.rope_theta)
+        else:
+            q = binding.split_heads_rope(qkv, 0, c.n_heads, D, True, pos0, c.rope_theta)
+            k = binding.split_heads_rope(qkv, c.n_heads * D, G, D, True, pos0, c.rope_theta)
+            qc, qs = self._cast(q.view(c.n_heads * S, D))
+            kc, ks = self._cast(k.view(G * S, D))
         if self.fused_attention:
             vc, vs = self._cast_v(v, nsc)
             fmt = binding.make_format(self.fmt.scale, False, 32) if self.baseline else self.fmt

@@ -64,6 +64,34 @@ def test_split_heads_rope(rotate):
         assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16), want)
 
 
+@pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.FP8_E5M2, 0), (ref.E8M0_FLOOR, 1), (ref.E8M0_ROUND, 0),
+                                        (ref.FP8_E4M3, 1)])
+@pytest.mark.parametrize("seq,heads,d,col0", [(257, 5, 128, 64), (33, 8, 64, 0), (130, 11, 256, 128), (1, 1, 128, 0)])
+def test_split_heads_rope_quantize(seq, heads, d, col0, scale, asym):
+    """The rotary embedding that casts its own result: codes and scales bit for bit those of split_heads_rope followed by
+    quantize (whose parity with the oracle the tests above and the cast tests establish), and dequantized values within
+    the cast of the oracle's rotated heads wherever that did not land a BF16 step off."""
+    rng = np.random.default_rng(seq + d)
+    proj = (rng.standard_normal((seq, col0 + heads * d + 32)) * 4).astype(np.float32)
+    proj[:, col0 + 3] *= 40.0   # an outlier dimension in the first head
+    fmt = binding.make_format(scale, asym, 32)
+    pd = dev_f32(proj)
+    codes, scales = binding.split_heads_rope_quantize(fmt, pd, col0, heads, d, pos0=8000, theta=500000.0)
+    rotated = binding.split_heads_rope(pd, col0, heads, d, True, pos0=8000, theta=500000.0)
+    c2, s2 = binding.quantize(fmt, rotated.view(heads * seq, d))
+    torch.cuda.synchronize()
+    assert tuple(codes.shape) == (heads, seq, d // 2) and scales.shape[:3] == (heads, seq, d // 32)
+    assert torch.equal(codes.view(heads * seq, d // 2), c2)
+    assert torch.equal(scales.reshape(s2.shape), s2)
+    # and against the oracle end to end: rows whose rotated BF16 values agree must have identical codes and scales
+    want = L.split_heads_rope(proj, col0, heads, d, True, pos0=8000, theta=500000.0).reshape(heads * seq, d)
+    same = (rotated.view(torch.int16).cpu().numpy().view(np.uint16).reshape(heads * seq, d) == want).all(axis=1)
+    rc, rs = ref.quantize(want, 32, scale, asym)
+    assert same.mean() > 0.5
+    assert np.array_equal(codes.view(heads * seq, d // 2).cpu().numpy()[same], rc[same])
+    assert np.array_equal(scales.reshape(s2.shape).cpu().numpy()[same], rs[same])
+
+
 def test_softmax_causal():
     rng = np.random.default_rng(4)
     batch, per, seq = 2, 4, 264
