@@ -125,3 +125,88 @@ def test_close_to_exact_attention_of_the_quantized_operands(causal):
     exact = (p / p.sum(axis=1, keepdims=True)) @ vh
     rel = np.linalg.norm(out - exact) / np.linalg.norm(exact)
     assert 1e-4 < rel < 0.12
+
+
+# ---- split keys (the decoding shape) -----------------------------------------------------------------------------------
+
+def _dequantized(b, ax):
+    return ref.dequantize(*ref.quantize(np.ascontiguousarray(b), 32, ref.FP8_E5M2, 1, k_axis=ax), 32, ref.FP8_E5M2, 1)
+
+
+@pytest.mark.parametrize("n", [2, 3, 5, 8, 64])
+def test_split_keys_closed_forms(n):
+    """Q = 0 makes every range's maximum 0 and every probability 1 (cast to 0.9375), so whatever the number of ranges
+    the combination must give 0.9375 * mean of V_hat over the visible keys: checks the ranges' weights l_c and that
+    ranges past the causal limit (and, for n = 64 > 8 tiles, empty ones) contribute nothing. And one dominant key:
+    only the range that holds it survives the combination."""
+    Sk, Sq, D = 256, 5, 32
+    v = synth.activations(Sk, D, seed=3)[None]
+    k = synth.activations(Sk, D, seed=4)[None]
+    q = np.zeros((1, Sq, D), np.uint16)
+    out = attention_ref.fused_attention(q, k, v, 0.125, True, key_splits=n)
+    vh = _dequantized(v[0], 0).T
+    want = 0.9375 * np.stack([vh[:Sk - Sq + i + 1].mean(axis=0) for i in range(Sq)])
+    assert np.allclose(out[0], want.astype(np.float32), rtol=1e-6, atol=1e-30)
+    # dominant key 77 (range depends on n): q = k[77] direction, scaled up
+    kk = np.zeros((Sk, D), np.float32)
+    kk[:, 0] = 1.0
+    kk[77, 0] = 6.0
+    qq = np.zeros((1, D), np.float32)
+    qq[0, 0] = 4.0
+    out = attention_ref.fused_attention(bits(qq)[None], bits(kk)[None], v, 4.0, False, key_splits=n)
+    assert np.allclose(out[0, 0], 0.9375 * vh[77], rtol=1e-6, atol=1e-20)
+
+
+@pytest.mark.parametrize("n,causal", [(2, False), (4, False), (3, True), (4, True)])
+def test_split_keys_are_a_weighted_mean_of_the_ranges_own_attention(n, causal):
+    """Each range's (l_c, m_c) is the exact softmax denominator of its keys, sum_j exp(s_j) = l_c exp(m_c), because l
+    sums the un-quantized probabilities. So the split result must equal the single-range oracle (key_splits = 1) run on
+    each key range alone, combined with weights W_c = sum over the range's visible keys of exp(s_j) computed here in
+    float64 from the dequantized operands: pins the combination rule without using its code."""
+    Sk, Sq, D = 256, 6, 64
+    tiles_per_range = -(-(Sk // 32) // n)
+    q = synth.activations(Sq, D, seed=21)[None]
+    k = synth.activations(Sk, D, seed=22)[None]
+    v = synth.activations(Sk, D, seed=23)[None]
+    sc = D ** -0.5
+    out = attention_ref.fused_attention(q, k, v, sc, causal, key_splits=n)[0].astype(np.float64)
+    s = (_dequantized(q[0], -1) @ _dequantized(k[0], -1).T) * np.float64(np.float32(sc))
+    num, den = np.zeros((Sq, D)), np.zeros(Sq)
+    shift = s.max(axis=1)
+    for r0 in range(0, Sk, tiles_per_range * 32):
+        r1 = min(r0 + tiles_per_range * 32, Sk)
+        for i in range(Sq):
+            last = i + Sk - Sq if causal else Sk - 1
+            hi = min(r1, last + 1)
+            if hi <= r0:
+                continue
+            # this query against this range alone: non-causal call on the visible keys, padded to a whole tile with
+            # keys the query cannot see in the causal call (the V group of the last tile must be the same group)
+            if hi % 32 == 0 or not causal:
+                part = attention_ref.fused_attention(q[:, i:i + 1], k[:, r0:hi], v[:, r0:hi], sc, False)[0, 0]
+            else:
+                top = -(-hi // 32) * 32
+                # causal call whose single query sits at position hi - 1 of the range: Sq' = 1 aligned to the end of
+                # top - r0 keys would see all of them, so align by passing top - hi extra queries in front
+                qq = np.concatenate([q[:, i:i + 1]] + [q[:, i:i + 1]] * (top - hi), axis=1)
+                part = attention_ref.fused_attention(qq, k[:, r0:top], v[:, r0:top], sc, True)[0, 0]
+            w = np.exp(s[i, r0:hi] - shift[i]).sum()
+            num[i] += w * part.astype(np.float64)
+            den[i] += w
+    assert np.allclose(out, num / den[:, None], rtol=2e-6, atol=1e-12)
+
+
+def test_split_keys_stay_close_to_exact_attention_and_differ_from_one_range():
+    S, Sq, D = 512, 4, 64
+    q = synth.activations(Sq, D, seed=31)[None]
+    k = synth.activations(S, D, seed=32)[None]
+    v = synth.activations(S, D, seed=33)[None]
+    one = attention_ref.fused_attention(q, k, v, D ** -0.5, True, key_splits=1)[0].astype(np.float64)
+    four = attention_ref.fused_attention(q, k, v, D ** -0.5, True, key_splits=4)[0].astype(np.float64)
+    s = (_dequantized(q[0], -1) @ _dequantized(k[0], -1).T) * np.float64(np.float32(D ** -0.5))
+    s = np.where(np.arange(S)[None, :] <= np.arange(Sq)[:, None] + S - Sq, s, -np.inf)
+    p = np.exp(s - s.max(axis=1, keepdims=True))
+    exact = (p / p.sum(axis=1, keepdims=True)) @ _dequantized(v[0], 0).T
+    for got in (one, four):
+        assert 1e-4 < np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.12
+    assert not np.array_equal(one, four)   # the ranges' probabilities are cast against their own maxima
