@@ -272,6 +272,31 @@ int amxfp4_attention_merged(const amx_format_t* fmt, int64_t q_heads, int64_t kv
                             int32_t causal, void* out_bf16, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The fused attention for FEW queries against many keys (decoding one or a handful of new tokens against a key / value
+ * cache; Sec. 5.1 quantizes both attention products, Sec. 5.2 discusses long context). K and V are read as packed codes
+ * and dequantized in registers (no expansion, no panels), the query heads sharing a key / value head are the columns
+ * of one wave, and the keys are the parallelism: the Sk / 32 key tiles are cut into key_splits contiguous ranges of
+ * ceil((Sk / 32) / key_splits) tiles (the last ones may be shorter or empty); the recurrence of amxfp4_attention runs
+ * over each range on its own, from m = -inf, l = 0, O = 0, giving (m_c, l_c, O_c), and
+ *     m* = max_c m_c;   out[i, :] = sum_c O_c exp(m_c - m*) / sum_c l_c exp(m_c - m*)
+ * (ranges in which the query sees no key left out). The probabilities of a range are cast against that range's own
+ * running maximum, so the result depends on key_splits; key_splits = 1 is amxfp4_attention's definition.
+ *   limits     (q_heads / kv_heads) * Sq <= 32 (AMX_ERR_UNSUPPORTED beyond: use amxfp4_attention); group_size 32;
+ *              head_dim 128 or 64; 1 <= key_splits <= min(1024, Sk / 32); kv_heads <= 65535. A batch of sequences of
+ *              equal length is a larger number of heads.
+ *   workspace  at least amxfp4_attention_decode_workspace_bytes() bytes, 256-byte aligned (the ranges' partial results:
+ *              kv_heads * key_splits * 32 * (head_dim + 2) floats).
+ * Other arguments, layouts and status codes as amxfp4_attention; out is FP32 [q_heads][Sq][head_dim].
+ */
+size_t amxfp4_attention_decode_workspace_bytes(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq,
+                                               int64_t Sk, int64_t head_dim, int64_t key_splits);
+int amxfp4_attention_decode(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq, int64_t Sk,
+                            int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
+                            const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
+                            int32_t causal, int64_t key_splits, float* out, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/*
  * Measurement aid (not part of the method): arms a pair of caller-owned hipEvent_t (passed as void*) for the NEXT
  * amxfp4_gemm / mxfp4_gemm call made on this host thread. That call records `start` on its stream immediately before
  * and `stop` immediately after the launch of its matrix-multiply kernel (the MFMA main loop, excluding the operand

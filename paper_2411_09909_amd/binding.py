@@ -93,6 +93,11 @@ def load():
     L.amxfp4_attention.restype = ctypes.c_int
     L.amxfp4_attention_merged.argtypes = L.amxfp4_attention.argtypes
     L.amxfp4_attention_merged.restype = ctypes.c_int
+    L.amxfp4_attention_decode_workspace_bytes.argtypes = [fp, i64, i64, i64, i64, i64, i64]
+    L.amxfp4_attention_decode_workspace_bytes.restype = ctypes.c_size_t
+    L.amxfp4_attention_decode.argtypes = [fp, i64, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, f32, i32, i64, vp, vp,
+                                          ctypes.c_size_t, vp]
+    L.amxfp4_attention_decode.restype = ctypes.c_int
     L.amxfp4_peak_mfma.argtypes = [i32, vp, i32, vp, ctypes.POINTER(f64), vp]
     L.amxfp4_peak_mfma.restype = ctypes.c_int
     L.amxfp4_peak_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
@@ -357,6 +362,29 @@ def gemm_static(fmt, a_codes, a_scales, b_codes, b_scales, out):
     _check(load().amxfp4_gemm_static(ctypes.byref(fmt), M, N, K, a_codes.data_ptr(), a_scales.data_ptr(),
                                      b_codes.data_ptr(), b_scales.data_ptr(), out.data_ptr(), out.stride(-2), batch,
                                      _stream()))
+    return out
+
+
+def attention_decode(fmt, q_codes, q_scales, k_codes, k_scales, v_codes, v_scales, scale, causal=True, key_splits=1,
+                     out=None, workspace=None):
+    """amxfp4_attention_decode: few queries ((Hq / Hkv) * Sq <= 32) against many keys, the keys cut into `key_splits`
+    ranges. Shapes as attention(); returns FP32 [Hq, Sq, D]."""
+    _need_cuda(q_codes, q_scales, k_codes, k_scales, v_codes, v_scales)
+    Hq, Sq, D = q_codes.shape[0], q_codes.shape[1], q_codes.shape[2] * 2
+    Hkv, Sk = k_codes.shape[0], k_codes.shape[1]
+    assert k_codes.shape[2] * 2 == D and tuple(v_codes.shape) == (Hkv, D, Sk // 2)
+    for t in (q_codes, q_scales, k_codes, k_scales, v_codes, v_scales):
+        assert t.is_contiguous()
+    if out is None:
+        out = torch.empty((Hq, Sq, D), dtype=torch.float32, device=q_codes.device)
+    need = int(load().amxfp4_attention_decode_workspace_bytes(ctypes.byref(fmt), Hq, Hkv, Sq, Sk, D, key_splits))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q_codes.device)
+    _check(load().amxfp4_attention_decode(ctypes.byref(fmt), Hq, Hkv, Sq, Sk, D, q_codes.data_ptr(), q_scales.data_ptr(),
+                                          k_codes.data_ptr(), k_scales.data_ptr(), v_codes.data_ptr(),
+                                          v_scales.data_ptr(), float(scale), 1 if causal else 0, int(key_splits),
+                                          out.data_ptr(), workspace.data_ptr(),
+                                          workspace.numel() * workspace.element_size(), _stream()))
     return out
 
 

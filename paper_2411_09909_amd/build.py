@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libamxfp4.so")
-SOURCES = ["api.hip", "cast.hip", "gemm_bf16.hip", "gemm_fp4.hip", "gemm_e5m2.hip", "gemm_fp8m.hip", "gemm_fp6m.hip", "layer_ops.hip", "peaks.hip", "attention.hip", "gemm_skinny.hip"]
+SOURCES = ["api.hip", "cast.hip", "gemm_bf16.hip", "gemm_fp4.hip", "gemm_e5m2.hip", "gemm_fp8m.hip", "gemm_fp6m.hip", "layer_ops.hip", "peaks.hip", "attention.hip", "attention_decode.hip", "gemm_skinny.hip"]
 # packed FP32 VALU ops are switched off on purpose (they have given wrong results on these machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -610,6 +610,49 @@ static int attention_impl(const amx_format_t* fmt, int64_t q_heads, int64_t kv_h
   return e == hipSuccess ? AMX_OK : hip_fail(e, "attention launch");
 }
 
+size_t amxfp4_attention_decode_workspace_bytes(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq,
+                                               int64_t Sk, int64_t head_dim, int64_t key_splits) {
+  if (!fmt || Sk <= 0 || key_splits <= 0 || !amx::attention_decode_supported(q_heads, kv_heads, Sq, head_dim)) return 0;
+  return amx::attention_decode_workspace_bytes(kv_heads, head_dim, key_splits);
+}
+
+int amxfp4_attention_decode(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq, int64_t Sk,
+                            int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
+                            const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,
+                            int32_t causal, int64_t key_splits, float* out, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  if (int rc = check_format(fmt)) return rc;
+  if (fmt->group_size != 32) return fail(AMX_ERR_UNSUPPORTED, "the fused attention takes groups of 32 (one group per key tile)");
+  if (head_dim != 128 && head_dim != 64)
+    return fail(AMX_ERR_UNSUPPORTED, "the fused attention is built for head_dim 128 and 64 (got %lld)", (long long)head_dim);
+  if (q_heads <= 0 || kv_heads <= 0 || q_heads % kv_heads != 0 || kv_heads > 65535)
+    return fail(AMX_ERR_INVALID_ARG, "q_heads must be a positive multiple of kv_heads (kv_heads at most 65535)");
+  if (Sq <= 0 || Sk <= 0 || Sk % 32 != 0 || Sk > (1 << 20))
+    return fail(AMX_ERR_INVALID_ARG, "Sq and Sk must be positive, Sk a multiple of 32 and at most 2^20");
+  if ((q_heads / kv_heads) * Sq > 32)
+    return fail(AMX_ERR_UNSUPPORTED, "attention_decode takes at most 32 queries per key/value head ((q_heads / kv_heads) * Sq = "
+                "%lld); use amxfp4_attention", (long long)((q_heads / kv_heads) * Sq));
+  if (key_splits <= 0 || key_splits > 1024 || key_splits > Sk / 32)
+    return fail(AMX_ERR_INVALID_ARG, "key_splits must be between 1 and min(1024, Sk / 32)");
+  if (causal != 0 && causal != 1) return fail(AMX_ERR_INVALID_ARG, "causal must be 0 or 1");
+  if (causal && Sk < Sq) return fail(AMX_ERR_INVALID_ARG, "causal attention needs Sk >= Sq (queries are aligned to the end of the keys)");
+  if (!(scale > 0.0f) || !(scale < 1.0e30f)) return fail(AMX_ERR_INVALID_ARG, "scale must be a positive finite number");
+  if (!Q_codes || !Q_scales || !K_codes || !K_scales || !V_codes || !V_scales || !out)
+    return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
+  if (!aligned(Q_codes, 16) || !aligned(K_codes, 16) || !aligned(V_codes, 16) || !aligned(Q_scales, 2) ||
+      !aligned(K_scales, 2) || !aligned(V_scales, 2) || !aligned(out, 16))
+    return fail(AMX_ERR_INVALID_ARG, "codes and out need 16-byte, scales 2-byte alignment");
+  const size_t need = amx::attention_decode_workspace_bytes(kv_heads, head_dim, key_splits);
+  if (!workspace || workspace_bytes < need)
+    return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
+  if (!aligned(workspace, 256)) return fail(AMX_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  hipError_t e = amx::launch_attention_decode(fmt->scale, fmt->asymmetric != 0, q_heads, kv_heads, Sq, Sk, head_dim, Q_codes,
+                                              Q_scales, K_codes, K_scales, V_codes, V_scales, scale, causal,
+                                              (int)key_splits, out, workspace, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AMX_OK : hip_fail(e, "attention_decode launch");
+}
+
 int amxfp4_attention(const amx_format_t* fmt, int64_t q_heads, int64_t kv_heads, int64_t Sq, int64_t Sk,
                      int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales, const uint8_t* K_codes,
                      const uint8_t* K_scales, const uint8_t* V_codes, const uint8_t* V_scales, float scale,

@@ -14,6 +14,7 @@
 // (expand_kernel<PERMUTE>). Workgroup = 8 waves x 32 queries; the K and V fragments of a key tile are brought into
 // LDS once per workgroup by direct-to-LDS loads, double buffered.
 #include "../../include/amxfp4.h"
+#include "attention_tile.h"
 #include "cast_math.h"
 #include "gemm_common.h"
 
@@ -21,7 +22,6 @@ namespace amx {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kAttnWaves = 8;               // waves per workgroup, 32 queries each
 constexpr int kAttnQ = 32 * kAttnWaves;     // queries per workgroup
@@ -128,57 +128,8 @@ __global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
       const bf16x8 a = *reinterpret_cast<const bf16x8*>((CK) + kb * kFragBytes + lane_off);                        \
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kb], s, 0, 0, 0);                                          \
     }                                                                                                              \
-    float x[16];                                                                                                   \
-    const int key0 = (T) * 32 + row_in_tile;                                                                       \
     const bool diagonal = causal && (T) * 32 + 31 > qw + off; /* some key of the tile is masked for some query */ \
-    float mx = -__builtin_inff();                                                                                  \
-    _Pragma("unroll") for (int v = 0; v < 16; ++v) x[v] = s[v] * scale_log2;                                       \
-    if (diagonal) { /* uniform over the wave: most tiles skip the masking altogether */                           \
-      _Pragma("unroll") for (int v = 0; v < 16; ++v)                                                               \
-        if (key0 + 8 * (v >> 2) + (v & 3) > limit) x[v] = -__builtin_inff();                                       \
-    }                                                                                                              \
-    _Pragma("unroll") for (int v = 0; v < 16; ++v) mx = fmaxf(mx, x[v]);                                           \
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                                                        \
-    /* The subtraction below is exact 0 for the score that holds the maximum, so its probability is exactly 1, as \
-       in exact arithmetic (folding the scale into an FMA here would make it 1 - 2^-24 now and then, and a floored \
-       power-of-two scale of the tile would halve). */                                                            \
-    const float m_new = fmaxf(m, mx);                                                                              \
-    const float alpha = __builtin_amdgcn_exp2f(m - m_new);                                                         \
-    /* exp is monotonic: the largest probability of the tile is the one of the largest score */                   \
-    const float pmax = __builtin_amdgcn_exp2f(mx - m_new);                                                         \
-    float psum = 0.f;                                                                                              \
-    _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                                               \
-      x[v] = __builtin_amdgcn_exp2f(x[v] - m_new);                                                                 \
-      psum += x[v];                                                                                                \
-    }                                                                                                              \
-    psum += __shfl_xor(psum, 32, 64);                                                                              \
-    l = l * alpha + psum;                                                                                          \
-    m = m_new;                                                                                                     \
-    /* cast the 32 probabilities of each query as one group and take the dequantized values as BF16. The quotient \
-       p / S is taken as p * (1 / S): its error of an ulp or two is that of the hardware exp2 which produced p. */  \
-    float S, R;                                                                                                    \
-    if constexpr (SCALE_KIND == kScaleE5M2 || SCALE_KIND == kScaleE4M3) {                                          \
-      fp8_scale_inexact<SCALE_KIND>(pmax, S, R); /* pmax <= 1: no saturation */                                   \
-    } else {                                                                                                       \
-      (void)encode_scale_sr<SCALE_KIND>(pmax, S, R);                                                               \
-    }                                                                                                              \
-    uint32_t pb[8];                                                                                                \
-    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
-      if constexpr (SCALE_KIND == kScaleE5M2 || SCALE_KIND == kScaleE4M3) {                                        \
-        /* the conversion replaces byte 0 of its first operand, the only byte read below: any register will do,  \
-           and one that dies here saves the move of a zero */                                                      \
-        const float z0 = x[2 * i] * R, z1 = x[2 * i + 1] * R;                                                      \
-        const uint32_t code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(f2u(z0), z0, z1, 1.0f, 0);                  \
-        const f32x2 e = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(code, 1.0f, 0);                                   \
-        /* element * scale has at most 6 significant bits: the truncation to BF16 is exact */                     \
-        pb[i] = __builtin_amdgcn_perm(f2u(e[1] * S), f2u(e[0] * S), 0x07060302u);                                  \
-      } else {                                                                                                     \
-        /* a power-of-two scale is applied by the conversions themselves (they read the exponent field of S: the  \
-           first divides by it, the second multiplies) */                                                          \
-        const uint32_t code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(f2u(x[2 * i]), x[2 * i], x[2 * i + 1], S, 0); \
-        pb[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(code, S, 0));               \
-      }                                                                                                            \
-    }                                                                                                              \
+    AMX_ATTENTION_TILE_PROBS(false, s, scale_log2, diagonal, (T) * 32 + row_in_tile, limit, m, l, pb, alpha)       \
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) { /* the maximum moved for some query: rescale */        \
       _Pragma("unroll") for (int db = 0; db < kAttnD / 32; ++db)                                                   \
         _Pragma("unroll") for (int v = 0; v < 16; ++v) o[db][v] *= alpha;                                          \

@@ -78,6 +78,16 @@ hipError_t launch_attention_fused(int scale_kind, bool asym, int64_t Hq, int64_t
                                   const uint8_t* V_scales, float scale, int causal, float* out, bool merged_bf16,
                                   void* workspace, hipStream_t s, const KernelTimer& timer);
 
+// attention_decode.hip: the same attention for few queries ((Hq / Hkv) * Sq <= 32) against many keys, K and V read as
+// packed codes, the key tiles cut into key_splits ranges (workspace: the ranges' partial results)
+bool attention_decode_supported(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t head_dim);
+size_t attention_decode_workspace_bytes(int64_t Hkv, int64_t head_dim, int64_t key_splits);
+hipError_t launch_attention_decode(int scale_kind, bool asym, int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk,
+                                   int64_t head_dim, const uint8_t* Q_codes, const uint8_t* Q_scales,
+                                   const uint8_t* K_codes, const uint8_t* K_scales, const uint8_t* V_codes,
+                                   const uint8_t* V_scales, float scale, int causal, int key_splits, float* out,
+                                   void* workspace, hipStream_t s);
+
 // layer_ops.hip: RMS normalisation (after an optional residual addition y, whose BF16 sum goes to sum_out) with the
 // cast of the normalised row fused in; groups of 16, 32 or 64 dividing dim <= 16384
 bool rmsnorm_quantize_supported(int64_t group_size, int64_t dim);

@@ -258,7 +258,7 @@ def test_attention_rejects_bad_arguments(lib):
     assert call(ok, 4, 3, 64, 64, 128) == -1            # query heads not a multiple of key/value heads
     assert call(ok, 4, 2, 64, 48, 128) == -1            # Sk % 32
     assert call(ok, 4, 2, 64, 32, 128) == -1            # causal with fewer keys than queries
-    assert call(ok, 4, 2, 64, 64, 64) == -2             # head size
+    assert call(ok, 4, 2, 64, 64, 32) == -2             # head size (128 and 64 are built)
     assert call(binding.make_format(binding.FP8_E5M2, True, 16), 4, 2, 64, 64, 128) == -2   # group size
     assert call(ok, 4, 2, 64, 64, 128, scale=0.0) == -1
     assert call(ok, 4, 2, 64, 64, 128, causal=2) == -1
@@ -266,4 +266,4 @@ def test_attention_rejects_bad_arguments(lib):
     assert call(ok, 4, 2, 64, 64, 128, ws_bytes=16) == -3
     need = lib.amxfp4_attention_workspace_bytes(ctypes.byref(ok), 4, 2, 50, 96, 128)
     assert need == (4 * 64 + 2 * 96 + 2 * 128) * 128 * 2   # Q rows padded to 32, V keys padded to 64
-    assert lib.amxfp4_attention_workspace_bytes(ctypes.byref(ok), 4, 2, 50, 96, 64) == 0
+    assert lib.amxfp4_attention_workspace_bytes(ctypes.byref(ok), 4, 2, 50, 96, 32) == 0
