@@ -2,8 +2,8 @@
 // key / value cache). Same per-tile arithmetic as attention.hip (Sec. 5.1 quantizes Q.K^T and the attention map times V;
 // online softmax over key tiles of 32, each tile of probabilities cast as one group per query), but organised for the
 // shape: the work is reading K and V once, so
-//   - K and V are read as they are stored, packed codes and scale bytes, and dequantized in registers to exact BF16
-//     (no BF16 panels in a workspace: a quarter of the bytes, and no expansion pass in front);
+//   - K and V are read as they are stored, packed codes and scale bytes, and dequantized in registers to exact 16-bit
+//     floats (no BF16 panels in a workspace: a quarter of the bytes, and no expansion pass in front);
 //   - the query heads that share a key / value head, and their few queries, are the 32 columns of ONE wave
 //     (q_heads / kv_heads * Sq <= 32), so every K and V byte is read by one wave only;
 //   - the keys are the parallelism: the key tiles are cut into `key_splits` contiguous ranges, one wave per (key / value
@@ -31,14 +31,41 @@ namespace amx {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-// Eight codes (one word) of one group -> eight BF16, for any scale format: FP32 decode, times the scale of the
-// element's sign class as a float, truncated to BF16 (exact: at most 6 significant bits).
+// The 16-bit type the operands are dequantized to. FP8-E5M2 scales: FP16 with a bias of 2^-3 (every element * scale / 8
+// lies in [2^-20, 43008] with at most 5 significant bits: an FP16 number, subnormals included; the scale byte is the
+// upper byte of an FP16, so the dequantization is a conversion and one packed multiply); everything else: BF16.
+template <int SCALE_KIND>
+constexpr bool kDecodeF16 = SCALE_KIND == kScaleE5M2;
+
+template <int SCALE_KIND>
+__device__ __forceinline__ f32x16 decode_mfma(u32x4 a, u32x4 b, f32x16 acc) {
+  if constexpr (kDecodeF16<SCALE_KIND>)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+
+// Eight codes (one word) of one group -> eight exact 16-bit floats (element * scale has at most 6 significant bits).
+// FP8-E5M2 scales: FP16, biased (above). Power-of-two scales: the FP4 -> BF16 conversion applies the scale itself (it
+// reads the exponent field of a float). FP8-E4M3 scales: FP32 decode, times the scale of the element's sign class as a
+// float, truncated to BF16.
 template <int SCALE_KIND, bool ASYM>
-__device__ __forceinline__ bf16x8 decode_word(uint32_t word, uint32_t byte_pos, uint32_t byte_neg) {
-  const uint32_t sp = f2u(scale_value<SCALE_KIND>(byte_pos)), sn = ASYM ? f2u(scale_value<SCALE_KIND>(byte_neg)) : sp;
-  const u32x4 r = {dequant2_f32<ASYM, 0>(word, sp, sn), dequant2_f32<ASYM, 1>(word, sp, sn),
-                   dequant2_f32<ASYM, 2>(word, sp, sn), dequant2_f32<ASYM, 3>(word, sp, sn)};
-  return __builtin_bit_cast(bf16x8, r);
+__device__ __forceinline__ u32x4 decode_word(uint32_t word, uint32_t byte_pos, uint32_t byte_neg) {
+  u32x4 r;
+  if constexpr (kDecodeF16<SCALE_KIND>) {
+    const uint32_t sp = ((byte_pos << 8) | (byte_pos << 24)) & 0x7F007F00u, sn = ((byte_neg << 8) | (byte_neg << 24)) & 0x7F007F00u;
+    r = u32x4{dequant2_f16<ASYM, 0>(word, sp, sn), dequant2_f16<ASYM, 1>(word, sp, sn),
+              dequant2_f16<ASYM, 2>(word, sp, sn), dequant2_f16<ASYM, 3>(word, sp, sn)};
+  } else if constexpr (SCALE_KIND == kScaleE8M0Floor || SCALE_KIND == kScaleE8M0Round) {
+    const uint32_t sp = byte_pos << 23, sn = byte_neg << 23;
+    r = u32x4{dequant2_pot<ASYM, 0>(word, sp, sn), dequant2_pot<ASYM, 1>(word, sp, sn),
+              dequant2_pot<ASYM, 2>(word, sp, sn), dequant2_pot<ASYM, 3>(word, sp, sn)};
+  } else {
+    const uint32_t sp = f2u(scale_value<SCALE_KIND>(byte_pos)), sn = ASYM ? f2u(scale_value<SCALE_KIND>(byte_neg)) : sp;
+    r = u32x4{dequant2_f32<ASYM, 0>(word, sp, sn), dequant2_f32<ASYM, 1>(word, sp, sn),
+              dequant2_f32<ASYM, 2>(word, sp, sn), dequant2_f32<ASYM, 3>(word, sp, sn)};
+  }
+  return r;
 }
 
 // One row's share of a lane for the first product: the D / 4 bytes of codes of dimensions (D / 2) h .. and the scale
@@ -88,8 +115,9 @@ __device__ __forceinline__ void load_v_piece(const uint8_t* __restrict__ codes, 
 
 constexpr int kDecodeCols = 32;  // query columns of a wave
 
-// grid: (key_splits, kv_heads); block: one wave. part: [kv_heads][key_splits][32 columns][D + 2] floats: the
-// un-normalised O of the column, then its running maximum (log2 units) and its sum.
+// grid: (key_splits, kv_heads); block: one wave. part: [kv_heads][32 columns][key_splits][D + 2] floats: the
+// un-normalised O of the column in that range, then its running maximum (log2 units) and its sum; only the columns
+// that hold a query are written.
 template <int SCALE_KIND, bool ASYM, int D>
 __global__ __launch_bounds__(64) void attention_decode_kernel(
     const uint8_t* __restrict__ Qc, const uint8_t* __restrict__ Qs, const uint8_t* __restrict__ Kc,
@@ -105,7 +133,7 @@ __global__ __launch_bounds__(64) void attention_decode_kernel(
   const int limit = col_valid && causal ? qi + off : Sk - 1;
 
   // this column's query as the B operand of the first product, resident in registers
-  bf16x8 qf[kSteps];
+  u32x4 qf[kSteps];
   if (col_valid) {
     RowPiece<D> q;
     load_row_piece<D, ASYM>(Qc, Qs, ((int64_t)g * per + col / Sq) * Sq + qi, h, q);
@@ -113,8 +141,12 @@ __global__ __launch_bounds__(64) void attention_decode_kernel(
     for (int s = 0; s < kSteps; ++s) qf[s] = decode_word<SCALE_KIND, ASYM>(q.word[s], q.sp[s >> 2], q.sn[s >> 2]);
   } else {
 #pragma unroll
-    for (int s = 0; s < kSteps; ++s) qf[s] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+    for (int s = 0; s < kSteps; ++s) qf[s] = u32x4{0, 0, 0, 0};
   }
+  // FP16 operands carry 2^-3 each: the scores come out divided by 2^6, the second product (probabilities times 2^8, so
+  // that the smallest of them, 2^-17, is a normal FP16 number, times V / 8) multiplied by 2^5
+  constexpr bool kF16 = kDecodeF16<SCALE_KIND>;
+  const float score_scale = kF16 ? scale_log2 * 64.0f : scale_log2;
 
   f32x16 o[kRowBlocks];
 #pragma unroll
@@ -157,11 +189,18 @@ __global__ __launch_bounds__(64) void attention_decode_kernel(
     for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < kSteps; ++ks) {
-      const bf16x8 a = decode_word<SCALE_KIND, ASYM>(kp.word[ks], kp.sp[ks >> 2], kp.sn[ks >> 2]);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
+      const u32x4 a = decode_word<SCALE_KIND, ASYM>(kp.word[ks], kp.sp[ks >> 2], kp.sn[ks >> 2]);
+      s = decode_mfma<SCALE_KIND>(a, qf[ks], s);
     }
     const bool masked = causal && t * 32 + 31 > off;  // some key of the tile is masked for the first query (uniform)
-    AMX_ATTENTION_TILE_PROBS(true, s, scale_log2, masked, t * 32 + row_in_tile, limit, m, l, pb, alpha)
+    AMX_ATTENTION_TILE_PROBS(true, s, score_scale, masked, t * 32 + row_in_tile, limit, m, l, pb, alpha)
+    if constexpr (kF16) {  // BF16 pairs -> FP16 pairs of 2^8 p (exact: at most 6 significant bits, 2^-9 <= 2^8 p <= 2^8)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        pb[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(u2f(pb[i] << 16) * 256.0f,
+                                                                        u2f(pb[i] & 0xFFFF0000u) * 256.0f));
+      }
+    }
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // the maximum moved for some query: rescale
 #pragma unroll
       for (int db = 0; db < kRowBlocks; ++db)
@@ -170,12 +209,12 @@ __global__ __launch_bounds__(64) void attention_decode_kernel(
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const bf16x8 b = __builtin_bit_cast(bf16x8, u32x4{pb[4 * j], pb[4 * j + 1], pb[4 * j + 2], pb[4 * j + 3]});
+      const u32x4 b = {pb[4 * j], pb[4 * j + 1], pb[4 * j + 2], pb[4 * j + 3]};
 #pragma unroll
       for (int db = 0; db < kRowBlocks; ++db) {
         const uint32_t w0 = j ? vp[db].codes.z : vp[db].codes.x, w1 = j ? vp[db].codes.w : vp[db].codes.y;
-        const bf16x8 a = decode_word<SCALE_KIND, ASYM>(__builtin_amdgcn_perm(w1, w0, pick), vp[db].sp, vp[db].sn);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o[db], 0, 0, 0);
+        const u32x4 a = decode_word<SCALE_KIND, ASYM>(__builtin_amdgcn_perm(w1, w0, pick), vp[db].sp, vp[db].sn);
+        o[db] = decode_mfma<SCALE_KIND>(a, b, o[db]);
       }
     }
     kp = kn;
@@ -184,45 +223,56 @@ __global__ __launch_bounds__(64) void attention_decode_kernel(
   }
 
   // register 4c + r of row block db is d = 32 db + 8 c + 4 h + r of column col
-  float* dst = part + (((int64_t)g * nsplits + split) * kDecodeCols + col) * (D + 2);
+  if (!col_valid) return;
+  float* dst = part + (((int64_t)g * kDecodeCols + col) * nsplits + split) * (D + 2);
+  const float unbias = kF16 ? 0.03125f : 1.0f;  // 2^-5, exact
 #pragma unroll
   for (int db = 0; db < kRowBlocks; ++db)
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       float* d4 = dst + db * 32 + c * 8 + 4 * h;
-      d4[0] = o[db][4 * c], d4[1] = o[db][4 * c + 1], d4[2] = o[db][4 * c + 2], d4[3] = o[db][4 * c + 3];
+      d4[0] = o[db][4 * c] * unbias, d4[1] = o[db][4 * c + 1] * unbias, d4[2] = o[db][4 * c + 2] * unbias,
+      d4[3] = o[db][4 * c + 3] * unbias;
     }
   if (h == 0) dst[D] = m, dst[D + 1] = l;
 }
 
-// One thread per (kv head, valid column, 4 head dimensions): the exact combination of the ranges, in FP32.
+// One wave per (kv head, column that holds a query): the exact combination of the ranges, in FP32. The lanes first
+// share out the ranges (maximum, then every range's weight 2^(m_c - m*), 0 for a range in which the query saw no key,
+// and the weighted sum of the l_c), then the head dimensions (the ranges' rows are read whole lines at a time, eight
+// ranges in flight).
+constexpr int kDecodeMaxSplits = 1024;
 template <int D>
-__global__ __launch_bounds__(256) void attention_decode_combine_kernel(const float* __restrict__ part,
-                                                                       float* __restrict__ out, int kv_heads, int per,
-                                                                       int Sq, int nsplits) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int cols = per * Sq;
-  if (idx >= (int64_t)kv_heads * cols * (D / 4)) return;
-  const int d4 = (int)(idx % (D / 4));
-  const int col = (int)((idx / (D / 4)) % cols);
-  const int g = (int)(idx / ((int64_t)(D / 4) * cols));
-  const float* base = part + ((int64_t)g * nsplits * kDecodeCols + col) * (D + 2);
-  const int64_t stride = (int64_t)kDecodeCols * (D + 2);
+__global__ __launch_bounds__(64) void attention_decode_combine_kernel(const float* __restrict__ part,
+                                                                      float* __restrict__ out, int per, int Sq,
+                                                                      int nsplits) {
+  __shared__ float weight[kDecodeMaxSplits];
+  const int lane = threadIdx.x, col = (int)blockIdx.x, g = (int)blockIdx.y;
+  const float* base = part + ((int64_t)g * kDecodeCols + col) * nsplits * (D + 2);
   float mx = -__builtin_inff();
-  for (int c = 0; c < nsplits; ++c)
-    if (base[c * stride + D + 1] > 0.f) mx = fmaxf(mx, base[c * stride + D]);
-  float num[4] = {0.f, 0.f, 0.f, 0.f}, den = 0.f;
-  for (int c = 0; c < nsplits; ++c) {
-    const float lc = base[c * stride + D + 1];
-    if (!(lc > 0.f)) continue;  // a range in which this query saw no key
-    const float w = __builtin_amdgcn_exp2f(base[c * stride + D] - mx);
-    den += w * lc;
+  for (int c = lane; c < nsplits; c += 64)
+    if (base[(int64_t)c * (D + 2) + D + 1] > 0.f) mx = fmaxf(mx, base[(int64_t)c * (D + 2) + D]);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) num[e] += w * base[c * stride + 4 * d4 + e];
+  for (int d = 32; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+  float den = 0.f;
+  for (int c = lane; c < nsplits; c += 64) {
+    const float lc = base[(int64_t)c * (D + 2) + D + 1];
+    const float w = lc > 0.f ? __builtin_amdgcn_exp2f(base[(int64_t)c * (D + 2) + D] - mx) : 0.f;
+    weight[c] = w;
+    den += w * lc;
   }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) den += __shfl_xor(den, d, 64);
+  __syncthreads();
   const float inv = 1.0f / den;
-  float* dst = out + (((int64_t)g * per + col / Sq) * Sq + col % Sq) * D + 4 * d4;
-  *reinterpret_cast<float4*>(dst) = make_float4(num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv);
+  float* dst = out + (((int64_t)g * per + col / Sq) * Sq + col % Sq) * D;
+#pragma unroll
+  for (int d = lane; d < D; d += 64) {
+    float num = 0.f;
+#pragma unroll 8
+    for (int c = 0; c < nsplits; ++c) num += weight[c] * base[(int64_t)c * (D + 2) + d];
+    dst[d] = num * inv;
+  }
 }
 
 bool attention_decode_supported(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t head_dim) {
@@ -242,9 +292,8 @@ static hipError_t launch_decode(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk,
                      Kc, Ks, Vc, Vs, part, (int)Sq, (int)Sk, per, tiles_per_split, scale * 1.4426950408889634f, causal);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int64_t threads = Hkv * per * Sq * (D / 4);
-  hipLaunchKernelGGL((attention_decode_combine_kernel<D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, part,
-                     out, (int)Hkv, per, (int)Sq, splits);
+  hipLaunchKernelGGL((attention_decode_combine_kernel<D>), dim3((unsigned)(per * Sq), (unsigned)Hkv), dim3(64), 0, s, part,
+                     out, per, (int)Sq, splits);
   return hipGetLastError();
 }
 
