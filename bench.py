@@ -141,6 +141,31 @@ def measured_peaks(binding, torch, xd, wd, dev, iterations=30000):
     return res
 
 
+def other_workloads():
+    """The other benchmark configurations, a few steps each, so that their figures are measured in the same run as the
+    headline: the attention workload (32 heads x 4096, fused call and the materialised sequence), one new token
+    against 8192 cached keys (decode call), and the LLaMA-3-8B-shaped decoder layer at 8192 tokens in AMXFP4 against
+    the MXFP4 baselines (time, TFLOP/s over the flops its seven matmuls execute, MSE against a BF16 layer)."""
+    import torch
+    from paper_2411_09909_amd import attention_bench, decode_bench, layer_bench
+    res = {}
+    a = attention_bench.run(steps=5)
+    res["attention_32_heads_x_4096"] = {k: a[k] for k in ("format", "cast_qkv_ms", "fused_ms", "fused_TFLOPs_causal",
+                                                           "materialised_total_ms", "speedup_fused")}
+    torch.cuda.empty_cache()
+    d = decode_bench.run(steps=20, splits=(32, 64))
+    res["decode_1_token_x_8192_keys"] = {"format": d["format"], "cache_MB": d["cache_MB"], "decode_us": d["decode"],
+                                         "many_queries_kernel_us": d["many_queries_kernel_us"]}
+    torch.cuda.empty_cache()
+    lay = layer_bench.run(steps=5, formats=("amxfp4_e5m2", "mxfp4_e5m2", "amxfp4_e8m0", "mxfp4_e8m0"))
+    res["decoder_layer_8192_tokens"] = {
+        name: {"ms_per_layer": f["ms_per_layer"], "matmul_TFLOPs": f["matmul_TFLOPs"],
+               "mse_over_update": round(f["mse_over_update"], 5)} for name, f in lay["formats"].items()}
+    res["decoder_layer_8192_tokens"]["note"] = "fused attention; TFLOP/s over the 4.125 TFLOP the seven matmuls execute"
+    torch.cuda.empty_cache()
+    return res
+
+
 def cpu_baseline(x_bits, w_bits, K, sample_m=2048, sample_n=14336):
     """The oracle as it stands (oracle/amxfp4_ref.c: scalar C, FP64 accumulate, OpenMP over rows), timed on a slab of
     the same operands: quantize sample_m rows of X and sample_n rows of W, then the sample_m x sample_n x K GEMM."""
@@ -178,6 +203,8 @@ def main():
     ap.add_argument("--variants", action="store_true",
                     help="time every other format and kernel as well (the block-scaled formats are always listed)")
     ap.add_argument("--no-variants", action="store_true", help="only the headline format")
+    ap.add_argument("--no-workloads", action="store_true",
+                    help="skip the attention, decoding and decoder-layer workloads reported beside the headline")
     ap.add_argument("--no-cast-bandwidth", action="store_true",
                     help="skip the cast's bandwidth measurement over rotating buffers")
     ap.add_argument("--no-measured-peaks", action="store_true",
@@ -408,6 +435,8 @@ def main():
             "gemm_kernel_ms": round(v["kern_ms"], 4),
             "kernel_frac_of_mfma_peak": round(flops / (v["kern_ms"] * 1e-3) / 1e12 / v["peak"], 4),
             "kernel_traffic_bytes": MEASURED_TRAFFIC_VARIANTS.get(label) if args.workload == WORKLOAD else None}
+    if not (args.no_workloads or args.no_variants or args.workload != WORKLOAD):
+        out["workloads"] = other_workloads()
     if peaks is not None:
         out["measured_peaks"] = peaks
     if args.calib_copy:

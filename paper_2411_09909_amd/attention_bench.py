@@ -29,6 +29,13 @@ def timed(fn, steps):
     return (time.perf_counter() - t0) / steps * 1e3
 
 
+def run(heads=32, kv_heads=32, seq=4096, steps=10, fmt_name="amxfp4_e5m2", no_materialised=False):
+    """Returns the dictionary main() prints."""
+    import types
+    return _run(types.SimpleNamespace(heads=heads, kv_heads=kv_heads, seq=seq, steps=steps, format=fmt_name,
+                                      no_materialised=no_materialised))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--heads", type=int, default=32)
@@ -37,7 +44,10 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--format", default="amxfp4_e5m2", choices=sorted(FORMATS))
     ap.add_argument("--no-materialised", action="store_true", help="time the fused call only")
-    args = ap.parse_args()
+    print(json.dumps(_run(ap.parse_args())))
+
+
+def _run(args):
     H, G, S, D = args.heads, args.kv_heads, args.seq, 128
     per = H // G
     dev = torch.device("cuda:0")
@@ -124,7 +134,7 @@ def main():
         res["materialised_total_ms"] = round(sum(parts.values()), 4)
         res["materialised_rel_err_vs_exact"] = round(rel_err(o.view(H, S, D)), 5)
         res["speedup_fused"] = round(res["materialised_total_ms"] / res["fused_ms"], 2)
-    print(json.dumps(res))
+    return res
 
 
 if __name__ == "__main__":

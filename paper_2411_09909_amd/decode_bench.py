@@ -16,6 +16,15 @@ from . import binding, synth
 from .attention_bench import FORMATS, timed
 
 
+def run(batch=1, heads=32, kv_heads=8, keys=8192, queries=1, steps=50, fmt_name="amxfp4_e5m2", splits=None):
+    """Times the decode call for each number of key ranges in `splits` (default: a sweep) and the many-queries kernel
+    on the same operands; returns the dictionary main() prints."""
+    import types
+    args = types.SimpleNamespace(batch=batch, heads=heads, kv_heads=kv_heads, keys=keys, queries=queries, steps=steps,
+                                 format=fmt_name)
+    return _run(args, splits)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--batch", type=int, default=1, help="sequences (each with its own heads and cache)")
@@ -25,7 +34,10 @@ def main():
     ap.add_argument("--queries", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--format", default="amxfp4_e5m2", choices=sorted(FORMATS))
-    args = ap.parse_args()
+    print(json.dumps(_run(ap.parse_args(), None)))
+
+
+def _run(args, splits_wanted):
     H, G, Sk, Sq, D = args.batch * args.heads, args.batch * args.kv_heads, args.keys, args.queries, 128
     dev = torch.device("cuda:0")
     binding.load()
@@ -47,7 +59,7 @@ def main():
            "cache_MB": round(cache_bytes / 1e6, 2), "decode": {}}
     out = torch.empty((H, Sq, D), dtype=torch.float32, device=dev)
     tiles = Sk // 32
-    for splits in sorted({1, 4, 16, 32, 64, 128, 256} & set(range(1, tiles + 1))):
+    for splits in sorted(set(splits_wanted or (1, 4, 16, 32, 64, 128, 256)) & set(range(1, tiles + 1))):
         ws = torch.empty(max(256, G * splits * 32 * (D + 2) * 4), dtype=torch.uint8, device=dev)
         ms = timed(lambda: binding.attention_decode(fmt, *ops, scale, True, key_splits=splits, out=out, workspace=ws),
                    args.steps)
@@ -56,7 +68,7 @@ def main():
     ws = torch.empty(binding.attention_workspace_bytes(fmt, H, G, Sq, Sk, D), dtype=torch.uint8, device=dev)
     ms = timed(lambda: binding.attention(fmt, *ops, scale, True, out=out, workspace=ws), args.steps)
     res["many_queries_kernel_us"] = round(ms * 1e3, 1)
-    print(json.dumps(res))
+    return res
 
 
 if __name__ == "__main__":

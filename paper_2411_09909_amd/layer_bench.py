@@ -58,6 +58,45 @@ def bf16_reference(x, w, cfg, chunk_heads=4):
     return (x2.to(f32) + (act @ w["wd"].T).to(f32)).to(torch.bfloat16)
 
 
+def run(seq=8192, steps=5, formats=tuple(FORMATS), fused_attention=True, separate_norm=False):
+    """Times the layer in each format; returns the dictionary main() prints."""
+    cfg = layer.LayerConfig()
+    dev = torch.device("cuda:0")
+    binding.load()
+    w_host = synth.layer_weights(cfg, seed=0)
+    to_dev = lambda a: (torch.from_numpy(a).to(dev) if a.dtype == np.float32  # noqa: E731
+                        else torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16))
+    w = {k: to_dev(v) for k, v in w_host.items()}
+    x = to_dev(synth.layer_input(seq, cfg.d_model, seed=0))
+    ref_out = bf16_reference(x, w, cfg).to(torch.float32)
+    upd = (ref_out - x.to(torch.float32)).pow(2).mean().item()
+    out = {"workload": "c5_llama3_8b_decoder_layer", "seq": seq, "d_model": cfg.d_model, "heads": cfg.n_heads,
+           "kv_heads": cfg.n_kv_heads, "d_ff": cfg.d_ff, "data": "synthetic, random-init weights", "fused_attention": fused_attention,
+           "reference_update_mean_square": upd, "formats": {}}
+    for name in formats:
+        kind, asym = FORMATS[name]
+        lay = layer.DecoderLayer(cfg, w, binding.make_format(kind, asym), fused_attention=fused_attention,
+                                 fused_norm=False if separate_norm else None)
+        y = lay.forward(x)  # warm-up, also the output that is compared
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            lay.forward(x)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        mse = (y.to(torch.float32) - ref_out).pow(2).mean().item()
+        out["formats"][name] = {"ms_per_layer": round(dt * 1e3, 3),
+                                # flops the layer executes (the fused attention skips the masked key tiles) ...
+                                "matmul_TFLOPs": round(lay.matmul_flops(seq) / dt / 1e12, 1),
+                                # ... and with the attention products counted in full whatever runs
+                                "matmul_TFLOPs_dense_attention_credit": round(
+                                    lay.matmul_flops(seq, nominal=True) / dt / 1e12, 1),
+                                "mse_vs_bf16": mse, "mse_over_update": mse / upd}
+        del lay, y
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--seq", type=int, default=8192)
@@ -68,41 +107,7 @@ def main():
     ap.add_argument("--separate-norm", action="store_true",
                     help="residual addition, RMS normalisation and cast as three calls instead of one")
     args = ap.parse_args()
-    cfg = layer.LayerConfig()
-    dev = torch.device("cuda:0")
-    binding.load()
-    w_host = synth.layer_weights(cfg, seed=0)
-    to_dev = lambda a: (torch.from_numpy(a).to(dev) if a.dtype == np.float32  # noqa: E731
-                        else torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16))
-    w = {k: to_dev(v) for k, v in w_host.items()}
-    x = to_dev(synth.layer_input(args.seq, cfg.d_model, seed=0))
-    ref_out = bf16_reference(x, w, cfg).to(torch.float32)
-    upd = (ref_out - x.to(torch.float32)).pow(2).mean().item()
-    out = {"workload": "c5_llama3_8b_decoder_layer", "seq": args.seq, "d_model": cfg.d_model, "heads": cfg.n_heads,
-           "kv_heads": cfg.n_kv_heads, "d_ff": cfg.d_ff, "data": "synthetic, random-init weights", "fused_attention": args.fused_attention,
-           "reference_update_mean_square": upd, "formats": {}}
-    for name in args.formats.split(","):
-        kind, asym = FORMATS[name]
-        lay = layer.DecoderLayer(cfg, w, binding.make_format(kind, asym), fused_attention=args.fused_attention,
-                                 fused_norm=False if args.separate_norm else None)
-        y = lay.forward(x)  # warm-up, also the output that is compared
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            lay.forward(x)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / args.steps
-        mse = (y.to(torch.float32) - ref_out).pow(2).mean().item()
-        out["formats"][name] = {"ms_per_layer": round(dt * 1e3, 3),
-                                # flops the layer executes (the fused attention skips the masked key tiles) ...
-                                "matmul_TFLOPs": round(lay.matmul_flops(args.seq) / dt / 1e12, 1),
-                                # ... and with the attention products counted in full whatever runs
-                                "matmul_TFLOPs_dense_attention_credit": round(
-                                    lay.matmul_flops(args.seq, nominal=True) / dt / 1e12, 1),
-                                "mse_vs_bf16": mse, "mse_over_update": mse / upd}
-        del lay, y
-        torch.cuda.empty_cache()
-    print(json.dumps(out))
+    print(json.dumps(run(args.seq, args.steps, args.formats.split(","), args.fused_attention, args.separate_norm)))
 
 
 if __name__ == "__main__":
