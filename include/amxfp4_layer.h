@@ -93,6 +93,18 @@ int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int6
                          int64_t ld_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * amxfp4_gemm_silu_mul on prepared weights: `prepared` is what amxfp4_prepare_weights (include/amxfp4.h) wrote for the
+ * INTERLEAVED weight matrix B [2 * width][K]; the call then expands only A. Same result, bit for bit. For formats with
+ * nothing to prepare (amxfp4_weights_prepared_bytes() == 0) `prepared` is ignored and the call is amxfp4_gemm_silu_mul.
+ * workspace: at least amxfp4_gemm_silu_mul_prepared_workspace_bytes() bytes.
+ */
+size_t amxfp4_gemm_silu_mul_prepared_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K);
+int amxfp4_gemm_silu_mul_prepared(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K, const uint8_t* A_codes,
+                                  const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales,
+                                  const void* prepared, size_t prepared_bytes, void* out_bf16, int64_t ld_out,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * amxfp4_rmsnorm followed by amxfp4_quantize of its result (Appendix B Algorithm 1 / Sec. 4.2 Eq. 1, as amxfp4_quantize
  * along the row), in one pass: the normalised BF16 row is cast in registers and never written. Optionally with the
  * residual addition of amxfp4_residual_add in front: y != NULL adds the FP32 row y to x first, writes the BF16 sum to

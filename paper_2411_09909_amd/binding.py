@@ -57,6 +57,11 @@ def load():
     L.amxfp4_gemm_silu_mul_workspace_bytes.restype = ctypes.c_size_t
     L.amxfp4_gemm_silu_mul.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, i64, vp, ctypes.c_size_t, vp]
     L.amxfp4_gemm_silu_mul.restype = ctypes.c_int
+    L.amxfp4_gemm_silu_mul_prepared_workspace_bytes.argtypes = [fp, i64, i64, i64]
+    L.amxfp4_gemm_silu_mul_prepared_workspace_bytes.restype = ctypes.c_size_t
+    L.amxfp4_gemm_silu_mul_prepared.argtypes = [fp, i64, i64, i64, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, i64, vp,
+                                                ctypes.c_size_t, vp]
+    L.amxfp4_gemm_silu_mul_prepared.restype = ctypes.c_int
     L.amxfp4_quantize_batched.argtypes = [fp, vp, i64, i64, i64, i64, i64, i64, vp, vp, vp]
     L.amxfp4_quantize_batched.restype = ctypes.c_int
     L.amxfp4_profile_next_gemm.argtypes = [vp, vp]
@@ -275,14 +280,25 @@ def gemm_silu_mul_workspace_bytes(fmt, M, width, K):
     return int(load().amxfp4_gemm_silu_mul_workspace_bytes(ctypes.byref(fmt), M, width, K))
 
 
-def gemm_silu_mul(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None):
+def gemm_silu_mul(fmt, a_codes, a_scales, b_codes, b_scales, out=None, workspace=None, prepared=None):
     """bf16(silu(g) * u) of the fused gate / up projection (g | u) = A . B^T, B's rows interleaved as by
-    interleave_gate_up() before they were cast. Returns [M, width] BF16."""
+    interleave_gate_up() before they were cast. prepared: prepare_weights() of those interleaved weights
+    (amxfp4_gemm_silu_mul_prepared). Returns [M, width] BF16."""
     _need_cuda(a_codes, a_scales, b_codes, b_scales)
     M, K = a_codes.shape[0], a_codes.shape[1] * 2
     width = b_codes.shape[0] // 2
     if out is None:
         out = torch.empty((M, width), dtype=torch.bfloat16, device=a_codes.device)
+    if prepared is not None:
+        need = int(load().amxfp4_gemm_silu_mul_prepared_workspace_bytes(ctypes.byref(fmt), M, width, K))
+        if need and (workspace is None or workspace.numel() < need):
+            workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)
+        n_prep = prepared.numel() * prepared.element_size()
+        _check(load().amxfp4_gemm_silu_mul_prepared(
+            ctypes.byref(fmt), M, width, K, a_codes.data_ptr(), a_scales.data_ptr(), b_codes.data_ptr(),
+            b_scales.data_ptr(), prepared.data_ptr() if n_prep else None, n_prep, out.data_ptr(), out.stride(0),
+            workspace.data_ptr() if need else None, workspace.numel() if need else 0, _stream()))
+        return out
     need = gemm_silu_mul_workspace_bytes(fmt, M, width, K)
     if need and (workspace is None or workspace.numel() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)

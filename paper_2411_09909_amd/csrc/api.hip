@@ -371,9 +371,10 @@ int amxfp4_rmsnorm_quantize(const amx_format_t* fmt, const void* x_bf16, const f
   return e == hipSuccess ? AMX_OK : hip_fail(e, "rmsnorm_quantize launch");
 }
 
-int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K, const uint8_t* A_codes,
-                         const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, void* out_bf16,
-                         int64_t ld_out, void* workspace, size_t workspace_bytes, void* stream) {
+// B_panel: the prepared form of the interleaved weights (amxfp4_prepare_weights on [2 * width][K]), or null
+static int glu_impl(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K, const uint8_t* A_codes,
+                    const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, const void* B_panel,
+                    void* out_bf16, int64_t ld_out, void* workspace, size_t workspace_bytes, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
   amx_format_t f = *fmt;
   if (int rc = check_format(&f)) return rc;
@@ -386,7 +387,9 @@ int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int6
   if (!aligned(A_codes, 16) || !aligned(B_codes, 16) || !aligned(A_scales, 4) || !aligned(B_scales, 4) ||
       !aligned(out_bf16, 2))
     return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales 4-byte, out 2-byte alignment");
-  const size_t need = glu_workspace_bytes(f, M, 2 * width, K);
+  const GemmKernel glu_kernel = plan_glu(f, M, 2 * width, K).kernel;
+  if (glu_kernel != kGemmPanel) B_panel = nullptr;  // only the BF16-panel kernel reads an expanded B
+  const size_t need = B_panel ? amx::bf16_panel_bytes(M, K) : glu_workspace_bytes(f, M, 2 * width, K);
   if (need > 0) {
     if (!workspace || workspace_bytes < need)
       return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
@@ -396,7 +399,6 @@ int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int6
   g_timer = amx::KernelTimer();
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
   float* out = reinterpret_cast<float*>(out_bf16);
-  const GemmKernel glu_kernel = plan_glu(f, M, 2 * width, K).kernel;
   if (glu_kernel == kGemmFp8Merged) {
     hipError_t e = amx::launch_gemm_fp8m_path(M, 2 * width, K, A_codes, A_scales, B_codes, B_scales, out, ld_out, 1,
                                               workspace, hs, timer, true);
@@ -415,8 +417,36 @@ int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int6
   hipError_t e = amx::launch_gemm_bf16_path(f.scale, f.asymmetric != 0, f.group_size, M, 2 * width, K, A_codes, A_scales,
                                             B_codes, B_scales, nullptr, nullptr, reinterpret_cast<float*>(out_bf16),
                                             ld_out, 1, workspace, AMX_TILE_AUTO, reinterpret_cast<hipStream_t>(stream), timer,
-                                            true);
+                                            true, B_panel);
   return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
+}
+
+int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K, const uint8_t* A_codes,
+                         const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales, void* out_bf16,
+                         int64_t ld_out, void* workspace, size_t workspace_bytes, void* stream) {
+  return glu_impl(fmt, M, width, K, A_codes, A_scales, B_codes, B_scales, nullptr, out_bf16, ld_out, workspace,
+                  workspace_bytes, stream);
+}
+
+size_t amxfp4_gemm_silu_mul_prepared_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K) {
+  const size_t plain = amxfp4_gemm_silu_mul_workspace_bytes(fmt, M, width, K);
+  if (plain == 0 || amxfp4_weights_prepared_bytes(fmt, 2 * width, K) == 0) return plain;
+  return plan_glu(*fmt, M, 2 * width, K).kernel == kGemmPanel ? amx::bf16_panel_bytes(M, K) : plain;
+}
+
+int amxfp4_gemm_silu_mul_prepared(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K, const uint8_t* A_codes,
+                                  const uint8_t* A_scales, const uint8_t* B_codes, const uint8_t* B_scales,
+                                  const void* prepared, size_t prepared_bytes, void* out_bf16, int64_t ld_out,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
+  const size_t need = width > 0 && K > 0 ? amxfp4_weights_prepared_bytes(fmt, 2 * width, K) : 0;
+  if (need > 0) {
+    if (!prepared || prepared_bytes < need)
+      return fail(AMX_ERR_WORKSPACE, "prepared buffer of %zu bytes needed, %zu given", need, prepared ? prepared_bytes : 0);
+    if (!aligned(prepared, 256)) return fail(AMX_ERR_INVALID_ARG, "prepared buffer must be 256-byte aligned");
+  }
+  return glu_impl(fmt, M, width, K, A_codes, A_scales, B_codes, B_scales, need > 0 ? prepared : nullptr, out_bf16, ld_out,
+                  workspace, workspace_bytes, stream);
 }
 
 int amxfp4_dequantize(const amx_format_t* fmt, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,

@@ -46,7 +46,7 @@ class DecoderLayer:
     cast once here (they are static in inference); forward() casts the activations."""
 
     def __init__(self, cfg, weights, fmt, baseline=False, fused_attention=False, fused_glu=None, fused_norm=None,
-                 fused_rope=None):
+                 fused_rope=None, prepared_weights=False):
         self.cfg, self.fmt, self.baseline, self.fused_attention = cfg, fmt, baseline, fused_attention
         # the rotary embedding casts its result (Q and K never exist as BF16 tensors): same bits
         if fused_rope is None:
@@ -68,6 +68,12 @@ class DecoderLayer:
         self.wd = q(weights["wd"])
         self.norm1, self.norm2 = weights["norm1"].contiguous(), weights["norm2"].contiguous()
         self._ws = None
+        # static weights: their kernel-private form written once (2 bytes per element of extra memory for the formats
+        # that multiply on BF16 panels, nothing for the power-of-two formats); same bits
+        self.prepared = None
+        if prepared_weights and not baseline:
+            self.prepared = {id(w): binding.prepare_weights(fmt, w[0], w[1])
+                             for w in (self.wqkv, self.wo, self.wgu, self.wd)}
 
     def _gemm(self, a, b):
         fmt = self.fmt
@@ -75,6 +81,8 @@ class DecoderLayer:
         need = binding.gemm_workspace_bytes(fmt, a[0].shape[-2], b[0].shape[-2], a[0].shape[-1] * 2, batch)
         if need and (self._ws is None or self._ws.numel() < need):
             self._ws = torch.empty(need, dtype=torch.uint8, device=a[0].device)
+        if self.prepared is not None and id(b) in self.prepared and batch == 1:
+            return binding.gemm_prepared(fmt, a[0], a[1], b[0], b[1], self.prepared[id(b)], workspace=self._ws)
         return binding.gemm(fmt, a[0], a[1], b[0], b[1], workspace=self._ws if need else None, baseline=self.baseline)
 
     def _plain_fmt(self):
@@ -147,7 +155,8 @@ class DecoderLayer:
             need = binding.gemm_silu_mul_workspace_bytes(fmt, hc[0].shape[0], c.d_ff, c.d_model)
             if need and (self._ws is None or self._ws.numel() < need):
                 self._ws = torch.empty(need, dtype=torch.uint8, device=x.device)
-            act = binding.gemm_silu_mul(fmt, hc[0], hc[1], self.wgu[0], self.wgu[1], workspace=self._ws)
+            act = binding.gemm_silu_mul(fmt, hc[0], hc[1], self.wgu[0], self.wgu[1], workspace=self._ws,
+                                        prepared=self.prepared[id(self.wgu)] if self.prepared is not None else None)
         else:
             act = binding.silu_mul(self._gemm(hc, self.wgu))
         return binding.residual_add(x2, self._gemm(self._cast(act), self.wd))

@@ -58,7 +58,7 @@ def bf16_reference(x, w, cfg, chunk_heads=4):
     return (x2.to(f32) + (act @ w["wd"].T).to(f32)).to(torch.bfloat16)
 
 
-def run(seq=8192, steps=5, formats=tuple(FORMATS), fused_attention=True, separate_norm=False):
+def run(seq=8192, steps=5, formats=tuple(FORMATS), fused_attention=True, separate_norm=False, prepared_weights=False):
     """Times the layer in each format; returns the dictionary main() prints."""
     cfg = layer.LayerConfig()
     dev = torch.device("cuda:0")
@@ -72,11 +72,14 @@ def run(seq=8192, steps=5, formats=tuple(FORMATS), fused_attention=True, separat
     upd = (ref_out - x.to(torch.float32)).pow(2).mean().item()
     out = {"workload": "c5_llama3_8b_decoder_layer", "seq": seq, "d_model": cfg.d_model, "heads": cfg.n_heads,
            "kv_heads": cfg.n_kv_heads, "d_ff": cfg.d_ff, "data": "synthetic, random-init weights", "fused_attention": fused_attention,
+           "prepared_weights": prepared_weights,
            "reference_update_mean_square": upd, "formats": {}}
     for name in formats:
-        kind, asym = FORMATS[name]
+        # "<format>[prepared_w]": this entry on prepared weights whatever the argument says
+        kind, asym = FORMATS[name.replace("[prepared_w]", "")]
         lay = layer.DecoderLayer(cfg, w, binding.make_format(kind, asym), fused_attention=fused_attention,
-                                 fused_norm=False if separate_norm else None)
+                                 fused_norm=False if separate_norm else None,
+                                 prepared_weights=prepared_weights or name.endswith("[prepared_w]"))
         y = lay.forward(x)  # warm-up, also the output that is compared
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -106,8 +109,11 @@ def main():
                     help="one fused attention call instead of Q.K^T, softmax, cast and P.V with a materialised map")
     ap.add_argument("--separate-norm", action="store_true",
                     help="residual addition, RMS normalisation and cast as three calls instead of one")
+    ap.add_argument("--prepared-weights", action="store_true",
+                    help="the weights' kernel-private form (BF16 panels for FP8 scales) written once, not per call")
     args = ap.parse_args()
-    print(json.dumps(run(args.seq, args.steps, args.formats.split(","), args.fused_attention, args.separate_norm)))
+    print(json.dumps(run(args.seq, args.steps, args.formats.split(","), args.fused_attention, args.separate_norm,
+                         args.prepared_weights)))
 
 
 if __name__ == "__main__":
