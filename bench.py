@@ -411,6 +411,7 @@ def main():
     # MXFP4 and the asymmetric power-of-two format, each with its GEMM kernel's time and fraction of the peak of the
     # MFMA type it issues. --variants adds the rest.
     cases = [("mxfp4_e8m0", "panel", "merged_fp6", False), ("amxfp4_e8m0", "panel", "merged_fp6", False),
+             ("amxfp4_e8m0", "panel", "merged_fp6", True),   # B's merged FP6 panel written once
              ("amxfp4_e8m0", "panel", "merged_fp8", False), ("amxfp4_e8m0", "panel", "split", False)]
     if args.format not in DOUBLE_SCALED and FORMATS[args.format][2] == "bf16":
         # the headline format against weights whose BF16 expansion was written once (amxfp4_gemm_prepared): the step

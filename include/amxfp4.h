@@ -145,11 +145,13 @@ int amxfp4_gemm(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K, const 
 
 /*
  * Static weights. amxfp4_gemm re-derives the kernel's private form of B on every call (for FP8 scales and group sizes
- * other than 32: the exact BF16 expansion, 4 x the bytes of the codes); for weights that stay, that work can be done
- * once. The product is the same (Sec. 4.3), bit for bit what amxfp4_gemm returns.
- *   amxfp4_weights_prepared_bytes   size of the prepared form of B [N][K]; 0 for formats whose kernels read B as it
- *                                   is stored (power-of-two scales of 32-groups), for which the calls below need no
- *                                   buffer and do what amxfp4_gemm does.
+ * other than 32: the exact BF16 expansion, 4 x the bytes of the codes; for asymmetric power-of-two scales of 32-groups:
+ * the merged FP6 panel, its block scales and the positions where some row's two scales lie too far apart, about
+ * 1.6 bytes per element); for weights that stay, that work can be done once. The product is the same (Sec. 4.3), bit
+ * for bit what amxfp4_gemm returns.
+ *   amxfp4_weights_prepared_bytes   size of the prepared form of B [N][K]; 0 for the format whose kernel reads B as it
+ *                                   is stored (symmetric power-of-two scales of 32-groups), for which the calls below
+ *                                   need no buffer and do what amxfp4_gemm does.
  *   amxfp4_prepare_weights          writes it: `prepared` device out, 256-byte aligned, at least that many bytes
  *                                   (AMX_ERR_WORKSPACE otherwise). Depends on fmt, N, K and B only.
  *   amxfp4_gemm_prepared            C = A . B^T with B's prepared form. B_codes / B_scales are still passed: shapes

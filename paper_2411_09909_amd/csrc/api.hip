@@ -236,8 +236,10 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
       !aligned(C, 4))
     return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales and C 4-byte alignment");
   const GemmPlan plan = plan_gemm(f, opts, scaled, M, N, K, batch);
-  if (plan.kernel != kGemmPanel) B_panel = nullptr;  // only the BF16-panel kernel reads an expanded B
-  const size_t need = B_panel ? amx::bf16_panel_bytes(M, K) : plan_workspace_bytes(plan, f.asymmetric != 0, M, N, K, batch);
+  // a prepared B is read by the BF16-panel kernel (its expansion) and by the merged FP6 kernel (its own panel)
+  if (plan.kernel != kGemmPanel && plan.kernel != kGemmFp6Merged) B_panel = nullptr;
+  const size_t need = !B_panel ? plan_workspace_bytes(plan, f.asymmetric != 0, M, N, K, batch)
+                      : plan.kernel == kGemmPanel ? amx::bf16_panel_bytes(M, K) : amx::fp6m_prepared_workspace_bytes(M, N, K);
   if (need > 0) {
     if (!workspace || workspace_bytes < need)
       return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
@@ -257,7 +259,9 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
       e = amx::launch_gemm_fp8m_path(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, hs, timer);
       break;
     case kGemmFp6Merged:
-      e = amx::launch_gemm_fp6m_path(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, hs, timer);
+      e = B_panel ? amx::launch_gemm_fp6m_prepared(M, N, K, A_codes, A_scales, B_panel, C, ldc, workspace, hs, timer)
+                  : amx::launch_gemm_fp6m_path(M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace,
+                                               hs, timer);
       break;
     case kGemmFp4:
       e = amx::launch_gemm_fp4_path(asym, M, N, K, A_codes, A_scales, B_codes, B_scales, C, ldc, batch, workspace, hs,
@@ -388,8 +392,10 @@ static int glu_impl(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K
       !aligned(out_bf16, 2))
     return fail(AMX_ERR_INVALID_ARG, "codes need 16-byte, scales 4-byte, out 2-byte alignment");
   const GemmKernel glu_kernel = plan_glu(f, M, 2 * width, K).kernel;
-  if (glu_kernel != kGemmPanel) B_panel = nullptr;  // only the BF16-panel kernel reads an expanded B
-  const size_t need = B_panel ? amx::bf16_panel_bytes(M, K) : glu_workspace_bytes(f, M, 2 * width, K);
+  if (glu_kernel != kGemmPanel && glu_kernel != kGemmFp6Merged) B_panel = nullptr;
+  const size_t need = !B_panel ? glu_workspace_bytes(f, M, 2 * width, K)
+                      : glu_kernel == kGemmPanel ? amx::bf16_panel_bytes(M, K)
+                                                 : amx::fp6m_prepared_workspace_bytes(M, 2 * width, K);
   if (need > 0) {
     if (!workspace || workspace_bytes < need)
       return fail(AMX_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : 0);
@@ -405,8 +411,10 @@ static int glu_impl(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
   }
   if (glu_kernel == kGemmFp6Merged) {
-    hipError_t e = amx::launch_gemm_fp6m_path(M, 2 * width, K, A_codes, A_scales, B_codes, B_scales, out, ld_out, 1,
-                                              workspace, hs, timer, true);
+    hipError_t e = B_panel ? amx::launch_gemm_fp6m_prepared(M, 2 * width, K, A_codes, A_scales, B_panel, out, ld_out,
+                                                            workspace, hs, timer, true)
+                           : amx::launch_gemm_fp6m_path(M, 2 * width, K, A_codes, A_scales, B_codes, B_scales, out,
+                                                        ld_out, 1, workspace, hs, timer, true);
     return e == hipSuccess ? AMX_OK : hip_fail(e, "gemm_silu_mul launch");
   }
   if (glu_kernel == kGemmFp4) {
@@ -431,7 +439,10 @@ int amxfp4_gemm_silu_mul(const amx_format_t* fmt, int64_t M, int64_t width, int6
 size_t amxfp4_gemm_silu_mul_prepared_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K) {
   const size_t plain = amxfp4_gemm_silu_mul_workspace_bytes(fmt, M, width, K);
   if (plain == 0 || amxfp4_weights_prepared_bytes(fmt, 2 * width, K) == 0) return plain;
-  return plan_glu(*fmt, M, 2 * width, K).kernel == kGemmPanel ? amx::bf16_panel_bytes(M, K) : plain;
+  const GemmKernel kernel = plan_glu(*fmt, M, 2 * width, K).kernel;
+  return kernel == kGemmPanel        ? amx::bf16_panel_bytes(M, K)
+         : kernel == kGemmFp6Merged ? amx::fp6m_prepared_workspace_bytes(M, 2 * width, K)
+                                    : plain;
 }
 
 int amxfp4_gemm_silu_mul_prepared(const amx_format_t* fmt, int64_t M, int64_t width, int64_t K, const uint8_t* A_codes,
@@ -471,12 +482,14 @@ int amxfp4_gemm_ex(const amx_format_t* fmt, const amx_gemm_options_t* opts, int6
                    workspace_bytes, stream);
 }
 
-// Prepared weights: the formats whose large products run on the BF16-panel kernel (everything but power-of-two scales
-// of 32-groups) can have B's panel expanded once.
+// Prepared weights: the formats whose large products run on the BF16-panel kernel have B's panel expanded once; the
+// asymmetric power-of-two format has B's merged FP6 panel, anchors and plan written once; the symmetric power-of-two
+// format's kernel reads the codes as they are.
 size_t amxfp4_weights_prepared_bytes(const amx_format_t* fmt, int64_t N, int64_t K) {
-  if (!fmt || N <= 0 || K <= 0 || check_format(fmt) != AMX_OK) return 0;
+  if (!fmt || N <= 0 || K <= 0 || check_format(fmt) != AMX_OK || K % fmt->group_size != 0) return 0;
   const bool pot32 = fmt->group_size == 32 && (fmt->scale == AMX_SCALE_E8M0_FLOOR || fmt->scale == AMX_SCALE_E8M0_ROUND);
-  return pot32 ? 0 : amx::bf16_panel_bytes(N, K);
+  if (!pot32) return amx::bf16_panel_bytes(N, K);
+  return fmt->asymmetric && amx::fp6m_path_supported(1, N, K) ? amx::fp6m_prepared_bytes(N, K) : 0;
 }
 
 int amxfp4_prepare_weights(const amx_format_t* fmt, int64_t N, int64_t K, const uint8_t* B_codes,
@@ -492,15 +505,21 @@ int amxfp4_prepare_weights(const amx_format_t* fmt, int64_t N, int64_t K, const 
   if (!prepared || prepared_bytes < need)
     return fail(AMX_ERR_WORKSPACE, "prepared buffer of %zu bytes needed, %zu given", need, prepared ? prepared_bytes : 0);
   if (!aligned(prepared, 256)) return fail(AMX_ERR_INVALID_ARG, "prepared buffer must be 256-byte aligned");
-  const hipError_t e = amx::launch_expand_b_panel(fmt->scale, fmt->asymmetric != 0, fmt->group_size, N, K, B_codes, B_scales,
-                                                  prepared, reinterpret_cast<hipStream_t>(stream));
+  const bool pot32 = fmt->group_size == 32 && (fmt->scale == AMX_SCALE_E8M0_FLOOR || fmt->scale == AMX_SCALE_E8M0_ROUND);
+  const hipError_t e =
+      pot32 ? amx::launch_fp6m_prepare_b(N, K, B_codes, B_scales, prepared, reinterpret_cast<hipStream_t>(stream))
+            : amx::launch_expand_b_panel(fmt->scale, fmt->asymmetric != 0, fmt->group_size, N, K, B_codes, B_scales,
+                                         prepared, reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? AMX_OK : hip_fail(e, "prepare_weights launch");
 }
 
 size_t amxfp4_gemm_prepared_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K) {
   if (!fmt || M <= 0 || N <= 0 || K <= 0) return 0;
   const GemmPlan plan = plan_gemm(*fmt, nullptr, false, M, N, K, 1);
-  if (plan.kernel == kGemmPanel && amxfp4_weights_prepared_bytes(fmt, N, K) > 0) return amx::bf16_panel_bytes(M, K);
+  if (amxfp4_weights_prepared_bytes(fmt, N, K) > 0) {
+    if (plan.kernel == kGemmPanel) return amx::bf16_panel_bytes(M, K);
+    if (plan.kernel == kGemmFp6Merged) return amx::fp6m_prepared_workspace_bytes(M, N, K);
+  }
   return plan_workspace_bytes(plan, fmt->asymmetric != 0, M, N, K, 1);
 }
 

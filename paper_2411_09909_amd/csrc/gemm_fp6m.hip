@@ -48,6 +48,27 @@ static int64_t fp6_flag_bytes(int64_t rows, int64_t K) { return ((rows + kFp6Fla
 // per batch entry: positions (G + 1 words), split flags (G bytes, padded to words), the K step count
 static int64_t fp6_plan_bytes(int64_t K) { return round_up(((K >> 5) + 1) * 4 + (K >> 5) + 4, 256); }
 
+// B alone (prepared weights): at most every position split, 2 blocks each = K / 32 steps
+static int64_t fp6_prepared_steps(int64_t K) { return round_up(K >> 5, kFp6StepPad); }
+static int64_t fp6_prepared_panel_bytes(int64_t Np, int64_t K) { return (Np / 32) * fp6_prepared_steps(K) * kFp6FragBytes; }
+static int64_t fp6_prepared_anchor_bytes(int64_t Np, int64_t K) { return (Np / 32) * (fp6_prepared_steps(K) / 4) * 256; }
+// the table of B blocks behind the plan of a call on prepared weights: one word per 32-block of the lengthened K
+static int64_t fp6_table_offset(int64_t K) { return fp6_plan_bytes(K); }
+// (the kernel reads the entries of up to 16 stages past the last one: zeros)
+static int64_t fp6_table_bytes(int64_t K) { return round_up(2 * (fp6_max_steps(K) + 17) * 4, 256); }
+
+size_t fp6m_prepared_bytes(int64_t N, int64_t K) {
+  const int64_t Np = round_up(N, kPanelRows);
+  return (size_t)(fp6_prepared_panel_bytes(Np, K) + fp6_prepared_anchor_bytes(Np, K) + fp6_plan_bytes(K) +
+                  round_up(fp6_flag_bytes(N, K), 256));
+}
+
+size_t fp6m_prepared_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+  const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows);
+  return (size_t)(fp6_panel_bytes(Mp, K) + fp6_anchor_bytes(Mp, K) + fp6_anchor_bytes(Np, K) +
+                  round_up(fp6_flag_bytes(M, K), 256) + fp6_plan_bytes(K) + fp6_table_bytes(K));
+}
+
 size_t fp6m_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch) {
   const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows);
   return (size_t)(batch * (fp6_panel_bytes(Mp, K) + fp6_panel_bytes(Np, K) + fp6_anchor_bytes(Mp, K) +
@@ -95,10 +116,17 @@ __global__ __launch_bounds__(256) void fp6_flag_kernel(const uint8_t* __restrict
 // grid: (1, 1, batch); block 256. plan (per batch entry): pos[G + 1] words (first 32-block of group g; pos[G] = total
 // blocks), then G bytes of split flags (bit 0: A's position is split, bit 1: B's), then - word aligned - the number
 // of K steps (total blocks / 2 rounded up to a multiple of kFp6StepPad).
+// With a prepared B (prepared_plan: the plan B's own passes left, pos and split of B alone): B's flags come from that
+// plan instead of the flag array (chunks_b = 0), and a table at table_offset names, for every 32-block e of the
+// lengthened K, the block i of B's prepared panel that stands there (zero-padding blocks: block 0, against A's zeros),
+// as the byte offset of its 16-byte part within a row block of the panel, (i / 2) * 1536 + (i % 2) * 512, with i % 2
+// in bit 0 (its 8-byte part lies at (i / 2) * 1536 + 1024 + (i % 2) * 256).
 __global__ __launch_bounds__(256) void fp6_plan_kernel(const uint8_t* __restrict__ flags, int64_t G, int chunks_a,
                                                        int chunks_b, int64_t plan_stride, int64_t steps_offset,
-                                                       uint8_t* __restrict__ plan_base) {
+                                                       uint8_t* __restrict__ plan_base,
+                                                       const uint8_t* __restrict__ prepared_plan, int64_t table_offset) {
   __shared__ uint32_t part[256];
+  __shared__ uint32_t totals[2];  // blocks in use, blocks after padding to whole K steps
   const int64_t b = blockIdx.z;
   const uint8_t* fl = flags + b * (chunks_a + chunks_b) * G;
   uint8_t* plan = plan_base + b * plan_stride;
@@ -128,6 +156,12 @@ __global__ __launch_bounds__(256) void fp6_plan_kernel(const uint8_t* __restrict
       if (fl[idx]) atomicOr(&gathered[(idx % G) >> 2], (idx / G < chunks_a ? 1u : 2u) << (8 * (idx % G & 3)));
   }
   __syncthreads();
+  if (prepared_plan) {  // B's flags: bit 1 of its own plan's split bytes
+    const uint8_t* split_b = prepared_plan + (G + 1) * 4;
+    for (int64_t g = threadIdx.x; g < G; g += 256)
+      if (split_b[g] & 2u) atomicOr(&gathered[g >> 2], 2u << (8 * (g & 3)));
+    __syncthreads();
+  }
   auto flags_of = [&](int64_t g) { return (gathered[g >> 2] >> (8 * (g & 3))) & 3u; };
   for (int64_t g = threadIdx.x; g < G; g += 256) split[g] = (uint8_t)flags_of(g);
   const int64_t per = (G + 255) / 256, g0 = threadIdx.x * per, g1 = g0 + per < G ? g0 + per : G;
@@ -145,13 +179,26 @@ __global__ __launch_bounds__(256) void fp6_plan_kernel(const uint8_t* __restrict
     pos[G] = run;
     const uint32_t ks = (run + 1) / 2;
     steps[0] = (ks + kFp6StepPad - 1) / kFp6StepPad * kFp6StepPad;
+    totals[0] = run, totals[1] = 2 * steps[0];
   }
   __syncthreads();
   uint32_t run = part[threadIdx.x];
+  const uint32_t* pos_b = reinterpret_cast<const uint32_t*>(prepared_plan);
+  uint32_t* table = reinterpret_cast<uint32_t*>(plan + table_offset);
   for (int64_t g = g0; g < g1; ++g) {
     pos[g] = run;
-    run += (1u + (flags_of(g) & 1u)) * (1u + (flags_of(g) >> 1));
+    const uint32_t fa = flags_of(g) & 1u, fb = flags_of(g) >> 1;
+    if (prepared_plan) {  // A holds each sign class for as many blocks as B alternates: (b+, b-, b+, b-)
+      const uint32_t b0 = pos_b[g];
+      for (uint32_t e = 0; e < (1u + fa) * (1u + fb); ++e) {
+        const uint32_t i = b0 + (fb ? (e & 1u) : 0u);  // block i of B's panel: step i / 2, lanes 32 (i % 2) ..
+        table[run + e] = (i >> 1) * (uint32_t)kFp6FragBytes + (i & 1u) * 512u + (i & 1u);
+      }
+    }
+    run += (1u + fa) * (1u + fb);
   }
+  if (prepared_plan)  // the zero blocks that pad K, and the 17 stages the kernel's table reads may run past the end
+    for (uint32_t e = totals[0] + threadIdx.x; e < totals[1] + 34; e += 256) table[e] = 0;
 }
 
 // ---- pass 3: the merge ---------------------------------------------------------------------------------------------------
@@ -277,13 +324,41 @@ __global__ __launch_bounds__(256) void fp6_merge_kernel(Fp6MergeJob ja, Fp6Merge
   }
 }
 
+// Prepared B: its anchors in the order of this call's lengthened K. grid: (Np / 32, ceil(words / 4)); block 256 = four
+// anchor words x 64 lanes. Word w of lane 32 h + r holds, in byte q, the block scale of (row r, 32-block h) of K step
+// 4 w + q, i.e. of block e = 2 (4 w + q) + h, which is block table[e] of the prepared panel; steps beyond the call's
+// count get byte 0 (they multiply A's zero blocks).
+__global__ __launch_bounds__(256) void fp6_gather_anchors_kernel(const uint8_t* __restrict__ prepared_anchors,
+                                                                 int64_t prepared_words, const uint8_t* __restrict__ plan,
+                                                                 int64_t steps_offset, int64_t table_offset,
+                                                                 int64_t max_words, uint8_t* __restrict__ out) {
+  const uint32_t steps = *reinterpret_cast<const uint32_t*>(plan + steps_offset);
+  const uint32_t* table = reinterpret_cast<const uint32_t*>(plan + table_offset);
+  const int64_t rb = blockIdx.x, w = (int64_t)blockIdx.y * 4 + (threadIdx.x >> 6);
+  const uint32_t slot = threadIdx.x & 63, h = slot >> 5, r = slot & 31;
+  if (w >= max_words) return;
+  const uint8_t* src = prepared_anchors + rb * prepared_words * 256;
+  uint32_t word = 0;
+#pragma unroll
+  for (uint32_t q = 0; q < 4; ++q) {
+    const uint32_t step = (uint32_t)w * 4 + q;
+    if (step < steps) {
+      const uint32_t t = table[2 * step + h], odd = t & 1u, istep = t / (uint32_t)kFp6FragBytes;
+      word |= (uint32_t)src[((int64_t)(istep >> 2) * 64 + odd * 32 + r) * 4 + (istep & 3u)] << (8 * q);
+    }
+  }
+  reinterpret_cast<uint32_t*>(out)[(rb * max_words + w) * 64 + slot] = word;
+}
+
 // ---- the GEMM ------------------------------------------------------------------------------------------------------------
 // 256 x 256 tile, 2 x 2 waves of 4 x 4 MFMA tiles. One stage = one K step of 64: 16 fragments = 24 KiB; six stage
 // arrays form the ring: while stage S is multiplied, stage S + 1 is complete in LDS (fragment reads run ahead into it)
 // and stages S + 2 .. S + 5 are in flight as direct-to-LDS loads (the panels are fragment-major, so staging is a linear
 // copy of 1 KiB pieces). One barrier per stage.
 // GLU: the gated-activation epilogue of store_glu_tiles() (gemm_common.h); C is then the BF16 output [M][ldc].
-template <int WM, int WN, int FM, int FN, bool GLU = false>
+// PREP: B comes from a prepared panel (B's own blocks, independent of A): b_steps K steps per row block, and the plan
+// holds, behind the step count, the table of B blocks of the lengthened K; Bsc is this call's gathered anchor array.
+template <int WM, int WN, int FM, int FN, bool GLU = false, bool PREP = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* __restrict__ Ap,
                                                                  const uint8_t* __restrict__ Asc,
                                                                  const uint8_t* __restrict__ Bp,
@@ -292,7 +367,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* 
                                                                  int64_t plan_stride, int64_t plan_steps_offset,
                                                                  float* __restrict__ C, int64_t M, int64_t N, int64_t Mp,
                                                                  int64_t Np, int max_steps, int64_t ldc, int tiles_m,
-                                                                 int tiles_n, int super_m) {
+                                                                 int tiles_n, int super_m, int b_steps,
+                                                                 int64_t plan_table_offset) {
   static_assert(WM == 2 && WN == 2 && FM == 4 && FN == 4, "the issue schedule is written for 2 x 2 waves of 4 x 4 tiles");
   constexpr int kWaves = WM * WN, kRowBlocks = 8;           // row blocks of 32 per operand and tile
   constexpr int kStageBytes = 2 * kRowBlocks * kFp6FragBytes;  // 24 KiB
@@ -318,10 +394,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* 
   const int nwords = nsteps >> 2;
   const int64_t step_bytes = kFp6FragBytes;
   const uint8_t* Abase = Ap + ((b * (Mp >> 5) + (int64_t)tm * kRowBlocks) * max_steps) * step_bytes;
-  const uint8_t* Bbase = Bp + ((b * (Np >> 5) + (int64_t)tn * kRowBlocks) * max_steps) * step_bytes;
+  const int b_panel_steps = PREP ? b_steps : max_steps;  // K steps a row block of B's panel holds
+  const uint8_t* Bbase = Bp + ((b * (Np >> 5) + (int64_t)tn * kRowBlocks) * b_panel_steps) * step_bytes;
   const uint32_t panel_span = (uint32_t)kRowBlocks * (uint32_t)max_steps * (uint32_t)kFp6FragBytes;
+  const uint32_t b_span = (uint32_t)kRowBlocks * (uint32_t)b_panel_steps * (uint32_t)kFp6FragBytes;
   const __amdgpu_buffer_rsrc_t Ar = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(Abase), 0, (int)panel_span, 0x00020000);
-  const __amdgpu_buffer_rsrc_t Br = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(Bbase), 0, (int)panel_span, 0x00020000);
+  const __amdgpu_buffer_rsrc_t Br = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(Bbase), 0, (int)b_span, 0x00020000);
   const int max_words = max_steps >> 2;
   const __amdgpu_buffer_rsrc_t Asr = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t*>(Asc + ((b * (Mp >> 5) + (int64_t)tm * kRowBlocks + wm * FM) * max_words) * 256), 0,
@@ -342,14 +420,40 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* 
   };
   const int src0 = source_offset(wave), src1 = source_offset(wave + kWaves), src2 = source_offset(wave + 2 * kWaves);
 #define AMX_SRC(L) ((L) % 3 == 0 ? src0 : (L) % 3 == 1 ? src1 : src2)
-#define AMX_ISSUE_LOAD(L, ST, DST)                                                                          \
+  // PREP: the two 32-blocks of a stage come from anywhere in B's panel, so B's half stage is laid out differently in
+  // LDS: the eight fragments' 16-byte parts first ([8][64 lanes][16 bytes]: lanes 0-31 the stage's first block, 32-63
+  // its second), then their 8-byte parts ([8][64 lanes][8 bytes]). KiB 0 .. 7 of the half stage are then the 16-byte
+  // parts of row blocks 0 .. 7, KiB 8 + j the 8-byte parts of row blocks 2 j (lanes 0-31 of the load: 16-byte pieces
+  // 0-15 first block, 16-31 second) and 2 j + 1 (lanes 32-63). A wave's three loads are KiB wave, wave + 4 (16-byte
+  // parts) and wave + 8 (8-byte parts). Per lane and load, loop-invariant: the source offset without the block (pb*)
+  // and whether the lane takes the stage's second block (ps*); per stage, from the table: the two blocks' offsets.
+  int pb0 = 0, pb1 = 0, pb2 = 0;
+  bool ps0 = false, ps1 = false, ps2 = false;
+  if constexpr (PREP) {
+    const int row_block_bytes = b_panel_steps * kFp6FragBytes;
+    pb0 = wave * row_block_bytes + (lane & 31) * 16, ps0 = lane >= 32;
+    pb1 = (wave + kWaves) * row_block_bytes + (lane & 31) * 16, ps1 = lane >= 32;
+    pb2 = (2 * wave + (lane >> 5)) * row_block_bytes + 1024 + (lane & 15) * 16, ps2 = (lane & 31) >= 16;
+  }
+  const uint32_t* table = reinterpret_cast<const uint32_t*>(plan_base + b * plan_stride + plan_table_offset);
+#define AMX_PB(L) ((L) % 3 == 0 ? pb0 : (L) % 3 == 1 ? pb1 : pb2)
+#define AMX_PS(L) ((L) % 3 == 0 ? ps0 : (L) % 3 == 1 ? ps1 : ps2)
+  // T0, T1: the table entries of stage ST's two blocks (PREP only): offset of the 16-byte part, parity in bit 0; the
+  // 8-byte part of an odd block lies 256 bytes, not 512, behind the even one's
+#define AMX_PART(L, T) ((L) % 3 == 2 ? ((T) & ~1u) - ((T) & 1u) * 256u : ((T) & ~1u))
+#define AMX_ISSUE_LOAD(L, ST, DST, T0, T1)                                                                  \
   {                                                                                                         \
-    if ((L) < kLoads / 2)                                                                                   \
+    if ((L) < kLoads / 2) {                                                                                 \
       __builtin_amdgcn_raw_ptr_buffer_load_lds(Ar, (lds_ptr_t)((DST) + (wave + kWaves * (L)) * 1024), 16,   \
                                                AMX_SRC(L), (ST) * kFp6FragBytes, 0, 0);                     \
-    else                                                                                                    \
+    } else if constexpr (PREP) {                                                                            \
+      const int voff_ = AMX_PB(L) + (int)(AMX_PS(L) ? AMX_PART(L, T1) : AMX_PART(L, T0));                   \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(Br, (lds_ptr_t)((DST) + (wave + kWaves * (L)) * 1024), 16,   \
+                                               voff_, 0, 0, 0);                                             \
+    } else {                                                                                                \
       __builtin_amdgcn_raw_ptr_buffer_load_lds(Br, (lds_ptr_t)((DST) + (wave + kWaves * (L)) * 1024), 16,   \
                                                AMX_SRC(L), (ST) * kFp6FragBytes, 0, 0);                     \
+    }                                                                                                       \
   }
   // anchor words of four K steps (word W) into register set SET (three sets: the loop body covers three words)
   uint32_t sa[3][FM], sb[3][FN];
@@ -371,16 +475,20 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* 
 
   // prologue: the anchors of the first word, then five stages in flight; stages 0 and 1 must have landed
   AMX_LOAD_ANCHORS(0, 0);
+  uint32_t tp[12];  // table entries of stages 0 .. 5 (nsteps >= 12)
 #pragma unroll
-  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 0, lds0);
+  for (int e = 0; e < 12; ++e) tp[e] = PREP ? table[e] : 0u;
 #pragma unroll
-  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 1, lds1);
+  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 0, lds0, tp[0], tp[1]);
 #pragma unroll
-  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 2, lds2);
+  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 1, lds1, tp[2], tp[3]);
 #pragma unroll
-  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 3, lds3);
+  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 2, lds2, tp[4], tp[5]);
 #pragma unroll
-  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 4, lds4);
+  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 3, lds3, tp[6], tp[7]);
+#pragma unroll
+  for (int l = 0; l < kLoads; ++l) AMX_ISSUE_LOAD(l, 4, lds4, tp[8], tp[9]);
+
   AMX_WAIT_VMCNT(3 * kLoads);
   AMX_BARRIER();
 
@@ -392,6 +500,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* 
   };
   Frag aR[2], bR[2][FN];
   const int offA = (wm * FM) * kFp6FragBytes, offB = (kRowBlocks + wn * FN) * kFp6FragBytes;
+  // B fragment j of this wave: 16-byte parts at b_lo + j * b_lo_step, 8-byte parts at b_hi + j * b_hi_step (stage base
+  // and lane offsets included below)
+  constexpr int kHalf = kRowBlocks * kFp6FragBytes;
+  const int b_lo = PREP ? kHalf + wn * FN * 1024 : offB, b_hi = PREP ? kHalf + kRowBlocks * 1024 + wn * FN * 512 - 1024 : offB;
+  constexpr int b_lo_step = PREP ? 1024 : kFp6FragBytes, b_hi_step = PREP ? 512 : kFp6FragBytes;
   const int lo_off = lane * 16, hi_off = 1024 + lane * 8;
 #define AMX_RD_LO(P) (*reinterpret_cast<const u32x4*>(P))
 #define AMX_RD_HI(P) (*reinterpret_cast<const u32x2*>(P))
@@ -401,8 +514,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* 
   aR[0].hi = AMX_RD_HI(lds0 + offA + hi_off);
 #pragma unroll
   for (int j = 0; j < FN; ++j) {
-    bR[0][j].lo = AMX_RD_LO(lds0 + offB + j * kFp6FragBytes + lo_off);
-    bR[0][j].hi = AMX_RD_HI(lds0 + offB + j * kFp6FragBytes + hi_off);
+    bR[0][j].lo = AMX_RD_LO(lds0 + b_lo + j * b_lo_step + lo_off);
+    bR[0][j].hi = AMX_RD_HI(lds0 + b_hi + j * b_hi_step + hi_off);
   }
 
   // Stage S = K step Q (0..3, a literal: it selects the anchor byte) of the word in set SET; B operands in set BSET;
@@ -428,16 +541,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* 
       acc[i][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, AMX_OPERAND(bR[BSET][0]), acc[i][0], 3, 3, \
                                                                   Q, (int)sa[SET][i], Q, (int)sb[SET][0]);       \
       __builtin_amdgcn_sched_barrier(0);                                                                         \
-      bR[(BSET) ^ 1][i].lo = AMX_RD_LO((NXT) + offB + i * kFp6FragBytes + lo_off);                               \
-      bR[(BSET) ^ 1][i].hi = AMX_RD_HI((NXT) + offB + i * kFp6FragBytes + hi_off);                               \
+      bR[(BSET) ^ 1][i].lo = AMX_RD_LO((NXT) + b_lo + i * b_lo_step + lo_off);                                   \
+      bR[(BSET) ^ 1][i].hi = AMX_RD_HI((NXT) + b_hi + i * b_hi_step + hi_off);                                   \
       acc[i][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, AMX_OPERAND(bR[BSET][1]), acc[i][1], 3, 3, \
                                                                   Q, (int)sa[SET][i], Q, (int)sb[SET][1]);       \
       __builtin_amdgcn_sched_barrier(0);                                                                         \
-      AMX_ISSUE_LOAD(i, fetch_, FETCH);                                                                          \
+      AMX_ISSUE_LOAD(i, fetch_, FETCH, tt[2 * ((S) - s)], tt[2 * ((S) - s) + 1]);                                \
       acc[i][2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, AMX_OPERAND(bR[BSET][2]), acc[i][2], 3, 3, \
                                                                   Q, (int)sa[SET][i], Q, (int)sb[SET][2]);       \
       __builtin_amdgcn_sched_barrier(0);                                                                         \
-      if (i + FM < kLoads) AMX_ISSUE_LOAD(i + FM, fetch_, FETCH);                                                \
+      if (i + FM < kLoads) AMX_ISSUE_LOAD(i + FM, fetch_, FETCH, tt[2 * ((S) - s)], tt[2 * ((S) - s) + 1]);      \
       acc[i][3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, AMX_OPERAND(bR[BSET][3]), acc[i][3], 3, 3, \
                                                                   Q, (int)sa[SET][i], Q, (int)sb[SET][3]);       \
       __builtin_amdgcn_sched_barrier(0);                                                                         \
@@ -449,6 +562,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* 
   }
 
   for (int s = 0; s < nsteps; s += 12) {
+    // PREP: the table entries of the twelve stages this round fetches (stages s + 5 .. s + 16), read as scalars in one
+    // go: a scalar load's result is waited for together with every LDS read in flight, once per round instead of once
+    // per stage. Stages past the end read the zeros behind the table's last entry (block 0, into a buffer that is
+    // never multiplied).
+    uint32_t tt[24];
+#pragma unroll
+    for (int e = 0; e < 24; ++e) tt[e] = PREP ? table[2 * (s + 5) + e] : 0u;
     AMX_STAGE(s, 0, 1, 0, 0, lds0, lds1, lds5);
     AMX_STAGE(s + 1, 0, 1, 1, 1, lds1, lds2, lds0);
     AMX_STAGE(s + 2, 0, 1, 2, 0, lds2, lds3, lds1);
@@ -469,6 +589,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_fp6m_kernel(const uint8_t* 
 #undef AMX_RD_HI
 #undef AMX_LOAD_ANCHORS
 #undef AMX_ISSUE_LOAD
+#undef AMX_PB
+#undef AMX_PS
+#undef AMX_PART
 #undef AMX_SRC
 
   if constexpr (GLU) {
@@ -508,7 +631,7 @@ hipError_t launch_gemm_fp6m_path(int64_t M, int64_t N, int64_t K, const uint8_t*
                      dim3(256), 0, s,
                      A_scales, B_scales, M, N, G, chunks_a, chunks_b, flags);
   hipLaunchKernelGGL(fp6_plan_kernel, dim3(1, 1, (unsigned)batch), dim3(256), 0, s, flags, G, chunks_a, chunks_b,
-                     plan_stride, steps_offset, plan);
+                     plan_stride, steps_offset, plan, static_cast<const uint8_t*>(nullptr), (int64_t)0);
   const Fp6MergeJob ja = {A_codes, A_scales, Ap, Asc, M, Mp}, jb = {B_codes, B_scales, Bp, Bsc, N, Np};
   hipLaunchKernelGGL(fp6_merge_kernel,
                      dim3((unsigned)((Mp + Np) / 32), (unsigned)((G + 2 * kFp6StepPad + 7) / 8), (unsigned)batch),
@@ -524,11 +647,80 @@ hipError_t launch_gemm_fp6m_path(int64_t M, int64_t N, int64_t K, const uint8_t*
   if (glu)
     hipLaunchKernelGGL((gemm_fp6m_kernel<2, 2, 4, 4, true>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s,
                        Ap, Asc, Bp, Bsc, plan, plan_stride, steps_offset, C, M, N, Mp, Np, steps_cap, ldc, tiles_m,
-                       tiles_n, super_m);
+                       tiles_n, super_m, 0, (int64_t)0);
   else
     hipLaunchKernelGGL((gemm_fp6m_kernel<2, 2, 4, 4>), dim3(grid, 1, (unsigned)batch), dim3(Cfg::kThreads), 0, s, Ap,
                        Asc, Bp, Bsc, plan, plan_stride, steps_offset, C, M, N, Mp, Np, steps_cap, ldc, tiles_m, tiles_n,
-                       super_m);
+                       super_m, 0, (int64_t)0);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (timer.stop) e = hipEventRecord(timer.stop, s);
+  return e;
+}
+
+// ---- prepared weights ------------------------------------------------------------------------------------------------
+// prepared: [B's panel: its own blocks, one per position and two (b+, b-) where some row of B leaves the window]
+// [its anchors][its plan: pos, split][scratch: its flag array]. The three passes above, run on B alone.
+hipError_t launch_fp6m_prepare_b(int64_t N, int64_t K, const uint8_t* B_codes, const uint8_t* B_scales, void* prepared,
+                                 hipStream_t s) {
+  const int64_t Np = round_up(N, kPanelRows), G = K >> 5, b_steps = fp6_prepared_steps(K);
+  uint8_t* Bp = reinterpret_cast<uint8_t*>(prepared);
+  uint8_t* Bsc = Bp + fp6_prepared_panel_bytes(Np, K);
+  uint8_t* plan = Bsc + fp6_prepared_anchor_bytes(Np, K);
+  uint8_t* flags = plan + fp6_plan_bytes(K);
+  const int chunks_b = (int)((N + kFp6FlagRows - 1) / kFp6FlagRows);
+  const int64_t steps_offset = round_up((G + 1) * 4 + G, 4);
+  hipLaunchKernelGGL(fp6_flag_kernel, dim3((unsigned)((G + 63) / 64), (unsigned)chunks_b, 1), dim3(256), 0, s,
+                     static_cast<const uint8_t*>(nullptr), B_scales, (int64_t)0, N, G, 0, chunks_b, flags);
+  hipLaunchKernelGGL(fp6_plan_kernel, dim3(1, 1, 1), dim3(256), 0, s, flags, G, 0, chunks_b, fp6_plan_bytes(K),
+                     steps_offset, plan, static_cast<const uint8_t*>(nullptr), (int64_t)0);
+  const Fp6MergeJob none = {nullptr, nullptr, nullptr, nullptr, 0, 0}, jb = {B_codes, B_scales, Bp, Bsc, N, Np};
+  hipLaunchKernelGGL(fp6_merge_kernel, dim3((unsigned)(Np / 32), (unsigned)((G + 2 * kFp6StepPad + 7) / 8), 1), dim3(256), 0,
+                     s, none, jb, K, b_steps, fp6_plan_bytes(K), steps_offset, plan);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_fp6m_prepared(int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
+                                     const void* prepared, float* C, int64_t ldc, void* workspace, hipStream_t s,
+                                     const KernelTimer& timer, bool glu) {
+  const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows), G = K >> 5;
+  const int64_t max_steps = fp6_max_steps(K), b_steps = fp6_prepared_steps(K);
+  const uint8_t* Bp = reinterpret_cast<const uint8_t*>(prepared);
+  const uint8_t* Bsc_prepared = Bp + fp6_prepared_panel_bytes(Np, K);
+  const uint8_t* plan_b = Bsc_prepared + fp6_prepared_anchor_bytes(Np, K);
+  uint8_t* Ap = reinterpret_cast<uint8_t*>(workspace);
+  uint8_t* Asc = Ap + fp6_panel_bytes(Mp, K);
+  uint8_t* Bsc = Asc + fp6_anchor_bytes(Mp, K);
+  uint8_t* flags = Bsc + fp6_anchor_bytes(Np, K);
+  uint8_t* plan = flags + round_up(fp6_flag_bytes(M, K), 256);
+  const int chunks_a = (int)((M + kFp6FlagRows - 1) / kFp6FlagRows);
+  const int64_t plan_stride = fp6_plan_bytes(K) + fp6_table_bytes(K), steps_offset = round_up((G + 1) * 4 + G, 4);
+  const int64_t table_offset = fp6_table_offset(K);
+  hipLaunchKernelGGL(fp6_flag_kernel, dim3((unsigned)((G + 63) / 64), (unsigned)chunks_a, 1), dim3(256), 0, s, A_scales,
+                     static_cast<const uint8_t*>(nullptr), M, (int64_t)0, G, chunks_a, 0, flags);
+  hipLaunchKernelGGL(fp6_plan_kernel, dim3(1, 1, 1), dim3(256), 0, s, flags, G, chunks_a, 0, plan_stride, steps_offset, plan,
+                     plan_b, table_offset);
+  const Fp6MergeJob ja = {A_codes, A_scales, Ap, Asc, M, Mp}, none = {nullptr, nullptr, nullptr, nullptr, 0, 0};
+  hipLaunchKernelGGL(fp6_merge_kernel, dim3((unsigned)(Mp / 32), (unsigned)((G + 2 * kFp6StepPad + 7) / 8), 1), dim3(256), 0,
+                     s, ja, none, K, max_steps, plan_stride, steps_offset, plan);
+  const int64_t max_words = max_steps / 4;
+  hipLaunchKernelGGL(fp6_gather_anchors_kernel, dim3((unsigned)(Np / 32), (unsigned)((max_words + 3) / 4)), dim3(256), 0, s,
+                     Bsc_prepared, b_steps / 4, plan, steps_offset, table_offset, max_words, Bsc);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  using Cfg = TileCfg<2, 2, 4, 4>;
+  const int tiles_m = (int)((M + Cfg::kTileM - 1) / Cfg::kTileM), tiles_n = (int)((N + Cfg::kTileN - 1) / Cfg::kTileN);
+  int super_m;
+  const unsigned grid = supertile_grid(tiles_m, tiles_n, super_m);
+  if (timer.start && (e = hipEventRecord(timer.start, s)) != hipSuccess) return e;
+  const int steps_cap = (int)max_steps, b_cap = (int)b_steps;
+  if (glu)
+    hipLaunchKernelGGL((gemm_fp6m_kernel<2, 2, 4, 4, true, true>), dim3(grid, 1, 1), dim3(Cfg::kThreads), 0, s, Ap, Asc, Bp,
+                       Bsc, plan, plan_stride, steps_offset, C, M, N, Mp, Np, steps_cap, ldc, tiles_m, tiles_n, super_m,
+                       b_cap, table_offset);
+  else
+    hipLaunchKernelGGL((gemm_fp6m_kernel<2, 2, 4, 4, false, true>), dim3(grid, 1, 1), dim3(Cfg::kThreads), 0, s, Ap, Asc, Bp,
+                       Bsc, plan, plan_stride, steps_offset, C, M, N, Mp, Np, steps_cap, ldc, tiles_m, tiles_n, super_m,
+                       b_cap, table_offset);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (timer.stop) e = hipEventRecord(timer.stop, s);
   return e;

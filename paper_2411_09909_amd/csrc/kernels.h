@@ -128,6 +128,16 @@ size_t fp6m_path_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch)
 hipError_t launch_gemm_fp6m_path(int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
                                  const uint8_t* B_codes, const uint8_t* B_scales, float* C, int64_t ldc, int64_t batch,
                                  void* workspace, hipStream_t s, const KernelTimer& timer, bool glu = false);
+// the same on prepared weights: B's panel (its own blocks), anchors and plan written once (fp6m_prepared_bytes(N, K)
+// bytes); the call then flags and merges only A (workspace: A's panel and anchors, B's anchors in the call's K order,
+// the plan with the table of B blocks)
+size_t fp6m_prepared_bytes(int64_t N, int64_t K);
+size_t fp6m_prepared_workspace_bytes(int64_t M, int64_t N, int64_t K);
+hipError_t launch_fp6m_prepare_b(int64_t N, int64_t K, const uint8_t* B_codes, const uint8_t* B_scales, void* prepared,
+                                 hipStream_t s);
+hipError_t launch_gemm_fp6m_prepared(int64_t M, int64_t N, int64_t K, const uint8_t* A_codes, const uint8_t* A_scales,
+                                     const void* prepared, float* C, int64_t ldc, void* workspace, hipStream_t s,
+                                     const KernelTimer& timer, bool glu = false);
 
 // gemm_e5m2.hip: FP8-E5M2 scales, dequantization fused into the FP16-MFMA kernel (no workspace)
 bool e5m2_fused_supported(int64_t M, int64_t N, int64_t K);

@@ -233,10 +233,11 @@ def test_decoder_layer_on_the_tiled_kernels(scale, asym, fused):
     assert exact >= LAYER_EXACT, "only %.3f of the output elements are bit-identical" % exact
 
 
-@pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.FP8_E4M3, 1), (ref.E8M0_FLOOR, 1)])
+@pytest.mark.parametrize("scale,asym", [(ref.FP8_E5M2, 1), (ref.FP8_E4M3, 1), (ref.E8M0_FLOOR, 1), (ref.E8M0_FLOOR, 0)])
 def test_decoder_layer_on_prepared_weights_gives_the_same_bits(scale, asym):
-    """The layer with its weights' kernel-private form written once (BF16 panels for the FP8 scales; nothing to prepare
-    for power-of-two scales): all four linear layers, the gated GEMM included, must give the bits of the plain calls."""
+    """The layer with its weights' kernel-private form written once (BF16 panels for the FP8 scales, the merged FP6 panel
+    for asymmetric power-of-two scales, nothing for symmetric ones): all four linear layers, the gated GEMM included,
+    must give the bits of the plain calls."""
     cfg = layer.LayerConfig(d_model=1024, n_heads=8, n_kv_heads=2, head_dim=128, d_ff=2816)
     w = synth.layer_weights(cfg, seed=0)
     x = G.to_dev_bf16(synth.layer_input(640, cfg.d_model, seed=0))
@@ -244,7 +245,7 @@ def test_decoder_layer_on_prepared_weights_gives_the_same_bits(scale, asym):
     wd = {k: (dev_f32(v) if v.dtype == np.float32 else G.to_dev_bf16(v)) for k, v in w.items()}
     plain = layer.DecoderLayer(cfg, wd, fmt, fused_attention=True).forward(x)
     lay = layer.DecoderLayer(cfg, wd, fmt, fused_attention=True, prepared_weights=True)
-    assert all((p.numel() > 0) == (scale != ref.E8M0_FLOOR) for p in lay.prepared.values())
+    assert all((p.numel() > 0) == (scale != ref.E8M0_FLOOR or asym == 1) for p in lay.prepared.values())
     prepared = lay.forward(x)
     torch.cuda.synchronize()
     assert torch.equal(plain.view(torch.int16), prepared.view(torch.int16))
