@@ -158,12 +158,12 @@ def other_workloads():
                                          "many_queries_kernel_us": d["many_queries_kernel_us"]}
     torch.cuda.empty_cache()
     lay = layer_bench.run(steps=5, formats=("amxfp4_e5m2", "amxfp4_e5m2[prepared_w]", "mxfp4_e5m2", "amxfp4_e8m0",
-                                            "mxfp4_e8m0"))
+                                            "amxfp4_e8m0[prepared_w]", "mxfp4_e8m0"))
     res["decoder_layer_8192_tokens"] = {
         name: {"ms_per_layer": f["ms_per_layer"], "matmul_TFLOPs": f["matmul_TFLOPs"],
                "mse_over_update": round(f["mse_over_update"], 5)} for name, f in lay["formats"].items()}
     res["decoder_layer_8192_tokens"]["note"] = ("fused attention; TFLOP/s over the 4.125 TFLOP the seven matmuls execute; "
-                                                "[prepared_w]: the weights' BF16 panels written once, not per call")
+                                                "[prepared_w]: the weights' kernel-private form (BF16 / FP6 panels) written once, not per call")
     torch.cuda.empty_cache()
     return res
 

@@ -167,22 +167,30 @@ __global__ __launch_bounds__(256) void fp6_plan_kernel(const uint8_t* __restrict
   const int64_t per = (G + 255) / 256, g0 = threadIdx.x * per, g1 = g0 + per < G ? g0 + per : G;
   uint32_t sum = 0;
   for (int64_t g = g0; g < g1; ++g) sum += (1u + (flags_of(g) & 1u)) * (1u + (flags_of(g) >> 1));
-  part[threadIdx.x] = sum;
+  // exclusive scan of the 256 partial sums: within each wave by lane shifts, then the four waves' totals (a serial
+  // scan by one thread is a chain of 256 dependent LDS accesses, 9 of this pass's 10 microseconds)
+  uint32_t incl = sum;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t up = __shfl_up(incl, d, 64);
+    if ((int)(threadIdx.x & 63) >= d) incl += up;
+  }
+  if ((threadIdx.x & 63) == 63) part[threadIdx.x >> 6] = incl;  // the wave's total
   __syncthreads();
-  if (threadIdx.x == 0) {  // 256 partial sums: a serial scan is plenty
-    uint32_t run = 0;
-    for (int t = 0; t < 256; ++t) {
-      const uint32_t v = part[t];
-      part[t] = run;
-      run += v;
-    }
-    pos[G] = run;
-    const uint32_t ks = (run + 1) / 2;
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (w < (int)(threadIdx.x >> 6)) before += part[w];
+    all += part[w];
+  }
+  if (threadIdx.x == 0) {
+    pos[G] = all;
+    const uint32_t ks = (all + 1) / 2;
     steps[0] = (ks + kFp6StepPad - 1) / kFp6StepPad * kFp6StepPad;
-    totals[0] = run, totals[1] = 2 * steps[0];
+    totals[0] = all, totals[1] = 2 * steps[0];
   }
   __syncthreads();
-  uint32_t run = part[threadIdx.x];
+  uint32_t run = before + incl - sum;
   const uint32_t* pos_b = reinterpret_cast<const uint32_t*>(prepared_plan);
   uint32_t* table = reinterpret_cast<uint32_t*>(plan + table_offset);
   for (int64_t g = g0; g < g1; ++g) {
