@@ -26,6 +26,12 @@
 // Panels: [row block of 32][K step][1536 bytes], rows padded to 256, K steps to a multiple of 12 with zero blocks.
 // Anchors: [row block][K step / 4][64 lanes] words, byte q of lane 32 h + r = block scale of (row r, 32-block h) in
 // K step 4 w + q.
+//
+// Static weights. B's panel as described depends on A (a position that A splits repeats B's group), so it is rebuilt on
+// every call. For weights that stay, the three passes run once on B alone: the panel then holds B's own blocks (one
+// per position, two where some row of B needs the split) and a call merges only A; its plan pass writes, per 32-block
+// of K', where in B's panel that block lies, the GEMM kernel's PREP variant fetches B's blocks through that table,
+// and a small pass puts B's anchors into the call's K' order. Same blocks in the same order: the same bits.
 #include "device_formats.h"
 #include "gemm_common.h"
 #include "kernels.h"
