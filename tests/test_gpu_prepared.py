@@ -19,7 +19,8 @@ FORMATS = [(ref.FP8_E5M2, 1, 32), (ref.FP8_E5M2, 0, 32), (ref.FP8_E4M3, 1, 16), 
 
 
 @pytest.mark.parametrize("scale,asym,gs", FORMATS)
-@pytest.mark.parametrize("M,N,K", [(600, 700, 1088), (300, 130, 192), (2048, 512, 4096), (32, 512, 512), (257, 64, 256)])
+@pytest.mark.parametrize("M,N,K", [(600, 700, 1088), (300, 130, 192), (2048, 512, 4096), (32, 512, 512), (257, 64, 256),
+                                   (300, 290, 32), (1100, 260, 448)])
 def test_prepared_product_is_the_plain_product(M, N, K, scale, asym, gs):
     """Shapes with partial tiles and K tails, a long K, few rows (the kernel that reads B as packed codes ignores the
     prepared form) and a format with nothing to prepare (symmetric power-of-two scales of 32-groups: zero bytes). The
