@@ -5,7 +5,10 @@
  * Formats (paper Sec. 2.1, Sec. 4.2 Eq. 1, Sec. 4.3, Appendix B Algorithm 1 and the table of MX-compliant formats):
  *   element   FP4 E2M1: 1 sign, 2 exponent (bias 1), 1 mantissa bit; magnitudes {0, .5, 1, 1.5, 2, 3, 4, 6}.
  *   group     `group_size` consecutive elements along the contraction axis K share the scale(s): 32 in MX and in
- *             the paper's format; 16, 64 and 128 are the other points of its group-size study (Sec. 5.3, Table 5).
+ *             the paper's format; 16, 64 and 128 are the other points of its group-size study (Sec. 5.3, Table 5);
+ *             -1 makes each row one group, as the code example of Appendix B does (there K / group_size reads 1).
+ *             The contiguous cast, the dequantization and the amxfp4_gemm* calls take -1; every other call
+ *             returns AMX_ERR_UNSUPPORTED for it.
  *   MXFP4     one scale S per group;            x_hat = (-1)^s * elem * S
  *   AMXFP4    two scales (S_p, S_n) per group;  x_hat = (-1)^s * elem * (s == 0 ? S_p : S_n)         (Eq. 1)
  *   scale     8 bits: E8M0 power of two (Algorithm 1, exponent floored), or FP8 E5M2 (Sec. 4.2 "FP8";
@@ -59,7 +62,7 @@ extern "C" {
 typedef enum {
   AMX_OK = 0,
   AMX_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, K not a multiple of the group, bad enum, misalignment */
-  AMX_ERR_UNSUPPORTED = -2, /* a legal format this GPU library does not implement (group_size not 16, 32, 64 or 128) */
+  AMX_ERR_UNSUPPORTED = -2, /* a legal format this GPU library, or this call, does not implement (e.g. group_size 8) */
   AMX_ERR_WORKSPACE = -3,   /* workspace missing or smaller than amxfp4_gemm_workspace_bytes() */
   AMX_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed */
 } amx_status_t;
@@ -76,7 +79,7 @@ typedef enum {
 } amx_scale_t;
 
 typedef struct {
-  int32_t group_size; /* elements per group along K: 16, 32 (Sec. 2.1), 64 or 128; must divide K */
+  int32_t group_size; /* elements per group along K: 16, 32 (Sec. 2.1), 64 or 128, dividing K; -1: the whole row */
   int32_t elem;       /* amx_elem_t */
   int32_t scale;      /* amx_scale_t */
   int32_t asymmetric; /* 1 = AMXFP4: sign-dependent scale pair (Eq. 1); 0 = MXFP4: one scale per group */
@@ -87,7 +90,8 @@ const char* amxfp4_last_error(void);
 
 /* Size in bytes of the packed code array for a [rows][K] operand: rows*K/2. 0 on invalid arguments. */
 size_t amxfp4_codes_bytes(const amx_format_t* fmt, int64_t rows, int64_t K);
-/* Size in bytes of the scale array: rows*(K/group_size)*(asymmetric ? 2 : 1). 0 on invalid arguments. */
+/* Size in bytes of the scale array: rows*(K/group_size)*(asymmetric ? 2 : 1), one group per row for group_size -1.
+ * 0 on invalid arguments. */
 size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K);
 /* Device scratch amxfp4_gemm needs for `batch` problems of shape M x N x K in this format (may be 0): operand panels
  * for the formats multiplied as 16-bit, FP6 or FP8 values, the re-laid scale bytes for the FP4 kernels. */
@@ -99,7 +103,7 @@ size_t amxfp4_gemm_workspace_bytes(const amx_format_t* fmt, int64_t M, int64_t N
  *               k_stride == 1 is the contiguous case (16-byte aligned base, row_stride % 8 == 0);
  *               row_stride == 1 with k_stride >= rows quantizes along a strided axis (groups run down a column,
  *               e.g. V in softmax(P).V, grouped along the key sequence).
- *   rows, K     operand shape; K % group_size == 0 and K % 32 == 0.
+ *   rows, K     operand shape; K % group_size == 0 and K % 32 == 0. Whole-row groups: contiguous case only.
  *   codes       device out, amxfp4_codes_bytes() bytes, 16-byte aligned.
  *   scales      device out, amxfp4_scales_bytes() bytes, 4-byte aligned.
  */

@@ -140,6 +140,11 @@ def make_format(scale=FP8_E5M2, asymmetric=True, group_size=32):
     return AmxFormat(int(group_size), 0, int(scale), int(bool(asymmetric)))
 
 
+def _groups(fmt, K):
+    """Groups along a row of K elements (group_size -1: the whole row is one group)."""
+    return 1 if fmt.group_size == -1 else K // fmt.group_size
+
+
 def codes_bytes(fmt, rows, K):
     return load().amxfp4_codes_bytes(ctypes.byref(fmt), rows, K)
 
@@ -233,7 +238,7 @@ def quantize(fmt, x, k_axis=-1, codes=None, scales=None, baseline=False, tensor_
     if codes is None:
         codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
     if scales is None:
-        shape = (rows, K // fmt.group_size, 2) if asym else (rows, K // fmt.group_size)
+        shape = (rows, _groups(fmt, K), 2) if asym else (rows, _groups(fmt, K))
         scales = torch.empty(shape, dtype=torch.uint8, device=x.device)
     if tensor_pair is not None:
         if baseline:
@@ -262,7 +267,7 @@ def quantize_batched(fmt, x, k_axis=-1, codes=None, scales=None):
     if codes is None:
         codes = torch.empty((batch, rows, K // 2), dtype=torch.uint8, device=x.device)
     if scales is None:
-        shape = (batch, rows, K // fmt.group_size, 2) if asym else (batch, rows, K // fmt.group_size)
+        shape = (batch, rows, _groups(fmt, K), 2) if asym else (batch, rows, _groups(fmt, K))
         scales = torch.empty(shape, dtype=torch.uint8, device=x.device)
     _check(load().amxfp4_quantize_batched(ctypes.byref(fmt), x.data_ptr(), batch, x.stride(0), rows, K, row_stride,
                                           k_stride, codes.data_ptr(), scales.data_ptr(), _stream()))
@@ -490,7 +495,7 @@ def rmsnorm_quantize(fmt, x, weight, eps, y=None):
     assert x.is_contiguous() and x.dtype == torch.bfloat16 and weight.dtype == torch.float32 and x.dim() == 2
     rows, dim = x.shape
     codes = torch.empty((rows, dim // 2), dtype=torch.uint8, device=x.device)
-    shape = (rows, dim // fmt.group_size, 2) if fmt.asymmetric else (rows, dim // fmt.group_size)
+    shape = (rows, _groups(fmt, dim), 2) if fmt.asymmetric else (rows, _groups(fmt, dim))
     scales = torch.empty(shape, dtype=torch.uint8, device=x.device)
     total = None
     if y is not None:

@@ -38,16 +38,23 @@ constexpr int64_t kMaxGemmRows = (int64_t(1) << 21) - 256;
 constexpr int64_t kMaxBatch = 65535;
 constexpr int64_t kMaxLdc = int64_t(1) << 22;  // the kernels address a wave's window of C with 32-bit byte offsets
 
-// Validates a format for the GPU library. Returns AMX_OK or a negative status (message set).
-int check_format(const amx_format_t* f) {
+// Validates a format for the GPU library. Returns AMX_OK or a negative status (message set). whole_row_ok: the caller
+// implements one group per row (group_size -1): the contiguous cast, the dequantization and the GEMM entry points.
+int check_format(const amx_format_t* f, bool whole_row_ok = false) {
   if (!f) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
   if (f->elem != AMX_ELEM_FP4_E2M1) return fail(AMX_ERR_INVALID_ARG, "unknown element format %d", f->elem);
   if (f->scale < AMX_SCALE_E8M0_FLOOR || f->scale > AMX_SCALE_FP8_E4M3)
     return fail(AMX_ERR_INVALID_ARG, "unknown scale format %d", f->scale);
   if (f->asymmetric != 0 && f->asymmetric != 1) return fail(AMX_ERR_INVALID_ARG, "asymmetric must be 0 or 1");
   if (f->group_size == 0 || f->group_size < -1) return fail(AMX_ERR_INVALID_ARG, "bad group_size %d", f->group_size);
+  if (f->group_size == -1) {
+    if (!whole_row_ok)
+      return fail(AMX_ERR_UNSUPPORTED, "whole-row groups (group_size -1) are implemented by the contiguous cast, the "
+                                       "dequantization and the GEMM entry points only");
+    return AMX_OK;
+  }
   if (f->group_size != 16 && f->group_size != 32 && f->group_size != 64 && f->group_size != 128)
-    return fail(AMX_ERR_UNSUPPORTED, "the GPU library implements group sizes 16, 32, 64 and 128 (got %d)",
+    return fail(AMX_ERR_UNSUPPORTED, "the GPU library implements group sizes 16, 32, 64, 128 and -1 (got %d)",
                 f->group_size);
   return AMX_OK;
 }
@@ -55,7 +62,7 @@ int check_format(const amx_format_t* f) {
 int check_shape(const amx_format_t& f, int64_t rows, int64_t K) {
   if (rows <= 0 || K <= 0) return fail(AMX_ERR_INVALID_ARG, "rows and K must be positive (got %lld, %lld)",
                                        (long long)rows, (long long)K);
-  if (K % f.group_size != 0 || K % 32 != 0)
+  if (!amx::group_divides(K, f.group_size) || K % 32 != 0)
     return fail(AMX_ERR_INVALID_ARG, "K = %lld is not a multiple of the group size %d and of 32", (long long)K,
                 f.group_size);
   // launch grids and 32-bit offsets inside the kernels are laid out for these bounds
@@ -105,7 +112,7 @@ namespace {
 int quantize_impl(amx_format_t f, const void* x, int64_t batch, int64_t batch_stride, int64_t rows, int64_t K,
                   int64_t row_stride, int64_t k_stride, const float* tensor_pair, uint8_t* codes, uint8_t* scales,
                   void* stream) {
-  if (int rc = check_format(&f)) return rc;
+  if (int rc = check_format(&f, k_stride == 1)) return rc;
   if (int rc = check_shape(f, rows, K)) return rc;
   if (batch < 1 || batch > kMaxBatch)
     return fail(AMX_ERR_INVALID_ARG, "batch = %lld outside 1 .. %lld", (long long)batch, (long long)kMaxBatch);
@@ -135,7 +142,7 @@ int quantize_impl(amx_format_t f, const void* x, int64_t batch, int64_t batch_st
 
 int dequantize_impl(amx_format_t f, const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
                     const float* tensor_pair, void* out, int32_t out_dtype, void* stream) {
-  if (int rc = check_format(&f)) return rc;
+  if (int rc = check_format(&f, true)) return rc;
   if (int rc = check_shape(f, rows, K)) return rc;
   if (!codes || !scales || !out) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
   if (out_dtype != 0 && out_dtype != 1) return fail(AMX_ERR_INVALID_ARG, "out_dtype must be 0 (f32) or 1 (bf16)");
@@ -222,7 +229,7 @@ int gemm_impl(amx_format_t f, const amx_gemm_options_t* opts, int64_t M, int64_t
               const float* B_pair, float* C, int64_t ldc, int64_t batch, void* workspace, size_t workspace_bytes,
               void* stream, const void* B_panel = nullptr) {
   const bool scaled = A_pair != nullptr;
-  if (int rc = check_format(&f)) return rc;
+  if (int rc = check_format(&f, true)) return rc;
   if (int rc = check_options(opts)) return rc;
   if (int rc = check_shape(f, M, K)) return rc;
   if (N <= 0 || batch <= 0) return fail(AMX_ERR_INVALID_ARG, "N and batch must be positive");
@@ -316,8 +323,9 @@ size_t amxfp4_codes_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
 }
 
 size_t amxfp4_scales_bytes(const amx_format_t* fmt, int64_t rows, int64_t K) {
-  if (!fmt || rows <= 0 || K <= 0 || fmt->group_size <= 0 || K % fmt->group_size) return 0;
-  return (size_t)(rows * (K / fmt->group_size) * (fmt->asymmetric ? 2 : 1));
+  if (!fmt || rows <= 0 || K <= 0 || !amx::group_divides(K, fmt->group_size)) return 0;
+  const int64_t groups = fmt->group_size == -1 ? 1 : K / fmt->group_size;
+  return (size_t)(rows * groups * (fmt->asymmetric ? 2 : 1));
 }
 
 size_t amxfp4_gemm_workspace_bytes_ex(const amx_format_t* fmt, const amx_gemm_options_t* opts, int64_t M, int64_t N,
@@ -486,7 +494,7 @@ int amxfp4_gemm_ex(const amx_format_t* fmt, const amx_gemm_options_t* opts, int6
 // asymmetric power-of-two format has B's merged FP6 panel, anchors and plan written once; the symmetric power-of-two
 // format's kernel reads the codes as they are.
 size_t amxfp4_weights_prepared_bytes(const amx_format_t* fmt, int64_t N, int64_t K) {
-  if (!fmt || N <= 0 || K <= 0 || check_format(fmt) != AMX_OK || K % fmt->group_size != 0) return 0;
+  if (!fmt || N <= 0 || K <= 0 || check_format(fmt, true) != AMX_OK || !amx::group_divides(K, fmt->group_size)) return 0;
   const bool pot32 = fmt->group_size == 32 && (fmt->scale == AMX_SCALE_E8M0_FLOOR || fmt->scale == AMX_SCALE_E8M0_ROUND);
   if (!pot32) return amx::bf16_panel_bytes(N, K);
   return fmt->asymmetric && amx::fp6m_path_supported(1, N, K) ? amx::fp6m_prepared_bytes(N, K) : 0;
@@ -495,7 +503,7 @@ size_t amxfp4_weights_prepared_bytes(const amx_format_t* fmt, int64_t N, int64_t
 int amxfp4_prepare_weights(const amx_format_t* fmt, int64_t N, int64_t K, const uint8_t* B_codes,
                            const uint8_t* B_scales, void* prepared, size_t prepared_bytes, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  if (int rc = check_format(fmt)) return rc;
+  if (int rc = check_format(fmt, true)) return rc;
   if (int rc = check_shape(*fmt, N, K)) return rc;
   if (N > kMaxGemmRows) return fail(AMX_ERR_INVALID_ARG, "N may be at most %lld", (long long)kMaxGemmRows);
   if (!B_codes || !B_scales) return fail(AMX_ERR_INVALID_ARG, "NULL data pointer");
@@ -528,7 +536,7 @@ int amxfp4_gemm_prepared(const amx_format_t* fmt, int64_t M, int64_t N, int64_t 
                          size_t prepared_bytes, float* C, int64_t ldc, void* workspace, size_t workspace_bytes,
                          void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
-  if (int rc = check_format(fmt)) return rc;
+  if (int rc = check_format(fmt, true)) return rc;
   const size_t need = N > 0 && K > 0 ? amxfp4_weights_prepared_bytes(fmt, N, K) : 0;
   if (need > 0) {
     if (!prepared || prepared_bytes < need)
@@ -544,7 +552,7 @@ int amxfp4_gemm_static(const amx_format_t* fmt, int64_t M, int64_t N, int64_t K,
                        int64_t batch, void* stream) {
   if (!fmt) return fail(AMX_ERR_INVALID_ARG, "fmt is NULL");
   // the size check comes first, on the host, from the same plan amxfp4_gemm would follow
-  if (int rc = check_format(fmt)) return rc;
+  if (int rc = check_format(fmt, true)) return rc;
   if (int rc = check_shape(*fmt, M, K)) return rc;
   if (N <= 0 || batch <= 0 || M > kMaxGemmRows || N > kMaxGemmRows || batch > kMaxBatch)
     return fail(AMX_ERR_INVALID_ARG, "N and batch must be positive and M, N, batch within the limits of amxfp4_gemm");

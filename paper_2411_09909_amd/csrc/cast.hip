@@ -17,6 +17,7 @@
 //     which keeps it on the right side of every E2M1 boundary (see quotient()), and rounded to E2M1 by the hardware
 //     conversion v_cvt_scalef32_pk_fp4_f32.
 // Strided cast (groups down a column, for V in P.V): one lane per (row, group), the same arithmetic.
+// Whole-row groups (group size -1, as in the code example of Appendix B): one thread block per row, two sweeps.
 #include "cast_core.h"
 #include "device_formats.h"
 
@@ -126,6 +127,80 @@ __global__ __launch_bounds__(256) void quantize_contig_kernel(const uint16_t* __
       *reinterpret_cast<uint16_t*>(scales + g * 2) = (uint16_t)(sb_p | (sb_n << 8));
     else
       scales[g] = (uint8_t)sb_p;
+  }
+}
+
+// One group per row (the code example of Appendix B casts its tensor this way). One thread block per (row, batch
+// entry); a lane owns the 8-element chunks threadIdx.x, threadIdx.x + blockDim.x, ... of the row. First sweep: per
+// class extrema of the lane's chunks, reduced over the wave with lane exchanges and over the block's waves through
+// LDS. Second sweep (the row then comes from the cache): the element step of the grouped casts with the row's
+// scale(s). TENSOR_SCALED as in quantize_contig_kernel.
+template <int SCALE_KIND, bool ASYM, bool TENSOR_SCALED>
+__global__ __launch_bounds__(256) void quantize_row_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t K,
+                                                           int64_t row_stride, int64_t batch_stride,
+                                                           const float* __restrict__ tensor_pair,
+                                                           uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+  __shared__ uint32_t wave_max[2][4];
+  const int64_t r = blockIdx.x, out_row = (int64_t)blockIdx.y * rows + r;
+  const uint4* src = reinterpret_cast<const uint4*>(x + (int64_t)blockIdx.y * batch_stride + r * row_stride);
+  const int chunks = (int)(K >> 3), lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+  float rt = 1.0f;
+  if constexpr (TENSOR_SCALED) rt = tensor_pair[1];
+  // largest magnitude per sign class, as FP32 bit patterns (non-negative floats order like integers)
+  uint32_t amax_p = 0, amax_n = 0;
+  for (int c = threadIdx.x; c < chunks; c += blockDim.x) {
+    const uint4 v = src[c];
+    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+    float y[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) y[2 * j] = u2f(d[j] << 16) * rt, y[2 * j + 1] = u2f(d[j] & 0xFFFF0000u) * rt;
+    uint32_t p, n;
+    class_extrema<ASYM>(y, p, n);
+    amax_p = p > amax_p ? p : amax_p;
+    amax_n = n > amax_n ? n : amax_n;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint32_t p = __shfl_xor(amax_p, o), n = __shfl_xor(amax_n, o);
+    amax_p = p > amax_p ? p : amax_p;
+    amax_n = n > amax_n ? n : amax_n;
+  }
+  if (lane == 0) wave_max[0][wave] = amax_p, wave_max[1][wave] = amax_n;
+  __syncthreads();
+  for (int w = 0; w < waves; ++w) {
+    const uint32_t p = wave_max[0][w], n = wave_max[1][w];
+    amax_p = p > amax_p ? p : amax_p;
+    amax_n = n > amax_n ? n : amax_n;
+  }
+  float s_pos = 0.f, r_pos, s_neg = 0.f, r_neg;
+  uint32_t sb_p, sb_n;
+  if constexpr (TENSOR_SCALED) {
+    sb_p = encode_scale_sr<SCALE_KIND>(u2f(amax_p), s_pos, r_pos);
+    sb_n = sb_p, s_neg = s_pos, r_neg = r_pos;
+    if constexpr (ASYM) sb_n = encode_scale_sr<SCALE_KIND>(u2f(amax_n), s_neg, r_neg);
+  } else {
+    sb_p = encode_scale_r_bf16<SCALE_KIND>(u2f(amax_p), r_pos);
+    sb_n = sb_p, r_neg = r_pos;
+    if constexpr (ASYM) sb_n = encode_scale_r_bf16<SCALE_KIND>(u2f(amax_n), r_neg);
+  }
+  if (threadIdx.x == 0) {
+    if constexpr (ASYM)
+      scales[out_row * 2] = (uint8_t)sb_p, scales[out_row * 2 + 1] = (uint8_t)sb_n;
+    else
+      scales[out_row] = (uint8_t)sb_p;
+  }
+  uint32_t* dst = reinterpret_cast<uint32_t*>(codes + out_row * (K >> 1));
+  for (int c = threadIdx.x; c < chunks; c += blockDim.x) {
+    const uint4 v = src[c];
+    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+    if constexpr (TENSOR_SCALED) {
+      float y[8];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) y[2 * j] = u2f(d[j] << 16) * rt, y[2 * j + 1] = u2f(d[j] & 0xFFFF0000u) * rt;
+      dst[c] = encode8<SCALE_KIND, ASYM>(y, s_pos, r_pos, s_neg, r_neg);
+    } else {
+      dst[c] = encode8_bf16<ASYM>(d, r_pos, r_neg);
+    }
   }
 }
 
@@ -240,7 +315,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t* __restri
     const int64_t r = c / chunks_per_row;
     const int64_t cc = c - r * chunks_per_row;
     const uint32_t w = *reinterpret_cast<const uint32_t*>(codes + r * (K >> 1) + cc * 4);
-    const int64_t g = r * (K >> gs_log2) + ((cc * 8) >> gs_log2);
+    const int64_t g = r * groups_per_row(K, gs_log2) + ((cc * 8) >> gs_log2);
     float s_pos, s_neg;
     if constexpr (ASYM) {
       const uint32_t sb = *reinterpret_cast<const uint16_t*>(scales + g * 2);
@@ -276,8 +351,6 @@ static int grid_for(int64_t total_threads) {
   return (int)(blocks < cap ? blocks : cap);
 }
 
-// log2 of a supported group size (16, 32, 64, 128), else -1
-static int group_log2(int64_t gs) { return gs == 16 ? 4 : gs == 32 ? 5 : gs == 64 ? 6 : gs == 128 ? 7 : -1; }
 
 template <int SK, bool ASYM>
 static hipError_t launch_qc(const uint16_t* x, int64_t rows, int64_t K, int gs_log2, int64_t row_stride,
@@ -322,7 +395,20 @@ hipError_t launch_quantize_contig(int scale_kind, bool asym, int64_t group_size,
                                   int64_t K, int64_t row_stride, int64_t batch, int64_t batch_stride,
                                   const float* tensor_pair, uint8_t* codes, uint8_t* scales, hipStream_t s) {
   const int gl = group_log2(group_size);
-  if (gl < 0 || K % group_size != 0) return hipErrorInvalidValue;
+  if (gl < 0 || !group_divides(K, group_size)) return hipErrorInvalidValue;
+  if (gl == kWholeRowLog2) {
+    // one wave per short row (up to 8 chunks a lane), four waves beyond
+    const dim3 grid((unsigned)rows, (unsigned)batch), block(K <= 4096 ? 64 : 256);
+    return for_format(scale_kind, asym, [&]<int SK, bool ASYM>() {
+      if (tensor_pair)
+        hipLaunchKernelGGL((quantize_row_kernel<SK, ASYM, true>), grid, block, 0, s, x, rows, K, row_stride,
+                           batch_stride, tensor_pair, codes, scales);
+      else
+        hipLaunchKernelGGL((quantize_row_kernel<SK, ASYM, false>), grid, block, 0, s, x, rows, K, row_stride,
+                           batch_stride, tensor_pair, codes, scales);
+      return hipGetLastError();
+    });
+  }
   return for_format(scale_kind, asym, [&]<int SK, bool ASYM>() {
     return launch_qc<SK, ASYM>(x, rows, K, gl, row_stride, batch, batch_stride, tensor_pair, codes, scales, s);
   });
@@ -346,7 +432,7 @@ hipError_t launch_quantize_strided(int scale_kind, bool asym, int64_t group_size
                                    int64_t K, int64_t k_stride, int64_t batch, int64_t batch_stride,
                                    const float* tensor_pair, uint8_t* codes, uint8_t* scales, hipStream_t s) {
   const int gl = group_log2(group_size);
-  if (gl < 0 || K % group_size != 0) return hipErrorInvalidValue;
+  if (gl < 0 || gl == kWholeRowLog2 || K % group_size != 0) return hipErrorInvalidValue;
   return for_format(scale_kind, asym, [&]<int SK, bool ASYM>() {
     switch (gl) {
       case 4: return launch_qs<SK, ASYM, 16>(x, rows, K, k_stride, batch, batch_stride, tensor_pair, codes, scales, s);
@@ -374,7 +460,7 @@ hipError_t launch_dequantize(int scale_kind, bool asym, int64_t group_size, cons
                              const uint8_t* scales, int64_t rows, int64_t K, const float* tensor_pair, void* out,
                              int out_dtype, hipStream_t s) {
   const int gl = group_log2(group_size);
-  if (gl < 0 || K % group_size != 0) return hipErrorInvalidValue;
+  if (gl < 0 || !group_divides(K, group_size)) return hipErrorInvalidValue;
   // E8M0 floor and round share the byte encoding
   return for_format(scale_kind == kScaleE8M0Round ? kScaleE8M0Floor : scale_kind, asym, [&]<int SK, bool ASYM>() {
     return launch_dq<SK, ASYM>(codes, scales, rows, K, gl, tensor_pair, out, out_dtype, s);

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void expand_kernel(const uint8_t* __restrict__
   if (r < R && g < (K >> 5)) {
     const uint4 c = *reinterpret_cast<const uint4*>(codes + (b * R + r) * (K >> 1) + g * 16);
     w[0] = c.x, w[1] = c.y, w[2] = c.z, w[3] = c.w;
-    const int64_t row_groups = (b * R + r) * (K >> gs_log2);
+    const int64_t row_groups = (b * R + r) * groups_per_row(K, gs_log2);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       if (h == 1 && gs_log2 != 4) {
@@ -297,8 +297,8 @@ static hipError_t expand_dispatch(int scale_kind, bool asym, int gs_log2, const 
 hipError_t launch_expand_bf16(int scale_kind, bool asym, int64_t group_size, const uint8_t* codes,
                               const uint8_t* scales, int64_t R, int64_t K, int64_t Rp, int64_t Kp, int64_t batch,
                               bool permute, uint16_t* panel, hipStream_t s) {
-  const int gs_log2 = group_size == 16 ? 4 : group_size == 32 ? 5 : group_size == 64 ? 6 : group_size == 128 ? 7 : -1;
-  if (gs_log2 < 0 || K % group_size != 0 || K % 32 != 0 || Rp % 32 != 0 || Kp % 64 != 0) return hipErrorInvalidValue;
+  const int gs_log2 = group_log2(group_size);
+  if (gs_log2 < 0 || !group_divides(K, group_size) || K % 32 != 0 || Rp % 32 != 0 || Kp % 64 != 0) return hipErrorInvalidValue;
   if (!permute) return expand_dispatch(scale_kind, asym, gs_log2, codes, scales, R, K, Rp, Kp, batch, panel, s);
   const dim3 grid((unsigned)((Kp + 255) / 256), (unsigned)(Rp / 32), (unsigned)batch);
   auto go = [&]<int SK, bool ASYM>() {
@@ -360,8 +360,8 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
                                  const uint8_t* B_scales, const float* A_tensor_pair, const float* B_tensor_pair,
                                  float* C, int64_t ldc, int64_t batch, void* workspace, int tile, hipStream_t s,
                                  const KernelTimer& timer, bool glu, const void* B_panel) {
-  const int gs_log2 = group_size == 16 ? 4 : group_size == 32 ? 5 : group_size == 64 ? 6 : group_size == 128 ? 7 : -1;
-  if (gs_log2 < 0 || K % group_size != 0 || K % 32 != 0) return hipErrorInvalidValue;
+  const int gs_log2 = group_log2(group_size);
+  if (gs_log2 < 0 || !group_divides(K, group_size) || K % 32 != 0) return hipErrorInvalidValue;
   const int64_t Mp = round_up(M, kPanelRows), Np = round_up(N, kPanelRows), Kp = round_up(K, kPanelK);
   uint16_t* Ap = reinterpret_cast<uint16_t*>(workspace);
   const uint16_t* Bp = B_panel ? reinterpret_cast<const uint16_t*>(B_panel) : Ap + batch * Mp * Kp;
@@ -400,8 +400,8 @@ hipError_t launch_gemm_bf16_path(int scale_kind, bool asym, int64_t group_size, 
 
 hipError_t launch_expand_b_panel(int scale_kind, bool asym, int64_t group_size, int64_t N, int64_t K,
                                  const uint8_t* B_codes, const uint8_t* B_scales, void* panel, hipStream_t s) {
-  const int gs_log2 = group_size == 16 ? 4 : group_size == 32 ? 5 : group_size == 64 ? 6 : group_size == 128 ? 7 : -1;
-  if (gs_log2 < 0 || K % group_size != 0 || K % 32 != 0) return hipErrorInvalidValue;
+  const int gs_log2 = group_log2(group_size);
+  if (gs_log2 < 0 || !group_divides(K, group_size) || K % 32 != 0) return hipErrorInvalidValue;
   return expand_dispatch(scale_kind, asym, gs_log2, B_codes, B_scales, N, K, round_up(N, kPanelRows), round_up(K, kPanelK),
                          1, reinterpret_cast<uint16_t*>(panel), s);
 }

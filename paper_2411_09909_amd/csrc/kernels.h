@@ -16,11 +16,25 @@ constexpr int kPanelK = 128;
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 
+// Group sizes (Sec. 2.1; the code example of Appendix B uses one group per row, written as group size -1). Kernels
+// take log2 of the size and find an element's group with a shift; a whole-row group is the shift kWholeRowLog2,
+// which sends every element index below 2^31 to group 0.
+constexpr int kWholeRowLog2 = 31;
+// log2 of a supported group size (16, 32, 64, 128), kWholeRowLog2 for -1, else -1
+inline int group_log2(int64_t gs) {
+  return gs == 16 ? 4 : gs == 32 ? 5 : gs == 64 ? 6 : gs == 128 ? 7 : gs == -1 ? kWholeRowLog2 : -1;
+}
+inline bool group_divides(int64_t K, int64_t gs) { return gs == -1 || (gs > 0 && K % gs == 0); }
+// groups in a row of K elements
+__host__ __device__ inline int64_t groups_per_row(int64_t K, int gs_log2) {
+  return gs_log2 == kWholeRowLog2 ? 1 : K >> gs_log2;
+}
+
 // api.hip: status reporting shared by all entry points (thread-local message behind amxfp4_last_error)
 int report_error(int code, const char* msg);
 int report_hip_error(hipError_t e, const char* what);
 
-// cast.hip (group_size: 16, 32, 64 or 128, dividing K; tensor_pair: device {S_t, 1 / S_t} of a tensor-wise scale,
+// cast.hip (group_size: 16, 32, 64 or 128, dividing K, or -1 for whole rows, contiguous rows only; tensor_pair: device {S_t, 1 / S_t} of a tensor-wise scale,
 // or null for none; batch operands batch_stride elements apart, their outputs packed one after the other)
 hipError_t launch_quantize_contig(int scale_kind, bool asym, int64_t group_size, const uint16_t* x, int64_t rows,
                                   int64_t K, int64_t row_stride, int64_t batch, int64_t batch_stride,

@@ -125,14 +125,18 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert _q(lib, ok, p, 4, 64, 64, 1, ctypes.c_void_p(0x1001), p) == -1   # misaligned codes
     assert _q(lib, ok, p, 4, 64, 3, 2, p, p) == -1           # unsupported stride combination
     assert b"stride" in lib.amxfp4_last_error()
-    for bad, code in [(binding.AmxFormat(8, 0, 2, 1), -2), (binding.AmxFormat(-1, 0, 3, 1), -2),
-                      (binding.AmxFormat(48, 0, 2, 1), -2), (binding.AmxFormat(-2, 0, 2, 1), -1),
+    for bad, code in [(binding.AmxFormat(8, 0, 2, 1), -2), (binding.AmxFormat(48, 0, 2, 1), -2),
+                      (binding.AmxFormat(-2, 0, 2, 1), -1),
                       (binding.AmxFormat(32, 1, 2, 1), -1), (binding.AmxFormat(32, 0, 7, 1), -1),
                       (binding.AmxFormat(0, 0, 2, 1), -1), (binding.AmxFormat(32, 0, 2, 5), -1)]:
         assert _q(lib, bad, p, 4, 64, 64, 1, p, p) == code
     assert _q(lib, binding.AmxFormat(128, 0, 2, 1), p, 4, 64, 64, 1, p, p) == -1   # K smaller than one group of 128
     assert _q(lib, binding.AmxFormat(16, 0, 2, 1), p, 4, 48, 48, 1, p, p) == -1    # whole groups of 16, but K % 32 != 0
     assert lib.amxfp4_quantize(None, p, 4, 64, 64, 1, p, p, None) == -1
+    # one group per row: along contiguous rows only
+    whole = binding.AmxFormat(-1, 0, 2, 1)
+    assert _q(lib, whole, p, 4, 64, 1, 4, p, p) == -2 and b"whole-row" in lib.amxfp4_last_error()
+    assert lib.amxfp4_scales_bytes(ctypes.byref(whole), 5, 96) == 10
     # size limits: K, rows of a cast, M / N / batch of a GEMM
     big_k = (1 << 20) + 32
     assert _q(lib, ok, p, 4, big_k, big_k, 1, p, p) == -1 and b"maximum" in lib.amxfp4_last_error()
