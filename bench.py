@@ -352,12 +352,48 @@ def main():
                 "weights": round(per_elem(N) / t_w / 1e9, 1), "weights_us": round(t_w * 1e6, 1),
                 "frac_of_hbm_peak": round(per_elem(M) / t_hbm / 1e9 / 8000.0, 4)}
 
-    # The reference measurements come first: the register-resident MFMA loops and the streaming copy, then the cast's
-    # bandwidth. They also leave the chip in the state it holds under sustained load (its power management takes
-    # about 0.1 s of work to settle, and the settled state is the faster one), so a short run (--steps 20 --warmup 5)
-    # times the same kernels a long one does. The warm-up and timed steps of the headline follow, unchanged.
+    # The reference measurements come first: the register-resident MFMA loops and the streaming copy, the cast's
+    # bandwidth, then the other formats' steps. They also leave the chip in the state it holds under sustained load
+    # (its power management takes about 0.1 s of such work to settle, and the settled state is the faster one: in a
+    # run with --steps 20 --warmup 5 the same GEMM kernel took 1.335 ms when the headline came before the other
+    # formats and 1.302 ms right after), so a short run times what a long one does. The warm-up and timed steps of
+    # the headline follow, unchanged.
     peaks = None if args.no_measured_peaks else measured_peaks(binding, torch, xd, wd, dev)
     cast_bw = None if args.no_cast_bandwidth else cast_bandwidth(args.format)
+    # The formats that run on the block-scaled matrix instructions are part of every run (about ten steps each): OCP
+    # MXFP4 and the asymmetric power-of-two format, each with its GEMM kernel's time and fraction of the peak of the
+    # MFMA type it issues. --variants adds the rest.
+    cases = [("mxfp4_e8m0", "panel", "merged_fp6", False), ("amxfp4_e8m0", "panel", "merged_fp6", False),
+             ("amxfp4_e8m0", "panel", "merged_fp6", True),   # B's merged FP6 panel written once
+             ("amxfp4_e8m0", "panel", "merged_fp8", False), ("amxfp4_e8m0", "panel", "split", False)]
+    if args.format not in DOUBLE_SCALED and FORMATS[args.format][2] == "bf16":
+        # the headline format against weights whose BF16 expansion was written once (amxfp4_gemm_prepared): the step
+        # then expands only X; costs 2 bytes per weight element of extra memory
+        cases.append((args.format, "panel", "merged_fp6", True))
+    if args.variants:
+        cases += [(name, "panel", "merged_fp6", False) for name in sorted(FORMATS) if name not in ("mxfp4_e8m0", "amxfp4_e8m0")]
+        cases += [(name, k, "merged_fp6", False) for name in ("amxfp4_e5m2", "mxfp4_e5m2") for k in ("hybrid", "fused")]
+    if args.no_variants or args.group_size != 32:
+        cases = []
+    v_steps = max(3, min(args.steps, 10)) if not args.variants else max(3, args.steps // 2)
+    v_warm = max(2, min(args.warmup, 5)) if not args.variants else max(2, args.warmup // 2)
+    variants = {}
+    for name, kern, pot, prep in cases:
+        if name == args.format and kern == args.e5m2_kernel and pot == args.pot_kernel and not prep:
+            continue
+        # (the first of them is where the chip goes from register loops and casts to sustained GEMM load: it gets
+        # the warm-up steps that takes)
+        v = run_format(name, v_steps, v_warm if variants else max(v_warm, 40), kern, pot, prep)
+        label = (name + ("[%s]" % kern if kern != "panel" else "") + ("[%s]" % pot if pot != "merged_fp6" else "")
+                 + ("[prepared_w]" if prep else ""))
+        variants[label] = {
+            "value": round(flops / v["t_step"] / 1e12, 2), "unit": "TFLOP/s",
+            "frac_of_fp4_mfma_peak": round(flops / v["t_step"] / 1e12 / PEAK_FP4_TFLOPS, 4),
+            "ms_per_step": round(v["t_step"] * 1e3, 4), "steps": v_steps, "mfma": v["mfma"],
+            "workspace_MB": round(v["workspace_bytes"] / 1e6, 1), "prepared_weights_MB": round(v["prepared_bytes"] / 1e6, 1),
+            "gemm_kernel_ms": round(v["kern_ms"], 4),
+            "kernel_frac_of_mfma_peak": round(flops / (v["kern_ms"] * 1e-3) / 1e12 / v["peak"], 4),
+            "kernel_traffic_bytes": MEASURED_TRAFFIC_VARIANTS.get(label) if args.workload == WORKLOAD else None}
     r = run_format(args.format, args.steps, args.warmup, args.e5m2_kernel, args.pot_kernel)
     ms_per_step = r["t_step"] * 1e3
     value = flops / r["t_step"] / 1e12
@@ -407,37 +443,8 @@ def main():
     }
     if cast_bw is not None:
         out["cast_bandwidth"] = cast_bw
-    # The formats that run on the block-scaled matrix instructions are part of every run (about ten steps each): OCP
-    # MXFP4 and the asymmetric power-of-two format, each with its GEMM kernel's time and fraction of the peak of the
-    # MFMA type it issues. --variants adds the rest.
-    cases = [("mxfp4_e8m0", "panel", "merged_fp6", False), ("amxfp4_e8m0", "panel", "merged_fp6", False),
-             ("amxfp4_e8m0", "panel", "merged_fp6", True),   # B's merged FP6 panel written once
-             ("amxfp4_e8m0", "panel", "merged_fp8", False), ("amxfp4_e8m0", "panel", "split", False)]
-    if args.format not in DOUBLE_SCALED and FORMATS[args.format][2] == "bf16":
-        # the headline format against weights whose BF16 expansion was written once (amxfp4_gemm_prepared): the step
-        # then expands only X; costs 2 bytes per weight element of extra memory
-        cases.insert(0, (args.format, "panel", "merged_fp6", True))
-    if args.variants:
-        cases += [(name, "panel", "merged_fp6", False) for name in sorted(FORMATS) if name not in ("mxfp4_e8m0", "amxfp4_e8m0")]
-        cases += [(name, k, "merged_fp6", False) for name in ("amxfp4_e5m2", "mxfp4_e5m2") for k in ("hybrid", "fused")]
-    if args.no_variants or args.group_size != 32:
-        cases = []
-    v_steps = max(3, min(args.steps, 10)) if not args.variants else max(3, args.steps // 2)
-    v_warm = max(2, min(args.warmup, 5)) if not args.variants else max(2, args.warmup // 2)
-    for name, kern, pot, prep in cases:
-        if name == args.format and kern == args.e5m2_kernel and pot == args.pot_kernel and not prep:
-            continue
-        v = run_format(name, v_steps, v_warm, kern, pot, prep)
-        label = (name + ("[%s]" % kern if kern != "panel" else "") + ("[%s]" % pot if pot != "merged_fp6" else "")
-                 + ("[prepared_w]" if prep else ""))
-        out.setdefault("variants", {})[label] = {
-            "value": round(flops / v["t_step"] / 1e12, 2), "unit": "TFLOP/s",
-            "frac_of_fp4_mfma_peak": round(flops / v["t_step"] / 1e12 / PEAK_FP4_TFLOPS, 4),
-            "ms_per_step": round(v["t_step"] * 1e3, 4), "steps": v_steps, "mfma": v["mfma"],
-            "workspace_MB": round(v["workspace_bytes"] / 1e6, 1), "prepared_weights_MB": round(v["prepared_bytes"] / 1e6, 1),
-            "gemm_kernel_ms": round(v["kern_ms"], 4),
-            "kernel_frac_of_mfma_peak": round(flops / (v["kern_ms"] * 1e-3) / 1e12 / v["peak"], 4),
-            "kernel_traffic_bytes": MEASURED_TRAFFIC_VARIANTS.get(label) if args.workload == WORKLOAD else None}
+    if variants:
+        out["variants"] = variants
     if not (args.no_workloads or args.no_variants or args.workload != WORKLOAD):
         out["workloads"] = other_workloads()
     if peaks is not None:
