@@ -157,6 +157,10 @@ def other_workloads():
     res["decode_1_token_x_8192_keys"] = {"format": d["format"], "cache_MB": d["cache_MB"], "decode_us": d["decode"],
                                          "many_queries_kernel_us": d["many_queries_kernel_us"]}
     torch.cuda.empty_cache()
+    d = decode_bench.run(batch=16, steps=20, splits=(16, 32))
+    res["decode_16_sequences_x_8192_keys"] = {"format": d["format"], "cache_MB": d["cache_MB"], "decode_us": d["decode"],
+                                              "many_queries_kernel_us": d["many_queries_kernel_us"]}
+    torch.cuda.empty_cache()
     lay = layer_bench.run(steps=5, formats=("amxfp4_e5m2", "amxfp4_e5m2[prepared_w]", "mxfp4_e5m2", "amxfp4_e8m0",
                                             "amxfp4_e8m0[prepared_w]", "mxfp4_e8m0"))
     res["decoder_layer_8192_tokens"] = {

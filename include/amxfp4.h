@@ -290,6 +290,8 @@ int amxfp4_attention_merged(const amx_format_t* fmt, int64_t q_heads, int64_t kv
  *   limits     (q_heads / kv_heads) * Sq <= 32 (AMX_ERR_UNSUPPORTED beyond: use amxfp4_attention); group_size 32;
  *              head_dim 128 or 64; 1 <= key_splits <= min(1024, Sk / 32); kv_heads <= 65535. A batch of sequences of
  *              equal length is a larger number of heads.
+ *   speed      with Sk % 256 == 0 a wave fetches V in chunks of 8 key tiles; ranges of whole chunks (key_splits
+ *              dividing Sk / 256) read every byte of V once.
  *   workspace  at least amxfp4_attention_decode_workspace_bytes() bytes, 256-byte aligned (the ranges' partial results:
  *              kv_heads * key_splits * 32 * (head_dim + 2) floats).
  * Other arguments, layouts and status codes as amxfp4_attention; out is FP32 [q_heads][Sq][head_dim].

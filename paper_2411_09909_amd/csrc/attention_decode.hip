@@ -118,12 +118,23 @@ constexpr int kDecodeCols = 32;  // query columns of a wave
 // grid: (key_splits, kv_heads); block: one wave. part: [kv_heads][32 columns][key_splits][D + 2] floats: the
 // un-normalised O of the column in that range, then its running maximum (log2 units) and its sum; only the columns
 // that hold a query are written.
-template <int SCALE_KIND, bool ASYM, int D>
-__global__ __launch_bounds__(64) void attention_decode_kernel(
+//
+// CHUNKED (Sk % 256 == 0): V^T rows are contiguous along the keys, so a key tile is 16 bytes of each of the D rows, one
+// eighth of a cache line per row, and a wave that fetched them tile by tile would request every line of V eight times
+// (and every line of V's scale bytes as often). The wave instead brings V in chunks of 8 key tiles: whole 128-byte
+// lines of all D rows by direct-to-LDS loads (8 rows x 128 bytes per load; the 16-byte piece of tile j of row r goes to
+// slot j ^ ((r >> 1) & 7) of the row's line in LDS, so that the 32 rows a tile read touches spread over the banks), and
+// the chunk's scale bytes as D rows of 4-byte words. One chunk of LDS per wave, refilled when the wave has finished
+// the previous chunk (its other wave on the SIMD works meanwhile); no barrier: a wave reads only what it loaded.
+template <int SCALE_KIND, bool ASYM, int D, bool CHUNKED>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attention_decode_kernel(
     const uint8_t* __restrict__ Qc, const uint8_t* __restrict__ Qs, const uint8_t* __restrict__ Kc,
     const uint8_t* __restrict__ Ks, const uint8_t* __restrict__ Vc, const uint8_t* __restrict__ Vs,
     float* __restrict__ part, int Sq, int Sk, int per, int tiles_per_split, float scale_log2, int causal) {
   constexpr int kSteps = D / 16, kRowBlocks = D / 32;
+  constexpr int kScaleParts = ASYM ? 4 : 2;  // 4-byte words of scale bytes a row has per chunk of 8 tiles
+  __shared__ __attribute__((aligned(1024))) uint8_t v_lines[CHUNKED ? D * 128 : 16];
+  __shared__ __attribute__((aligned(256))) uint8_t v_scale_words[CHUNKED ? kScaleParts * D * 4 : 16];
   const int lane = threadIdx.x & 63, col = lane & 31, h = lane >> 5;
   const int split = (int)blockIdx.x, nsplits = (int)gridDim.x, g = (int)blockIdx.y;
   const int off = Sk - Sq;
@@ -165,23 +176,67 @@ __global__ __launch_bounds__(64) void attention_decode_kernel(
   // 4 h + 8 .. 4 h + 11 of each 16
   const uint32_t pick = h ? 0x07060302u : 0x05040100u;
 
+  // CHUNKED: this head's V^T codes and scale bytes as raw buffers (reads past the end return zeros), and the lane's
+  // share of a load of 8 rows x 128 bytes: row L / 8 of the eight, the piece that belongs in slot L % 8
+  const int v_row_bytes = Sk >> 1, vs_row_bytes = (Sk >> 5) * (ASYM ? 2 : 1);
+  // (the addresses are the same in every lane; said explicitly, or the descriptors end up in vector registers and
+  // every load in a loop over their distinct values)
+  auto uniform_ptr = [](const uint8_t* p) {
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    return reinterpret_cast<uint8_t*>(((uint64_t)hi << 32) | lo);
+  };
+  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(Vc + (int64_t)g * D * v_row_bytes), 0, __builtin_amdgcn_readfirstlane(D * v_row_bytes), 0x00020000);
+  const __amdgpu_buffer_rsrc_t vs_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_ptr(Vs + (int64_t)g * D * vs_row_bytes), 0, __builtin_amdgcn_readfirstlane(D * vs_row_bytes), 0x00020000);
+  const int v_gather0 = (lane >> 3) * v_row_bytes + (((lane & 7) ^ (lane >> 4)) << 4);        // even load units
+  const int v_gather1 = (lane >> 3) * v_row_bytes + (((lane & 7) ^ (4 + (lane >> 4))) << 4);  // odd load units
+  const int v_read_swz = (col >> 1) & 7;  // rows 32 db + col: (row >> 1) & 7 does not depend on db
+
   RowPiece<D> kp;
-  VPiece vp[kRowBlocks];
+  VPiece vp[CHUNKED ? 1 : kRowBlocks];
   if (t0 < t1) {
     load_row_piece<D, ASYM>(Kc, Ks, krow0 + (int64_t)t0 * 32, h, kp);
+    if constexpr (!CHUNKED) {
 #pragma unroll
-    for (int db = 0; db < kRowBlocks; ++db) load_v_piece<ASYM>(Vc, Vs, vrow0 + db * 32, Sk, t0, vp[db]);
+      for (int db = 0; db < kRowBlocks; ++db) load_v_piece<ASYM>(Vc, Vs, vrow0 + db * 32, Sk, t0, vp[db]);
+    }
   }
   for (int t = t0; t < t1; ++t) {
+    if constexpr (CHUNKED) {
+      if (t == t0 || (t & 7) == 0) {
+        // the wave is done with the previous chunk (its reads have returned): fetch the chunk of tile t
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        const int chunk = t >> 3;
+#pragma unroll
+        for (int u = 0; u < D / 8; ++u)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lds_ptr_t)(v_lines + u * 1024), 16,
+                                                   (u & 1) ? v_gather1 : v_gather0,
+                                                   u * 8 * v_row_bytes + chunk * 128, 0, 0);
+#pragma unroll
+        for (int q = 0; q < kScaleParts; ++q)
+#pragma unroll
+          for (int k = 0; k < D / 64; ++k)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(vs_rsrc, (lds_ptr_t)(v_scale_words + (q * D + 64 * k) * 4), 4,
+                                                     lane * vs_row_bytes,
+                                                     64 * k * vs_row_bytes + chunk * (kScaleParts * 4) + q * 4, 0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+    }
     // the next tile's bytes are requested before this tile's arithmetic
     RowPiece<D> kn = kp;
-    VPiece vn[kRowBlocks];
+    VPiece vn[CHUNKED ? 1 : kRowBlocks];
+    if constexpr (!CHUNKED) {
 #pragma unroll
-    for (int db = 0; db < kRowBlocks; ++db) vn[db] = vp[db];
+      for (int db = 0; db < kRowBlocks; ++db) vn[db] = vp[db];
+    }
     if (t + 1 < t1) {
       load_row_piece<D, ASYM>(Kc, Ks, krow0 + (int64_t)(t + 1) * 32, h, kn);
+      if constexpr (!CHUNKED) {
 #pragma unroll
-      for (int db = 0; db < kRowBlocks; ++db) load_v_piece<ASYM>(Vc, Vs, vrow0 + db * 32, Sk, t + 1, vn[db]);
+        for (int db = 0; db < kRowBlocks; ++db) load_v_piece<ASYM>(Vc, Vs, vrow0 + db * 32, Sk, t + 1, vn[db]);
+      }
     }
 
     f32x16 s;
@@ -212,14 +267,31 @@ __global__ __launch_bounds__(64) void attention_decode_kernel(
       const u32x4 b = {pb[4 * j], pb[4 * j + 1], pb[4 * j + 2], pb[4 * j + 3]};
 #pragma unroll
       for (int db = 0; db < kRowBlocks; ++db) {
-        const uint32_t w0 = j ? vp[db].codes.z : vp[db].codes.x, w1 = j ? vp[db].codes.w : vp[db].codes.y;
-        const u32x4 a = decode_word<SCALE_KIND, ASYM>(__builtin_amdgcn_perm(w1, w0, pick), vp[db].sp, vp[db].sn);
+        uint32_t w0, w1, vsp, vsn;
+        if constexpr (CHUNKED) {
+          // the tile's 16 bytes of V^T row 32 db + col, 8 of them per k-step, and the row's scale bytes for the tile
+          const int tj = t & 7, row = db * 32 + col;
+          const uint2 c = *reinterpret_cast<const uint2*>(v_lines + row * 128 + ((tj ^ v_read_swz) << 4) + 8 * j);
+          w0 = c.x, w1 = c.y;
+          if constexpr (ASYM) {
+            const uint32_t pair = *reinterpret_cast<const uint16_t*>(v_scale_words + ((tj >> 1) * D + row) * 4 + (tj & 1) * 2);
+            vsp = pair & 255u, vsn = pair >> 8;
+          } else {
+            vsp = vsn = v_scale_words[((tj >> 2) * D + row) * 4 + (tj & 3)];
+          }
+        } else {
+          w0 = j ? vp[db].codes.z : vp[db].codes.x, w1 = j ? vp[db].codes.w : vp[db].codes.y;
+          vsp = vp[db].sp, vsn = vp[db].sn;
+        }
+        const u32x4 a = decode_word<SCALE_KIND, ASYM>(__builtin_amdgcn_perm(w1, w0, pick), vsp, vsn);
         o[db] = decode_mfma<SCALE_KIND>(a, b, o[db]);
       }
     }
     kp = kn;
+    if constexpr (!CHUNKED) {
 #pragma unroll
-    for (int db = 0; db < kRowBlocks; ++db) vp[db] = vn[db];
+      for (int db = 0; db < kRowBlocks; ++db) vp[db] = vn[db];
+    }
   }
 
   // register 4c + r of row block db is d = 32 db + 8 c + 4 h + r of column col
@@ -288,8 +360,15 @@ static hipError_t launch_decode(int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk,
                                 const uint8_t* Kc, const uint8_t* Ks, const uint8_t* Vc, const uint8_t* Vs, float scale,
                                 int causal, int splits, float* out, float* part, hipStream_t s) {
   const int per = (int)(Hq / Hkv), tiles = (int)(Sk / 32), tiles_per_split = (tiles + splits - 1) / splits;
-  hipLaunchKernelGGL((attention_decode_kernel<SK, ASYM, D>), dim3((unsigned)splits, (unsigned)Hkv), dim3(64), 0, s, Qc, Qs,
-                     Kc, Ks, Vc, Vs, part, (int)Sq, (int)Sk, per, tiles_per_split, scale * 1.4426950408889634f, causal);
+  // whole chunks of 8 key tiles, and V^T of one head within the 32-bit offsets of a buffer: V through LDS by chunks
+  if (Sk % 256 == 0 && Sk <= (1 << 24))
+    hipLaunchKernelGGL((attention_decode_kernel<SK, ASYM, D, true>), dim3((unsigned)splits, (unsigned)Hkv), dim3(64), 0, s,
+                       Qc, Qs, Kc, Ks, Vc, Vs, part, (int)Sq, (int)Sk, per, tiles_per_split,
+                       scale * 1.4426950408889634f, causal);
+  else
+    hipLaunchKernelGGL((attention_decode_kernel<SK, ASYM, D, false>), dim3((unsigned)splits, (unsigned)Hkv), dim3(64), 0, s,
+                       Qc, Qs, Kc, Ks, Vc, Vs, part, (int)Sq, (int)Sk, per, tiles_per_split,
+                       scale * 1.4426950408889634f, causal);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attention_decode_combine_kernel<D>), dim3((unsigned)(per * Sq), (unsigned)Hkv), dim3(64), 0, s, part,
