@@ -40,6 +40,10 @@ SHAPES = [
     (6, 2, 2, 320, True, 10, 128),     # one tile per range
     (4, 2, 3, 256, True, 5, 64),       # heads of 64
     (8, 8, 1, 512, False, 4, 64),
+    # V goes through LDS in chunks of 8 tiles when Sk is a multiple of 256: ranges that start inside a chunk and run
+    # across chunk boundaries (32 tiles in 3 ranges of 11, 11, 10; 24 tiles in 2 ranges of 12)
+    (4, 1, 2, 1024, True, 3, 128),
+    (4, 2, 1, 768, False, 2, 64),
 ]
 
 
