@@ -11,7 +11,7 @@
 // 4c + r: all 32 keys of a query sit in the two lanes l and l ^ 32, so the row maximum, the row sum and the group
 // maximum of the cast are 16 in-lane steps and one exchange, and registers 8j .. 8j+7 of S^T, converted to BF16, are
 // already the B operand of k-step j of the second product, provided V^T was staged with its keys in that order
-// (expand_kernel<PERMUTE>). Workgroup = 8 waves x 32 queries; the K and V fragments of a key tile are brought into
+// (expand_kernel<PERMUTE>). Workgroup = kAttnWaves waves x 32 queries; the K and V fragments of a key tile are brought into
 // LDS once per workgroup by direct-to-LDS loads, double buffered.
 #include "../../include/amxfp4.h"
 #include "attention_tile.h"
@@ -23,14 +23,20 @@ namespace amx {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kAttnWaves = 8;               // waves per workgroup, 32 queries each
+// Waves per workgroup, 32 queries each. A wave's work on a tile is one long dependent chain (fragment reads -> eight
+// chained MFMAs -> maximum, exponentials, sum, cast -> MFMAs), and the barrier of a workgroup keeps its waves in the
+// same phase of it, so what hides the chain's latencies is waves of OTHER workgroups on the same SIMD: four waves per
+// workgroup and a register budget of a third of the file put three workgroups on a compute unit (8 waves with two
+// per SIMD: 0.243-0.248 ms for 32 heads x 4096; this: 0.229; a quarter of the file, four workgroups: 0.251, the heavy
+// and light query blocks of a causal problem then all start at once).
+constexpr int kAttnWaves = 4;
 constexpr int kAttnQ = 32 * kAttnWaves;     // queries per workgroup
 
 // kAttnD: the head dimension, 128 or 64. A key tile is kAttnD / 16 K fragments (one per 16 of D) and as many V^T
-// fragments (D / 32 row blocks x 2 k-steps), dealt over the eight waves: one K and one V fragment each for 128, one
-// fragment each (waves 0-3 K, waves 4-7 V) for 64.
+// fragments (D / 32 row blocks x 2 k-steps), dealt over the waves: wave w brings K and V fragments w, w + kAttnWaves,
+// ... (with more waves than fragments the first ones would bring K, the others V).
 template <int SCALE_KIND, int kAttnD>
-__global__ __launch_bounds__(64 * kAttnWaves) void attention_fused_kernel(
+__global__ __launch_bounds__(64 * kAttnWaves) __attribute__((amdgpu_waves_per_eu(3, 3))) void attention_fused_kernel(
     const uint16_t* __restrict__ Qp, const uint16_t* __restrict__ Kp, const uint16_t* __restrict__ Vp,
     float* __restrict__ out, int Sq, int Sk, int Sqp, int Skv, int kv_group, float scale_log2, int causal,
     int merged_bf16) {
