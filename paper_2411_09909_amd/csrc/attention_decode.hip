@@ -7,8 +7,8 @@
 //   - the query heads that share a key / value head, and their few queries, are the 32 columns of ONE wave
 //     (q_heads / kv_heads * Sq <= 32), so every K and V byte is read by one wave only;
 //   - the keys are the parallelism: the key tiles are cut into `key_splits` contiguous ranges, one wave per (key / value
-//     head, range), no LDS and no barriers; each wave leaves its un-normalised result, running maximum and sum in the
-//     workspace and a second kernel combines the ranges exactly:
+//     head, range), no barriers (LDS only as a wave's own staging space for V); each wave leaves its un-normalised
+//     result, running maximum and sum in the workspace and a second kernel combines the ranges exactly:
 //       m* = max_c m_c,   out = sum_c O_c 2^(m_c - m*) / sum_c l_c 2^(m_c - m*).
 //     The probabilities of a range are cast against that range's own running maximum, so the result depends on
 //     key_splits (with one range it is the other kernel's result up to summation order).
