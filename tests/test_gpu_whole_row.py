@@ -153,6 +153,24 @@ def test_gemm_batched_with_a_scale_pair_of_its_own_on_every_row():
     assert G.rel_fro(Cp.cpu().numpy(), Cr[1]) <= TOL
 
 
+@pytest.mark.parametrize("K", [96, 4128, 28672])
+def test_cast_writes_only_its_outputs(K):
+    """Codes and scale bytes land in windows of pattern-filled buffers; the guard bytes around them stay untouched."""
+    rows, guard = 7, 4096
+    x = synth.activations(rows, K, seed=K, n_outlier=1, outlier_gain=30.0)
+    fmt = binding.make_format(ref.FP8_E5M2, 1, -1)
+    cbuf = torch.full((guard + rows * K // 2 + guard,), 0xA5, dtype=torch.uint8, device="cuda")
+    sbuf = torch.full((guard + rows * 2 + guard,), 0xA5, dtype=torch.uint8, device="cuda")
+    codes = cbuf[guard:guard + rows * K // 2].view(rows, K // 2)
+    scales = sbuf[guard:guard + rows * 2].view(rows, 1, 2)
+    binding.quantize(fmt, G.to_dev_bf16(x), codes=codes, scales=scales)
+    torch.cuda.synchronize()
+    rc, rs = ref.quantize(x, -1, ref.FP8_E5M2, 1)
+    assert np.array_equal(codes.cpu().numpy(), rc) and np.array_equal(scales.cpu().numpy(), rs)
+    for buf, n in ((cbuf, rows * K // 2), (sbuf, rows * 2)):
+        assert bool((buf[:guard] == 0xA5).all()) and bool((buf[guard + n:] == 0xA5).all())
+
+
 def test_calls_without_a_whole_row_form_say_so():
     fmt = binding.make_format(ref.FP8_E5M2, 1, -1)
     x = G.to_dev_bf16(synth.activations(64, 128, seed=1))
