@@ -22,6 +22,7 @@ namespace amx {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 // Waves per workgroup, 32 queries each. A wave's work on a tile is one long dependent chain (fragment reads -> eight
 // chained MFMAs -> maximum, exponentials, sum, cast -> MFMAs), and the barrier of a workgroup keeps its waves in the
@@ -41,6 +42,11 @@ __global__ __launch_bounds__(64 * kAttnWaves) __attribute__((amdgpu_waves_per_eu
     float* __restrict__ out, int Sq, int Sk, int Sqp, int Skv, int kv_group, float scale_log2, int causal,
     int merged_bf16) {
   static_assert(kAttnD == 128 || kAttnD == 64, "head dimension");
+  // FP8-E5M2 scales: the second product runs on FP16 operands. The cast leaves the probabilities as FP16 times 2^8
+  // (the scale byte is the upper byte of an FP16: a conversion and a packed multiply per pair instead of a conversion,
+  // two multiplies and a permute), V^T comes as an FP16 panel biased by 2^-3, and the 2^5 is taken out with the row
+  // sum at the end. Same values, same sums.
+  constexpr bool kPF16 = SCALE_KIND == kScaleE5M2;
   constexpr int kAttnKFrags = kAttnD / 16, kAttnVFrags = (kAttnD / 32) * 2;
   static_assert(kAttnKFrags == kAttnVFrags && (kAttnKFrags % kAttnWaves == 0 || 2 * kAttnKFrags == kAttnWaves),
                 "fragments must divide over the waves");
@@ -135,16 +141,21 @@ __global__ __launch_bounds__(64 * kAttnWaves) __attribute__((amdgpu_waves_per_eu
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kb], s, 0, 0, 0);                                          \
     }                                                                                                              \
     const bool diagonal = causal && (T) * 32 + 31 > qw + off; /* some key of the tile is masked for some query */ \
-    AMX_ATTENTION_TILE_PROBS(false, s, scale_log2, diagonal, (T) * 32 + row_in_tile, limit, m, l, pb, alpha)       \
+    AMX_ATTENTION_TILE_PROBS(false, s, scale_log2, diagonal, (T) * 32 + row_in_tile, limit, m, l, pb, alpha, kPF16)       \
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) { /* the maximum moved for some query: rescale */        \
       _Pragma("unroll") for (int db = 0; db < kAttnD / 32; ++db)                                                   \
         _Pragma("unroll") for (int v = 0; v < 16; ++v) o[db][v] *= alpha;                                          \
     }                                                                                                              \
     _Pragma("unroll") for (int j = 0; j < 2; ++j) {                                                                \
-      const bf16x8 b = __builtin_bit_cast(bf16x8, u32x4{pb[4 * j], pb[4 * j + 1], pb[4 * j + 2], pb[4 * j + 3]}); \
+      const u32x4 b = {pb[4 * j], pb[4 * j + 1], pb[4 * j + 2], pb[4 * j + 3]};                                    \
       _Pragma("unroll") for (int db = 0; db < kAttnD / 32; ++db) {                                                 \
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>((CV) + (db * 2 + j) * kFragBytes + lane_off);            \
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o[db], 0, 0, 0);                                     \
+        const u32x4 a = *reinterpret_cast<const u32x4*>((CV) + (db * 2 + j) * kFragBytes + lane_off);              \
+        if constexpr (kPF16)                                                                                       \
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), \
+                                                         o[db], 0, 0, 0);                                          \
+        else                                                                                                       \
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),                           \
+                                                          __builtin_bit_cast(bf16x8, b), o[db], 0, 0, 0);          \
       }                                                                                                            \
     }                                                                                                              \
   }
@@ -174,7 +185,7 @@ __global__ __launch_bounds__(64 * kAttnWaves) __attribute__((amdgpu_waves_per_eu
   // projection's cast reads: no head-merge pass over an FP32 copy).
   const int q = qw + (lane & 31);
   if (wave_active && q < Sq && merged_bf16) {
-    const float inv = 1.0f / l;
+    const float inv = (kPF16 ? 0.03125f : 1.0f) / l;
     uint16_t* dst = reinterpret_cast<uint16_t*>(out) + ((int64_t)q * nheads + h) * kAttnD + row_in_tile;
 #pragma unroll
     for (int db = 0; db < kAttnD / 32; ++db)
@@ -183,7 +194,7 @@ __global__ __launch_bounds__(64 * kAttnWaves) __attribute__((amdgpu_waves_per_eu
         *reinterpret_cast<uint2*>(dst + db * 32 + c * 8) = make_uint2(
             pack2(o[db][4 * c] * inv, o[db][4 * c + 1] * inv), pack2(o[db][4 * c + 2] * inv, o[db][4 * c + 3] * inv));
   } else if (wave_active && q < Sq) {
-    const float inv = 1.0f / l;
+    const float inv = (kPF16 ? 0.03125f : 1.0f) / l;
     float* dst = out + ((int64_t)h * Sq + q) * kAttnD + row_in_tile;
 #pragma unroll
     for (int db = 0; db < kAttnD / 32; ++db)

@@ -248,14 +248,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       s = decode_mfma<SCALE_KIND>(a, qf[ks], s);
     }
     const bool masked = causal && t * 32 + 31 > off;  // some key of the tile is masked for the first query (uniform)
-    AMX_ATTENTION_TILE_PROBS(true, s, score_scale, masked, t * 32 + row_in_tile, limit, m, l, pb, alpha)
-    if constexpr (kF16) {  // BF16 pairs -> FP16 pairs of 2^8 p (exact: at most 6 significant bits, 2^-9 <= 2^8 p <= 2^8)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        pb[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(u2f(pb[i] << 16) * 256.0f,
-                                                                        u2f(pb[i] & 0xFFFF0000u) * 256.0f));
-      }
-    }
+    AMX_ATTENTION_TILE_PROBS(true, s, score_scale, masked, t * 32 + row_in_tile, limit, m, l, pb, alpha, kF16)
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // the maximum moved for some query: rescale
 #pragma unroll
       for (int db = 0; db < kRowBlocks; ++db)

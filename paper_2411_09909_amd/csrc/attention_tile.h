@@ -17,6 +17,7 @@
 
 namespace amx {
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 }  // namespace amx
 
 // Inside a kernel templated on SCALE_KIND. SACC: the tile's raw scores (f32x16); SCALE_LOG2: softmax scale times
@@ -25,7 +26,10 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 // (in units of log2) and sum of this lane's query, updated. Declares PB, the eight words of dequantized probabilities,
 // and ALPHA, the factor the query's accumulated output must be multiplied with. EMPTY_OK (a literal): a query may have
 // seen no key at all so far; kernels in which every query sees the first key of its first tile pass false.
-#define AMX_ATTENTION_TILE_PROBS(EMPTY_OK, SACC, SCALE_LOG2, MASKED, KEY0, LIMIT, M, L, PB, ALPHA)                 \
+// P_F16 (a literal; FP8-E5M2 scales only): PB holds FP16 pairs of 2^8 times the dequantized probabilities instead of
+// BF16 pairs (exact: at most 6 significant bits, 2^-9 <= 2^8 p <= 2^8, so even the smallest is a normal FP16 number):
+// the scale byte is the upper byte of an FP16, so the FP4 -> FP16 conversion and one packed multiply do it.
+#define AMX_ATTENTION_TILE_PROBS(EMPTY_OK, SACC, SCALE_LOG2, MASKED, KEY0, LIMIT, M, L, PB, ALPHA, P_F16)          \
     float x[16];                                                                                                   \
     float mx = -__builtin_inff();                                                                                  \
     _Pragma("unroll") for (int v = 0; v < 16; ++v) x[v] = (SACC)[v] * (SCALE_LOG2);                                \
@@ -61,8 +65,16 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
       (void)encode_scale_sr<SCALE_KIND>(pmax, S, R);                                                               \
     }                                                                                                              \
     uint32_t PB[8];                                                                                                \
+    static_assert(!(P_F16) || SCALE_KIND == kScaleE5M2, "FP16 probabilities: FP8-E5M2 scales");                    \
+    const _Float16 s_half_ = (_Float16)S; /* exact: an E5M2 value, subnormals included */                          \
+    const f16x2 s_half2_ = {s_half_, s_half_};                                                                     \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
-      if constexpr (SCALE_KIND == kScaleE5M2 || SCALE_KIND == kScaleE4M3) {                                        \
+      if constexpr ((P_F16) && SCALE_KIND == kScaleE5M2) {                                                         \
+        const float z0 = x[2 * i] * R, z1 = x[2 * i + 1] * R;                                                      \
+        const uint32_t code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(f2u(z0), z0, z1, 1.0f, 0);                  \
+        const f16x2 e = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(code, 256.0f, 0);                                 \
+        PB[i] = __builtin_bit_cast(uint32_t, e * s_half2_);                                                        \
+      } else if constexpr (SCALE_KIND == kScaleE5M2 || SCALE_KIND == kScaleE4M3) {                                 \
         /* the conversion replaces byte 0 of its first operand, the only byte read below: any register will do,    \
            and one that dies here saves the move of a zero */                                                      \
         const float z0 = x[2 * i] * R, z1 = x[2 * i + 1] * R;                                                      \

@@ -306,7 +306,16 @@ hipError_t launch_expand_bf16(int scale_kind, bool asym, int64_t group_size, con
                        gs_log2, panel);
     return hipGetLastError();
   };
-  if (scale_kind == kScaleE5M2) return asym ? go.template operator()<kScaleE5M2, true>() : go.template operator()<kScaleE5M2, false>();
+  if (scale_kind == kScaleE5M2) {
+    // FP16 with a bias of 2^-3 (every element * scale / 8 is an FP16 number): the probabilities it is multiplied with
+    // come out of the attention kernel's cast as FP16 for this scale format
+    auto go16 = [&]<bool ASYM>() {
+      hipLaunchKernelGGL((expand_kernel<kScaleE5M2, ASYM, true, true>), grid, dim3(256), 0, s, codes, scales, R, K, Rp,
+                         Kp, gs_log2, panel);
+      return hipGetLastError();
+    };
+    return asym ? go16.template operator()<true>() : go16.template operator()<false>();
+  }
   if (scale_kind == kScaleE4M3) return asym ? go.template operator()<kScaleE4M3, true>() : go.template operator()<kScaleE4M3, false>();
   return asym ? go.template operator()<kScaleE8M0Floor, true>() : go.template operator()<kScaleE8M0Floor, false>();
 }

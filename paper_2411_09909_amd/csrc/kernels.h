@@ -72,6 +72,8 @@ hipError_t launch_expand_b_panel(int scale_kind, bool asym, int64_t group_size, 
 hipError_t launch_expand_bf16(int scale_kind, bool asym, int64_t group_size, const uint8_t* codes,
                               const uint8_t* scales, int64_t R, int64_t K, int64_t Rp, int64_t Kp, int64_t batch,
                               bool permute, uint16_t* panel, hipStream_t s);
+// (a permuted panel of an FP8-E5M2 operand is FP16 biased by 2^-3 instead of BF16: what the attention kernel's second
+// product takes for that scale format)
 
 // gemm_skinny.hip: M <= 256, K a multiple of 256, groups of 32: B dequantized in registers straight from its codes
 // (workspace: the BF16 panel of A and, with several outer K slices, the partial tiles; forced_slices: 0 = the number
